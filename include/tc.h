@@ -1,0 +1,208 @@
+/*
+ * tc.h -- C ABI of the MI355X tensor-commitment prover library (libtc.so).
+ *
+ * The library implements the prover-side hot path of TensorCommitments on one
+ * gfx950 GPU: quantised tensor -> field elements -> tensor commitment (Def. 4.1,
+ * Com) -> Terkle Tree of commitments (Sec. 4, Terkle Tree definition) ->
+ * openings (Def. 4.1, Open; Terkle membership proof) -> path verification
+ * (Def. 4.1, Ver in its sum form, checked with the trapdoor; Terkle verification).
+ *
+ * Conventions
+ *   - Every function returns TC_OK (0) or a negative TC_ERR_* code; nothing
+ *     aborts or throws across this boundary.  tc_last_error(ctx) returns a
+ *     human-readable message for the last failure on that context.
+ *   - tc_ctx / tc_srs / tc_tree / tc_vk are opaque and owned by the library
+ *     (create / destroy pairs).  All data buffers are owned by the caller.
+ *   - Pointers named d_* are DEVICE pointers on the context's GPU; they are
+ *     borrowed until the call returns (every call that returns bytes to the
+ *     host synchronises the context's stream before returning).  All other
+ *     pointers are HOST pointers.
+ *   - Fr element: 32 bytes little-endian, value < r.  G1 element: 96 bytes
+ *     x || y, 48 bytes little-endian each, affine, value < p; the point at
+ *     infinity is 96 zero bytes.  Curve: BLS12-381 (App. E), commitments and
+ *     proofs in G1.
+ *   - Shapes are uint32_t[m], 1 <= m <= TC_MAX_ORDER, row-major with the last
+ *     axis fastest (the lexicographic layout of App. A).  Grid positions are
+ *     0-based; position i on an axis is the evaluation node zeta = i + 1.
+ *   - One trapdoor vector (tau_1..tau_4) serves every shape of a context: axis
+ *     j of any shape uses tau_j.
+ */
+#ifndef TC_H_
+#define TC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TC_MAX_ORDER 4
+#define TC_MAX_STEPS 16
+
+#define TC_OK 0
+#define TC_ERR_ARG (-1)    /* null pointer, bad enum, bad count */
+#define TC_ERR_SHAPE (-2)  /* shape / order out of range or mismatching the SRS */
+#define TC_ERR_RANGE (-3)  /* non-canonical field element, index outside the grid, trapdoor on the grid */
+#define TC_ERR_NOMEM (-4)  /* host or device allocation failed */
+#define TC_ERR_HIP (-5)    /* a HIP runtime call failed */
+#define TC_ERR_VERIFY (-6) /* a proof was checked and rejected */
+#define TC_ERR_STATE (-7)  /* object lacks what the call needs (e.g. SRS built without suffix tables) */
+
+/* element types of caller buffers */
+#define TC_I8 1  /* int8_t   */
+#define TC_I16 2 /* int16_t  */
+#define TC_FR 3  /* 32-byte canonical Fr elements */
+#define TC_F16 4 /* IEEE binary16 (source type of tc_encode_tensor only) */
+
+typedef struct tc_ctx tc_ctx;
+typedef struct tc_srs tc_srs;
+typedef struct tc_tree tc_tree;
+typedef struct tc_vk tc_vk;
+
+/* ---- context ----------------------------------------------------------------- */
+
+/* Creates a context on GPU `device`.  `hip_stream` is a hipStream_t (as void*) on
+ * which all work of this context is enqueued, or NULL for the default stream.
+ * The stream stays owned by the caller.  Fails with TC_ERR_HIP when no GPU /
+ * runtime is available: there is no CPU path. */
+int tc_ctx_create(tc_ctx** out, int device, void* hip_stream);
+void tc_ctx_destroy(tc_ctx* ctx);
+const char* tc_last_error(const tc_ctx* ctx);
+/* Blocks until all work enqueued by this context has finished. */
+int tc_ctx_sync(tc_ctx* ctx);
+
+/* ---- Setup (Def. 4.1, Setup) -- test-only trusted setup from a known trapdoor -- */
+
+#define TC_SRS_SUFFIX 1u     /* also build the suffix tables S^(a), a = 1..m-1, needed by tc_open */
+#define TC_SRS_FIXED_BASE 2u /* also build fixed-base window tables for every table (node shapes of a
+                                tree: small shapes only, 50 MB per base) */
+
+/* Builds, on the device, the Lagrange-basis SRS for `shape`:
+ *   S[i] = [ prod_j l_{j,i_j}(tau_j) ] G,  i in prod_j {0..d_j-1},
+ * the image of the monomial SRS of Def. 4.1 under the (public, linear) change of
+ * basis; committing against it gives the same group element as interpolating and
+ * committing against the monomial SRS.  tau: m canonical Fr values (m * 32 bytes);
+ * a trapdoor that is 0 or lies on the grid {1..d_j} is rejected with TC_ERR_RANGE. */
+int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, const uint32_t* shape, uint32_t flags,
+                           tc_srs** out);
+void tc_srs_destroy(tc_srs* srs);
+/* Number of points of table S^(first_axis) (prod of shape[first_axis..]); 0 if absent. */
+uint64_t tc_srs_size(const tc_srs* srs, int first_axis);
+/* Copies one SRS point to the host in canonical form (inspection / spot checks). */
+int tc_srs_get_point(tc_ctx* ctx, const tc_srs* srs, int first_axis, uint64_t index, uint8_t out_g1[96]);
+
+/* ---- encode (quantisation + field embedding of the synthetic workloads) ------- */
+
+/* d_src: n elements of `src_dtype`.  TC_F16: q = clamp(rint(float(x) * inv_scale), -32767, 32767)
+ * (round half to even, one float32 multiply) written as int16 to d_dst.  TC_I8 / TC_I16: copied
+ * unchanged to d_dst (same type).  The embedding e(q) = q mod r (negatives as r - |q|) is applied
+ * inside the commitment kernels: -|q| P is computed as |q| (-P). */
+int tc_encode_tensor(tc_ctx* ctx, const void* d_src, int src_dtype, size_t n, float inv_scale, void* d_dst);
+
+/* ---- Com (Def. 4.1, Com) -------------------------------------------------------- */
+
+/* C_T = sum_i [e(T[i])] S[i] = g^{f_T(tau)}.  d_scalars: prod(shape) elements of `dtype`
+ * (TC_I8, TC_I16 or TC_FR), laid out row-major.  Writes the canonical commitment. */
+int tc_commit(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, int dtype, uint8_t out_g1[96]);
+/* `count` independent commitments; out_g1 holds count * 96 bytes. */
+int tc_commit_batch(tc_ctx* ctx, int count, const tc_srs* const* srs, const void* const* d_scalars,
+                    const int* dtype, uint8_t* out_g1);
+
+/* ---- Open (Def. 4.1, Open; Algorithm 1 in evaluation form) ----------------------- */
+
+/* Opens T at grid position kappa: y = T[kappa] and pi_i = g^{q_i(tau)}, i = 1..m, with
+ * r_{i-1} = q_i (X_i - omega_i) + r_i.  The quotients are formed as values on the grid
+ * (divided differences along axis i of the slice fixed by kappa_1..kappa_{i-1}) and
+ * committed against the suffix table S^(i).  Needs TC_SRS_SUFFIX.  out_pi: m * 96 bytes. */
+int tc_open(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, int dtype, const uint32_t* kappa,
+            uint8_t out_y[32], uint8_t* out_pi);
+
+/* ---- Ver (Def. 4.1, Ver, sum form; trapdoor-form check) --------------------------- */
+
+/* Verification key of the test harness: the trapdoors themselves. */
+int tc_vk_from_trapdoor(const uint8_t* tau, int m, tc_vk** out);
+void tc_vk_destroy(tc_vk* vk);
+/* Accepts (TC_OK) iff  C - [y]G == sum_i [tau_i - (kappa_i + 1)] pi_i  in G1, which holds iff
+ * e(C g^{-y}, g) = prod_i e(pi_i, g^{tau_i - omega_i}).  Rejects with TC_ERR_VERIFY. */
+int tc_verify(tc_ctx* ctx, const tc_vk* vk, int m, const uint32_t* shape, const uint8_t commitment[96],
+              const uint32_t* kappa, const uint8_t y[32], const uint8_t* pi);
+
+/* ---- Terkle Tree (Sec. 4: Terkle Tree, membership proof, verification) ------------- */
+
+#define TC_LEAF_ENTRIES 0 /* bottom level = blocks of payload entries */
+#define TC_LEAF_TENSORS 1 /* bottom level = whole tensors, one commitment each */
+
+typedef struct tc_tree_desc {
+    int m;                       /* order of the payload grid */
+    uint32_t grid[TC_MAX_ORDER]; /* payload grid: entries (ENTRIES) or tensors (TENSORS) */
+    uint32_t node_shape[TC_MAX_ORDER]; /* node shape d^(u) of every blocked level; arity B = prod */
+    const tc_srs* node_srs;      /* SRS for node_shape, built with TC_SRS_SUFFIX | TC_SRS_FIXED_BASE */
+    int leaf_kind;               /* TC_LEAF_ENTRIES or TC_LEAF_TENSORS */
+    /* TC_LEAF_ENTRIES */
+    const void* d_payload;       /* prod(grid) entries of `dtype` (TC_I8 / TC_I16), row-major */
+    int dtype;
+    /* TC_LEAF_TENSORS: prod(grid) tensors, row-major over the grid */
+    const tc_srs* const* leaf_srs;      /* SRS of each tensor (its shape) */
+    const void* const* d_leaf_scalars;  /* device buffer of each tensor */
+    const int* leaf_dtype;
+} tc_tree_desc;
+
+/* Builds the tree level by level.  Level grids: ceil(grid / node_shape) per axis, repeated
+ * until all ones; children outside the grid count as the field element 0; a child commitment
+ * C enters its parent's tensor as phi(C) = (2 x_C + [y_C > (p-1)/2]) mod r, phi(O) = 0.
+ * The payload / leaf buffers must stay valid for as long as openings are requested. */
+int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** out);
+void tc_tree_destroy(tc_tree* tree);
+int tc_terkle_root(const tc_tree* tree, uint8_t out_g1[96]);
+/* Number of levels (bottom = 0, root level = levels - 1). */
+int tc_terkle_levels(const tc_tree* tree);
+/* Grid of a level (m entries) and its node count. */
+int tc_terkle_level_info(const tc_tree* tree, int level, uint32_t* grid, uint64_t* n_nodes);
+/* Commitment of node `index` (row-major in the level grid) in canonical form. */
+int tc_terkle_node(tc_ctx* ctx, const tc_tree* tree, int level, uint64_t index, uint8_t out_g1[96]);
+
+/* Path of a payload position.  Steps run from the root down.  Step s opens a tensor of shape
+ * shape[s] (order m[s]) at kappa[s]. */
+typedef struct tc_path {
+    int n_steps;
+    int m[TC_MAX_STEPS];
+    uint32_t shape[TC_MAX_STEPS][TC_MAX_ORDER];
+    uint32_t kappa[TC_MAX_STEPS][TC_MAX_ORDER];
+} tc_path;
+
+/* Host-only: the path of `leaf_index` (m grid coordinates) in a tree over `grid` with uniform
+ * `node_shape`.  For TC_LEAF_TENSORS the last step opens the leaf tensor (inner_m, inner_shape)
+ * at inner_index; pass inner_m = 0 for TC_LEAF_ENTRIES. */
+int tc_path_from_grid(int m, const uint32_t* grid, const uint32_t* node_shape, int leaf_kind,
+                      const uint32_t* leaf_index, int inner_m, const uint32_t* inner_shape,
+                      const uint32_t* inner_index, tc_path* out);
+
+/* Membership proof.  Serialised top-down; step s contributes
+ *     m[s] * 96 bytes  (pi_1..pi_m)  ||  32 bytes (opened value y)  ||  96 bytes (commitment of
+ *     the next node on the path; absent in the last step).
+ * On entry *proof_len is the capacity of proof_buf, on return the bytes written (TC_ERR_ARG with
+ * the needed size in *proof_len if too small).  inner_index: position inside the leaf tensor
+ * (TC_LEAF_TENSORS) or NULL. */
+int tc_terkle_open(tc_ctx* ctx, const tc_tree* tree, const uint32_t* leaf_index, const uint32_t* inner_index,
+                   void* proof_buf, size_t* proof_len);
+/* `count` proofs at once; leaf_index / inner_index hold count * m (inner: count * inner order of
+ * each leaf, concatenated); proofs are written at proof_buf + i * proof_stride, lengths to proof_len[i]. */
+int tc_terkle_open_batch(tc_ctx* ctx, const tc_tree* tree, int count, const uint32_t* leaf_index,
+                         const uint32_t* inner_index, void* proof_buf, size_t proof_stride, size_t* proof_len);
+
+/* Walks the path from the root: every opening must verify against the commitment carried down,
+ * every opened value above the bottom must equal phi(next commitment), the bottom value must equal
+ * leaf_value, and the chain must start at `root`.  TC_OK = accept, TC_ERR_VERIFY = reject. */
+int tc_verify_path(tc_ctx* ctx, const tc_vk* vk, const tc_path* path, const uint8_t root[96],
+                   const uint8_t leaf_value[32], const void* proof, size_t proof_len);
+/* `count` paths on the GPU at once; results[i] = TC_OK or TC_ERR_VERIFY.  Returns TC_OK when the
+ * batch ran (whatever the verdicts). */
+int tc_verify_paths_batch(tc_ctx* ctx, const tc_vk* vk, int count, const tc_path* paths, const uint8_t* roots,
+                          const uint8_t* leaf_values, const void* proofs, size_t proof_stride,
+                          const size_t* proof_len, int* results);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TC_H_ */

@@ -1,0 +1,338 @@
+"""ctypes binding of libtc.so: argument marshalling only.
+
+Every function of include/tc.h is reachable under its own name through
+`load_library().tc_*`; the classes below only pack arguments (shapes, byte
+strings, device pointers taken from torch tensors) and raise TcError on a
+negative status."""
+import ctypes
+import os
+
+TC_OK = 0
+TC_ERR_ARG, TC_ERR_SHAPE, TC_ERR_RANGE, TC_ERR_NOMEM, TC_ERR_HIP, TC_ERR_VERIFY, TC_ERR_STATE = -1, -2, -3, -4, -5, -6, -7
+TC_I8, TC_I16, TC_FR, TC_F16 = 1, 2, 3, 4
+TC_SRS_SUFFIX, TC_SRS_FIXED_BASE = 1, 2
+TC_LEAF_ENTRIES, TC_LEAF_TENSORS = 0, 1
+TC_MAX_ORDER, TC_MAX_STEPS = 4, 16
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ERR_NAMES = {-1: "TC_ERR_ARG", -2: "TC_ERR_SHAPE", -3: "TC_ERR_RANGE", -4: "TC_ERR_NOMEM", -5: "TC_ERR_HIP",
+              -6: "TC_ERR_VERIFY", -7: "TC_ERR_STATE"}
+
+
+class TcError(RuntimeError):
+    def __init__(self, code, message=""):
+        super().__init__("%s (%d): %s" % (_ERR_NAMES.get(code, "TC_ERR"), code, message))
+        self.code = code
+
+
+class tc_tree_desc(ctypes.Structure):
+    _fields_ = [
+        ("m", ctypes.c_int),
+        ("grid", ctypes.c_uint32 * TC_MAX_ORDER),
+        ("node_shape", ctypes.c_uint32 * TC_MAX_ORDER),
+        ("node_srs", ctypes.c_void_p),
+        ("leaf_kind", ctypes.c_int),
+        ("d_payload", ctypes.c_void_p),
+        ("dtype", ctypes.c_int),
+        ("leaf_srs", ctypes.POINTER(ctypes.c_void_p)),
+        ("d_leaf_scalars", ctypes.POINTER(ctypes.c_void_p)),
+        ("leaf_dtype", ctypes.POINTER(ctypes.c_int)),
+    ]
+
+
+class tc_path(ctypes.Structure):
+    _fields_ = [
+        ("n_steps", ctypes.c_int),
+        ("m", ctypes.c_int * TC_MAX_STEPS),
+        ("shape", (ctypes.c_uint32 * TC_MAX_ORDER) * TC_MAX_STEPS),
+        ("kappa", (ctypes.c_uint32 * TC_MAX_ORDER) * TC_MAX_STEPS),
+    ]
+
+
+def library_path():
+    return os.path.join(_HERE, "libtc.so")
+
+
+_LIBS = {}
+
+
+def load_library(path=None):
+    """Loads libtc.so (or the library at `path`) and declares the prototypes of include/tc.h."""
+    path = os.path.abspath(path or library_path())
+    if path in _LIBS:
+        return _LIBS[path]
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            "%s is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`; "
+            "there is no fallback implementation" % path)
+    L = ctypes.CDLL(path)
+    vp, u8p, u32p = ctypes.c_void_p, ctypes.c_char_p, ctypes.POINTER(ctypes.c_uint32)
+    sig = {
+        "tc_ctx_create": (ctypes.c_int, [ctypes.POINTER(vp), ctypes.c_int, vp]),
+        "tc_ctx_destroy": (None, [vp]),
+        "tc_last_error": (ctypes.c_char_p, [vp]),
+        "tc_ctx_sync": (ctypes.c_int, [vp]),
+        "tc_setup_from_trapdoor": (ctypes.c_int, [vp, u8p, ctypes.c_int, u32p, ctypes.c_uint32, ctypes.POINTER(vp)]),
+        "tc_srs_destroy": (None, [vp]),
+        "tc_srs_size": (ctypes.c_uint64, [vp, ctypes.c_int]),
+        "tc_srs_get_point": (ctypes.c_int, [vp, vp, ctypes.c_int, ctypes.c_uint64, vp]),
+        "tc_encode_tensor": (ctypes.c_int, [vp, vp, ctypes.c_int, ctypes.c_size_t, ctypes.c_float, vp]),
+        "tc_commit": (ctypes.c_int, [vp, vp, vp, ctypes.c_int, vp]),
+        "tc_commit_batch": (ctypes.c_int, [vp, ctypes.c_int, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                           ctypes.POINTER(ctypes.c_int), vp]),
+        "tc_open": (ctypes.c_int, [vp, vp, vp, ctypes.c_int, u32p, vp, vp]),
+        "tc_vk_from_trapdoor": (ctypes.c_int, [u8p, ctypes.c_int, ctypes.POINTER(vp)]),
+        "tc_vk_destroy": (None, [vp]),
+        "tc_verify": (ctypes.c_int, [vp, vp, ctypes.c_int, u32p, u8p, u32p, u8p, u8p]),
+        "tc_terkle_build": (ctypes.c_int, [vp, ctypes.POINTER(tc_tree_desc), ctypes.POINTER(vp)]),
+        "tc_tree_destroy": (None, [vp]),
+        "tc_terkle_root": (ctypes.c_int, [vp, vp]),
+        "tc_terkle_levels": (ctypes.c_int, [vp]),
+        "tc_terkle_level_info": (ctypes.c_int, [vp, ctypes.c_int, u32p, ctypes.POINTER(ctypes.c_uint64)]),
+        "tc_terkle_node": (ctypes.c_int, [vp, vp, ctypes.c_int, ctypes.c_uint64, vp]),
+        "tc_path_from_grid": (ctypes.c_int, [ctypes.c_int, u32p, u32p, ctypes.c_int, u32p, ctypes.c_int, u32p, u32p,
+                                             ctypes.POINTER(tc_path)]),
+        "tc_terkle_open": (ctypes.c_int, [vp, vp, u32p, u32p, vp, ctypes.POINTER(ctypes.c_size_t)]),
+        "tc_terkle_open_batch": (ctypes.c_int, [vp, vp, ctypes.c_int, u32p, u32p, vp, ctypes.c_size_t,
+                                                ctypes.POINTER(ctypes.c_size_t)]),
+        "tc_verify_path": (ctypes.c_int, [vp, vp, ctypes.POINTER(tc_path), u8p, u8p, vp, ctypes.c_size_t]),
+        "tc_verify_paths_batch": (ctypes.c_int, [vp, vp, ctypes.c_int, ctypes.POINTER(tc_path), u8p, u8p, vp,
+                                                 ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t),
+                                                 ctypes.POINTER(ctypes.c_int)]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)              # AttributeError here = the library does not export a declared symbol
+        fn.restype = res
+        fn.argtypes = args
+    L._tc_signatures = sig
+    _LIBS[path] = L
+    return L
+
+
+def _u32(values):
+    values = [int(v) for v in values]
+    return (ctypes.c_uint32 * max(len(values), 1))(*values)
+
+
+def _ptr(x):
+    """Device pointer of a torch tensor, address of a numpy array (host-emulation tests) or an int."""
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return ctypes.c_void_p(x.data_ptr())
+    if hasattr(x, "ctypes"):
+        return ctypes.c_void_p(x.ctypes.data)
+    return ctypes.c_void_p(int(x))
+
+
+class Srs:
+    def __init__(self, ctx, handle, shape, flags):
+        self.ctx, self.handle, self.shape, self.flags = ctx, handle, tuple(shape), flags
+
+    def size(self, first_axis=0):
+        return int(self.ctx.lib.tc_srs_size(self.handle, first_axis))
+
+    def point(self, index, first_axis=0):
+        out = ctypes.create_string_buffer(96)
+        self.ctx._check(self.ctx.lib.tc_srs_get_point(self.ctx.handle, self.handle, first_axis, index, out))
+        return out.raw
+
+    def close(self):
+        if self.handle:
+            self.ctx.lib.tc_srs_destroy(self.handle)
+            self.handle = None
+
+
+class Tree:
+    def __init__(self, ctx, handle, desc_keepalive, grid, node_shape, leaf_kind, leaf_shapes=None):
+        self.ctx, self.handle, self._keep = ctx, handle, desc_keepalive
+        self.grid, self.node_shape, self.leaf_kind, self.leaf_shapes = tuple(grid), tuple(node_shape), leaf_kind, leaf_shapes
+
+    @property
+    def root(self):
+        out = ctypes.create_string_buffer(96)
+        self.ctx._check(self.ctx.lib.tc_terkle_root(self.handle, out))
+        return out.raw
+
+    @property
+    def levels(self):
+        return int(self.ctx.lib.tc_terkle_levels(self.handle))
+
+    def level_info(self, level):
+        grid = (ctypes.c_uint32 * TC_MAX_ORDER)()
+        n = ctypes.c_uint64()
+        self.ctx._check(self.ctx.lib.tc_terkle_level_info(self.handle, level, grid, ctypes.byref(n)))
+        return tuple(grid[: len(self.grid)]), int(n.value)
+
+    def node(self, level, index):
+        out = ctypes.create_string_buffer(96)
+        self.ctx._check(self.ctx.lib.tc_terkle_node(self.ctx.handle, self.handle, level, index, out))
+        return out.raw
+
+    def path(self, leaf_index, inner_index=None):
+        return self.ctx.path_from_grid(self.grid, self.node_shape, self.leaf_kind, leaf_index,
+                                       None if inner_index is None else self._leaf_shape(leaf_index), inner_index)
+
+    def _leaf_shape(self, leaf_index):
+        flat = 0
+        for i, g in zip(leaf_index, self.grid):
+            flat = flat * g + int(i)
+        return self.leaf_shapes[flat]
+
+    def open(self, leaf_index, inner_index=None):
+        (proof,) = self.open_batch([leaf_index], None if inner_index is None else [inner_index])
+        return proof
+
+    def open_batch(self, leaf_indices, inner_indices=None, stride=8192):
+        count = len(leaf_indices)
+        flat_leaf = [int(v) for li in leaf_indices for v in li]
+        flat_inner = [int(v) for ii in (inner_indices or []) for v in ii]
+        buf = ctypes.create_string_buffer(stride * max(count, 1))
+        lens = (ctypes.c_size_t * max(count, 1))()
+        self.ctx._check(self.ctx.lib.tc_terkle_open_batch(
+            self.ctx.handle, self.handle, count, _u32(flat_leaf), _u32(flat_inner) if inner_indices else None,
+            buf, stride, lens))
+        return [buf.raw[i * stride : i * stride + lens[i]] for i in range(count)]
+
+    def close(self):
+        if self.handle:
+            self.ctx.lib.tc_tree_destroy(self.handle)
+            self.handle = None
+
+
+class Context:
+    """One GPU context.  `stream` is a raw hipStream_t (int) or None for the default stream."""
+
+    def __init__(self, device=0, stream=None, lib=None):
+        self.lib = lib or load_library()
+        h = ctypes.c_void_p()
+        rc = self.lib.tc_ctx_create(ctypes.byref(h), int(device), ctypes.c_void_p(stream) if stream else None)
+        if rc != TC_OK:
+            raise TcError(rc, "tc_ctx_create failed (is a GPU visible?)")
+        self.handle = h
+        self._vk = {}
+
+    def _check(self, rc):
+        if rc != TC_OK:
+            raise TcError(rc, self.lib.tc_last_error(self.handle).decode())
+
+    def sync(self):
+        self._check(self.lib.tc_ctx_sync(self.handle))
+
+    def close(self):
+        for vk in self._vk.values():
+            self.lib.tc_vk_destroy(vk)
+        self._vk = {}
+        if self.handle:
+            self.lib.tc_ctx_destroy(self.handle)
+            self.handle = None
+
+    # -- Setup ---------------------------------------------------------------------------
+    def setup_from_trapdoor(self, tau_bytes, shape, flags=0):
+        h = ctypes.c_void_p()
+        m = len(shape)
+        self._check(self.lib.tc_setup_from_trapdoor(self.handle, bytes(tau_bytes), m, _u32(shape), flags, ctypes.byref(h)))
+        return Srs(self, h, shape, flags)
+
+    # -- encode / commit / open ------------------------------------------------------------
+    def encode_tensor(self, src, src_dtype, n, inv_scale, dst):
+        self._check(self.lib.tc_encode_tensor(self.handle, _ptr(src), src_dtype, n, float(inv_scale), _ptr(dst)))
+
+    def commit(self, srs, scalars, dtype):
+        out = ctypes.create_string_buffer(96)
+        self._check(self.lib.tc_commit(self.handle, srs.handle, _ptr(scalars), dtype, out))
+        return out.raw
+
+    def commit_batch(self, srs_list, scalars_list, dtypes):
+        n = len(srs_list)
+        out = ctypes.create_string_buffer(96 * max(n, 1))
+        a = (ctypes.c_void_p * max(n, 1))(*[s.handle for s in srs_list])
+        b = (ctypes.c_void_p * max(n, 1))(*[_ptr(s) for s in scalars_list])
+        c = (ctypes.c_int * max(n, 1))(*dtypes)
+        self._check(self.lib.tc_commit_batch(self.handle, n, a, b, c, out))
+        return [out.raw[96 * i : 96 * (i + 1)] for i in range(n)]
+
+    def open(self, srs, scalars, dtype, kappa):
+        y = ctypes.create_string_buffer(32)
+        pi = ctypes.create_string_buffer(96 * len(srs.shape))
+        self._check(self.lib.tc_open(self.handle, srs.handle, _ptr(scalars), dtype, _u32(kappa), y, pi))
+        return y.raw, [pi.raw[96 * i : 96 * (i + 1)] for i in range(len(srs.shape))]
+
+    # -- verify ------------------------------------------------------------------------------
+    def vk_from_trapdoor(self, tau_bytes, m=TC_MAX_ORDER):
+        key = (bytes(tau_bytes), m)
+        if key not in self._vk:
+            h = ctypes.c_void_p()
+            rc = self.lib.tc_vk_from_trapdoor(bytes(tau_bytes), m, ctypes.byref(h))
+            if rc != TC_OK:
+                raise TcError(rc, "tc_vk_from_trapdoor")
+            self._vk[key] = h
+        return self._vk[key]
+
+    def verify(self, vk, shape, commitment, kappa, y, pi):
+        rc = self.lib.tc_verify(self.handle, vk, len(shape), _u32(shape), bytes(commitment), _u32(kappa), bytes(y),
+                                b"".join(pi))
+        if rc == TC_ERR_VERIFY:
+            return False
+        self._check(rc)
+        return True
+
+    # -- Terkle ------------------------------------------------------------------------------
+    def terkle_build_entries(self, node_srs, payload, dtype, grid, node_shape):
+        d = tc_tree_desc()
+        d.m = len(grid)
+        for j, (g, s) in enumerate(zip(grid, node_shape)):
+            d.grid[j], d.node_shape[j] = int(g), int(s)
+        d.node_srs = node_srs.handle
+        d.leaf_kind = TC_LEAF_ENTRIES
+        d.d_payload = _ptr(payload)
+        d.dtype = dtype
+        h = ctypes.c_void_p()
+        self._check(self.lib.tc_terkle_build(self.handle, ctypes.byref(d), ctypes.byref(h)))
+        return Tree(self, h, (d, payload, node_srs), grid, node_shape, TC_LEAF_ENTRIES)
+
+    def terkle_build_tensors(self, node_srs, leaf_srs, leaf_scalars, leaf_dtypes, grid, node_shape):
+        n = len(leaf_srs)
+        d = tc_tree_desc()
+        d.m = len(grid)
+        for j, (g, s) in enumerate(zip(grid, node_shape)):
+            d.grid[j], d.node_shape[j] = int(g), int(s)
+        d.node_srs = node_srs.handle
+        d.leaf_kind = TC_LEAF_TENSORS
+        a = (ctypes.c_void_p * n)(*[s.handle for s in leaf_srs])
+        b = (ctypes.c_void_p * n)(*[_ptr(s) for s in leaf_scalars])
+        c = (ctypes.c_int * n)(*leaf_dtypes)
+        d.leaf_srs, d.d_leaf_scalars, d.leaf_dtype = a, b, c
+        h = ctypes.c_void_p()
+        self._check(self.lib.tc_terkle_build(self.handle, ctypes.byref(d), ctypes.byref(h)))
+        return Tree(self, h, (d, a, b, c, leaf_scalars, leaf_srs, node_srs), grid, node_shape, TC_LEAF_TENSORS,
+                    [s.shape for s in leaf_srs])
+
+    def path_from_grid(self, grid, node_shape, leaf_kind, leaf_index, inner_shape=None, inner_index=None):
+        p = tc_path()
+        rc = self.lib.tc_path_from_grid(len(grid), _u32(grid), _u32(node_shape), leaf_kind, _u32(leaf_index),
+                                        len(inner_shape) if inner_shape else 0,
+                                        _u32(inner_shape) if inner_shape else None,
+                                        _u32(inner_index) if inner_index is not None else None, ctypes.byref(p))
+        if rc != TC_OK:
+            raise TcError(rc, "tc_path_from_grid")
+        return p
+
+    def verify_path(self, vk, path, root, leaf_value, proof):
+        rc = self.lib.tc_verify_path(self.handle, vk, ctypes.byref(path), bytes(root), bytes(leaf_value), bytes(proof),
+                                     len(proof))
+        if rc == TC_ERR_VERIFY:
+            return False
+        self._check(rc)
+        return True
+
+    def verify_paths_batch(self, vk, paths, roots, leaf_values, proofs):
+        n = len(paths)
+        stride = max([len(p) for p in proofs] + [1])
+        buf = b"".join(p + bytes(stride - len(p)) for p in proofs)
+        lens = (ctypes.c_size_t * max(n, 1))(*[len(p) for p in proofs])
+        arr = (tc_path * max(n, 1))(*paths)
+        res = (ctypes.c_int * max(n, 1))()
+        self._check(self.lib.tc_verify_paths_batch(self.handle, vk, n, arr, b"".join(roots), b"".join(leaf_values), buf,
+                                                   stride, lens, res))
+        return [res[i] == TC_OK for i in range(n)]

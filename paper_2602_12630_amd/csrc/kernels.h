@@ -1,0 +1,812 @@
+/*
+ * Kernel bodies of the library, one functor per kernel (lane = one call of
+ * operator()).  Host code in tc_lib.cpp launches them through rt::launch.
+ *
+ * Commitment (Def. 4.1, Com) is the multi-scalar multiplication
+ *     C_T = sum_i [e(T[i])] S[i]
+ * over the Lagrange-basis SRS.  Scalars of quantised tensors are one signed
+ * 8- or 16-bit digit, so the bucket method needs one insertion per entry:
+ *     count digits -> prefix sums -> scatter point indices by bucket
+ *     -> balanced segmented sums of SRS points per bucket (several passes)
+ *     -> sum_k k B_k per window -> combine windows.
+ * Full-width scalars (quotient values of Open, child commitments mapped into
+ * Fr inside the tree) use the same engine with 8- or 16-bit signed windows, or
+ * fixed-base window tables when the bases are the 16 points of a node shape.
+ */
+#pragma once
+#include "g1.h"
+#include "rt.h"
+
+namespace tc {
+
+enum { DT_I8 = 1, DT_I16 = 2, DT_FR = 3, DT_F16 = 4 };
+
+struct alignas(16) fr_plain {           /* canonical (non-Montgomery) Fr value, 8 limbs */
+    uint32_t l[8];
+};
+
+/* ---- small utilities ---------------------------------------------------------- */
+struct Fill32 {
+    uint32_t* dst;
+    uint32_t value;
+    TC_DEV void operator()(uint32_t t) const { dst[t] = value; }
+};
+
+/* fp16 -> int16 by one float multiply, round-half-even, clamp; or pass-through copies */
+struct EncodeF16 {
+    const uint16_t* src;
+    int16_t* dst;
+    float inv_scale;
+    TC_DEV static float half_to_float(uint16_t h) {
+        uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+        uint32_t exp = (h >> 10) & 0x1Fu;
+        uint32_t man = h & 0x3FFu;
+        uint32_t bits;
+        if (exp == 0) {
+            if (man == 0) {
+                bits = sign;
+            } else {                         /* subnormal: normalise */
+                int e = -1;
+                do { man <<= 1; ++e; } while (!(man & 0x400u));
+                bits = sign | ((uint32_t)(127 - 15 - e) << 23) | ((man & 0x3FFu) << 13);
+            }
+        } else if (exp == 31) {
+            bits = sign | 0x7F800000u | (man << 13);
+        } else {
+            bits = sign | ((exp + 112u) << 23) | (man << 13);
+        }
+        float f;
+        memcpy(&f, &bits, 4);
+        return f;
+    }
+    TC_DEV void operator()(uint32_t t) const {
+        float x = half_to_float(src[t]);
+        float y = x * inv_scale;
+        float r = __builtin_rintf(y);         /* round half to even in the default mode */
+        if (!(r == r)) r = 0.0f;              /* NaN -> 0 */
+        if (r > 32767.0f) r = 32767.0f;
+        if (r < -32767.0f) r = -32767.0f;
+        dst[t] = (int16_t)r;
+    }
+};
+struct Copy8 {
+    const uint8_t* src;
+    uint8_t* dst;
+    TC_DEV void operator()(uint32_t t) const { dst[t] = src[t]; }
+};
+struct Copy16 {
+    const uint16_t* src;
+    uint16_t* dst;
+    TC_DEV void operator()(uint32_t t) const { dst[t] = src[t]; }
+};
+
+/* ---- signed window digits ----------------------------------------------------- */
+/* Digit w of a canonical Fr value for window width c (c divides 32... c in {8,16}):
+ * raw = bits + carry; raw > 2^(c-1) => digit = raw - 2^c and carry 1.  Digits lie in
+ * [-(2^(c-1) - 1), 2^(c-1)].  Calls must walk w = 0, 1, .. in order and thread `carry`. */
+TC_HD int32_t fr_window_digit(const uint32_t* v, int w, int c, uint32_t& carry) {
+    int bit = w * c;
+    uint32_t raw = (v[bit >> 5] >> (bit & 31)) & ((1u << c) - 1u);
+    raw += carry;
+    uint32_t half = 1u << (c - 1);
+    if (raw > half) {
+        carry = 1;
+        return (int32_t)raw - (int32_t)(1u << c);
+    }
+    carry = 0;
+    return (int32_t)raw;
+}
+
+TC_HD int32_t small_scalar(const void* s, int dtype, uint64_t i) {
+    return dtype == DT_I8 ? (int32_t)((const int8_t*)s)[i] : (int32_t)((const int16_t*)s)[i];
+}
+
+/* ---- MSM: count, scatter --------------------------------------------------------- */
+struct MsmCount {
+    const void* scalars;
+    int dtype;
+    int W, c;
+    uint32_t nb;          /* buckets per window = 2^(c-1) */
+    uint32_t* cnt;        /* W * nb counters */
+    TC_DEV void operator()(uint32_t t) const {
+        if (dtype == DT_FR) {
+            const uint32_t* v = ((const fr_plain*)scalars)[t].l;
+            uint32_t carry = 0;
+            for (int w = 0; w < W; ++w) {
+                int32_t d = fr_window_digit(v, w, c, carry);
+                if (d) atomic_add_u32(&cnt[(uint32_t)w * nb + (uint32_t)(d < 0 ? -d : d) - 1u], 1u);
+            }
+        } else {
+            int32_t d = small_scalar(scalars, dtype, t);
+            if (d) atomic_add_u32(&cnt[(uint32_t)(d < 0 ? -d : d) - 1u], 1u);
+        }
+    }
+};
+
+struct MsmScatter {
+    const void* scalars;
+    int dtype;
+    int W, c;
+    uint32_t nb;
+    const uint32_t* start;   /* exclusive prefix of cnt */
+    uint32_t* cursor;        /* zeroed, W * nb */
+    uint32_t* sorted;        /* point index | sign << 31, grouped by bucket */
+    TC_DEV void put(uint32_t key, uint32_t i, bool negative) const {
+        uint32_t pos = start[key] + atomic_add_u32(&cursor[key], 1u);
+        sorted[pos] = i | (negative ? 0x80000000u : 0u);
+    }
+    TC_DEV void operator()(uint32_t t) const {
+        if (dtype == DT_FR) {
+            const uint32_t* v = ((const fr_plain*)scalars)[t].l;
+            uint32_t carry = 0;
+            for (int w = 0; w < W; ++w) {
+                int32_t d = fr_window_digit(v, w, c, carry);
+                if (d) put((uint32_t)w * nb + (uint32_t)(d < 0 ? -d : d) - 1u, t, d < 0);
+            }
+        } else {
+            int32_t d = small_scalar(scalars, dtype, t);
+            if (d) put((uint32_t)(d < 0 ? -d : d) - 1u, t, d < 0);
+        }
+    }
+};
+
+/* ---- prefix sums over bucket counts (three lane-independent steps) ---------------- */
+/* chunk = 256 consecutive buckets.  A: per-chunk totals of cnt and of ceil(cnt / L);
+ * B: one lane turns the chunk totals into exclusive offsets; C: per-chunk serial prefix. */
+constexpr uint32_t SCAN_CHUNK = 256;
+
+struct ScanChunkTotals {
+    const uint32_t* cnt;
+    uint32_t n, L;
+    uint32_t* tot_a;
+    uint32_t* tot_b;
+    TC_DEV void operator()(uint32_t ch) const {
+        uint32_t lo = ch * SCAN_CHUNK, hi = lo + SCAN_CHUNK < n ? lo + SCAN_CHUNK : n;
+        uint32_t a = 0, b = 0;
+        for (uint32_t i = lo; i < hi; ++i) {
+            uint32_t v = cnt[i];
+            a += v;
+            b += (v + L - 1) / L;
+        }
+        tot_a[ch] = a;
+        tot_b[ch] = b;
+    }
+};
+struct ScanChunkOffsets {
+    uint32_t nchunks;
+    uint32_t* tot_a;
+    uint32_t* tot_b;
+    TC_DEV void operator()(uint32_t) const {
+        uint32_t a = 0, b = 0;
+        for (uint32_t i = 0; i < nchunks; ++i) {
+            uint32_t va = tot_a[i], vb = tot_b[i];
+            tot_a[i] = a;
+            tot_b[i] = b;
+            a += va;
+            b += vb;
+        }
+        tot_a[nchunks] = a;
+        tot_b[nchunks] = b;
+    }
+};
+struct ScanWrite {
+    const uint32_t* cnt;
+    uint32_t n, L;
+    const uint32_t* tot_a;
+    const uint32_t* tot_b;
+    uint32_t nchunks;
+    uint32_t* start;     /* n + 1 */
+    uint32_t* lstart;    /* n + 1 */
+    uint32_t* zero_me;   /* optional array of n counters to clear (scatter cursors) */
+    TC_DEV void operator()(uint32_t ch) const {
+        uint32_t lo = ch * SCAN_CHUNK, hi = lo + SCAN_CHUNK < n ? lo + SCAN_CHUNK : n;
+        uint32_t a = tot_a[ch], b = tot_b[ch];
+        for (uint32_t i = lo; i < hi; ++i) {
+            uint32_t v = cnt[i];
+            start[i] = a;
+            lstart[i] = b;
+            a += v;
+            b += (v + L - 1) / L;
+            if (zero_me) zero_me[i] = 0;
+        }
+        if (ch == nchunks - 1) {
+            start[n] = tot_a[nchunks];
+            lstart[n] = tot_b[nchunks];
+        }
+    }
+};
+/* cnt[i] = prefix[i + 1] - prefix[i] */
+struct DiffCounts {
+    const uint32_t* prefix;
+    uint32_t* cnt;
+    TC_DEV void operator()(uint32_t t) const { cnt[t] = prefix[t + 1] - prefix[t]; }
+};
+
+/* largest b in [0, n) with prefix[b] <= t, for a non-decreasing prefix with prefix[n] > t */
+TC_HD uint32_t find_segment(const uint32_t* prefix, uint32_t n, uint32_t t) {
+    uint32_t lo = 0, hi = n;       /* invariant: prefix[lo] <= t < prefix[hi] */
+    while (hi - lo > 1) {
+        uint32_t mid = lo + ((hi - lo) >> 1);
+        if (prefix[mid] <= t) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+/* ---- MSM: balanced segmented sums per bucket -------------------------------------- */
+/* Lane t owns sub-run `t - lstart[b]` of bucket b: at most L entries, all of one bucket.
+ * Output slot t, so the partial sums of bucket b are the slots lstart[b] .. lstart[b+1]. */
+struct AccAffine {
+    const g1_affine* pts;
+    const uint32_t* sorted;
+    const uint32_t* start;
+    const uint32_t* lstart;
+    uint32_t nbk, L;
+    g1_xyzz* out;
+    TC_DEV void operator()(uint32_t t) const {
+        if (t >= lstart[nbk]) return;
+        uint32_t b = find_segment(lstart, nbk, t);
+        uint32_t begin = start[b] + (t - lstart[b]) * L;
+        uint32_t end = begin + L < start[b + 1] ? begin + L : start[b + 1];
+        g1_xyzz acc = xyzz_identity();
+        for (uint32_t i = begin; i < end; ++i) {
+            uint32_t e = sorted[i];
+            g1_affine p = pts[e & 0x7FFFFFFFu];
+            if (e >> 31) p.y = fp_neg(p.y);
+            acc = xyzz_madd(acc, p);
+        }
+        out[t] = acc;
+    }
+};
+struct AccXyzz {
+    const g1_xyzz* in;
+    const uint32_t* start;     /* slots of bucket b in `in`: start[b] .. start[b+1] */
+    const uint32_t* lstart;
+    uint32_t nbk, L;
+    g1_xyzz* out;
+    TC_DEV void operator()(uint32_t t) const {
+        if (t >= lstart[nbk]) return;
+        uint32_t b = find_segment(lstart, nbk, t);
+        uint32_t begin = start[b] + (t - lstart[b]) * L;
+        uint32_t end = begin + L < start[b + 1] ? begin + L : start[b + 1];
+        g1_xyzz acc = in[begin];
+        for (uint32_t i = begin + 1; i < end; ++i) acc = xyzz_add(acc, in[i]);
+        out[t] = acc;
+    }
+};
+/* last pass: one lane per bucket sums whatever partials remain (bounded by the pass plan) */
+struct AccFinal {
+    const g1_xyzz* in;
+    const uint32_t* start;
+    g1_xyzz* bucket;
+    TC_DEV void operator()(uint32_t b) const {
+        uint32_t begin = start[b], end = start[b + 1];
+        g1_xyzz acc = xyzz_identity();
+        for (uint32_t i = begin; i < end; ++i) acc = xyzz_add(acc, in[i]);
+        bucket[b] = acc;
+    }
+};
+
+/* ---- bucket reduction: sum_k k B_k --------------------------------------------------- */
+/* Cooperative kernel (one workgroup = BLOCK consecutive entries of `in`), phases separated
+ * by barriers.  For block g:  S_g = sum_j in[g BLOCK + j]  and
+ * W_g = sum_j (j + 1) in[g BLOCK + j]  (suffix sums by doubling strides, then their sum). */
+template <int BLOCK>
+struct WeightedBlockSum {
+    static constexpr int LOG = (BLOCK == 256) ? 8 : (BLOCK == 128) ? 7 : (BLOCK == 64) ? 6 : -1;
+    static constexpr int PHASES = 1 + LOG + 1 + LOG + 1;
+    static constexpr size_t LDS_BYTES = 2 * BLOCK * sizeof(g1_xyzz);
+    const g1_xyzz* in;
+    uint32_t n;                 /* entries; positions >= n count as the identity */
+    g1_xyzz* out_w;             /* per block */
+    g1_xyzz* out_s;             /* per block */
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        g1_xyzz* buf0 = (g1_xyzz*)lds;
+        g1_xyzz* buf1 = buf0 + BLOCK;
+        if (ph == 0) {
+            uint64_t i = (uint64_t)wg * BLOCK + lane;
+            buf0[lane] = i < n ? in[i] : xyzz_identity();
+            return;
+        }
+        if (ph <= LOG) {                       /* suffix sums, ping-pong */
+            int s = ph - 1;
+            g1_xyzz* cur = (s & 1) ? buf1 : buf0;
+            g1_xyzz* nxt = (s & 1) ? buf0 : buf1;
+            uint32_t stride = 1u << s;
+            g1_xyzz v = cur[lane];
+            if (lane + stride < (uint32_t)BLOCK) v = xyzz_add(v, cur[lane + stride]);
+            nxt[lane] = v;
+            return;
+        }
+        g1_xyzz* cur = (LOG & 1) ? buf1 : buf0;     /* suffix sums live here now */
+        if (ph == LOG + 1) {
+            if (lane == 0) out_s[wg] = cur[0];
+            return;
+        }
+        if (ph <= 2 * LOG + 1) {                     /* tree sum in place */
+            int s = ph - (LOG + 2);
+            uint32_t stride = 1u << s;
+            if ((lane & (2 * stride - 1)) == 0) cur[lane] = xyzz_add(cur[lane], cur[lane + stride]);
+            return;
+        }
+        if (lane == 0) out_w[wg] = cur[0];
+    }
+};
+
+/* One lane per window: Wsum = sumW + BLOCK * (W2 - S2) where, over the G blocks of the window,
+ * sumW = sum_g W_g, W2 = sum_g (g+1) S_g, S2 = sum_g S_g.  With G == 1: Wsum = W_0. */
+struct WindowFinish {
+    const g1_xyzz* w1;     /* W_g of stage 1, G per window (G == 1) or sum of them (stage 3 S) */
+    const g1_xyzz* w2;     /* W of stage 2 per window */
+    const g1_xyzz* s2;     /* S of stage 2 per window */
+    int G, log_block;
+    g1_xyzz* out;
+    TC_DEV void operator()(uint32_t w) const {
+        if (G == 1) { out[w] = w1[w]; return; }
+        g1_xyzz t = xyzz_add(w2[w], xyzz_neg(s2[w]));
+        for (int i = 0; i < log_block; ++i) t = xyzz_dbl(t);
+        out[w] = xyzz_add(t, w1[w]);
+    }
+};
+/* One lane: Horner over windows, result = sum_w 2^(c w) Wsum_w */
+struct WindowCombine {
+    const g1_xyzz* wsum;
+    int W, c;
+    g1_xyzz* out;
+    TC_DEV void operator()(uint32_t) const {
+        g1_xyzz acc = wsum[W - 1];
+        for (int w = W - 2; w >= 0; --w) {
+            for (int i = 0; i < c; ++i) acc = xyzz_dbl(acc);
+            acc = xyzz_add(acc, wsum[w]);
+        }
+        out[0] = acc;
+    }
+};
+
+/* ---- normalisation: XYZZ -> affine (batched inversion) and canonical bytes ---------- */
+/* Lane handles G consecutive points with one field inversion (Montgomery's trick).  The
+ * running products are parked in out[i].x until the backward sweep overwrites them. */
+struct BatchNormalize {
+    const g1_xyzz* in;
+    uint64_t n;
+    uint32_t G;
+    g1_affine* out;
+    TC_DEV void operator()(uint32_t t) const {
+        uint64_t lo = (uint64_t)t * G, hi = lo + G < n ? lo + G : n;
+        if (lo >= hi) return;
+        fp_t run = fe_one<FpParams>();
+        for (uint64_t i = lo; i < hi; ++i) {
+            out[i].x = run;                       /* product of z_lo .. z_{i-1} */
+            if (!fe_is_zero(in[i].ZZ)) run = fp_mul(run, fp_mul(in[i].ZZ, in[i].ZZZ));
+        }
+        fp_t inv = fe_inv_fermat<FpParams>(run);   /* run != 0: product of non-zero values */
+        for (uint64_t i = hi; i-- > lo;) {
+            g1_xyzz p = in[i];
+            if (fe_is_zero(p.ZZ)) {
+                out[i] = affine_identity();
+                continue;
+            }
+            fp_t zi = fp_mul(inv, out[i].x);       /* 1 / (ZZ_i ZZZ_i) */
+            inv = fp_mul(inv, fp_mul(p.ZZ, p.ZZZ));
+            out[i] = xyzz_to_affine_with_inv(p, zi);
+        }
+    }
+};
+struct ToCanonical {
+    const g1_affine* in;
+    uint32_t* out;          /* 24 words per point */
+    TC_DEV void operator()(uint32_t t) const { affine_to_canonical(in[t], out + 24 * (uint64_t)t); }
+};
+struct PhiKernel {
+    const g1_affine* in;
+    fr_plain* out;
+    TC_DEV void operator()(uint32_t t) const {
+        fr_t v = phi_map(in[t]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[t].l[i] = v.l[i];
+    }
+};
+
+/* ---- fixed-base window tables -------------------------------------------------------- */
+/* Table layout: entry ((k * FB_W + w) * FB_NB + j - 1) = j * 2^(c w) * B_k, affine, j = 1..2^(c-1),
+ * c = FB_C (16: 16 windows of 32768 entries, 50 MB per base). */
+#ifndef TC_FB_C
+#define TC_FB_C 16             /* window width; the host-emulation build of the tests uses 8 */
+#endif
+constexpr int FB_C = TC_FB_C;
+constexpr int FB_W = 256 / FB_C;
+constexpr uint32_t FB_NB = 1u << (FB_C - 1);
+constexpr uint32_t FB_CHUNK = 64;
+
+struct FbWindowBases {         /* lane k: 2^(c w) B_k for every window w */
+    const g1_affine* bases;
+    g1_xyzz* out;              /* nbases * FB_W */
+    TC_DEV void operator()(uint32_t k) const {
+        g1_xyzz p = xyzz_from_affine(bases[k]);
+        for (int w = 0; w < FB_W; ++w) {
+            out[(uint64_t)k * FB_W + w] = p;
+            if (w + 1 < FB_W)
+                for (int i = 0; i < FB_C; ++i) p = xyzz_dbl(p);
+        }
+    }
+};
+struct FbChunkFill {           /* lane (bw, chunk): multiples j0 .. j0 + 63 of window base bw */
+    const g1_affine* wbase;    /* affine window bases, `count` of them starting at bw0 */
+    uint32_t bw0;
+    g1_xyzz* out;              /* count * FB_NB */
+    TC_DEV void operator()(uint32_t t) const {
+        uint32_t chunks = FB_NB / FB_CHUNK;
+        uint32_t bw = t / chunks, ch = t % chunks;
+        g1_affine b = wbase[bw0 + bw];
+        uint32_t j0 = ch * FB_CHUNK + 1;
+        g1_xyzz acc = xyzz_mul_affine(&j0, 17, b);
+        uint64_t base = (uint64_t)bw * FB_NB + (j0 - 1);
+        for (uint32_t i = 0; i < FB_CHUNK; ++i) {
+            out[base + i] = acc;
+            acc = xyzz_madd(acc, b);
+        }
+    }
+};
+
+/* acc += sum_w digit_w(v) * table[(k, w)] for a canonical Fr value v */
+TC_HD g1_xyzz fb_mul_accumulate(g1_xyzz acc, const g1_affine* table, uint32_t k, const uint32_t* v) {
+    uint32_t carry = 0;
+    for (int w = 0; w < FB_W; ++w) {
+        int32_t d = fr_window_digit(v, w, FB_C, carry);
+        if (d) {
+            g1_affine p = table[((uint64_t)k * FB_W + w) * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u];
+            if (d < 0) p.y = fp_neg(p.y);
+            acc = xyzz_madd(acc, p);
+        }
+    }
+    return acc;
+}
+/* same for a small signed integer |d| <= 2^15 (one lookup when the window is 16 bits wide) */
+TC_HD g1_xyzz fb_small_accumulate(g1_xyzz acc, const g1_affine* table, uint32_t k, int32_t d) {
+    if (!d) return acc;
+    uint32_t mag = (uint32_t)(d < 0 ? -d : d);
+    if (FB_C == 16) {
+        g1_affine p = table[((uint64_t)k * FB_W) * FB_NB + mag - 1u];
+        if (d < 0) p.y = fp_neg(p.y);
+        return xyzz_madd(acc, p);
+    }
+    uint32_t v[8] = {mag, 0, 0, 0, 0, 0, 0, 0};
+    uint32_t carry = 0;
+    for (int w = 0; w * FB_C < 24; ++w) {
+        int32_t dw = fr_window_digit(v, w, FB_C, carry);
+        if (dw) {
+            bool negative = (dw < 0) != (d < 0);
+            g1_affine p = table[((uint64_t)k * FB_W + w) * FB_NB + (uint32_t)(dw < 0 ? -dw : dw) - 1u];
+            if (negative) p.y = fp_neg(p.y);
+            acc = xyzz_madd(acc, p);
+        }
+    }
+    return acc;
+}
+
+/* ---- SRS generation (Def. 4.1 Setup, Lagrange image) ---------------------------------- */
+struct ShapeInfo {
+    int m;
+    uint32_t d[4];
+};
+TC_HD void unflatten(uint64_t f, const ShapeInfo& s, int first_axis, uint32_t* idx) {
+    for (int j = s.m - 1; j >= first_axis; --j) {
+        idx[j] = (uint32_t)(f % s.d[j]);
+        f /= s.d[j];
+    }
+}
+struct SrsGen {                /* lane i: S^(a)[i] = [prod_{j>=a} l_j[i_j]] G */
+    ShapeInfo shape;
+    int first_axis;
+    const fr_t* ell;           /* Montgomery Lagrange values, axes concatenated */
+    uint32_t ell_off[4];
+    const g1_affine* gtable;   /* fixed-base table of G (one base) */
+    uint64_t i0;               /* first point of this launch */
+    g1_xyzz* out;              /* indexed from 0 for point i0 */
+    TC_DEV void operator()(uint32_t t) const {
+        uint64_t i = i0 + t;
+        uint32_t idx[4];
+        unflatten(i, shape, first_axis, idx);
+        fr_t s = ell[ell_off[first_axis] + idx[first_axis]];
+        for (int j = first_axis + 1; j < shape.m; ++j) s = fr_mul(s, ell[ell_off[j] + idx[j]]);
+        fr_t plain = fe_to_plain(s);
+        out[t] = fb_mul_accumulate(xyzz_identity(), gtable, 0, plain.l);
+    }
+};
+
+/* ---- Terkle node commitments ----------------------------------------------------------- */
+struct TreeGeom {
+    int m;
+    uint32_t node[4];          /* node shape */
+    uint32_t below[4];         /* grid of the level below (payload grid for level 0) */
+    uint32_t grid[4];          /* grid of this level */
+    uint32_t B;                /* arity */
+};
+/* flat index in the level below of child k (flat in node shape) of node a (flat in grid); -1 if outside */
+TC_HD int64_t child_index(const TreeGeom& g, uint64_t a, uint32_t k) {
+    uint32_t ai[4], ki[4];
+    for (int j = g.m - 1; j >= 0; --j) {
+        ai[j] = (uint32_t)(a % g.grid[j]);
+        a /= g.grid[j];
+        ki[j] = k % g.node[j];
+        k /= g.node[j];
+    }
+    uint64_t f = 0;
+    for (int j = 0; j < g.m; ++j) {
+        uint64_t p = (uint64_t)ai[j] * g.node[j] + ki[j];
+        if (p >= g.below[j]) return -1;
+        f = f * g.below[j] + p;
+    }
+    return (int64_t)f;
+}
+/* bottom level of an entries tree: lane = node, children are small integers */
+struct NodeCommitSmall {
+    TreeGeom g;
+    const void* payload;
+    int dtype;
+    const g1_affine* table;
+    g1_xyzz* out;
+    TC_DEV void operator()(uint32_t a) const {
+        g1_xyzz acc = xyzz_identity();
+        for (uint32_t k = 0; k < g.B; ++k) {
+            int64_t f = child_index(g, a, k);
+            if (f < 0) continue;
+            acc = fb_small_accumulate(acc, table, k, small_scalar(payload, dtype, (uint64_t)f));
+        }
+        out[a] = acc;
+    }
+};
+/* upper levels: lane = (node, child); the child's value is phi of the commitment below */
+struct NodeCommitFr {
+    TreeGeom g;
+    const fr_plain* below;
+    const g1_affine* table;
+    g1_xyzz* out;               /* n_nodes * B partial sums */
+    TC_DEV void operator()(uint32_t t) const {
+        uint32_t a = t / g.B, k = t % g.B;
+        int64_t f = child_index(g, a, k);
+        g1_xyzz acc = xyzz_identity();
+        if (f >= 0) acc = fb_mul_accumulate(acc, table, k, below[f].l);
+        out[t] = acc;
+    }
+};
+/* out[i] = sum of in[i * group .. (i + 1) * group) */
+struct SumGroups {
+    const g1_xyzz* in;
+    uint32_t group;
+    g1_xyzz* out;
+    TC_DEV void operator()(uint32_t t) const {
+        const g1_xyzz* p = in + (uint64_t)t * group;
+        g1_xyzz acc = p[0];
+        for (uint32_t i = 1; i < group; ++i) acc = xyzz_add(acc, p[i]);
+        out[t] = acc;
+    }
+};
+/* out[i] = sum of in[off[i] .. off[i + 1]) */
+struct SumSegments {
+    const g1_xyzz* in;
+    const uint32_t* off;
+    g1_xyzz* out;
+    TC_DEV void operator()(uint32_t t) const {
+        g1_xyzz acc = xyzz_identity();
+        for (uint32_t i = off[t]; i < off[t + 1]; ++i) acc = xyzz_add(acc, in[i]);
+        out[t] = acc;
+    }
+};
+
+/* ---- Open: quotient values on the grid (Algorithm 1 in evaluation form) ----------------- */
+/* Along one axis of length d with the opening at position kap, for every line t of the slice:
+ *   q[k] = (g[k] - g[kap]) / (zeta_k - zeta_kap)            k != kap
+ *   q[kap] = - sum_{k != kap} (beta_k / beta_kap) q[k]       (value of the same polynomial at zeta_kap)
+ * with zeta_k = k + 1 and beta the barycentric weights of App. C. */
+struct AxisTables {
+    const fr_t* inv_int;     /* inv_int[j] = 1 / j (Montgomery), j = 1..d-1; entry 0 unused */
+    const fr_t* beta;        /* beta_k (Montgomery) */
+    const fr_t* beta_inv;    /* 1 / beta_k */
+};
+TC_HD fr_t scalar_as_fr(const void* s, int dtype, uint64_t i) {
+    if (dtype == DT_FR) return fe_from_limbs<FrParams>(((const fr_plain*)s)[i].l);
+    return fe_from_i32<FrParams>(small_scalar(s, dtype, i));
+}
+struct QuotientRows {        /* lane (k, t), k != kap */
+    const void* scalars;
+    int dtype;
+    uint64_t offset;         /* start of the slice */
+    uint32_t d, kap;
+    uint64_t inner;
+    AxisTables ax;
+    fr_plain* q;             /* d * inner */
+    TC_DEV void operator()(uint32_t lane) const {
+        uint32_t k = (uint32_t)(lane / inner);
+        uint64_t t = lane % inner;
+        if (k == kap) return;
+        fr_t num = fr_sub(scalar_as_fr(scalars, dtype, offset + (uint64_t)k * inner + t),
+                          scalar_as_fr(scalars, dtype, offset + (uint64_t)kap * inner + t));
+        uint32_t dist = k > kap ? k - kap : kap - k;
+        fr_t v = fr_mul(num, ax.inv_int[dist]);
+        if (k < kap) v = fr_neg(v);
+        fr_t plain = fe_to_plain(v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) q[(uint64_t)k * inner + t].l[i] = plain.l[i];
+    }
+};
+struct QuotientKappaRow {    /* lane t */
+    uint32_t d, kap;
+    uint64_t inner;
+    AxisTables ax;
+    fr_plain* q;
+    TC_DEV void operator()(uint32_t t) const {
+        fr_t acc = fe_zero<FrParams>();
+        for (uint32_t k = 0; k < d; ++k) {
+            if (k == kap) continue;
+            fr_t qv = fe_from_limbs<FrParams>(q[(uint64_t)k * inner + t].l);
+            acc = fr_add(acc, fr_mul(ax.beta[k], qv));
+        }
+        acc = fr_neg(fr_mul(acc, ax.beta_inv[kap]));
+        fr_t plain = fe_to_plain(acc);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) q[(uint64_t)kap * inner + t].l[i] = plain.l[i];
+    }
+};
+/* y = e(T[f]) as canonical bytes */
+struct FetchScalar {
+    const void* scalars;
+    int dtype;
+    uint64_t f;
+    fr_plain* out;
+    TC_DEV void operator()(uint32_t) const {
+        fr_t plain = fe_to_plain(scalar_as_fr(scalars, dtype, f));
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[0].l[i] = plain.l[i];
+    }
+};
+
+/* ---- Terkle openings of node tensors (small shapes, fixed-base tables) ------------------- */
+struct NodeOpenJob {           /* one (path, level) */
+    uint64_t node;             /* flat node index in the level grid */
+    uint32_t kappa[4];         /* child multi-index */
+    int level;                 /* 0 = bottom (children are payload entries) */
+    uint32_t term0;            /* first output slot of this job */
+};
+struct LevelView {             /* what a node's children are */
+    TreeGeom g;
+    const void* payload;       /* level 0 of an entries tree */
+    int dtype;
+    const fr_plain* below;     /* upper levels: phi values of the level below */
+};
+constexpr int MAX_LEVELS = 16;
+struct NodeOpenTerms {         /* lane (job, axis, term): one quotient value times its suffix-SRS point */
+    const NodeOpenJob* jobs;
+    LevelView lv[MAX_LEVELS];
+    ShapeInfo node;            /* node shape */
+    uint32_t terms_per_job;    /* sum_a prod_{j>=a} d_j */
+    uint32_t axis_first[5];    /* first term of axis a within a job */
+    AxisTables ax[4];
+    const g1_affine* table[4]; /* fixed-base tables of S^(a) */
+    g1_xyzz* out;              /* jobs * terms_per_job */
+    fr_plain* y_out;           /* per job: the opened value */
+
+    TC_DEV fr_t child_value(const LevelView& v, uint64_t a, const uint32_t* k) const {
+        uint32_t kf = 0;
+        for (int j = 0; j < node.m; ++j) kf = kf * node.d[j] + k[j];
+        int64_t f = child_index(v.g, a, kf);
+        if (f < 0) return fe_zero<FrParams>();
+        if (v.payload) return fe_from_i32<FrParams>(small_scalar(v.payload, v.dtype, (uint64_t)f));
+        return fe_from_limbs<FrParams>(v.below[f].l);
+    }
+    TC_DEV void operator()(uint32_t lane) const {
+        uint32_t job = lane / terms_per_job, term = lane % terms_per_job;
+        const NodeOpenJob& J = jobs[job];
+        const LevelView& v = lv[J.level];
+        int a = 0;
+        while (a + 1 < node.m && term >= axis_first[a + 1]) ++a;
+        uint32_t local = term - axis_first[a];
+        /* child multi-index: axes < a fixed to kappa, axes >= a from `local` */
+        uint32_t k[4];
+        for (int j = 0; j < a; ++j) k[j] = J.kappa[j];
+        unflatten(local, node, a, k);
+        uint32_t kap = J.kappa[a], d = node.d[a];
+        uint32_t kk[4];
+        for (int j = 0; j < node.m; ++j) kk[j] = k[j];
+        kk[a] = kap;
+        fr_t gk = child_value(v, J.node, kk);
+        fr_t qv;
+        if (k[a] != kap) {
+            uint32_t dist = k[a] > kap ? k[a] - kap : kap - k[a];
+            qv = fr_mul(fr_sub(child_value(v, J.node, k), gk), ax[a].inv_int[dist]);
+            if (k[a] < kap) qv = fr_neg(qv);
+        } else {
+            fr_t acc = fe_zero<FrParams>();
+            for (uint32_t x = 0; x < d; ++x) {
+                if (x == kap) continue;
+                kk[a] = x;
+                uint32_t dist = x > kap ? x - kap : kap - x;
+                fr_t t = fr_mul(fr_sub(child_value(v, J.node, kk), gk), ax[a].inv_int[dist]);
+                if (x < kap) t = fr_neg(t);
+                acc = fr_add(acc, fr_mul(ax[a].beta[x], t));
+            }
+            qv = fr_neg(fr_mul(acc, ax[a].beta_inv[kap]));
+        }
+        fr_t plain = fe_to_plain(qv);
+        out[(uint64_t)J.term0 + term] = fb_mul_accumulate(xyzz_identity(), table[a], local, plain.l);
+        if (term == 0) {
+            fr_t y = fe_to_plain(child_value(v, J.node, J.kappa));
+#pragma unroll
+            for (int i = 0; i < 8; ++i) y_out[job].l[i] = y.l[i];
+        }
+    }
+};
+
+/* ---- Ver (sum form, trapdoor-form check in G1) -------------------------------------------- */
+/* One verification step: is  C - [y]G == sum_i [tau_i - (kappa_i + 1)] pi_i ?
+ * Points arrive as canonical bytes; a point that is not on the curve rejects the step. */
+struct VerifyStep {
+    uint32_t C[24];
+    uint32_t y[8];
+    uint32_t pi[4][24];
+    uint32_t kappa[4];
+    int m;
+};
+TC_HD bool affine_on_curve(const g1_affine& p) {
+    if (affine_is_identity(p)) return true;
+    fp_t y2 = fp_sqr(p.y);
+    fp_t x3 = fp_mul(fp_sqr(p.x), p.x);
+    fp_t four = fe_from_u32<FpParams>(4);
+    return fe_eq(y2, fp_add(x3, four));
+}
+TC_HD bool canonical_fp(const uint32_t* w) { return limbs_gt<12>(FpParams::MOD, w); }
+TC_HD bool xyzz_equal(const g1_xyzz& a, const g1_xyzz& b) {
+    bool ia = xyzz_is_identity(a), ib = xyzz_is_identity(b);
+    if (ia || ib) return ia && ib;
+    return fe_eq(fp_mul(a.X, b.ZZ), fp_mul(b.X, a.ZZ)) && fe_eq(fp_mul(a.Y, b.ZZZ), fp_mul(b.Y, a.ZZZ));
+}
+/* lane (step, term): term 0 = [y]G, term i = [tau_i - zeta] pi_i; writes XYZZ and a validity flag */
+struct VerifyTerms {
+    const VerifyStep* steps;
+    const fr_t* tau;           /* Montgomery */
+    const g1_affine* gtable;
+    g1_xyzz* out;              /* steps * 5 */
+    uint32_t* ok;              /* per step, preset to 1; cleared on malformed input */
+    TC_DEV void operator()(uint32_t lane) const {
+        uint32_t s = lane / 5, term = lane % 5;
+        const VerifyStep& st = steps[s];
+        g1_xyzz r = xyzz_identity();
+        if (term == 0) {
+            if (!limbs_gt<8>(FrParams::MOD, st.y)) atomic_and_u32(&ok[s], 0u);
+            r = fb_mul_accumulate(r, gtable, 0, st.y);
+            g1_affine c = affine_from_canonical(st.C);
+            if (!canonical_fp(st.C) || !canonical_fp(st.C + 12) || !affine_on_curve(c)) atomic_and_u32(&ok[s], 0u);
+        } else if ((int)term <= st.m) {
+            int i = (int)term - 1;
+            const uint32_t* w = st.pi[i];
+            g1_affine p = affine_from_canonical(w);
+            if (!canonical_fp(w) || !canonical_fp(w + 12) || !affine_on_curve(p)) atomic_and_u32(&ok[s], 0u);
+            fr_t k = fe_to_plain(fr_sub(tau[i], fe_from_u32<FrParams>(st.kappa[i] + 1u)));
+            r = xyzz_mul_affine(k.l, 255, p);
+        }
+        out[lane] = r;
+    }
+};
+struct VerifyCombine {         /* lane = step */
+    const VerifyStep* steps;
+    const g1_xyzz* terms;
+    uint32_t* ok;
+    TC_DEV void operator()(uint32_t s) const {
+        const VerifyStep& st = steps[s];
+        g1_xyzz lhs = xyzz_add(xyzz_from_affine(affine_from_canonical(st.C)), xyzz_neg(terms[(uint64_t)s * 5]));
+        g1_xyzz rhs = xyzz_identity();
+        for (int i = 1; i <= st.m; ++i) rhs = xyzz_add(rhs, terms[(uint64_t)s * 5 + i]);
+        if (!xyzz_equal(lhs, rhs)) ok[s] = 0;
+    }
+};
+/* phi of canonical commitments (the verifier's side of "the opened value matches the next commitment") */
+struct PhiCanonical {
+    const uint32_t* pts;       /* 24 words each */
+    fr_plain* out;
+    TC_DEV void operator()(uint32_t t) const {
+        fr_t v = phi_map(affine_from_canonical(pts + 24 * (uint64_t)t));
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[t].l[i] = v.l[i];
+    }
+};
+
+}  // namespace tc

@@ -1,0 +1,90 @@
+/*
+ * Thin runtime layer under the library: device memory, copies, kernel launch.
+ *
+ * The product build (hipcc, gfx950) maps these onto HIP: every kernel is a
+ * functor `F` with `void operator()(uint32_t lane) const` launched as
+ * `kernel<F, BLOCK>` over `n` lanes on the context's stream.
+ *
+ * With -DTC_HOST_EMU the same functors are executed lane by lane on the host.
+ * That build exists only so that the CPU test-suite and a debugger can walk
+ * the library's host logic (sorting passes, level loops, buffer sizes) without
+ * a GPU.  The Python binding never loads it; the product library has no CPU
+ * path.
+ */
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#if defined(TC_HOST_EMU)
+
+namespace tc {
+namespace rt {
+typedef void* stream_t;
+inline int dev_malloc(void** p, size_t n) { *p = malloc(n ? n : 1); return *p ? 0 : 2; }
+inline int dev_free(void* p) { free(p); return 0; }
+inline int memcpy_h2d(void* d, const void* s, size_t n, stream_t) { memcpy(d, s, n); return 0; }
+inline int memcpy_d2h(void* d, const void* s, size_t n, stream_t) { memcpy(d, s, n); return 0; }
+inline int memcpy_d2d(void* d, const void* s, size_t n, stream_t) { memmove(d, s, n); return 0; }
+inline int memset_async(void* d, int v, size_t n, stream_t) { memset(d, v, n); return 0; }
+inline int stream_sync(stream_t) { return 0; }
+inline int set_device(int) { return 0; }
+inline int last_error() { return 0; }
+inline const char* error_string(int) { return "host emulation"; }
+template <int BLOCK, class F>
+inline int launch(uint64_t n, stream_t, const F& f) {
+    for (uint64_t t = 0; t < n; ++t) f((uint32_t)t);
+    return 0;
+}
+}  // namespace rt
+inline uint32_t atomic_add_u32(uint32_t* p, uint32_t v) { uint32_t o = *p; *p += v; return o; }
+inline uint32_t atomic_and_u32(uint32_t* p, uint32_t v) { uint32_t o = *p; *p &= v; return o; }
+inline uint32_t atomic_max_u32(uint32_t* p, uint32_t v) { uint32_t o = *p; if (v > o) *p = v; return o; }
+}  // namespace tc
+
+#else
+
+#include <hip/hip_runtime.h>
+
+namespace tc {
+
+template <class F, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void kernel(const F f, uint32_t n) {
+    uint32_t t = blockIdx.x * BLOCK + threadIdx.x;
+    if (t < n) f(t);
+}
+
+namespace rt {
+typedef hipStream_t stream_t;
+inline int dev_malloc(void** p, size_t n) { return (int)hipMalloc(p, n ? n : 1); }
+inline int dev_free(void* p) { return (int)hipFree(p); }
+inline int memcpy_h2d(void* d, const void* s, size_t n, stream_t st) { return (int)hipMemcpyAsync(d, s, n, hipMemcpyHostToDevice, st); }
+inline int memcpy_d2h(void* d, const void* s, size_t n, stream_t st) { return (int)hipMemcpyAsync(d, s, n, hipMemcpyDeviceToHost, st); }
+inline int memcpy_d2d(void* d, const void* s, size_t n, stream_t st) { return (int)hipMemcpyAsync(d, s, n, hipMemcpyDeviceToDevice, st); }
+inline int memset_async(void* d, int v, size_t n, stream_t st) { return (int)hipMemsetAsync(d, v, n, st); }
+inline int stream_sync(stream_t st) { return (int)hipStreamSynchronize(st); }
+inline int set_device(int dev) { return (int)hipSetDevice(dev); }
+inline int last_error() { return (int)hipGetLastError(); }
+inline const char* error_string(int e) { return hipGetErrorString((hipError_t)e); }
+template <int BLOCK, class F>
+inline int launch(uint64_t n, stream_t st, const F& f) {
+    if (n == 0) return 0;
+    if (n > 0xFFFFFFFFull) return (int)hipErrorInvalidValue;
+    uint32_t blocks = (uint32_t)((n + BLOCK - 1) / BLOCK);
+    hipLaunchKernelGGL((kernel<F, BLOCK>), dim3(blocks), dim3(BLOCK), 0, st, f, (uint32_t)n);
+    return (int)hipGetLastError();
+}
+}  // namespace rt
+__device__ __forceinline__ uint32_t atomic_add_u32(uint32_t* p, uint32_t v) { return atomicAdd(p, v); }
+__device__ __forceinline__ uint32_t atomic_and_u32(uint32_t* p, uint32_t v) { return atomicAnd(p, v); }
+__device__ __forceinline__ uint32_t atomic_max_u32(uint32_t* p, uint32_t v) { return atomicMax(p, v); }
+}  // namespace tc
+
+#endif
+
+#if defined(__HIPCC__)
+#define TC_DEV __device__ __forceinline__
+#else
+#define TC_DEV inline
+#endif

@@ -1,0 +1,1330 @@
+/*
+ * Host side of libtc.so: the C ABI declared in include/tc.h.
+ *
+ * Everything that touches tensor data runs in the kernels of kernels.h; this
+ * file plans launches, owns device memory and moves the few result bytes.
+ * Compiled by hipcc for gfx950 (product) or, with -DTC_HOST_EMU, by g++ as a
+ * lane-by-lane emulation used only by CPU tests of this host logic.
+ */
+#include <algorithm>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/tc.h"
+#include "kernels.h"
+
+using namespace tc;
+
+/* ======================================================================================= */
+/* objects                                                                                 */
+/* ======================================================================================= */
+struct Arena {
+    uint8_t* base = nullptr;
+    size_t cap = 0, off = 0, demand = 0;
+    std::vector<void*> extra;
+};
+
+struct tc_ctx {
+    int device = 0;
+    rt::stream_t stream = nullptr;
+    std::string err;
+    Arena ws;
+    g1_affine* gtable = nullptr;       /* fixed-base table of the generator */
+};
+
+struct tc_srs {
+    int m = 0;
+    uint32_t shape[4] = {1, 1, 1, 1};
+    uint32_t flags = 0;
+    uint64_t n[4] = {0, 0, 0, 0};
+    g1_affine* pts[4] = {nullptr, nullptr, nullptr, nullptr};
+    g1_affine* fb[4] = {nullptr, nullptr, nullptr, nullptr};
+    fr_t* axis_mem = nullptr;
+    AxisTables ax[4];
+};
+
+struct TreeLevel {
+    uint32_t grid[4] = {1, 1, 1, 1};
+    uint64_t n = 0;
+    g1_affine* C = nullptr;
+    fr_plain* phi = nullptr;
+};
+
+struct tc_tree {
+    int m = 0;
+    uint32_t grid[4] = {1, 1, 1, 1};
+    uint32_t node_shape[4] = {1, 1, 1, 1};
+    uint32_t B = 1;
+    const tc_srs* node_srs = nullptr;
+    int leaf_kind = 0;
+    const void* d_payload = nullptr;
+    int dtype = 0;
+    std::vector<const tc_srs*> leaf_srs;
+    std::vector<const void*> leaf_scalars;
+    std::vector<int> leaf_dtype;
+    std::vector<TreeLevel> levels;
+    uint8_t root[96];
+};
+
+struct tc_vk {
+    int m = 0;
+    uint8_t tau[4][32];
+};
+
+/* ======================================================================================= */
+/* helpers                                                                                 */
+/* ======================================================================================= */
+static int fail(tc_ctx* ctx, int code, const char* msg) {
+    if (ctx) ctx->err = msg;
+    return code;
+}
+static int fail_hip(tc_ctx* ctx, int e, const char* where) {
+    if (ctx) ctx->err = std::string(where) + ": " + rt::error_string(e);
+    return TC_ERR_HIP;
+}
+#define RT(call)                                             \
+    do {                                                     \
+        int e_ = (call);                                     \
+        if (e_) return fail_hip(ctx, e_, #call);             \
+    } while (0)
+#define TRY(call)                 \
+    do {                          \
+        int rc_ = (call);         \
+        if (rc_ != TC_OK) return rc_; \
+    } while (0)
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+/* Workspace: a slab that grows to the largest demand seen; within one API call allocations
+ * are bump-pointer, overflow goes to one-off blocks released at the next reset. */
+static int ws_reset(tc_ctx* ctx) {
+    Arena& A = ctx->ws;
+    if (!A.extra.empty() || A.demand > A.cap) {
+        RT(rt::stream_sync(ctx->stream));
+        for (void* p : A.extra) rt::dev_free(p);
+        A.extra.clear();
+        if (A.demand > A.cap) {
+            if (A.base) rt::dev_free(A.base);
+            A.base = nullptr;
+            A.cap = 0;
+            void* p = nullptr;
+            size_t want = align_up(A.demand + A.demand / 8, 1 << 20);
+            if (rt::dev_malloc(&p, want) == 0) {
+                A.base = (uint8_t*)p;
+                A.cap = want;
+            }
+        }
+    }
+    A.off = 0;
+    A.demand = 0;
+    return TC_OK;
+}
+static void* ws_alloc(tc_ctx* ctx, size_t bytes) {
+    Arena& A = ctx->ws;
+    bytes = align_up(bytes ? bytes : 1, 256);
+    A.demand += bytes;
+    if (A.off + bytes <= A.cap) {
+        void* p = A.base + A.off;
+        A.off += bytes;
+        return p;
+    }
+    void* p = nullptr;
+    if (rt::dev_malloc(&p, bytes) != 0) return nullptr;
+    A.extra.push_back(p);
+    return p;
+}
+template <class T>
+static T* ws_array(tc_ctx* ctx, uint64_t count) {
+    return (T*)ws_alloc(ctx, (size_t)count * sizeof(T));
+}
+#define WS(ptr, T, count)                                                   \
+    T* ptr = ws_array<T>(ctx, (count));                                     \
+    if (!ptr) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed")
+
+static bool valid_dtype_scalar(int dt) { return dt == TC_I8 || dt == TC_I16 || dt == TC_FR; }
+static size_t dtype_size(int dt) { return dt == TC_I8 ? 1 : dt == TC_I16 ? 2 : dt == TC_FR ? 32 : dt == TC_F16 ? 2 : 0; }
+
+static bool shape_ok(int m, const uint32_t* shape, uint64_t* total) {
+    if (m < 1 || m > TC_MAX_ORDER || !shape) return false;
+    uint64_t n = 1;
+    for (int j = 0; j < m; ++j) {
+        if (shape[j] == 0) return false;
+        n *= shape[j];
+        if (n > (1ull << 31) - 1) return false;       /* point indices carry a sign bit */
+    }
+    if (total) *total = n;
+    return true;
+}
+
+/* ---- host-side Fr helpers (setup only) ------------------------------------------------- */
+static bool fr_bytes_canonical(const uint8_t* b, uint32_t* w) {
+    memcpy(w, b, 32);
+    return limbs_gt<8>(FrParams::MOD, w);
+}
+static void fr_batch_inverse(std::vector<fr_t>& v) {       /* every entry non-zero */
+    size_t n = v.size();
+    if (!n) return;
+    std::vector<fr_t> pre(n);
+    fr_t run = fe_one<FrParams>();
+    for (size_t i = 0; i < n; ++i) {
+        pre[i] = run;
+        run = fr_mul(run, v[i]);
+    }
+    fr_t inv = fe_inv_fermat<FrParams>(run);
+    for (size_t i = n; i-- > 0;) {
+        fr_t vi = v[i];
+        v[i] = fr_mul(inv, pre[i]);
+        inv = fr_mul(inv, vi);
+    }
+}
+
+/* ======================================================================================= */
+/* context                                                                                 */
+/* ======================================================================================= */
+extern "C" int tc_ctx_create(tc_ctx** out, int device, void* hip_stream) {
+    if (!out) return TC_ERR_ARG;
+    *out = nullptr;
+    tc_ctx* ctx = new (std::nothrow) tc_ctx();
+    if (!ctx) return TC_ERR_NOMEM;
+    ctx->device = device;
+    ctx->stream = (rt::stream_t)hip_stream;
+    int e = rt::set_device(device);
+    if (e) {
+        delete ctx;
+        return TC_ERR_HIP;
+    }
+    /* probe: a tiny allocation proves that a device is really there */
+    void* p = nullptr;
+    if (rt::dev_malloc(&p, 256) != 0) {
+        delete ctx;
+        return TC_ERR_HIP;
+    }
+    rt::dev_free(p);
+    *out = ctx;
+    return TC_OK;
+}
+extern "C" void tc_ctx_destroy(tc_ctx* ctx) {
+    if (!ctx) return;
+    rt::set_device(ctx->device);
+    rt::stream_sync(ctx->stream);
+    for (void* p : ctx->ws.extra) rt::dev_free(p);
+    if (ctx->ws.base) rt::dev_free(ctx->ws.base);
+    if (ctx->gtable) rt::dev_free(ctx->gtable);
+    delete ctx;
+}
+extern "C" const char* tc_last_error(const tc_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+extern "C" int tc_ctx_sync(tc_ctx* ctx) {
+    if (!ctx) return TC_ERR_ARG;
+    RT(rt::stream_sync(ctx->stream));
+    return TC_OK;
+}
+
+/* ======================================================================================= */
+/* normalisation and fixed-base tables                                                     */
+/* ======================================================================================= */
+static int normalize(tc_ctx* ctx, const g1_xyzz* d_in, uint64_t n, g1_affine* d_out) {
+    uint32_t G = n >= (1u << 18) ? 8 : n >= (1u << 14) ? 2 : 1;
+    BatchNormalize k{d_in, n, G, d_out};
+    RT(rt::launch<64>((n + G - 1) / G, ctx->stream, k));
+    return TC_OK;
+}
+/* XYZZ points on the device -> canonical bytes on the host */
+static int points_to_host(tc_ctx* ctx, const g1_xyzz* d_in, uint32_t n, uint8_t* out) {
+    WS(aff, g1_affine, n);
+    WS(can, uint32_t, 24ull * n);
+    TRY(normalize(ctx, d_in, n, aff));
+    RT(rt::launch<64>(n, ctx->stream, ToCanonical{aff, can}));
+    RT(rt::memcpy_d2h(out, can, 96ull * n, ctx->stream));
+    RT(rt::stream_sync(ctx->stream));
+    return TC_OK;
+}
+static int affine_to_host(tc_ctx* ctx, const g1_affine* d_in, uint32_t n, uint8_t* out) {
+    WS(can, uint32_t, 24ull * n);
+    RT(rt::launch<64>(n, ctx->stream, ToCanonical{d_in, can}));
+    RT(rt::memcpy_d2h(out, can, 96ull * n, ctx->stream));
+    RT(rt::stream_sync(ctx->stream));
+    return TC_OK;
+}
+
+/* table[(k, w, j)] = j 2^(16 w) B_k for `nbases` affine bases already on the device */
+static int build_fixed_base_table(tc_ctx* ctx, const g1_affine* d_bases, uint32_t nbases, g1_affine** out) {
+    *out = nullptr;
+    uint64_t entries = (uint64_t)nbases * FB_W * FB_NB;
+    void* tab = nullptr;
+    if (rt::dev_malloc(&tab, entries * sizeof(g1_affine)) != 0) return fail(ctx, TC_ERR_NOMEM, "fixed-base table allocation failed");
+    g1_affine* table = (g1_affine*)tab;
+    uint32_t nbw = nbases * FB_W;
+    void *wbx = nullptr, *wba = nullptr, *tmp = nullptr;
+    const uint32_t slab_bw = 32;                      /* window bases per slab: 32 * 32768 points */
+    int rc = TC_OK;
+    do {
+        if (rt::dev_malloc(&wbx, (size_t)nbw * sizeof(g1_xyzz)) || rt::dev_malloc(&wba, (size_t)nbw * sizeof(g1_affine)) ||
+            rt::dev_malloc(&tmp, (size_t)slab_bw * FB_NB * sizeof(g1_xyzz))) {
+            rc = fail(ctx, TC_ERR_NOMEM, "fixed-base scratch allocation failed");
+            break;
+        }
+        int e = rt::launch<64>(nbases, ctx->stream, FbWindowBases{d_bases, (g1_xyzz*)wbx});
+        if (e) { rc = fail_hip(ctx, e, "FbWindowBases"); break; }
+        rc = normalize(ctx, (g1_xyzz*)wbx, nbw, (g1_affine*)wba);
+        if (rc) break;
+        for (uint32_t bw0 = 0; bw0 < nbw && rc == TC_OK; bw0 += slab_bw) {
+            uint32_t cnt = std::min(slab_bw, nbw - bw0);
+            e = rt::launch<64>((uint64_t)cnt * (FB_NB / FB_CHUNK), ctx->stream, FbChunkFill{(g1_affine*)wba, bw0, (g1_xyzz*)tmp});
+            if (e) { rc = fail_hip(ctx, e, "FbChunkFill"); break; }
+            rc = normalize(ctx, (g1_xyzz*)tmp, (uint64_t)cnt * FB_NB, table + (uint64_t)bw0 * FB_NB);
+        }
+        if (rc) break;
+        e = rt::stream_sync(ctx->stream);
+        if (e) rc = fail_hip(ctx, e, "fixed-base table sync");
+    } while (0);
+    rt::stream_sync(ctx->stream);
+    if (wbx) rt::dev_free(wbx);
+    if (wba) rt::dev_free(wba);
+    if (tmp) rt::dev_free(tmp);
+    if (rc) {
+        rt::dev_free(table);
+        return rc;
+    }
+    *out = table;
+    return TC_OK;
+}
+
+static int ensure_gtable(tc_ctx* ctx) {
+    if (ctx->gtable) return TC_OK;
+    g1_affine g = affine_generator();
+    void* d = nullptr;
+    if (rt::dev_malloc(&d, sizeof g) != 0) return fail(ctx, TC_ERR_NOMEM, "generator upload failed");
+    int e = rt::memcpy_h2d(d, &g, sizeof g, ctx->stream);
+    if (!e) e = rt::stream_sync(ctx->stream);
+    int rc = e ? fail_hip(ctx, e, "generator upload") : build_fixed_base_table(ctx, (g1_affine*)d, 1, &ctx->gtable);
+    rt::dev_free(d);
+    return rc;
+}
+
+/* ======================================================================================= */
+/* Setup                                                                                   */
+/* ======================================================================================= */
+extern "C" void tc_srs_destroy(tc_srs* srs) {
+    if (!srs) return;
+    for (int a = 0; a < 4; ++a) {
+        if (srs->pts[a]) rt::dev_free(srs->pts[a]);
+        if (srs->fb[a]) rt::dev_free(srs->fb[a]);
+    }
+    if (srs->axis_mem) rt::dev_free(srs->axis_mem);
+    delete srs;
+}
+extern "C" uint64_t tc_srs_size(const tc_srs* srs, int first_axis) {
+    if (!srs || first_axis < 0 || first_axis >= srs->m || !srs->pts[first_axis]) return 0;
+    return srs->n[first_axis];
+}
+
+static const uint32_t FB_MAX_BASES = 64;
+
+extern "C" int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, const uint32_t* shape, uint32_t flags,
+                                      tc_srs** out) {
+    if (!ctx || !tau || !out) return ctx ? fail(ctx, TC_ERR_ARG, "null argument") : TC_ERR_ARG;
+    *out = nullptr;
+    uint64_t total = 0;
+    if (!shape_ok(m, shape, &total)) return fail(ctx, TC_ERR_SHAPE, "bad shape");
+    if ((flags & TC_SRS_FIXED_BASE) && total > FB_MAX_BASES)
+        return fail(ctx, TC_ERR_SHAPE, "fixed-base tables are limited to shapes with at most 64 entries");
+    RT(rt::set_device(ctx->device));
+    TRY(ws_reset(ctx));
+
+    /* per-axis Lagrange values at tau_j (barycentric form, App. C) and the tables Open needs */
+    std::vector<fr_t> ell_all, tab_all;
+    uint32_t ell_off[4] = {0, 0, 0, 0};
+    size_t tab_off[4] = {0, 0, 0, 0};
+    for (int j = 0; j < m; ++j) {
+        uint32_t w[8];
+        if (!fr_bytes_canonical(tau + 32 * j, w)) return fail(ctx, TC_ERR_RANGE, "trapdoor is not a canonical Fr element");
+        bool small = true;
+        for (int i = 1; i < 8; ++i) small = small && w[i] == 0;
+        if (small && w[0] <= shape[j]) return fail(ctx, TC_ERR_RANGE, "trapdoor is zero or lies on the grid");
+        uint32_t d = shape[j];
+        fr_t t = fe_from_limbs<FrParams>(w);
+        /* beta_i = 1 / (i! (d-1-i)! (-1)^(d-1-i)) */
+        std::vector<fr_t> fact(d), beta(d), beta_inv(d), diff(d), inv_int(d);
+        fact[0] = fe_one<FrParams>();
+        for (uint32_t i = 1; i < d; ++i) fact[i] = fr_mul(fact[i - 1], fe_from_u32<FrParams>(i));
+        for (uint32_t i = 0; i < d; ++i) {
+            fr_t den = fr_mul(fact[i], fact[d - 1 - i]);
+            if ((d - 1 - i) & 1u) den = fr_neg(den);
+            beta_inv[i] = den;
+            beta[i] = den;
+            diff[i] = fr_sub(t, fe_from_u32<FrParams>(i + 1));
+            inv_int[i] = fe_from_u32<FrParams>(i ? i : 1);
+        }
+        fr_batch_inverse(beta);
+        std::vector<fr_t> diff_inv = diff;
+        fr_batch_inverse(diff_inv);
+        fr_batch_inverse(inv_int);
+        fr_t sum = fe_zero<FrParams>();
+        std::vector<fr_t> term(d);
+        for (uint32_t i = 0; i < d; ++i) {
+            term[i] = fr_mul(beta[i], diff_inv[i]);
+            sum = fr_add(sum, term[i]);
+        }
+        fr_t sum_inv = fe_inv_fermat<FrParams>(sum);
+        ell_off[j] = (uint32_t)ell_all.size();
+        for (uint32_t i = 0; i < d; ++i) ell_all.push_back(fr_mul(term[i], sum_inv));
+        tab_off[j] = tab_all.size();
+        tab_all.insert(tab_all.end(), inv_int.begin(), inv_int.end());
+        tab_all.insert(tab_all.end(), beta.begin(), beta.end());
+        tab_all.insert(tab_all.end(), beta_inv.begin(), beta_inv.end());
+    }
+
+    TRY(ensure_gtable(ctx));
+    tc_srs* srs = new (std::nothrow) tc_srs();
+    if (!srs) return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    srs->m = m;
+    srs->flags = flags;
+    for (int j = 0; j < m; ++j) srs->shape[j] = shape[j];
+    int rc = TC_OK;
+    void* d_ell = nullptr;
+    do {
+        void* p = nullptr;
+        if (rt::dev_malloc(&p, tab_all.size() * sizeof(fr_t)) != 0 || rt::dev_malloc(&d_ell, ell_all.size() * sizeof(fr_t)) != 0) {
+            if (p) rt::dev_free(p);
+            rc = fail(ctx, TC_ERR_NOMEM, "SRS table allocation failed");
+            break;
+        }
+        srs->axis_mem = (fr_t*)p;
+        int e = rt::memcpy_h2d(p, tab_all.data(), tab_all.size() * sizeof(fr_t), ctx->stream);
+        if (!e) e = rt::memcpy_h2d(d_ell, ell_all.data(), ell_all.size() * sizeof(fr_t), ctx->stream);
+        if (!e) e = rt::stream_sync(ctx->stream);
+        if (e) { rc = fail_hip(ctx, e, "SRS table upload"); break; }
+        for (int j = 0; j < m; ++j) {
+            uint32_t d = shape[j];
+            srs->ax[j].inv_int = srs->axis_mem + tab_off[j];
+            srs->ax[j].beta = srs->axis_mem + tab_off[j] + d;
+            srs->ax[j].beta_inv = srs->axis_mem + tab_off[j] + 2 * (size_t)d;
+        }
+        int last_axis = (flags & TC_SRS_SUFFIX) ? m - 1 : 0;
+        const uint64_t slab = 1ull << 20;
+        void* tmp = nullptr;
+        if (rt::dev_malloc(&tmp, (size_t)std::min<uint64_t>(slab, total) * sizeof(g1_xyzz)) != 0) {
+            rc = fail(ctx, TC_ERR_NOMEM, "SRS scratch allocation failed");
+            break;
+        }
+        for (int a = 0; a <= last_axis && rc == TC_OK; ++a) {
+            uint64_t na = 1;
+            for (int j = a; j < m; ++j) na *= shape[j];
+            srs->n[a] = na;
+            void* q = nullptr;
+            if (rt::dev_malloc(&q, (size_t)na * sizeof(g1_affine)) != 0) { rc = fail(ctx, TC_ERR_NOMEM, "SRS allocation failed"); break; }
+            srs->pts[a] = (g1_affine*)q;
+            SrsGen gen;
+            gen.shape.m = m;
+            for (int j = 0; j < 4; ++j) { gen.shape.d[j] = j < m ? shape[j] : 1; gen.ell_off[j] = ell_off[j]; }
+            gen.first_axis = a;
+            gen.ell = (const fr_t*)d_ell;
+            gen.gtable = ctx->gtable;
+            gen.out = (g1_xyzz*)tmp;
+            for (uint64_t i0 = 0; i0 < na && rc == TC_OK; i0 += slab) {
+                uint64_t cnt = std::min(slab, na - i0);
+                gen.i0 = i0;
+                e = rt::launch<64>(cnt, ctx->stream, gen);
+                if (e) { rc = fail_hip(ctx, e, "SrsGen"); break; }
+                rc = normalize(ctx, (g1_xyzz*)tmp, cnt, srs->pts[a] + i0);
+            }
+            if (rc == TC_OK && (flags & TC_SRS_FIXED_BASE)) rc = build_fixed_base_table(ctx, srs->pts[a], (uint32_t)na, &srs->fb[a]);
+        }
+        e = rt::stream_sync(ctx->stream);
+        if (e && rc == TC_OK) rc = fail_hip(ctx, e, "SRS generation");
+        rt::dev_free(tmp);
+    } while (0);
+    if (d_ell) rt::dev_free(d_ell);
+    if (rc != TC_OK) {
+        tc_srs_destroy(srs);
+        return rc;
+    }
+    *out = srs;
+    return TC_OK;
+}
+
+extern "C" int tc_srs_get_point(tc_ctx* ctx, const tc_srs* srs, int first_axis, uint64_t index, uint8_t out_g1[96]) {
+    if (!ctx || !srs || !out_g1) return ctx ? fail(ctx, TC_ERR_ARG, "null argument") : TC_ERR_ARG;
+    if (first_axis < 0 || first_axis >= srs->m || !srs->pts[first_axis]) return fail(ctx, TC_ERR_STATE, "table not present");
+    if (index >= srs->n[first_axis]) return fail(ctx, TC_ERR_RANGE, "index outside the table");
+    RT(rt::set_device(ctx->device));
+    TRY(ws_reset(ctx));
+    return affine_to_host(ctx, srs->pts[first_axis] + index, 1, out_g1);
+}
+
+/* ======================================================================================= */
+/* encode                                                                                  */
+/* ======================================================================================= */
+extern "C" int tc_encode_tensor(tc_ctx* ctx, const void* d_src, int src_dtype, size_t n, float inv_scale, void* d_dst) {
+    if (!ctx) return TC_ERR_ARG;
+    if ((!d_src || !d_dst) && n) return fail(ctx, TC_ERR_ARG, "null buffer");
+    if (n > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "tensor too large");
+    RT(rt::set_device(ctx->device));
+    switch (src_dtype) {
+        case TC_F16:
+            if (!(inv_scale == inv_scale) || inv_scale < 0) return fail(ctx, TC_ERR_RANGE, "inv_scale must be a non-negative number");
+            RT(rt::launch<256>(n, ctx->stream, EncodeF16{(const uint16_t*)d_src, (int16_t*)d_dst, inv_scale}));
+            return TC_OK;
+        case TC_I8:
+            RT(rt::launch<256>(n, ctx->stream, Copy8{(const uint8_t*)d_src, (uint8_t*)d_dst}));
+            return TC_OK;
+        case TC_I16:
+            RT(rt::launch<256>(n, ctx->stream, Copy16{(const uint16_t*)d_src, (uint16_t*)d_dst}));
+            return TC_OK;
+        default:
+            return fail(ctx, TC_ERR_ARG, "unsupported source dtype");
+    }
+}
+
+/* ======================================================================================= */
+/* MSM engine                                                                              */
+/* ======================================================================================= */
+#if defined(TC_HOST_EMU)
+template <int BLOCK, class F>
+static int launch_coop(uint32_t groups, rt::stream_t, const F& f) {
+    std::vector<uint8_t> lds(F::LDS_BYTES);
+    for (uint32_t g = 0; g < groups; ++g)
+        for (int ph = 0; ph < F::PHASES; ++ph)
+            for (uint32_t lane = 0; lane < (uint32_t)BLOCK; ++lane) f.phase(ph, lane, g, lds.data());
+    return 0;
+}
+#else
+template <class F, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void coop_kernel(const F f) {
+    extern __shared__ __align__(16) uint8_t lds[];
+    for (int ph = 0; ph < F::PHASES; ++ph) {
+        f.phase(ph, threadIdx.x, blockIdx.x, lds);
+        __syncthreads();
+    }
+}
+template <int BLOCK, class F>
+static int launch_coop(uint32_t groups, rt::stream_t st, const F& f) {
+    if (!groups) return 0;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&coop_kernel<F, BLOCK>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)F::LDS_BYTES);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((coop_kernel<F, BLOCK>), dim3(groups), dim3(BLOCK), F::LDS_BYTES, st, f);
+    return (int)hipGetLastError();
+}
+#endif
+
+/* prefix sums of cnt (n entries): start, lstart (of ceil(cnt / L)); optional zeroing of a cursor array */
+static int scan_counts(tc_ctx* ctx, const uint32_t* cnt, uint32_t n, uint32_t L, uint32_t* start, uint32_t* lstart,
+                       uint32_t* zero_me, uint32_t* tot_a, uint32_t* tot_b) {
+    uint32_t nchunks = (n + SCAN_CHUNK - 1) / SCAN_CHUNK;
+    RT(rt::launch<64>(nchunks, ctx->stream, ScanChunkTotals{cnt, n, L, tot_a, tot_b}));
+    RT(rt::launch<64>(1, ctx->stream, ScanChunkOffsets{nchunks, tot_a, tot_b}));
+    RT(rt::launch<64>(nchunks, ctx->stream, ScanWrite{cnt, n, L, tot_a, tot_b, nchunks, start, lstart, zero_me}));
+    return TC_OK;
+}
+
+/* sum_k k B_k for every window of `bucket` (W windows of nb buckets) -> wsum[W] */
+template <int BLOCK>
+static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb, g1_xyzz* wsum) {
+    uint32_t G = nb / BLOCK;                          /* blocks per window */
+    uint32_t nblk = (uint32_t)W * G;
+    WS(w1, g1_xyzz, nblk);
+    WS(s1, g1_xyzz, nblk);
+    RT((launch_coop<BLOCK>(nblk, ctx->stream, WeightedBlockSum<BLOCK>{bucket, (uint32_t)W * nb, w1, s1})));
+    if (G == 1) {
+        RT(rt::launch<64>((uint32_t)W, ctx->stream, WindowFinish{w1, nullptr, nullptr, 1, 0, wsum}));
+        return TC_OK;
+    }
+    if (G != 128) return fail(ctx, TC_ERR_STATE, "unsupported bucket count");
+    WS(w2, g1_xyzz, (uint32_t)W);
+    WS(s2, g1_xyzz, (uint32_t)W);
+    WS(w3, g1_xyzz, (uint32_t)W);
+    WS(s3, g1_xyzz, (uint32_t)W);
+    RT((launch_coop<128>((uint32_t)W, ctx->stream, WeightedBlockSum<128>{s1, nblk, w2, s2})));
+    RT((launch_coop<128>((uint32_t)W, ctx->stream, WeightedBlockSum<128>{w1, nblk, w3, s3})));
+    int log_block = BLOCK == 256 ? 8 : 7;
+    RT(rt::launch<64>((uint32_t)W, ctx->stream, WindowFinish{s3, w2, s2, (int)G, log_block, wsum}));
+    return TC_OK;
+}
+
+/* result[0] = sum_i [e(s_i)] pts[i] */
+static int msm_engine(tc_ctx* ctx, const g1_affine* pts, const void* d_scalars, int dtype, uint64_t n, g1_xyzz* result) {
+    int W, c;
+    if (dtype == TC_I8) { W = 1; c = 8; }
+    else if (dtype == TC_I16) { W = 1; c = 16; }
+    else { c = n >= 32768 ? 16 : 8; W = 256 / c; }
+    uint32_t nb = 1u << (c - 1);
+    uint32_t nbk = (uint32_t)W * nb;
+    uint64_t items = n * (uint64_t)W;
+    if (items > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "MSM too large");
+    uint32_t nchunks = (nbk + SCAN_CHUNK - 1) / SCAN_CHUNK;
+
+    WS(cnt, uint32_t, nbk);
+    WS(cursor, uint32_t, nbk);
+    WS(start, uint32_t, nbk + 1);
+    WS(lstart, uint32_t, nbk + 1);
+    WS(lstart2, uint32_t, nbk + 1);
+    WS(tot_a, uint32_t, nchunks + 1);
+    WS(tot_b, uint32_t, nchunks + 1);
+    WS(sorted, uint32_t, items ? items : 1);
+    WS(maxcnt, uint32_t, 1);
+
+    /* lanes of the first pass: enough sub-runs to fill the machine, at most 64 entries each */
+    const uint64_t target_lanes = 262144;
+    uint32_t L1 = (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(4, (items + target_lanes - 1) / target_lanes));
+    const uint32_t L2 = 16;
+
+    RT(rt::launch<256>(nbk, ctx->stream, Fill32{cnt, 0u}));
+    RT(rt::launch<256>(n, ctx->stream, MsmCount{d_scalars, dtype, W, c, nb, cnt}));
+    TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, cursor, tot_a, tot_b));
+    RT(rt::launch<256>(n, ctx->stream, MsmScatter{d_scalars, dtype, W, c, nb, start, cursor, sorted}));
+
+    uint64_t max_part = items / L1 + nbk + 1;          /* upper bound on first-pass lanes */
+    WS(bufA, g1_xyzz, max_part);
+    WS(bufB, g1_xyzz, max_part / L2 + nbk + 1);
+    WS(bucket, g1_xyzz, nbk);
+    WS(wsum, g1_xyzz, (uint32_t)W);
+    RT(rt::launch<64>(max_part, ctx->stream, AccAffine{pts, sorted, start, lstart, nbk, L1, bufA}));
+
+    /* worst case: every item in one bucket.  Middle passes shrink the per-bucket partial count
+     * by L2 until at most L2 remain; the plan is fixed on the host from the sizes alone. */
+    uint64_t worst = (items + L1 - 1) / L1;
+    g1_xyzz *cur = bufA, *nxt = bufB;
+    uint32_t *cur_start = lstart, *nxt_start = lstart2;
+    uint64_t lanes_bound = max_part;
+    while (worst > L2) {
+        /* counts of this pass = number of partials per bucket = differences of cur_start */
+        RT(rt::launch<256>(nbk, ctx->stream, DiffCounts{cur_start, cnt}));
+        TRY(scan_counts(ctx, cnt, nbk, L2, start, nxt_start, nullptr, tot_a, tot_b));
+        /* `start` now equals cur_start (prefix of the same counts) */
+        lanes_bound = lanes_bound / L2 + nbk + 1;
+        RT(rt::launch<64>(lanes_bound, ctx->stream, AccXyzz{cur, cur_start, nxt_start, nbk, L2, nxt}));
+        std::swap(cur, nxt);
+        std::swap(cur_start, nxt_start);
+        worst = (worst + L2 - 1) / L2;
+    }
+    RT(rt::launch<64>(nbk, ctx->stream, AccFinal{cur, cur_start, bucket}));
+    (void)maxcnt;
+
+    if (nb == 128) TRY(reduce_windows<128>(ctx, bucket, W, nb, wsum));
+    else TRY(reduce_windows<256>(ctx, bucket, W, nb, wsum));
+    RT(rt::launch<64>(1, ctx->stream, WindowCombine{wsum, W, c, result}));
+    return TC_OK;
+}
+
+static int check_commit_args(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, int dtype) {
+    if (!srs || !d_scalars) return fail(ctx, TC_ERR_ARG, "null argument");
+    if (!valid_dtype_scalar(dtype)) return fail(ctx, TC_ERR_ARG, "unsupported scalar dtype");
+    if (!srs->pts[0]) return fail(ctx, TC_ERR_STATE, "SRS has no points");
+    return TC_OK;
+}
+
+extern "C" int tc_commit_batch(tc_ctx* ctx, int count, const tc_srs* const* srs, const void* const* d_scalars,
+                               const int* dtype, uint8_t* out_g1) {
+    if (!ctx) return TC_ERR_ARG;
+    if (count < 0 || (count && (!srs || !d_scalars || !dtype || !out_g1))) return fail(ctx, TC_ERR_ARG, "null argument");
+    for (int i = 0; i < count; ++i) TRY(check_commit_args(ctx, srs[i], d_scalars[i], dtype[i]));
+    if (!count) return TC_OK;
+    RT(rt::set_device(ctx->device));
+    TRY(ws_reset(ctx));
+    WS(results, g1_xyzz, (uint32_t)count);
+    for (int i = 0; i < count; ++i) {
+        size_t mark_off = ctx->ws.off;
+        TRY(msm_engine(ctx, srs[i]->pts[0], d_scalars[i], dtype[i], srs[i]->n[0], results + i));
+        /* engine scratch is reusable by the next MSM: the stream orders the kernels */
+        ctx->ws.off = mark_off;
+    }
+    return points_to_host(ctx, results, (uint32_t)count, out_g1);
+}
+extern "C" int tc_commit(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, int dtype, uint8_t out_g1[96]) {
+    if (!ctx) return TC_ERR_ARG;
+    if (!out_g1) return fail(ctx, TC_ERR_ARG, "null argument");
+    return tc_commit_batch(ctx, 1, &srs, &d_scalars, &dtype, out_g1);
+}
+
+/* ======================================================================================= */
+/* Open                                                                                    */
+/* ======================================================================================= */
+/* proof elements as XYZZ on the device (pi[0..m)), opened value as canonical Fr on the device */
+static int open_device(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, int dtype, const uint32_t* kappa,
+                       g1_xyzz* pi, fr_plain* y) {
+    int m = srs->m;
+    uint64_t offset = 0;
+    for (int a = 0; a < m; ++a) {
+        uint64_t na = srs->n[a];
+        uint32_t d = srs->shape[a];
+        uint64_t inner = na / d;
+        size_t mark = ctx->ws.off;
+        WS(q, fr_plain, na);
+        if (na > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "slice too large");
+        RT(rt::launch<128>(na, ctx->stream, QuotientRows{d_scalars, dtype, offset, d, kappa[a], inner, srs->ax[a], q}));
+        RT(rt::launch<128>(inner, ctx->stream, QuotientKappaRow{d, kappa[a], inner, srs->ax[a], q}));
+        TRY(msm_engine(ctx, srs->pts[a], q, TC_FR, na, pi + a));
+        ctx->ws.off = mark;
+        offset += (uint64_t)kappa[a] * inner;
+    }
+    RT(rt::launch<64>(1, ctx->stream, FetchScalar{d_scalars, dtype, offset, y}));
+    return TC_OK;
+}
+
+static int check_open_args(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, int dtype, const uint32_t* kappa) {
+    TRY(check_commit_args(ctx, srs, d_scalars, dtype));
+    if (!kappa) return fail(ctx, TC_ERR_ARG, "null argument");
+    for (int a = 0; a < srs->m; ++a) {
+        if (!srs->pts[a]) return fail(ctx, TC_ERR_STATE, "SRS was built without suffix tables");
+        if (kappa[a] >= srs->shape[a]) return fail(ctx, TC_ERR_RANGE, "opening position outside the grid");
+    }
+    return TC_OK;
+}
+
+extern "C" int tc_open(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, int dtype, const uint32_t* kappa,
+                       uint8_t out_y[32], uint8_t* out_pi) {
+    if (!ctx) return TC_ERR_ARG;
+    if (!out_y || !out_pi) return fail(ctx, TC_ERR_ARG, "null argument");
+    TRY(check_open_args(ctx, srs, d_scalars, dtype, kappa));
+    RT(rt::set_device(ctx->device));
+    TRY(ws_reset(ctx));
+    WS(pi, g1_xyzz, 4);
+    WS(y, fr_plain, 1);
+    TRY(open_device(ctx, srs, d_scalars, dtype, kappa, pi, y));
+    RT(rt::memcpy_d2h(out_y, y, 32, ctx->stream));
+    return points_to_host(ctx, pi, (uint32_t)srs->m, out_pi);
+}
+
+/* ======================================================================================= */
+/* Ver                                                                                     */
+/* ======================================================================================= */
+extern "C" int tc_vk_from_trapdoor(const uint8_t* tau, int m, tc_vk** out) {
+    if (!tau || !out || m < 1 || m > TC_MAX_ORDER) return TC_ERR_ARG;
+    *out = nullptr;
+    uint32_t w[8];
+    for (int j = 0; j < m; ++j)
+        if (!fr_bytes_canonical(tau + 32 * j, w)) return TC_ERR_RANGE;
+    tc_vk* vk = new (std::nothrow) tc_vk();
+    if (!vk) return TC_ERR_NOMEM;
+    vk->m = m;
+    memcpy(vk->tau, tau, 32 * (size_t)m);
+    *out = vk;
+    return TC_OK;
+}
+extern "C" void tc_vk_destroy(tc_vk* vk) { delete vk; }
+
+/* runs the steps on the device; ok[i] = 1 iff step i verifies */
+static int verify_steps(tc_ctx* ctx, const tc_vk* vk, const std::vector<VerifyStep>& steps, std::vector<uint32_t>& ok) {
+    uint32_t n = (uint32_t)steps.size();
+    ok.assign(n, 0);
+    if (!n) return TC_OK;
+    TRY(ensure_gtable(ctx));
+    fr_t tau_m[4];
+    for (int j = 0; j < 4; ++j) {
+        uint32_t w[8] = {0};
+        if (j < vk->m) memcpy(w, vk->tau[j], 32);
+        tau_m[j] = fe_from_limbs<FrParams>(w);
+    }
+    WS(d_steps, VerifyStep, n);
+    WS(d_tau, fr_t, 4);
+    WS(d_terms, g1_xyzz, 5ull * n);
+    WS(d_ok, uint32_t, n);
+    RT(rt::memcpy_h2d(d_steps, steps.data(), sizeof(VerifyStep) * n, ctx->stream));
+    RT(rt::memcpy_h2d(d_tau, tau_m, sizeof tau_m, ctx->stream));
+    RT(rt::launch<256>(n, ctx->stream, Fill32{d_ok, 1u}));
+    RT(rt::launch<64>(5ull * n, ctx->stream, VerifyTerms{d_steps, d_tau, ctx->gtable, d_terms, d_ok}));
+    RT(rt::launch<64>(n, ctx->stream, VerifyCombine{d_steps, d_terms, d_ok}));
+    RT(rt::memcpy_d2h(ok.data(), d_ok, 4ull * n, ctx->stream));
+    RT(rt::stream_sync(ctx->stream));
+    return TC_OK;
+}
+
+extern "C" int tc_verify(tc_ctx* ctx, const tc_vk* vk, int m, const uint32_t* shape, const uint8_t commitment[96],
+                         const uint32_t* kappa, const uint8_t y[32], const uint8_t* pi) {
+    if (!ctx) return TC_ERR_ARG;
+    if (!vk || !shape || !commitment || !kappa || !y || !pi) return fail(ctx, TC_ERR_ARG, "null argument");
+    if (!shape_ok(m, shape, nullptr) || m > vk->m) return fail(ctx, TC_ERR_SHAPE, "bad shape");
+    for (int j = 0; j < m; ++j)
+        if (kappa[j] >= shape[j]) return fail(ctx, TC_ERR_RANGE, "opening position outside the grid");
+    RT(rt::set_device(ctx->device));
+    TRY(ws_reset(ctx));
+    std::vector<VerifyStep> steps(1);
+    memset(&steps[0], 0, sizeof(VerifyStep));
+    memcpy(steps[0].C, commitment, 96);
+    memcpy(steps[0].y, y, 32);
+    for (int j = 0; j < m; ++j) {
+        memcpy(steps[0].pi[j], pi + 96 * j, 96);
+        steps[0].kappa[j] = kappa[j];
+    }
+    steps[0].m = m;
+    std::vector<uint32_t> ok;
+    TRY(verify_steps(ctx, vk, steps, ok));
+    if (!ok[0]) return fail(ctx, TC_ERR_VERIFY, "opening rejected");
+    return TC_OK;
+}
+
+/* ======================================================================================= */
+/* Terkle Tree                                                                             */
+/* ======================================================================================= */
+extern "C" void tc_tree_destroy(tc_tree* tree) {
+    if (!tree) return;
+    for (auto& lv : tree->levels) {
+        if (lv.C) rt::dev_free(lv.C);
+        if (lv.phi) rt::dev_free(lv.phi);
+    }
+    delete tree;
+}
+extern "C" int tc_terkle_root(const tc_tree* tree, uint8_t out_g1[96]) {
+    if (!tree || !out_g1) return TC_ERR_ARG;
+    memcpy(out_g1, tree->root, 96);
+    return TC_OK;
+}
+extern "C" int tc_terkle_levels(const tc_tree* tree) { return tree ? (int)tree->levels.size() : TC_ERR_ARG; }
+extern "C" int tc_terkle_level_info(const tc_tree* tree, int level, uint32_t* grid, uint64_t* n_nodes) {
+    if (!tree || level < 0 || level >= (int)tree->levels.size()) return TC_ERR_ARG;
+    if (grid)
+        for (int j = 0; j < tree->m; ++j) grid[j] = tree->levels[level].grid[j];
+    if (n_nodes) *n_nodes = tree->levels[level].n;
+    return TC_OK;
+}
+extern "C" int tc_terkle_node(tc_ctx* ctx, const tc_tree* tree, int level, uint64_t index, uint8_t out_g1[96]) {
+    if (!ctx) return TC_ERR_ARG;
+    if (!tree || !out_g1 || level < 0 || level >= (int)tree->levels.size()) return fail(ctx, TC_ERR_ARG, "bad argument");
+    if (index >= tree->levels[level].n) return fail(ctx, TC_ERR_RANGE, "node index outside the level");
+    RT(rt::set_device(ctx->device));
+    TRY(ws_reset(ctx));
+    return affine_to_host(ctx, tree->levels[level].C + index, 1, out_g1);
+}
+
+static TreeGeom make_geom(const tc_tree* t, const uint32_t* below, const uint32_t* grid) {
+    TreeGeom g;
+    g.m = t->m;
+    g.B = t->B;
+    for (int j = 0; j < 4; ++j) {
+        g.node[j] = j < t->m ? t->node_shape[j] : 1;
+        g.below[j] = j < t->m ? below[j] : 1;
+        g.grid[j] = j < t->m ? grid[j] : 1;
+    }
+    return g;
+}
+
+/* gather the children of one node as a dense tensor of the node shape (zero padded) */
+struct GatherNodeSmall {
+    TreeGeom g;
+    const void* payload;
+    int dtype;
+    uint64_t node;
+    void* out;
+    TC_DEV void operator()(uint32_t k) const {
+        int64_t f = child_index(g, node, k);
+        int32_t v = f < 0 ? 0 : small_scalar(payload, dtype, (uint64_t)f);
+        if (dtype == DT_I8) ((int8_t*)out)[k] = (int8_t)v; else ((int16_t*)out)[k] = (int16_t)v;
+    }
+};
+struct GatherNodeFr {
+    TreeGeom g;
+    const fr_plain* below;
+    uint64_t node;
+    fr_plain* out;
+    TC_DEV void operator()(uint32_t k) const {
+        int64_t f = child_index(g, node, k);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[k].l[i] = f < 0 ? 0u : below[f].l[i];
+    }
+};
+
+extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** out) {
+    if (!ctx) return TC_ERR_ARG;
+    if (!desc || !out) return fail(ctx, TC_ERR_ARG, "null argument");
+    *out = nullptr;
+    uint64_t n_payload = 0, B = 0;
+    if (!shape_ok(desc->m, desc->grid, &n_payload) || !shape_ok(desc->m, desc->node_shape, &B))
+        return fail(ctx, TC_ERR_SHAPE, "bad grid or node shape");
+    const tc_srs* ns = desc->node_srs;
+    if (!ns) return fail(ctx, TC_ERR_ARG, "node SRS missing");
+    if (ns->m != desc->m) return fail(ctx, TC_ERR_SHAPE, "node SRS order differs from the grid order");
+    for (int j = 0; j < desc->m; ++j)
+        if (ns->shape[j] != desc->node_shape[j]) return fail(ctx, TC_ERR_SHAPE, "node SRS shape differs from node_shape");
+    bool more_than_one = false;
+    for (int j = 0; j < desc->m; ++j) more_than_one = more_than_one || desc->node_shape[j] > 1;
+    if (!more_than_one) return fail(ctx, TC_ERR_SHAPE, "node shape must have more than one entry");
+    if (desc->leaf_kind == TC_LEAF_ENTRIES) {
+        if (!desc->d_payload) return fail(ctx, TC_ERR_ARG, "payload missing");
+        if (desc->dtype != TC_I8 && desc->dtype != TC_I16) return fail(ctx, TC_ERR_ARG, "payload must be int8 or int16");
+    } else if (desc->leaf_kind == TC_LEAF_TENSORS) {
+        if (!desc->leaf_srs || !desc->d_leaf_scalars || !desc->leaf_dtype) return fail(ctx, TC_ERR_ARG, "leaf arrays missing");
+        for (uint64_t i = 0; i < n_payload; ++i) TRY(check_commit_args(ctx, desc->leaf_srs[i], desc->d_leaf_scalars[i], desc->leaf_dtype[i]));
+    } else {
+        return fail(ctx, TC_ERR_ARG, "bad leaf kind");
+    }
+    RT(rt::set_device(ctx->device));
+    TRY(ws_reset(ctx));
+
+    tc_tree* t = new (std::nothrow) tc_tree();
+    if (!t) return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    t->m = desc->m;
+    t->B = (uint32_t)B;
+    t->node_srs = ns;
+    t->leaf_kind = desc->leaf_kind;
+    t->d_payload = desc->d_payload;
+    t->dtype = desc->dtype;
+    for (int j = 0; j < desc->m; ++j) { t->grid[j] = desc->grid[j]; t->node_shape[j] = desc->node_shape[j]; }
+    if (desc->leaf_kind == TC_LEAF_TENSORS) {
+        t->leaf_srs.assign(desc->leaf_srs, desc->leaf_srs + n_payload);
+        t->leaf_scalars.assign(desc->d_leaf_scalars, desc->d_leaf_scalars + n_payload);
+        t->leaf_dtype.assign(desc->leaf_dtype, desc->leaf_dtype + n_payload);
+    }
+    /* level grids, bottom-up */
+    {
+        uint32_t g[4] = {1, 1, 1, 1};
+        for (int j = 0; j < t->m; ++j) g[j] = t->grid[j];
+        bool first = true;
+        for (;;) {
+            bool blocked = !(first && t->leaf_kind == TC_LEAF_TENSORS);
+            TreeLevel lv;
+            lv.n = 1;
+            bool all_one = true;
+            for (int j = 0; j < t->m; ++j) {
+                lv.grid[j] = blocked ? (g[j] + t->node_shape[j] - 1) / t->node_shape[j] : g[j];
+                lv.n *= lv.grid[j];
+                all_one = all_one && lv.grid[j] == 1;
+                g[j] = lv.grid[j];
+            }
+            t->levels.push_back(lv);
+            first = false;
+            if (all_one) break;
+            if (t->levels.size() >= MAX_LEVELS) {
+                delete t;
+                return fail(ctx, TC_ERR_SHAPE, "tree too deep");
+            }
+        }
+    }
+    int rc = TC_OK;
+    for (auto& lv : t->levels) {
+        void *c = nullptr, *p = nullptr;
+        if (rt::dev_malloc(&c, (size_t)lv.n * sizeof(g1_affine)) != 0 || rt::dev_malloc(&p, (size_t)lv.n * sizeof(fr_plain)) != 0) {
+            if (c) rt::dev_free(c);
+            rc = fail(ctx, TC_ERR_NOMEM, "tree level allocation failed");
+            break;
+        }
+        lv.C = (g1_affine*)c;
+        lv.phi = (fr_plain*)p;
+    }
+    bool use_fb = ns->fb[0] != nullptr;
+    for (size_t L = 0; L < t->levels.size() && rc == TC_OK; ++L) {
+        TreeLevel& lv = t->levels[L];
+        size_t mark = ctx->ws.off;
+        do {
+            if (lv.n > 0xFFFFFFFFull / t->B) { rc = fail(ctx, TC_ERR_SHAPE, "level too large"); break; }
+            g1_xyzz* acc = ws_array<g1_xyzz>(ctx, lv.n);
+            if (!acc) { rc = fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed"); break; }
+            if (L == 0 && t->leaf_kind == TC_LEAF_TENSORS) {
+                for (uint64_t i = 0; i < lv.n && rc == TC_OK; ++i) {
+                    size_t mk = ctx->ws.off;
+                    rc = msm_engine(ctx, t->leaf_srs[i]->pts[0], t->leaf_scalars[i], t->leaf_dtype[i], t->leaf_srs[i]->n[0], acc + i);
+                    ctx->ws.off = mk;
+                }
+            } else {
+                const uint32_t* below = L == 0 ? t->grid : t->levels[L - 1].grid;
+                TreeGeom g = make_geom(t, below, lv.grid);
+                bool bottom = (L == 0);
+                if (use_fb) {
+                    int e;
+                    if (bottom) {
+                        e = rt::launch<64>(lv.n, ctx->stream, NodeCommitSmall{g, t->d_payload, t->dtype, ns->fb[0], acc});
+                    } else {
+                        g1_xyzz* part = ws_array<g1_xyzz>(ctx, lv.n * t->B);
+                        if (!part) { rc = fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed"); break; }
+                        e = rt::launch<64>(lv.n * t->B, ctx->stream, NodeCommitFr{g, t->levels[L - 1].phi, ns->fb[0], part});
+                        if (!e) e = rt::launch<64>(lv.n, ctx->stream, SumGroups{part, t->B, acc});
+                    }
+                    if (e) { rc = fail_hip(ctx, e, "node commit"); break; }
+                } else {
+                    /* large node shapes: every node is its own MSM over the gathered children */
+                    size_t esz = bottom ? dtype_size(t->dtype) : 32;
+                    void* z = ws_alloc(ctx, (size_t)t->B * esz);
+                    if (!z) { rc = fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed"); break; }
+                    for (uint64_t a = 0; a < lv.n && rc == TC_OK; ++a) {
+                        int e = bottom ? rt::launch<64>(t->B, ctx->stream, GatherNodeSmall{g, t->d_payload, t->dtype, a, z})
+                                       : rt::launch<64>(t->B, ctx->stream, GatherNodeFr{g, t->levels[L - 1].phi, a, (fr_plain*)z});
+                        if (e) { rc = fail_hip(ctx, e, "gather"); break; }
+                        size_t mk = ctx->ws.off;
+                        rc = msm_engine(ctx, ns->pts[0], z, bottom ? t->dtype : TC_FR, t->B, acc + a);
+                        ctx->ws.off = mk;
+                    }
+                    if (rc) break;
+                }
+            }
+            if (rc) break;
+            rc = normalize(ctx, acc, lv.n, lv.C);
+            if (rc) break;
+            int e = rt::launch<64>(lv.n, ctx->stream, PhiKernel{lv.C, lv.phi});
+            if (e) rc = fail_hip(ctx, e, "phi");
+        } while (0);
+        ctx->ws.off = mark;
+    }
+    if (rc == TC_OK) rc = affine_to_host(ctx, t->levels.back().C, 1, t->root);
+    if (rc != TC_OK) {
+        rt::stream_sync(ctx->stream);
+        tc_tree_destroy(t);
+        return rc;
+    }
+    *out = t;
+    return TC_OK;
+}
+
+/* ---- paths ------------------------------------------------------------------------------ */
+extern "C" int tc_path_from_grid(int m, const uint32_t* grid, const uint32_t* node_shape, int leaf_kind,
+                                 const uint32_t* leaf_index, int inner_m, const uint32_t* inner_shape,
+                                 const uint32_t* inner_index, tc_path* out) {
+    if (!grid || !node_shape || !leaf_index || !out) return TC_ERR_ARG;
+    if (!shape_ok(m, grid, nullptr) || !shape_ok(m, node_shape, nullptr)) return TC_ERR_SHAPE;
+    if (leaf_kind != TC_LEAF_ENTRIES && leaf_kind != TC_LEAF_TENSORS) return TC_ERR_ARG;
+    bool grow = false;
+    for (int j = 0; j < m; ++j) {
+        if (leaf_index[j] >= grid[j]) return TC_ERR_RANGE;
+        grow = grow || node_shape[j] > 1;
+    }
+    if (!grow) return TC_ERR_SHAPE;
+    /* bottom-up, then reversed */
+    uint32_t pos[4] = {0, 0, 0, 0}, g[4] = {1, 1, 1, 1};
+    for (int j = 0; j < m; ++j) { pos[j] = leaf_index[j]; g[j] = grid[j]; }
+    std::vector<std::vector<uint32_t>> kap;
+    bool first = true;
+    for (;;) {
+        bool blocked = !(first && leaf_kind == TC_LEAF_TENSORS);
+        bool all_one = true;
+        if (blocked) {
+            std::vector<uint32_t> k(4, 0);
+            for (int j = 0; j < m; ++j) {
+                k[j] = pos[j] % node_shape[j];
+                pos[j] /= node_shape[j];
+                g[j] = (g[j] + node_shape[j] - 1) / node_shape[j];
+            }
+            kap.push_back(k);
+        }
+        for (int j = 0; j < m; ++j) all_one = all_one && g[j] == 1;
+        first = false;
+        if (all_one) break;
+        if (kap.size() >= TC_MAX_STEPS - 1) return TC_ERR_SHAPE;
+    }
+    memset(out, 0, sizeof *out);
+    int s = 0;
+    for (size_t i = kap.size(); i-- > 0; ++s) {
+        out->m[s] = m;
+        for (int j = 0; j < m; ++j) { out->shape[s][j] = node_shape[j]; out->kappa[s][j] = kap[i][j]; }
+    }
+    if (leaf_kind == TC_LEAF_TENSORS) {
+        if (!inner_shape || !inner_index || !shape_ok(inner_m, inner_shape, nullptr)) return TC_ERR_ARG;
+        out->m[s] = inner_m;
+        for (int j = 0; j < inner_m; ++j) {
+            if (inner_index[j] >= inner_shape[j]) return TC_ERR_RANGE;
+            out->shape[s][j] = inner_shape[j];
+            out->kappa[s][j] = inner_index[j];
+        }
+        ++s;
+    }
+    out->n_steps = s;
+    return TC_OK;
+}
+
+static uint64_t flat_of(const uint32_t* idx, const uint32_t* grid, int m) {
+    uint64_t f = 0;
+    for (int j = 0; j < m; ++j) f = f * grid[j] + idx[j];
+    return f;
+}
+
+extern "C" int tc_terkle_open_batch(tc_ctx* ctx, const tc_tree* t, int count, const uint32_t* leaf_index,
+                                    const uint32_t* inner_index, void* proof_buf, size_t proof_stride, size_t* proof_len) {
+    if (!ctx) return TC_ERR_ARG;
+    if (!t || count < 0 || (count && (!leaf_index || !proof_buf || !proof_len))) return fail(ctx, TC_ERR_ARG, "null argument");
+    if (t->leaf_kind == TC_LEAF_TENSORS && count && !inner_index) return fail(ctx, TC_ERR_ARG, "inner index missing");
+    if (!count) return TC_OK;
+    const tc_srs* ns = t->node_srs;
+    int m = t->m;
+    for (int a = 0; a < m; ++a)
+        if (!ns->pts[a]) return fail(ctx, TC_ERR_STATE, "node SRS was built without suffix tables");
+    RT(rt::set_device(ctx->device));
+    TRY(ws_reset(ctx));
+
+    int first_blocked = t->leaf_kind == TC_LEAF_TENSORS ? 1 : 0;
+    int n_blocked = (int)t->levels.size() - first_blocked;
+    bool use_fb = ns->fb[0] != nullptr;
+    for (int a = 0; a < m && use_fb; ++a) use_fb = ns->fb[a] != nullptr;
+
+    /* per path: node index and kappa at every blocked level (bottom-up), leaf flat index */
+    struct PathInfo { std::vector<uint64_t> node; std::vector<std::vector<uint32_t>> kap; uint64_t leaf_flat; const uint32_t* inner; };
+    std::vector<PathInfo> P(count);
+    const uint32_t* inner_cursor = inner_index;
+    for (int i = 0; i < count; ++i) {
+        const uint32_t* li = leaf_index + (size_t)i * m;
+        for (int j = 0; j < m; ++j)
+            if (li[j] >= t->grid[j]) return fail(ctx, TC_ERR_RANGE, "leaf index outside the grid");
+        uint32_t pos[4] = {0, 0, 0, 0};
+        for (int j = 0; j < m; ++j) pos[j] = li[j];
+        P[i].leaf_flat = flat_of(pos, t->grid, m);
+        for (int b = 0; b < n_blocked; ++b) {
+            std::vector<uint32_t> k(4, 0);
+            for (int j = 0; j < m; ++j) { k[j] = pos[j] % t->node_shape[j]; pos[j] /= t->node_shape[j]; }
+            P[i].node.push_back(flat_of(pos, t->levels[first_blocked + b].grid, m));
+            P[i].kap.push_back(k);
+        }
+        if (t->leaf_kind == TC_LEAF_TENSORS) {
+            const tc_srs* ls = t->leaf_srs[P[i].leaf_flat];
+            for (int a = 0; a < ls->m; ++a) {
+                if (!ls->pts[a]) return fail(ctx, TC_ERR_STATE, "leaf SRS was built without suffix tables");
+                if (inner_cursor[a] >= ls->shape[a]) return fail(ctx, TC_ERR_RANGE, "inner index outside the leaf tensor");
+            }
+            P[i].inner = inner_cursor;
+            inner_cursor += ls->m;
+        }
+    }
+    /* proof sizes */
+    std::vector<size_t> need(count);
+    for (int i = 0; i < count; ++i) {
+        size_t bytes = (size_t)n_blocked * (96 * (size_t)m + 32 + 96);
+        if (t->leaf_kind == TC_LEAF_TENSORS) bytes += 96 * (size_t)t->leaf_srs[P[i].leaf_flat]->m + 32;
+        else bytes -= 96;                               /* the bottom step carries no child commitment */
+        need[i] = bytes;
+        proof_len[i] = bytes;
+        if (bytes > proof_stride) return fail(ctx, TC_ERR_ARG, "proof buffer too small");
+    }
+
+    /* blocked levels: pi and y for every (path, level) */
+    uint32_t jobs = (uint32_t)count * (uint32_t)n_blocked;
+    std::vector<uint8_t> h_pi((size_t)jobs * m * 96), h_y((size_t)jobs * 32);
+    if (jobs) {
+        WS(d_pi, g1_xyzz, (uint64_t)jobs * m);
+        WS(d_y, fr_plain, jobs);
+        if (use_fb) {
+            NodeOpenTerms k;
+            memset((void*)&k, 0, sizeof k);
+            k.node.m = m;
+            uint32_t terms = 0;
+            for (int j = 0; j < 4; ++j) k.node.d[j] = j < m ? t->node_shape[j] : 1;
+            for (int a = 0; a < m; ++a) {
+                k.axis_first[a] = terms;
+                terms += (uint32_t)ns->n[a];
+                k.ax[a] = ns->ax[a];
+                k.table[a] = ns->fb[a];
+            }
+            for (int a = m; a <= 4; ++a) k.axis_first[a] = terms;
+            k.terms_per_job = terms;
+            for (int b = 0; b < n_blocked; ++b) {
+                int L = first_blocked + b;
+                const uint32_t* below = L == 0 ? t->grid : t->levels[L - 1].grid;
+                k.lv[b].g = make_geom(t, below, t->levels[L].grid);
+                k.lv[b].payload = L == 0 ? t->d_payload : nullptr;
+                k.lv[b].dtype = t->dtype;
+                k.lv[b].below = L == 0 ? nullptr : t->levels[L - 1].phi;
+            }
+            std::vector<NodeOpenJob> hj(jobs);
+            std::vector<uint32_t> seg((size_t)jobs * m + 1);
+            for (int i = 0; i < count; ++i)
+                for (int b = 0; b < n_blocked; ++b) {
+                    uint32_t j = (uint32_t)i * n_blocked + b;
+                    hj[j].node = P[i].node[b];
+                    for (int a = 0; a < 4; ++a) hj[j].kappa[a] = P[i].kap[b][a];
+                    hj[j].level = b;
+                    hj[j].term0 = j * terms;
+                    for (int a = 0; a < m; ++a) seg[(size_t)j * m + a] = j * terms + k.axis_first[a];
+                }
+            seg[(size_t)jobs * m] = jobs * terms;
+            WS(d_jobs, NodeOpenJob, jobs);
+            WS(d_seg, uint32_t, (uint64_t)jobs * m + 1);
+            WS(d_terms, g1_xyzz, (uint64_t)jobs * terms);
+            RT(rt::memcpy_h2d(d_jobs, hj.data(), sizeof(NodeOpenJob) * jobs, ctx->stream));
+            RT(rt::memcpy_h2d(d_seg, seg.data(), 4 * seg.size(), ctx->stream));
+            k.jobs = d_jobs;
+            k.out = d_terms;
+            k.y_out = d_y;
+            RT(rt::launch<64>((uint64_t)jobs * terms, ctx->stream, k));
+            RT(rt::launch<64>((uint64_t)jobs * m, ctx->stream, SumSegments{d_terms, d_seg, d_pi}));
+        } else {
+            /* large node shapes: gather the node tensor and open it like any tensor */
+            for (int i = 0; i < count; ++i)
+                for (int b = 0; b < n_blocked; ++b) {
+                    int L = first_blocked + b;
+                    uint32_t j = (uint32_t)i * n_blocked + b;
+                    const uint32_t* below = L == 0 ? t->grid : t->levels[L - 1].grid;
+                    TreeGeom g = make_geom(t, below, t->levels[L].grid);
+                    size_t mk = ctx->ws.off;
+                    bool bottom = L == 0;
+                    void* z = ws_alloc(ctx, (size_t)t->B * (bottom ? dtype_size(t->dtype) : 32));
+                    if (!z) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed");
+                    if (bottom) RT(rt::launch<64>(t->B, ctx->stream, GatherNodeSmall{g, t->d_payload, t->dtype, P[i].node[b], z}));
+                    else RT(rt::launch<64>(t->B, ctx->stream, GatherNodeFr{g, t->levels[L - 1].phi, P[i].node[b], (fr_plain*)z}));
+                    uint32_t kap[4];
+                    for (int a = 0; a < 4; ++a) kap[a] = P[i].kap[b][a];
+                    TRY(open_device(ctx, ns, z, bottom ? t->dtype : TC_FR, kap, d_pi + (uint64_t)j * m, d_y + j));
+                    ctx->ws.off = mk;
+                }
+        }
+        RT(rt::memcpy_d2h(h_y.data(), d_y, 32ull * jobs, ctx->stream));
+        TRY(points_to_host(ctx, d_pi, jobs * (uint32_t)m, h_pi.data()));
+    }
+    /* leaf tensors */
+    std::vector<std::vector<uint8_t>> leaf_part(count);
+    if (t->leaf_kind == TC_LEAF_TENSORS) {
+        for (int i = 0; i < count; ++i) {
+            const tc_srs* ls = t->leaf_srs[P[i].leaf_flat];
+            size_t mk = ctx->ws.off;
+            WS(pi, g1_xyzz, 4);
+            WS(y, fr_plain, 1);
+            TRY(open_device(ctx, ls, t->leaf_scalars[P[i].leaf_flat], t->leaf_dtype[P[i].leaf_flat], P[i].inner, pi, y));
+            leaf_part[i].resize(96 * (size_t)ls->m + 32);
+            RT(rt::memcpy_d2h(leaf_part[i].data() + 96 * (size_t)ls->m, y, 32, ctx->stream));
+            TRY(points_to_host(ctx, pi, (uint32_t)ls->m, leaf_part[i].data()));
+            ctx->ws.off = mk;
+        }
+    }
+    /* child commitments along the paths */
+    uint32_t n_child = 0;
+    std::vector<uint8_t> h_child;
+    {
+        /* for blocked level b (0 = lowest blocked) the child is the node of the level below on the path */
+        std::vector<std::pair<int, uint64_t>> want;     /* (level, node) */
+        for (int i = 0; i < count; ++i)
+            for (int b = 0; b < n_blocked; ++b) {
+                int L = first_blocked + b;
+                if (L == 0) continue;
+                uint64_t child = (b == 0) ? P[i].leaf_flat : P[i].node[b - 1];
+                want.push_back({L - 1, child});
+            }
+        n_child = (uint32_t)want.size();
+        if (n_child) {
+            WS(d_sel, g1_affine, n_child);
+            for (uint32_t w = 0; w < n_child; ++w)
+                RT(rt::memcpy_d2d(d_sel + w, t->levels[want[w].first].C + want[w].second, sizeof(g1_affine), ctx->stream));
+            h_child.resize(96ull * n_child);
+            TRY(affine_to_host(ctx, d_sel, n_child, h_child.data()));
+        }
+    }
+    /* assemble, top level first */
+    uint32_t child_cursor = 0;
+    for (int i = 0; i < count; ++i) {
+        uint8_t* dst = (uint8_t*)proof_buf + (size_t)i * proof_stride;
+        /* children were queued bottom-up for this path */
+        uint32_t n_child_i = 0;
+        for (int b = 0; b < n_blocked; ++b)
+            if (first_blocked + b > 0) ++n_child_i;
+        for (int b = n_blocked - 1; b >= 0; --b) {
+            uint32_t j = (uint32_t)i * n_blocked + b;
+            memcpy(dst, h_pi.data() + (size_t)j * m * 96, 96 * (size_t)m);
+            dst += 96 * (size_t)m;
+            memcpy(dst, h_y.data() + 32 * (size_t)j, 32);
+            dst += 32;
+            if (first_blocked + b > 0) {
+                uint32_t slot = child_cursor + (uint32_t)(b - (first_blocked ? 0 : 1));
+                memcpy(dst, h_child.data() + 96ull * slot, 96);
+                dst += 96;
+            }
+        }
+        child_cursor += n_child_i;
+        if (t->leaf_kind == TC_LEAF_TENSORS) {
+            memcpy(dst, leaf_part[i].data(), leaf_part[i].size());
+            dst += leaf_part[i].size();
+        }
+        if ((size_t)(dst - ((uint8_t*)proof_buf + (size_t)i * proof_stride)) != need[i]) return fail(ctx, TC_ERR_STATE, "internal: proof size mismatch");
+    }
+    return TC_OK;
+}
+
+extern "C" int tc_terkle_open(tc_ctx* ctx, const tc_tree* tree, const uint32_t* leaf_index, const uint32_t* inner_index,
+                              void* proof_buf, size_t* proof_len) {
+    if (!ctx) return TC_ERR_ARG;
+    if (!proof_len) return fail(ctx, TC_ERR_ARG, "null argument");
+    size_t cap = *proof_len;
+    return tc_terkle_open_batch(ctx, tree, 1, leaf_index, inner_index, proof_buf, cap, proof_len);
+}
+
+/* ---- path verification --------------------------------------------------------------------- */
+extern "C" int tc_verify_paths_batch(tc_ctx* ctx, const tc_vk* vk, int count, const tc_path* paths, const uint8_t* roots,
+                                     const uint8_t* leaf_values, const void* proofs, size_t proof_stride,
+                                     const size_t* proof_len, int* results) {
+    if (!ctx) return TC_ERR_ARG;
+    if (!vk || count < 0 || (count && (!paths || !roots || !leaf_values || !proofs || !proof_len || !results)))
+        return fail(ctx, TC_ERR_ARG, "null argument");
+    if (!count) return TC_OK;
+    RT(rt::set_device(ctx->device));
+    TRY(ws_reset(ctx));
+    std::vector<VerifyStep> steps;
+    std::vector<int> first_step(count + 1, 0);
+    std::vector<uint8_t> malformed(count, 0);
+    std::vector<std::vector<uint8_t>> child_bytes;        /* per step: commitment carried to the next step (or empty) */
+    for (int i = 0; i < count; ++i) {
+        const tc_path& p = paths[i];
+        first_step[i] = (int)steps.size();
+        const uint8_t* src = (const uint8_t*)proofs + (size_t)i * proof_stride;
+        size_t expect = 0;
+        bool bad = p.n_steps < 1 || p.n_steps > TC_MAX_STEPS;
+        for (int s = 0; s < p.n_steps && !bad; ++s) {
+            if (p.m[s] < 1 || p.m[s] > vk->m || !shape_ok(p.m[s], p.shape[s], nullptr)) bad = true;
+            else {
+                for (int j = 0; j < p.m[s]; ++j) bad = bad || p.kappa[s][j] >= p.shape[s][j];
+                expect += 96 * (size_t)p.m[s] + 32 + (s + 1 < p.n_steps ? 96 : 0);
+            }
+        }
+        if (bad || expect != proof_len[i]) {
+            malformed[i] = 1;
+            continue;
+        }
+        const uint8_t* carried = roots + 96 * (size_t)i;
+        for (int s = 0; s < p.n_steps; ++s) {
+            VerifyStep st;
+            memset(&st, 0, sizeof st);
+            st.m = p.m[s];
+            memcpy(st.C, carried, 96);
+            for (int j = 0; j < st.m; ++j) {
+                memcpy(st.pi[j], src, 96);
+                src += 96;
+                st.kappa[j] = p.kappa[s][j];
+            }
+            memcpy(st.y, src, 32);
+            src += 32;
+            steps.push_back(st);
+            if (s + 1 < p.n_steps) {
+                child_bytes.emplace_back(src, src + 96);
+                carried = src;
+                src += 96;
+            } else {
+                child_bytes.emplace_back();
+            }
+        }
+    }
+    first_step[count] = (int)steps.size();
+    std::vector<uint32_t> ok;
+    TRY(verify_steps(ctx, vk, steps, ok));
+    /* phi of every carried commitment, on the device */
+    uint32_t ns = (uint32_t)steps.size();
+    std::vector<uint8_t> h_phi(32ull * (ns ? ns : 1), 0);
+    if (ns) {
+        std::vector<uint32_t> pts(24ull * ns, 0);
+        for (uint32_t s = 0; s < ns; ++s)
+            if (!child_bytes[s].empty()) memcpy(&pts[24ull * s], child_bytes[s].data(), 96);
+        WS(d_pts, uint32_t, 24ull * ns);
+        WS(d_phi, fr_plain, ns);
+        RT(rt::memcpy_h2d(d_pts, pts.data(), 96ull * ns, ctx->stream));
+        RT(rt::launch<64>(ns, ctx->stream, PhiCanonical{d_pts, d_phi}));
+        RT(rt::memcpy_d2h(h_phi.data(), d_phi, 32ull * ns, ctx->stream));
+        RT(rt::stream_sync(ctx->stream));
+    }
+    for (int i = 0; i < count; ++i) {
+        if (malformed[i]) { results[i] = TC_ERR_VERIFY; continue; }
+        bool good = true;
+        for (int s = first_step[i]; s < first_step[i + 1]; ++s) {
+            good = good && ok[s];
+            bool last = s + 1 == first_step[i + 1];
+            const uint8_t* yb = (const uint8_t*)steps[s].y;
+            if (last) good = good && memcmp(yb, leaf_values + 32 * (size_t)i, 32) == 0;
+            else good = good && memcmp(yb, &h_phi[32ull * s], 32) == 0;
+        }
+        results[i] = good ? TC_OK : TC_ERR_VERIFY;
+    }
+    return TC_OK;
+}
+
+extern "C" int tc_verify_path(tc_ctx* ctx, const tc_vk* vk, const tc_path* path, const uint8_t root[96],
+                              const uint8_t leaf_value[32], const void* proof, size_t proof_len) {
+    if (!ctx) return TC_ERR_ARG;
+    int result = TC_ERR_VERIFY;
+    int rc = tc_verify_paths_batch(ctx, vk, 1, path, root, leaf_value, proof, proof_len, &proof_len, &result);
+    if (rc != TC_OK) return rc;
+    if (result != TC_OK) return fail(ctx, TC_ERR_VERIFY, "path rejected");
+    return TC_OK;
+}

@@ -1,0 +1,38 @@
+"""Helpers shared by the GPU parity tests: device buffers through torch, oracle-side caches."""
+import numpy as np
+
+import tc_inputs
+from oracle import bls12_381 as ec
+from oracle import tc
+
+TAU = tc_inputs.trapdoors()
+TAU_BYTES = tc_inputs.trapdoor_bytes()
+_pp = {}
+
+
+def pps(shape):
+    shape = tuple(int(d) for d in shape)
+    if shape not in _pp:
+        _pp[shape] = tc.setup(shape, TAU)
+    return _pp[shape]
+
+
+def to_device(arr):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(arr)).cuda()
+
+
+def fr_bytes_array(values):
+    """Python ints -> contiguous uint8 array of canonical 32-byte Fr values."""
+    return np.frombuffer(b"".join(ec.fr_to_bytes(int(v) % ec.R) for v in values), dtype=np.uint8).copy()
+
+
+def serialize_steps(steps):
+    """Oracle path steps -> the proof byte layout of the library (top level first)."""
+    out = b""
+    for (_k, y, pi, child) in steps:
+        out += b"".join(ec.g1_to_bytes(p) for p in pi) + ec.fr_to_bytes(y)
+        if child is not None:
+            out += ec.g1_to_bytes(child)
+    return out

@@ -1,0 +1,49 @@
+// Host build of the library's field / curve headers, exported for CPU-side tests.
+// The same inline functions run inside the HIP kernels; compiling them with g++ lets
+// the CPU test-suite check them against the oracle without a GPU.
+#include <cstring>
+
+#include "../../paper_2602_12630_amd/csrc/g1.h"
+
+using namespace tc;
+
+static fp_t fp_load(const uint8_t* b) { uint32_t w[12]; memcpy(w, b, 48); return fe_from_limbs<FpParams>(w); }
+static void fp_store(uint8_t* b, const fp_t& a) { fp_t p = fe_to_plain(a); memcpy(b, p.l, 48); }
+static fr_t fr_load(const uint8_t* b) { uint32_t w[8]; memcpy(w, b, 32); return fe_from_limbs<FrParams>(w); }
+static void fr_store(uint8_t* b, const fr_t& a) { fr_t p = fe_to_plain(a); memcpy(b, p.l, 32); }
+static g1_affine pt_load(const uint8_t* b) { uint32_t w[24]; memcpy(w, b, 96); return affine_from_canonical(w); }
+static void pt_store(uint8_t* b, const g1_affine& p) { uint32_t w[24]; affine_to_canonical(p, w); memcpy(b, w, 96); }
+
+extern "C" {
+void hm_fp_mul(const uint8_t* a, const uint8_t* b, uint8_t* o) { fp_store(o, fp_mul(fp_load(a), fp_load(b))); }
+void hm_fp_add(const uint8_t* a, const uint8_t* b, uint8_t* o) { fp_store(o, fp_add(fp_load(a), fp_load(b))); }
+void hm_fp_sub(const uint8_t* a, const uint8_t* b, uint8_t* o) { fp_store(o, fp_sub(fp_load(a), fp_load(b))); }
+void hm_fp_inv(const uint8_t* a, uint8_t* o) { fp_store(o, fe_inv_fermat<FpParams>(fp_load(a))); }
+void hm_fr_mul(const uint8_t* a, const uint8_t* b, uint8_t* o) { fr_store(o, fr_mul(fr_load(a), fr_load(b))); }
+void hm_fr_add(const uint8_t* a, const uint8_t* b, uint8_t* o) { fr_store(o, fr_add(fr_load(a), fr_load(b))); }
+void hm_fr_sub(const uint8_t* a, const uint8_t* b, uint8_t* o) { fr_store(o, fr_sub(fr_load(a), fr_load(b))); }
+void hm_fr_from_i32(int32_t v, uint8_t* o) { fr_store(o, fe_from_i32<FrParams>(v)); }
+// a + b through the XYZZ laws: mode 0 = mixed add (a accumulated from affine), 1 = full add
+// with both operands pushed away from Z = 1 first (a = (a + g) - g style is avoided: we use 2a - a)
+void hm_g1_add(const uint8_t* a, const uint8_t* b, int mode, uint8_t* o) {
+    g1_affine A = pt_load(a), B = pt_load(b);
+    g1_xyzz r;
+    if (mode == 0) {
+        r = xyzz_madd(xyzz_from_affine(A), B);
+    } else if (mode == 1) {
+        r = xyzz_add(xyzz_from_affine(A), xyzz_from_affine(B));
+    } else {
+        // non-trivial ZZ on both sides: A = 2A + (-A), B = 2B + (-B)
+        g1_xyzz A2 = xyzz_madd(xyzz_dbl_affine(A), affine_neg(A));
+        g1_xyzz B2 = xyzz_madd(xyzz_dbl(xyzz_from_affine(B)), affine_neg(B));
+        r = xyzz_add(A2, B2);
+    }
+    pt_store(o, xyzz_to_affine(r));
+}
+void hm_g1_mul(const uint8_t* k, const uint8_t* p, uint8_t* o) {
+    uint32_t w[8]; memcpy(w, k, 32);
+    pt_store(o, xyzz_to_affine(xyzz_mul_affine(w, 256, pt_load(p))));
+}
+void hm_g1_generator(uint8_t* o) { pt_store(o, affine_generator()); }
+void hm_phi(const uint8_t* p, uint8_t* o) { fr_t v = phi_map(pt_load(p)); memcpy(o, v.l, 32); }
+}

@@ -1,0 +1,295 @@
+"""GPU parity: the HIP library through its C ABI against the CPU oracle, byte for byte.
+
+All integer work, so every comparison is exact equality of canonical encodings."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import tc_inputs
+from oracle import bls12_381 as ec
+from oracle import cbind, quantize, tc, terkle
+from oracle.bls12_381 import R
+
+from gpu_util import TAU_BYTES, fr_bytes_array, pps, serialize_steps, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def T():
+    import paper_2602_12630_amd as pkg
+
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def ctx(T):
+    import torch
+
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    c = T.Context(0)
+    yield c
+    c.close()
+
+
+@pytest.fixture(scope="module")
+def node_srs(T, ctx):
+    s = ctx.setup_from_trapdoor(TAU_BYTES, tc_inputs.NODE_SHAPE, T.TC_SRS_SUFFIX | T.TC_SRS_FIXED_BASE)
+    yield s
+    s.close()
+
+
+@pytest.fixture(scope="module")
+def c1(T, ctx):
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, tc_inputs.C1_SHAPE, T.TC_SRS_SUFFIX)
+    X = tc_inputs.c1_tensor()
+    yield srs, X, to_device(X)
+    srs.close()
+
+
+def test_srs_points_match_oracle(ctx, c1):
+    srs, _, _ = c1
+    pp = pps(tc_inputs.C1_SHAPE)
+    rng = np.random.default_rng(1)
+    for f in [0, 1023] + [int(v) for v in rng.integers(0, 1024, 10)]:
+        want = ec.mul(pp.lagrange_scalar(tc.multi_index(f, pp.shape)), ec.G1)
+        assert srs.point(f) == ec.g1_to_bytes(want)
+    for a, n in ((1, 256), (2, 16)):
+        assert srs.size(a) == n
+        for f in (0, n - 1, n // 3):
+            want = ec.mul(pp.lagrange_scalar(tc.multi_index(f, pp.shape[a:]), a), ec.G1)
+            assert srs.point(f, a) == ec.g1_to_bytes(want)
+
+
+def test_c1_commit_and_golden(T, ctx, c1):
+    srs, X, dX = c1
+    got = ctx.commit(srs, dX, T.TC_I8)
+    assert got == ec.g1_to_bytes(tc.commit(pps(tc_inputs.C1_SHAPE), X))
+    with open(os.path.join(os.path.dirname(__file__), "golden", "c1_oracle.json")) as f:
+        gold = json.load(f)
+    assert got.hex() == gold["commitment"]
+
+
+def test_c1_openings_and_verification(T, ctx, c1):
+    srs, X, dX = c1
+    pp = pps(tc_inputs.C1_SHAPE)
+    C = ctx.commit(srs, dX, T.TC_I8)
+    vk = ctx.vk_from_trapdoor(TAU_BYTES)
+    for kappa in tc_inputs.opening_positions(tc_inputs.C1_SHAPE, 8, tc_inputs.tensor_seed(0)):
+        y, pi = ctx.open(srs, dX, T.TC_I8, kappa)
+        yo, po = tc.open_(pp, X, kappa)
+        assert y == ec.fr_to_bytes(yo)
+        assert pi == [ec.g1_to_bytes(p) for p in po]
+        assert ctx.verify(vk, tc_inputs.C1_SHAPE, C, kappa, y, pi)
+        assert tc.verify(pp, ec.g1_from_bytes(C), kappa, yo, [ec.g1_from_bytes(p) for p in pi])
+        assert not ctx.verify(vk, tc_inputs.C1_SHAPE, C, kappa, ec.fr_to_bytes((yo + 1) % R), pi)
+        bad = list(pi)
+        bad[1] = ec.g1_to_bytes(ec.add(po[1], ec.G1))
+        assert not ctx.verify(vk, tc_inputs.C1_SHAPE, C, kappa, y, bad)
+
+
+@pytest.mark.parametrize("shape", [(1,), (5,), (3, 4), (2, 3, 2), (2, 2, 2, 2), (7, 33), (16, 16)])
+def test_commit_small_shapes_all_dtypes(T, ctx, shape):
+    pp = pps(shape)
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, T.TC_SRS_SUFFIX)
+    try:
+        X16 = tc_inputs.int16_uniform(shape, 11, -32768, 32767)
+        X16.reshape(-1)[0] = -32768
+        X8 = tc_inputs.int8_uniform(shape, 12)
+        X8.reshape(-1)[-1] = -128
+        rng = np.random.default_rng(13)
+        fr_vals = [int.from_bytes(rng.bytes(32), "little") % R for _ in range(tc.prod(shape))]
+        assert ctx.commit(srs, to_device(X16), T.TC_I16) == ec.g1_to_bytes(tc.commit(pp, X16))
+        assert ctx.commit(srs, to_device(X8), T.TC_I8) == ec.g1_to_bytes(tc.commit(pp, X8))
+        assert ctx.commit(srs, to_device(fr_bytes_array(fr_vals)), T.TC_FR) == ec.g1_to_bytes(tc.commit(pp, fr_vals))
+        kappa = tuple(d - 1 for d in shape)
+        y, pi = ctx.open(srs, to_device(X16), T.TC_I16, kappa)
+        yo, po = tc.open_(pp, X16, kappa)
+        assert (y, pi) == (ec.fr_to_bytes(yo), [ec.g1_to_bytes(p) for p in po])
+    finally:
+        srs.close()
+
+
+def test_special_tensors(T, ctx):
+    shape = (6, 50)
+    pp = pps(shape)
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, 0)
+    try:
+        assert ctx.commit(srs, to_device(np.zeros(shape, np.int16)), T.TC_I16) == bytes(96)
+        for c in (1, -1, 77, -32768, 32767):
+            got = ctx.commit(srs, to_device(np.full(shape, c, np.int16)), T.TC_I16)
+            assert got == ec.g1_to_bytes(ec.mul(c % R, ec.G1))                    # constant tensor => [c]G
+        for f in (0, 149, 299):
+            onehot = np.zeros(300, np.int8)
+            onehot[f] = 1
+            assert ctx.commit(srs, to_device(onehot), T.TC_I8) == srs.point(f)     # one-hot => S[f]
+            onehot[f] = -1
+            neg = ec.neg(ec.g1_from_bytes(srs.point(f)))
+            assert ctx.commit(srs, to_device(onehot), T.TC_I8) == ec.g1_to_bytes(neg)
+        # two entries that cancel: P + (-P)
+        two = np.zeros(300, np.int16)
+        two[5], two[6] = 9, -9
+        want = ec.mul(9 * (pp.lagrange_scalar((0, 5)) - pp.lagrange_scalar((0, 6))) % R, ec.G1)
+        assert ctx.commit(srs, to_device(two), T.TC_I16) == ec.g1_to_bytes(want)
+    finally:
+        srs.close()
+
+
+def test_linearity(T, ctx):
+    shape = (9, 21)
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, 0)
+    try:
+        A = tc_inputs.int8_uniform(shape, 1).astype(np.int16)
+        B = tc_inputs.int8_uniform(shape, 2).astype(np.int16)
+        a, b = 37, -91
+        lhs = ctx.commit(srs, to_device((a * A + b * B).astype(np.int16)), T.TC_I16)
+        CA = ec.g1_from_bytes(ctx.commit(srs, to_device(A), T.TC_I16))
+        CB = ec.g1_from_bytes(ctx.commit(srs, to_device(B), T.TC_I16))
+        assert lhs == ec.g1_to_bytes(ec.add(ec.mul(a % R, CA), ec.mul(b % R, CB)))
+    finally:
+        srs.close()
+
+
+def test_encode_matches_oracle_quantisation(T, ctx):
+    import torch
+
+    x = tc_inputs.f16_normal((257, 131), 5)
+    x.reshape(-1)[:6] = np.array([0.0, -0.0, 65504.0, -65504.0, 6e-8, np.inf], np.float16)
+    for inv in (quantize.inv_scale_for(x[np.isfinite(x)]), np.float32(2.0), np.float32(0.0)):
+        dst = torch.empty(x.size, dtype=torch.int16, device="cuda")
+        ctx.encode_tensor(to_device(x.view(np.int16)), T.TC_F16, x.size, float(inv), dst)
+        ctx.sync()
+        want = quantize.quantize_f16(np.where(np.isfinite(x), x, np.float16(0)), inv).reshape(-1)
+        got = dst.cpu().numpy()
+        finite = np.isfinite(x.reshape(-1))
+        assert np.array_equal(got[finite], want[finite])
+    half = np.array([0.25, 0.75, 1.25, -0.25, -0.75], np.float16)
+    dst = torch.empty(5, dtype=torch.int16, device="cuda")
+    ctx.encode_tensor(to_device(half.view(np.int16)), T.TC_F16, 5, 2.0, dst)
+    ctx.sync()
+    assert dst.cpu().tolist() == [0, 2, 2, 0, -2]
+
+
+def _check_tree_against_oracle(ctx, tree, otree):
+    assert tree.levels == len(otree.levels)
+    for L in range(tree.levels):
+        grid, n = tree.level_info(L)
+        assert grid == otree.levels[L]["grid"] and n == len(otree.levels[L]["C"])
+        for i in range(n):
+            assert tree.node(L, i) == ec.g1_to_bytes(otree.levels[L]["C"][tc.multi_index(i, grid)])
+    assert tree.root == ec.g1_to_bytes(otree.root)
+
+
+@pytest.mark.parametrize("grid,dtype_name", [((37, 53), "i16"), ((4, 4), "i8"), ((1, 70), "i8"), ((19, 3), "i16")])
+def test_entries_tree_small(T, ctx, node_srs, grid, dtype_name):
+    node = tc_inputs.NODE_SHAPE
+    X = tc_inputs.int16_uniform(grid, 7) if dtype_name == "i16" else tc_inputs.int8_uniform(grid, 7)
+    dt = T.TC_I16 if dtype_name == "i16" else T.TC_I8
+    dX = to_device(X)
+    tree = ctx.terkle_build_entries(node_srs, dX, dt, grid, node)
+    otree = terkle.build(pps, tc.as_flat_ints(X), grid, node)
+    try:
+        _check_tree_against_oracle(ctx, tree, otree)
+        vk = ctx.vk_from_trapdoor(TAU_BYTES)
+        leaves = tc_inputs.opening_positions(grid, 5, 3) + [tuple(g - 1 for g in grid), (0, 0)]
+        proofs = tree.open_batch(leaves)
+        paths = [tree.path(l) for l in leaves]
+        values = [ec.fr_to_bytes(int(X[l]) % R) for l in leaves]
+        for leaf, proof, path in zip(leaves, proofs, paths):
+            steps = terkle.open_path(pps, otree, grid, node, leaf)
+            assert proof == serialize_steps(steps)
+            assert path.n_steps == len(steps)
+        assert ctx.verify_paths_batch(vk, paths, [tree.root] * len(leaves), values, proofs) == [True] * len(leaves)
+        # tampering: leaf value, one byte of a proof element, the root
+        wrong = [ec.fr_to_bytes((int(X[l]) + 1) % R) for l in leaves]
+        assert ctx.verify_paths_batch(vk, paths, [tree.root] * len(leaves), wrong, proofs) == [False] * len(leaves)
+        bad = bytearray(proofs[0])
+        bad[10] ^= 1
+        assert not ctx.verify_path(vk, paths[0], tree.root, values[0], bytes(bad))
+        other_root = ec.g1_to_bytes(ec.add(otree.root, ec.G1))
+        assert not ctx.verify_path(vk, paths[0], other_root, values[0], proofs[0])
+        # flipped entry: the rebuilt root differs and the old proof no longer verifies against it
+        X2 = X.copy()
+        X2[leaves[0]] ^= 1
+        tree2 = ctx.terkle_build_entries(node_srs, to_device(X2), dt, grid, node)
+        assert tree2.root != tree.root
+        assert not ctx.verify_path(vk, paths[0], tree2.root, values[0], proofs[0])
+        tree2.close()
+    finally:
+        tree.close()
+
+
+def test_tensors_tree_small(T, ctx, node_srs):
+    node = tc_inputs.NODE_SHAPE
+    grid = (5, 3)
+    shapes = [(2, 3), (4,), (2, 2, 2), (3, 3), (5,), (2, 2), (6, 7), (1,), (3,), (2, 5), (4, 4), (2, 2, 3), (8,), (3, 2), (9,)]
+    leaves = [tc_inputs.int16_uniform(s, 50 + i) for i, s in enumerate(shapes)]
+    lsrs = [ctx.setup_from_trapdoor(TAU_BYTES, s, T.TC_SRS_SUFFIX) for s in shapes]
+    dl = [to_device(x) for x in leaves]
+    tree = ctx.terkle_build_tensors(node_srs, lsrs, dl, [T.TC_I16] * len(shapes), grid, node)
+    otree = terkle.build(pps, [tc.as_flat_ints(t) for t in leaves], grid, node, kind="tensors", leaf_shapes=shapes)
+    try:
+        _check_tree_against_oracle(ctx, tree, otree)
+        vk = ctx.vk_from_trapdoor(TAU_BYTES)
+        for leaf, inner in (((0, 2), (0, 1, 1)), ((4, 2), (8,)), ((2, 0), (5, 6)), ((1, 0), (1, 2))):
+            flat = leaf[0] * 3 + leaf[1]
+            proof = tree.open(leaf, inner)
+            steps = terkle.open_path(pps, otree, grid, node, leaf, inner)
+            assert proof == serialize_steps(steps)
+            path = tree.path(leaf, inner)
+            value = ec.fr_to_bytes(int(leaves[flat][inner]) % R)
+            assert ctx.verify_path(vk, path, tree.root, value, proof)
+            assert not ctx.verify_path(vk, path, tree.root, ec.fr_to_bytes(5), proof)
+    finally:
+        tree.close()
+        for s in lsrs:
+            s.close()
+
+
+def test_c1_single_level_tree(T, ctx, c1):
+    srs, X, dX = c1
+    shape = tc_inputs.C1_SHAPE
+    tree = ctx.terkle_build_entries(srs, dX, T.TC_I8, shape, shape)
+    try:
+        assert tree.levels == 1
+        assert tree.root == ec.g1_to_bytes(tc.commit(pps(shape), X))
+        vk = ctx.vk_from_trapdoor(TAU_BYTES)
+        leaves = tc_inputs.opening_positions(shape, 8, tc_inputs.tensor_seed(0))
+        proofs = tree.open_batch(leaves)
+        for leaf, proof in zip(leaves, proofs):
+            yo, po = tc.open_(pps(shape), X, leaf)
+            assert proof == b"".join(ec.g1_to_bytes(p) for p in po) + ec.fr_to_bytes(yo)
+        paths = [tree.path(l) for l in leaves]
+        vals = [ec.fr_to_bytes(int(X[l]) % R) for l in leaves]
+        assert ctx.verify_paths_batch(vk, paths, [tree.root] * 8, vals, proofs) == [True] * 8
+    finally:
+        tree.close()
+
+
+def test_c2_activation_commit(T, ctx):
+    """Config 2: one 512 x 4096 fp16 activation, quantised on the GPU, committed as one tensor."""
+    import torch
+
+    shape = tc_inputs.C2_SHAPE
+    x = tc_inputs.c2_activation()
+    inv = quantize.inv_scale_for(x)
+    q_want = quantize.quantize_f16(x, inv)
+    dq = torch.empty(x.size, dtype=torch.int16, device="cuda")
+    ctx.encode_tensor(to_device(x.view(np.int16)), T.TC_F16, x.size, float(inv), dq)
+    ctx.sync()
+    assert np.array_equal(dq.cpu().numpy().reshape(shape), q_want)
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, 0)
+    try:
+        pp = pps(shape)
+        got = ctx.commit(srs, dq, T.TC_I16)
+        want = cbind.commit(pp, q_want, nthreads=8)
+        assert got == ec.g1_to_bytes(want)
+        # SRS spot checks at this size
+        rng = np.random.default_rng(2)
+        for f in [0, tc.prod(shape) - 1] + [int(v) for v in rng.integers(0, tc.prod(shape), 6)]:
+            want_pt = cbind.g1_mul(pp.lagrange_scalar(tc.multi_index(f, shape)), ec.G1)
+            assert srs.point(f) == ec.g1_to_bytes(want_pt)
+    finally:
+        srs.close()

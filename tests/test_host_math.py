@@ -1,0 +1,97 @@
+"""The library's field / curve headers, compiled for the host with g++, against the oracle.
+
+The HIP kernels inline these same functions; this CPU test finds arithmetic mistakes
+(carry handling, exceptional cases of the group law, the G1 -> Fr map) without a GPU."""
+import ctypes
+import os
+import random
+import subprocess
+
+import pytest
+
+from oracle import bls12_381 as ec
+from oracle import terkle
+from oracle.bls12_381 import P, R
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "hostmath", "hostmath.cpp")
+LIB = os.path.join(HERE, "hostmath", "libhostmath.so")
+
+
+@pytest.fixture(scope="module")
+def hm():
+    hdrs = [os.path.join(HERE, "..", "paper_2602_12630_amd", "csrc", h) for h in ("field.h", "g1.h", "constants.h")]
+    newest = max(os.path.getmtime(f) for f in [SRC] + hdrs)
+    if not os.path.exists(LIB) or os.path.getmtime(LIB) < newest:
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-o", LIB, SRC])
+    return ctypes.CDLL(LIB)
+
+
+def _b(x, n):
+    return (ctypes.c_uint8 * n).from_buffer_copy(int(x).to_bytes(n, "little"))
+
+
+def _call2(fn, a, b, n):
+    out = (ctypes.c_uint8 * n)()
+    fn(_b(a, n), _b(b, n), out)
+    return int.from_bytes(bytes(out), "little")
+
+
+def test_fp_fr_arithmetic(hm):
+    rng = random.Random(1)
+    edge_p = [0, 1, 2, P - 1, P - 2, (P - 1) // 2, (1 << 380), 0xFFFFFFFF, (1 << 352) - 1]
+    vals = edge_p + [rng.randrange(P) for _ in range(60)]
+    for a in vals:
+        for b in edge_p + [rng.randrange(P) for _ in range(4)]:
+            assert _call2(hm.hm_fp_mul, a, b, 48) == a * b % P
+            assert _call2(hm.hm_fp_add, a, b, 48) == (a + b) % P
+            assert _call2(hm.hm_fp_sub, a, b, 48) == (a - b) % P
+    edge_r = [0, 1, 2, R - 1, R - 2, (1 << 254), 0xFFFFFFFF]
+    for a in edge_r + [rng.randrange(R) for _ in range(60)]:
+        for b in edge_r + [rng.randrange(R) for _ in range(4)]:
+            assert _call2(hm.hm_fr_mul, a, b, 32) == a * b % R
+            assert _call2(hm.hm_fr_add, a, b, 32) == (a + b) % R
+            assert _call2(hm.hm_fr_sub, a, b, 32) == (a - b) % R
+    for a in (1, 2, P - 1, rng.randrange(1, P)):
+        out = (ctypes.c_uint8 * 48)()
+        hm.hm_fp_inv(_b(a, 48), out)
+        assert int.from_bytes(bytes(out), "little") * a % P == 1
+    for v in (0, 1, -1, 127, -128, 32767, -32768, 2**31 - 1, -(2**31)):
+        out = (ctypes.c_uint8 * 32)()
+        hm.hm_fr_from_i32(ctypes.c_int32(v), out)
+        assert int.from_bytes(bytes(out), "little") == v % R
+
+
+def _pt(fn, *args):
+    out = (ctypes.c_uint8 * 96)()
+    fn(*args, out)
+    return ec.g1_from_bytes(bytes(out))
+
+
+def _pb(pt):
+    return (ctypes.c_uint8 * 96).from_buffer_copy(ec.g1_to_bytes(pt))
+
+
+def test_group_law_including_exceptional_cases(hm):
+    rng = random.Random(2)
+    assert _pt(hm.hm_g1_generator) == ec.G1
+    pts = [ec.mul(rng.randrange(1, R), ec.G1) for _ in range(5)]
+    for mode in (0, 1, 2):
+        for a in pts:
+            assert _pt(hm.hm_g1_add, _pb(a), _pb(a), mode) == ec.add_affine(a, a)                 # P + P
+            assert _pt(hm.hm_g1_add, _pb(a), _pb(ec.neg(a)), mode) is ec.INF                      # P + (-P)
+            assert _pt(hm.hm_g1_add, _pb(a), _pb(ec.INF), mode) == a                              # P + O
+            assert _pt(hm.hm_g1_add, _pb(ec.INF), _pb(a), mode) == a                              # O + P
+            for b in pts:
+                assert _pt(hm.hm_g1_add, _pb(a), _pb(b), mode) == ec.add_affine(a, b)
+        assert _pt(hm.hm_g1_add, _pb(ec.INF), _pb(ec.INF), mode) is ec.INF
+    for k in (0, 1, 2, 3, R - 1, rng.randrange(R), 1 << 200):
+        assert _pt(hm.hm_g1_mul, _b(k, 32), _pb(pts[0])) == ec.mul_affine(k, pts[0])
+
+
+def test_phi_map(hm):
+    rng = random.Random(3)
+    for pt in [ec.INF, ec.G1, ec.neg(ec.G1)] + [ec.mul(rng.randrange(1, R), ec.G1) for _ in range(20)]:
+        out = (ctypes.c_uint8 * 32)()
+        hm.hm_phi(_pb(pt), out)
+        assert int.from_bytes(bytes(out), "little") == terkle.phi(pt)
