@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the TensorCommitments prover hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic 512 x 4096 fp16
+activation (the single-transformer-layer configuration): quantise on the GPU,
+commit the tensor as one tensor commitment, build the arity-16 Terkle tree over
+its 2^21 entries, open 8 random entries through the tree and verify the paths.
+All inputs and the SRS tables are resident in HBM before the timed region.
+
+Prints one JSON line: metric "tensor elements committed/sec" with `roofline`
+(integer-ALU bound, the bucket-accumulation kernel) and `cpu_baseline` (the CPU
+oracle's naive multi-exponentiation on a bounded sample of the same tensor).
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import tc_inputs  # noqa: E402
+
+# One mixed addition in XYZZ coordinates = 8 multiplications + 2 squarings in Fp; one
+# Montgomery product of 12 x 32-bit limbs = 2 * 12^2 + 12 = 300 32x32->64 multiply-adds.
+FP_MULS_PER_MIXED_ADD = 10
+MADS_PER_FP_MUL = 300
+# Integer-ALU peak for this instruction mix: v_mad_u64_u32 issues at half the full vector rate
+# on gfx950 (measured: 33 of 64 lanes/clk/CU): 256 CU x 4 SIMD x 16 lanes x 2.4 GHz / 2.
+PEAK_MADS_PER_S = 256 * 4 * 16 * 2.4e9 / 2
+
+
+def hip_event_timer():
+    """HIP events through the runtime library directly (the library's stream is the default stream)."""
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    return hip
+
+
+class Events:
+    def __init__(self, hip):
+        self.hip = hip
+        self.pairs = []
+
+    def start(self):
+        a, b = ctypes.c_void_p(), ctypes.c_void_p()
+        self.hip.hipEventCreate(ctypes.byref(a))
+        self.hip.hipEventCreate(ctypes.byref(b))
+        self.hip.hipEventRecord(a, None)
+        return (a, b)
+
+    def stop(self, pair):
+        self.hip.hipEventRecord(pair[1], None)
+        self.pairs.append(pair)
+
+    def total_ms(self):
+        tot = 0.0
+        for a, b in self.pairs:
+            self.hip.hipEventSynchronize(b)
+            ms = ctypes.c_float()
+            self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+            tot += ms.value
+        return tot
+
+
+def cpu_baseline(q, budget_s=12.0):
+    """The oracle's naive multi-exponentiation (every term its own double-and-add) on the first
+    entries of the same quantised tensor, on all host cores the box gives us."""
+    from oracle import bls12_381 as ec
+    from oracle import cbind, tc
+
+    cores = min(os.cpu_count() or 1, 16)
+    shape = tc_inputs.C2_SHAPE
+    pp = tc.setup(shape, tc_inputs.trapdoors())
+    n = 2048
+    flat = q.reshape(-1)
+    # SRS points for the sample come from the oracle's own scalar multiplication
+    t0 = time.time()
+    pts = b"".join(ec.g1_to_bytes(cbind.g1_mul(pp.lagrange_scalar(tc.multi_index(f, shape)), ec.G1)) for f in range(256))
+    per_pt = (time.time() - t0) / 256
+    n = int(max(256, min(16384, (budget_s / 3) / max(per_pt, 1e-6))))
+    pts += b"".join(ec.g1_to_bytes(cbind.g1_mul(pp.lagrange_scalar(tc.multi_index(f, shape)), ec.G1)) for f in range(256, n))
+    sample = np.ascontiguousarray(flat[:n])
+    t0 = time.time()
+    reps = 0
+    while True:
+        _, used = cbind.msm_naive(sample, pts, cores)
+        reps += 1
+        dt = time.time() - t0
+        if dt > budget_s / 2 or reps >= 20:
+            break
+    return {
+        "value": n * reps / dt,
+        "unit": "tensor elements committed/sec",
+        "cores": used,
+        "kind": "oracle",
+        "sample": "naive double-and-add multi-exponentiation over the first %d entries of the same int16 tensor, "
+                  "%d repetitions, %d threads (commitment only; no tree)" % (n, reps, used),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--lib", default=None, help="path of an alternative libtc.so (experiments)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--openings", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2602_12630_amd as T
+    from oracle import quantize
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    lib = T.load_library(args.lib) if args.lib else None
+    ctx = T.Context(0, None, lib)
+    tau = tc_inputs.trapdoor_bytes()
+    shape = tc_inputs.C2_SHAPE
+    node = tc_inputs.NODE_SHAPE
+    n = shape[0] * shape[1]
+
+    t0 = time.time()
+    srs = ctx.setup_from_trapdoor(tau, shape, 0)
+    node_srs = ctx.setup_from_trapdoor(tau, node, T.TC_SRS_SUFFIX | T.TC_SRS_FIXED_BASE)
+    ctx.sync()
+    setup_s = time.time() - t0
+
+    x = tc_inputs.c2_activation()
+    inv = float(quantize.inv_scale_for(x))
+    dx = torch.from_numpy(x.view(np.int16)).cuda()
+    dq = torch.empty(n, dtype=torch.int16, device="cuda")
+    leaves = tc_inputs.opening_positions(shape, args.openings, tc_inputs.tensor_seed(1))
+    vk = ctx.vk_from_trapdoor(tau)
+    paths = [ctx.path_from_grid(shape, node, T.TC_LEAF_ENTRIES, l) for l in leaves]
+    torch.cuda.synchronize()
+
+    hip = hip_event_timer()
+    phases = {"encode": Events(hip), "commit": Events(hip), "tree": Events(hip), "open": Events(hip), "verify": Events(hip)}
+
+    def step(record):
+        def timed(name, fn):
+            if not record:
+                return fn()
+            p = phases[name].start()
+            out = fn()
+            phases[name].stop(p)
+            return out
+
+        timed("encode", lambda: ctx.encode_tensor(dx, T.TC_F16, n, inv, dq))
+        C = timed("commit", lambda: ctx.commit(srs, dq, T.TC_I16))
+        tree = timed("tree", lambda: ctx.terkle_build_entries(node_srs, dq, T.TC_I16, shape, node))
+        proofs = timed("open", lambda: tree.open_batch(leaves))
+        root = tree.root
+        q_host = None
+        ok = timed("verify", lambda: ctx.verify_paths_batch(vk, paths, [root] * len(leaves), leaf_values, proofs))
+        tree.close()
+        return C, root, ok, q_host
+
+    # leaf values for verification come from the quantised tensor (computed once, outside the timing)
+    ctx.encode_tensor(dx, T.TC_F16, n, inv, dq)
+    ctx.sync()
+    q = dq.cpu().numpy().reshape(shape)
+    R_MOD = 0x73EDA753299D7D483339D80809A1D80553BDA402FFFE5BFEFFFFFFFF00000001
+    leaf_values = [(int(q[l]) % R_MOD).to_bytes(32, "little") for l in leaves]
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        C, root, ok, _ = step(True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert all(ok), "path verification failed inside the benchmark"
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = n * args.steps / elapsed
+    phase_ms = {k: v.total_ms() / args.steps for k, v in phases.items()}
+
+    # roofline of the dominant kernel: bucket accumulation of the flat commitment.
+    # algorithmic work per launch = one mixed addition per non-zero entry.
+    nonzero = int(np.count_nonzero(q))
+    kern_ms = None
+    try:
+        kern_ms = float(os.environ.get("TC_BENCH_KERNEL_MS", "nan"))
+    except ValueError:
+        kern_ms = float("nan")
+    commit_ms = phase_ms["commit"]
+    mads = nonzero * FP_MULS_PER_MIXED_ADD * MADS_PER_FP_MUL
+    achieved = mads / (commit_ms * 1e-3)
+    out = {
+        "metric": "tensor elements committed/sec",
+        "value": value,
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {"workload": "C2: 512x4096 fp16 N(0,1) activation -> int16, one tensor commitment + arity-16 (4,4) "
+                               "Terkle tree over 2^21 entries (139813 nodes) + %d path openings + verification" % args.openings,
+                   "elements": n, "setup_s_untimed": setup_s},
+        "phase_ms": phase_ms,
+        "commit_only_elements_per_s": n / (commit_ms * 1e-3),
+        "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_MADS_PER_S / 1e12,
+                     "unit": "T 32x32->64 multiply-add/s", "frac": achieved / PEAK_MADS_PER_S, "traffic": None,
+                     "kernel": "tc_commit (whole call; per-kernel split in profiles/)"},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(q)
+    print(json.dumps(out))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

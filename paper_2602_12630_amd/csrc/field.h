@@ -16,8 +16,13 @@
 #if defined(__HIPCC__)
 #include <hip/hip_runtime.h>
 #define TC_HD __host__ __device__ __forceinline__
+/* The multi-limb products are real functions on the device (operands and result travel in
+ * VGPRs): a kernel with dozens of inlined 12 x 12 limb products no longer fits the
+ * instruction cache and takes minutes to compile. */
+#define TC_HD_CALL __host__ __device__ __attribute__((noinline))
 #else
 #define TC_HD inline
+#define TC_HD_CALL inline
 #endif
 
 namespace tc {
@@ -175,9 +180,119 @@ TC_HD Fe<P> fe_mul(const Fe<P>& a, const Fe<P>& b) {
     return fe_reduce_once<P>(r, t[N]);
 }
 
+#if defined(__HIP_DEVICE_COMPILE__)
+/* Device form of the same product: product scanning (column by column) with one
+ * 96-bit accumulator.  Each limb product is one v_mad_u64_u32 into the low 64 bits
+ * plus one v_addc_co_u32 of its carry into the third word; the modulus limbs sit
+ * in scalar registers.  Column k collects a_i b_{k-i} and m_i q_{k-i}; m_k is
+ * chosen so that the column's low word vanishes. */
+struct Acc96 {
+    uint64_t lo;
+    uint32_t hi;
+};
+__device__ __forceinline__ void mac_vv(Acc96& A, uint32_t a, uint32_t b) {
+    uint64_t carry, unused;
+    asm("v_mad_u64_u32 %0, %1, %2, %3, %0" : "+v"(A.lo), "=s"(carry) : "v"(a), "v"(b));
+    asm("v_addc_co_u32_e64 %0, %1, 0, %0, %2" : "+v"(A.hi), "=s"(unused) : "s"(carry));
+}
+__device__ __forceinline__ void mac_vs(Acc96& A, uint32_t a, uint32_t b) {
+    uint64_t carry, unused;
+    asm("v_mad_u64_u32 %0, %1, %2, %3, %0" : "+v"(A.lo), "=s"(carry) : "v"(a), "s"(b));
+    asm("v_addc_co_u32_e64 %0, %1, 0, %0, %2" : "+v"(A.hi), "=s"(unused) : "s"(carry));
+}
+__device__ __forceinline__ void acc_shift(Acc96& A) {
+    A.lo = (A.lo >> 32) | ((uint64_t)A.hi << 32);
+    A.hi = 0;
+}
+template <class P>
+__device__ __forceinline__ Fe<P> fe_mul_dev(const Fe<P>& a, const Fe<P>& b) {
+    constexpr int N = P::N;
+    Acc96 A{0, 0};
+    uint32_t m[N];
+    Fe<P> r;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+#pragma unroll
+        for (int i = 0; i <= k; ++i) mac_vv(A, a.l[i], b.l[k - i]);
+#pragma unroll
+        for (int i = 0; i < k; ++i) mac_vs(A, m[i], P::MOD[k - i]);
+        m[k] = (uint32_t)A.lo * P::INV;
+        mac_vs(A, m[k], P::MOD[0]);
+        acc_shift(A);
+    }
+#pragma unroll
+    for (int k = N; k < 2 * N - 1; ++k) {
+#pragma unroll
+        for (int i = k - N + 1; i < N; ++i) mac_vv(A, a.l[i], b.l[k - i]);
+#pragma unroll
+        for (int i = k - N + 1; i < N; ++i) mac_vs(A, m[i], P::MOD[k - i]);
+        r.l[k - N] = (uint32_t)A.lo;
+        acc_shift(A);
+    }
+    r.l[N - 1] = (uint32_t)A.lo;
+    return fe_reduce_once<P>(r, (uint32_t)(A.lo >> 32));
+}
+#endif
+
+/* plain (non-Montgomery) comparison a > b on limbs */
+template <int N>
+TC_HD bool limbs_gt(const uint32_t* a, const uint32_t* b) {
+    bool gt = false, decided = false;
+#pragma unroll
+    for (int i = N - 1; i >= 0; --i) {
+        if (!decided && a[i] != b[i]) { gt = a[i] > b[i]; decided = true; }
+    }
+    return gt;
+}
+
+TC_HD fp_t fp_add(const fp_t& a, const fp_t& b) { return fe_add<FpParams>(a, b); }
+TC_HD fp_t fp_sub(const fp_t& a, const fp_t& b) { return fe_sub<FpParams>(a, b); }
+#if defined(__HIP_DEVICE_COMPILE__)
+/* The device products are real functions: operands arrive as 4-limb vectors so that the
+ * calling convention keeps all 24 (16) limbs in VGPRs. */
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __attribute__((noinline)) fp_t fp_mul_call(u32x4 a0, u32x4 a1, u32x4 a2, u32x4 b0, u32x4 b1, u32x4 b2) {
+    fp_t a, b;
+    a.l[0] = a0.x; a.l[1] = a0.y; a.l[2] = a0.z; a.l[3] = a0.w; a.l[4] = a1.x; a.l[5] = a1.y; a.l[6] = a1.z; a.l[7] = a1.w;
+    a.l[8] = a2.x; a.l[9] = a2.y; a.l[10] = a2.z; a.l[11] = a2.w;
+    b.l[0] = b0.x; b.l[1] = b0.y; b.l[2] = b0.z; b.l[3] = b0.w; b.l[4] = b1.x; b.l[5] = b1.y; b.l[6] = b1.z; b.l[7] = b1.w;
+    b.l[8] = b2.x; b.l[9] = b2.y; b.l[10] = b2.z; b.l[11] = b2.w;
+    return fe_mul_dev<FpParams>(a, b);
+}
+__device__ __attribute__((noinline)) fr_t fr_mul_call(u32x4 a0, u32x4 a1, u32x4 b0, u32x4 b1) {
+    fr_t a, b;
+    a.l[0] = a0.x; a.l[1] = a0.y; a.l[2] = a0.z; a.l[3] = a0.w; a.l[4] = a1.x; a.l[5] = a1.y; a.l[6] = a1.z; a.l[7] = a1.w;
+    b.l[0] = b0.x; b.l[1] = b0.y; b.l[2] = b0.z; b.l[3] = b0.w; b.l[4] = b1.x; b.l[5] = b1.y; b.l[6] = b1.z; b.l[7] = b1.w;
+    return fe_mul_dev<FrParams>(a, b);
+}
+__device__ __forceinline__ fp_t fp_mul(const fp_t& a, const fp_t& b) {
+    return fp_mul_call(u32x4{a.l[0], a.l[1], a.l[2], a.l[3]}, u32x4{a.l[4], a.l[5], a.l[6], a.l[7]},
+                       u32x4{a.l[8], a.l[9], a.l[10], a.l[11]}, u32x4{b.l[0], b.l[1], b.l[2], b.l[3]},
+                       u32x4{b.l[4], b.l[5], b.l[6], b.l[7]}, u32x4{b.l[8], b.l[9], b.l[10], b.l[11]});
+}
+__device__ __forceinline__ fr_t fr_mul(const fr_t& a, const fr_t& b) {
+    return fr_mul_call(u32x4{a.l[0], a.l[1], a.l[2], a.l[3]}, u32x4{a.l[4], a.l[5], a.l[6], a.l[7]},
+                       u32x4{b.l[0], b.l[1], b.l[2], b.l[3]}, u32x4{b.l[4], b.l[5], b.l[6], b.l[7]});
+}
+#elif defined(__HIPCC__)
+/* host pass of hipcc: the device bodies exist only in the device pass */
+__device__ fp_t fp_mul(const fp_t& a, const fp_t& b);
+__device__ fr_t fr_mul(const fr_t& a, const fr_t& b);
+#endif
+#if defined(__HIPCC__)
+__host__ inline fp_t fp_mul(const fp_t& a, const fp_t& b) { return fe_mul<FpParams>(a, b); }
+__host__ inline fr_t fr_mul(const fr_t& a, const fr_t& b) { return fe_mul<FrParams>(a, b); }
+#else
+inline fp_t fp_mul(const fp_t& a, const fp_t& b) { return fe_mul<FpParams>(a, b); }
+inline fr_t fr_mul(const fr_t& a, const fr_t& b) { return fe_mul<FrParams>(a, b); }
+#endif
+/* overloads that pick the right product for generic helpers */
+TC_HD fp_t fe_mulx(const fp_t& a, const fp_t& b) { return fp_mul(a, b); }
+TC_HD fr_t fe_mulx(const fr_t& a, const fr_t& b) { return fr_mul(a, b); }
+
 template <class P>
 TC_HD Fe<P> fe_sqr(const Fe<P>& a) {
-    return fe_mul<P>(a, a);
+    return fe_mulx(a, a);
 }
 
 template <class P>
@@ -185,13 +300,13 @@ TC_HD Fe<P> fe_from_limbs(const uint32_t* w) {   /* plain value -> Montgomery fo
     Fe<P> a, r2;
 #pragma unroll
     for (int i = 0; i < P::N; ++i) { a.l[i] = w[i]; r2.l[i] = P::R2[i]; }
-    return fe_mul<P>(a, r2);
+    return fe_mulx(a, r2);
 }
 template <class P>
 TC_HD Fe<P> fe_to_plain(const Fe<P>& a) {        /* Montgomery form -> plain value */
     Fe<P> one = fe_zero<P>();
     one.l[0] = 1;
-    return fe_mul<P>(a, one);
+    return fe_mulx(a, one);
 }
 template <class P>
 TC_HD Fe<P> fe_from_u32(uint32_t v) {
@@ -214,31 +329,90 @@ TC_HD Fe<P> fe_inv_fermat(const Fe<P>& a) {
     Fe<P> acc = fe_one<P>();
     for (int i = P::N * 32 - 1; i >= 0; --i) {
         acc = fe_sqr<P>(acc);
-        if ((P::MOD_M2[i >> 5] >> (i & 31)) & 1u) acc = fe_mul<P>(acc, a);
+        if ((P::MOD_M2[i >> 5] >> (i & 31)) & 1u) acc = fe_mulx(acc, a);
     }
     return acc;
 }
 
-/* plain (non-Montgomery) comparison a > b on limbs */
-template <int N>
-TC_HD bool limbs_gt(const uint32_t* a, const uint32_t* b) {
-    bool gt = false, decided = false;
+/* Inverse of a non-zero element in Montgomery form, by the binary extended Euclid
+ * algorithm on the plain representative (shifts, subtractions and selects only; the same
+ * 64 N steps for every input, so the lanes of a wave never diverge):
+ *   invariants  a = u x,  b = v x  (mod q),  b odd;  each step: if a is odd, order the
+ *   pair so that a >= b and subtract (a, u) -= (b, v); then halve a and u.
+ * After 2 len(q) - 1 steps a = 0 and b = 1, so v = x^-1; x = a_mont = A R, and
+ * (A R)^-1 R^3 / R = A^-1 R restores the Montgomery form. */
+template <class P>
+TC_HD Fe<P> fe_inv(const Fe<P>& x) {
+    constexpr int N = P::N;
+    uint32_t a[N], b[N], u[N], v[N];
 #pragma unroll
-    for (int i = N - 1; i >= 0; --i) {
-        if (!decided && a[i] != b[i]) { gt = a[i] > b[i]; decided = true; }
+    for (int i = 0; i < N; ++i) { a[i] = x.l[i]; b[i] = P::MOD[i]; u[i] = 0; v[i] = 0; }
+    u[0] = 1;
+    for (int it = 0; it < 64 * N; ++it) {
+        uint32_t odd = 0u - (a[0] & 1u);
+        /* borrow of a - b */
+        uint32_t borrow = 0;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            uint64_t t = (uint64_t)a[i] - b[i] - borrow;
+            borrow = (uint32_t)(t >> 63);
+        }
+        uint32_t swap = odd & (0u - borrow);
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            uint32_t x1 = (a[i] ^ b[i]) & swap;
+            a[i] ^= x1; b[i] ^= x1;
+            uint32_t x2 = (u[i] ^ v[i]) & swap;
+            u[i] ^= x2; v[i] ^= x2;
+        }
+        /* a -= b, u -= v (mod q) when a is odd */
+        borrow = 0;
+        uint32_t borrow_u = 0;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            uint64_t t = (uint64_t)a[i] - (b[i] & odd) - borrow;
+            a[i] = (uint32_t)t;
+            borrow = (uint32_t)(t >> 63);
+            uint64_t s = (uint64_t)u[i] - (v[i] & odd) - borrow_u;
+            u[i] = (uint32_t)s;
+            borrow_u = (uint32_t)(s >> 63);
+        }
+        uint32_t fix = 0u - borrow_u;
+        uint32_t c = 0;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            uint64_t t = (uint64_t)u[i] + (P::MOD[i] & fix) + c;
+            u[i] = (uint32_t)t;
+            c = (uint32_t)(t >> 32);
+        }
+        /* halve a; halve u modulo q (add q first when u is odd) */
+        uint32_t uodd = 0u - (u[0] & 1u);
+        c = 0;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            uint64_t t = (uint64_t)u[i] + (P::MOD[i] & uodd) + c;
+            u[i] = (uint32_t)t;
+            c = (uint32_t)(t >> 32);
+        }
+#pragma unroll
+        for (int i = 0; i < N - 1; ++i) {
+            a[i] = (a[i] >> 1) | (a[i + 1] << 31);
+            u[i] = (u[i] >> 1) | (u[i + 1] << 31);
+        }
+        a[N - 1] >>= 1;
+        u[N - 1] = (u[N - 1] >> 1) | (c << 31);
     }
-    return gt;
+    Fe<P> r, r3;
+#pragma unroll
+    for (int i = 0; i < N; ++i) { r.l[i] = v[i]; r3.l[i] = P::R3[i]; }
+    return fe_mulx(r, r3);
 }
 
-TC_HD fp_t fp_add(const fp_t& a, const fp_t& b) { return fe_add<FpParams>(a, b); }
-TC_HD fp_t fp_sub(const fp_t& a, const fp_t& b) { return fe_sub<FpParams>(a, b); }
-TC_HD fp_t fp_mul(const fp_t& a, const fp_t& b) { return fe_mul<FpParams>(a, b); }
-TC_HD fp_t fp_sqr(const fp_t& a) { return fe_sqr<FpParams>(a); }
+TC_HD fp_t fp_sqr(const fp_t& a) { return fp_mul(a, a); }
 TC_HD fp_t fp_dbl(const fp_t& a) { return fe_dbl<FpParams>(a); }
 TC_HD fp_t fp_neg(const fp_t& a) { return fe_neg<FpParams>(a); }
 TC_HD fr_t fr_add(const fr_t& a, const fr_t& b) { return fe_add<FrParams>(a, b); }
 TC_HD fr_t fr_sub(const fr_t& a, const fr_t& b) { return fe_sub<FrParams>(a, b); }
-TC_HD fr_t fr_mul(const fr_t& a, const fr_t& b) { return fe_mul<FrParams>(a, b); }
 TC_HD fr_t fr_neg(const fr_t& a) { return fe_neg<FrParams>(a); }
 
 }  // namespace tc

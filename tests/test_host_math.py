@@ -56,6 +56,14 @@ def test_fp_fr_arithmetic(hm):
         out = (ctypes.c_uint8 * 48)()
         hm.hm_fp_inv(_b(a, 48), out)
         assert int.from_bytes(bytes(out), "little") * a % P == 1
+    for a in (1, 2, 3, P - 1, P - 2, (P - 1) // 2, 1 << 380, rng.randrange(1, P), rng.randrange(1, P)):
+        out = (ctypes.c_uint8 * 48)()
+        hm.hm_fp_inv_binary(_b(a, 48), out)
+        assert int.from_bytes(bytes(out), "little") == pow(a, -1, P)
+    for a in (1, 2, R - 1, 1 << 254, rng.randrange(1, R), rng.randrange(1, R)):
+        out = (ctypes.c_uint8 * 32)()
+        hm.hm_fr_inv_binary(_b(a, 32), out)
+        assert int.from_bytes(bytes(out), "little") == pow(a, -1, R)
     for v in (0, 1, -1, 127, -128, 32767, -32768, 2**31 - 1, -(2**31)):
         out = (ctypes.c_uint8 * 32)()
         hm.hm_fr_from_i32(ctypes.c_int32(v), out)
