@@ -72,6 +72,16 @@ const char* tc_last_error(const tc_ctx* ctx);
 /* Blocks until all work enqueued by this context has finished. */
 int tc_ctx_sync(tc_ctx* ctx);
 
+/* Measurement hooks (for benchmarks; not part of the method).  With profiling enabled the
+ * library brackets every launch of the selected kernel class with HIP events on the context's
+ * stream; tc_ctx_profile_read synchronises, returns the summed duration and launch count since
+ * the last read, and resets them. */
+#define TC_PROF_BUCKET_ACC 0 /* bucket accumulation of tc_commit: one mixed addition per non-zero entry */
+#define TC_PROF_NODE_COMMIT 1 /* bottom-level node commitments of an entries tree */
+#define TC_PROF_KINDS 2
+int tc_ctx_profile(tc_ctx* ctx, int enable);
+int tc_ctx_profile_read(tc_ctx* ctx, int kind, double* total_ms, uint64_t* launches);
+
 /* ---- Setup (Def. 4.1, Setup) -- test-only trusted setup from a known trapdoor -- */
 
 #define TC_SRS_SUFFIX 1u     /* also build the suffix tables S^(a), a = 1..m-1, needed by tc_open */

@@ -12,6 +12,7 @@ TC_ERR_ARG, TC_ERR_SHAPE, TC_ERR_RANGE, TC_ERR_NOMEM, TC_ERR_HIP, TC_ERR_VERIFY,
 TC_I8, TC_I16, TC_FR, TC_F16 = 1, 2, 3, 4
 TC_SRS_SUFFIX, TC_SRS_FIXED_BASE = 1, 2
 TC_LEAF_ENTRIES, TC_LEAF_TENSORS = 0, 1
+TC_PROF_BUCKET_ACC, TC_PROF_NODE_COMMIT = 0, 1
 TC_MAX_ORDER, TC_MAX_STEPS = 4, 16
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -72,6 +73,9 @@ def load_library(path=None):
         "tc_ctx_destroy": (None, [vp]),
         "tc_last_error": (ctypes.c_char_p, [vp]),
         "tc_ctx_sync": (ctypes.c_int, [vp]),
+        "tc_ctx_profile": (ctypes.c_int, [vp, ctypes.c_int]),
+        "tc_ctx_profile_read": (ctypes.c_int, [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
+                                               ctypes.POINTER(ctypes.c_uint64)]),
         "tc_setup_from_trapdoor": (ctypes.c_int, [vp, u8p, ctypes.c_int, u32p, ctypes.c_uint32, ctypes.POINTER(vp)]),
         "tc_srs_destroy": (None, [vp]),
         "tc_srs_size": (ctypes.c_uint64, [vp, ctypes.c_int]),
@@ -218,6 +222,14 @@ class Context:
 
     def sync(self):
         self._check(self.lib.tc_ctx_sync(self.handle))
+
+    def profile(self, enable=True):
+        self._check(self.lib.tc_ctx_profile(self.handle, 1 if enable else 0))
+
+    def profile_read(self, kind):
+        ms, n = ctypes.c_double(), ctypes.c_uint64()
+        self._check(self.lib.tc_ctx_profile_read(self.handle, kind, ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, int(n.value)
 
     def close(self):
         for vk in self._vk.values():

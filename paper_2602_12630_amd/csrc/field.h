@@ -63,9 +63,53 @@ TC_HD bool fe_eq(const Fe<P>& a, const Fe<P>& b) {
     return o == 0;
 }
 
+#if defined(__HIP_DEVICE_COMPILE__)
+/* Carry chains on the device: one VALU instruction per limb, the carry / borrow travelling in
+ * an SGPR pair that is an explicit operand (so the compiler may schedule freely around them). */
+typedef uint64_t lanemask_t;
+__device__ __forceinline__ uint32_t add_co(uint32_t a, uint32_t b, lanemask_t& c) {
+    uint32_t r;
+    asm("v_add_co_u32_e64 %0, %1, %2, %3" : "=v"(r), "=s"(c) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ uint32_t addc_co(uint32_t a, uint32_t b, lanemask_t& c) {
+    uint32_t r;
+    asm("v_addc_co_u32_e64 %0, %1, %2, %3, %1" : "=v"(r), "+s"(c) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ uint32_t sub_co(uint32_t a, uint32_t b, lanemask_t& c) {
+    uint32_t r;
+    asm("v_sub_co_u32_e64 %0, %1, %2, %3" : "=v"(r), "=s"(c) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ uint32_t subb_co(uint32_t a, uint32_t b, lanemask_t& c) {
+    uint32_t r;
+    asm("v_subb_co_u32_e64 %0, %1, %2, %3, %1" : "=v"(r), "+s"(c) : "v"(a), "v"(b));
+    return r;
+}
+/* per lane: mask set ? x : y */
+__device__ __forceinline__ uint32_t select_mask(lanemask_t mask, uint32_t x, uint32_t y) {
+    uint32_t r;
+    asm("v_cndmask_b32_e64 %0, %1, %2, %3" : "=v"(r) : "v"(y), "v"(x), "s"(mask));
+    return r;
+}
+#endif
+
 /* r = a - MOD if a >= MOD else a, for a < 2 MOD given as limbs plus a carry bit */
 template <class P>
 TC_HD Fe<P> fe_reduce_once(const Fe<P>& a, uint32_t carry) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    /* 2 MOD < 2^(32 N) for both fields, so callers never pass a set carry */
+    (void)carry;
+    Fe<P> dd, rr;
+    lanemask_t bw;
+    dd.l[0] = sub_co(a.l[0], P::MOD[0], bw);
+#pragma unroll
+    for (int i = 1; i < P::N; ++i) dd.l[i] = subb_co(a.l[i], P::MOD[i], bw);
+#pragma unroll
+    for (int i = 0; i < P::N; ++i) rr.l[i] = select_mask(bw, a.l[i], dd.l[i]);   /* borrow: keep a */
+    return rr;
+#endif
     Fe<P> d;
     uint32_t borrow = 0;
 #pragma unroll
@@ -84,6 +128,16 @@ TC_HD Fe<P> fe_reduce_once(const Fe<P>& a, uint32_t carry) {
 
 template <class P>
 TC_HD Fe<P> fe_add(const Fe<P>& a, const Fe<P>& b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    {
+        Fe<P> t;
+        lanemask_t cy;
+        t.l[0] = add_co(a.l[0], b.l[0], cy);
+#pragma unroll
+        for (int i = 1; i < P::N; ++i) t.l[i] = addc_co(a.l[i], b.l[i], cy);
+        return fe_reduce_once<P>(t, 0);
+    }
+#endif
     Fe<P> s;
     uint32_t c = 0;
 #pragma unroll
@@ -97,6 +151,21 @@ TC_HD Fe<P> fe_add(const Fe<P>& a, const Fe<P>& b) {
 
 template <class P>
 TC_HD Fe<P> fe_sub(const Fe<P>& a, const Fe<P>& b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    {
+        Fe<P> t, u;
+        lanemask_t bw, cy;
+        t.l[0] = sub_co(a.l[0], b.l[0], bw);
+#pragma unroll
+        for (int i = 1; i < P::N; ++i) t.l[i] = subb_co(a.l[i], b.l[i], bw);
+        u.l[0] = add_co(t.l[0], P::MOD[0], cy);
+#pragma unroll
+        for (int i = 1; i < P::N; ++i) u.l[i] = addc_co(t.l[i], P::MOD[i], cy);
+#pragma unroll
+        for (int i = 0; i < P::N; ++i) u.l[i] = select_mask(bw, u.l[i], t.l[i]);   /* borrow: take t + MOD */
+        return u;
+    }
+#endif
     Fe<P> d;
     uint32_t borrow = 0;
 #pragma unroll
@@ -348,6 +417,62 @@ TC_HD Fe<P> fe_inv(const Fe<P>& x) {
 #pragma unroll
     for (int i = 0; i < N; ++i) { a[i] = x.l[i]; b[i] = P::MOD[i]; u[i] = 0; v[i] = 0; }
     u[0] = 1;
+#if defined(__HIP_DEVICE_COMPILE__)
+    for (int it = 0; it < 64 * N; ++it) {
+        /* lanes where a is odd and a < b exchange (a, u) with (b, v) */
+        lanemask_t lt, odd;
+        (void)sub_co(a[0], b[0], lt);
+#pragma unroll
+        for (int i = 1; i < N; ++i) (void)subb_co(a[i], b[i], lt);
+        asm("v_cmp_ne_u32_e64 %0, 0, %1" : "=s"(odd) : "v"(a[0] & 1u));
+        lanemask_t swap = lt & odd;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            uint32_t na = select_mask(swap, b[i], a[i]);
+            b[i] = select_mask(swap, a[i], b[i]);
+            a[i] = na;
+            uint32_t nu = select_mask(swap, v[i], u[i]);
+            v[i] = select_mask(swap, u[i], v[i]);
+            u[i] = nu;
+        }
+        /* odd lanes: a -= b (no borrow now), u = u - v mod q */
+        uint32_t d[N], w[N], w2[N];
+        lanemask_t bw, bu, cy;
+        d[0] = sub_co(a[0], b[0], bw);
+#pragma unroll
+        for (int i = 1; i < N; ++i) d[i] = subb_co(a[i], b[i], bw);
+        w[0] = sub_co(u[0], v[0], bu);
+#pragma unroll
+        for (int i = 1; i < N; ++i) w[i] = subb_co(u[i], v[i], bu);
+        w2[0] = add_co(w[0], P::MOD[0], cy);
+#pragma unroll
+        for (int i = 1; i < N; ++i) w2[i] = addc_co(w[i], P::MOD[i], cy);
+        lanemask_t fix = bu & odd;          /* take w + q */
+        lanemask_t plain = odd & ~bu;       /* take w */
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            a[i] = select_mask(odd, d[i], a[i]);
+            u[i] = select_mask(fix, w2[i], select_mask(plain, w[i], u[i]));
+        }
+        /* halve a; halve u modulo q */
+        lanemask_t uodd;
+        asm("v_cmp_ne_u32_e64 %0, 0, %1" : "=s"(uodd) : "v"(u[0] & 1u));
+        uint32_t h[N];
+        h[0] = add_co(u[0], P::MOD[0], cy);
+#pragma unroll
+        for (int i = 1; i < N; ++i) h[i] = addc_co(u[i], P::MOD[i], cy);
+        uint32_t top = select_mask(cy & uodd, 1u, 0u);
+#pragma unroll
+        for (int i = 0; i < N; ++i) u[i] = select_mask(uodd, h[i], u[i]);
+#pragma unroll
+        for (int i = 0; i < N - 1; ++i) {
+            a[i] = __builtin_amdgcn_alignbit(a[i + 1], a[i], 1);
+            u[i] = __builtin_amdgcn_alignbit(u[i + 1], u[i], 1);
+        }
+        a[N - 1] >>= 1;
+        u[N - 1] = __builtin_amdgcn_alignbit(top, u[N - 1], 1);
+    }
+#else
     for (int it = 0; it < 64 * N; ++it) {
         uint32_t odd = 0u - (a[0] & 1u);
         /* borrow of a - b */
@@ -402,6 +527,7 @@ TC_HD Fe<P> fe_inv(const Fe<P>& x) {
         a[N - 1] >>= 1;
         u[N - 1] = (u[N - 1] >> 1) | (c << 31);
     }
+#endif
     Fe<P> r, r3;
 #pragma unroll
     for (int i = 0; i < N; ++i) { r.l[i] = v[i]; r3.l[i] = P::R3[i]; }

@@ -30,6 +30,11 @@ inline int memcpy_d2d(void* d, const void* s, size_t n, stream_t) { memmove(d, s
 inline int memset_async(void* d, int v, size_t n, stream_t) { memset(d, v, n); return 0; }
 inline int stream_sync(stream_t) { return 0; }
 inline int set_device(int) { return 0; }
+typedef void* event_t;
+inline int event_create(event_t* e) { *e = nullptr; return 0; }
+inline int event_record(event_t, stream_t) { return 0; }
+inline int event_elapsed_ms(event_t, event_t, float* ms) { *ms = 0.0f; return 0; }
+inline void event_destroy(event_t) {}
 inline int last_error() { return 0; }
 inline const char* error_string(int) { return "host emulation"; }
 template <int BLOCK, class F>
@@ -65,6 +70,14 @@ inline int memcpy_d2d(void* d, const void* s, size_t n, stream_t st) { return (i
 inline int memset_async(void* d, int v, size_t n, stream_t st) { return (int)hipMemsetAsync(d, v, n, st); }
 inline int stream_sync(stream_t st) { return (int)hipStreamSynchronize(st); }
 inline int set_device(int dev) { return (int)hipSetDevice(dev); }
+typedef hipEvent_t event_t;
+inline int event_create(event_t* e) { return (int)hipEventCreate(e); }
+inline int event_record(event_t e, stream_t st) { return (int)hipEventRecord(e, st); }
+inline int event_elapsed_ms(event_t a, event_t b, float* ms) {
+    int e = (int)hipEventSynchronize(b);
+    return e ? e : (int)hipEventElapsedTime(ms, a, b);
+}
+inline void event_destroy(event_t e) { hipEventDestroy(e); }
 inline int last_error() { return (int)hipGetLastError(); }
 inline const char* error_string(int e) { return hipGetErrorString((hipError_t)e); }
 template <int BLOCK, class F>

@@ -31,6 +31,8 @@ struct tc_ctx {
     std::string err;
     Arena ws;
     g1_affine* gtable = nullptr;       /* fixed-base table of the generator */
+    bool profiling = false;
+    std::vector<std::pair<rt::event_t, rt::event_t>> prof[TC_PROF_KINDS];
 };
 
 struct tc_srs {
@@ -211,7 +213,45 @@ extern "C" void tc_ctx_destroy(tc_ctx* ctx) {
     for (void* p : ctx->ws.extra) rt::dev_free(p);
     if (ctx->ws.base) rt::dev_free(ctx->ws.base);
     if (ctx->gtable) rt::dev_free(ctx->gtable);
+    for (auto& v : ctx->prof)
+        for (auto& pr : v) { rt::event_destroy(pr.first); rt::event_destroy(pr.second); }
     delete ctx;
+}
+/* measurement hooks */
+static void prof_begin(tc_ctx* ctx, int kind, rt::event_t* a, rt::event_t* b) {
+    *a = *b = nullptr;
+    if (!ctx->profiling) return;
+    if (rt::event_create(a) || rt::event_create(b)) return;
+    rt::event_record(*a, ctx->stream);
+    (void)kind;
+}
+static void prof_end(tc_ctx* ctx, int kind, rt::event_t a, rt::event_t b) {
+    if (!ctx->profiling || !a || !b) return;
+    rt::event_record(b, ctx->stream);
+    ctx->prof[kind].push_back({a, b});
+}
+extern "C" int tc_ctx_profile(tc_ctx* ctx, int enable) {
+    if (!ctx) return TC_ERR_ARG;
+    ctx->profiling = enable != 0;
+    return TC_OK;
+}
+extern "C" int tc_ctx_profile_read(tc_ctx* ctx, int kind, double* total_ms, uint64_t* launches) {
+    if (!ctx) return TC_ERR_ARG;
+    if (kind < 0 || kind >= TC_PROF_KINDS || !total_ms || !launches) return fail(ctx, TC_ERR_ARG, "bad argument");
+    RT(rt::set_device(ctx->device));
+    RT(rt::stream_sync(ctx->stream));
+    double tot = 0;
+    for (auto& pr : ctx->prof[kind]) {
+        float ms = 0;
+        RT(rt::event_elapsed_ms(pr.first, pr.second, &ms));
+        tot += ms;
+        rt::event_destroy(pr.first);
+        rt::event_destroy(pr.second);
+    }
+    *total_ms = tot;
+    *launches = ctx->prof[kind].size();
+    ctx->prof[kind].clear();
+    return TC_OK;
 }
 extern "C" const char* tc_last_error(const tc_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 extern "C" int tc_ctx_sync(tc_ctx* ctx) {
@@ -583,7 +623,12 @@ static int msm_engine(tc_ctx* ctx, const g1_affine* pts, const void* d_scalars, 
     WS(bufB, g1_xyzz, max_part / L2 + nbk + 1);
     WS(bucket, g1_xyzz, nbk);
     WS(wsum, g1_xyzz, (uint32_t)W);
-    RT(rt::launch<64>(max_part, ctx->stream, AccAffine{pts, sorted, start, lstart, nbk, L1, bufA}));
+    {
+        rt::event_t e0, e1;
+        prof_begin(ctx, TC_PROF_BUCKET_ACC, &e0, &e1);
+        RT(rt::launch<64>(max_part, ctx->stream, AccAffine{pts, sorted, start, lstart, nbk, L1, bufA}));
+        prof_end(ctx, TC_PROF_BUCKET_ACC, e0, e1);
+    }
 
     /* worst case: every item in one bucket.  Middle passes shrink the per-bucket partial count
      * by L2 until at most L2 remain; the plan is fixed on the host from the sizes alone. */
@@ -926,7 +971,10 @@ extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** 
                 if (use_fb) {
                     int e;
                     if (bottom) {
+                        rt::event_t e0, e1;
+                        prof_begin(ctx, TC_PROF_NODE_COMMIT, &e0, &e1);
                         e = rt::launch<64>(lv.n, ctx->stream, NodeCommitSmall{g, t->d_payload, t->dtype, ns->fb[0], acc});
+                        prof_end(ctx, TC_PROF_NODE_COMMIT, e0, e1);
                     } else {
                         g1_xyzz* part = ws_array<g1_xyzz>(ctx, lv.n * t->B);
                         if (!part) { rc = fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed"); break; }
