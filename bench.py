@@ -106,6 +106,44 @@ def cpu_baseline(q, budget_s=12.0):
     }
 
 
+def c3_forward(ctx, T, torch, node_srs, tau, reps=3):
+    """Second half of the metric: Terkle build per LLaMA2-7B-shaped forward pass (32 layers x
+    {512x4096, 512x4096, 512x11008} fp16 N(0,1) activations as whole-tensor leaves, (4,4) tree over
+    the (32, 3) grid).  Timed: quantisation of all 96 tensors + 96 leaf commitments + upper levels."""
+    cfg = tc_inputs.LLAMA7B
+    shapes3 = tc_inputs.c3_shapes(cfg)
+    srs_by_shape = {s: ctx.setup_from_trapdoor(tau, s, 0) for s in set(shapes3)}
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(tc_inputs.tensor_seed(2))
+    xs, qs, invs, leaf_srs = [], [], [], []
+    for layer in range(cfg["layers"]):
+        for s in shapes3:
+            x = torch.randn(s[0] * s[1], generator=gen, device="cuda", dtype=torch.float32).to(torch.float16)
+            xs.append(x)
+            qs.append(torch.empty(x.numel(), dtype=torch.int16, device="cuda"))
+            invs.append(float(np.float32(32767.0) / np.float32(x.abs().max().item())))
+            leaf_srs.append(srs_by_shape[s])
+    total = sum(x.numel() for x in xs)
+    torch.cuda.synchronize()
+    times = []
+    for rep in range(reps + 1):
+        t0 = time.perf_counter()
+        for x, qv, inv in zip(xs, qs, invs):
+            ctx.encode_tensor(x, T.TC_F16, x.numel(), inv, qv)
+        tree = ctx.terkle_build_tensors(node_srs, leaf_srs, qs, [T.TC_I16] * len(qs), (cfg["layers"], 3), tc_inputs.NODE_SHAPE)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        tree.close()
+        if rep:
+            times.append(dt * 1e3)
+    for s in srs_by_shape.values():
+        s.close()
+    times.sort()
+    ms = times[len(times) // 2]
+    return {"ms": ms, "elements": total, "elements_per_s": total / (ms * 1e-3), "tensors": len(xs), "reps": reps,
+            "workload": "C3: 96 whole-tensor leaves (314 572 800 int16 entries) + 11 upper nodes"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -114,6 +152,7 @@ def main():
     ap.add_argument("--lib", default=None, help="path of an alternative libtc.so (experiments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--openings", type=int, default=8)
+    ap.add_argument("--no-c3", action="store_true", help="skip the LLaMA2-7B-shaped forward (second half of the metric)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -227,6 +266,8 @@ def main():
                      "launches": acc_launches, "mixed_additions_per_launch": nonzero,
                      "node_commit_kernel_ms": node_ms / max(node_launches, 1)},
     }
+    if not args.no_c3:
+        out["terkle_build_llama2_7b_fwd"] = c3_forward(ctx, T, torch, node_srs, tau)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(q)
     print(json.dumps(out))

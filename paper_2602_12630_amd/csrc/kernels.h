@@ -236,7 +236,8 @@ TC_HD uint32_t find_segment(const uint32_t* prefix, uint32_t n, uint32_t t) {
 /* Lane t owns sub-run `t - lstart[b]` of bucket b: at most L entries, all of one bucket.
  * Output slot t, so the partial sums of bucket b are the slots lstart[b] .. lstart[b+1]. */
 struct AccAffine {
-    const g1_affine* pts;
+    const g1_affine* const* tables;   /* SRS table of problem p; bucket b belongs to problem b / nbk_pp */
+    uint32_t nbk_pp;
     const uint32_t* sorted;
     const uint32_t* start;
     const uint32_t* lstart;
@@ -247,6 +248,7 @@ struct AccAffine {
         uint32_t b = find_segment(lstart, nbk, t);
         uint32_t begin = start[b] + (t - lstart[b]) * L;
         uint32_t end = begin + L < start[b + 1] ? begin + L : start[b + 1];
+        const g1_affine* pts = tables[b / nbk_pp];
         g1_xyzz acc = xyzz_identity();
         for (uint32_t i = begin; i < end; ++i) {
             uint32_t e = sorted[i];
@@ -347,18 +349,19 @@ struct WindowFinish {
         out[w] = xyzz_add(t, w1[w]);
     }
 };
-/* One lane: Horner over windows, result = sum_w 2^(c w) Wsum_w */
+/* One lane per problem: Horner over its windows, result = sum_w 2^(c w) Wsum_w */
 struct WindowCombine {
     const g1_xyzz* wsum;
     int W, c;
     g1_xyzz* out;
-    TC_DEV void operator()(uint32_t) const {
-        g1_xyzz acc = wsum[W - 1];
+    TC_DEV void operator()(uint32_t p) const {
+        const g1_xyzz* ws = wsum + (uint64_t)p * W;
+        g1_xyzz acc = ws[W - 1];
         for (int w = W - 2; w >= 0; --w) {
             for (int i = 0; i < c; ++i) acc = xyzz_dbl(acc);
-            acc = xyzz_add(acc, wsum[w]);
+            acc = xyzz_add(acc, ws[w]);
         }
-        out[0] = acc;
+        out[p] = acc;
     }
 };
 

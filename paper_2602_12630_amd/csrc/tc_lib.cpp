@@ -586,16 +586,31 @@ static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb
     return TC_OK;
 }
 
-/* result[0] = sum_i [e(s_i)] pts[i] */
-static int msm_engine(tc_ctx* ctx, const g1_affine* pts, const void* d_scalars, int dtype, uint64_t n, g1_xyzz* result) {
-    int W, c;
-    if (dtype == TC_I8) { W = 1; c = 8; }
-    else if (dtype == TC_I16) { W = 1; c = 16; }
-    else { c = n >= 32768 ? 16 : 8; W = 256 / c; }
+/* One MSM problem: result = sum_i [e(s_i)] pts[i] over n terms */
+struct MsmProblem {
+    const g1_affine* pts;
+    const void* scalars;
+    uint64_t n;
+};
+static void msm_config(int dtype, uint64_t n, int* W, int* c) {
+    if (dtype == TC_I8) { *W = 1; *c = 8; }
+    else if (dtype == TC_I16) { *W = 1; *c = 16; }
+    else { *c = n >= 32768 ? 16 : 8; *W = 256 / *c; }
+}
+/* `count` problems of one scalar type and window plan, run through shared launches: the buckets of
+ * problem p are the keys p * nbk .. (p + 1) * nbk of one big bucket space, so every pass (prefix
+ * sums, balanced bucket sums, bucket reduction, window combination) is one launch for all problems. */
+static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int dtype, int W, int c, g1_xyzz* results) {
     uint32_t nb = 1u << (c - 1);
-    uint32_t nbk = (uint32_t)W * nb;
-    uint64_t items = n * (uint64_t)W;
-    if (items > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "MSM too large");
+    uint32_t nbk_pp = (uint32_t)W * nb;
+    uint64_t items = 0, max_items = 0;
+    for (int p = 0; p < count; ++p) {
+        items += prob[p].n * (uint64_t)W;
+        max_items = std::max<uint64_t>(max_items, prob[p].n * (uint64_t)W);
+    }
+    uint64_t nbk64 = (uint64_t)nbk_pp * (uint64_t)count;
+    if (items > 0xFFFFFFF0ull || nbk64 > 0x7FFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "MSM batch too large");
+    uint32_t nbk = (uint32_t)nbk64;
     uint32_t nchunks = (nbk + SCAN_CHUNK - 1) / SCAN_CHUNK;
 
     WS(cnt, uint32_t, nbk);
@@ -606,7 +621,10 @@ static int msm_engine(tc_ctx* ctx, const g1_affine* pts, const void* d_scalars, 
     WS(tot_a, uint32_t, nchunks + 1);
     WS(tot_b, uint32_t, nchunks + 1);
     WS(sorted, uint32_t, items ? items : 1);
-    WS(maxcnt, uint32_t, 1);
+    WS(tables, const g1_affine*, (uint32_t)count);
+    std::vector<const g1_affine*> h_tables(count);
+    for (int p = 0; p < count; ++p) h_tables[p] = prob[p].pts;
+    RT(rt::memcpy_h2d(tables, h_tables.data(), sizeof(void*) * (size_t)count, ctx->stream));
 
     /* lanes of the first pass: enough sub-runs to fill the machine, at most 64 entries each */
     const uint64_t target_lanes = 262144;
@@ -614,25 +632,28 @@ static int msm_engine(tc_ctx* ctx, const g1_affine* pts, const void* d_scalars, 
     const uint32_t L2 = 16;
 
     RT(rt::launch<256>(nbk, ctx->stream, Fill32{cnt, 0u}));
-    RT(rt::launch<256>(n, ctx->stream, MsmCount{d_scalars, dtype, W, c, nb, cnt}));
+    for (int p = 0; p < count; ++p)
+        RT(rt::launch<256>(prob[p].n, ctx->stream, MsmCount{prob[p].scalars, dtype, W, c, nb, cnt + (size_t)p * nbk_pp}));
     TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, cursor, tot_a, tot_b));
-    RT(rt::launch<256>(n, ctx->stream, MsmScatter{d_scalars, dtype, W, c, nb, start, cursor, sorted}));
+    for (int p = 0; p < count; ++p)
+        RT(rt::launch<256>(prob[p].n, ctx->stream,
+                           MsmScatter{prob[p].scalars, dtype, W, c, nb, start + (size_t)p * nbk_pp, cursor + (size_t)p * nbk_pp, sorted}));
 
     uint64_t max_part = items / L1 + nbk + 1;          /* upper bound on first-pass lanes */
     WS(bufA, g1_xyzz, max_part);
     WS(bufB, g1_xyzz, max_part / L2 + nbk + 1);
     WS(bucket, g1_xyzz, nbk);
-    WS(wsum, g1_xyzz, (uint32_t)W);
+    WS(wsum, g1_xyzz, (uint64_t)W * count);
     {
         rt::event_t e0, e1;
         prof_begin(ctx, TC_PROF_BUCKET_ACC, &e0, &e1);
-        RT(rt::launch<64>(max_part, ctx->stream, AccAffine{pts, sorted, start, lstart, nbk, L1, bufA}));
+        RT(rt::launch<64>(max_part, ctx->stream, AccAffine{tables, nbk_pp, sorted, start, lstart, nbk, L1, bufA}));
         prof_end(ctx, TC_PROF_BUCKET_ACC, e0, e1);
     }
 
-    /* worst case: every item in one bucket.  Middle passes shrink the per-bucket partial count
-     * by L2 until at most L2 remain; the plan is fixed on the host from the sizes alone. */
-    uint64_t worst = (items + L1 - 1) / L1;
+    /* worst case: every item of a problem in one bucket.  Middle passes shrink the per-bucket
+     * partial count by L2 until at most L2 remain; the plan is fixed on the host from the sizes alone. */
+    uint64_t worst = (max_items + L1 - 1) / L1;
     g1_xyzz *cur = bufA, *nxt = bufB;
     uint32_t *cur_start = lstart, *nxt_start = lstart2;
     uint64_t lanes_bound = max_part;
@@ -648,11 +669,46 @@ static int msm_engine(tc_ctx* ctx, const g1_affine* pts, const void* d_scalars, 
         worst = (worst + L2 - 1) / L2;
     }
     RT(rt::launch<64>(nbk, ctx->stream, AccFinal{cur, cur_start, bucket}));
-    (void)maxcnt;
 
-    if (nb == 128) TRY(reduce_windows<128>(ctx, bucket, W, nb, wsum));
-    else TRY(reduce_windows<256>(ctx, bucket, W, nb, wsum));
-    RT(rt::launch<64>(1, ctx->stream, WindowCombine{wsum, W, c, result}));
+    if (nb == 128) TRY(reduce_windows<128>(ctx, bucket, W * count, nb, wsum));
+    else TRY(reduce_windows<256>(ctx, bucket, W * count, nb, wsum));
+    RT(rt::launch<64>((uint32_t)count, ctx->stream, WindowCombine{wsum, W, c, results}));
+    return TC_OK;
+}
+
+/* result[0] = sum_i [e(s_i)] pts[i] */
+static int msm_engine(tc_ctx* ctx, const g1_affine* pts, const void* d_scalars, int dtype, uint64_t n, g1_xyzz* result) {
+    int W, c;
+    msm_config(dtype, n, &W, &c);
+    MsmProblem one{pts, d_scalars, n};
+    return msm_engine_multi(ctx, 1, &one, dtype, W, c, result);
+}
+
+/* any list of problems: consecutive problems with the same scalar type and window plan share launches,
+ * up to a bound on the batch size (the sorted index array is 4 bytes per term) */
+static int msm_engine_list(tc_ctx* ctx, int count, const MsmProblem* prob, const int* dtype, g1_xyzz* results) {
+    const uint64_t max_batch_items = 1ull << 30;
+    const uint64_t max_batch_buckets = 1ull << 26;
+    int i = 0;
+    while (i < count) {
+        int W, c;
+        msm_config(dtype[i], prob[i].n, &W, &c);
+        uint64_t items = prob[i].n * (uint64_t)W, buckets = (uint64_t)W << (c - 1);
+        int j = i + 1;
+        while (j < count) {
+            int W2, c2;
+            msm_config(dtype[j], prob[j].n, &W2, &c2);
+            if (dtype[j] != dtype[i] || W2 != W || c2 != c) break;
+            if (items + prob[j].n * (uint64_t)W > max_batch_items || buckets + ((uint64_t)W << (c - 1)) > max_batch_buckets) break;
+            items += prob[j].n * (uint64_t)W;
+            buckets += (uint64_t)W << (c - 1);
+            ++j;
+        }
+        size_t mark = ctx->ws.off;
+        TRY(msm_engine_multi(ctx, j - i, prob + i, dtype[i], W, c, results + i));
+        ctx->ws.off = mark;            /* scratch is reusable by the next batch: the stream orders the kernels */
+        i = j;
+    }
     return TC_OK;
 }
 
@@ -672,12 +728,9 @@ extern "C" int tc_commit_batch(tc_ctx* ctx, int count, const tc_srs* const* srs,
     RT(rt::set_device(ctx->device));
     TRY(ws_reset(ctx));
     WS(results, g1_xyzz, (uint32_t)count);
-    for (int i = 0; i < count; ++i) {
-        size_t mark_off = ctx->ws.off;
-        TRY(msm_engine(ctx, srs[i]->pts[0], d_scalars[i], dtype[i], srs[i]->n[0], results + i));
-        /* engine scratch is reusable by the next MSM: the stream orders the kernels */
-        ctx->ws.off = mark_off;
-    }
+    std::vector<MsmProblem> prob(count);
+    for (int i = 0; i < count; ++i) prob[i] = MsmProblem{srs[i]->pts[0], d_scalars[i], srs[i]->n[0]};
+    TRY(msm_engine_list(ctx, count, prob.data(), dtype, results));
     return points_to_host(ctx, results, (uint32_t)count, out_g1);
 }
 extern "C" int tc_commit(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, int dtype, uint8_t out_g1[96]) {
@@ -959,11 +1012,9 @@ extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** 
             g1_xyzz* acc = ws_array<g1_xyzz>(ctx, lv.n);
             if (!acc) { rc = fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed"); break; }
             if (L == 0 && t->leaf_kind == TC_LEAF_TENSORS) {
-                for (uint64_t i = 0; i < lv.n && rc == TC_OK; ++i) {
-                    size_t mk = ctx->ws.off;
-                    rc = msm_engine(ctx, t->leaf_srs[i]->pts[0], t->leaf_scalars[i], t->leaf_dtype[i], t->leaf_srs[i]->n[0], acc + i);
-                    ctx->ws.off = mk;
-                }
+                std::vector<MsmProblem> prob(lv.n);
+                for (uint64_t i = 0; i < lv.n; ++i) prob[i] = MsmProblem{t->leaf_srs[i]->pts[0], t->leaf_scalars[i], t->leaf_srs[i]->n[0]};
+                rc = msm_engine_list(ctx, (int)lv.n, prob.data(), t->leaf_dtype.data(), acc);
             } else {
                 const uint32_t* below = L == 0 ? t->grid : t->levels[L - 1].grid;
                 TreeGeom g = make_geom(t, below, lv.grid);

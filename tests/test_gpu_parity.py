@@ -293,3 +293,124 @@ def test_c2_activation_commit(T, ctx):
             assert srs.point(f) == ec.g1_to_bytes(want_pt)
     finally:
         srs.close()
+
+
+def test_c2_tree_sampled_nodes_and_paths(T, ctx, node_srs):
+    """Config 2, tree form at full size: (4,4) tree over the 2^21 quantised entries, 139 813 nodes.
+    The oracle recomputes sampled nodes of the three lowest levels from the payload alone, checks
+    level sizes, and its own verifier accepts the GPU's membership proofs against the GPU's root."""
+    import torch
+
+    shape, node = tc_inputs.C2_SHAPE, tc_inputs.NODE_SHAPE
+    x = tc_inputs.c2_activation()
+    q = quantize.quantize_f16(x, quantize.inv_scale_for(x))
+    dq = to_device(q)
+    tree = ctx.terkle_build_entries(node_srs, dq, T.TC_I16, shape, node)
+    try:
+        assert tree.levels == 6
+        assert [tree.level_info(L)[1] for L in range(6)] == [131072, 8192, 512, 32, 4, 1]
+        ppn = pps(node)
+        rng = np.random.default_rng(5)
+
+        def oracle_node(level, a):
+            """commitment of node `a` (multi-index) at `level`, from payload entries only"""
+            if level == 0:
+                block = q[4 * a[0] : 4 * a[0] + 4, 4 * a[1] : 4 * a[1] + 4]
+                return tc.commit(ppn, block)
+            Z = [terkle.phi(oracle_node(level - 1, (4 * a[0] + k // 4, 4 * a[1] + k % 4))) for k in range(16)]
+            return tc.commit(ppn, Z)
+
+        for level, count in ((0, 6), (1, 3), (2, 1)):
+            grid, _ = tree.level_info(level)
+            for _ in range(count):
+                a = (int(rng.integers(0, grid[0])), int(rng.integers(0, grid[1])))
+                assert tree.node(level, a[0] * grid[1] + a[1]) == ec.g1_to_bytes(oracle_node(level, a))
+        # membership proofs: accepted by the oracle's verifier and by the library, rejected when tampered
+        leaves = tc_inputs.opening_positions(shape, 8, tc_inputs.tensor_seed(1))
+        proofs = tree.open_batch(leaves)
+        vk = ctx.vk_from_trapdoor(TAU_BYTES)
+        root = ec.g1_from_bytes(tree.root)
+        for leaf, proof in zip(leaves, proofs):
+            assert len(proof) == 6 * (2 * 96 + 32) + 5 * 96
+            steps, off = [], 0
+            path = tree.path(leaf)
+            for s in range(6):
+                pi = [ec.g1_from_bytes(proof[off + 96 * i : off + 96 * (i + 1)]) for i in range(2)]
+                off += 192
+                y = ec.fr_from_bytes(proof[off : off + 32])
+                off += 32
+                child = None
+                if s < 5:
+                    child = ec.g1_from_bytes(proof[off : off + 96])
+                    off += 96
+                steps.append((tuple(path.kappa[s][j] for j in range(2)), y, pi, child))
+            assert terkle.verify_path(pps, root, [node] * 6, int(q[leaf]), steps)
+            assert not terkle.verify_path(pps, root, [node] * 6, int(q[leaf]) + 1, steps)
+        vals = [ec.fr_to_bytes(int(q[l]) % R) for l in leaves]
+        assert ctx.verify_paths_batch(vk, [tree.path(l) for l in leaves], [tree.root] * 8, vals, proofs) == [True] * 8
+    finally:
+        tree.close()
+
+
+@pytest.mark.slow
+def test_c3_llama7b_forward_leaf_commitments_and_tree(T, ctx, node_srs):
+    """Config 3: 32 layers x {512x4096, 512x4096, 512x11008} int16 tensors as whole-tensor leaves,
+    (4,4) tree over the (32, 3) grid.  Every leaf commitment is compared with the oracle's closed
+    form (field sums in C), the upper tree with the oracle's recursive build over those commitments,
+    and sampled openings with the oracle's openings."""
+    import torch
+
+    cfg = tc_inputs.LLAMA7B
+    shapes3 = tc_inputs.c3_shapes(cfg)
+    layers = int(os.environ.get("TC_TEST_C3_LAYERS", cfg["layers"]))
+    grid = (layers, 3)
+    srs_by_shape = {}
+    for s in set(shapes3):
+        srs_by_shape[s] = ctx.setup_from_trapdoor(TAU_BYTES, s, T.TC_SRS_SUFFIX)
+    leaves_q, leaves_d, leaf_srs, leaf_shapes = [], [], [], []
+    want_commit = []
+    for layer in range(layers):
+        for kind, s in enumerate(shapes3):
+            x = tc_inputs.f16_normal(s, tc_inputs.tensor_seed(2, 0, layer, kind))
+            inv = quantize.inv_scale_for(x)
+            qv = quantize.quantize_f16(x, inv)
+            dq = torch.empty(x.size, dtype=torch.int16, device="cuda")
+            ctx.encode_tensor(to_device(x.view(np.int16)), T.TC_F16, x.size, float(inv), dq)
+            leaves_q.append(qv)
+            leaves_d.append(dq)
+            leaf_srs.append(srs_by_shape[s])
+            leaf_shapes.append(s)
+            want_commit.append(cbind.commit(pps(s), qv, nthreads=16))
+    ctx.sync()
+    for qv, dq in zip(leaves_q[:3], leaves_d[:3]):
+        assert np.array_equal(dq.cpu().numpy(), qv.reshape(-1))
+    tree = ctx.terkle_build_tensors(node_srs, leaf_srs, leaves_d, [T.TC_I16] * len(leaves_d), grid, tc_inputs.NODE_SHAPE)
+    try:
+        for i, w in enumerate(want_commit):
+            assert tree.node(0, i) == ec.g1_to_bytes(w), "leaf %d" % i
+        # upper levels from the oracle's own leaf commitments
+        phis = [terkle.phi(w) for w in want_commit]
+        otree = terkle.build(pps, phis, grid, tc_inputs.NODE_SHAPE)
+        assert tree.levels == len(otree.levels) + 1
+        for L in range(1, tree.levels):
+            g, n = tree.level_info(L)
+            for i in range(n):
+                assert tree.node(L, i) == ec.g1_to_bytes(otree.levels[L - 1]["C"][tc.multi_index(i, g)])
+        assert tree.root == ec.g1_to_bytes(otree.root)
+        # two openings down to tensor entries
+        vk = ctx.vk_from_trapdoor(TAU_BYTES)
+        rng = np.random.default_rng(9)
+        for _ in range(2):
+            leaf = (int(rng.integers(0, layers)), int(rng.integers(0, 3)))
+            flat = leaf[0] * 3 + leaf[1]
+            inner = tuple(int(rng.integers(0, d)) for d in leaf_shapes[flat])
+            proof = tree.open(leaf, inner)
+            yo, po = tc.open_(pps(leaf_shapes[flat]), leaves_q[flat], inner)
+            tail = b"".join(ec.g1_to_bytes(p) for p in po) + ec.fr_to_bytes(yo)
+            assert proof[-len(tail):] == tail
+            value = ec.fr_to_bytes(int(leaves_q[flat][inner]) % R)
+            assert ctx.verify_path(vk, tree.path(leaf, inner), tree.root, value, proof)
+    finally:
+        tree.close()
+        for s in srs_by_shape.values():
+            s.close()
