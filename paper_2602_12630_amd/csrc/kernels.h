@@ -160,33 +160,39 @@ struct ScanChunkTotals {
     uint32_t n, L;
     uint32_t* tot_a;
     uint32_t* tot_b;
+    uint32_t* tot_max;     /* per chunk: largest count */
     TC_DEV void operator()(uint32_t ch) const {
         uint32_t lo = ch * SCAN_CHUNK, hi = lo + SCAN_CHUNK < n ? lo + SCAN_CHUNK : n;
-        uint32_t a = 0, b = 0;
+        uint32_t a = 0, b = 0, mx = 0;
         for (uint32_t i = lo; i < hi; ++i) {
             uint32_t v = cnt[i];
             a += v;
             b += (v + L - 1) / L;
+            mx = v > mx ? v : mx;
         }
         tot_a[ch] = a;
         tot_b[ch] = b;
+        tot_max[ch] = mx;
     }
 };
 struct ScanChunkOffsets {
     uint32_t nchunks;
     uint32_t* tot_a;
     uint32_t* tot_b;
+    uint32_t* tot_max;     /* in: per-chunk maxima; out: tot_max[nchunks] = overall maximum */
     TC_DEV void operator()(uint32_t) const {
-        uint32_t a = 0, b = 0;
+        uint32_t a = 0, b = 0, mx = 0;
         for (uint32_t i = 0; i < nchunks; ++i) {
             uint32_t va = tot_a[i], vb = tot_b[i];
             tot_a[i] = a;
             tot_b[i] = b;
             a += va;
             b += vb;
+            mx = tot_max[i] > mx ? tot_max[i] : mx;
         }
         tot_a[nchunks] = a;
         tot_b[nchunks] = b;
+        tot_max[nchunks] = mx;
     }
 };
 struct ScanWrite {
@@ -298,15 +304,18 @@ struct WeightedBlockSum {
     static constexpr int PHASES = 1 + LOG + 1 + LOG + 1;
     static constexpr size_t LDS_BYTES = 2 * BLOCK * sizeof(g1_xyzz);
     const g1_xyzz* in;
-    uint32_t n;                 /* entries; positions >= n count as the identity */
+    uint32_t n;                 /* entries of `in`; positions >= n count as the identity */
     g1_xyzz* out_w;             /* per block */
     g1_xyzz* out_s;             /* per block */
+    const g1_xyzz* in2;         /* optional second array: blocks split .. read in2 from position 0 */
+    uint32_t split;             /* first block that reads in2 (ignored when in2 is null) */
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         g1_xyzz* buf0 = (g1_xyzz*)lds;
         g1_xyzz* buf1 = buf0 + BLOCK;
         if (ph == 0) {
-            uint64_t i = (uint64_t)wg * BLOCK + lane;
-            buf0[lane] = i < n ? in[i] : xyzz_identity();
+            bool second = in2 && wg >= split;
+            uint64_t i = (uint64_t)(second ? wg - split : wg) * BLOCK + lane;
+            buf0[lane] = i < n ? (second ? in2[i] : in[i]) : xyzz_identity();
             return;
         }
         if (ph <= LOG) {                       /* suffix sums, ping-pong */
@@ -572,6 +581,40 @@ struct NodeCommitFr {
         out[t] = acc;
     }
 };
+/* upper levels, arity a power of two <= 64: workgroup of 64 lanes = 64 / B nodes; each lane commits one
+ * child, then the B partial sums of a node are added pairwise through LDS. */
+template <int BLOCK>
+struct NodeCommitFrCoop {
+    static constexpr size_t LDS_BYTES = BLOCK * sizeof(g1_xyzz);
+    static constexpr int PHASES = 8;         /* 1 + log2(64) + 1 */
+    TreeGeom g;
+    const fr_plain* below;
+    const g1_affine* table;
+    uint64_t n_nodes;
+    int logB;
+    g1_xyzz* out;               /* n_nodes */
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        g1_xyzz* buf = (g1_xyzz*)lds;
+        uint64_t t = (uint64_t)wg * BLOCK + lane;
+        uint64_t a = t >> logB;
+        uint32_t k = (uint32_t)(t & (g.B - 1));
+        if (ph == 0) {
+            g1_xyzz acc = xyzz_identity();
+            if (a < n_nodes) {
+                int64_t f = child_index(g, a, k);
+                if (f >= 0) acc = fb_mul_accumulate(acc, table, k, below[f].l);
+            }
+            buf[lane] = acc;
+            return;
+        }
+        if (ph <= logB) {
+            uint32_t stride = 1u << (ph - 1);
+            if ((k & (2 * stride - 1)) == 0) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
+            return;
+        }
+        if (ph == logB + 1 && k == 0 && a < n_nodes) out[a] = buf[lane];
+    }
+};
 /* out[i] = sum of in[i * group .. (i + 1) * group) */
 struct SumGroups {
     const g1_xyzz* in;
@@ -741,14 +784,19 @@ struct NodeOpenTerms {         /* lane (job, axis, term): one quotient value tim
 
 /* ---- Ver (sum form, trapdoor-form check in G1) -------------------------------------------- */
 /* One verification step: is  C - [y]G == sum_i [tau_i - (kappa_i + 1)] pi_i ?
- * Points arrive as canonical bytes; a point that is not on the curve rejects the step. */
+ * Points arrive as canonical bytes; a point that is not on the curve rejects the step.
+ * Each scalar k_i = tau_i - zeta_i arrives split as k_i = k1 + k2 lambda (both below 2^128), lambda the
+ * eigenvalue of the endomorphism (x, y) -> (beta x, y), so that [k]P = [k1]P + [k2](beta x, y) costs two
+ * half-length double-and-add chains that run in separate lanes. */
 struct VerifyStep {
     uint32_t C[24];
     uint32_t y[8];
     uint32_t pi[4][24];
-    uint32_t kappa[4];
+    uint32_t k1[4][4];
+    uint32_t k2[4][4];
     int m;
 };
+constexpr uint32_t VERIFY_TERMS = 9;      /* [y]G and two half-scalar terms per proof element */
 TC_HD bool affine_on_curve(const g1_affine& p) {
     if (affine_is_identity(p)) return true;
     fp_t y2 = fp_sqr(p.y);
@@ -762,15 +810,14 @@ TC_HD bool xyzz_equal(const g1_xyzz& a, const g1_xyzz& b) {
     if (ia || ib) return ia && ib;
     return fe_eq(fp_mul(a.X, b.ZZ), fp_mul(b.X, a.ZZ)) && fe_eq(fp_mul(a.Y, b.ZZZ), fp_mul(b.Y, a.ZZZ));
 }
-/* lane (step, term): term 0 = [y]G, term i = [tau_i - zeta] pi_i; writes XYZZ and a validity flag */
+/* lane (step, term): term 0 = [y]G; term 1 + 2i = [k1_i] pi_i; term 2 + 2i = [k2_i] (beta x, y) of pi_i */
 struct VerifyTerms {
     const VerifyStep* steps;
-    const fr_t* tau;           /* Montgomery */
     const g1_affine* gtable;
-    g1_xyzz* out;              /* steps * 5 */
+    g1_xyzz* out;              /* steps * VERIFY_TERMS */
     uint32_t* ok;              /* per step, preset to 1; cleared on malformed input */
     TC_DEV void operator()(uint32_t lane) const {
-        uint32_t s = lane / 5, term = lane % 5;
+        uint32_t s = lane / VERIFY_TERMS, term = lane % VERIFY_TERMS;
         const VerifyStep& st = steps[s];
         g1_xyzz r = xyzz_identity();
         if (term == 0) {
@@ -778,13 +825,19 @@ struct VerifyTerms {
             r = fb_mul_accumulate(r, gtable, 0, st.y);
             g1_affine c = affine_from_canonical(st.C);
             if (!canonical_fp(st.C) || !canonical_fp(st.C + 12) || !affine_on_curve(c)) atomic_and_u32(&ok[s], 0u);
-        } else if ((int)term <= st.m) {
-            int i = (int)term - 1;
+        } else if ((int)(term - 1) / 2 < st.m) {
+            int i = (int)(term - 1) / 2;
+            bool second = ((term - 1) & 1u) != 0;
             const uint32_t* w = st.pi[i];
             g1_affine p = affine_from_canonical(w);
-            if (!canonical_fp(w) || !canonical_fp(w + 12) || !affine_on_curve(p)) atomic_and_u32(&ok[s], 0u);
-            fr_t k = fe_to_plain(fr_sub(tau[i], fe_from_u32<FrParams>(st.kappa[i] + 1u)));
-            r = xyzz_mul_affine(k.l, 255, p);
+            if (!second && (!canonical_fp(w) || !canonical_fp(w + 12) || !affine_on_curve(p))) atomic_and_u32(&ok[s], 0u);
+            if (second) {
+                fp_t beta;
+#pragma unroll
+                for (int j = 0; j < 12; ++j) beta.l[j] = GLV_BETA[j];
+                p.x = fp_mul(p.x, beta);
+            }
+            r = xyzz_mul_affine(second ? st.k2[i] : st.k1[i], 128, p);
         }
         out[lane] = r;
     }
@@ -795,9 +848,10 @@ struct VerifyCombine {         /* lane = step */
     uint32_t* ok;
     TC_DEV void operator()(uint32_t s) const {
         const VerifyStep& st = steps[s];
-        g1_xyzz lhs = xyzz_add(xyzz_from_affine(affine_from_canonical(st.C)), xyzz_neg(terms[(uint64_t)s * 5]));
+        const g1_xyzz* t = terms + (uint64_t)s * VERIFY_TERMS;
+        g1_xyzz lhs = xyzz_add(xyzz_from_affine(affine_from_canonical(st.C)), xyzz_neg(t[0]));
         g1_xyzz rhs = xyzz_identity();
-        for (int i = 1; i <= st.m; ++i) rhs = xyzz_add(rhs, terms[(uint64_t)s * 5 + i]);
+        for (int i = 1; i <= 2 * st.m; ++i) rhs = xyzz_add(rhs, t[i]);
         if (!xyzz_equal(lhs, rhs)) ok[s] = 0;
     }
 };

@@ -554,10 +554,10 @@ static int launch_coop(uint32_t groups, rt::stream_t st, const F& f) {
 
 /* prefix sums of cnt (n entries): start, lstart (of ceil(cnt / L)); optional zeroing of a cursor array */
 static int scan_counts(tc_ctx* ctx, const uint32_t* cnt, uint32_t n, uint32_t L, uint32_t* start, uint32_t* lstart,
-                       uint32_t* zero_me, uint32_t* tot_a, uint32_t* tot_b) {
+                       uint32_t* zero_me, uint32_t* tot_a, uint32_t* tot_b, uint32_t* tot_max) {
     uint32_t nchunks = (n + SCAN_CHUNK - 1) / SCAN_CHUNK;
-    RT(rt::launch<64>(nchunks, ctx->stream, ScanChunkTotals{cnt, n, L, tot_a, tot_b}));
-    RT(rt::launch<64>(1, ctx->stream, ScanChunkOffsets{nchunks, tot_a, tot_b}));
+    RT(rt::launch<64>(nchunks, ctx->stream, ScanChunkTotals{cnt, n, L, tot_a, tot_b, tot_max}));
+    RT(rt::launch<64>(1, ctx->stream, ScanChunkOffsets{nchunks, tot_a, tot_b, tot_max}));
     RT(rt::launch<64>(nchunks, ctx->stream, ScanWrite{cnt, n, L, tot_a, tot_b, nchunks, start, lstart, zero_me}));
     return TC_OK;
 }
@@ -569,20 +569,18 @@ static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb
     uint32_t nblk = (uint32_t)W * G;
     WS(w1, g1_xyzz, nblk);
     WS(s1, g1_xyzz, nblk);
-    RT((launch_coop<BLOCK>(nblk, ctx->stream, WeightedBlockSum<BLOCK>{bucket, (uint32_t)W * nb, w1, s1})));
+    RT((launch_coop<BLOCK>(nblk, ctx->stream, WeightedBlockSum<BLOCK>{bucket, (uint32_t)W * nb, w1, s1, nullptr, 0})));
     if (G == 1) {
         RT(rt::launch<64>((uint32_t)W, ctx->stream, WindowFinish{w1, nullptr, nullptr, 1, 0, wsum}));
         return TC_OK;
     }
     if (G != 128) return fail(ctx, TC_ERR_STATE, "unsupported bucket count");
-    WS(w2, g1_xyzz, (uint32_t)W);
-    WS(s2, g1_xyzz, (uint32_t)W);
-    WS(w3, g1_xyzz, (uint32_t)W);
-    WS(s3, g1_xyzz, (uint32_t)W);
-    RT((launch_coop<128>((uint32_t)W, ctx->stream, WeightedBlockSum<128>{s1, nblk, w2, s2})));
-    RT((launch_coop<128>((uint32_t)W, ctx->stream, WeightedBlockSum<128>{w1, nblk, w3, s3})));
+    /* second level in one launch: blocks 0 .. W-1 reduce the block totals S, blocks W .. 2W-1 the block sums W */
+    WS(w23, g1_xyzz, 2u * (uint32_t)W);
+    WS(s23, g1_xyzz, 2u * (uint32_t)W);
+    RT((launch_coop<128>(2u * (uint32_t)W, ctx->stream, WeightedBlockSum<128>{s1, nblk, w23, s23, w1, (uint32_t)W})));
     int log_block = BLOCK == 256 ? 8 : 7;
-    RT(rt::launch<64>((uint32_t)W, ctx->stream, WindowFinish{s3, w2, s2, (int)G, log_block, wsum}));
+    RT(rt::launch<64>((uint32_t)W, ctx->stream, WindowFinish{s23 + W, w23, s23, (int)G, log_block, wsum}));
     return TC_OK;
 }
 
@@ -620,6 +618,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     WS(lstart2, uint32_t, nbk + 1);
     WS(tot_a, uint32_t, nchunks + 1);
     WS(tot_b, uint32_t, nchunks + 1);
+    WS(tot_max, uint32_t, nchunks + 1);
     WS(sorted, uint32_t, items ? items : 1);
     WS(tables, const g1_affine*, (uint32_t)count);
     std::vector<const g1_affine*> h_tables(count);
@@ -634,7 +633,9 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     RT(rt::launch<256>(nbk, ctx->stream, Fill32{cnt, 0u}));
     for (int p = 0; p < count; ++p)
         RT(rt::launch<256>(prob[p].n, ctx->stream, MsmCount{prob[p].scalars, dtype, W, c, nb, cnt + (size_t)p * nbk_pp}));
-    TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, cursor, tot_a, tot_b));
+    TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, cursor, tot_a, tot_b, tot_max));
+    uint32_t max_count = 0;        /* largest bucket: fixes how many shrinking passes are needed */
+    RT(rt::memcpy_d2h(&max_count, tot_max + nchunks, 4, ctx->stream));
     for (int p = 0; p < count; ++p)
         RT(rt::launch<256>(prob[p].n, ctx->stream,
                            MsmScatter{prob[p].scalars, dtype, W, c, nb, start + (size_t)p * nbk_pp, cursor + (size_t)p * nbk_pp, sorted}));
@@ -651,16 +652,17 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         prof_end(ctx, TC_PROF_BUCKET_ACC, e0, e1);
     }
 
-    /* worst case: every item of a problem in one bucket.  Middle passes shrink the per-bucket
-     * partial count by L2 until at most L2 remain; the plan is fixed on the host from the sizes alone. */
-    uint64_t worst = (max_items + L1 - 1) / L1;
+    /* Middle passes shrink the per-bucket partial count by L2 until at most L2 remain. */
+    RT(rt::stream_sync(ctx->stream));
+    if (max_count > max_items) return fail(ctx, TC_ERR_STATE, "internal: bucket count exceeds the term count");
+    uint64_t worst = ((uint64_t)max_count + L1 - 1) / L1;
     g1_xyzz *cur = bufA, *nxt = bufB;
     uint32_t *cur_start = lstart, *nxt_start = lstart2;
     uint64_t lanes_bound = max_part;
     while (worst > L2) {
         /* counts of this pass = number of partials per bucket = differences of cur_start */
         RT(rt::launch<256>(nbk, ctx->stream, DiffCounts{cur_start, cnt}));
-        TRY(scan_counts(ctx, cnt, nbk, L2, start, nxt_start, nullptr, tot_a, tot_b));
+        TRY(scan_counts(ctx, cnt, nbk, L2, start, nxt_start, nullptr, tot_a, tot_b, tot_max));
         /* `start` now equals cur_start (prefix of the same counts) */
         lanes_bound = lanes_bound / L2 + nbk + 1;
         RT(rt::launch<64>(lanes_bound, ctx->stream, AccXyzz{cur, cur_start, nxt_start, nbk, L2, nxt}));
@@ -806,26 +808,47 @@ extern "C" int tc_vk_from_trapdoor(const uint8_t* tau, int m, tc_vk** out) {
 }
 extern "C" void tc_vk_destroy(tc_vk* vk) { delete vk; }
 
+/* k = k2 * lambda + k1 with 0 <= k1 < lambda < 2^128 (k < r < lambda^2 + lambda + 1, so k2 < 2^128) */
+static void glv_split(const uint32_t k[8], uint32_t k1[4], uint32_t k2[4]) {
+    typedef unsigned __int128 u128;
+    u128 lam = 0, rem = 0, q = 0;
+    for (int i = 3; i >= 0; --i) lam = (lam << 32) | GLV_LAMBDA[i];
+    for (int i = 255; i >= 0; --i) {
+        bool top = (rem >> 127) & 1;
+        rem = (rem << 1) | ((k[i >> 5] >> (i & 31)) & 1u);
+        if (top || rem >= lam) {
+            rem -= lam;                      /* when `top` is set the true value is 2^128 + rem, still >= lambda */
+            if (i < 128) q |= (u128)1 << i;
+        }
+    }
+    for (int i = 0; i < 4; ++i) {
+        k1[i] = (uint32_t)(rem >> (32 * i));
+        k2[i] = (uint32_t)(q >> (32 * i));
+    }
+}
+/* fills the split scalars of a step: k_i = tau_i - (kappa_i + 1) mod r */
+static void fill_step_scalars(const tc_vk* vk, const uint32_t* kappa, VerifyStep* st) {
+    for (int i = 0; i < st->m; ++i) {
+        uint32_t w[8];
+        memcpy(w, vk->tau[i], 32);
+        fr_t k = fe_to_plain(fr_sub(fe_from_limbs<FrParams>(w), fe_from_u32<FrParams>(kappa[i] + 1u)));
+        glv_split(k.l, st->k1[i], st->k2[i]);
+    }
+}
+
 /* runs the steps on the device; ok[i] = 1 iff step i verifies */
 static int verify_steps(tc_ctx* ctx, const tc_vk* vk, const std::vector<VerifyStep>& steps, std::vector<uint32_t>& ok) {
     uint32_t n = (uint32_t)steps.size();
     ok.assign(n, 0);
     if (!n) return TC_OK;
+    (void)vk;
     TRY(ensure_gtable(ctx));
-    fr_t tau_m[4];
-    for (int j = 0; j < 4; ++j) {
-        uint32_t w[8] = {0};
-        if (j < vk->m) memcpy(w, vk->tau[j], 32);
-        tau_m[j] = fe_from_limbs<FrParams>(w);
-    }
     WS(d_steps, VerifyStep, n);
-    WS(d_tau, fr_t, 4);
-    WS(d_terms, g1_xyzz, 5ull * n);
+    WS(d_terms, g1_xyzz, (uint64_t)VERIFY_TERMS * n);
     WS(d_ok, uint32_t, n);
     RT(rt::memcpy_h2d(d_steps, steps.data(), sizeof(VerifyStep) * n, ctx->stream));
-    RT(rt::memcpy_h2d(d_tau, tau_m, sizeof tau_m, ctx->stream));
     RT(rt::launch<256>(n, ctx->stream, Fill32{d_ok, 1u}));
-    RT(rt::launch<64>(5ull * n, ctx->stream, VerifyTerms{d_steps, d_tau, ctx->gtable, d_terms, d_ok}));
+    RT(rt::launch<64>((uint64_t)VERIFY_TERMS * n, ctx->stream, VerifyTerms{d_steps, ctx->gtable, d_terms, d_ok}));
     RT(rt::launch<64>(n, ctx->stream, VerifyCombine{d_steps, d_terms, d_ok}));
     RT(rt::memcpy_d2h(ok.data(), d_ok, 4ull * n, ctx->stream));
     RT(rt::stream_sync(ctx->stream));
@@ -845,11 +868,9 @@ extern "C" int tc_verify(tc_ctx* ctx, const tc_vk* vk, int m, const uint32_t* sh
     memset(&steps[0], 0, sizeof(VerifyStep));
     memcpy(steps[0].C, commitment, 96);
     memcpy(steps[0].y, y, 32);
-    for (int j = 0; j < m; ++j) {
-        memcpy(steps[0].pi[j], pi + 96 * j, 96);
-        steps[0].kappa[j] = kappa[j];
-    }
+    for (int j = 0; j < m; ++j) memcpy(steps[0].pi[j], pi + 96 * j, 96);
     steps[0].m = m;
+    fill_step_scalars(vk, kappa, &steps[0]);
     std::vector<uint32_t> ok;
     TRY(verify_steps(ctx, vk, steps, ok));
     if (!ok[0]) return fail(ctx, TC_ERR_VERIFY, "opening rejected");
@@ -1026,6 +1047,12 @@ extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** 
                         prof_begin(ctx, TC_PROF_NODE_COMMIT, &e0, &e1);
                         e = rt::launch<64>(lv.n, ctx->stream, NodeCommitSmall{g, t->d_payload, t->dtype, ns->fb[0], acc});
                         prof_end(ctx, TC_PROF_NODE_COMMIT, e0, e1);
+                    } else if ((t->B & (t->B - 1)) == 0 && t->B <= 64) {
+                        int logB = 0;
+                        while ((1u << logB) < t->B) ++logB;
+                        uint64_t lanes = lv.n * t->B;
+                        e = launch_coop<64>((uint32_t)((lanes + 63) / 64), ctx->stream,
+                                            NodeCommitFrCoop<64>{g, t->levels[L - 1].phi, ns->fb[0], lv.n, logB, acc});
                     } else {
                         g1_xyzz* part = ws_array<g1_xyzz>(ctx, lv.n * t->B);
                         if (!part) { rc = fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed"); break; }
@@ -1372,8 +1399,8 @@ extern "C" int tc_verify_paths_batch(tc_ctx* ctx, const tc_vk* vk, int count, co
             for (int j = 0; j < st.m; ++j) {
                 memcpy(st.pi[j], src, 96);
                 src += 96;
-                st.kappa[j] = p.kappa[s][j];
             }
+            fill_step_scalars(vk, p.kappa[s], &st);
             memcpy(st.y, src, 32);
             src += 32;
             steps.push_back(st);
