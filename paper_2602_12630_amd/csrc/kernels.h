@@ -343,6 +343,53 @@ struct WeightedBlockSum {
     }
 };
 
+/* Row and column sums of a window's 128 x 256 bucket matrix (bucket k = 256 h + l + 1): workgroup g of
+ * window w sums row h = g (g < 128: the 256 buckets with that high part) or column l = g - 128 (the 128
+ * buckets with that low part), pairwise through LDS.  With R_h and C_l,
+ *     sum_k k B_k = 256 sum_h h R_h + sum_l (l + 1) C_l,
+ * one plain addition per bucket and direction instead of a weighted scan over all of them. */
+struct RowColSums {
+    static constexpr int PHASES = 10;          /* load, 8 halving steps, store */
+    static constexpr size_t LDS_BYTES = 256 * sizeof(g1_xyzz);
+    static constexpr uint32_t GROUPS = 128 + 256;
+    const g1_xyzz* bucket;      /* windows * 32768 */
+    g1_xyzz* rows;              /* windows * 256: entries 128..255 of a window are the identity */
+    g1_xyzz* cols;              /* windows * 256 */
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        g1_xyzz* buf = (g1_xyzz*)lds;
+        uint32_t w = wg / GROUPS, g = wg % GROUPS;
+        const g1_xyzz* base = bucket + (uint64_t)w * 32768u;
+        if (ph == 0) {
+            if (g < 128) buf[lane] = base[g * 256u + lane];
+            else buf[lane] = lane < 128 ? base[lane * 256u + (g - 128)] : xyzz_identity();
+            return;
+        }
+        if (ph <= 8) {
+            uint32_t stride = 128u >> (ph - 1);
+            if (lane < stride) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
+            return;
+        }
+        if (lane == 0) {
+            if (g < 128) rows[(uint64_t)w * 256 + g] = buf[0];
+            else cols[(uint64_t)w * 256 + (g - 128)] = buf[0];
+        } else if (lane == 1 && g < 128) {
+            rows[(uint64_t)w * 256 + 128 + g] = xyzz_identity();
+        }
+    }
+};
+/* one lane per window: 256 (W_R - S_R) + W_C */
+struct RowColFinish {
+    const g1_xyzz* w_rows;      /* sum_h (h + 1) R_h */
+    const g1_xyzz* s_rows;      /* sum_h R_h */
+    const g1_xyzz* w_cols;      /* sum_l (l + 1) C_l */
+    g1_xyzz* out;
+    TC_DEV void operator()(uint32_t w) const {
+        g1_xyzz t = xyzz_add(w_rows[w], xyzz_neg(s_rows[w]));
+        for (int i = 0; i < 8; ++i) t = xyzz_dbl(t);
+        out[w] = xyzz_add(t, w_cols[w]);
+    }
+};
+
 /* One lane per window: Wsum = sumW + BLOCK * (W2 - S2) where, over the G blocks of the window,
  * sumW = sum_g W_g, W2 = sum_g (g+1) S_g, S2 = sum_g S_g.  With G == 1: Wsum = W_0. */
 struct WindowFinish {

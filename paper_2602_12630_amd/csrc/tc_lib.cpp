@@ -563,24 +563,24 @@ static int scan_counts(tc_ctx* ctx, const uint32_t* cnt, uint32_t n, uint32_t L,
 }
 
 /* sum_k k B_k for every window of `bucket` (W windows of nb buckets) -> wsum[W] */
-template <int BLOCK>
 static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb, g1_xyzz* wsum) {
-    uint32_t G = nb / BLOCK;                          /* blocks per window */
-    uint32_t nblk = (uint32_t)W * G;
-    WS(w1, g1_xyzz, nblk);
-    WS(s1, g1_xyzz, nblk);
-    RT((launch_coop<BLOCK>(nblk, ctx->stream, WeightedBlockSum<BLOCK>{bucket, (uint32_t)W * nb, w1, s1, nullptr, 0})));
-    if (G == 1) {
+    if (nb == 128) {
+        WS(w1, g1_xyzz, (uint32_t)W);
+        WS(s1, g1_xyzz, (uint32_t)W);
+        RT((launch_coop<128>((uint32_t)W, ctx->stream, WeightedBlockSum<128>{bucket, (uint32_t)W * nb, w1, s1, nullptr, 0})));
         RT(rt::launch<64>((uint32_t)W, ctx->stream, WindowFinish{w1, nullptr, nullptr, 1, 0, wsum}));
         return TC_OK;
     }
-    if (G != 128) return fail(ctx, TC_ERR_STATE, "unsupported bucket count");
-    /* second level in one launch: blocks 0 .. W-1 reduce the block totals S, blocks W .. 2W-1 the block sums W */
-    WS(w23, g1_xyzz, 2u * (uint32_t)W);
-    WS(s23, g1_xyzz, 2u * (uint32_t)W);
-    RT((launch_coop<128>(2u * (uint32_t)W, ctx->stream, WeightedBlockSum<128>{s1, nblk, w23, s23, w1, (uint32_t)W})));
-    int log_block = BLOCK == 256 ? 8 : 7;
-    RT(rt::launch<64>((uint32_t)W, ctx->stream, WindowFinish{s23 + W, w23, s23, (int)G, log_block, wsum}));
+    if (nb != 32768) return fail(ctx, TC_ERR_STATE, "unsupported bucket count");
+    /* 128 x 256 bucket matrix: row / column sums, then two small weighted sums per window */
+    WS(rows, g1_xyzz, 256ull * W);
+    WS(cols, g1_xyzz, 256ull * W);
+    WS(w_rc, g1_xyzz, 2u * (uint32_t)W);     /* [0, W): columns, [W, 2W): rows */
+    WS(s_rc, g1_xyzz, 2u * (uint32_t)W);
+    RT((launch_coop<256>((uint32_t)W * RowColSums::GROUPS, ctx->stream, RowColSums{bucket, rows, cols})));
+    RT((launch_coop<256>(2u * (uint32_t)W, ctx->stream,
+                         WeightedBlockSum<256>{cols, 256u * (uint32_t)W, w_rc, s_rc, rows, (uint32_t)W})));
+    RT(rt::launch<64>((uint32_t)W, ctx->stream, RowColFinish{w_rc + W, s_rc + W, w_rc, wsum}));
     return TC_OK;
 }
 
@@ -672,8 +672,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     }
     RT(rt::launch<64>(nbk, ctx->stream, AccFinal{cur, cur_start, bucket}));
 
-    if (nb == 128) TRY(reduce_windows<128>(ctx, bucket, W * count, nb, wsum));
-    else TRY(reduce_windows<256>(ctx, bucket, W * count, nb, wsum));
+    TRY(reduce_windows(ctx, bucket, W * count, nb, wsum));
     RT(rt::launch<64>((uint32_t)count, ctx->stream, WindowCombine{wsum, W, c, results}));
     return TC_OK;
 }
