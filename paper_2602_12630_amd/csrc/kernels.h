@@ -150,6 +150,91 @@ struct MsmScatter {
     }
 };
 
+/* ---- MSM: count / scatter for one-digit scalars without global atomics ---------------- */
+/* A workgroup owns a tile of consecutive terms of one problem.  CountTile builds the tile's
+ * histogram in LDS and writes it as a row of the matrix M[problem][tile][key]; TileColumnScan turns
+ * every column into exclusive offsets (and the per-key totals); ScatterTile reloads its row,
+ * adds the global bucket starts and hands out positions with LDS atomics. */
+struct TileProblem {
+    const void* scalars;
+    uint64_t n;
+    uint32_t tile;            /* terms per workgroup */
+};
+template <int NB>
+struct CountTile {
+    static constexpr int BLOCK = 1024;
+    static constexpr int PHASES = 3;
+    static constexpr size_t LDS_BYTES = NB * sizeof(uint32_t);
+    const TileProblem* prob;
+    int dtype;
+    uint32_t n_wg;            /* tiles per problem */
+    uint32_t* M;              /* problems * n_wg * NB */
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        uint32_t* hist = (uint32_t*)lds;
+        uint32_t p = wg / n_wg, tl = wg % n_wg;
+        if (ph == 0) {
+            for (uint32_t k = lane; k < (uint32_t)NB; k += BLOCK) hist[k] = 0;
+        } else if (ph == 1) {
+            const TileProblem P = prob[p];
+            uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
+            for (uint64_t i = lo + lane; i < hi; i += BLOCK) {
+                int32_t d = small_scalar(P.scalars, dtype, i);
+                if (d) atomic_add_u32(&hist[(uint32_t)(d < 0 ? -d : d) - 1u], 1u);
+            }
+        } else {
+            uint32_t* row = M + (uint64_t)wg * NB;
+            for (uint32_t k = lane; k < (uint32_t)NB; k += BLOCK) row[k] = hist[k];
+        }
+    }
+};
+struct TileColumnScan {       /* lane = (problem, key) */
+    uint32_t nb, n_wg;
+    uint32_t* M;
+    uint32_t* cnt;            /* problems * nb */
+    TC_DEV void operator()(uint32_t t) const {
+        uint32_t p = t / nb, key = t % nb;
+        uint32_t* col = M + (uint64_t)p * n_wg * nb + key;
+        uint32_t off = 0;
+        for (uint32_t w = 0; w < n_wg; ++w) {
+            uint32_t v = col[(uint64_t)w * nb];
+            col[(uint64_t)w * nb] = off;
+            off += v;
+        }
+        cnt[t] = off;
+    }
+};
+template <int NB>
+struct ScatterTile {
+    static constexpr int BLOCK = 1024;
+    static constexpr int PHASES = 2;
+    static constexpr size_t LDS_BYTES = NB * sizeof(uint32_t);
+    const TileProblem* prob;
+    int dtype;
+    uint32_t n_wg;
+    const uint32_t* M;
+    const uint32_t* start;    /* global bucket starts, problems * NB (+1) */
+    uint32_t* sorted;
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        uint32_t* cur = (uint32_t*)lds;
+        uint32_t p = wg / n_wg, tl = wg % n_wg;
+        if (ph == 0) {
+            const uint32_t* row = M + (uint64_t)wg * NB;
+            const uint32_t* st = start + (uint64_t)p * NB;
+            for (uint32_t k = lane; k < (uint32_t)NB; k += BLOCK) cur[k] = st[k] + row[k];
+        } else {
+            const TileProblem P = prob[p];
+            uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
+            for (uint64_t i = lo + lane; i < hi; i += BLOCK) {
+                int32_t d = small_scalar(P.scalars, dtype, i);
+                if (d) {
+                    uint32_t pos = atomic_add_u32(&cur[(uint32_t)(d < 0 ? -d : d) - 1u], 1u);
+                    sorted[pos] = (uint32_t)i | (d < 0 ? 0x80000000u : 0u);
+                }
+            }
+        }
+    }
+};
+
 /* ---- prefix sums over bucket counts (three lane-independent steps) ---------------- */
 /* chunk = 256 consecutive buckets.  A: per-chunk totals of cnt and of ceil(cnt / L);
  * B: one lane turns the chunk totals into exclusive offsets; C: per-chunk serial prefix. */
@@ -349,8 +434,9 @@ struct WeightedBlockSum {
  *     sum_k k B_k = 256 sum_h h R_h + sum_l (l + 1) C_l,
  * one plain addition per bucket and direction instead of a weighted scan over all of them. */
 struct RowColSums {
-    static constexpr int PHASES = 10;          /* load, 8 halving steps, store */
-    static constexpr size_t LDS_BYTES = 256 * sizeof(g1_xyzz);
+    static constexpr int BLOCK = 64;
+    static constexpr int PHASES = 8;           /* serial part, 6 halving steps, store */
+    static constexpr size_t LDS_BYTES = BLOCK * sizeof(g1_xyzz);
     static constexpr uint32_t GROUPS = 128 + 256;
     const g1_xyzz* bucket;      /* windows * 32768 */
     g1_xyzz* rows;              /* windows * 256: entries 128..255 of a window are the identity */
@@ -360,12 +446,20 @@ struct RowColSums {
         uint32_t w = wg / GROUPS, g = wg % GROUPS;
         const g1_xyzz* base = bucket + (uint64_t)w * 32768u;
         if (ph == 0) {
-            if (g < 128) buf[lane] = base[g * 256u + lane];
-            else buf[lane] = lane < 128 ? base[lane * 256u + (g - 128)] : xyzz_identity();
+            g1_xyzz acc;
+            if (g < 128) {                     /* row g: lane takes 4 neighbouring buckets */
+                const g1_xyzz* p = base + g * 256u + lane * 4u;
+                acc = p[0];
+                for (int i = 1; i < 4; ++i) acc = xyzz_add(acc, p[i]);
+            } else {                           /* column g - 128: lane takes 2 of the 128 rows */
+                const g1_xyzz* p = base + (g - 128);
+                acc = xyzz_add(p[(lane * 2u) * 256u], p[(lane * 2u + 1u) * 256u]);
+            }
+            buf[lane] = acc;
             return;
         }
-        if (ph <= 8) {
-            uint32_t stride = 128u >> (ph - 1);
+        if (ph <= 6) {
+            uint32_t stride = 32u >> (ph - 1);
             if (lane < stride) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
             return;
         }

@@ -577,7 +577,7 @@ static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb
     WS(cols, g1_xyzz, 256ull * W);
     WS(w_rc, g1_xyzz, 2u * (uint32_t)W);     /* [0, W): columns, [W, 2W): rows */
     WS(s_rc, g1_xyzz, 2u * (uint32_t)W);
-    RT((launch_coop<256>((uint32_t)W * RowColSums::GROUPS, ctx->stream, RowColSums{bucket, rows, cols})));
+    RT((launch_coop<RowColSums::BLOCK>((uint32_t)W * RowColSums::GROUPS, ctx->stream, RowColSums{bucket, rows, cols})));
     RT((launch_coop<256>(2u * (uint32_t)W, ctx->stream,
                          WeightedBlockSum<256>{cols, 256u * (uint32_t)W, w_rc, s_rc, rows, (uint32_t)W})));
     RT(rt::launch<64>((uint32_t)W, ctx->stream, RowColFinish{w_rc + W, s_rc + W, w_rc, wsum}));
@@ -630,15 +630,37 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     uint32_t L1 = (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(4, (items + target_lanes - 1) / target_lanes));
     const uint32_t L2 = 16;
 
-    RT(rt::launch<256>(nbk, ctx->stream, Fill32{cnt, 0u}));
-    for (int p = 0; p < count; ++p)
-        RT(rt::launch<256>(prob[p].n, ctx->stream, MsmCount{prob[p].scalars, dtype, W, c, nb, cnt + (size_t)p * nbk_pp}));
-    TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, cursor, tot_a, tot_b, tot_max));
     uint32_t max_count = 0;        /* largest bucket: fixes how many shrinking passes are needed */
-    RT(rt::memcpy_d2h(&max_count, tot_max + nchunks, 4, ctx->stream));
-    for (int p = 0; p < count; ++p)
-        RT(rt::launch<256>(prob[p].n, ctx->stream,
-                           MsmScatter{prob[p].scalars, dtype, W, c, nb, start + (size_t)p * nbk_pp, cursor + (size_t)p * nbk_pp, sorted}));
+    if (W == 1) {
+        /* one digit per term: tile histograms in LDS, no global atomics */
+        uint32_t n_wg = (uint32_t)std::min<uint64_t>(256, std::max<uint64_t>(8, 4096 / (uint64_t)count));
+        std::vector<TileProblem> h_prob(count);
+        for (int p = 0; p < count; ++p) {
+            h_prob[p].scalars = prob[p].scalars;
+            h_prob[p].n = prob[p].n;
+            h_prob[p].tile = (uint32_t)((prob[p].n + n_wg - 1) / n_wg);
+        }
+        WS(d_prob, TileProblem, (uint32_t)count);
+        WS(M, uint32_t, (uint64_t)count * n_wg * nb);
+        RT(rt::memcpy_h2d(d_prob, h_prob.data(), sizeof(TileProblem) * (size_t)count, ctx->stream));
+        uint32_t groups = (uint32_t)count * n_wg;
+        if (nb == 128) RT((launch_coop<1024>(groups, ctx->stream, CountTile<128>{d_prob, dtype, n_wg, M})));
+        else RT((launch_coop<1024>(groups, ctx->stream, CountTile<32768>{d_prob, dtype, n_wg, M})));
+        RT(rt::launch<256>(nbk, ctx->stream, TileColumnScan{nb, n_wg, M, cnt}));
+        TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, nullptr, tot_a, tot_b, tot_max));
+        RT(rt::memcpy_d2h(&max_count, tot_max + nchunks, 4, ctx->stream));
+        if (nb == 128) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<128>{d_prob, dtype, n_wg, M, start, sorted})));
+        else RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<32768>{d_prob, dtype, n_wg, M, start, sorted})));
+    } else {
+        RT(rt::launch<256>(nbk, ctx->stream, Fill32{cnt, 0u}));
+        for (int p = 0; p < count; ++p)
+            RT(rt::launch<256>(prob[p].n, ctx->stream, MsmCount{prob[p].scalars, dtype, W, c, nb, cnt + (size_t)p * nbk_pp}));
+        TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, cursor, tot_a, tot_b, tot_max));
+        RT(rt::memcpy_d2h(&max_count, tot_max + nchunks, 4, ctx->stream));
+        for (int p = 0; p < count; ++p)
+            RT(rt::launch<256>(prob[p].n, ctx->stream,
+                               MsmScatter{prob[p].scalars, dtype, W, c, nb, start + (size_t)p * nbk_pp, cursor + (size_t)p * nbk_pp, sorted}));
+    }
 
     uint64_t max_part = items / L1 + nbk + 1;          /* upper bound on first-pass lanes */
     WS(bufA, g1_xyzz, max_part);
