@@ -534,6 +534,161 @@ TC_HD Fe<P> fe_inv(const Fe<P>& x) {
     return fe_mulx(r, r3);
 }
 
+/* Inverse by the binary GCD with word-sized batches of steps (Pornin, "Optimized Binary GCD for
+ * Modular Inversion", 2020).  Invariants a = u x 4^T, b = v x 4^T (mod q) after T rounds.  A round
+ * runs 30 halving / subtracting steps on 62-bit approximations of (a, b) (their 30 low bits, which
+ * decide the parities exactly, and their 32 top bits, which decide the comparisons) while recording
+ * the steps as a 2 x 2 integer matrix (f0 g0; f1 g1), then applies the matrix once to the full
+ * (a, b) (exact division by 2^30, signs fixed afterwards) and to (u, v) (one Montgomery-style word
+ * reduction, i.e. a division by 2^32 modulo q).  After GCD_ROUNDS rounds a = 0, b = 1 and
+ * x^-1 = v 4^GCD_ROUNDS; further rounds change nothing.  The final product with
+ * GCD_FIX = 4^GCD_ROUNDS R^3 restores the Montgomery form of the inverse. */
+template <class P>
+TC_HD Fe<P> fe_inv_gcd(const Fe<P>& x) {
+    constexpr int N = P::N;
+    constexpr int K = 30;
+    uint32_t a[N], b[N], u[N], v[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) { a[i] = x.l[i]; b[i] = P::MOD[i]; u[i] = 0; v[i] = 0; }
+    u[0] = 1;
+    for (int round = 0; round < P::GCD_ROUNDS; ++round) {
+        /* approximations: top limb index j of (a | b), then 64 bits below it */
+        uint32_t ctop = a[N - 1] | b[N - 1], ahi = a[N - 1], alo = a[N - 2], bhi = b[N - 1], blo = b[N - 2];
+        bool found = ctop != 0;
+#pragma unroll
+        for (int i = N - 2; i >= 1; --i) {
+            uint32_t c = a[i] | b[i];
+            bool take = !found && c != 0;
+            ctop = take ? c : ctop;
+            ahi = take ? a[i] : ahi; alo = take ? a[i - 1] : alo;
+            bhi = take ? b[i] : bhi; blo = take ? b[i - 1] : blo;
+            found = found || c != 0;
+        }
+        uint64_t xa, xb;
+        if (!found) {                                     /* both fit in 64 bits: exact */
+            xa = ((uint64_t)a[1] << 32) | a[0];
+            xb = ((uint64_t)b[1] << 32) | b[0];
+        } else {
+            int lz = __builtin_clz(ctop);
+            uint64_t ta = (((uint64_t)ahi << 32) | alo) << lz;
+            uint64_t tb = (((uint64_t)bhi << 32) | blo) << lz;
+            xa = (uint64_t)(a[0] & 0x3FFFFFFFu) | ((ta >> 32) << 30);
+            xb = (uint64_t)(b[0] & 0x3FFFFFFFu) | ((tb >> 32) << 30);
+        }
+        /* when a and b fit in two limbs the `found` search above picked limb 1 only if it is
+         * non-zero; with limb 1 set and everything above zero the exact values are used too */
+        bool upper_zero = true;
+#pragma unroll
+        for (int i = 2; i < N; ++i) upper_zero = upper_zero && (a[i] | b[i]) == 0;
+        if (upper_zero) {
+            xa = ((uint64_t)a[1] << 32) | a[0];
+            xb = ((uint64_t)b[1] << 32) | b[0];
+        }
+        int32_t f0 = 1, g0 = 0, f1 = 0, g1 = 1;
+        for (int j = 0; j < K; ++j) {
+            uint64_t odd = 0ull - (xa & 1ull);
+            uint64_t swap = odd & (0ull - (uint64_t)(xa < xb));
+            uint64_t t = (xa ^ xb) & swap;
+            xa ^= t; xb ^= t;
+            int32_t s32 = (int32_t)swap;
+            int32_t tf = (f0 ^ f1) & s32, tg = (g0 ^ g1) & s32;
+            f0 ^= tf; f1 ^= tf; g0 ^= tg; g1 ^= tg;
+            xa -= xb & odd;
+            f0 -= f1 & (int32_t)odd;
+            g0 -= g1 & (int32_t)odd;
+            xa >>= 1;
+            f1 <<= 1;
+            g1 <<= 1;
+        }
+        /* (a, b) <- (a f0 + b g0, a f1 + b g1) / 2^30, exact; then make both non-negative */
+        uint32_t na[N + 1], nbv[N + 1];
+        int64_t ca = 0, cb = 0;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            ca += (int64_t)a[i] * f0 + (int64_t)b[i] * g0;
+            cb += (int64_t)a[i] * f1 + (int64_t)b[i] * g1;
+            na[i] = (uint32_t)ca; nbv[i] = (uint32_t)cb;
+            ca >>= 32; cb >>= 32;
+        }
+        na[N] = (uint32_t)ca; nbv[N] = (uint32_t)cb;
+        bool nega = (int32_t)na[N] < 0, negb = (int32_t)nbv[N] < 0;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            a[i] = (na[i] >> K) | (na[i + 1] << (32 - K));
+            b[i] = (nbv[i] >> K) | (nbv[i + 1] << (32 - K));
+        }
+        {   /* two's complement negation where needed */
+            uint32_t ma = nega ? 0xFFFFFFFFu : 0u, mb = negb ? 0xFFFFFFFFu : 0u;
+            uint32_t c1 = nega ? 1u : 0u, c2 = negb ? 1u : 0u;
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                uint64_t t1 = (uint64_t)(a[i] ^ ma) + c1;
+                a[i] = (uint32_t)t1; c1 = (uint32_t)(t1 >> 32);
+                uint64_t t2 = (uint64_t)(b[i] ^ mb) + c2;
+                b[i] = (uint32_t)t2; c2 = (uint32_t)(t2 >> 32);
+            }
+            if (nega) { f0 = -f0; g0 = -g0; }
+            if (negb) { f1 = -f1; g1 = -g1; }
+        }
+        /* (u, v) <- (u f0 + v g0, u f1 + v g1) / 2^32 mod q */
+        uint32_t nu[N + 1], nv[N + 1];
+        int64_t cu = 0, cv = 0;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            cu += (int64_t)u[i] * f0 + (int64_t)v[i] * g0;
+            cv += (int64_t)u[i] * f1 + (int64_t)v[i] * g1;
+            nu[i] = (uint32_t)cu; nv[i] = (uint32_t)cv;
+            cu >>= 32; cv >>= 32;
+        }
+        nu[N] = (uint32_t)cu; nv[N] = (uint32_t)cv;
+        uint32_t qu = nu[0] * P::INV, qv = nv[0] * P::INV;
+        int64_t du = 0, dv = 0;
+        /* add q * MOD; the low limb becomes zero and is dropped */
+        uint64_t ku = 0, kv = 0;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            ku += (uint64_t)qu * P::MOD[i] + nu[i];
+            kv += (uint64_t)qv * P::MOD[i] + nv[i];
+            if (i > 0) { u[i - 1] = (uint32_t)ku; v[i - 1] = (uint32_t)kv; }
+            ku >>= 32; kv >>= 32;
+        }
+        /* top limb: signed high word of the combination plus the carry of the addition */
+        du = (int64_t)(int32_t)nu[N] + (int64_t)ku;
+        dv = (int64_t)(int32_t)nv[N] + (int64_t)kv;
+        u[N - 1] = (uint32_t)du; v[N - 1] = (uint32_t)dv;
+        int32_t su = (int32_t)(du >> 32), sv = (int32_t)(dv >> 32);   /* -1, 0 (value in (-q, 2q)) */
+        {   /* bring into [0, q): add q when negative, subtract q when >= q */
+            uint32_t t1[N], t2[N];
+            uint32_t c = 0, bw = 0;
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                uint64_t s1 = (uint64_t)u[i] + P::MOD[i] + c;
+                t1[i] = (uint32_t)s1; c = (uint32_t)(s1 >> 32);
+                uint64_t s2 = (uint64_t)u[i] - P::MOD[i] - bw;
+                t2[i] = (uint32_t)s2; bw = (uint32_t)(s2 >> 63);
+            }
+            bool neg = su < 0, ge = !neg && !bw;
+#pragma unroll
+            for (int i = 0; i < N; ++i) u[i] = neg ? t1[i] : (ge ? t2[i] : u[i]);
+            c = 0; bw = 0;
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                uint64_t s1 = (uint64_t)v[i] + P::MOD[i] + c;
+                t1[i] = (uint32_t)s1; c = (uint32_t)(s1 >> 32);
+                uint64_t s2 = (uint64_t)v[i] - P::MOD[i] - bw;
+                t2[i] = (uint32_t)s2; bw = (uint32_t)(s2 >> 63);
+            }
+            neg = sv < 0; ge = !neg && !bw;
+#pragma unroll
+            for (int i = 0; i < N; ++i) v[i] = neg ? t1[i] : (ge ? t2[i] : v[i]);
+        }
+    }
+    Fe<P> r, fix;
+#pragma unroll
+    for (int i = 0; i < N; ++i) { r.l[i] = v[i]; fix.l[i] = P::GCD_FIX[i]; }
+    return fe_mulx(r, fix);
+}
+
 TC_HD fp_t fp_sqr(const fp_t& a) { return fp_mul(a, a); }
 TC_HD fp_t fp_dbl(const fp_t& a) { return fe_dbl<FpParams>(a); }
 TC_HD fp_t fp_neg(const fp_t& a) { return fe_neg<FpParams>(a); }

@@ -531,7 +531,7 @@ struct BatchNormalize {
             out[i].x = run;                       /* product of z_lo .. z_{i-1} */
             if (!fe_is_zero(in[i].ZZ)) run = fp_mul(run, fp_mul(in[i].ZZ, in[i].ZZZ));
         }
-        fp_t inv = fe_inv<FpParams>(run);          /* run != 0: product of non-zero values */
+        fp_t inv = fe_inv_gcd<FpParams>(run);      /* run != 0: product of non-zero values */
         for (uint64_t i = hi; i-- > lo;) {
             g1_xyzz p = in[i];
             if (fe_is_zero(p.ZZ)) {

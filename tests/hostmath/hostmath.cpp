@@ -21,6 +21,8 @@ void hm_fp_sub(const uint8_t* a, const uint8_t* b, uint8_t* o) { fp_store(o, fp_
 void hm_fp_inv(const uint8_t* a, uint8_t* o) { fp_store(o, fe_inv_fermat<FpParams>(fp_load(a))); }
 void hm_fp_inv_binary(const uint8_t* a, uint8_t* o) { fp_store(o, fe_inv<FpParams>(fp_load(a))); }
 void hm_fr_inv_binary(const uint8_t* a, uint8_t* o) { fr_store(o, fe_inv<FrParams>(fr_load(a))); }
+void hm_fp_inv_gcd(const uint8_t* a, uint8_t* o) { fp_store(o, fe_inv_gcd<FpParams>(fp_load(a))); }
+void hm_fr_inv_gcd(const uint8_t* a, uint8_t* o) { fr_store(o, fe_inv_gcd<FrParams>(fr_load(a))); }
 void hm_fr_mul(const uint8_t* a, const uint8_t* b, uint8_t* o) { fr_store(o, fr_mul(fr_load(a), fr_load(b))); }
 void hm_fr_add(const uint8_t* a, const uint8_t* b, uint8_t* o) { fr_store(o, fr_add(fr_load(a), fr_load(b))); }
 void hm_fr_sub(const uint8_t* a, const uint8_t* b, uint8_t* o) { fr_store(o, fr_sub(fr_load(a), fr_load(b))); }

@@ -64,6 +64,18 @@ def test_fp_fr_arithmetic(hm):
         out = (ctypes.c_uint8 * 32)()
         hm.hm_fr_inv_binary(_b(a, 32), out)
         assert int.from_bytes(bytes(out), "little") == pow(a, -1, R)
+    for fn_p, fn_r in ((hm.hm_fp_inv_gcd, hm.hm_fr_inv_gcd),):
+        edge = [1, 2, 3, (1 << 32), (1 << 62) + 1, (1 << 63) + 5, (1 << 64) - 1, 1 << 64]
+        for a in edge + [P - 1, P - 2, (P - 1) // 2, 1 << 380] + [rng.randrange(1, P) for _ in range(300)] + \
+                [rng.randrange(1, 1 << rng.randrange(1, 381)) for _ in range(300)]:
+            out = (ctypes.c_uint8 * 48)()
+            fn_p(_b(a, 48), out)
+            assert int.from_bytes(bytes(out), "little") == pow(a, -1, P)
+        for a in edge + [R - 1, R - 2, 1 << 254] + [rng.randrange(1, R) for _ in range(300)] + \
+                [rng.randrange(1, 1 << rng.randrange(1, 255)) for _ in range(300)]:
+            out = (ctypes.c_uint8 * 32)()
+            fn_r(_b(a, 32), out)
+            assert int.from_bytes(bytes(out), "little") == pow(a, -1, R)
     for v in (0, 1, -1, 127, -128, 32767, -32768, 2**31 - 1, -(2**31)):
         out = (ctypes.c_uint8 * 32)()
         hm.hm_fr_from_i32(ctypes.c_int32(v), out)
