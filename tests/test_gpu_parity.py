@@ -137,6 +137,23 @@ def test_special_tensors(T, ctx):
         srs.close()
 
 
+def test_degenerate_bucket_loads_at_size(T, ctx):
+    """All terms in one bucket (constant tensor) and two-valued tensors at a size where the engine
+    needs its shrinking passes; closed forms: constant c => [c]G, and linearity for the two-valued one."""
+    shape = (512, 512)
+    pp = pps(shape)
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, 0)
+    try:
+        for c in (7, -32768):
+            got = ctx.commit(srs, to_device(np.full(shape, c, np.int16)), T.TC_I16)
+            assert got == ec.g1_to_bytes(ec.mul(c % R, ec.G1))
+        X = np.full(shape, 3, np.int8)
+        X[::2, :] = -5
+        assert ctx.commit(srs, to_device(X), T.TC_I8) == ec.g1_to_bytes(cbind.commit(pp, X, nthreads=8))
+    finally:
+        srs.close()
+
+
 def test_linearity(T, ctx):
     shape = (9, 21)
     srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, 0)
