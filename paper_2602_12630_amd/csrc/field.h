@@ -301,6 +301,45 @@ __device__ __forceinline__ Fe<P> fe_mul_dev(const Fe<P>& a, const Fe<P>& b) {
     r.l[N - 1] = (uint32_t)A.lo;
     return fe_reduce_once<P>(r, (uint32_t)(A.lo >> 32));
 }
+/* Square: the cross products a_i a_j (i < j) of a column are collected once and doubled. */
+template <class P>
+__device__ __forceinline__ Fe<P> fe_sqr_dev(const Fe<P>& a) {
+    constexpr int N = P::N;
+    Acc96 A{0, 0};
+    uint32_t m[N];
+    Fe<P> r;
+#pragma unroll
+    for (int k = 0; k < 2 * N - 1; ++k) {
+        Acc96 C{0, 0};
+#pragma unroll
+        for (int i = (k < N ? 0 : k - N + 1); i < k - i; ++i) mac_vv(C, a.l[i], a.l[k - i]);
+        {
+            uint32_t c0 = (uint32_t)C.lo, c1 = (uint32_t)(C.lo >> 32), c2 = C.hi;
+            uint32_t d0 = c0 << 1;
+            uint32_t d1 = __builtin_amdgcn_alignbit(c1, c0, 31);
+            uint32_t d2 = __builtin_amdgcn_alignbit(c2, c1, 31);
+            lanemask_t cy;
+            uint32_t lo0 = add_co((uint32_t)A.lo, d0, cy);
+            uint32_t lo1 = addc_co((uint32_t)(A.lo >> 32), d1, cy);
+            A.hi = addc_co(A.hi, d2, cy);
+            A.lo = ((uint64_t)lo1 << 32) | lo0;
+        }
+        if ((k & 1) == 0) mac_vv(A, a.l[k / 2], a.l[k / 2]);
+        if (k < N) {
+#pragma unroll
+            for (int i = 0; i < k; ++i) mac_vs(A, m[i], P::MOD[k - i]);
+            m[k] = (uint32_t)A.lo * P::INV;
+            mac_vs(A, m[k], P::MOD[0]);
+        } else {
+#pragma unroll
+            for (int i = k - N + 1; i < N; ++i) mac_vs(A, m[i], P::MOD[k - i]);
+            r.l[k - N] = (uint32_t)A.lo;
+        }
+        acc_shift(A);
+    }
+    r.l[N - 1] = (uint32_t)A.lo;
+    return fe_reduce_once<P>(r, (uint32_t)(A.lo >> 32));
+}
 #endif
 
 /* plain (non-Montgomery) comparison a > b on limbs */
@@ -334,6 +373,16 @@ __device__ __attribute__((noinline)) fr_t fr_mul_call(u32x4 a0, u32x4 a1, u32x4 
     b.l[0] = b0.x; b.l[1] = b0.y; b.l[2] = b0.z; b.l[3] = b0.w; b.l[4] = b1.x; b.l[5] = b1.y; b.l[6] = b1.z; b.l[7] = b1.w;
     return fe_mul_dev<FrParams>(a, b);
 }
+__device__ __attribute__((noinline)) fp_t fp_sqr_call(u32x4 a0, u32x4 a1, u32x4 a2) {
+    fp_t a;
+    a.l[0] = a0.x; a.l[1] = a0.y; a.l[2] = a0.z; a.l[3] = a0.w; a.l[4] = a1.x; a.l[5] = a1.y; a.l[6] = a1.z; a.l[7] = a1.w;
+    a.l[8] = a2.x; a.l[9] = a2.y; a.l[10] = a2.z; a.l[11] = a2.w;
+    return fe_sqr_dev<FpParams>(a);
+}
+__device__ __forceinline__ fp_t fp_sqr(const fp_t& a) {
+    return fp_sqr_call(u32x4{a.l[0], a.l[1], a.l[2], a.l[3]}, u32x4{a.l[4], a.l[5], a.l[6], a.l[7]},
+                       u32x4{a.l[8], a.l[9], a.l[10], a.l[11]});
+}
 __device__ __forceinline__ fp_t fp_mul(const fp_t& a, const fp_t& b) {
     return fp_mul_call(u32x4{a.l[0], a.l[1], a.l[2], a.l[3]}, u32x4{a.l[4], a.l[5], a.l[6], a.l[7]},
                        u32x4{a.l[8], a.l[9], a.l[10], a.l[11]}, u32x4{b.l[0], b.l[1], b.l[2], b.l[3]},
@@ -346,13 +395,16 @@ __device__ __forceinline__ fr_t fr_mul(const fr_t& a, const fr_t& b) {
 #elif defined(__HIPCC__)
 /* host pass of hipcc: the device bodies exist only in the device pass */
 __device__ fp_t fp_mul(const fp_t& a, const fp_t& b);
+__device__ fp_t fp_sqr(const fp_t& a);
 __device__ fr_t fr_mul(const fr_t& a, const fr_t& b);
 #endif
 #if defined(__HIPCC__)
 __host__ inline fp_t fp_mul(const fp_t& a, const fp_t& b) { return fe_mul<FpParams>(a, b); }
+__host__ inline fp_t fp_sqr(const fp_t& a) { return fe_mul<FpParams>(a, a); }
 __host__ inline fr_t fr_mul(const fr_t& a, const fr_t& b) { return fe_mul<FrParams>(a, b); }
 #else
 inline fp_t fp_mul(const fp_t& a, const fp_t& b) { return fe_mul<FpParams>(a, b); }
+inline fp_t fp_sqr(const fp_t& a) { return fe_mul<FpParams>(a, a); }
 inline fr_t fr_mul(const fr_t& a, const fr_t& b) { return fe_mul<FrParams>(a, b); }
 #endif
 /* overloads that pick the right product for generic helpers */
@@ -689,7 +741,6 @@ TC_HD Fe<P> fe_inv_gcd(const Fe<P>& x) {
     return fe_mulx(r, fix);
 }
 
-TC_HD fp_t fp_sqr(const fp_t& a) { return fp_mul(a, a); }
 TC_HD fp_t fp_dbl(const fp_t& a) { return fe_dbl<FpParams>(a); }
 TC_HD fp_t fp_neg(const fp_t& a) { return fe_neg<FpParams>(a); }
 TC_HD fr_t fr_add(const fr_t& a, const fr_t& b) { return fe_add<FrParams>(a, b); }

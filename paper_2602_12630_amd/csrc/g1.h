@@ -173,6 +173,20 @@ TC_HD g1_xyzz xyzz_mul_affine(const uint32_t* k, int nbits, const g1_affine& p) 
     return acc;
 }
 
+/* [k] P with 4-bit windows, MSB first; `tab` is scratch for the 15 multiples P .. 15 P (nbits a multiple of 4) */
+TC_HD g1_xyzz xyzz_mul_affine_w4(const uint32_t* k, int nbits, const g1_affine& p, g1_xyzz* tab) {
+    tab[0] = xyzz_from_affine(p);
+    tab[1] = xyzz_dbl_affine(p);
+    for (int j = 2; j < 15; ++j) tab[j] = xyzz_madd(tab[j - 1], p);
+    g1_xyzz acc = xyzz_identity();
+    for (int w = nbits / 4 - 1; w >= 0; --w) {
+        for (int i = 0; i < 4; ++i) acc = xyzz_dbl(acc);
+        uint32_t d = (k[w >> 3] >> ((w & 7) * 4)) & 15u;
+        if (d) acc = xyzz_add(acc, tab[d - 1]);
+    }
+    return acc;
+}
+
 /* canonical 96-byte encoding <-> affine Montgomery point */
 TC_HD void affine_to_canonical(const g1_affine& p, uint32_t out[24]) {
     fp_t x = fe_to_plain(p.x), y = fe_to_plain(p.y);

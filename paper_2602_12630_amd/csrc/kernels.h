@@ -957,6 +957,7 @@ struct VerifyTerms {
     const g1_affine* gtable;
     g1_xyzz* out;              /* steps * VERIFY_TERMS */
     uint32_t* ok;              /* per step, preset to 1; cleared on malformed input */
+    g1_xyzz* window_tab;       /* 15 points of scratch per lane */
     TC_DEV void operator()(uint32_t lane) const {
         uint32_t s = lane / VERIFY_TERMS, term = lane % VERIFY_TERMS;
         const VerifyStep& st = steps[s];
@@ -978,7 +979,7 @@ struct VerifyTerms {
                 for (int j = 0; j < 12; ++j) beta.l[j] = GLV_BETA[j];
                 p.x = fp_mul(p.x, beta);
             }
-            r = xyzz_mul_affine(second ? st.k2[i] : st.k1[i], 128, p);
+            r = xyzz_mul_affine_w4(second ? st.k2[i] : st.k1[i], 128, p, window_tab + 15ull * lane);
         }
         out[lane] = r;
     }

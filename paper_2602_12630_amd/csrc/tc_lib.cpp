@@ -871,9 +871,10 @@ static int verify_steps(tc_ctx* ctx, const tc_vk* vk, const std::vector<VerifySt
     WS(d_steps, VerifyStep, n);
     WS(d_terms, g1_xyzz, (uint64_t)VERIFY_TERMS * n);
     WS(d_ok, uint32_t, n);
+    WS(d_tab, g1_xyzz, 15ull * VERIFY_TERMS * n);
     RT(rt::memcpy_h2d(d_steps, steps.data(), sizeof(VerifyStep) * n, ctx->stream));
     RT(rt::launch<256>(n, ctx->stream, Fill32{d_ok, 1u}));
-    RT(rt::launch<64>((uint64_t)VERIFY_TERMS * n, ctx->stream, VerifyTerms{d_steps, ctx->gtable, d_terms, d_ok}));
+    RT(rt::launch<64>((uint64_t)VERIFY_TERMS * n, ctx->stream, VerifyTerms{d_steps, ctx->gtable, d_terms, d_ok, d_tab}));
     RT(rt::launch<64>(n, ctx->stream, VerifyCombine{d_steps, d_terms, d_ok}));
     RT(rt::memcpy_d2h(ok.data(), d_ok, 4ull * n, ctx->stream));
     RT(rt::stream_sync(ctx->stream));
