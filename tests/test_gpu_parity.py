@@ -431,3 +431,99 @@ def test_c3_llama7b_forward_leaf_commitments_and_tree(T, ctx, node_srs):
         tree.close()
         for s in srs_by_shape.values():
             s.close()
+
+
+@pytest.mark.slow
+def test_c4_weight_matrices_streamed(T, ctx, node_srs):
+    """Config 4 at true matrix shapes (Wq/Wk/Wv/Wo 4096x4096, W_gate/W_up 4096x11008, W_down 11008x4096,
+    int8 uniform in [-127,127]), a slice of the layers (TC_TEST_C4_LAYERS, default 2; 32 = the full
+    6.5e9-scalar configuration): every matrix commitment against the oracle's closed form, then the
+    (4,4) tree over the (layers, 7) grid against the oracle's recursive build."""
+    import torch
+
+    layers = int(os.environ.get("TC_TEST_C4_LAYERS", "2"))
+    shapes7 = tc_inputs.c4_shapes()
+    grid = (layers, 7)
+    srs_by_shape = {s: ctx.setup_from_trapdoor(TAU_BYTES, s, 0) for s in set(shapes7)}
+    leaves_d, leaf_srs, want = [], [], []
+    for layer in range(layers):
+        for kind, s in enumerate(shapes7):
+            W = tc_inputs.int8_uniform(s, tc_inputs.tensor_seed(3, 0, layer, kind), -127, 127)
+            leaves_d.append(to_device(W))
+            leaf_srs.append(srs_by_shape[s])
+            want.append(cbind.commit(pps(s), W, nthreads=16))
+    tree = ctx.terkle_build_tensors(node_srs, leaf_srs, leaves_d, [T.TC_I8] * len(leaves_d), grid, tc_inputs.NODE_SHAPE)
+    try:
+        for i, w in enumerate(want):
+            assert tree.node(0, i) == ec.g1_to_bytes(w), "matrix %d" % i
+        otree = terkle.build(pps, [terkle.phi(w) for w in want], grid, tc_inputs.NODE_SHAPE)
+        assert tree.root == ec.g1_to_bytes(otree.root)
+        got = ctx.commit_batch(leaf_srs[:7], leaves_d[:7], [T.TC_I8] * 7)
+        assert got == [ec.g1_to_bytes(w) for w in want[:7]]
+    finally:
+        tree.close()
+        for s in srs_by_shape.values():
+            s.close()
+
+
+@pytest.mark.slow
+def test_c5_batched_requests(T, ctx, node_srs):
+    """Config 5 at true tensor shapes (2048x5120 twice and 2048x13824 per layer, int16 from fp16 N(0,1)),
+    a slice of it (TC_TEST_C5_REQUESTS x TC_TEST_C5_LAYERS, default 2 x 2; 8 x 40 = the full configuration):
+    one tree per request over its (layers, 3) grid, roots against the oracle and different per request,
+    path openings into the tensors verified in one batch on the GPU."""
+    import torch
+
+    cfg = tc_inputs.LLAMA13B
+    requests = int(os.environ.get("TC_TEST_C5_REQUESTS", "2"))
+    layers = int(os.environ.get("TC_TEST_C5_LAYERS", "2"))
+    shapes3 = tc_inputs.c3_shapes(cfg)
+    grid = (layers, 3)
+    srs_by_shape = {s: ctx.setup_from_trapdoor(TAU_BYTES, s, T.TC_SRS_SUFFIX) for s in set(shapes3)}
+    vk = ctx.vk_from_trapdoor(TAU_BYTES)
+    roots, trees, keep = [], [], []
+    paths, proofs, values, proof_roots = [], [], [], []
+    try:
+        for req in range(requests):
+            leaves_q, leaves_d, leaf_srs, want = [], [], [], []
+            for layer in range(layers):
+                for kind, s in enumerate(shapes3):
+                    x = tc_inputs.f16_normal(s, tc_inputs.tensor_seed(4, req, layer, kind))
+                    inv = quantize.inv_scale_for(x)
+                    qv = quantize.quantize_f16(x, inv)
+                    dq = torch.empty(x.size, dtype=torch.int16, device="cuda")
+                    ctx.encode_tensor(to_device(x.view(np.int16)), T.TC_F16, x.size, float(inv), dq)
+                    leaves_q.append(qv)
+                    leaves_d.append(dq)
+                    leaf_srs.append(srs_by_shape[s])
+                    want.append(cbind.commit(pps(s), qv, nthreads=16))
+            tree = ctx.terkle_build_tensors(node_srs, leaf_srs, leaves_d, [T.TC_I16] * len(leaves_d), grid, tc_inputs.NODE_SHAPE)
+            trees.append(tree)
+            keep.append(leaves_d)
+            for i, w in enumerate(want):
+                assert tree.node(0, i) == ec.g1_to_bytes(w)
+            otree = terkle.build(pps, [terkle.phi(w) for w in want], grid, tc_inputs.NODE_SHAPE)
+            assert tree.root == ec.g1_to_bytes(otree.root)
+            roots.append(tree.root)
+            rng = np.random.default_rng(tc_inputs.tensor_seed(4, req) + 999)
+            for _ in range(2):
+                leaf = (int(rng.integers(0, layers)), int(rng.integers(0, 3)))
+                flat = leaf[0] * 3 + leaf[1]
+                inner = tuple(int(rng.integers(0, d)) for d in shapes3[flat % 3])
+                proof = tree.open(leaf, inner)
+                yo, po = tc.open_(pps(shapes3[flat % 3]), leaves_q[flat], inner)
+                tail = b"".join(ec.g1_to_bytes(p) for p in po) + ec.fr_to_bytes(yo)
+                assert proof[-len(tail):] == tail
+                paths.append(tree.path(leaf, inner))
+                proofs.append(proof)
+                values.append(ec.fr_to_bytes(int(leaves_q[flat][inner]) % R))
+                proof_roots.append(tree.root)
+        assert len(set(roots)) == requests
+        assert ctx.verify_paths_batch(vk, paths, proof_roots, values, proofs) == [True] * len(paths)
+        if requests > 1:   # a proof of request 0 does not verify against the root of request 1
+            assert not ctx.verify_path(vk, paths[0], roots[1], values[0], proofs[0])
+    finally:
+        for t in trees:
+            t.close()
+        for s in srs_by_shape.values():
+            s.close()
