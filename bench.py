@@ -32,6 +32,9 @@ MADS_PER_FP_MUL = 300
 # Integer-ALU peak for this instruction mix: v_mad_u64_u32 issues at half the full vector rate
 # on gfx950 (measured: 33 of 64 lanes/clk/CU): 256 CU x 4 SIMD x 16 lanes x 2.4 GHz / 2.
 PEAK_MADS_PER_S = 256 * 4 * 16 * 2.4e9 / 2
+# HBM bytes moved by one AccAffine launch at this workload (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
+# 256 MiB copy kernel; the runs and the scale factors are in profiles/c2_hbm_traffic_pmc.txt)
+ACC_AFFINE_TRAFFIC_BYTES = 4.911e8
 
 
 def hip_event_timer():
@@ -153,6 +156,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--openings", type=int, default=8)
     ap.add_argument("--no-c3", action="store_true", help="skip the LLaMA2-7B-shaped forward (second half of the metric)")
+    ap.add_argument("--calibrate-copy", action="store_true", help="also run one plain copy kernel of 256 MiB "
+                    "(reference dispatch for scaling the HBM byte counters of a rocprofv3 --pmc run)")
     ap.add_argument("--serial", action="store_true", help="run the flat commitment and the tree build one after the other "
                     "on one stream instead of concurrently on two")
     args = ap.parse_args()
@@ -195,6 +200,13 @@ def main():
     side_stream = torch.cuda.Stream()
     ctx2 = T.Context(0, side_stream.cuda_stream, lib)
     import threading
+
+    if args.calibrate_copy:
+        cal_src = torch.zeros(128 * 1024 * 1024, dtype=torch.int16, device="cuda")
+        cal_dst = torch.empty_like(cal_src)
+        ctx.encode_tensor(cal_src, T.TC_I16, cal_src.numel(), 1.0, cal_dst)      # Copy16: 256 MiB read, 256 MiB written
+        ctx.sync()
+        del cal_src, cal_dst
 
     hip = hip_event_timer()
     phases = {"encode": Events(hip), "commit": Events(hip), "tree": Events(hip), "open": Events(hip), "verify": Events(hip)}
@@ -287,7 +299,8 @@ def main():
         "phase_ms": phase_ms,
         "commit_only_elements_per_s": n / (commit_ms * 1e-3),
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_MADS_PER_S / 1e12,
-                     "unit": "T 32x32->64 multiply-add/s", "frac": achieved / PEAK_MADS_PER_S, "traffic": None,
+                     "unit": "T 32x32->64 multiply-add/s", "frac": achieved / PEAK_MADS_PER_S, "traffic": ACC_AFFINE_TRAFFIC_BYTES,
+                     "traffic_unit": "HBM bytes per launch (fetch + write)",
                      "kernel": "AccAffine (bucket accumulation of tc_commit)", "kernel_ms": kern_ms,
                      "launches": acc_launches, "mixed_additions_per_launch": nonzero,
                      "node_commit_kernel_ms": node_ms / max(node_launches, 1)},

@@ -497,6 +497,9 @@ def test_c5_batched_requests(T, ctx, node_srs):
                     leaves_d.append(dq)
                     leaf_srs.append(srs_by_shape[s])
                     want.append(cbind.commit(pps(s), qv, nthreads=16))
+                if layer % 8 == 7:
+                    print("config 5: request %d layer %d" % (req, layer), flush=True)
+            print("config 5: request %d inputs and oracle commitments ready" % req, flush=True)
             tree = ctx.terkle_build_tensors(node_srs, leaf_srs, leaves_d, [T.TC_I16] * len(leaves_d), grid, tc_inputs.NODE_SHAPE)
             trees.append(tree)
             keep.append(leaves_d)
