@@ -19,7 +19,8 @@
 
 namespace tc {
 
-enum { DT_I8 = 1, DT_I16 = 2, DT_FR = 3, DT_F16 = 4 };
+enum { DT_I8 = 1, DT_I16 = 2, DT_FR = 3, DT_F16 = 4,
+       DT_DIFF8 = 5, DT_DIFF16 = 6 /* internal: difference of two int8 / int16 arrays, two 9-bit signed digits */ };
 
 struct alignas(16) fr_plain {           /* canonical (non-Montgomery) Fr value, 8 limbs */
     uint32_t l[8];
@@ -98,7 +99,18 @@ TC_HD int32_t fr_window_digit(const uint32_t* v, int w, int c, uint32_t& carry) 
 }
 
 TC_HD int32_t small_scalar(const void* s, int dtype, uint64_t i) {
-    return dtype == DT_I8 ? (int32_t)((const int8_t*)s)[i] : (int32_t)((const int16_t*)s)[i];
+    return (dtype == DT_I8 || dtype == DT_DIFF8) ? (int32_t)((const int8_t*)s)[i] : (int32_t)((const int16_t*)s)[i];
+}
+/* window digit of a small magnitude (at most 17 bits), same recoding as fr_window_digit */
+TC_HD int32_t small_window_digit(uint32_t mag, int w, int c, uint32_t& carry) {
+    uint32_t raw = ((mag >> (w * c)) & ((1u << c) - 1u)) + carry;
+    uint32_t half = 1u << (c - 1);
+    if (raw > half) {
+        carry = 1;
+        return (int32_t)raw - (int32_t)(1u << c);
+    }
+    carry = 0;
+    return (int32_t)raw;
 }
 
 /* ---- MSM: count, scatter --------------------------------------------------------- */
@@ -157,33 +169,44 @@ struct MsmScatter {
  * adds the global bucket starts and hands out positions with LDS atomics. */
 struct TileProblem {
     const void* scalars;
+    const void* sub;          /* optional subtrahend array (same element type): value = scalars[i] - sub[i] */
     uint64_t n;
     uint32_t tile;            /* terms per workgroup */
 };
-template <int NB>
+TC_HD int32_t tile_value(const TileProblem& P, int dtype, uint64_t i) {
+    int32_t v = small_scalar(P.scalars, dtype, i);
+    if (P.sub) v -= small_scalar(P.sub, dtype, i);
+    return v;
+}
+template <int NBK>            /* keys per problem = windows * buckets per window */
 struct CountTile {
     static constexpr int BLOCK = 1024;
     static constexpr int PHASES = 3;
-    static constexpr size_t LDS_BYTES = NB * sizeof(uint32_t);
+    static constexpr size_t LDS_BYTES = NBK * sizeof(uint32_t);
     const TileProblem* prob;
-    int dtype;
+    int dtype, W, c;
     uint32_t n_wg;            /* tiles per problem */
-    uint32_t* M;              /* problems * n_wg * NB */
+    uint32_t* M;              /* problems * n_wg * NBK */
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         uint32_t* hist = (uint32_t*)lds;
         uint32_t p = wg / n_wg, tl = wg % n_wg;
+        uint32_t nb = (uint32_t)NBK / (uint32_t)W;
         if (ph == 0) {
-            for (uint32_t k = lane; k < (uint32_t)NB; k += BLOCK) hist[k] = 0;
+            for (uint32_t k = lane; k < (uint32_t)NBK; k += BLOCK) hist[k] = 0;
         } else if (ph == 1) {
             const TileProblem P = prob[p];
             uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
             for (uint64_t i = lo + lane; i < hi; i += BLOCK) {
-                int32_t d = small_scalar(P.scalars, dtype, i);
-                if (d) atomic_add_u32(&hist[(uint32_t)(d < 0 ? -d : d) - 1u], 1u);
+                int32_t v = tile_value(P, dtype, i);
+                uint32_t mag = (uint32_t)(v < 0 ? -v : v), carry = 0;
+                for (int w = 0; w < W; ++w) {
+                    int32_t d = W == 1 ? (int32_t)mag : small_window_digit(mag, w, c, carry);
+                    if (d) atomic_add_u32(&hist[(uint32_t)w * nb + (uint32_t)(d < 0 ? -d : d) - 1u], 1u);
+                }
             }
         } else {
-            uint32_t* row = M + (uint64_t)wg * NB;
-            for (uint32_t k = lane; k < (uint32_t)NB; k += BLOCK) row[k] = hist[k];
+            uint32_t* row = M + (uint64_t)wg * NBK;
+            for (uint32_t k = lane; k < (uint32_t)NBK; k += BLOCK) row[k] = hist[k];
         }
     }
 };
@@ -203,32 +226,38 @@ struct TileColumnScan {       /* lane = (problem, key) */
         cnt[t] = off;
     }
 };
-template <int NB>
+template <int NBK>
 struct ScatterTile {
     static constexpr int BLOCK = 1024;
     static constexpr int PHASES = 2;
-    static constexpr size_t LDS_BYTES = NB * sizeof(uint32_t);
+    static constexpr size_t LDS_BYTES = NBK * sizeof(uint32_t);
     const TileProblem* prob;
-    int dtype;
+    int dtype, W, c;
     uint32_t n_wg;
     const uint32_t* M;
-    const uint32_t* start;    /* global bucket starts, problems * NB (+1) */
+    const uint32_t* start;    /* global bucket starts, problems * NBK (+1) */
     uint32_t* sorted;
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         uint32_t* cur = (uint32_t*)lds;
         uint32_t p = wg / n_wg, tl = wg % n_wg;
+        uint32_t nb = (uint32_t)NBK / (uint32_t)W;
         if (ph == 0) {
-            const uint32_t* row = M + (uint64_t)wg * NB;
-            const uint32_t* st = start + (uint64_t)p * NB;
-            for (uint32_t k = lane; k < (uint32_t)NB; k += BLOCK) cur[k] = st[k] + row[k];
+            const uint32_t* row = M + (uint64_t)wg * NBK;
+            const uint32_t* st = start + (uint64_t)p * NBK;
+            for (uint32_t k = lane; k < (uint32_t)NBK; k += BLOCK) cur[k] = st[k] + row[k];
         } else {
             const TileProblem P = prob[p];
             uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
             for (uint64_t i = lo + lane; i < hi; i += BLOCK) {
-                int32_t d = small_scalar(P.scalars, dtype, i);
-                if (d) {
-                    uint32_t pos = atomic_add_u32(&cur[(uint32_t)(d < 0 ? -d : d) - 1u], 1u);
-                    sorted[pos] = (uint32_t)i | (d < 0 ? 0x80000000u : 0u);
+                int32_t v = tile_value(P, dtype, i);
+                uint32_t mag = (uint32_t)(v < 0 ? -v : v), carry = 0;
+                for (int w = 0; w < W; ++w) {
+                    int32_t d = W == 1 ? (int32_t)mag : small_window_digit(mag, w, c, carry);
+                    if (d) {
+                        uint32_t pos = atomic_add_u32(&cur[(uint32_t)w * nb + (uint32_t)(d < 0 ? -d : d) - 1u], 1u);
+                        bool negative = (d < 0) != (v < 0);
+                        sorted[pos] = (uint32_t)i | (negative ? 0x80000000u : 0u);
+                    }
                 }
             }
         }
@@ -816,24 +845,107 @@ struct QuotientRows {        /* lane (k, t), k != kap */
         for (int i = 0; i < 8; ++i) q[(uint64_t)k * inner + t].l[i] = plain.l[i];
     }
 };
-struct QuotientKappaRow {    /* lane t */
-    uint32_t d, kap;
+/* q[kap, t] = -(1/beta_kap) sum_{k != kap} beta_k q[k, t], in two steps so that a single line (inner = 1)
+ * of thousands of entries is not one serial chain: lane (chunk, t) sums a chunk of k's, then lane t
+ * adds the chunk sums. */
+struct QuotientKappaPartial {
+    uint32_t d, kap, chunks;
     uint64_t inner;
     AxisTables ax;
-    fr_plain* q;
-    TC_DEV void operator()(uint32_t t) const {
+    const fr_plain* q;
+    fr_t* partial;             /* chunks * inner, Montgomery */
+    TC_DEV void operator()(uint32_t lane) const {
+        uint32_t ch = (uint32_t)(lane / inner);
+        uint64_t t = lane % inner;
+        uint32_t per = (d + chunks - 1) / chunks;
+        uint32_t k0 = ch * per, k1 = k0 + per < d ? k0 + per : d;
         fr_t acc = fe_zero<FrParams>();
-        for (uint32_t k = 0; k < d; ++k) {
+        for (uint32_t k = k0; k < k1; ++k) {
             if (k == kap) continue;
             fr_t qv = fe_from_limbs<FrParams>(q[(uint64_t)k * inner + t].l);
             acc = fr_add(acc, fr_mul(ax.beta[k], qv));
         }
+        partial[(uint64_t)ch * inner + t] = acc;
+    }
+};
+struct QuotientKappaRow {    /* lane t */
+    uint32_t kap, chunks;
+    uint64_t inner;
+    AxisTables ax;
+    const fr_t* partial;
+    fr_plain* q;
+    TC_DEV void operator()(uint32_t t) const {
+        fr_t acc = partial[t];
+        for (uint32_t ch = 1; ch < chunks; ++ch) acc = fr_add(acc, partial[(uint64_t)ch * inner + t]);
         acc = fr_neg(fr_mul(acc, ax.beta_inv[kap]));
         fr_t plain = fe_to_plain(acc);
 #pragma unroll
         for (int i = 0; i < 8; ++i) q[(uint64_t)kap * inner + t].l[i] = plain.l[i];
     }
 };
+/* Open along an axis with many lines per row (a leading axis of a large tensor), small-integer data:
+ *   pi = sum_{k != kap} c_k R_k + sum_t q[kap, t] S[kap, t],   c_k = 1 / (zeta_k - zeta_kap),
+ *   R_k = sum_t (T[k, t] - T[kap, t]) S[k, t]   (one small-scalar problem per row, 17-bit numerators),
+ * so the bulk of the work is two 9-bit digits per entry instead of sixteen 16-bit windows. */
+struct RowWeights {            /* lane j: plain c_k for the j-th row other than kap */
+    AxisTables ax;
+    uint32_t kap;
+    fr_plain* out;
+    TC_DEV void operator()(uint32_t j) const {
+        uint32_t k = j < kap ? j : j + 1;
+        uint32_t dist = k > kap ? k - kap : kap - k;
+        fr_t c = ax.inv_int[dist];
+        if (k < kap) c = fr_neg(c);
+        fr_t plain = fe_to_plain(c);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[j].l[i] = plain.l[i];
+    }
+};
+struct KappaWeights {          /* lane k: beta_k c_k in Montgomery form (0 for k = kap) */
+    AxisTables ax;
+    uint32_t kap;
+    fr_t* out;
+    TC_DEV void operator()(uint32_t k) const {
+        if (k == kap) { out[k] = fe_zero<FrParams>(); return; }
+        uint32_t dist = k > kap ? k - kap : kap - k;
+        fr_t w = fr_mul(ax.beta[k], ax.inv_int[dist]);
+        out[k] = k < kap ? fr_neg(w) : w;
+    }
+};
+struct KappaRowDirect {        /* lane t: q[kap, t] = -(1/beta_kap) sum_{k != kap} beta_k c_k (T[k,t] - T[kap,t]) */
+    const void* scalars;
+    int dtype;
+    uint64_t offset;
+    uint32_t d, kap;
+    uint64_t inner;
+    AxisTables ax;
+    const fr_t* wk;            /* KappaWeights */
+    fr_plain* q;               /* inner values */
+    TC_DEV void operator()(uint32_t t) const {
+        int32_t gk = small_scalar(scalars, dtype, offset + (uint64_t)kap * inner + t);
+        fr_t acc = fe_zero<FrParams>();
+        for (uint32_t k = 0; k < d; ++k) {
+            int32_t num = small_scalar(scalars, dtype, offset + (uint64_t)k * inner + t) - gk;
+            if (!num || k == kap) continue;
+            acc = fr_add(acc, fr_mul(wk[k], fe_from_i32<FrParams>(num)));
+        }
+        acc = fr_neg(fr_mul(acc, ax.beta_inv[kap]));
+        fr_t plain = fe_to_plain(acc);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) q[t].l[i] = plain.l[i];
+    }
+};
+struct FillIdentity {
+    g1_xyzz* out;
+    TC_DEV void operator()(uint32_t t) const { out[t] = xyzz_identity(); }
+};
+struct AddTwo {
+    const g1_xyzz* a;
+    const g1_xyzz* b;
+    g1_xyzz* out;
+    TC_DEV void operator()(uint32_t t) const { out[t] = xyzz_add(a[t], b[t]); }
+};
+
 /* y = e(T[f]) as canonical bytes */
 struct FetchScalar {
     const void* scalars;

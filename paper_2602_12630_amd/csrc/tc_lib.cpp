@@ -564,10 +564,11 @@ static int scan_counts(tc_ctx* ctx, const uint32_t* cnt, uint32_t n, uint32_t L,
 
 /* sum_k k B_k for every window of `bucket` (W windows of nb buckets) -> wsum[W] */
 static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb, g1_xyzz* wsum) {
-    if (nb == 128) {
+    if (nb == 128 || nb == 256) {
         WS(w1, g1_xyzz, (uint32_t)W);
         WS(s1, g1_xyzz, (uint32_t)W);
-        RT((launch_coop<128>((uint32_t)W, ctx->stream, WeightedBlockSum<128>{bucket, (uint32_t)W * nb, w1, s1, nullptr, 0})));
+        if (nb == 128) RT((launch_coop<128>((uint32_t)W, ctx->stream, WeightedBlockSum<128>{bucket, (uint32_t)W * nb, w1, s1, nullptr, 0})));
+        else RT((launch_coop<256>((uint32_t)W, ctx->stream, WeightedBlockSum<256>{bucket, (uint32_t)W * nb, w1, s1, nullptr, 0})));
         RT(rt::launch<64>((uint32_t)W, ctx->stream, WindowFinish{w1, nullptr, nullptr, 1, 0, wsum}));
         return TC_OK;
     }
@@ -589,10 +590,12 @@ struct MsmProblem {
     const g1_affine* pts;
     const void* scalars;
     uint64_t n;
+    const void* sub = nullptr;     /* DT_DIFF8 / DT_DIFF16: value = scalars[i] - sub[i] */
 };
 static void msm_config(int dtype, uint64_t n, int* W, int* c) {
     if (dtype == TC_I8) { *W = 1; *c = 8; }
     else if (dtype == TC_I16) { *W = 1; *c = 16; }
+    else if (dtype == DT_DIFF8 || dtype == DT_DIFF16) { *W = 2; *c = 9; }
     else { *c = n >= 32768 ? 16 : 8; *W = 256 / *c; }
 }
 /* `count` problems of one scalar type and window plan, run through shared launches: the buckets of
@@ -635,26 +638,30 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     }
 
     uint32_t max_count = 0;        /* largest bucket: fixes how many shrinking passes are needed */
-    if (W == 1) {
-        /* one digit per term: tile histograms in LDS, no global atomics */
+    if (dtype != TC_FR) {
+        /* small scalars (one or two digits per term): tile histograms in LDS, no global atomics */
         uint32_t n_wg = (uint32_t)std::min<uint64_t>(256, std::max<uint64_t>(8, 4096 / (uint64_t)count));
         std::vector<TileProblem> h_prob(count);
         for (int p = 0; p < count; ++p) {
             h_prob[p].scalars = prob[p].scalars;
+            h_prob[p].sub = prob[p].sub;
             h_prob[p].n = prob[p].n;
             h_prob[p].tile = (uint32_t)((prob[p].n + n_wg - 1) / n_wg);
         }
         WS(d_prob, TileProblem, (uint32_t)count);
-        WS(M, uint32_t, (uint64_t)count * n_wg * nb);
+        WS(M, uint32_t, (uint64_t)count * n_wg * nbk_pp);
         RT(rt::memcpy_h2d(d_prob, h_prob.data(), sizeof(TileProblem) * (size_t)count, ctx->stream));
         uint32_t groups = (uint32_t)count * n_wg;
-        if (nb == 128) RT((launch_coop<1024>(groups, ctx->stream, CountTile<128>{d_prob, dtype, n_wg, M})));
-        else RT((launch_coop<1024>(groups, ctx->stream, CountTile<32768>{d_prob, dtype, n_wg, M})));
-        RT(rt::launch<256>(nbk, ctx->stream, TileColumnScan{nb, n_wg, M, cnt}));
+        if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, CountTile<128>{d_prob, dtype, W, c, n_wg, M})));
+        else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, CountTile<512>{d_prob, dtype, W, c, n_wg, M})));
+        else if (nbk_pp == 32768) RT((launch_coop<1024>(groups, ctx->stream, CountTile<32768>{d_prob, dtype, W, c, n_wg, M})));
+        else return fail(ctx, TC_ERR_STATE, "internal: unsupported key count");
+        RT(rt::launch<256>(nbk, ctx->stream, TileColumnScan{nbk_pp, n_wg, M, cnt}));
         TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, nullptr, tot_a, tot_b, tot_max));
         RT(rt::memcpy_d2h(&max_count, tot_max + nchunks, 4, ctx->stream));
-        if (nb == 128) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<128>{d_prob, dtype, n_wg, M, start, sorted})));
-        else RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<32768>{d_prob, dtype, n_wg, M, start, sorted})));
+        if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<128>{d_prob, dtype, W, c, n_wg, M, start, sorted})));
+        else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<512>{d_prob, dtype, W, c, n_wg, M, start, sorted})));
+        else RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<32768>{d_prob, dtype, W, c, n_wg, M, start, sorted})));
     } else {
         RT(rt::launch<256>(nbk, ctx->stream, Fill32{cnt, 0u}));
         for (int p = 0; p < count; ++p)
@@ -770,24 +777,133 @@ extern "C" int tc_commit(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, 
 /* Open                                                                                    */
 /* ======================================================================================= */
 /* proof elements as XYZZ on the device (pi[0..m)), opened value as canonical Fr on the device */
+/* One opening request: tensor, position. */
+struct OpenSpec {
+    const tc_srs* srs;
+    const void* scalars;
+    int dtype;
+    uint32_t kappa[4];
+};
+
+/* Openings of `count` tensors at once.  pi: count * 4 slots (m_i used), y: count values.
+ * Every axis of every opening ends in full-width MSMs (quotient values against a suffix table, or the
+ * row sums weighted by 1 / (zeta_k - zeta_kap)); all of them run through ONE list of problems so
+ * that their window combinations (a chain of ~250 doublings each) proceed side by side.  Leading axes of
+ * large small-integer tensors first go by rows: R_k = sum_t (T[k,t] - T[kap,t]) S[k,t] for every row
+ * k != kap, two 9-bit digits per entry, all rows of all openings in shared launches. */
+static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xyzz* pi, fr_plain* y) {
+    struct AxisJob {
+        int open, axis;
+        bool by_rows;
+        uint64_t offset, inner, na;
+        uint32_t d, kap;
+        size_t row0;        /* first row problem (by_rows) */
+        int fr0;            /* first full-width problem */
+    };
+    std::vector<AxisJob> jobs;
+    std::vector<MsmProblem> row_prob;
+    std::vector<int> row_dtype;
+    for (int o = 0; o < count; ++o) {
+        const tc_srs* srs = spec[o].srs;
+        uint64_t offset = 0;
+        for (int a = 0; a < srs->m; ++a) {
+            AxisJob J;
+            J.open = o; J.axis = a;
+            J.na = srs->n[a]; J.d = srs->shape[a]; J.inner = J.na / J.d; J.kap = spec[o].kappa[a]; J.offset = offset;
+            if (J.na > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "slice too large");
+            int dt = spec[o].dtype;
+            J.by_rows = (dt == TC_I8 || dt == TC_I16) && J.d >= 2 && J.inner >= 2 && J.na >= 16384;
+            J.row0 = row_prob.size(); J.fr0 = 0;
+            if (J.by_rows) {
+                size_t esz = dtype_size(dt);
+                const uint8_t* base = (const uint8_t*)spec[o].scalars + offset * esz;
+                for (uint32_t j = 0; j + 1 < J.d; ++j) {
+                    uint32_t k = j < J.kap ? j : j + 1;
+                    MsmProblem P;
+                    P.pts = srs->pts[a] + (uint64_t)k * J.inner;
+                    P.scalars = base + (uint64_t)k * J.inner * esz;
+                    P.sub = base + (uint64_t)J.kap * J.inner * esz;
+                    P.n = J.inner;
+                    row_prob.push_back(P);
+                    row_dtype.push_back(dt == TC_I8 ? DT_DIFF8 : DT_DIFF16);
+                }
+            }
+            jobs.push_back(J);
+            offset += (uint64_t)J.kap * J.inner;
+        }
+        RT(rt::launch<64>(1, ctx->stream, FetchScalar{spec[o].scalars, spec[o].dtype, offset, y + o}));
+    }
+    /* rows: all R_k of all openings */
+    g1_xyzz* Rk = nullptr;
+    g1_affine* RkA = nullptr;
+    if (!row_prob.empty()) {
+        Rk = ws_array<g1_xyzz>(ctx, row_prob.size());
+        RkA = ws_array<g1_affine>(ctx, row_prob.size());
+        if (!Rk || !RkA) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed");
+        TRY(msm_engine_list(ctx, (int)row_prob.size(), row_prob.data(), row_dtype.data(), Rk));
+        TRY(normalize(ctx, Rk, row_prob.size(), RkA));
+    }
+    /* full-width problems */
+    std::vector<MsmProblem> fr_prob;
+    for (auto& J : jobs) {
+        const tc_srs* srs = spec[J.open].srs;
+        const void* sc = spec[J.open].scalars;
+        int dt = spec[J.open].dtype;
+        J.fr0 = (int)fr_prob.size();
+        if (J.by_rows) {
+            uint32_t rows = J.d - 1;
+            WS(ck, fr_plain, rows);
+            WS(wk, fr_t, J.d);
+            WS(qk, fr_plain, J.inner);
+            RT(rt::launch<64>(rows, ctx->stream, RowWeights{srs->ax[J.axis], J.kap, ck}));
+            RT(rt::launch<64>(J.d, ctx->stream, KappaWeights{srs->ax[J.axis], J.kap, wk}));
+            RT(rt::launch<64>(J.inner, ctx->stream, KappaRowDirect{sc, dt, J.offset, J.d, J.kap, J.inner, srs->ax[J.axis], wk, qk}));
+            MsmProblem A, B;
+            A.pts = RkA + J.row0; A.scalars = ck; A.n = rows;
+            B.pts = srs->pts[J.axis] + (uint64_t)J.kap * J.inner; B.scalars = qk; B.n = J.inner;
+            fr_prob.push_back(A);
+            fr_prob.push_back(B);
+        } else {
+            WS(q, fr_plain, J.na);
+            uint32_t chunks = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(64, 8192 / std::max<uint64_t>(J.inner, 1)));
+            chunks = std::min<uint32_t>(chunks, J.d);
+            WS(part, fr_t, (uint64_t)chunks * J.inner);
+            RT(rt::launch<128>(J.na, ctx->stream, QuotientRows{sc, dt, J.offset, J.d, J.kap, J.inner, srs->ax[J.axis], q}));
+            RT(rt::launch<128>((uint64_t)chunks * J.inner, ctx->stream, QuotientKappaPartial{J.d, J.kap, chunks, J.inner, srs->ax[J.axis], q, part}));
+            RT(rt::launch<128>(J.inner, ctx->stream, QuotientKappaRow{J.kap, chunks, J.inner, srs->ax[J.axis], part, q}));
+            MsmProblem A;
+            A.pts = srs->pts[J.axis]; A.scalars = q; A.n = J.na;
+            fr_prob.push_back(A);
+        }
+    }
+    /* sort the full-width problems by window plan so that equal plans are neighbours and share launches */
+    std::vector<int> order(fr_prob.size());
+    for (size_t i = 0; i < order.size(); ++i) order[i] = (int)i;
+    std::stable_sort(order.begin(), order.end(), [&](int x, int z) { return (fr_prob[x].n >= 32768) < (fr_prob[z].n >= 32768); });
+    std::vector<MsmProblem> sorted_prob(fr_prob.size());
+    std::vector<int> fr_dtype(fr_prob.size(), TC_FR);
+    for (size_t i = 0; i < order.size(); ++i) sorted_prob[i] = fr_prob[order[i]];
+    WS(res_sorted, g1_xyzz, fr_prob.size());
+    WS(res, g1_xyzz, fr_prob.size());
+    TRY(msm_engine_list(ctx, (int)sorted_prob.size(), sorted_prob.data(), fr_dtype.data(), res_sorted));
+    for (size_t i = 0; i < order.size(); ++i)
+        RT(rt::memcpy_d2d(res + order[i], res_sorted + i, sizeof(g1_xyzz), ctx->stream));
+    for (auto& J : jobs) {
+        g1_xyzz* dst = pi + (size_t)J.open * 4 + J.axis;
+        if (J.by_rows) RT(rt::launch<64>(1, ctx->stream, AddTwo{res + J.fr0, res + J.fr0 + 1, dst}));
+        else RT(rt::memcpy_d2d(dst, res + J.fr0, sizeof(g1_xyzz), ctx->stream));
+    }
+    return TC_OK;
+}
+
 static int open_device(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, int dtype, const uint32_t* kappa,
                        g1_xyzz* pi, fr_plain* y) {
-    int m = srs->m;
-    uint64_t offset = 0;
-    for (int a = 0; a < m; ++a) {
-        uint64_t na = srs->n[a];
-        uint32_t d = srs->shape[a];
-        uint64_t inner = na / d;
-        size_t mark = ctx->ws.off;
-        WS(q, fr_plain, na);
-        if (na > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "slice too large");
-        RT(rt::launch<128>(na, ctx->stream, QuotientRows{d_scalars, dtype, offset, d, kappa[a], inner, srs->ax[a], q}));
-        RT(rt::launch<128>(inner, ctx->stream, QuotientKappaRow{d, kappa[a], inner, srs->ax[a], q}));
-        TRY(msm_engine(ctx, srs->pts[a], q, TC_FR, na, pi + a));
-        ctx->ws.off = mark;
-        offset += (uint64_t)kappa[a] * inner;
-    }
-    RT(rt::launch<64>(1, ctx->stream, FetchScalar{d_scalars, dtype, offset, y}));
+    OpenSpec sp;
+    sp.srs = srs; sp.scalars = d_scalars; sp.dtype = dtype;
+    for (int a = 0; a < 4; ++a) sp.kappa[a] = a < srs->m ? kappa[a] : 0;
+    WS(pi4, g1_xyzz, 4);
+    TRY(open_device_batch(ctx, 1, &sp, pi4, y));
+    RT(rt::memcpy_d2d(pi, pi4, sizeof(g1_xyzz) * (size_t)srs->m, ctx->stream));
     return TC_OK;
 }
 
@@ -1310,19 +1426,29 @@ extern "C" int tc_terkle_open_batch(tc_ctx* ctx, const tc_tree* t, int count, co
         RT(rt::memcpy_d2h(h_y.data(), d_y, 32ull * jobs, ctx->stream));
         TRY(points_to_host(ctx, d_pi, jobs * (uint32_t)m, h_pi.data()));
     }
-    /* leaf tensors */
+    /* leaf tensors: all openings in one batch */
     std::vector<std::vector<uint8_t>> leaf_part(count);
     if (t->leaf_kind == TC_LEAF_TENSORS) {
+        std::vector<OpenSpec> specs(count);
         for (int i = 0; i < count; ++i) {
             const tc_srs* ls = t->leaf_srs[P[i].leaf_flat];
-            size_t mk = ctx->ws.off;
-            WS(pi, g1_xyzz, 4);
-            WS(y, fr_plain, 1);
-            TRY(open_device(ctx, ls, t->leaf_scalars[P[i].leaf_flat], t->leaf_dtype[P[i].leaf_flat], P[i].inner, pi, y));
-            leaf_part[i].resize(96 * (size_t)ls->m + 32);
-            RT(rt::memcpy_d2h(leaf_part[i].data() + 96 * (size_t)ls->m, y, 32, ctx->stream));
-            TRY(points_to_host(ctx, pi, (uint32_t)ls->m, leaf_part[i].data()));
-            ctx->ws.off = mk;
+            specs[i].srs = ls;
+            specs[i].scalars = t->leaf_scalars[P[i].leaf_flat];
+            specs[i].dtype = t->leaf_dtype[P[i].leaf_flat];
+            for (int a = 0; a < 4; ++a) specs[i].kappa[a] = a < ls->m ? P[i].inner[a] : 0;
+        }
+        WS(pi, g1_xyzz, 4ull * count);
+        WS(y, fr_plain, (uint32_t)count);
+        RT(rt::launch<64>(4ull * count, ctx->stream, FillIdentity{pi}));     /* slots of unused axes */
+        TRY(open_device_batch(ctx, count, specs.data(), pi, y));
+        std::vector<uint8_t> hy(32ull * count), hp(96ull * 4 * count);
+        RT(rt::memcpy_d2h(hy.data(), y, 32ull * count, ctx->stream));
+        TRY(points_to_host(ctx, pi, 4u * (uint32_t)count, hp.data()));
+        for (int i = 0; i < count; ++i) {
+            int lm = specs[i].srs->m;
+            leaf_part[i].resize(96 * (size_t)lm + 32);
+            memcpy(leaf_part[i].data(), hp.data() + 96ull * 4 * i, 96 * (size_t)lm);
+            memcpy(leaf_part[i].data() + 96 * (size_t)lm, hy.data() + 32ull * i, 32);
         }
     }
     /* child commitments along the paths */

@@ -154,6 +154,32 @@ def test_degenerate_bucket_loads_at_size(T, ctx):
         srs.close()
 
 
+@pytest.mark.parametrize("shape", [(64, 512), (5, 37, 100), (300, 64)])
+def test_open_by_rows_matches_oracle(T, ctx, shape):
+    """Openings of tensors large enough for the row-wise route (two 9-bit digits per entry for the
+    leading axes) against the oracle's closed form; int16 incl. extreme differences, and int8."""
+    pp = pps(shape)
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, T.TC_SRS_SUFFIX)
+    try:
+        X16 = tc_inputs.int16_uniform(shape, 3, -32768, 32767)
+        flat = X16.reshape(shape[0], -1)
+        flat[0, 0], flat[-1, -1] = -32768, 32767
+        flat[1, :] = flat[0, :]
+        X8 = tc_inputs.int8_uniform(shape, 4)
+        vk = ctx.vk_from_trapdoor(TAU_BYTES)
+        for X, dt in ((X16, T.TC_I16), (X8, T.TC_I8)):
+            dX = to_device(X)
+            C = ctx.commit(srs, dX, dt)
+            for kappa in [tuple(0 for _ in shape), tuple(d - 1 for d in shape)] + tc_inputs.opening_positions(shape, 2, 17):
+                y, pi = ctx.open(srs, dX, dt, kappa)
+                yo, po = tc.open_(pp, X, kappa)
+                assert y == ec.fr_to_bytes(yo)
+                assert pi == [ec.g1_to_bytes(p) for p in po]
+                assert ctx.verify(vk, shape, C, kappa, y, pi)
+    finally:
+        srs.close()
+
+
 def test_linearity(T, ctx):
     shape = (9, 21)
     srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, 0)

@@ -103,6 +103,27 @@ def test_emulated_commit_open_verify(emu):
     srs.close()
 
 
+def test_emulated_open_by_rows(emu):
+    """Openings along a leading axis of a larger tensor take the row-wise route (17-bit numerators as two
+    9-bit digits per entry); same bytes as the oracle's closed form."""
+    shape = (8, 2048)
+    pp = pps(shape)
+    srs = emu.setup_from_trapdoor(TAU_BYTES, shape, T.TC_SRS_SUFFIX)
+    try:
+        X16 = tc_inputs.int16_uniform(shape, 3, -32768, 32767)
+        X16[0, 0], X16[7, 2047], X16[3, 77] = -32768, 32767, -32768
+        X16[4, :] = X16[3, :]                                    # a row equal to the opened row: zero numerators
+        X8 = tc_inputs.int8_uniform(shape, 4)
+        for X, dt in ((X16, T.TC_I16), (X8, T.TC_I8)):
+            for kappa in [(3, 77), (0, 0), (7, 2047)]:
+                y, pi = emu.open(srs, X, dt, kappa)
+                yo, po = tc.open_(pp, X, kappa)
+                assert y == ec.fr_to_bytes(yo)
+                assert pi == [ec.g1_to_bytes(p) for p in po]
+    finally:
+        srs.close()
+
+
 def test_emulated_entries_tree(emu, node_srs):
     node, grid = (2, 2), (5, 7)
     X = tc_inputs.int16_uniform(grid, 7)
