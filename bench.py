@@ -32,6 +32,7 @@ MADS_PER_FP_MUL = 300
 # Integer-ALU peak for this instruction mix: v_mad_u64_u32 issues at half the full vector rate
 # on gfx950 (measured: 33 of 64 lanes/clk/CU): 256 CU x 4 SIMD x 16 lanes x 2.4 GHz / 2.
 PEAK_MADS_PER_S = 256 * 4 * 16 * 2.4e9 / 2
+R_MODULUS = 0x73EDA753299D7D483339D80809A1D80553BDA402FFFE5BFEFFFFFFFF00000001      # group order (embedding of negatives)
 # HBM bytes moved by one AccAffine launch at this workload (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # 256 MiB copy kernel; the runs and the scale factors are in profiles/c2_hbm_traffic_pmc.txt)
 ACC_AFFINE_TRAFFIC_BYTES = 4.911e8
@@ -115,7 +116,7 @@ def c3_forward(ctx, T, torch, node_srs, tau, reps=3):
     the (32, 3) grid).  Timed: quantisation of all 96 tensors + 96 leaf commitments + upper levels."""
     cfg = tc_inputs.LLAMA7B
     shapes3 = tc_inputs.c3_shapes(cfg)
-    srs_by_shape = {s: ctx.setup_from_trapdoor(tau, s, 0) for s in set(shapes3)}
+    srs_by_shape = {s: ctx.setup_from_trapdoor(tau, s, T.TC_SRS_SUFFIX) for s in set(shapes3)}
     gen = torch.Generator(device="cuda")
     gen.manual_seed(tc_inputs.tensor_seed(2))
     xs, qs, invs, leaf_srs = [], [], [], []
@@ -129,13 +130,32 @@ def c3_forward(ctx, T, torch, node_srs, tau, reps=3):
     total = sum(x.numel() for x in xs)
     torch.cuda.synchronize()
     times = []
+    grid = (cfg["layers"], 3)
+    rng = np.random.default_rng(tc_inputs.tensor_seed(2) + 999)
+    leaves = [(int(rng.integers(0, grid[0])), int(rng.integers(0, 3))) for _ in range(64)]
+    inners = [tuple(int(rng.integers(0, d)) for d in shapes3[l[1]]) for l in leaves]
+    vk = ctx.vk_from_trapdoor(tau)
+    open_ms = verify_ms = None
     for rep in range(reps + 1):
         t0 = time.perf_counter()
         for x, qv, inv in zip(xs, qs, invs):
             ctx.encode_tensor(x, T.TC_F16, x.numel(), inv, qv)
-        tree = ctx.terkle_build_tensors(node_srs, leaf_srs, qs, [T.TC_I16] * len(qs), (cfg["layers"], 3), tc_inputs.NODE_SHAPE)
+        tree = ctx.terkle_build_tensors(node_srs, leaf_srs, qs, [T.TC_I16] * len(qs), grid, tc_inputs.NODE_SHAPE)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        if rep == reps:
+            # the configuration's 64 random openings down to tensor entries, then their verification
+            t1 = time.perf_counter()
+            proofs = tree.open_batch(leaves, inners)
+            t2 = time.perf_counter()
+            values = [(int(qs[l[0] * 3 + l[1]][i[0] * shapes3[l[1]][1] + i[1]].item()) % R_MODULUS).to_bytes(32, "little")
+                      for l, i in zip(leaves, inners)]
+            paths = [tree.path(l, i) for l, i in zip(leaves, inners)]
+            t3 = time.perf_counter()
+            ok = ctx.verify_paths_batch(vk, paths, [tree.root] * 64, values, proofs)
+            t4 = time.perf_counter()
+            assert all(ok), "C3 openings failed verification"
+            open_ms, verify_ms = (t2 - t1) * 1e3, (t4 - t3) * 1e3
         tree.close()
         if rep:
             times.append(dt * 1e3)
@@ -144,7 +164,9 @@ def c3_forward(ctx, T, torch, node_srs, tau, reps=3):
     times.sort()
     ms = times[len(times) // 2]
     return {"ms": ms, "elements": total, "elements_per_s": total / (ms * 1e-3), "tensors": len(xs), "reps": reps,
-            "workload": "C3: 96 whole-tensor leaves (314 572 800 int16 entries) + 11 upper nodes"}
+            "open_64_paths_ms": open_ms, "verify_64_paths_ms": verify_ms,
+            "workload": "C3: 96 whole-tensor leaves (314 572 800 int16 entries) + 11 upper nodes; then 64 random "
+                        "path openings down to tensor entries and their batch verification"}
 
 
 def main():

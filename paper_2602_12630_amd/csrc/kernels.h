@@ -289,24 +289,52 @@ struct ScanChunkTotals {
         tot_max[ch] = mx;
     }
 };
-struct ScanChunkOffsets {
+struct ScanChunkOffsets {     /* one workgroup: every lane owns a slice of the chunk totals */
+    static constexpr int BLOCK = 1024;
+    static constexpr int PHASES = 3;
+    static constexpr size_t LDS_BYTES = 3 * BLOCK * sizeof(uint32_t);
     uint32_t nchunks;
     uint32_t* tot_a;
     uint32_t* tot_b;
     uint32_t* tot_max;     /* in: per-chunk maxima; out: tot_max[nchunks] = overall maximum */
-    TC_DEV void operator()(uint32_t) const {
-        uint32_t a = 0, b = 0, mx = 0;
-        for (uint32_t i = 0; i < nchunks; ++i) {
-            uint32_t va = tot_a[i], vb = tot_b[i];
-            tot_a[i] = a;
-            tot_b[i] = b;
-            a += va;
-            b += vb;
-            mx = tot_max[i] > mx ? tot_max[i] : mx;
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t, uint8_t* lds) const {
+        uint32_t* sa = (uint32_t*)lds;
+        uint32_t* sb = sa + BLOCK;
+        uint32_t* sm = sb + BLOCK;
+        uint32_t per = (nchunks + BLOCK - 1) / BLOCK;
+        uint32_t lo = lane * per < nchunks ? lane * per : nchunks;
+        uint32_t hi = lo + per < nchunks ? lo + per : nchunks;
+        if (ph == 0) {
+            uint32_t a = 0, b = 0, mx = 0;
+            for (uint32_t i = lo; i < hi; ++i) {
+                a += tot_a[i];
+                b += tot_b[i];
+                mx = tot_max[i] > mx ? tot_max[i] : mx;
+            }
+            sa[lane] = a; sb[lane] = b; sm[lane] = mx;
+        } else if (ph == 1) {
+            if (lane == 0) {
+                uint32_t a = 0, b = 0, mx = 0;
+                for (uint32_t i = 0; i < (uint32_t)BLOCK; ++i) {
+                    uint32_t va = sa[i], vb = sb[i];
+                    sa[i] = a; sb[i] = b;
+                    a += va; b += vb;
+                    mx = sm[i] > mx ? sm[i] : mx;
+                }
+                tot_a[nchunks] = a;
+                tot_b[nchunks] = b;
+                tot_max[nchunks] = mx;
+            }
+        } else {
+            uint32_t a = sa[lane], b = sb[lane];
+            for (uint32_t i = lo; i < hi; ++i) {
+                uint32_t va = tot_a[i], vb = tot_b[i];
+                tot_a[i] = a;
+                tot_b[i] = b;
+                a += va;
+                b += vb;
+            }
         }
-        tot_a[nchunks] = a;
-        tot_b[nchunks] = b;
-        tot_max[nchunks] = mx;
     }
 };
 struct ScanWrite {
@@ -510,6 +538,59 @@ struct RowColFinish {
         g1_xyzz t = xyzz_add(w_rows[w], xyzz_neg(s_rows[w]));
         for (int i = 0; i < 8; ++i) t = xyzz_dbl(t);
         out[w] = xyzz_add(t, w_cols[w]);
+    }
+};
+
+/* sum_k k B_k for a window of 256 buckets seen as a 16 x 16 matrix (k = 16 h + l + 1): row and column
+ * sums first (one addition per bucket and direction), then two weighted sums over 16 elements:
+ *     16 sum_h h R_h + sum_l (l + 1) C_l.
+ * About 3 additions per bucket instead of the 16 of a weighted scan over all 256; one wave per window. */
+struct SmallWindowReduce256 {
+    static constexpr int BLOCK = 64;
+    static constexpr int PHASES = 12;
+    static constexpr size_t LDS_BYTES = 2 * BLOCK * sizeof(g1_xyzz);
+    const g1_xyzz* bucket;      /* windows * 256 */
+    g1_xyzz* out;               /* per window */
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        g1_xyzz* buf0 = (g1_xyzz*)lds;
+        g1_xyzz* buf1 = buf0 + BLOCK;
+        const g1_xyzz* B = bucket + (uint64_t)wg * 256u;
+        uint32_t i = lane & 15u;
+        if (ph == 0) {
+            uint32_t idx = (lane & 31u) >> 1, half = lane & 1u;
+            g1_xyzz acc;
+            if (lane < 32) {                 /* half a row */
+                const g1_xyzz* p = B + idx * 16u + half * 8u;
+                acc = p[0];
+                for (int j = 1; j < 8; ++j) acc = xyzz_add(acc, p[j]);
+            } else {                         /* half a column */
+                const g1_xyzz* p = B + (half * 8u) * 16u + idx;
+                acc = p[0];
+                for (int j = 1; j < 8; ++j) acc = xyzz_add(acc, p[j * 16]);
+            }
+            buf0[lane] = acc;
+        } else if (ph == 1) {
+            if ((lane & 1u) == 0) buf1[(lane < 32 ? 0u : 16u) + ((lane & 31u) >> 1)] = xyzz_add(buf0[lane], buf0[lane + 1]);
+        } else if (ph <= 5) {                /* suffix sums within each family of 16 */
+            int s = ph - 2;
+            g1_xyzz* cur = (s & 1) ? buf0 : buf1;
+            g1_xyzz* nxt = (s & 1) ? buf1 : buf0;
+            uint32_t stride = 1u << s;
+            if (lane < 32) {
+                g1_xyzz v = cur[lane];
+                if (i + stride < 16u) v = xyzz_add(v, cur[lane + stride]);
+                nxt[lane] = v;
+            }
+        } else if (ph == 6) {
+            if (lane == 0) buf0[32] = buf1[0];             /* S_R = sum of the row sums */
+        } else if (ph <= 10) {               /* sum of the suffix sums, in place */
+            uint32_t stride = 1u << (ph - 7);
+            if (lane < 32 && (i & (2 * stride - 1)) == 0) buf1[lane] = xyzz_add(buf1[lane], buf1[lane + stride]);
+        } else if (lane == 0) {
+            g1_xyzz t = xyzz_add(buf1[0], xyzz_neg(buf0[32]));   /* sum_h h R_h */
+            for (int j = 0; j < 4; ++j) t = xyzz_dbl(t);
+            out[wg] = xyzz_add(t, buf1[16]);
+        }
     }
 };
 
@@ -912,6 +993,29 @@ struct KappaWeights {          /* lane k: beta_k c_k in Montgomery form (0 for k
         out[k] = k < kap ? fr_neg(w) : w;
     }
 };
+/* 320-bit accumulator for sums of (small integer) x (Montgomery-form Fr value): no reduction per term */
+struct Wide320 {
+    uint32_t l[10];
+};
+TC_HD void wide_mac(Wide320& acc, const fr_t& w, uint32_t mag) {
+    uint64_t carry = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        uint64_t t = (uint64_t)w.l[i] * mag + acc.l[i] + carry;
+        acc.l[i] = (uint32_t)t;
+        carry = t >> 32;
+    }
+    uint64_t t = (uint64_t)acc.l[8] + carry;
+    acc.l[8] = (uint32_t)t;
+    acc.l[9] += (uint32_t)(t >> 32);
+}
+/* value mod r, keeping the Montgomery factor of the summands: lo R / R + hi R^2 / R = lo + hi 2^256 */
+TC_HD fr_t wide_reduce(const Wide320& a) {
+    fr_t lo, hi, one, r2;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { lo.l[i] = a.l[i]; hi.l[i] = i < 2 ? a.l[8 + i] : 0u; one.l[i] = FrParams::ONE[i]; r2.l[i] = FrParams::R2[i]; }
+    return fr_add(fr_mul(lo, one), fr_mul(hi, r2));
+}
 struct KappaRowDirect {        /* lane t: q[kap, t] = -(1/beta_kap) sum_{k != kap} beta_k c_k (T[k,t] - T[kap,t]) */
     const void* scalars;
     int dtype;
@@ -923,12 +1027,16 @@ struct KappaRowDirect {        /* lane t: q[kap, t] = -(1/beta_kap) sum_{k != ka
     fr_plain* q;               /* inner values */
     TC_DEV void operator()(uint32_t t) const {
         int32_t gk = small_scalar(scalars, dtype, offset + (uint64_t)kap * inner + t);
-        fr_t acc = fe_zero<FrParams>();
+        Wide320 pos, neg;
+#pragma unroll
+        for (int i = 0; i < 10; ++i) { pos.l[i] = 0; neg.l[i] = 0; }
         for (uint32_t k = 0; k < d; ++k) {
             int32_t num = small_scalar(scalars, dtype, offset + (uint64_t)k * inner + t) - gk;
             if (!num || k == kap) continue;
-            acc = fr_add(acc, fr_mul(wk[k], fe_from_i32<FrParams>(num)));
+            if (num > 0) wide_mac(pos, wk[k], (uint32_t)num);
+            else wide_mac(neg, wk[k], (uint32_t)(-num));
         }
+        fr_t acc = fr_sub(wide_reduce(pos), wide_reduce(neg));
         acc = fr_neg(fr_mul(acc, ax.beta_inv[kap]));
         fr_t plain = fe_to_plain(acc);
 #pragma unroll

@@ -557,13 +557,18 @@ static int scan_counts(tc_ctx* ctx, const uint32_t* cnt, uint32_t n, uint32_t L,
                        uint32_t* zero_me, uint32_t* tot_a, uint32_t* tot_b, uint32_t* tot_max) {
     uint32_t nchunks = (n + SCAN_CHUNK - 1) / SCAN_CHUNK;
     RT(rt::launch<64>(nchunks, ctx->stream, ScanChunkTotals{cnt, n, L, tot_a, tot_b, tot_max}));
-    RT(rt::launch<64>(1, ctx->stream, ScanChunkOffsets{nchunks, tot_a, tot_b, tot_max}));
+    RT((launch_coop<ScanChunkOffsets::BLOCK>(1, ctx->stream, ScanChunkOffsets{nchunks, tot_a, tot_b, tot_max})));
     RT(rt::launch<64>(nchunks, ctx->stream, ScanWrite{cnt, n, L, tot_a, tot_b, nchunks, start, lstart, zero_me}));
     return TC_OK;
 }
 
 /* sum_k k B_k for every window of `bucket` (W windows of nb buckets) -> wsum[W] */
 static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb, g1_xyzz* wsum) {
+    if (nb == 256 && W >= 512) {
+        /* many small windows (row problems of openings): throughput matters, not depth */
+        RT((launch_coop<SmallWindowReduce256::BLOCK>((uint32_t)W, ctx->stream, SmallWindowReduce256{bucket, wsum})));
+        return TC_OK;
+    }
     if (nb == 128 || nb == 256) {
         WS(w1, g1_xyzz, (uint32_t)W);
         WS(s1, g1_xyzz, (uint32_t)W);

@@ -122,6 +122,18 @@ def test_emulated_open_by_rows(emu):
                 assert pi == [ec.g1_to_bytes(p) for p in po]
     finally:
         srs.close()
+    # many rows: the bucket reduction of the row problems switches to the 16 x 16 form
+    shape = (260, 64)
+    pp = pps(shape)
+    srs = emu.setup_from_trapdoor(TAU_BYTES, shape, T.TC_SRS_SUFFIX)
+    try:
+        X = tc_inputs.int16_uniform(shape, 6, -32768, 32767)
+        for kappa in [(0, 63), (259, 0), (100, 31)]:
+            y, pi = emu.open(srs, X, T.TC_I16, kappa)
+            yo, po = tc.open_(pp, X, kappa)
+            assert y == ec.fr_to_bytes(yo) and pi == [ec.g1_to_bytes(p) for p in po]
+    finally:
+        srs.close()
 
 
 def test_emulated_entries_tree(emu, node_srs):
