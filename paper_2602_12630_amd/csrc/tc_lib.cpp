@@ -637,10 +637,6 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     const uint64_t target_lanes = 262144;
     uint32_t L1 = (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(4, (items + target_lanes - 1) / target_lanes));
     const uint32_t L2 = 16;
-    if (const char* e = getenv("TC_DEBUG_L1")) {       /* tuning experiments only */
-        int v = atoi(e);
-        if (v >= 1 && v <= 4096) L1 = (uint32_t)v;
-    }
 
     uint32_t max_count = 0;        /* largest bucket: fixes how many shrinking passes are needed */
     if (dtype != TC_FR) {

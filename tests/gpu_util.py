@@ -36,3 +36,22 @@ def serialize_steps(steps):
         if child is not None:
             out += ec.g1_to_bytes(child)
     return out
+
+
+def parse_proof(path, proof):
+    """Library proof bytes -> oracle path steps (kappa, y, [pi], child) and the step shapes, top first."""
+    steps, shapes, off = [], [], 0
+    for s in range(path.n_steps):
+        m = path.m[s]
+        pi = [ec.g1_from_bytes(proof[off + 96 * i : off + 96 * (i + 1)]) for i in range(m)]
+        off += 96 * m
+        y = ec.fr_from_bytes(proof[off : off + 32])
+        off += 32
+        child = None
+        if s < path.n_steps - 1:
+            child = ec.g1_from_bytes(proof[off : off + 96])
+            off += 96
+        steps.append((tuple(path.kappa[s][j] for j in range(m)), y, pi, child))
+        shapes.append(tuple(path.shape[s][j] for j in range(m)))
+    assert off == len(proof)
+    return steps, shapes

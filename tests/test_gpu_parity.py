@@ -12,7 +12,7 @@ from oracle import bls12_381 as ec
 from oracle import cbind, quantize, tc, terkle
 from oracle.bls12_381 import R
 
-from gpu_util import TAU_BYTES, fr_bytes_array, pps, serialize_steps, to_device
+from gpu_util import TAU_BYTES, fr_bytes_array, parse_proof, pps, serialize_steps, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -496,13 +496,16 @@ def test_c4_weight_matrices_streamed(T, ctx, node_srs):
 def test_c5_batched_requests(T, ctx, node_srs):
     """Config 5 at true tensor shapes (2048x5120 twice and 2048x13824 per layer, int16 from fp16 N(0,1)),
     a slice of it (TC_TEST_C5_REQUESTS x TC_TEST_C5_LAYERS, default 2 x 2; 8 x 40 = the full configuration):
-    one tree per request over its (layers, 3) grid, roots against the oracle and different per request,
-    path openings into the tensors verified in one batch on the GPU."""
+    one tree per request over its (layers, 3) grid, roots against the oracle and different per request;
+    per request TC_TEST_C5_OPENINGS path openings (default 8; 128 = the configuration's 1024 in total) made
+    in one batch: two recomputed by the oracle, four more run through the oracle's verifier, all verified in
+    one batch on the GPU."""
     import torch
 
     cfg = tc_inputs.LLAMA13B
     requests = int(os.environ.get("TC_TEST_C5_REQUESTS", "2"))
     layers = int(os.environ.get("TC_TEST_C5_LAYERS", "2"))
+    openings = int(os.environ.get("TC_TEST_C5_OPENINGS", "8"))
     shapes3 = tc_inputs.c3_shapes(cfg)
     grid = (layers, 3)
     srs_by_shape = {s: ctx.setup_from_trapdoor(TAU_BYTES, s, T.TC_SRS_SUFFIX) for s in set(shapes3)}
@@ -535,18 +538,29 @@ def test_c5_batched_requests(T, ctx, node_srs):
             assert tree.root == ec.g1_to_bytes(otree.root)
             roots.append(tree.root)
             rng = np.random.default_rng(tc_inputs.tensor_seed(4, req) + 999)
-            for _ in range(2):
+            leaf_idx, inner_idx = [], []
+            for _ in range(openings):
                 leaf = (int(rng.integers(0, layers)), int(rng.integers(0, 3)))
+                leaf_idx.append(leaf)
+                inner_idx.append(tuple(int(rng.integers(0, d)) for d in shapes3[leaf[1]]))
+            got = tree.open_batch(leaf_idx, inner_idx)
+            for j, (leaf, inner, proof) in enumerate(zip(leaf_idx, inner_idx, got)):
                 flat = leaf[0] * 3 + leaf[1]
-                inner = tuple(int(rng.integers(0, d)) for d in shapes3[flat % 3])
-                proof = tree.open(leaf, inner)
-                yo, po = tc.open_(pps(shapes3[flat % 3]), leaves_q[flat], inner)
-                tail = b"".join(ec.g1_to_bytes(p) for p in po) + ec.fr_to_bytes(yo)
-                assert proof[-len(tail):] == tail
-                paths.append(tree.path(leaf, inner))
+                path = tree.path(leaf, inner)
+                if j < 2:      # the tensor-level opening recomputed by the oracle
+                    yo, po = tc.open_(pps(shapes3[leaf[1]]), leaves_q[flat], inner)
+                    tail = b"".join(ec.g1_to_bytes(p) for p in po) + ec.fr_to_bytes(yo)
+                    assert proof[-len(tail):] == tail
+                elif j < 6:    # the whole path through the oracle's verifier
+                    steps, step_shapes = parse_proof(path, proof)
+                    root_pt = ec.g1_from_bytes(tree.root)
+                    assert terkle.verify_path(pps, root_pt, step_shapes, int(leaves_q[flat][inner]), steps)
+                    assert not terkle.verify_path(pps, root_pt, step_shapes, int(leaves_q[flat][inner]) + 1, steps)
+                paths.append(path)
                 proofs.append(proof)
                 values.append(ec.fr_to_bytes(int(leaves_q[flat][inner]) % R))
                 proof_roots.append(tree.root)
+            print("config 5: request %d: %d openings checked" % (req, openings), flush=True)
         assert len(set(roots)) == requests
         assert ctx.verify_paths_batch(vk, paths, proof_roots, values, proofs) == [True] * len(paths)
         if requests > 1:   # a proof of request 0 does not verify against the root of request 1
