@@ -723,6 +723,29 @@ TC_HD g1_xyzz fb_mul_accumulate(g1_xyzz acc, const g1_affine* table, uint32_t k,
     }
     return acc;
 }
+/* windows 2h and 2h + 1 only: digit_{2h}(v) table[(k, 2h)] + digit_{2h+1}(v) table[(k, 2h + 1)].  The digits are
+ * found first (their carries come from the windows below), so that the two additions sit outside any loop
+ * whose length differs between the lanes of a wave. */
+TC_HD g1_xyzz fb_window_pair(const g1_affine* table, uint32_t k, const uint32_t* v, uint32_t h) {
+    uint32_t carry = 0;
+    int32_t d0 = 0, d1 = 0;
+    for (int w = 0; w <= (int)(2 * h + 1); ++w) {
+        int32_t d = fr_window_digit(v, w, FB_C, carry);
+        if (w == (int)(2 * h)) d0 = d;
+        if (w == (int)(2 * h + 1)) d1 = d;
+    }
+    g1_xyzz acc = xyzz_identity();
+    for (int j = 0; j < 2; ++j) {
+        int32_t d = j ? d1 : d0;
+        g1_affine p = affine_identity();
+        if (d) {
+            p = table[((uint64_t)k * FB_W + 2 * h + j) * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u];
+            if (d < 0) p.y = fp_neg(p.y);
+        }
+        acc = xyzz_madd(acc, p);
+    }
+    return acc;
+}
 /* same for a small signed integer |d| <= 2^15 (one lookup when the window is 16 bits wide) */
 TC_HD g1_xyzz fb_small_accumulate(g1_xyzz acc, const g1_affine* table, uint32_t k, int32_t d) {
     if (!d) return acc;
@@ -832,8 +855,10 @@ struct NodeCommitFr {
         out[t] = acc;
     }
 };
-/* upper levels, arity a power of two <= 64: workgroup of 64 lanes = 64 / B nodes; each lane commits one
- * child, then the B partial sums of a node are added pairwise through LDS. */
+/* upper levels, arity a power of two <= 64: a workgroup is one wave; a lane commits FB_W >> logH consecutive
+ * windows of one child (B << logH <= 64 lanes per node, 64 / (B << logH) nodes per wave), then the partial
+ * sums of a node are added pairwise through LDS.  logH = 0 (one lane per child) does the least work in
+ * total; a level of few nodes is bound by the depth of one lane's work instead and takes logH > 0. */
 template <int BLOCK>
 struct NodeCommitFrCoop {
     static constexpr size_t LDS_BYTES = BLOCK * sizeof(g1_xyzz);
@@ -842,28 +867,43 @@ struct NodeCommitFrCoop {
     const fr_plain* below;
     const g1_affine* table;
     uint64_t n_nodes;
-    int logB;
+    int logB, logH;
     g1_xyzz* out;               /* n_nodes */
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         g1_xyzz* buf = (g1_xyzz*)lds;
+        int logL = logB + logH;
         uint64_t t = (uint64_t)wg * BLOCK + lane;
-        uint64_t a = t >> logB;
-        uint32_t k = (uint32_t)(t & (g.B - 1));
+        uint64_t a = t >> logL;
+        uint32_t r = (uint32_t)(t & ((1u << logL) - 1u));
         if (ph == 0) {
+            uint32_t k = r >> logH, h = r & ((1u << logH) - 1u);
             g1_xyzz acc = xyzz_identity();
             if (a < n_nodes) {
                 int64_t f = child_index(g, a, k);
-                if (f >= 0) acc = fb_mul_accumulate(acc, table, k, below[f].l);
+                if (f >= 0) {
+                    const uint32_t* v = below[f].l;
+                    int per = FB_W >> logH, w0 = (int)h * per;
+                    uint32_t carry = 0;
+                    for (int w = 0; w < w0; ++w) (void)fr_window_digit(v, w, FB_C, carry);     /* carry into the first window */
+                    for (int j = 0; j < per; ++j) {            /* the same trip count in every lane */
+                        int32_t d = fr_window_digit(v, w0 + j, FB_C, carry);
+                        if (d) {
+                            g1_affine p = table[((uint64_t)k * FB_W + w0 + j) * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u];
+                            if (d < 0) p.y = fp_neg(p.y);
+                            acc = xyzz_madd(acc, p);
+                        }
+                    }
+                }
             }
             buf[lane] = acc;
             return;
         }
-        if (ph <= logB) {
+        if (ph <= logL) {
             uint32_t stride = 1u << (ph - 1);
-            if ((k & (2 * stride - 1)) == 0) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
+            if ((r & (2 * stride - 1)) == 0) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
             return;
         }
-        if (ph == logB + 1 && k == 0 && a < n_nodes) out[a] = buf[lane];
+        if (ph == logL + 1 && r == 0 && a < n_nodes) out[a] = buf[lane];
     }
 };
 /* out[i] = sum of in[i * group .. (i + 1) * group) */
@@ -878,15 +918,31 @@ struct SumGroups {
         out[t] = acc;
     }
 };
-/* out[i] = sum of in[off[i] .. off[i + 1]) */
-struct SumSegments {
+/* out[t] = sum of a segment of `in`, a wave per segment: strided partial sums, then pairwise through LDS; the elements of segment
+ * t are in[off[t] * scale .. off[t + 1] * scale) */
+struct SumSegmentsCoop {
+    static constexpr int BLOCK = 64;
+    static constexpr size_t LDS_BYTES = BLOCK * sizeof(g1_xyzz);
+    static constexpr int PHASES = 8;         /* 1 + log2(64) + 1 */
     const g1_xyzz* in;
     const uint32_t* off;
+    uint32_t scale;
     g1_xyzz* out;
-    TC_DEV void operator()(uint32_t t) const {
-        g1_xyzz acc = xyzz_identity();
-        for (uint32_t i = off[t]; i < off[t + 1]; ++i) acc = xyzz_add(acc, in[i]);
-        out[t] = acc;
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        g1_xyzz* buf = (g1_xyzz*)lds;
+        if (ph == 0) {
+            uint64_t lo = (uint64_t)off[wg] * scale, hi = (uint64_t)off[wg + 1] * scale;
+            g1_xyzz acc = xyzz_identity();
+            for (uint64_t i = lo + lane; i < hi; i += BLOCK) acc = xyzz_add(acc, in[i]);
+            buf[lane] = acc;
+            return;
+        }
+        if (ph <= 6) {
+            uint32_t stride = 1u << (ph - 1);
+            if ((lane & (2 * stride - 1)) == 0) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
+            return;
+        }
+        if (lane == 0) out[wg] = buf[0];
     }
 };
 
@@ -1081,7 +1137,7 @@ struct LevelView {             /* what a node's children are */
     const fr_plain* below;     /* upper levels: phi values of the level below */
 };
 constexpr int MAX_LEVELS = 16;
-struct NodeOpenTerms {         /* lane (job, axis, term): one quotient value times its suffix-SRS point */
+struct NodeOpenTerms {         /* lane (job, axis, term, window pair): two windows of one quotient value times its suffix-SRS point */
     const NodeOpenJob* jobs;
     LevelView lv[MAX_LEVELS];
     ShapeInfo node;            /* node shape */
@@ -1089,7 +1145,8 @@ struct NodeOpenTerms {         /* lane (job, axis, term): one quotient value tim
     uint32_t axis_first[5];    /* first term of axis a within a job */
     AxisTables ax[4];
     const g1_affine* table[4]; /* fixed-base tables of S^(a) */
-    g1_xyzz* out;              /* jobs * terms_per_job */
+    int logH;                  /* log2(FB_W / 2) window pairs per term */
+    g1_xyzz* out;              /* jobs * terms_per_job << logH */
     fr_plain* y_out;           /* per job: the opened value */
 
     TC_DEV fr_t child_value(const LevelView& v, uint64_t a, const uint32_t* k) const {
@@ -1101,7 +1158,8 @@ struct NodeOpenTerms {         /* lane (job, axis, term): one quotient value tim
         return fe_from_limbs<FrParams>(v.below[f].l);
     }
     TC_DEV void operator()(uint32_t lane) const {
-        uint32_t job = lane / terms_per_job, term = lane % terms_per_job;
+        uint32_t h = lane & ((1u << logH) - 1u);
+        uint32_t job = (lane >> logH) / terms_per_job, term = (lane >> logH) % terms_per_job;
         const NodeOpenJob& J = jobs[job];
         const LevelView& v = lv[J.level];
         int a = 0;
@@ -1134,8 +1192,8 @@ struct NodeOpenTerms {         /* lane (job, axis, term): one quotient value tim
             qv = fr_neg(fr_mul(acc, ax[a].beta_inv[kap]));
         }
         fr_t plain = fe_to_plain(qv);
-        out[(uint64_t)J.term0 + term] = fb_mul_accumulate(xyzz_identity(), table[a], local, plain.l);
-        if (term == 0) {
+        out[(((uint64_t)J.term0 + term) << logH) + h] = fb_window_pair(table[a], local, plain.l, h);
+        if (term == 0 && h == 0) {
             fr_t y = fe_to_plain(child_value(v, J.node, J.kappa));
 #pragma unroll
             for (int i = 0; i < 8; ++i) y_out[job].l[i] = y.l[i];
@@ -1177,7 +1235,7 @@ struct VerifyTerms {
     const g1_affine* gtable;
     g1_xyzz* out;              /* steps * VERIFY_TERMS */
     uint32_t* ok;              /* per step, preset to 1; cleared on malformed input */
-    g1_xyzz* window_tab;       /* 15 points of scratch per lane */
+    g1_jtab* window_tab;       /* 8 multiples of scratch per lane */
     TC_DEV void operator()(uint32_t lane) const {
         uint32_t s = lane / VERIFY_TERMS, term = lane % VERIFY_TERMS;
         const VerifyStep& st = steps[s];
@@ -1199,7 +1257,7 @@ struct VerifyTerms {
                 for (int j = 0; j < 12; ++j) beta.l[j] = GLV_BETA[j];
                 p.x = fp_mul(p.x, beta);
             }
-            r = xyzz_mul_affine_w4(second ? st.k2[i] : st.k1[i], 128, p, window_tab + 15ull * lane);
+            r = xyzz_mul_affine_w4(second ? st.k2[i] : st.k1[i], 128, p, window_tab + 8ull * lane);
         }
         out[lane] = r;
     }

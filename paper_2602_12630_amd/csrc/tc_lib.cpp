@@ -552,6 +552,9 @@ static int launch_coop(uint32_t groups, rt::stream_t st, const F& f) {
 }
 #endif
 
+/* a tree level spreads the windows of a child over lanes as long as it stays within this many lanes (two waves per SIMD) */
+static const uint64_t SPLIT_LEVEL_LANES = 131072;
+
 /* prefix sums of cnt (n entries): start, lstart (of ceil(cnt / L)); optional zeroing of a cursor array */
 static int scan_counts(tc_ctx* ctx, const uint32_t* cnt, uint32_t n, uint32_t L, uint32_t* start, uint32_t* lstart,
                        uint32_t* zero_me, uint32_t* tot_a, uint32_t* tot_b, uint32_t* tot_max) {
@@ -988,7 +991,7 @@ static int verify_steps(tc_ctx* ctx, const tc_vk* vk, const std::vector<VerifySt
     WS(d_steps, VerifyStep, n);
     WS(d_terms, g1_xyzz, (uint64_t)VERIFY_TERMS * n);
     WS(d_ok, uint32_t, n);
-    WS(d_tab, g1_xyzz, 15ull * VERIFY_TERMS * n);
+    WS(d_tab, g1_jtab, 8ull * VERIFY_TERMS * n);
     RT(rt::memcpy_h2d(d_steps, steps.data(), sizeof(VerifyStep) * n, ctx->stream));
     RT(rt::launch<256>(n, ctx->stream, Fill32{d_ok, 1u}));
     RT(rt::launch<64>((uint64_t)VERIFY_TERMS * n, ctx->stream, VerifyTerms{d_steps, ctx->gtable, d_terms, d_ok, d_tab}));
@@ -1193,9 +1196,12 @@ extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** 
                     } else if ((t->B & (t->B - 1)) == 0 && t->B <= 64) {
                         int logB = 0;
                         while ((1u << logB) < t->B) ++logB;
-                        uint64_t lanes = lv.n * t->B;
+                        /* few nodes: one lane's depth is the cost, spread the windows of a child over lanes too */
+                        int logH = 0;
+                        while (logB + logH < 6 && (2 << logH) <= FB_W && (lv.n << (logB + logH + 1)) <= SPLIT_LEVEL_LANES) ++logH;
+                        uint64_t lanes = lv.n << (logB + logH);
                         e = launch_coop<64>((uint32_t)((lanes + 63) / 64), ctx->stream,
-                                            NodeCommitFrCoop<64>{g, t->levels[L - 1].phi, ns->fb[0], lv.n, logB, acc});
+                                            NodeCommitFrCoop<64>{g, t->levels[L - 1].phi, ns->fb[0], lv.n, logB, logH, acc});
                     } else {
                         g1_xyzz* part = ws_array<g1_xyzz>(ctx, lv.n * t->B);
                         if (!part) { rc = fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed"); break; }
@@ -1396,14 +1402,18 @@ extern "C" int tc_terkle_open_batch(tc_ctx* ctx, const tc_tree* t, int count, co
             seg[(size_t)jobs * m] = jobs * terms;
             WS(d_jobs, NodeOpenJob, jobs);
             WS(d_seg, uint32_t, (uint64_t)jobs * m + 1);
-            WS(d_terms, g1_xyzz, (uint64_t)jobs * terms);
+            int logH = 0;
+            while ((2u << logH) < (uint32_t)FB_W) ++logH;
+            if ((((uint64_t)jobs * terms) << logH) > 0xFFFFFFFFull) return fail(ctx, TC_ERR_ARG, "too many openings in one batch");
+            WS(d_terms, g1_xyzz, ((uint64_t)jobs * terms) << logH);
             RT(rt::memcpy_h2d(d_jobs, hj.data(), sizeof(NodeOpenJob) * jobs, ctx->stream));
             RT(rt::memcpy_h2d(d_seg, seg.data(), 4 * seg.size(), ctx->stream));
             k.jobs = d_jobs;
             k.out = d_terms;
             k.y_out = d_y;
-            RT(rt::launch<64>((uint64_t)jobs * terms, ctx->stream, k));
-            RT(rt::launch<64>((uint64_t)jobs * m, ctx->stream, SumSegments{d_terms, d_seg, d_pi}));
+            k.logH = logH;
+            RT(rt::launch<64>(((uint64_t)jobs * terms) << logH, ctx->stream, k));
+            RT((launch_coop<SumSegmentsCoop::BLOCK>(jobs * (uint32_t)m, ctx->stream, SumSegmentsCoop{d_terms, d_seg, 1u << logH, d_pi})));
         } else {
             /* large node shapes: gather the node tensor and open it like any tensor */
             for (int i = 0; i < count; ++i)

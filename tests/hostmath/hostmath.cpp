@@ -48,6 +48,12 @@ void hm_g1_mul(const uint8_t* k, const uint8_t* p, uint8_t* o) {
     uint32_t w[8]; memcpy(w, k, 32);
     pt_store(o, xyzz_to_affine(xyzz_mul_affine(w, 256, pt_load(p))));
 }
+// the signed-window multiplication the verifier uses, 128-bit scalars
+void hm_g1_mul_w4(const uint8_t* k, const uint8_t* p, uint8_t* o) {
+    uint32_t w[4]; memcpy(w, k, 16);
+    g1_jtab tab[8];
+    pt_store(o, xyzz_to_affine(xyzz_mul_affine_w4(w, 128, pt_load(p), tab)));
+}
 void hm_g1_generator(uint8_t* o) { pt_store(o, affine_generator()); }
 void hm_phi(const uint8_t* p, uint8_t* o) { fr_t v = phi_map(pt_load(p)); memcpy(o, v.l, 32); }
 }
