@@ -174,14 +174,9 @@ TC_HD g1_xyzz xyzz_mul_affine(const uint32_t* k, int nbits, const g1_affine& p) 
 }
 
 /* Jacobian coordinates (x = X / Z^2, y = Y / Z^3; identity: Z = 0): the doubling costs two products and five
- * squarings, against six and three in XYZZ form, which is what counts in a variable-base scalar multiplication,
- * where nearly every step is a doubling. */
+ * squarings, against six and three in XYZZ form: the form for the long doubling chains of the verifier. */
 struct g1_jac {
     fp_t X, Y, Z;
-};
-/* a multiple of the base point kept for the window additions: XYZZ form together with Z itself */
-struct g1_jtab {
-    fp_t X, Y, Z, ZZ, ZZZ;
 };
 TC_HD g1_jac jac_identity() {
     g1_jac r;
@@ -204,34 +199,6 @@ TC_HD g1_jac jac_dbl(const g1_jac& p) {
     r.Z = fp_dbl(fp_mul(p.Y, p.Z));
     return r;
 }
-/* a + (+-) t */
-TC_HD g1_jac jac_add_tab(const g1_jac& a, const g1_jtab& t, bool negate) {
-    fp_t Y2 = negate ? fp_neg(t.Y) : t.Y;
-    if (fe_is_zero(a.Z)) {
-        g1_jac r;
-        r.X = t.X; r.Y = Y2; r.Z = t.Z;
-        return r;
-    }
-    fp_t Z1Z1 = fp_sqr(a.Z);
-    fp_t U1 = fp_mul(a.X, t.ZZ);
-    fp_t U2 = fp_mul(t.X, Z1Z1);
-    fp_t S1 = fp_mul(a.Y, t.ZZZ);
-    fp_t S2 = fp_mul(Y2, fp_mul(a.Z, Z1Z1));
-    fp_t H = fp_sub(U2, U1);
-    fp_t Rd = fp_sub(S2, S1);
-    if (fe_is_zero(H)) {
-        if (fe_is_zero(Rd)) return jac_dbl(a);
-        return jac_identity();
-    }
-    fp_t HH = fp_sqr(H);
-    fp_t HHH = fp_mul(H, HH);
-    fp_t V = fp_mul(U1, HH);
-    g1_jac r;
-    r.X = fp_sub(fp_sub(fp_sub(fp_sqr(Rd), HHH), V), V);
-    r.Y = fp_sub(fp_mul(Rd, fp_sub(V, r.X)), fp_mul(S1, HHH));
-    r.Z = fp_mul(fp_mul(a.Z, t.Z), H);
-    return r;
-}
 TC_HD g1_xyzz jac_to_xyzz(const g1_jac& p) {
     if (fe_is_zero(p.Z)) return xyzz_identity();
     g1_xyzz r;
@@ -240,66 +207,6 @@ TC_HD g1_xyzz jac_to_xyzz(const g1_jac& p) {
     r.ZZ = fp_sqr(p.Z);
     r.ZZZ = fp_mul(p.Z, r.ZZ);
     return r;
-}
-
-/* [k] P for a plain scalar of `nbits` bits (a multiple of 4), signed 4-bit windows, MSB first: digits in
- * [-8, 8], so eight multiples P .. 8 P (`tab`, scratch) serve; Jacobian accumulator.  The multiples come from
- * the XYZZ chord rule with Z carried along (Z' = Z (x_P ZZ - X)). */
-TC_HD g1_xyzz xyzz_mul_affine_w4(const uint32_t* k, int nbits, const g1_affine& p, g1_jtab* tab) {
-    if (affine_is_identity(p)) return xyzz_identity();
-    {
-        g1_jtab e;
-        e.X = p.x; e.Y = p.y;
-        e.Z = fe_one<FpParams>(); e.ZZ = e.Z; e.ZZZ = e.Z;
-        tab[0] = e;
-        g1_xyzz d = xyzz_dbl_affine(p);
-        bool dead = xyzz_is_identity(d);          /* y = 0 cannot happen on this curve's prime-order group; kept total */
-        e.X = d.X; e.Y = d.Y; e.ZZ = d.ZZ; e.ZZZ = d.ZZZ;
-        e.Z = dead ? fe_zero<FpParams>() : fp_dbl(p.y);
-        tab[1] = e;
-        for (int j = 2; j < 8; ++j) {
-            /* e + P by the chord rule; e = j P with 2 <= j < 8 is never +-P or the identity for a point of order r */
-            fp_t Pd = fp_sub(fp_mul(p.x, e.ZZ), e.X);
-            fp_t Rd = fp_sub(fp_mul(p.y, e.ZZZ), e.Y);
-            fp_t PP = fp_sqr(Pd);
-            fp_t PPP = fp_mul(Pd, PP);
-            fp_t Q = fp_mul(e.X, PP);
-            g1_jtab n;
-            n.X = fp_sub(fp_sub(fp_sub(fp_sqr(Rd), PPP), Q), Q);
-            n.Y = fp_sub(fp_mul(Rd, fp_sub(Q, n.X)), fp_mul(e.Y, PPP));
-            n.Z = fp_mul(e.Z, Pd);
-            n.ZZ = fp_mul(e.ZZ, PP);
-            n.ZZZ = fp_mul(e.ZZZ, PPP);
-            e = n;
-            tab[j] = e;
-        }
-    }
-    /* signed digits, least significant first: d_w in [-8, 8], top carry as one more digit */
-    int nw = nbits / 4;
-    g1_jac acc = jac_identity();
-    /* the digits are consumed from the top but the carries run from the bottom: one pass collects them (nw <= 64) */
-    uint64_t carries = 0;
-    {
-        uint32_t c = 0;
-        for (int w = 0; w < nw; ++w) {
-            uint32_t d = ((k[w >> 3] >> ((w & 7) * 4)) & 15u) + c;
-            c = d > 8u ? 1u : 0u;
-            carries |= (uint64_t)c << w;
-        }
-    }
-    for (int w = nw; w >= 0; --w) {
-        if (w < nw) for (int i = 0; i < 4; ++i) acc = jac_dbl(acc);
-        int d;
-        if (w == nw) {
-            d = (int)((carries >> (nw - 1)) & 1u);
-        } else {
-            uint32_t cin = w ? (uint32_t)((carries >> (w - 1)) & 1u) : 0u;
-            d = (int)(((k[w >> 3] >> ((w & 7) * 4)) & 15u) + cin);
-            if (d > 8) d -= 16;
-        }
-        if (d) acc = jac_add_tab(acc, tab[(d < 0 ? -d : d) - 1], d < 0);     /* one call site: lanes of either sign stay together */
-    }
-    return jac_to_xyzz(acc);
 }
 
 /* canonical 96-byte encoding <-> affine Montgomery point */

@@ -659,6 +659,11 @@ struct ToCanonical {
     uint32_t* out;          /* 24 words per point */
     TC_DEV void operator()(uint32_t t) const { affine_to_canonical(in[t], out + 24 * (uint64_t)t); }
 };
+struct ToCanonicalGather {   /* the same for points scattered over several arrays */
+    const g1_affine* const* in;
+    uint32_t* out;
+    TC_DEV void operator()(uint32_t t) const { affine_to_canonical(*in[t], out + 24 * (uint64_t)t); }
+};
 struct PhiKernel {
     const g1_affine* in;
     fr_plain* out;
@@ -1215,7 +1220,8 @@ struct VerifyStep {
     uint32_t k2[4][4];
     int m;
 };
-constexpr uint32_t VERIFY_TERMS = 9;      /* [y]G and two half-scalar terms per proof element */
+constexpr uint32_t VERIFY_CHAINS = 8;     /* two half-scalar terms per proof element, at most four elements */
+constexpr uint32_t VERIFY_BITS = 128;
 TC_HD bool affine_on_curve(const g1_affine& p) {
     if (affine_is_identity(p)) return true;
     fp_t y2 = fp_sqr(p.y);
@@ -1229,50 +1235,91 @@ TC_HD bool xyzz_equal(const g1_xyzz& a, const g1_xyzz& b) {
     if (ia || ib) return ia && ib;
     return fe_eq(fp_mul(a.X, b.ZZ), fp_mul(b.X, a.ZZ)) && fe_eq(fp_mul(a.Y, b.ZZZ), fp_mul(b.Y, a.ZZZ));
 }
-/* lane (step, term): term 0 = [y]G; term 1 + 2i = [k1_i] pi_i; term 2 + 2i = [k2_i] (beta x, y) of pi_i */
-struct VerifyTerms {
+/* The 128 doublings of a half-length scalar multiplication cannot be spread over lanes, everything else can:
+ * lane (step, chain) of VerifyChain walks P, 2P, 4P, .. 2^127 P (chain 2i: P = pi_i, chain 2i + 1: its image
+ * (beta x, y)) and keeps every point; VerifySum then adds, for a step, the points whose bit is set in the
+ * half scalars, the sixteen window terms of [y]G and -C in one pairwise sum, and accepts iff
+ *   sum_i [k_i] pi_i + [y] G - C = O. */
+struct VerifyChain {
     const VerifyStep* steps;
-    const g1_affine* gtable;
-    g1_xyzz* out;              /* steps * VERIFY_TERMS */
     uint32_t* ok;              /* per step, preset to 1; cleared on malformed input */
-    g1_jtab* window_tab;       /* 8 multiples of scratch per lane */
+    g1_jac* chain;             /* lanes * VERIFY_BITS */
     TC_DEV void operator()(uint32_t lane) const {
-        uint32_t s = lane / VERIFY_TERMS, term = lane % VERIFY_TERMS;
+        uint32_t s = lane / VERIFY_CHAINS, j = lane % VERIFY_CHAINS;
         const VerifyStep& st = steps[s];
-        g1_xyzz r = xyzz_identity();
-        if (term == 0) {
-            if (!limbs_gt<8>(FrParams::MOD, st.y)) atomic_and_u32(&ok[s], 0u);
-            r = fb_mul_accumulate(r, gtable, 0, st.y);
-            g1_affine c = affine_from_canonical(st.C);
-            if (!canonical_fp(st.C) || !canonical_fp(st.C + 12) || !affine_on_curve(c)) atomic_and_u32(&ok[s], 0u);
-        } else if ((int)(term - 1) / 2 < st.m) {
-            int i = (int)(term - 1) / 2;
-            bool second = ((term - 1) & 1u) != 0;
-            const uint32_t* w = st.pi[i];
-            g1_affine p = affine_from_canonical(w);
-            if (!second && (!canonical_fp(w) || !canonical_fp(w + 12) || !affine_on_curve(p))) atomic_and_u32(&ok[s], 0u);
+        int i = (int)(j >> 1);
+        if (i >= st.m) return;
+        bool second = (j & 1u) != 0;
+        const uint32_t* w = st.pi[i];
+        g1_affine p = affine_from_canonical(w);
+        if (!second && (!canonical_fp(w) || !canonical_fp(w + 12) || !affine_on_curve(p))) atomic_and_u32(&ok[s], 0u);
+        g1_jac q = jac_identity();
+        if (!affine_is_identity(p)) {
             if (second) {
                 fp_t beta;
 #pragma unroll
-                for (int j = 0; j < 12; ++j) beta.l[j] = GLV_BETA[j];
+                for (int t = 0; t < 12; ++t) beta.l[t] = GLV_BETA[t];
                 p.x = fp_mul(p.x, beta);
             }
-            r = xyzz_mul_affine_w4(second ? st.k2[i] : st.k1[i], 128, p, window_tab + 8ull * lane);
+            q.X = p.x;
+            q.Y = p.y;
+            q.Z = fe_one<FpParams>();
         }
-        out[lane] = r;
+        g1_jac* out = chain + (uint64_t)lane * VERIFY_BITS;
+        for (uint32_t b = 0; b < VERIFY_BITS; ++b) {
+            out[b] = q;
+            if (b + 1 < VERIFY_BITS) q = jac_dbl(q);
+        }
     }
 };
-struct VerifyCombine {         /* lane = step */
+struct VerifySum {             /* workgroup = step */
+    static constexpr int BLOCK = 256;
+    static constexpr size_t LDS_BYTES = BLOCK * sizeof(g1_xyzz);
+    static constexpr int PHASES = 10;        /* gather, 8 halving steps, decision */
     const VerifyStep* steps;
-    const g1_xyzz* terms;
+    const g1_affine* gtable;
+    const g1_jac* chain;
     uint32_t* ok;
-    TC_DEV void operator()(uint32_t s) const {
-        const VerifyStep& st = steps[s];
-        const g1_xyzz* t = terms + (uint64_t)s * VERIFY_TERMS;
-        g1_xyzz lhs = xyzz_add(xyzz_from_affine(affine_from_canonical(st.C)), xyzz_neg(t[0]));
-        g1_xyzz rhs = xyzz_identity();
-        for (int i = 1; i <= 2 * st.m; ++i) rhs = xyzz_add(rhs, t[i]);
-        if (!xyzz_equal(lhs, rhs)) ok[s] = 0;
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        g1_xyzz* buf = (g1_xyzz*)lds;
+        const VerifyStep& st = steps[wg];
+        if (ph == 0) {
+            g1_xyzz acc = xyzz_identity();
+            uint32_t npts = 2u * (uint32_t)st.m * VERIFY_BITS;
+            for (uint32_t base = 0; base < npts; base += BLOCK) {
+                uint32_t idx = base + lane;          /* npts is a multiple of BLOCK */
+                uint32_t j = idx / VERIFY_BITS, b = idx % VERIFY_BITS;
+                const uint32_t* k = (j & 1u) ? st.k2[j >> 1] : st.k1[j >> 1];
+                if ((k[b >> 5] >> (b & 31)) & 1u)
+                    acc = xyzz_add(acc, jac_to_xyzz(chain[((uint64_t)wg * VERIFY_CHAINS + j) * VERIFY_BITS + b]));
+            }
+            if (lane <= (uint32_t)FB_W) {
+                g1_affine p = affine_identity();
+                if (lane < (uint32_t)FB_W) {         /* window `lane` of [y] G */
+                    uint32_t carry = 0;
+                    int32_t d = 0;
+                    for (uint32_t w = 0; w <= lane; ++w) d = fr_window_digit(st.y, (int)w, FB_C, carry);
+                    if (d) {
+                        p = gtable[(uint64_t)lane * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u];
+                        if (d < 0) p.y = fp_neg(p.y);
+                    }
+                } else {                             /* -C, and the checks on C and y */
+                    p = affine_from_canonical(st.C);
+                    bool good = canonical_fp(st.C) && canonical_fp(st.C + 12) && affine_on_curve(p) && limbs_gt<8>(FrParams::MOD, st.y);
+                    if (!good) atomic_and_u32(&ok[wg], 0u);
+                    if (!affine_is_identity(p)) p.y = fp_neg(p.y);
+                }
+                acc = xyzz_madd(acc, p);
+            }
+            buf[lane] = acc;
+            return;
+        }
+        if (ph <= 8) {
+            uint32_t stride = 1u << (ph - 1);
+            if ((lane & (2 * stride - 1)) == 0) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
+            return;
+        }
+        if (lane == 0 && !xyzz_is_identity(buf[0])) ok[wg] = 0;
     }
 };
 /* phi of canonical commitments (the verifier's side of "the opened value matches the next commitment") */

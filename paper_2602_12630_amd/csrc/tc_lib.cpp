@@ -66,6 +66,7 @@ struct tc_tree {
     std::vector<const void*> leaf_scalars;
     std::vector<int> leaf_dtype;
     std::vector<TreeLevel> levels;
+    void* block = nullptr;          /* one device allocation holds C and phi of every level */
     uint8_t root[96];
 };
 
@@ -981,6 +982,9 @@ static void fill_step_scalars(const tc_vk* vk, const uint32_t* kappa, VerifyStep
     }
 }
 
+/* at most this many steps share the chain buffer (144 KiB per step) */
+static const uint32_t VERIFY_CHUNK_STEPS = 4096;
+
 /* runs the steps on the device; ok[i] = 1 iff step i verifies */
 static int verify_steps(tc_ctx* ctx, const tc_vk* vk, const std::vector<VerifyStep>& steps, std::vector<uint32_t>& ok) {
     uint32_t n = (uint32_t)steps.size();
@@ -989,13 +993,16 @@ static int verify_steps(tc_ctx* ctx, const tc_vk* vk, const std::vector<VerifySt
     (void)vk;
     TRY(ensure_gtable(ctx));
     WS(d_steps, VerifyStep, n);
-    WS(d_terms, g1_xyzz, (uint64_t)VERIFY_TERMS * n);
     WS(d_ok, uint32_t, n);
-    WS(d_tab, g1_jtab, 8ull * VERIFY_TERMS * n);
+    uint32_t chunk = n < VERIFY_CHUNK_STEPS ? n : VERIFY_CHUNK_STEPS;
+    WS(d_chain, g1_jac, (uint64_t)chunk * VERIFY_CHAINS * VERIFY_BITS);
     RT(rt::memcpy_h2d(d_steps, steps.data(), sizeof(VerifyStep) * n, ctx->stream));
     RT(rt::launch<256>(n, ctx->stream, Fill32{d_ok, 1u}));
-    RT(rt::launch<64>((uint64_t)VERIFY_TERMS * n, ctx->stream, VerifyTerms{d_steps, ctx->gtable, d_terms, d_ok, d_tab}));
-    RT(rt::launch<64>(n, ctx->stream, VerifyCombine{d_steps, d_terms, d_ok}));
+    for (uint32_t c0 = 0; c0 < n; c0 += chunk) {       /* the chain buffer serves one chunk of steps after the other */
+        uint32_t cn = n - c0 < chunk ? n - c0 : chunk;
+        RT(rt::launch<64>((uint64_t)VERIFY_CHAINS * cn, ctx->stream, VerifyChain{d_steps + c0, d_ok + c0, d_chain}));
+        RT((launch_coop<VerifySum::BLOCK>(cn, ctx->stream, VerifySum{d_steps + c0, ctx->gtable, d_chain, d_ok + c0})));
+    }
     RT(rt::memcpy_d2h(ok.data(), d_ok, 4ull * n, ctx->stream));
     RT(rt::stream_sync(ctx->stream));
     return TC_OK;
@@ -1028,10 +1035,7 @@ extern "C" int tc_verify(tc_ctx* ctx, const tc_vk* vk, int m, const uint32_t* sh
 /* ======================================================================================= */
 extern "C" void tc_tree_destroy(tc_tree* tree) {
     if (!tree) return;
-    for (auto& lv : tree->levels) {
-        if (lv.C) rt::dev_free(lv.C);
-        if (lv.phi) rt::dev_free(lv.phi);
-    }
+    if (tree->block) rt::dev_free(tree->block);
     delete tree;
 }
 extern "C" int tc_terkle_root(const tc_tree* tree, uint8_t out_g1[96]) {
@@ -1160,15 +1164,21 @@ extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** 
         }
     }
     int rc = TC_OK;
-    for (auto& lv : t->levels) {
-        void *c = nullptr, *p = nullptr;
-        if (rt::dev_malloc(&c, (size_t)lv.n * sizeof(g1_affine)) != 0 || rt::dev_malloc(&p, (size_t)lv.n * sizeof(fr_plain)) != 0) {
-            if (c) rt::dev_free(c);
+    {
+        size_t total = 0;
+        for (auto& lv : t->levels) total += ((size_t)lv.n * sizeof(g1_affine) + 255) / 256 * 256 + ((size_t)lv.n * sizeof(fr_plain) + 255) / 256 * 256;
+        if (rt::dev_malloc(&t->block, total) != 0) {
+            t->block = nullptr;
             rc = fail(ctx, TC_ERR_NOMEM, "tree level allocation failed");
-            break;
+        } else {
+            uint8_t* at = (uint8_t*)t->block;
+            for (auto& lv : t->levels) {
+                lv.C = (g1_affine*)at;
+                at += ((size_t)lv.n * sizeof(g1_affine) + 255) / 256 * 256;
+                lv.phi = (fr_plain*)at;
+                at += ((size_t)lv.n * sizeof(fr_plain) + 255) / 256 * 256;
+            }
         }
-        lv.C = (g1_affine*)c;
-        lv.phi = (fr_plain*)p;
     }
     bool use_fb = ns->fb[0] != nullptr;
     for (size_t L = 0; L < t->levels.size() && rc == TC_OK; ++L) {
@@ -1477,11 +1487,15 @@ extern "C" int tc_terkle_open_batch(tc_ctx* ctx, const tc_tree* t, int count, co
             }
         n_child = (uint32_t)want.size();
         if (n_child) {
-            WS(d_sel, g1_affine, n_child);
-            for (uint32_t w = 0; w < n_child; ++w)
-                RT(rt::memcpy_d2d(d_sel + w, t->levels[want[w].first].C + want[w].second, sizeof(g1_affine), ctx->stream));
+            std::vector<const g1_affine*> src(n_child);
+            for (uint32_t w = 0; w < n_child; ++w) src[w] = t->levels[want[w].first].C + want[w].second;
+            WS(d_src, const g1_affine*, n_child);
+            WS(can, uint32_t, 24ull * n_child);
+            RT(rt::memcpy_h2d(d_src, src.data(), sizeof(const g1_affine*) * n_child, ctx->stream));
+            RT(rt::launch<64>(n_child, ctx->stream, ToCanonicalGather{d_src, can}));
             h_child.resize(96ull * n_child);
-            TRY(affine_to_host(ctx, d_sel, n_child, h_child.data()));
+            RT(rt::memcpy_d2h(h_child.data(), can, 96ull * n_child, ctx->stream));
+            RT(rt::stream_sync(ctx->stream));
         }
     }
     /* assemble, top level first */

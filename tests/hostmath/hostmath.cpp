@@ -48,11 +48,13 @@ void hm_g1_mul(const uint8_t* k, const uint8_t* p, uint8_t* o) {
     uint32_t w[8]; memcpy(w, k, 32);
     pt_store(o, xyzz_to_affine(xyzz_mul_affine(w, 256, pt_load(p))));
 }
-// the signed-window multiplication the verifier uses, 128-bit scalars
-void hm_g1_mul_w4(const uint8_t* k, const uint8_t* p, uint8_t* o) {
-    uint32_t w[4]; memcpy(w, k, 16);
-    g1_jtab tab[8];
-    pt_store(o, xyzz_to_affine(xyzz_mul_affine_w4(w, 128, pt_load(p), tab)));
+// 2^n P through the Jacobian doubling the verifier's chains use
+void hm_g1_dbl_chain(const uint8_t* p, int n, uint8_t* o) {
+    g1_affine a = pt_load(p);
+    g1_jac q = jac_identity();
+    if (!affine_is_identity(a)) { q.X = a.x; q.Y = a.y; q.Z = fe_one<FpParams>(); }
+    for (int i = 0; i < n; ++i) q = jac_dbl(q);
+    pt_store(o, xyzz_to_affine(jac_to_xyzz(q)));
 }
 void hm_g1_generator(uint8_t* o) { pt_store(o, affine_generator()); }
 void hm_phi(const uint8_t* p, uint8_t* o) { fr_t v = phi_map(pt_load(p)); memcpy(o, v.l, 32); }

@@ -107,12 +107,10 @@ def test_group_law_including_exceptional_cases(hm):
         assert _pt(hm.hm_g1_add, _pb(ec.INF), _pb(ec.INF), mode) is ec.INF
     for k in (0, 1, 2, 3, R - 1, rng.randrange(R), 1 << 200):
         assert _pt(hm.hm_g1_mul, _b(k, 32), _pb(pts[0])) == ec.mul_affine(k, pts[0])
-    # signed 4-bit windows: carries through runs of 0xF / 0x8 / 0x9 digits, the top carry, zero, the identity
-    edge = [0, 1, 7, 8, 9, 15, 16, (1 << 128) - 1, int("8" * 32, 16), int("9" * 32, 16), int("7" * 32, 16),
-            int("f0" * 16, 16), int("0f" * 16, 16), 1 << 127, (1 << 127) - 1] + [rng.randrange(1 << 128) for _ in range(12)]
-    for k in edge:
-        assert _pt(hm.hm_g1_mul_w4, _b(k, 16), _pb(pts[1])) == ec.mul_affine(k, pts[1]), hex(k)
-    assert _pt(hm.hm_g1_mul_w4, _b(12345, 16), _pb(ec.INF)) is ec.INF
+    # Jacobian doubling chain: 2^n P for the lengths around a half scalar, and the identity
+    for n in (0, 1, 2, 5, 127, 128):
+        assert _pt(hm.hm_g1_dbl_chain, _pb(pts[1]), n) == ec.mul_affine(1 << n, pts[1]), n
+    assert _pt(hm.hm_g1_dbl_chain, _pb(ec.INF), 7) is ec.INF
 
 
 def test_phi_map(hm):
