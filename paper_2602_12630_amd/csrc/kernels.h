@@ -1237,8 +1237,8 @@ TC_HD bool xyzz_equal(const g1_xyzz& a, const g1_xyzz& b) {
 }
 /* The 128 doublings of a half-length scalar multiplication cannot be spread over lanes, everything else can:
  * lane (step, chain) of VerifyChain walks P, 2P, 4P, .. 2^127 P (chain 2i: P = pi_i, chain 2i + 1: its image
- * (beta x, y)) and keeps every point; VerifySum then adds, for a step, the points whose bit is set in the
- * half scalars, the sixteen window terms of [y]G and -C in one pairwise sum, and accepts iff
+ * (beta x, y)) and keeps every point; VerifySum and VerifyDecide then add, for a step, the points whose bit is
+ * set in the half scalars, the window terms of [y]G and -C pairwise, and accept iff
  *   sum_i [k_i] pi_i + [y] G - C = O. */
 struct VerifyChain {
     const VerifyStep* steps;
@@ -1272,28 +1272,35 @@ struct VerifyChain {
         }
     }
 };
-struct VerifySum {             /* workgroup = step */
-    static constexpr int BLOCK = 256;
+/* Workgroups of one wave each (pairwise sums through LDS run at full speed only then): of the `groups` groups
+ * of a step (4 m + 1, m the largest order among the steps of the launch) all but the last add the points of 64
+ * consecutive (chain, bit) slots, the last one the window terms of [y]G and -C. */
+constexpr uint32_t VERIFY_MAX_GROUPS = VERIFY_CHAINS * VERIFY_BITS / 64 + 1;
+struct VerifySum {
+    static constexpr int BLOCK = 64;
     static constexpr size_t LDS_BYTES = BLOCK * sizeof(g1_xyzz);
-    static constexpr int PHASES = 10;        /* gather, 8 halving steps, decision */
+    static constexpr int PHASES = 8;         /* gather, 6 halving steps, store */
     const VerifyStep* steps;
     const g1_affine* gtable;
     const g1_jac* chain;
     uint32_t* ok;
+    uint32_t groups;
+    g1_xyzz* partial;          /* steps * groups */
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         g1_xyzz* buf = (g1_xyzz*)lds;
-        const VerifyStep& st = steps[wg];
+        uint32_t s = wg / groups, g = wg % groups;
+        const VerifyStep& st = steps[s];
         if (ph == 0) {
             g1_xyzz acc = xyzz_identity();
-            uint32_t npts = 2u * (uint32_t)st.m * VERIFY_BITS;
-            for (uint32_t base = 0; base < npts; base += BLOCK) {
-                uint32_t idx = base + lane;          /* npts is a multiple of BLOCK */
+            if (g + 1 < groups) {
+                uint32_t idx = g * BLOCK + lane;
                 uint32_t j = idx / VERIFY_BITS, b = idx % VERIFY_BITS;
-                const uint32_t* k = (j & 1u) ? st.k2[j >> 1] : st.k1[j >> 1];
-                if ((k[b >> 5] >> (b & 31)) & 1u)
-                    acc = xyzz_add(acc, jac_to_xyzz(chain[((uint64_t)wg * VERIFY_CHAINS + j) * VERIFY_BITS + b]));
-            }
-            if (lane <= (uint32_t)FB_W) {
+                if ((int)(j >> 1) < st.m) {
+                    const uint32_t* k = (j & 1u) ? st.k2[j >> 1] : st.k1[j >> 1];
+                    if ((k[b >> 5] >> (b & 31)) & 1u)
+                        acc = jac_to_xyzz(chain[((uint64_t)s * VERIFY_CHAINS + j) * VERIFY_BITS + b]);
+                }
+            } else if (lane <= (uint32_t)FB_W) {
                 g1_affine p = affine_identity();
                 if (lane < (uint32_t)FB_W) {         /* window `lane` of [y] G */
                     uint32_t carry = 0;
@@ -1306,22 +1313,44 @@ struct VerifySum {             /* workgroup = step */
                 } else {                             /* -C, and the checks on C and y */
                     p = affine_from_canonical(st.C);
                     bool good = canonical_fp(st.C) && canonical_fp(st.C + 12) && affine_on_curve(p) && limbs_gt<8>(FrParams::MOD, st.y);
-                    if (!good) atomic_and_u32(&ok[wg], 0u);
-                    if (!affine_is_identity(p)) p.y = fp_neg(p.y);
+                    if (!good) atomic_and_u32(&ok[s], 0u);
+                    p = affine_neg(p);
                 }
-                acc = xyzz_madd(acc, p);
+                acc = xyzz_from_affine(p);
             }
             buf[lane] = acc;
             return;
         }
-        if (ph <= 8) {
+        if (ph <= 6) {
             uint32_t stride = 1u << (ph - 1);
             if ((lane & (2 * stride - 1)) == 0) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
+            return;
+        }
+        if (lane == 0) partial[wg] = buf[0];
+    }
+};
+struct VerifyDecide {          /* workgroup = step: the partial sums must cancel */
+    static constexpr int BLOCK = 64;
+    static constexpr size_t LDS_BYTES = BLOCK * sizeof(g1_xyzz);
+    static constexpr int PHASES = 7;         /* load, 5 halving steps over 32 slots, decision */
+    const g1_xyzz* partial;
+    uint32_t groups;
+    uint32_t* ok;
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        g1_xyzz* buf = (g1_xyzz*)lds;
+        if (ph == 0) {
+            buf[lane] = lane < groups ? partial[(uint64_t)wg * groups + lane] : xyzz_identity();
+            return;
+        }
+        if (ph <= 5) {
+            uint32_t stride = 1u << (ph - 1);
+            if (lane < 32 && (lane & (2 * stride - 1)) == 0) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
             return;
         }
         if (lane == 0 && !xyzz_is_identity(buf[0])) ok[wg] = 0;
     }
 };
+static_assert(VERIFY_MAX_GROUPS <= 32, "VerifyDecide sums 32 slots");
 /* phi of canonical commitments (the verifier's side of "the opened value matches the next commitment") */
 struct PhiCanonical {
     const uint32_t* pts;       /* 24 words each */

@@ -996,12 +996,17 @@ static int verify_steps(tc_ctx* ctx, const tc_vk* vk, const std::vector<VerifySt
     WS(d_ok, uint32_t, n);
     uint32_t chunk = n < VERIFY_CHUNK_STEPS ? n : VERIFY_CHUNK_STEPS;
     WS(d_chain, g1_jac, (uint64_t)chunk * VERIFY_CHAINS * VERIFY_BITS);
+    WS(d_part, g1_xyzz, (uint64_t)chunk * VERIFY_MAX_GROUPS);
     RT(rt::memcpy_h2d(d_steps, steps.data(), sizeof(VerifyStep) * n, ctx->stream));
     RT(rt::launch<256>(n, ctx->stream, Fill32{d_ok, 1u}));
     for (uint32_t c0 = 0; c0 < n; c0 += chunk) {       /* the chain buffer serves one chunk of steps after the other */
         uint32_t cn = n - c0 < chunk ? n - c0 : chunk;
         RT(rt::launch<64>((uint64_t)VERIFY_CHAINS * cn, ctx->stream, VerifyChain{d_steps + c0, d_ok + c0, d_chain}));
-        RT((launch_coop<VerifySum::BLOCK>(cn, ctx->stream, VerifySum{d_steps + c0, ctx->gtable, d_chain, d_ok + c0})));
+        int mmax = 1;
+        for (uint32_t i = c0; i < c0 + cn; ++i) mmax = steps[i].m > mmax ? steps[i].m : mmax;
+        uint32_t groups = VERIFY_CHAINS * VERIFY_BITS / 64 * (uint32_t)mmax / TC_MAX_ORDER + 1;
+        RT((launch_coop<VerifySum::BLOCK>(cn * groups, ctx->stream, VerifySum{d_steps + c0, ctx->gtable, d_chain, d_ok + c0, groups, d_part})));
+        RT((launch_coop<VerifyDecide::BLOCK>(cn, ctx->stream, VerifyDecide{d_part, groups, d_ok + c0})));
     }
     RT(rt::memcpy_d2h(ok.data(), d_ok, 4ull * n, ctx->stream));
     RT(rt::stream_sync(ctx->stream));
