@@ -1236,39 +1236,115 @@ TC_HD bool xyzz_equal(const g1_xyzz& a, const g1_xyzz& b) {
     return fe_eq(fp_mul(a.X, b.ZZ), fp_mul(b.X, a.ZZ)) && fe_eq(fp_mul(a.Y, b.ZZZ), fp_mul(b.Y, a.ZZZ));
 }
 /* The 128 doublings of a half-length scalar multiplication cannot be spread over lanes, everything else can:
- * lane (step, chain) of VerifyChain walks P, 2P, 4P, .. 2^127 P (chain 2i: P = pi_i, chain 2i + 1: its image
+ * chain (step, j) of VerifyChain walks P, 2P, 4P, .. 2^127 P (chain 2i: P = pi_i, chain 2i + 1: its image
  * (beta x, y)) and keeps every point; VerifySum and VerifyDecide then add, for a step, the points whose bit is
  * set in the half scalars, the window terms of [y]G and -C pairwise, and accept iff
  *   sum_i [k_i] pi_i + [y] G - C = O. */
+/* Three waves per 64 chains: the seven products of a Jacobian doubling (A = X^2, B = Y^2, YZ; F = (3A)^2,
+ * C = B^2, XB; E (D - X3)) fall into three levels of independent ones, and a wave alone on its SIMD issues
+ * them no faster one after the other than three waves do side by side.  Wave 0 carries X and Y, wave 1 the
+ * powers of Y, wave 2 Z and D = 4 X B; operands pass through LDS, a barrier after every level.  Z = 0 (the
+ * identity) reproduces itself under these formulas, so the loop has no special cases. */
 struct VerifyChain {
+    static constexpr int BLOCK = 192;
+    enum { FX, FY, FZ, FE, FB, FC8, FD, FF, NFIELD };
+    static constexpr size_t LDS_BYTES = (size_t)NFIELD * 3 * 64 * 16;
+    static constexpr int PHASES = 1 + 3 * ((int)VERIFY_BITS - 1);
+    struct Quad { uint32_t v[4]; };
     const VerifyStep* steps;
-    uint32_t* ok;              /* per step, preset to 1; cleared on malformed input */
-    g1_jac* chain;             /* lanes * VERIFY_BITS */
-    TC_DEV void operator()(uint32_t lane) const {
-        uint32_t s = lane / VERIFY_CHAINS, j = lane % VERIFY_CHAINS;
-        const VerifyStep& st = steps[s];
-        int i = (int)(j >> 1);
-        if (i >= st.m) return;
-        bool second = (j & 1u) != 0;
-        const uint32_t* w = st.pi[i];
-        g1_affine p = affine_from_canonical(w);
-        if (!second && (!canonical_fp(w) || !canonical_fp(w + 12) || !affine_on_curve(p))) atomic_and_u32(&ok[s], 0u);
-        g1_jac q = jac_identity();
-        if (!affine_is_identity(p)) {
-            if (second) {
-                fp_t beta;
+    uint32_t n_chains;         /* VERIFY_CHAINS per step */
+    uint32_t* ok;
+    g1_jac* chain;
+
+    TC_DEV static fp_t ld(const uint8_t* lds, int f, uint32_t l) {
+        const Quad* q = (const Quad*)lds;
+        fp_t r;
 #pragma unroll
-                for (int t = 0; t < 12; ++t) beta.l[t] = GLV_BETA[t];
-                p.x = fp_mul(p.x, beta);
-            }
-            q.X = p.x;
-            q.Y = p.y;
-            q.Z = fe_one<FpParams>();
+        for (int i = 0; i < 3; ++i) {
+            Quad t = q[(f * 3 + i) * 64 + l];
+            r.l[4 * i] = t.v[0]; r.l[4 * i + 1] = t.v[1]; r.l[4 * i + 2] = t.v[2]; r.l[4 * i + 3] = t.v[3];
         }
-        g1_jac* out = chain + (uint64_t)lane * VERIFY_BITS;
-        for (uint32_t b = 0; b < VERIFY_BITS; ++b) {
-            out[b] = q;
-            if (b + 1 < VERIFY_BITS) q = jac_dbl(q);
+        return r;
+    }
+    TC_DEV static void st(uint8_t* lds, int f, uint32_t l, const fp_t& x) {
+        Quad* q = (Quad*)lds;
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            Quad t;
+            t.v[0] = x.l[4 * i]; t.v[1] = x.l[4 * i + 1]; t.v[2] = x.l[4 * i + 2]; t.v[3] = x.l[4 * i + 3];
+            q[(f * 3 + i) * 64 + l] = t;
+        }
+    }
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        uint32_t wave = lane >> 6, l = lane & 63u;
+        uint32_t c = wg * 64u + l;
+        bool live = false;
+        if (c < n_chains) live = (int)((c % VERIFY_CHAINS) >> 1) < steps[c / VERIFY_CHAINS].m;
+        g1_jac* out = chain + (uint64_t)c * VERIFY_BITS;
+        if (ph == 0) {
+            if (wave != 0) return;
+            g1_jac q = jac_identity();
+            if (live) {
+                uint32_t s = c / VERIFY_CHAINS, j = c % VERIFY_CHAINS;
+                const uint32_t* w = steps[s].pi[j >> 1];
+                g1_affine p = affine_from_canonical(w);
+                bool second = (j & 1u) != 0;
+                if (!second && (!canonical_fp(w) || !canonical_fp(w + 12) || !affine_on_curve(p))) atomic_and_u32(&ok[s], 0u);
+                if (!affine_is_identity(p)) {
+                    if (second) {
+                        fp_t beta;
+#pragma unroll
+                        for (int t = 0; t < 12; ++t) beta.l[t] = GLV_BETA[t];
+                        p.x = fp_mul(p.x, beta);
+                    }
+                    q.X = p.x;
+                    q.Y = p.y;
+                    q.Z = fe_one<FpParams>();
+                }
+                out[0] = q;
+            }
+            st(lds, FX, l, q.X);
+            st(lds, FY, l, q.Y);
+            st(lds, FZ, l, q.Z);
+            return;
+        }
+        uint32_t b = (uint32_t)(ph - 1) / 3u + 1u;      /* the point 2^b P is in the making */
+        int level = (ph - 1) % 3;
+        if (level == 0) {
+            if (wave == 0) {
+                fp_t A = fp_sqr(ld(lds, FX, l));
+                st(lds, FE, l, fp_add(fp_dbl(A), A));
+            } else if (wave == 1) {
+                st(lds, FB, l, fp_sqr(ld(lds, FY, l)));
+            } else {
+                fp_t Z3 = fp_dbl(fp_mul(ld(lds, FY, l), ld(lds, FZ, l)));
+                st(lds, FZ, l, Z3);
+                if (live) out[b].Z = Z3;
+            }
+            return;
+        }
+        if (level == 1) {
+            if (wave == 0) {
+                st(lds, FF, l, fp_sqr(ld(lds, FE, l)));
+            } else if (wave == 1) {
+                fp_t C = fp_sqr(ld(lds, FB, l));
+                st(lds, FC8, l, fp_dbl(fp_dbl(fp_dbl(C))));
+            } else {
+                fp_t XB = fp_mul(ld(lds, FX, l), ld(lds, FB, l));
+                st(lds, FD, l, fp_dbl(fp_dbl(XB)));
+            }
+            return;
+        }
+        if (wave == 0) {
+            fp_t D = ld(lds, FD, l);
+            fp_t X3 = fp_sub(fp_sub(ld(lds, FF, l), D), D);
+            fp_t Y3 = fp_sub(fp_mul(ld(lds, FE, l), fp_sub(D, X3)), ld(lds, FC8, l));
+            st(lds, FX, l, X3);
+            st(lds, FY, l, Y3);
+            if (live) {
+                out[b].X = X3;
+                out[b].Y = Y3;
+            }
         }
     }
 };

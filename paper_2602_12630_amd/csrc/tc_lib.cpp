@@ -1001,7 +1001,7 @@ static int verify_steps(tc_ctx* ctx, const tc_vk* vk, const std::vector<VerifySt
     RT(rt::launch<256>(n, ctx->stream, Fill32{d_ok, 1u}));
     for (uint32_t c0 = 0; c0 < n; c0 += chunk) {       /* the chain buffer serves one chunk of steps after the other */
         uint32_t cn = n - c0 < chunk ? n - c0 : chunk;
-        RT(rt::launch<64>((uint64_t)VERIFY_CHAINS * cn, ctx->stream, VerifyChain{d_steps + c0, d_ok + c0, d_chain}));
+        RT((launch_coop<VerifyChain::BLOCK>((VERIFY_CHAINS * cn + 63) / 64, ctx->stream, VerifyChain{d_steps + c0, VERIFY_CHAINS * cn, d_ok + c0, d_chain})));
         int mmax = 1;
         for (uint32_t i = c0; i < c0 + cn; ++i) mmax = steps[i].m > mmax ? steps[i].m : mmax;
         uint32_t groups = VERIFY_CHAINS * VERIFY_BITS / 64 * (uint32_t)mmax / TC_MAX_ORDER + 1;
