@@ -174,7 +174,7 @@ TC_HD g1_xyzz xyzz_mul_affine(const uint32_t* k, int nbits, const g1_affine& p) 
 }
 
 /* Jacobian coordinates (x = X / Z^2, y = Y / Z^3; identity: Z = 0): the doubling costs two products and five
- * squarings, against six and three in XYZZ form: the form for the long doubling chains of the verifier. */
+ * squarings, against six and three in XYZZ form: the form of the verifier's long doubling chains. */
 struct g1_jac {
     fp_t X, Y, Z;
 };
@@ -183,20 +183,6 @@ TC_HD g1_jac jac_identity() {
     r.X = fe_one<FpParams>();
     r.Y = fe_one<FpParams>();
     r.Z = fe_zero<FpParams>();
-    return r;
-}
-TC_HD g1_jac jac_dbl(const g1_jac& p) {
-    if (fe_is_zero(p.Z) || fe_is_zero(p.Y)) return jac_identity();
-    fp_t A = fp_sqr(p.X);
-    fp_t B = fp_sqr(p.Y);
-    fp_t C = fp_sqr(B);
-    fp_t D = fp_dbl(fp_sub(fp_sub(fp_sqr(fp_add(p.X, B)), A), C));
-    fp_t E = fp_add(fp_dbl(A), A);
-    g1_jac r;
-    r.X = fp_sub(fp_sub(fp_sqr(E), D), D);
-    fp_t C8 = fp_dbl(fp_dbl(fp_dbl(C)));
-    r.Y = fp_sub(fp_mul(E, fp_sub(D, r.X)), C8);
-    r.Z = fp_dbl(fp_mul(p.Y, p.Z));
     return r;
 }
 TC_HD g1_xyzz jac_to_xyzz(const g1_jac& p) {

@@ -436,6 +436,146 @@ struct AccFinal {
     }
 };
 
+/* ---- sums of few points, where depth is the cost ------------------------------------------ */
+/* One workgroup of four waves adds up to 256 XYZZ points pairwise, and the four waves share every addition:
+ * its fourteen products fall into four levels of independent ones (U1 U2 S1 S2 | PP RR ZZa.ZZb ZZZa.ZZZb |
+ * PPP Q ZZ' | T1 T2 ZZZ'), and a wave alone on its SIMD issues products no faster one after the other than four
+ * waves do side by side, so an addition costs four product latencies instead of fourteen.  Points and
+ * intermediates live in LDS, field by field (lanes of a wave touch consecutive 16-byte pieces); a barrier
+ * separates the levels.  Reads of the operands happen in the first two levels, writes of the result (into the
+ * slot of the first operand) in the last three, and only when the addition is a regular one; an identity
+ * operand, opposite points and equal points are settled by wave 0 in the last level.
+ *
+ * `Src` says what is summed: count(wg) <= 256 slots, load(wg, i) the point of slot i, store(wg, sum). */
+struct Quad16 { uint32_t v[4]; };
+template <class Src>
+struct CoopReduce {
+    static constexpr int BLOCK = 256;
+    static constexpr int NP = 256;
+    enum { PX, PY, PZZ, PZZZ, NPF };
+    enum { TU1, TU2, TS1, TS2, TPP, TRR, TZA, TZB, TPPP, TQ, NT };
+    static constexpr size_t TEMP_BASE = (size_t)NPF * 3 * NP;                 /* in 16-byte pieces */
+    static constexpr size_t FLAG_BASE = (TEMP_BASE + (size_t)NT * 3 * (NP / 2)) * 16;   /* in bytes */
+    static constexpr size_t LDS_BYTES = FLAG_BASE + 3 * (NP / 2) * 4;
+    static constexpr int PHASES = 1 + 8 * 5 + 1;
+    Src src;
+
+    TC_DEV static fp_t ldq(const uint8_t* lds, size_t base, int f, uint32_t n, uint32_t i) {
+        const Quad16* q = (const Quad16*)lds + base;
+        fp_t r;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            Quad16 t = q[(size_t)(f * 3 + k) * n + i];
+            r.l[4 * k] = t.v[0]; r.l[4 * k + 1] = t.v[1]; r.l[4 * k + 2] = t.v[2]; r.l[4 * k + 3] = t.v[3];
+        }
+        return r;
+    }
+    TC_DEV static void stq(uint8_t* lds, size_t base, int f, uint32_t n, uint32_t i, const fp_t& x) {
+        Quad16* q = (Quad16*)lds + base;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            Quad16 t;
+            t.v[0] = x.l[4 * k]; t.v[1] = x.l[4 * k + 1]; t.v[2] = x.l[4 * k + 2]; t.v[3] = x.l[4 * k + 3];
+            q[(size_t)(f * 3 + k) * n + i] = t;
+        }
+    }
+    TC_DEV static fp_t pt(const uint8_t* lds, int f, uint32_t slot) { return ldq(lds, 0, f, NP, slot); }
+    TC_DEV static void pt_set(uint8_t* lds, int f, uint32_t slot, const fp_t& x) { stq(lds, 0, f, NP, slot, x); }
+    TC_DEV static fp_t tmp(const uint8_t* lds, int f, uint32_t pair) { return ldq(lds, TEMP_BASE, f, NP / 2, pair); }
+    TC_DEV static void tmp_set(uint8_t* lds, int f, uint32_t pair, const fp_t& x) { stq(lds, TEMP_BASE, f, NP / 2, pair, x); }
+    TC_DEV static g1_xyzz point(const uint8_t* lds, uint32_t slot) {
+        g1_xyzz r;
+        r.X = pt(lds, PX, slot); r.Y = pt(lds, PY, slot); r.ZZ = pt(lds, PZZ, slot); r.ZZZ = pt(lds, PZZZ, slot);
+        return r;
+    }
+    TC_DEV static void point_set(uint8_t* lds, uint32_t slot, const g1_xyzz& p) {
+        pt_set(lds, PX, slot, p.X); pt_set(lds, PY, slot, p.Y); pt_set(lds, PZZ, slot, p.ZZ); pt_set(lds, PZZZ, slot, p.ZZZ);
+    }
+
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        uint32_t count = src.count(wg);
+        if (ph == 0) {
+            point_set(lds, lane, lane < count ? src.load(wg, lane) : xyzz_identity());
+            return;
+        }
+        if (ph == PHASES - 1) {
+            if (lane == 0) src.store(wg, point(lds, 0));
+            return;
+        }
+        int lv = (ph - 1) / 5, sub = (ph - 1) % 5;
+        uint32_t stride = 1u << lv, npairs = (uint32_t)(NP / 2) >> lv;
+        uint32_t wave = lane >> 6;
+        uint32_t* flag_id = (uint32_t*)(lds + FLAG_BASE);      /* 0 regular, 1 keep a, 2 take b */
+        uint32_t* flag_pz = flag_id + NP / 2;                   /* same x */
+        uint32_t* flag_rz = flag_pz + NP / 2;                   /* same y */
+        for (uint32_t pr = lane & 63u; pr < npairs; pr += 64) {
+            uint32_t a = pr * 2 * stride, b = a + stride;
+            if (b >= count) continue;                           /* nothing but identities from b on */
+            if (sub == 0) {
+                if (wave == 0) {
+                    fp_t ZZa = pt(lds, PZZ, a), ZZb = pt(lds, PZZ, b);
+                    flag_id[pr] = fe_is_zero(ZZb) ? 1u : fe_is_zero(ZZa) ? 2u : 0u;
+                    tmp_set(lds, TU1, pr, fp_mul(pt(lds, PX, a), ZZb));
+                } else if (wave == 1) {
+                    tmp_set(lds, TU2, pr, fp_mul(pt(lds, PX, b), pt(lds, PZZ, a)));
+                } else if (wave == 2) {
+                    tmp_set(lds, TS1, pr, fp_mul(pt(lds, PY, a), pt(lds, PZZZ, b)));
+                } else {
+                    tmp_set(lds, TS2, pr, fp_mul(pt(lds, PY, b), pt(lds, PZZZ, a)));
+                }
+            } else if (sub == 1) {
+                if (wave == 0) {
+                    fp_t Pd = fp_sub(tmp(lds, TU2, pr), tmp(lds, TU1, pr));
+                    flag_pz[pr] = fe_is_zero(Pd) ? 1u : 0u;
+                    tmp_set(lds, TU2, pr, Pd);
+                    tmp_set(lds, TPP, pr, fp_sqr(Pd));
+                } else if (wave == 1) {
+                    fp_t Rd = fp_sub(tmp(lds, TS2, pr), tmp(lds, TS1, pr));
+                    flag_rz[pr] = fe_is_zero(Rd) ? 1u : 0u;
+                    tmp_set(lds, TS2, pr, Rd);
+                    tmp_set(lds, TRR, pr, fp_sqr(Rd));
+                } else if (wave == 2) {
+                    tmp_set(lds, TZA, pr, fp_mul(pt(lds, PZZ, a), pt(lds, PZZ, b)));
+                } else {
+                    tmp_set(lds, TZB, pr, fp_mul(pt(lds, PZZZ, a), pt(lds, PZZZ, b)));
+                }
+            } else {
+                bool regular = flag_id[pr] == 0u && flag_pz[pr] == 0u;
+                if (sub == 2) {
+                    if (wave == 0) {
+                        tmp_set(lds, TPPP, pr, fp_mul(tmp(lds, TU2, pr), tmp(lds, TPP, pr)));
+                    } else if (wave == 1) {
+                        tmp_set(lds, TQ, pr, fp_mul(tmp(lds, TU1, pr), tmp(lds, TPP, pr)));
+                    } else if (wave == 2) {
+                        fp_t ZZ3 = fp_mul(tmp(lds, TZA, pr), tmp(lds, TPP, pr));
+                        if (regular) pt_set(lds, PZZ, a, ZZ3);
+                    }
+                } else if (sub == 3) {
+                    if (wave == 0) {
+                        fp_t Q = tmp(lds, TQ, pr);
+                        fp_t X3 = fp_sub(fp_sub(fp_sub(tmp(lds, TRR, pr), tmp(lds, TPPP, pr)), Q), Q);
+                        tmp_set(lds, TRR, pr, fp_mul(tmp(lds, TS2, pr), fp_sub(Q, X3)));
+                        if (regular) pt_set(lds, PX, a, X3);
+                    } else if (wave == 1) {
+                        tmp_set(lds, TS1, pr, fp_mul(tmp(lds, TS1, pr), tmp(lds, TPPP, pr)));
+                    } else if (wave == 2) {
+                        fp_t ZZZ3 = fp_mul(tmp(lds, TZB, pr), tmp(lds, TPPP, pr));
+                        if (regular) pt_set(lds, PZZZ, a, ZZZ3);
+                    }
+                } else if (wave == 0) {
+                    if (regular) {
+                        pt_set(lds, PY, a, fp_sub(tmp(lds, TRR, pr), tmp(lds, TS1, pr)));
+                    } else if (flag_id[pr] == 2u) {
+                        point_set(lds, a, point(lds, b));
+                    } else if (flag_id[pr] == 0u) {             /* same x: the same point, or opposite ones */
+                        point_set(lds, a, flag_rz[pr] ? xyzz_dbl(point(lds, a)) : xyzz_identity());
+                    }
+                }
+            }
+        }
+    }
+};
+
 /* ---- bucket reduction: sum_k k B_k --------------------------------------------------- */
 /* Cooperative kernel (one workgroup = BLOCK consecutive entries of `in`), phases separated
  * by barriers.  For block g:  S_g = sum_j in[g BLOCK + j]  and
@@ -911,6 +1051,32 @@ struct NodeCommitFrCoop {
         if (ph == logL + 1 && r == 0 && a < n_nodes) out[a] = buf[lane];
     }
 };
+/* levels of very few nodes: a node is the sum of its B * FB_W (child, window) table points */
+struct NodeWindowSrc {
+    TreeGeom g;
+    const fr_plain* below;
+    const g1_affine* table;
+    g1_xyzz* out;               /* n_nodes */
+    TC_DEV uint32_t count(uint32_t) const { return g.B * (uint32_t)FB_W < 256u ? g.B * (uint32_t)FB_W : 256u; }
+    TC_DEV g1_xyzz load(uint32_t node, uint32_t i) const {
+        g1_xyzz acc = xyzz_identity();
+        for (uint32_t idx = i; idx < g.B * (uint32_t)FB_W; idx += 256) {
+            uint32_t k = idx / (uint32_t)FB_W, w = idx % (uint32_t)FB_W;
+            int64_t f = child_index(g, node, k);
+            if (f < 0) continue;
+            const uint32_t* v = below[f].l;
+            uint32_t carry = 0;
+            int32_t d = 0;
+            for (uint32_t x = 0; x <= w; ++x) d = fr_window_digit(v, (int)x, FB_C, carry);
+            if (!d) continue;
+            g1_affine p = table[((uint64_t)k * FB_W + w) * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u];
+            if (d < 0) p.y = fp_neg(p.y);
+            acc = xyzz_madd(acc, p);
+        }
+        return acc;
+    }
+    TC_DEV void store(uint32_t node, const g1_xyzz& r) const { out[node] = r; }
+};
 /* out[i] = sum of in[i * group .. (i + 1) * group) */
 struct SumGroups {
     const g1_xyzz* in;
@@ -923,32 +1089,23 @@ struct SumGroups {
         out[t] = acc;
     }
 };
-/* out[t] = sum of a segment of `in`, a wave per segment: strided partial sums, then pairwise through LDS; the elements of segment
- * t are in[off[t] * scale .. off[t + 1] * scale) */
-struct SumSegmentsCoop {
-    static constexpr int BLOCK = 64;
-    static constexpr size_t LDS_BYTES = BLOCK * sizeof(g1_xyzz);
-    static constexpr int PHASES = 8;         /* 1 + log2(64) + 1 */
+/* out[t] = sum of segment t of `in`: the elements in[off[t] * scale .. off[t + 1] * scale) */
+struct SegmentSrc {
     const g1_xyzz* in;
     const uint32_t* off;
     uint32_t scale;
     g1_xyzz* out;
-    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
-        g1_xyzz* buf = (g1_xyzz*)lds;
-        if (ph == 0) {
-            uint64_t lo = (uint64_t)off[wg] * scale, hi = (uint64_t)off[wg + 1] * scale;
-            g1_xyzz acc = xyzz_identity();
-            for (uint64_t i = lo + lane; i < hi; i += BLOCK) acc = xyzz_add(acc, in[i]);
-            buf[lane] = acc;
-            return;
-        }
-        if (ph <= 6) {
-            uint32_t stride = 1u << (ph - 1);
-            if ((lane & (2 * stride - 1)) == 0) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
-            return;
-        }
-        if (lane == 0) out[wg] = buf[0];
+    TC_DEV uint32_t count(uint32_t t) const {
+        uint64_t len = (uint64_t)(off[t + 1] - off[t]) * scale;
+        return len < 256 ? (uint32_t)len : 256u;
     }
+    TC_DEV g1_xyzz load(uint32_t t, uint32_t i) const {
+        uint64_t lo = (uint64_t)off[t] * scale, hi = (uint64_t)off[t + 1] * scale;
+        g1_xyzz acc = in[lo + i];
+        for (uint64_t x = lo + i + 256; x < hi; x += 256) acc = xyzz_add(acc, in[x]);
+        return acc;
+    }
+    TC_DEV void store(uint32_t t, const g1_xyzz& r) const { out[t] = r; }
 };
 
 /* ---- Open: quotient values on the grid (Algorithm 1 in evaluation form) ----------------- */
@@ -1237,8 +1394,8 @@ TC_HD bool xyzz_equal(const g1_xyzz& a, const g1_xyzz& b) {
 }
 /* The 128 doublings of a half-length scalar multiplication cannot be spread over lanes, everything else can:
  * chain (step, j) of VerifyChain walks P, 2P, 4P, .. 2^127 P (chain 2i: P = pi_i, chain 2i + 1: its image
- * (beta x, y)) and keeps every point; VerifySum and VerifyDecide then add, for a step, the points whose bit is
- * set in the half scalars, the window terms of [y]G and -C pairwise, and accept iff
+ * (beta x, y)) and keeps every point; cooperative sums then add, for a step, the points whose bit is set in
+ * the half scalars, the window terms of [y]G and -C, and the step is accepted iff
  *   sum_i [k_i] pi_i + [y] G - C = O. */
 /* Three waves per 64 chains: the seven products of a Jacobian doubling (A = X^2, B = Y^2, YZ; F = (3A)^2,
  * C = B^2, XB; E (D - X3)) fall into three levels of independent ones, and a wave alone on its SIMD issues
@@ -1348,85 +1505,60 @@ struct VerifyChain {
         }
     }
 };
-/* Workgroups of one wave each (pairwise sums through LDS run at full speed only then): of the `groups` groups
- * of a step (4 m + 1, m the largest order among the steps of the launch) all but the last add the points of 64
- * consecutive (chain, bit) slots, the last one the window terms of [y]G and -C. */
-constexpr uint32_t VERIFY_MAX_GROUPS = VERIFY_CHAINS * VERIFY_BITS / 64 + 1;
-struct VerifySum {
-    static constexpr int BLOCK = 64;
-    static constexpr size_t LDS_BYTES = BLOCK * sizeof(g1_xyzz);
-    static constexpr int PHASES = 8;         /* gather, 6 halving steps, store */
+/* What the cooperative sums of a step add: group g < groups - 1 the points of chains 2g and 2g + 1 whose bit is
+ * set (an identity elsewhere), the last group the window terms of [y]G and -C; `groups` is one more than the
+ * largest order among the steps of the launch. */
+struct VerifyGroupSrc {
     const VerifyStep* steps;
     const g1_affine* gtable;
     const g1_jac* chain;
     uint32_t* ok;
     uint32_t groups;
     g1_xyzz* partial;          /* steps * groups */
-    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
-        g1_xyzz* buf = (g1_xyzz*)lds;
+    TC_DEV uint32_t count(uint32_t wg) const {
+        uint32_t s = wg / groups, g = wg % groups;
+        if (g + 1 == groups) return (uint32_t)FB_W + 1u;
+        return (int)g < steps[s].m ? 2u * VERIFY_BITS : 0u;
+    }
+    TC_DEV g1_xyzz load(uint32_t wg, uint32_t i) const {
         uint32_t s = wg / groups, g = wg % groups;
         const VerifyStep& st = steps[s];
-        if (ph == 0) {
-            g1_xyzz acc = xyzz_identity();
-            if (g + 1 < groups) {
-                uint32_t idx = g * BLOCK + lane;
-                uint32_t j = idx / VERIFY_BITS, b = idx % VERIFY_BITS;
-                if ((int)(j >> 1) < st.m) {
-                    const uint32_t* k = (j & 1u) ? st.k2[j >> 1] : st.k1[j >> 1];
-                    if ((k[b >> 5] >> (b & 31)) & 1u)
-                        acc = jac_to_xyzz(chain[((uint64_t)s * VERIFY_CHAINS + j) * VERIFY_BITS + b]);
-                }
-            } else if (lane <= (uint32_t)FB_W) {
-                g1_affine p = affine_identity();
-                if (lane < (uint32_t)FB_W) {         /* window `lane` of [y] G */
-                    uint32_t carry = 0;
-                    int32_t d = 0;
-                    for (uint32_t w = 0; w <= lane; ++w) d = fr_window_digit(st.y, (int)w, FB_C, carry);
-                    if (d) {
-                        p = gtable[(uint64_t)lane * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u];
-                        if (d < 0) p.y = fp_neg(p.y);
-                    }
-                } else {                             /* -C, and the checks on C and y */
-                    p = affine_from_canonical(st.C);
-                    bool good = canonical_fp(st.C) && canonical_fp(st.C + 12) && affine_on_curve(p) && limbs_gt<8>(FrParams::MOD, st.y);
-                    if (!good) atomic_and_u32(&ok[s], 0u);
-                    p = affine_neg(p);
-                }
-                acc = xyzz_from_affine(p);
+        if (g + 1 < groups) {
+            uint32_t j = 2 * g + i / VERIFY_BITS, b = i % VERIFY_BITS;
+            const uint32_t* k = (j & 1u) ? st.k2[j >> 1] : st.k1[j >> 1];
+            if (!((k[b >> 5] >> (b & 31)) & 1u)) return xyzz_identity();
+            return jac_to_xyzz(chain[((uint64_t)s * VERIFY_CHAINS + j) * VERIFY_BITS + b]);
+        }
+        g1_affine p = affine_identity();
+        if (i < (uint32_t)FB_W) {                /* window i of [y] G */
+            uint32_t carry = 0;
+            int32_t d = 0;
+            for (uint32_t w = 0; w <= i; ++w) d = fr_window_digit(st.y, (int)w, FB_C, carry);
+            if (d) {
+                p = gtable[(uint64_t)i * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u];
+                if (d < 0) p.y = fp_neg(p.y);
             }
-            buf[lane] = acc;
-            return;
+        } else {                                 /* -C, and the checks on C and y */
+            p = affine_from_canonical(st.C);
+            bool good = canonical_fp(st.C) && canonical_fp(st.C + 12) && affine_on_curve(p) && limbs_gt<8>(FrParams::MOD, st.y);
+            if (!good) atomic_and_u32(&ok[s], 0u);
+            p = affine_neg(p);
         }
-        if (ph <= 6) {
-            uint32_t stride = 1u << (ph - 1);
-            if ((lane & (2 * stride - 1)) == 0) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
-            return;
-        }
-        if (lane == 0) partial[wg] = buf[0];
+        return xyzz_from_affine(p);
     }
+    TC_DEV void store(uint32_t wg, const g1_xyzz& r) const { partial[wg] = r; }
 };
-struct VerifyDecide {          /* workgroup = step: the partial sums must cancel */
-    static constexpr int BLOCK = 64;
-    static constexpr size_t LDS_BYTES = BLOCK * sizeof(g1_xyzz);
-    static constexpr int PHASES = 7;         /* load, 5 halving steps over 32 slots, decision */
+struct VerifyDecideSrc {       /* workgroup = step: the partial sums must cancel */
     const g1_xyzz* partial;
     uint32_t groups;
     uint32_t* ok;
-    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
-        g1_xyzz* buf = (g1_xyzz*)lds;
-        if (ph == 0) {
-            buf[lane] = lane < groups ? partial[(uint64_t)wg * groups + lane] : xyzz_identity();
-            return;
-        }
-        if (ph <= 5) {
-            uint32_t stride = 1u << (ph - 1);
-            if (lane < 32 && (lane & (2 * stride - 1)) == 0) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
-            return;
-        }
-        if (lane == 0 && !xyzz_is_identity(buf[0])) ok[wg] = 0;
+    TC_DEV uint32_t count(uint32_t) const { return groups; }
+    TC_DEV g1_xyzz load(uint32_t s, uint32_t i) const { return partial[(uint64_t)s * groups + i]; }
+    TC_DEV void store(uint32_t s, const g1_xyzz& r) const {
+        if (!xyzz_is_identity(r)) ok[s] = 0;
     }
 };
-static_assert(VERIFY_MAX_GROUPS <= 32, "VerifyDecide sums 32 slots");
+constexpr uint32_t VERIFY_MAX_GROUPS = VERIFY_CHAINS / 2 + 1;
 /* phi of canonical commitments (the verifier's side of "the opened value matches the next commitment") */
 struct PhiCanonical {
     const uint32_t* pts;       /* 24 words each */

@@ -553,6 +553,8 @@ static int launch_coop(uint32_t groups, rt::stream_t st, const F& f) {
 }
 #endif
 
+/* a tree level of at most this many nodes (one workgroup per compute unit) takes the cooperative sums */
+static const uint64_t COOP_LEVEL_NODES = 256;
 /* a tree level spreads the windows of a child over lanes as long as it stays within this many lanes (two waves per SIMD) */
 static const uint64_t SPLIT_LEVEL_LANES = 131072;
 
@@ -1004,9 +1006,11 @@ static int verify_steps(tc_ctx* ctx, const tc_vk* vk, const std::vector<VerifySt
         RT((launch_coop<VerifyChain::BLOCK>((VERIFY_CHAINS * cn + 63) / 64, ctx->stream, VerifyChain{d_steps + c0, VERIFY_CHAINS * cn, d_ok + c0, d_chain})));
         int mmax = 1;
         for (uint32_t i = c0; i < c0 + cn; ++i) mmax = steps[i].m > mmax ? steps[i].m : mmax;
-        uint32_t groups = VERIFY_CHAINS * VERIFY_BITS / 64 * (uint32_t)mmax / TC_MAX_ORDER + 1;
-        RT((launch_coop<VerifySum::BLOCK>(cn * groups, ctx->stream, VerifySum{d_steps + c0, ctx->gtable, d_chain, d_ok + c0, groups, d_part})));
-        RT((launch_coop<VerifyDecide::BLOCK>(cn, ctx->stream, VerifyDecide{d_part, groups, d_ok + c0})));
+        uint32_t groups = (uint32_t)mmax + 1u;
+        typedef CoopReduce<VerifyGroupSrc> Sum;
+        typedef CoopReduce<VerifyDecideSrc> Decide;
+        RT((launch_coop<Sum::BLOCK>(cn * groups, ctx->stream, Sum{VerifyGroupSrc{d_steps + c0, ctx->gtable, d_chain, d_ok + c0, groups, d_part}})));
+        RT((launch_coop<Decide::BLOCK>(cn, ctx->stream, Decide{VerifyDecideSrc{d_part, groups, d_ok + c0}})));
     }
     RT(rt::memcpy_d2h(ok.data(), d_ok, 4ull * n, ctx->stream));
     RT(rt::stream_sync(ctx->stream));
@@ -1208,6 +1212,10 @@ extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** 
                         prof_begin(ctx, TC_PROF_NODE_COMMIT, &e0, &e1);
                         e = rt::launch<64>(lv.n, ctx->stream, NodeCommitSmall{g, t->d_payload, t->dtype, ns->fb[0], acc});
                         prof_end(ctx, TC_PROF_NODE_COMMIT, e0, e1);
+                    } else if (lv.n <= COOP_LEVEL_NODES) {
+                        /* very few nodes: every (child, window) term its own lane, sums shared by four waves */
+                        typedef CoopReduce<NodeWindowSrc> Sum;
+                        e = launch_coop<Sum::BLOCK>((uint32_t)lv.n, ctx->stream, Sum{NodeWindowSrc{g, t->levels[L - 1].phi, ns->fb[0], acc}});
                     } else if ((t->B & (t->B - 1)) == 0 && t->B <= 64) {
                         int logB = 0;
                         while ((1u << logB) < t->B) ++logB;
@@ -1428,7 +1436,8 @@ extern "C" int tc_terkle_open_batch(tc_ctx* ctx, const tc_tree* t, int count, co
             k.y_out = d_y;
             k.logH = logH;
             RT(rt::launch<64>(((uint64_t)jobs * terms) << logH, ctx->stream, k));
-            RT((launch_coop<SumSegmentsCoop::BLOCK>(jobs * (uint32_t)m, ctx->stream, SumSegmentsCoop{d_terms, d_seg, 1u << logH, d_pi})));
+            typedef CoopReduce<SegmentSrc> Sum;
+            RT((launch_coop<Sum::BLOCK>(jobs * (uint32_t)m, ctx->stream, Sum{SegmentSrc{d_terms, d_seg, 1u << logH, d_pi}})));
         } else {
             /* large node shapes: gather the node tensor and open it like any tensor */
             for (int i = 0; i < count; ++i)

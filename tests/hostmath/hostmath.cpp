@@ -3,7 +3,10 @@
 // the CPU test-suite check them against the oracle without a GPU.
 #include <cstring>
 
-#include "../../paper_2602_12630_amd/csrc/g1.h"
+#define TC_HOST_EMU 1
+#include <vector>
+
+#include "../../paper_2602_12630_amd/csrc/kernels.h"
 
 using namespace tc;
 
@@ -48,13 +51,29 @@ void hm_g1_mul(const uint8_t* k, const uint8_t* p, uint8_t* o) {
     uint32_t w[8]; memcpy(w, k, 32);
     pt_store(o, xyzz_to_affine(xyzz_mul_affine(w, 256, pt_load(p))));
 }
-// 2^n P through the Jacobian doubling the verifier's chains use
-void hm_g1_dbl_chain(const uint8_t* p, int n, uint8_t* o) {
-    g1_affine a = pt_load(p);
-    g1_jac q = jac_identity();
-    if (!affine_is_identity(a)) { q.X = a.x; q.Y = a.y; q.Z = fe_one<FpParams>(); }
-    for (int i = 0; i < n; ++i) q = jac_dbl(q);
-    pt_store(o, xyzz_to_affine(jac_to_xyzz(q)));
+// sum of n points through the four-wave cooperative reduction, phases run lane by lane
+struct ArraySrc {
+    const g1_xyzz* in;
+    uint32_t n;
+    g1_xyzz* out;
+    uint32_t count(uint32_t) const { return n; }
+    g1_xyzz load(uint32_t, uint32_t i) const { return in[i]; }
+    void store(uint32_t, const g1_xyzz& r) const { *out = r; }
+};
+void hm_coop_reduce(const uint8_t* pts, uint32_t n, int spread, uint8_t* o) {
+    std::vector<g1_xyzz> in(n ? n : 1);
+    for (uint32_t i = 0; i < n; ++i) {
+        g1_affine a = pt_load(pts + 96 * (size_t)i);
+        // spread = 1: operands away from ZZ = 1, as sums of sums are (2a - a)
+        in[i] = spread ? xyzz_madd(xyzz_dbl_affine(a), affine_neg(a)) : xyzz_from_affine(a);
+    }
+    g1_xyzz r;
+    typedef CoopReduce<ArraySrc> K;
+    K k{ArraySrc{in.data(), n, &r}};
+    std::vector<uint8_t> lds(K::LDS_BYTES);
+    for (int ph = 0; ph < K::PHASES; ++ph)
+        for (uint32_t lane = 0; lane < (uint32_t)K::BLOCK; ++lane) k.phase(ph, lane, 0, lds.data());
+    pt_store(o, xyzz_to_affine(r));
 }
 void hm_g1_generator(uint8_t* o) { pt_store(o, affine_generator()); }
 void hm_phi(const uint8_t* p, uint8_t* o) { fr_t v = phi_map(pt_load(p)); memcpy(o, v.l, 32); }

@@ -20,7 +20,7 @@ LIB = os.path.join(HERE, "hostmath", "libhostmath.so")
 
 @pytest.fixture(scope="module")
 def hm():
-    hdrs = [os.path.join(HERE, "..", "paper_2602_12630_amd", "csrc", h) for h in ("field.h", "g1.h", "constants.h")]
+    hdrs = [os.path.join(HERE, "..", "paper_2602_12630_amd", "csrc", h) for h in ("field.h", "g1.h", "constants.h", "kernels.h", "rt.h")]
     newest = max(os.path.getmtime(f) for f in [SRC] + hdrs)
     if not os.path.exists(LIB) or os.path.getmtime(LIB) < newest:
         subprocess.check_call(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-o", LIB, SRC])
@@ -107,10 +107,48 @@ def test_group_law_including_exceptional_cases(hm):
         assert _pt(hm.hm_g1_add, _pb(ec.INF), _pb(ec.INF), mode) is ec.INF
     for k in (0, 1, 2, 3, R - 1, rng.randrange(R), 1 << 200):
         assert _pt(hm.hm_g1_mul, _b(k, 32), _pb(pts[0])) == ec.mul_affine(k, pts[0])
-    # Jacobian doubling chain: 2^n P for the lengths around a half scalar, and the identity
-    for n in (0, 1, 2, 5, 127, 128):
-        assert _pt(hm.hm_g1_dbl_chain, _pb(pts[1]), n) == ec.mul_affine(1 << n, pts[1]), n
-    assert _pt(hm.hm_g1_dbl_chain, _pb(ec.INF), 7) is ec.INF
+
+def test_cooperative_reduction(hm):
+    """Sums of up to 256 points through the shared-addition kernel, with the operand patterns that leave the
+    regular chord rule: identities anywhere, equal neighbours (tangent rule), opposite neighbours, everything
+    cancelling."""
+    rng = random.Random(5)
+    base = [ec.mul(rng.randrange(1, R), ec.G1) for _ in range(6)]
+
+    def run(points, spread):
+        buf = b"".join(ec.g1_to_bytes(p) for p in points)
+        arr = (ctypes.c_uint8 * max(len(buf), 1)).from_buffer_copy(buf or b"\0")
+        out = (ctypes.c_uint8 * 96)()
+        hm.hm_coop_reduce(arr, len(points), spread, out)
+        return ec.g1_from_bytes(bytes(out))
+
+    def want(points):
+        acc = ec.INF
+        for p in points:
+            acc = ec.add_affine(acc, p)
+        return acc
+
+    cases = [
+        [],
+        [base[0]],
+        [base[0], base[1]],
+        [base[0], base[0]],                                  # tangent rule at the first level
+        [base[0], ec.neg(base[0])],                          # opposite points
+        [ec.INF, base[2]],
+        [base[2], ec.INF],
+        [ec.INF, ec.INF, ec.INF],
+        [base[0], base[1], base[0], base[1]],                # equal partial sums one level up
+        [base[0], base[1], ec.neg(base[0]), ec.neg(base[1])],
+        [base[i % 6] for i in range(17)],
+        [base[rng.randrange(6)] if rng.random() < 0.6 else ec.INF for _ in range(255)],
+        [ec.mul(i + 1, base[3]) for i in range(64)] + [ec.neg(ec.mul(i + 1, base[3])) for i in range(64)],
+        [base[rng.randrange(6)] for _ in range(256)],
+    ]
+    for spread in (0, 1):
+        for pts in cases:
+            got = run(pts, spread)
+            w = want(pts)
+            assert (got is ec.INF and w is ec.INF) or got == w, (len(pts), spread)
 
 
 def test_phi_map(hm):
