@@ -9,6 +9,7 @@
 #include <algorithm>
 #include <new>
 #include <string>
+#include <memory>
 #include <vector>
 
 #include "../../include/tc.h"
@@ -25,7 +26,17 @@ struct Arena {
     std::vector<void*> extra;
 };
 
+/* The level arrays of the last destroyed tree, kept for the next build: allocating and freeing device memory
+ * costs more than a small tree's levels and waits for every stream of the device.  Shared by a context and
+ * its trees, so that either may go first. */
+struct TreePool {
+    void* block = nullptr;
+    size_t cap = 0;
+    bool closed = false;
+};
+
 struct tc_ctx {
+    std::shared_ptr<TreePool> tree_pool = std::make_shared<TreePool>();
     int device = 0;
     rt::stream_t stream = nullptr;
     std::string err;
@@ -67,6 +78,8 @@ struct tc_tree {
     std::vector<int> leaf_dtype;
     std::vector<TreeLevel> levels;
     void* block = nullptr;          /* one device allocation holds C and phi of every level */
+    size_t block_cap = 0;
+    std::shared_ptr<TreePool> pool;
     uint8_t root[96];
 };
 
@@ -214,6 +227,10 @@ extern "C" void tc_ctx_destroy(tc_ctx* ctx) {
     for (void* p : ctx->ws.extra) rt::dev_free(p);
     if (ctx->ws.base) rt::dev_free(ctx->ws.base);
     if (ctx->gtable) rt::dev_free(ctx->gtable);
+    if (ctx->tree_pool->block) rt::dev_free(ctx->tree_pool->block);
+    ctx->tree_pool->block = nullptr;
+    ctx->tree_pool->cap = 0;
+    ctx->tree_pool->closed = true;
     for (auto& v : ctx->prof)
         for (auto& pr : v) { rt::event_destroy(pr.first); rt::event_destroy(pr.second); }
     delete ctx;
@@ -1044,7 +1061,19 @@ extern "C" int tc_verify(tc_ctx* ctx, const tc_vk* vk, int m, const uint32_t* sh
 /* ======================================================================================= */
 extern "C" void tc_tree_destroy(tc_tree* tree) {
     if (!tree) return;
-    if (tree->block) rt::dev_free(tree->block);
+    if (tree->block) {
+        TreePool* pool = tree->pool.get();
+        if (pool && !pool->closed && tree->block_cap > pool->cap) {
+            if (pool->block) rt::dev_free(pool->block);
+            pool->block = tree->block;
+            pool->cap = tree->block_cap;
+        } else if (pool && !pool->closed && !pool->block) {
+            pool->block = tree->block;
+            pool->cap = tree->block_cap;
+        } else {
+            rt::dev_free(tree->block);
+        }
+    }
     delete tree;
 }
 extern "C" int tc_terkle_root(const tc_tree* tree, uint8_t out_g1[96]) {
@@ -1176,8 +1205,18 @@ extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** 
     {
         size_t total = 0;
         for (auto& lv : t->levels) total += ((size_t)lv.n * sizeof(g1_affine) + 255) / 256 * 256 + ((size_t)lv.n * sizeof(fr_plain) + 255) / 256 * 256;
-        if (rt::dev_malloc(&t->block, total) != 0) {
+        t->pool = ctx->tree_pool;
+        if (ctx->tree_pool->block && ctx->tree_pool->cap >= total) {
+            t->block = ctx->tree_pool->block;
+            t->block_cap = ctx->tree_pool->cap;
+            ctx->tree_pool->block = nullptr;
+            ctx->tree_pool->cap = 0;
+        } else if (rt::dev_malloc(&t->block, total) == 0) {
+            t->block_cap = total;
+        } else {
             t->block = nullptr;
+        }
+        if (!t->block) {
             rc = fail(ctx, TC_ERR_NOMEM, "tree level allocation failed");
         } else {
             uint8_t* at = (uint8_t*)t->block;
