@@ -454,10 +454,11 @@ struct CoopReduce {
     static constexpr int NP = 256;
     enum { PX, PY, PZZ, PZZZ, NPF };
     enum { TU1, TU2, TS1, TS2, TPP, TRR, TZA, TZB, TPPP, TQ, NT };
+    static constexpr int TP = 64;                                             /* pairs in flight: one per lane of a wave */
     static constexpr size_t TEMP_BASE = (size_t)NPF * 3 * NP;                 /* in 16-byte pieces */
-    static constexpr size_t FLAG_BASE = (TEMP_BASE + (size_t)NT * 3 * (NP / 2)) * 16;   /* in bytes */
-    static constexpr size_t LDS_BYTES = FLAG_BASE + 3 * (NP / 2) * 4;
-    static constexpr int PHASES = 1 + 8 * 5 + 1;
+    static constexpr size_t FLAG_BASE = (TEMP_BASE + (size_t)NT * 3 * TP) * 16;   /* in bytes */
+    static constexpr size_t LDS_BYTES = FLAG_BASE + 3 * TP * 4;
+    static constexpr int PHASES = 1 + 9 * 5 + 1;     /* load; the 128 pairs of the first level in two passes, seven more levels; store */
     Src src;
 
     TC_DEV static fp_t ldq(const uint8_t* lds, size_t base, int f, uint32_t n, uint32_t i) {
@@ -481,8 +482,8 @@ struct CoopReduce {
     }
     TC_DEV static fp_t pt(const uint8_t* lds, int f, uint32_t slot) { return ldq(lds, 0, f, NP, slot); }
     TC_DEV static void pt_set(uint8_t* lds, int f, uint32_t slot, const fp_t& x) { stq(lds, 0, f, NP, slot, x); }
-    TC_DEV static fp_t tmp(const uint8_t* lds, int f, uint32_t pair) { return ldq(lds, TEMP_BASE, f, NP / 2, pair); }
-    TC_DEV static void tmp_set(uint8_t* lds, int f, uint32_t pair, const fp_t& x) { stq(lds, TEMP_BASE, f, NP / 2, pair, x); }
+    TC_DEV static fp_t tmp(const uint8_t* lds, int f, uint32_t t) { return ldq(lds, TEMP_BASE, f, TP, t); }
+    TC_DEV static void tmp_set(uint8_t* lds, int f, uint32_t t, const fp_t& x) { stq(lds, TEMP_BASE, f, TP, t, x); }
     TC_DEV static g1_xyzz point(const uint8_t* lds, uint32_t slot) {
         g1_xyzz r;
         r.X = pt(lds, PX, slot); r.Y = pt(lds, PY, slot); r.ZZ = pt(lds, PZZ, slot); r.ZZZ = pt(lds, PZZZ, slot);
@@ -502,15 +503,19 @@ struct CoopReduce {
             if (lane == 0) src.store(wg, point(lds, 0));
             return;
         }
-        int lv = (ph - 1) / 5, sub = (ph - 1) % 5;
+        int q = ph - 1;
+        int lv = q < 10 ? 0 : (q - 10) / 5 + 1, sub = q % 5;
         uint32_t stride = 1u << lv, npairs = (uint32_t)(NP / 2) >> lv;
         uint32_t wave = lane >> 6;
         uint32_t* flag_id = (uint32_t*)(lds + FLAG_BASE);      /* 0 regular, 1 keep a, 2 take b */
-        uint32_t* flag_pz = flag_id + NP / 2;                   /* same x */
-        uint32_t* flag_rz = flag_pz + NP / 2;                   /* same y */
-        for (uint32_t pr = lane & 63u; pr < npairs; pr += 64) {
+        uint32_t* flag_pz = flag_id + TP;                       /* same x */
+        uint32_t* flag_rz = flag_pz + TP;                       /* same y */
+        {
+            uint32_t pr = (lane & 63u) + ((q >= 5 && q < 10) ? 64u : 0u);       /* the pair; its temporaries sit at lane & 63 */
+            if (pr >= npairs) return;
             uint32_t a = pr * 2 * stride, b = a + stride;
-            if (b >= count) continue;                           /* nothing but identities from b on */
+            if (b >= count) return;                             /* nothing but identities from b on */
+            pr &= 63u;
             if (sub == 0) {
                 if (wave == 0) {
                     fp_t ZZa = pt(lds, PZZ, a), ZZb = pt(lds, PZZ, b);

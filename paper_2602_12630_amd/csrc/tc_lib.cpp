@@ -570,8 +570,8 @@ static int launch_coop(uint32_t groups, rt::stream_t st, const F& f) {
 }
 #endif
 
-/* a tree level of at most this many nodes (one workgroup per compute unit) takes the cooperative sums */
-static const uint64_t COOP_LEVEL_NODES = 256;
+/* a tree level of at most this many nodes (two workgroups per compute unit) takes the cooperative sums */
+static const uint64_t COOP_LEVEL_NODES = 512;
 /* a tree level spreads the windows of a child over lanes as long as it stays within this many lanes (two waves per SIMD) */
 static const uint64_t SPLIT_LEVEL_LANES = 131072;
 
