@@ -314,6 +314,8 @@ def main():
     nonzero = int(np.count_nonzero(q))
     acc_ms, acc_launches = ctx.profile_read(T.binding.TC_PROF_BUCKET_ACC)
     node_ms, node_launches = ctx.profile_read(T.binding.TC_PROF_NODE_COMMIT)
+    upper_ms, upper_launches = ctx.profile_read(T.binding.TC_PROF_NODE_COMMIT_UPPER)
+    chain_ms, chain_launches = ctx.profile_read(T.binding.TC_PROF_VERIFY_CHAIN)
     ctx.profile(False)
     kern_ms = acc_ms / max(acc_launches, 1)              # HIP events around each launch, on the library's stream
     commit_ms = phase_ms["commit"]
@@ -345,6 +347,30 @@ def main():
                      "launches": acc_launches, "mixed_additions_per_launch": nonzero,
                      "node_commit_kernel_ms": node_ms / max(node_launches, 1)},
     }
+    # the other long launches of a step, with the same accounting (a squaring counted as a product); the upper
+    # tree levels and the verifier's doubling chains are bound by depth, not by the ALUs, at this size
+    levels, g = [], shape
+    while True:
+        g = tuple(-(-d // b) for d, b in zip(g, node))
+        levels.append(int(np.prod(g)))
+        if all(d == 1 for d in g):
+            break
+    upper_children = sum(levels[:-1])                      # children of levels 1.. = nodes of the levels below
+    per_mixed = FP_MULS_PER_MIXED_ADD * MADS_PER_FP_MUL
+
+    def kernel_line(name, ms_step, mads_step, note):
+        ach = mads_step / (ms_step * 1e-3) if ms_step > 0 else 0.0
+        return {"kernel": name, "ms_per_step": ms_step, "achieved": ach / 1e12, "frac": ach / PEAK_MADS_PER_S, "note": note}
+
+    chains = sum(2 * int(p.m[s]) for p in paths for s in range(p.n_steps))
+    out["other_kernels"] = [
+        kernel_line("NodeCommitSmall (level 0 of the tree)", node_ms / prof_steps, nonzero * per_mixed,
+                    "one mixed addition per non-zero entry, fixed-base tables"),
+        kernel_line("node commitments of levels 1..%d" % (len(levels) - 1), upper_ms / prof_steps,
+                    upper_children * 16 * per_mixed, "16 window terms per child; %d launches a step, the small levels bound by depth" % (upper_launches // prof_steps)),
+        kernel_line("VerifyChain", chain_ms / prof_steps, chains * 127 * 7 * MADS_PER_FP_MUL,
+                    "%d chains of 127 Jacobian doublings, three waves a chain group: bound by depth" % chains),
+    ]
     if not args.no_c3:
         out["terkle_build_llama2_7b_fwd"] = c3_forward(ctx, T, torch, node_srs, tau)
     if not args.no_cpu_baseline:

@@ -78,7 +78,9 @@ int tc_ctx_sync(tc_ctx* ctx);
  * the last read, and resets them. */
 #define TC_PROF_BUCKET_ACC 0 /* bucket accumulation of tc_commit: one mixed addition per non-zero entry */
 #define TC_PROF_NODE_COMMIT 1 /* bottom-level node commitments of an entries tree */
-#define TC_PROF_KINDS 2
+#define TC_PROF_NODE_COMMIT_UPPER 2 /* node commitments of the levels above (one launch per level) */
+#define TC_PROF_VERIFY_CHAIN 3 /* doubling chains of path verification */
+#define TC_PROF_KINDS 4
 int tc_ctx_profile(tc_ctx* ctx, int enable);
 int tc_ctx_profile_read(tc_ctx* ctx, int kind, double* total_ms, uint64_t* launches);
 

@@ -12,7 +12,7 @@ TC_ERR_ARG, TC_ERR_SHAPE, TC_ERR_RANGE, TC_ERR_NOMEM, TC_ERR_HIP, TC_ERR_VERIFY,
 TC_I8, TC_I16, TC_FR, TC_F16 = 1, 2, 3, 4
 TC_SRS_SUFFIX, TC_SRS_FIXED_BASE = 1, 2
 TC_LEAF_ENTRIES, TC_LEAF_TENSORS = 0, 1
-TC_PROF_BUCKET_ACC, TC_PROF_NODE_COMMIT = 0, 1
+TC_PROF_BUCKET_ACC, TC_PROF_NODE_COMMIT, TC_PROF_NODE_COMMIT_UPPER, TC_PROF_VERIFY_CHAIN = 0, 1, 2, 3
 TC_MAX_ORDER, TC_MAX_STEPS = 4, 16
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

@@ -1020,7 +1020,11 @@ static int verify_steps(tc_ctx* ctx, const tc_vk* vk, const std::vector<VerifySt
     RT(rt::launch<256>(n, ctx->stream, Fill32{d_ok, 1u}));
     for (uint32_t c0 = 0; c0 < n; c0 += chunk) {       /* the chain buffer serves one chunk of steps after the other */
         uint32_t cn = n - c0 < chunk ? n - c0 : chunk;
-        RT((launch_coop<VerifyChain::BLOCK>((VERIFY_CHAINS * cn + 63) / 64, ctx->stream, VerifyChain{d_steps + c0, VERIFY_CHAINS * cn, d_ok + c0, d_chain})));
+        rt::event_t e0, e1;
+        prof_begin(ctx, TC_PROF_VERIFY_CHAIN, &e0, &e1);
+        int ce = launch_coop<VerifyChain::BLOCK>((VERIFY_CHAINS * cn + 63) / 64, ctx->stream, VerifyChain{d_steps + c0, VERIFY_CHAINS * cn, d_ok + c0, d_chain});
+        prof_end(ctx, TC_PROF_VERIFY_CHAIN, e0, e1);
+        RT(ce);
         int mmax = 1;
         for (uint32_t i = c0; i < c0 + cn; ++i) mmax = steps[i].m > mmax ? steps[i].m : mmax;
         uint32_t groups = (uint32_t)mmax + 1u;
@@ -1252,9 +1256,12 @@ extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** 
                         e = rt::launch<64>(lv.n, ctx->stream, NodeCommitSmall{g, t->d_payload, t->dtype, ns->fb[0], acc});
                         prof_end(ctx, TC_PROF_NODE_COMMIT, e0, e1);
                     } else if (lv.n <= COOP_LEVEL_NODES) {
+                        rt::event_t e0, e1;
+                        prof_begin(ctx, TC_PROF_NODE_COMMIT_UPPER, &e0, &e1);
                         /* very few nodes: every (child, window) term its own lane, sums shared by four waves */
                         typedef CoopReduce<NodeWindowSrc> Sum;
                         e = launch_coop<Sum::BLOCK>((uint32_t)lv.n, ctx->stream, Sum{NodeWindowSrc{g, t->levels[L - 1].phi, ns->fb[0], acc}});
+                        prof_end(ctx, TC_PROF_NODE_COMMIT_UPPER, e0, e1);
                     } else if ((t->B & (t->B - 1)) == 0 && t->B <= 64) {
                         int logB = 0;
                         while ((1u << logB) < t->B) ++logB;
@@ -1262,8 +1269,11 @@ extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** 
                         int logH = 0;
                         while (logB + logH < 6 && (2 << logH) <= FB_W && (lv.n << (logB + logH + 1)) <= SPLIT_LEVEL_LANES) ++logH;
                         uint64_t lanes = lv.n << (logB + logH);
+                        rt::event_t e0, e1;
+                        prof_begin(ctx, TC_PROF_NODE_COMMIT_UPPER, &e0, &e1);
                         e = launch_coop<64>((uint32_t)((lanes + 63) / 64), ctx->stream,
                                             NodeCommitFrCoop<64>{g, t->levels[L - 1].phi, ns->fb[0], lv.n, logB, logH, acc});
+                        prof_end(ctx, TC_PROF_NODE_COMMIT_UPPER, e0, e1);
                     } else {
                         g1_xyzz* part = ws_array<g1_xyzz>(ctx, lv.n * t->B);
                         if (!part) { rc = fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed"); break; }
