@@ -180,6 +180,8 @@ def main():
     ap.add_argument("--no-c3", action="store_true", help="skip the LLaMA2-7B-shaped forward (second half of the metric)")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one plain copy kernel of 256 MiB "
                     "(reference dispatch for scaling the HBM byte counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--in-flight", type=int, default=2, help="steps in flight: each has its own host thread, contexts, "
+                    "streams and buffers; the K timed steps are dealt out to them (1 = one step after the other)")
     ap.add_argument("--serial", action="store_true", help="run the flat commitment and the tree build one after the other "
                     "on one stream instead of concurrently on two")
     args = ap.parse_args()
@@ -211,34 +213,50 @@ def main():
     x = tc_inputs.c2_activation()
     inv = float(quantize.inv_scale_for(x))
     dx = torch.from_numpy(x.view(np.int16)).cuda()
-    dq = torch.empty(n, dtype=torch.int16, device="cuda")
     leaves = tc_inputs.opening_positions(shape, args.openings, tc_inputs.tensor_seed(1))
     vk = ctx.vk_from_trapdoor(tau)
     paths = [ctx.path_from_grid(shape, node, T.TC_LEAF_ENTRIES, l) for l in leaves]
     torch.cuda.synchronize()
 
-    # second context on its own (default-priority) stream: the flat commitment of the tensor and the
-    # tree build over its entries are independent and run concurrently
-    side_stream = torch.cuda.Stream()
-    ctx2 = T.Context(0, side_stream.cuda_stream, lib)
     import queue
     import threading
 
-    # the flat commitment runs on its own stream, driven by one long-lived host thread
-    jobs, done = queue.Queue(), queue.Queue()
+    class Lane:
+        """One step in flight: a main context (tree, openings, verification) and a side context on its own
+        default-priority stream for the flat commitment, which a long-lived host thread drives."""
 
-    def side_worker():
-        while True:
-            job = jobs.get()
-            if job is None:
-                return
-            try:
-                done.put(job())
-            except Exception as exc:      # surfaces in the main thread
-                done.put(exc)
+        def __init__(self, main_ctx):
+            self.own_ctx = main_ctx is None
+            if main_ctx is None:
+                self.main_stream = torch.cuda.Stream()
+                main_ctx = T.Context(0, self.main_stream.cuda_stream, lib)
+            self.ctx = main_ctx
+            self.side_stream = torch.cuda.Stream()
+            self.ctx2 = T.Context(0, self.side_stream.cuda_stream, lib)
+            self.dq = torch.empty(n, dtype=torch.int16, device="cuda")
+            self.jobs, self.done = queue.Queue(), queue.Queue()
+            self.thread = threading.Thread(target=self.side_worker, daemon=True)
+            self.thread.start()
 
-    side = threading.Thread(target=side_worker, daemon=True)
-    side.start()
+        def side_worker(self):
+            while True:
+                job = self.jobs.get()
+                if job is None:
+                    return
+                try:
+                    self.done.put(job())
+                except Exception as exc:      # surfaces in the lane's thread
+                    self.done.put(exc)
+
+        def close(self):
+            self.jobs.put(None)
+            self.thread.join()
+            self.ctx2.close()
+            if self.own_ctx:
+                self.ctx.close()
+
+    lanes = [Lane(ctx)] + [Lane(None) for _ in range(max(1, args.in_flight) - 1)]
+    dq = lanes[0].dq
 
     if args.calibrate_copy:
         cal_src = torch.zeros(128 * 1024 * 1024, dtype=torch.int16, device="cuda")
@@ -250,7 +268,10 @@ def main():
     hip = hip_event_timer()
     phases = {"encode": Events(hip), "commit": Events(hip), "tree": Events(hip), "open": Events(hip), "verify": Events(hip)}
 
-    def step(record):
+    def step(record, lane=None):
+        lane = lane or lanes[0]
+        ctx, dq = lane.ctx, lane.dq
+
         def timed(name, fn):
             if not record:
                 return fn()
@@ -265,19 +286,18 @@ def main():
             tree = timed("tree", lambda: ctx.terkle_build_entries(node_srs, dq, T.TC_I16, shape, node))
         else:
             ctx.sync()                                   # the quantised tensor is complete before the side stream reads it
-            jobs.put(lambda: ctx2.commit(srs, dq, T.TC_I16))
+            lane.jobs.put(lambda: lane.ctx2.commit(srs, dq, T.TC_I16))
             tree = ctx.terkle_build_entries(node_srs, dq, T.TC_I16, shape, node)
             C = None
         proofs = timed("open", lambda: tree.open_batch(leaves))
         root = tree.root
-        q_host = None
         ok = timed("verify", lambda: ctx.verify_paths_batch(vk, paths, [root] * len(leaves), leaf_values, proofs))
         tree.close()
         if C is None:                                    # the step ends when the flat commitment is in as well
-            C = done.get()
+            C = lane.done.get()
             if isinstance(C, Exception):
                 raise C
-        return C, root, ok, q_host
+        return C, root, ok
 
     # leaf values for verification come from the quantised tensor (computed once, outside the timing)
     ctx.encode_tensor(dx, T.TC_F16, n, inv, dq)
@@ -286,22 +306,56 @@ def main():
     R_MOD = 0x73EDA753299D7D483339D80809A1D80553BDA402FFFE5BFEFFFFFFFF00000001
     leaf_values = [(int(q[l]) % R_MOD).to_bytes(32, "little") for l in leaves]
 
-    for _ in range(args.warmup):
-        step(False)
+    def run_steps(count_per_lane):
+        """Deals the steps out to the lanes, one host thread per lane; returns every step's results."""
+        results, errors = [[] for _ in lanes], []
+
+        def work(i):
+            try:
+                for _ in range(count_per_lane[i]):
+                    results[i].append(step(False, lanes[i]))
+            except Exception as exc:
+                errors.append(exc)
+
+        if len(lanes) == 1:
+            work(0)
+        else:
+            threads = [threading.Thread(target=work, args=(i,)) for i in range(len(lanes)) if count_per_lane[i]]
+            for t in threads:
+                t.start()
+            for t in threads:
+                t.join()
+        if errors:
+            raise errors[0]
+        return [r for lane_results in results for r in lane_results]
+
+    def deal(total):
+        return [total // len(lanes) + (1 if i < total % len(lanes) else 0) for i in range(len(lanes))]
+
+    run_steps([args.warmup] * len(lanes))               # every lane warms up its own contexts
     torch.cuda.synchronize()
     # timed region: exactly `steps` steps, wall clock between two device synchronisations
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        C, root, ok, _ = step(False)
+    timed_results = run_steps(deal(args.steps))
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    assert all(ok), "path verification failed inside the benchmark"
-    C_timed, root_timed = C, root
+    assert len(timed_results) == args.steps
+    assert all(all(r[2]) for r in timed_results), "path verification failed inside the benchmark"
+    C_timed, root_timed = timed_results[0][0], timed_results[0][1]
+    assert all(r[0] == C_timed and r[1] == root_timed for r in timed_results)
+    # latency of one step on its own (lane 0, nothing else in flight)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(min(args.steps, 5)):
+        step(False)
+    torch.cuda.synchronize()
+    step_latency_ms = (time.perf_counter() - t1) * 1e3 / min(args.steps, 5)
+    ctx = lanes[0].ctx
     # a second, serial pass with HIP events around every phase and around the dominant kernel
     ctx.profile(True)
     prof_steps = min(args.steps, 5)
     for _ in range(prof_steps):
-        C, root, ok, _ = step(True)
+        C, root, ok = step(True)
     torch.cuda.synchronize()
     assert C == C_timed and root == root_timed and all(ok)
 
@@ -337,7 +391,9 @@ def main():
         "config": {"workload": "C2: 512x4096 fp16 N(0,1) activation -> int16, one tensor commitment + arity-16 (4,4) "
                                "Terkle tree over 2^21 entries (139813 nodes) + %d path openings + verification" % args.openings,
                    "elements": n, "setup_s_untimed": setup_s,
-                   "streams": "serial (one stream)" if args.serial else "flat commitment on a second stream, concurrent with tree build, openings and verification"},
+                   "streams": "serial (one stream)" if args.serial else "flat commitment on a second stream, concurrent with tree build, openings and verification",
+                   "steps_in_flight": len(lanes)},
+        "step_latency_ms": step_latency_ms,
         "phase_ms": phase_ms,
         "commit_only_elements_per_s": n / (commit_ms * 1e-3),
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_MADS_PER_S / 1e12,
@@ -376,9 +432,9 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(q)
     print(json.dumps(out))
-    jobs.put(None)
-    side.join()
-    ctx2.close()
+    for lane in lanes[1:]:
+        lane.close()
+    lanes[0].close()
     ctx.close()
 
 
