@@ -427,6 +427,31 @@ def main():
         kernel_line("VerifyChain", chain_ms / prof_steps, chains * 127 * 7 * MADS_PER_FP_MUL,
                     "%d chains of 127 Jacobian doublings, three waves a chain group: bound by depth" % chains),
     ]
+    # public verification of one of this step's paths with the pairing, on the host (the paper's verifier has no GPU);
+    # beside it the oracle's pairing check of the same path's top step
+    pv = T.binding.PairingVerifier(tau, 2, lib)
+    tree = ctx.terkle_build_entries(node_srs, lanes[0].dq, T.TC_I16, shape, node)
+    proofs = tree.open_batch(leaves)
+    t_pv = time.perf_counter()
+    ok_pv = [pv.verify_path(p, tree.root, v, pr) for p, v, pr in zip(paths, leaf_values, proofs)]
+    t_pv = (time.perf_counter() - t_pv) * 1e3 / len(paths)
+    assert all(ok_pv)
+    out["public_verification"] = {"ms_per_path": t_pv, "steps_per_path": int(paths[0].n_steps), "where": "host CPU, one thread",
+                                  "how": "pairing form of Ver: the steps of a path combined with random weights into "
+                                         "3 Miller loops and one final exponentiation"}
+    if not args.no_cpu_baseline:
+        from oracle import bls12_381 as oec
+        from oracle import pairing as opr
+        step0 = proofs[0]
+        pi = [oec.g1_from_bytes(step0[96 * i : 96 * (i + 1)]) for i in range(2)]
+        y0 = oec.fr_from_bytes(step0[192:224])
+        vkey = opr.verifier_key(tc_inputs.trapdoors()[:2])
+        t_o = time.perf_counter()
+        ok_o = opr.verify(vkey, oec.g1_from_bytes(tree.root), tuple(paths[0].kappa[0][j] for j in range(2)), y0, pi)
+        out["public_verification"]["oracle_ms_per_step"] = (time.perf_counter() - t_o) * 1e3
+        assert ok_o
+    tree.close()
+    pv.close()
     if not args.no_c3:
         out["terkle_build_llama2_7b_fwd"] = c3_forward(ctx, T, torch, node_srs, tau)
     if not args.no_cpu_baseline:

@@ -214,6 +214,37 @@ int tc_verify_paths_batch(tc_ctx* ctx, const tc_vk* vk, int count, const tc_path
                           const uint8_t* leaf_values, const void* proofs, size_t proof_stride,
                           const size_t* proof_len, int* results);
 
+/* ---- public verification with the pairing (CPU only) ----------------------------------------
+ *
+ * The pairing form of Ver (Def. 4.1; the bilinear map of App. E) in the sum form used throughout:
+ *     e(C - [y]G, H) = prod_i e(pi_i, [tau_i]H - [zeta_i]H),   zeta_i = kappa_i + 1,
+ * with H the generator of G2 and [tau_i]H part of the public parameters: no trapdoor is needed to verify.
+ * The paper's verifier has no GPU; these calls run on the host, need no context and never touch the HIP
+ * runtime.  G2 points: 192 bytes = x.c0, x.c1, y.c0, y.c1 (x = x.c0 + x.c1 u), canonical, 48 bytes
+ * little-endian each, all zero for the identity.  Target-group elements: 576 bytes = the twelve Fp coefficients of
+ * w^0 .. w^11 in Fp[w]/(w^12 - 2 w^6 + 2), 48 bytes little-endian each.  Points must lie on their curves
+ * (checked); membership in the prime-order subgroups is not checked. */
+typedef struct tc_vkp tc_vkp;
+
+/* Test-only setup of the public verification key [tau_i]H, i < m <= TC_MAX_ORDER, from the trapdoor
+ * (m canonical 32-byte Fr values).  TC_ERR_ARG / TC_ERR_RANGE / TC_ERR_NOMEM. */
+int tc_vkp_from_trapdoor(const uint8_t* tau, int m, tc_vkp** out);
+void tc_vkp_destroy(tc_vkp* vkp);
+/* out_g2 = [tau_axis]H, or H for axis = -1 */
+int tc_vkp_get(const tc_vkp* vkp, int axis, uint8_t out_g2[192]);
+/* out_gt = e(P, Q) = f_{|z|,Q}(P)^(-(p^12 - 1)/r) (z < 0 the curve parameter); the identity on either side gives 1.
+ * TC_ERR_ARG for a null pointer, TC_ERR_RANGE for a point that is not canonical or not on its curve. */
+int tc_pairing(const uint8_t p_g1[96], const uint8_t q_g2[192], uint8_t out_gt[576]);
+/* Ver for one opening; arguments as tc_verify.  TC_OK, TC_ERR_VERIFY (including malformed points), or
+ * TC_ERR_ARG / TC_ERR_SHAPE / TC_ERR_RANGE for bad arguments. */
+int tc_verify_pairing(const tc_vkp* vkp, int m, const uint32_t* shape, const uint8_t commitment[96],
+                      const uint32_t* kappa, const uint8_t y[32], const uint8_t* pi);
+/* Path verification as tc_verify_path, with the pairing and phi on the host.  The equations of the steps are
+ * combined with random 128-bit weights into one check (m + 1 Miller loops and one final exponentiation for the
+ * whole path): a path with a wrong step is accepted with probability about 2^-128. */
+int tc_verify_path_pairing(const tc_vkp* vkp, const tc_path* path, const uint8_t root[96],
+                           const uint8_t leaf_value[32], const void* proof, size_t proof_len);
+
 #ifdef __cplusplus
 }
 #endif

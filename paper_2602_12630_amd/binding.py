@@ -103,6 +103,12 @@ def load_library(path=None):
         "tc_verify_paths_batch": (ctypes.c_int, [vp, vp, ctypes.c_int, ctypes.POINTER(tc_path), u8p, u8p, vp,
                                                  ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t),
                                                  ctypes.POINTER(ctypes.c_int)]),
+        "tc_vkp_from_trapdoor": (ctypes.c_int, [u8p, ctypes.c_int, ctypes.POINTER(vp)]),
+        "tc_vkp_destroy": (None, [vp]),
+        "tc_vkp_get": (ctypes.c_int, [vp, ctypes.c_int, vp]),
+        "tc_pairing": (ctypes.c_int, [u8p, u8p, vp]),
+        "tc_verify_pairing": (ctypes.c_int, [vp, ctypes.c_int, u32p, u8p, u32p, u8p, u8p]),
+        "tc_verify_path_pairing": (ctypes.c_int, [vp, ctypes.POINTER(tc_path), u8p, u8p, vp, ctypes.c_size_t]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)              # AttributeError here = the library does not export a declared symbol
@@ -111,6 +117,55 @@ def load_library(path=None):
     L._tc_signatures = sig
     _LIBS[path] = L
     return L
+
+
+class PairingVerifier:
+    """Public verification with the pairing: host only, needs neither a GPU nor a Context."""
+
+    def __init__(self, tau_bytes, m=TC_MAX_ORDER, lib=None):
+        self.lib = lib or load_library()
+        self.handle = ctypes.c_void_p()
+        rc = self.lib.tc_vkp_from_trapdoor(bytes(tau_bytes), m, ctypes.byref(self.handle))
+        if rc != TC_OK:
+            raise TcError(rc, "tc_vkp_from_trapdoor")
+        self.m = m
+
+    def key(self, axis):
+        out = ctypes.create_string_buffer(192)
+        rc = self.lib.tc_vkp_get(self.handle, axis, out)
+        if rc != TC_OK:
+            raise TcError(rc, "tc_vkp_get")
+        return out.raw
+
+    def pairing(self, p_g1, q_g2):
+        out = ctypes.create_string_buffer(576)
+        rc = self.lib.tc_pairing(bytes(p_g1), bytes(q_g2), out)
+        if rc != TC_OK:
+            raise TcError(rc, "tc_pairing")
+        return out.raw
+
+    def verify(self, shape, commitment, kappa, y, pi):
+        rc = self.lib.tc_verify_pairing(self.handle, len(shape), _u32(shape), bytes(commitment), _u32(kappa), bytes(y),
+                                        b"".join(pi))
+        if rc == TC_ERR_VERIFY:
+            return False
+        if rc != TC_OK:
+            raise TcError(rc, "tc_verify_pairing")
+        return True
+
+    def verify_path(self, path, root, leaf_value, proof):
+        rc = self.lib.tc_verify_path_pairing(self.handle, ctypes.byref(path), bytes(root), bytes(leaf_value),
+                                             bytes(proof), len(proof))
+        if rc == TC_ERR_VERIFY:
+            return False
+        if rc != TC_OK:
+            raise TcError(rc, "tc_verify_path_pairing")
+        return True
+
+    def close(self):
+        if self.handle:
+            self.lib.tc_vkp_destroy(self.handle)
+            self.handle = None
 
 
 def _u32(values):

@@ -54,6 +54,40 @@ def endomorphism():
     raise AssertionError("no matching cube root of unity")
 
 
+# G2 generator on the twist y^2 = x^3 + 4 (u + 1) over Fp2 = Fp[u]/(u^2 + 1) (x = x0 + x1 u, y = y0 + y1 u)
+G2X = (0x024AA2B2F08F0A91260805272DC51051C6E47AD4FA403B02B4510B647AE3D1770BAC0326A805BBEFD48056C8C121BDB8,
+       0x13E02B6052719F607DACD3A088274F65596BD0D09920B61AB5DA61BBDC7F5049334CF11213945D57E5AC7D055D042B7E)
+G2Y = (0x0CE5D527727D6E118CC9CDC6DA2E351AADFD9BAA8CBDD3A76D429A695160D12C923AC9CC3BACA289E193548608B82801,
+       0x0606C4A02EA734CC32ACD2B02BC28B99CB3E287E85A763AF267492AB572E99AB3F370D275CEC1DA1AAA9075FF05F79BE)
+
+
+def f2mul(a, b):
+    return ((a[0] * b[0] - a[1] * b[1]) % P_MOD, (a[0] * b[1] + a[1] * b[0]) % P_MOD)
+
+
+def f2pow(a, e):
+    out = (1, 0)
+    for bit in bin(e)[2:]:
+        out = f2mul(out, out)
+        if bit == "1":
+            out = f2mul(out, a)
+    return out
+
+
+def pairing_constants():
+    """gamma = (u + 1)^((p^2 - 1) / 6): with Fp12 = Fp2[w]/(w^6 - (u + 1)) the p^2-power map multiplies the
+    coefficient of w^k by gamma^k; the hard part of the final exponentiation is (p^4 - p^2 + 1) / r."""
+    xi = (1, 1)
+    x3 = f2mul(f2mul(G2X, G2X), G2X)
+    assert f2mul(G2Y, G2Y) == ((x3[0] + 4) % P_MOD, (x3[1] + 4) % P_MOD), "G2 generator is not on the twist"
+    assert (P_MOD * P_MOD - 1) % 6 == 0
+    gamma = f2pow(xi, (P_MOD * P_MOD - 1) // 6)
+    assert f2pow(gamma, 6) == (1, 0) and f2pow(gamma, 3) != (1, 0) and f2pow(gamma, 2) != (1, 0)
+    assert (P_MOD**4 - P_MOD**2 + 1) % R_MOD == 0
+    hard = (P_MOD**4 - P_MOD**2 + 1) // R_MOD
+    return gamma, hard
+
+
 def limbs(x, n):
     return ", ".join("0x%08xu" % ((x >> (32 * i)) & 0xFFFFFFFF) for i in range(n))
 
@@ -83,6 +117,7 @@ def main():
     here = os.path.dirname(os.path.abspath(__file__))
     Rp = 1 << 384
     LAM, BETA = endomorphism()
+    GAMMA, HARD = pairing_constants()
     text = [
         "/* GENERATED by gen_constants.py -- do not edit.  BLS12-381 Montgomery constants,",
         " * 32-bit limbs, little-endian limb order.  Fp: R = 2^384; Fr: R = 2^256. */",
@@ -97,6 +132,16 @@ def main():
         "/* endomorphism (x, y) -> (beta x, y) = [lambda](x, y), lambda = z^2 - 1 < 2^128 */",
         "static constexpr uint32_t GLV_LAMBDA[4] = {%s};" % limbs(LAM, 4),
         "static constexpr uint32_t GLV_BETA[12] = {%s};      /* Montgomery form */" % limbs(BETA * Rp % P_MOD, 12),
+        "/* pairing (host side): G2 generator on the twist, Montgomery form, (c0, c1) of x then of y */",
+        "static constexpr uint32_t G2_GEN[4][12] = {%s};"
+        % ", ".join("{%s}" % limbs(v * Rp % P_MOD, 12) for v in (G2X[0], G2X[1], G2Y[0], G2Y[1])),
+        "/* (u + 1)^((p^2 - 1) / 6), Montgomery form (c0, c1) */",
+        "static constexpr uint32_t FROB2_GAMMA[2][12] = {%s};" % ", ".join("{%s}" % limbs(v * Rp % P_MOD, 12) for v in GAMMA),
+        "/* |z|, the loop length of the Miller function */",
+        "static constexpr uint64_t BLS_Z_ABS = 0x%xull;" % abs(Z),
+        "/* (p^4 - p^2 + 1) / r, %d bits */" % HARD.bit_length(),
+        "static constexpr int HARD_EXP_LIMBS = %d;" % ((HARD.bit_length() + 31) // 32),
+        "static constexpr uint32_t HARD_EXP[%d] = {%s};" % ((HARD.bit_length() + 31) // 32, limbs(HARD, (HARD.bit_length() + 31) // 32)),
         "}  // namespace tc",
         "",
     ]

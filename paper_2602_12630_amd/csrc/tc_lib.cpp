@@ -8,12 +8,14 @@
  */
 #include <algorithm>
 #include <new>
+#include <random>
 #include <string>
 #include <memory>
 #include <vector>
 
 #include "../../include/tc.h"
 #include "kernels.h"
+#include "pairing.h"
 
 using namespace tc;
 
@@ -1693,4 +1695,151 @@ extern "C" int tc_verify_path(tc_ctx* ctx, const tc_vk* vk, const tc_path* path,
     if (rc != TC_OK) return rc;
     if (result != TC_OK) return fail(ctx, TC_ERR_VERIFY, "path rejected");
     return TC_OK;
+}
+
+/* ======================================================================================= */
+/* Public verification with the pairing: host only                                         */
+/* ======================================================================================= */
+struct tc_vkp {
+    int m = 0;
+    pairing::g2_affine tau_h[TC_MAX_ORDER];
+};
+
+extern "C" int tc_vkp_from_trapdoor(const uint8_t* tau, int m, tc_vkp** out) {
+    if (!tau || !out || m < 1 || m > TC_MAX_ORDER) return TC_ERR_ARG;
+    *out = nullptr;
+    tc_vkp* vkp = new (std::nothrow) tc_vkp();
+    if (!vkp) return TC_ERR_NOMEM;
+    vkp->m = m;
+    pairing::g2_affine h = pairing::g2_generator();
+    for (int j = 0; j < m; ++j) {
+        uint32_t w[8];
+        if (!fr_bytes_canonical(tau + 32 * j, w)) {
+            delete vkp;
+            return TC_ERR_RANGE;
+        }
+        vkp->tau_h[j] = pairing::g2_mul(w, 256, h);
+    }
+    *out = vkp;
+    return TC_OK;
+}
+extern "C" void tc_vkp_destroy(tc_vkp* vkp) { delete vkp; }
+extern "C" int tc_vkp_get(const tc_vkp* vkp, int axis, uint8_t out_g2[192]) {
+    if (!vkp || !out_g2 || axis < -1 || axis >= vkp->m) return TC_ERR_ARG;
+    pairing::g2_to_bytes(axis < 0 ? pairing::g2_generator() : vkp->tau_h[axis], out_g2);
+    return TC_OK;
+}
+
+/* canonical bytes -> affine point on E; false when not canonical or not on the curve */
+static bool g1_from_bytes_checked(const uint8_t* b, g1_affine* out) {
+    uint32_t w[24];
+    memcpy(w, b, 96);
+    if (!canonical_fp(w) || !canonical_fp(w + 12)) return false;
+    *out = affine_from_canonical(w);
+    return affine_on_curve(*out);
+}
+
+extern "C" int tc_pairing(const uint8_t p_g1[96], const uint8_t q_g2[192], uint8_t out_gt[576]) {
+    if (!p_g1 || !q_g2 || !out_gt) return TC_ERR_ARG;
+    pairing::pair_t pr;
+    if (!g1_from_bytes_checked(p_g1, &pr.p) || !pairing::g2_from_bytes(q_g2, &pr.q)) return TC_ERR_RANGE;
+    pairing::gt_to_bytes(pairing::pairing_product({pr}), out_gt);
+    return TC_OK;
+}
+
+/* Every opening's equation, moved to fixed second arguments,
+ *     e(C - [y]G + sum_i [zeta_i] pi_i, H) prod_i e(-pi_i, [tau_i]H) = 1,
+ * is raised to a weight rho and multiplied into one running equation: by bilinearity the weights go to the G1
+ * side, so any number of openings costs m + 1 Miller loops and one final exponentiation.  The first opening has
+ * weight 1, the others 128-bit weights drawn at random: a set of openings with a wrong one passes only with
+ * probability about 2^-128. */
+struct PairingBatch {
+    g1_xyzz h_term = xyzz_identity();
+    g1_xyzz tau_term[TC_MAX_ORDER];
+    int m_used = 0;
+    int count = 0;
+    std::mt19937_64 rng{std::random_device{}()};
+    PairingBatch() {
+        for (int i = 0; i < TC_MAX_ORDER; ++i) tau_term[i] = xyzz_identity();
+    }
+};
+static g1_xyzz weigh(const g1_xyzz& p, const uint32_t rho[4], bool unit) {
+    if (unit) return p;
+    return xyzz_mul_affine(rho, 128, xyzz_to_affine(p));
+}
+/* adds one opening; false when a point or the value is malformed */
+static bool pairing_batch_add(PairingBatch* B, int m, const uint8_t* commitment, const uint32_t* kappa, const uint8_t* y,
+                              const uint8_t* pi) {
+    g1_affine C;
+    uint32_t yw[8];
+    if (!g1_from_bytes_checked(commitment, &C) || !fr_bytes_canonical(y, yw)) return false;
+    bool unit = B->count == 0;
+    uint32_t rho[4] = {1, 0, 0, 0};
+    if (!unit)
+        for (int i = 0; i < 4; ++i) rho[i] = (uint32_t)B->rng();
+    g1_xyzz t = xyzz_add(xyzz_from_affine(C), xyzz_neg(xyzz_mul_affine(yw, 256, affine_generator())));
+    for (int i = 0; i < m; ++i) {
+        g1_affine p;
+        if (!g1_from_bytes_checked(pi + 96 * (size_t)i, &p)) return false;
+        uint32_t zeta[1] = {kappa[i] + 1u};
+        t = xyzz_add(t, xyzz_mul_affine(zeta, 32, p));
+        B->tau_term[i] = xyzz_add(B->tau_term[i], weigh(xyzz_from_affine(affine_neg(p)), rho, unit));
+    }
+    B->h_term = xyzz_add(B->h_term, weigh(t, rho, unit));
+    if (m > B->m_used) B->m_used = m;
+    ++B->count;
+    return true;
+}
+static bool pairing_batch_check(const tc_vkp* vkp, const PairingBatch& B) {
+    std::vector<pairing::pair_t> pairs;
+    pairs.push_back({xyzz_to_affine(B.h_term), pairing::g2_generator()});
+    for (int i = 0; i < B.m_used; ++i) pairs.push_back({xyzz_to_affine(B.tau_term[i]), vkp->tau_h[i]});
+    return pairing::f12_eq(pairing::pairing_product(pairs), pairing::f12_one());
+}
+
+extern "C" int tc_verify_pairing(const tc_vkp* vkp, int m, const uint32_t* shape, const uint8_t commitment[96],
+                                 const uint32_t* kappa, const uint8_t y[32], const uint8_t* pi) {
+    if (!vkp || !shape || !commitment || !kappa || !y || !pi) return TC_ERR_ARG;
+    if (!shape_ok(m, shape, nullptr) || m > vkp->m) return TC_ERR_SHAPE;
+    for (int j = 0; j < m; ++j)
+        if (kappa[j] >= shape[j]) return TC_ERR_RANGE;
+    PairingBatch B;
+    if (!pairing_batch_add(&B, m, commitment, kappa, y, pi)) return TC_ERR_VERIFY;
+    return pairing_batch_check(vkp, B) ? TC_OK : TC_ERR_VERIFY;
+}
+
+extern "C" int tc_verify_path_pairing(const tc_vkp* vkp, const tc_path* path, const uint8_t root[96],
+                                      const uint8_t leaf_value[32], const void* proof, size_t proof_len) {
+    if (!vkp || !path || !root || !leaf_value || !proof) return TC_ERR_ARG;
+    const tc_path& p = *path;
+    if (p.n_steps < 1 || p.n_steps > TC_MAX_STEPS) return TC_ERR_VERIFY;
+    size_t expect = 0;
+    for (int s = 0; s < p.n_steps; ++s) {
+        if (p.m[s] < 1 || p.m[s] > vkp->m || !shape_ok(p.m[s], p.shape[s], nullptr)) return TC_ERR_VERIFY;
+        for (int j = 0; j < p.m[s]; ++j)
+            if (p.kappa[s][j] >= p.shape[s][j]) return TC_ERR_VERIFY;
+        expect += 96 * (size_t)p.m[s] + 32 + (s + 1 < p.n_steps ? 96 : 0);
+    }
+    if (expect != proof_len) return TC_ERR_VERIFY;
+    const uint8_t* src = (const uint8_t*)proof;
+    const uint8_t* carried = root;
+    PairingBatch B;
+    for (int s = 0; s < p.n_steps; ++s) {
+        const uint8_t* pi = src;
+        const uint8_t* y = src + 96 * (size_t)p.m[s];
+        src = y + 32;
+        if (!pairing_batch_add(&B, p.m[s], carried, p.kappa[s], y, pi)) return TC_ERR_VERIFY;
+        if (s + 1 < p.n_steps) {
+            /* the opened value is phi of the commitment carried to the next step */
+            g1_affine child;
+            if (!g1_from_bytes_checked(src, &child)) return TC_ERR_VERIFY;
+            fr_t v = phi_map(child);
+            if (memcmp(v.l, y, 32) != 0) return TC_ERR_VERIFY;
+            carried = src;
+            src += 96;
+        } else if (memcmp(y, leaf_value, 32) != 0) {
+            return TC_ERR_VERIFY;
+        }
+    }
+    return pairing_batch_check(vkp, B) ? TC_OK : TC_ERR_VERIFY;
 }

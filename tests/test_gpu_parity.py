@@ -245,6 +245,11 @@ def test_entries_tree_small(T, ctx, node_srs, grid, dtype_name):
             assert proof == serialize_steps(steps)
             assert path.n_steps == len(steps)
         assert ctx.verify_paths_batch(vk, paths, [tree.root] * len(leaves), values, proofs) == [True] * len(leaves)
+        # the same proofs under public verification (pairing, host only): no trapdoor involved
+        pv = T.binding.PairingVerifier(TAU_BYTES, 2)
+        assert pv.verify_path(paths[0], tree.root, values[0], proofs[0])
+        assert not pv.verify_path(paths[0], tree.root, ec.fr_to_bytes((int(X[leaves[0]]) + 1) % R), proofs[0])
+        pv.close()
         # tampering: leaf value, one byte of a proof element, the root
         wrong = [ec.fr_to_bytes((int(X[l]) + 1) % R) for l in leaves]
         assert ctx.verify_paths_batch(vk, paths, [tree.root] * len(leaves), wrong, proofs) == [False] * len(leaves)

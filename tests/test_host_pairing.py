@@ -1,0 +1,136 @@
+"""The library's public (pairing) verifier, which runs on the host only, against the oracle: keys, values of the
+pairing byte for byte, single openings and whole Terkle paths produced by the oracle, tampering, malformed input.
+Runs without a GPU: these entry points need no context."""
+import ctypes
+import os
+import sys
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+import __graft_entry__ as entry  # noqa: E402
+import tc_inputs  # noqa: E402
+from oracle import bls12_381 as ec  # noqa: E402
+from oracle import pairing as pr  # noqa: E402
+from oracle import tc, terkle  # noqa: E402
+from oracle.bls12_381 import R  # noqa: E402
+
+import paper_2602_12630_amd as T  # noqa: E402
+from paper_2602_12630_amd import binding  # noqa: E402
+from gpu_util import TAU, TAU_BYTES, pps, serialize_steps  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(T.library_path()):
+        entry.build_hip()
+    return T.load_library()
+
+
+@pytest.fixture(scope="module")
+def verifier(lib):
+    v = binding.PairingVerifier(TAU_BYTES, 3, lib)
+    yield v
+    v.close()
+
+
+def make_path(lib, grid, node_shape, leaf_kind, leaf, inner_shape=None, inner=None):
+    p = binding.tc_path()
+    u32 = binding._u32
+    rc = lib.tc_path_from_grid(len(grid), u32(grid), u32(node_shape), leaf_kind, u32(leaf),
+                               len(inner_shape) if inner_shape else 0, u32(inner_shape) if inner_shape else None,
+                               u32(inner) if inner is not None else None, ctypes.byref(p))
+    assert rc == T.TC_OK
+    return p
+
+
+def test_keys_and_pairing_values(verifier):
+    assert verifier.key(-1) == pr.g2_to_bytes(pr.G2)
+    for i in range(3):
+        assert verifier.key(i) == pr.g2_to_bytes(pr.g2_mul(TAU[i], pr.G2))
+    cases = [(ec.G1, pr.G2), (ec.mul(0xABCDEF, ec.G1), pr.g2_mul(0x1234567, pr.G2)),
+             (ec.mul(R - 2, ec.G1), pr.g2_mul(R - 3, pr.G2))]
+    for p1, q2 in cases:
+        assert verifier.pairing(ec.g1_to_bytes(p1), pr.g2_to_bytes(q2)) == pr.gt_to_bytes(pr.pairing(p1, q2))
+    one = pr.gt_to_bytes(pr.F12_ONE)
+    assert verifier.pairing(ec.g1_to_bytes(ec.INF), pr.g2_to_bytes(pr.G2)) == one
+    assert verifier.pairing(ec.g1_to_bytes(ec.G1), pr.g2_to_bytes(ec.INF)) == one
+    # malformed input: off the curve / the twist, not canonical
+    bad = bytearray(ec.g1_to_bytes(ec.G1))
+    bad[0] ^= 1
+    with pytest.raises(binding.TcError):
+        verifier.pairing(bytes(bad), pr.g2_to_bytes(pr.G2))
+    badq = bytearray(pr.g2_to_bytes(pr.G2))
+    badq[100] ^= 1
+    with pytest.raises(binding.TcError):
+        verifier.pairing(ec.g1_to_bytes(ec.G1), bytes(badq))
+    with pytest.raises(binding.TcError):
+        verifier.pairing(b"\xff" * 96, pr.g2_to_bytes(pr.G2))
+
+
+def test_single_openings(verifier):
+    rng = np.random.default_rng(11)
+    for shape, kappa in (((3, 4), (2, 1)), ((5,), (0,)), ((2, 3, 2), (1, 2, 0))):
+        pp = pps(shape)
+        t = rng.integers(-128, 128, size=shape)
+        C = tc.commit(pp, t)
+        y, pi = tc.open_(pp, t, kappa)
+        cb, yb, pib = ec.g1_to_bytes(C), ec.fr_to_bytes(y), [ec.g1_to_bytes(p) for p in pi]
+        assert verifier.verify(shape, cb, kappa, yb, pib)
+        assert not verifier.verify(shape, cb, kappa, ec.fr_to_bytes((y + 1) % R), pib)
+        assert not verifier.verify(shape, ec.g1_to_bytes(ec.add(C, ec.G1)), kappa, yb, pib)
+        moved = [ec.g1_to_bytes(ec.add(pi[0], ec.G1))] + pib[1:]
+        assert not verifier.verify(shape, cb, kappa, yb, moved)
+        other = tuple((k + 1) % d for k, d in zip(kappa, shape))
+        assert not verifier.verify(shape, cb, other, yb, pib)
+        off_curve = bytearray(pib[0])
+        off_curve[5] ^= 4
+        assert not verifier.verify(shape, cb, kappa, yb, [bytes(off_curve)] + pib[1:])
+    # a constant tensor opens with the identity as every proof element
+    const = np.full((3, 4), -5)
+    y, pi = tc.open_(pps((3, 4)), const, (0, 3))
+    assert verifier.verify((3, 4), ec.g1_to_bytes(tc.commit(pps((3, 4)), const)), (0, 3), ec.fr_to_bytes(y),
+                           [ec.g1_to_bytes(p) for p in pi])
+    with pytest.raises(binding.TcError):          # position outside the grid: an argument error, not a verdict
+        verifier.verify((3, 4), ec.g1_to_bytes(ec.G1), (3, 0), ec.fr_to_bytes(0), [ec.g1_to_bytes(ec.G1)] * 2)
+
+
+def test_paths_of_an_entries_tree(lib, verifier):
+    grid, node = (5, 6), (2, 2)
+    rng = np.random.default_rng(12)
+    payload = rng.integers(-100, 100, size=grid)
+    tree = terkle.build(pps, tc.as_flat_ints(payload), grid, node)
+    root = ec.g1_to_bytes(tree.root)
+    for leaf in ((0, 0), (4, 5), (2, 3)):
+        steps = terkle.open_path(pps, tree, grid, node, leaf)
+        proof = serialize_steps(steps)
+        path = make_path(lib, grid, node, T.TC_LEAF_ENTRIES, leaf)
+        value = ec.fr_to_bytes(int(payload[leaf]) % R)
+        assert terkle.verify_path(pps, tree.root, [node] * len(steps), int(payload[leaf]), steps)
+        assert verifier.verify_path(path, root, value, proof)
+        assert not verifier.verify_path(path, root, ec.fr_to_bytes((int(payload[leaf]) + 1) % R), proof)
+        assert not verifier.verify_path(path, ec.g1_to_bytes(ec.add(tree.root, ec.G1)), value, proof)
+        assert not verifier.verify_path(path, root, value, proof[:-1])
+        flipped = bytearray(proof)
+        flipped[len(proof) // 2] ^= 1
+        assert not verifier.verify_path(path, root, value, bytes(flipped))
+    wrong = make_path(lib, grid, node, T.TC_LEAF_ENTRIES, (1, 1))
+    assert not verifier.verify_path(wrong, root, ec.fr_to_bytes(int(payload[2, 3]) % R), proof)
+
+
+def test_path_into_a_tensors_tree(lib, verifier):
+    grid, node = (2, 2), (2, 2)
+    shapes = [(2, 3), (4,), (2, 2, 2), (3, 2)]
+    rng = np.random.default_rng(13)
+    leaves = [rng.integers(-50, 50, size=s) for s in shapes]
+    tree = terkle.build(pps, [tc.as_flat_ints(t) for t in leaves], grid, node, kind="tensors", leaf_shapes=shapes)
+    leaf, inner = (1, 0), (1, 0, 1)
+    steps = terkle.open_path(pps, tree, grid, node, leaf, inner)
+    path = make_path(lib, grid, node, T.TC_LEAF_TENSORS, leaf, shapes[2], inner)
+    value = ec.fr_to_bytes(int(leaves[2][inner]) % R)
+    assert verifier.verify_path(path, ec.g1_to_bytes(tree.root), value, serialize_steps(steps))
+    assert not verifier.verify_path(path, ec.g1_to_bytes(tree.root), ec.fr_to_bytes(1), serialize_steps(steps))
