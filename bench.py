@@ -74,6 +74,49 @@ class Events:
         return tot
 
 
+def coefficient_route(ctx, T, torch, with_oracle):
+    """Interpolation to monomial coefficients (the first step of Com as Def. 4.1 prints it, bypassed by the hot
+    path): the sweep of Fig. 1, N = 2^12 samples reshaped to order-m grids, and the C2 activation; one Fr product
+    = 2 * 8^2 + 8 = 136 multiply-adds, an axis of length d costs 2 (d - 1) products per entry."""
+    from oracle import tc as otc
+
+    out = {"sweep_n_4096": []}
+    rng = np.random.default_rng(5)
+    for shape in ((4096,), (64, 64), (16, 16, 16), (8, 8, 8, 8), (4,) * 6, (2,) * 12):
+        x = rng.integers(-32768, 32768, size=shape).astype(np.int16)
+        dx = torch.from_numpy(x).cuda()
+        coeffs = torch.empty(32 * x.size, dtype=torch.uint8, device="cuda")
+        ctx.interpolate(shape, dx, T.TC_I16, coeffs)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            ctx.interpolate(shape, dx, T.TC_I16, coeffs)
+        torch.cuda.synchronize()
+        line = {"m": len(shape), "shape": list(shape), "gpu_ms": (time.perf_counter() - t0) * 1e3 / 3}
+        if with_oracle and len(shape) >= 2:
+            t1 = time.perf_counter()
+            want = otc.interpolate(x, shape)
+            line["oracle_ms"] = (time.perf_counter() - t1) * 1e3
+            raw = coeffs.cpu().numpy().tobytes()
+            assert [int.from_bytes(raw[32 * i : 32 * (i + 1)], "little") for i in range(x.size)] == want
+        out["sweep_n_4096"].append(line)
+    shape = tc_inputs.C2_SHAPE
+    x = tc_inputs.c2_activation()
+    q = np.clip(np.rint(x.astype(np.float32) * 1000.0), -32767, 32767).astype(np.int16)
+    dx = torch.from_numpy(q).cuda()
+    coeffs = torch.empty(32 * q.size, dtype=torch.uint8, device="cuda")
+    ctx.interpolate(shape, dx, T.TC_I16, coeffs)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ctx.interpolate(shape, dx, T.TC_I16, coeffs)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3
+    mads = q.size * sum(2 * (d - 1) for d in shape) * 136
+    out["c2_activation"] = {"shape": list(shape), "ms": ms, "achieved": mads / (ms * 1e-3) / 1e12,
+                            "frac": mads / (ms * 1e-3) / PEAK_MADS_PER_S, "unit": "T 32x32->64 multiply-add/s"}
+    return out
+
+
 def cpu_baseline(q, budget_s=12.0):
     """The oracle's naive multi-exponentiation (every term its own double-and-add) on the first
     entries of the same quantised tensor, on all host cores the box gives us."""
@@ -452,6 +495,7 @@ def main():
         assert ok_o
     tree.close()
     pv.close()
+    out["coefficient_route"] = coefficient_route(ctx, T, torch, not args.no_cpu_baseline)
     if not args.no_c3:
         out["terkle_build_llama2_7b_fwd"] = c3_forward(ctx, T, torch, node_srs, tau)
     if not args.no_cpu_baseline:

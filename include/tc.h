@@ -89,6 +89,10 @@ int tc_ctx_profile_read(tc_ctx* ctx, int kind, double* total_ms, uint64_t* launc
 #define TC_SRS_SUFFIX 1u     /* also build the suffix tables S^(a), a = 1..m-1, needed by tc_open */
 #define TC_SRS_FIXED_BASE 2u /* also build fixed-base window tables for every table (node shapes of a
                                 tree: small shapes only, 50 MB per base) */
+#define TC_SRS_MONOMIAL 4u   /* the monomial SRS of Def. 4.1 itself, S[k] = [prod_j tau_j^(k_j)] G, instead of its
+                                Lagrange-basis image: for committing coefficient arrays (tc_interpolate,
+                                tc_divide_by_linear) with tc_commit; not combinable with the other flags, and
+                                tc_open / trees refuse it (TC_ERR_STATE) */
 
 /* Builds, on the device, the Lagrange-basis SRS for `shape`:
  *   S[i] = [ prod_j l_{j,i_j}(tau_j) ] G,  i in prod_j {0..d_j-1},
@@ -213,6 +217,24 @@ int tc_verify_path(tc_ctx* ctx, const tc_vk* vk, const tc_path* path, const uint
 int tc_verify_paths_batch(tc_ctx* ctx, const tc_vk* vk, int count, const tc_path* paths, const uint8_t* roots,
                           const uint8_t* leaf_values, const void* proofs, size_t proof_stride,
                           const size_t* proof_len, int* results);
+
+/* ---- the coefficient route: interpolation and Algorithm 1 on the device -----------------------
+ *
+ * Def. 4.1 commits to the monomial coefficients of the interpolant f_T; the hot path above never forms them
+ * (a Lagrange-basis SRS gives the same group element).  These two calls are the literal route.  Coefficient
+ * arrays have the tensor's shape, row-major (entry k = coefficient of prod_j x_j^(k_j)), canonical Fr values of
+ * 32 bytes, device memory. */
+
+/* d_coeffs = monomial coefficients of the polynomial with f(zeta) = T[zeta] on the grid prod_j {1..d_j}
+ * (Sec. 4, Com; one axis at a time in Newton form, App. C: divided differences on the equispaced nodes, then
+ * expansion of the nested products).  m <= TC_MAX_INTERP_ORDER axes; the scalars as in tc_commit. */
+#define TC_MAX_INTERP_ORDER 12
+int tc_interpolate(tc_ctx* ctx, int m, const uint32_t* shape, const void* d_scalars, int dtype, void* d_coeffs);
+/* Algorithm 1 (App. A): f = q (x_axis - omega) + r with omega = kappa_axis + 1 and r free of x_axis, on the
+ * coefficient arrays; d_quotient and d_remainder have the full shape (zeros at the top degree of the axis in q,
+ * at every positive degree in r) and may not alias d_coeffs. */
+int tc_divide_by_linear(tc_ctx* ctx, int m, const uint32_t* shape, const void* d_coeffs, int axis, uint32_t kappa_axis,
+                        void* d_quotient, void* d_remainder);
 
 /* ---- public verification with the pairing (CPU only) ----------------------------------------
  *

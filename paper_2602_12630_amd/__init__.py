@@ -12,8 +12,10 @@ from .binding import (  # noqa: F401
     TC_LEAF_TENSORS,
     TC_OK,
     TC_SRS_FIXED_BASE,
+    TC_SRS_MONOMIAL,
     TC_SRS_SUFFIX,
     Context,
+    PairingVerifier,
     Srs,
     TcError,
     Tree,

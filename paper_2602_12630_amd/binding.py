@@ -10,7 +10,7 @@ import os
 TC_OK = 0
 TC_ERR_ARG, TC_ERR_SHAPE, TC_ERR_RANGE, TC_ERR_NOMEM, TC_ERR_HIP, TC_ERR_VERIFY, TC_ERR_STATE = -1, -2, -3, -4, -5, -6, -7
 TC_I8, TC_I16, TC_FR, TC_F16 = 1, 2, 3, 4
-TC_SRS_SUFFIX, TC_SRS_FIXED_BASE = 1, 2
+TC_SRS_SUFFIX, TC_SRS_FIXED_BASE, TC_SRS_MONOMIAL = 1, 2, 4
 TC_LEAF_ENTRIES, TC_LEAF_TENSORS = 0, 1
 TC_PROF_BUCKET_ACC, TC_PROF_NODE_COMMIT, TC_PROF_NODE_COMMIT_UPPER, TC_PROF_VERIFY_CHAIN = 0, 1, 2, 3
 TC_MAX_ORDER, TC_MAX_STEPS = 4, 16
@@ -103,6 +103,8 @@ def load_library(path=None):
         "tc_verify_paths_batch": (ctypes.c_int, [vp, vp, ctypes.c_int, ctypes.POINTER(tc_path), u8p, u8p, vp,
                                                  ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t),
                                                  ctypes.POINTER(ctypes.c_int)]),
+        "tc_interpolate": (ctypes.c_int, [vp, ctypes.c_int, u32p, vp, ctypes.c_int, vp]),
+        "tc_divide_by_linear": (ctypes.c_int, [vp, ctypes.c_int, u32p, vp, ctypes.c_int, ctypes.c_uint32, vp, vp]),
         "tc_vkp_from_trapdoor": (ctypes.c_int, [u8p, ctypes.c_int, ctypes.POINTER(vp)]),
         "tc_vkp_destroy": (None, [vp]),
         "tc_vkp_get": (ctypes.c_int, [vp, ctypes.c_int, vp]),
@@ -324,6 +326,14 @@ class Context:
         pi = ctypes.create_string_buffer(96 * len(srs.shape))
         self._check(self.lib.tc_open(self.handle, srs.handle, _ptr(scalars), dtype, _u32(kappa), y, pi))
         return y.raw, [pi.raw[96 * i : 96 * (i + 1)] for i in range(len(srs.shape))]
+
+    # -- coefficient route -----------------------------------------------------------------------
+    def interpolate(self, shape, scalars, dtype, coeffs_out):
+        self._check(self.lib.tc_interpolate(self.handle, len(shape), _u32(shape), _ptr(scalars), dtype, _ptr(coeffs_out)))
+
+    def divide_by_linear(self, shape, coeffs, axis, kappa_axis, quotient_out, remainder_out):
+        self._check(self.lib.tc_divide_by_linear(self.handle, len(shape), _u32(shape), _ptr(coeffs), axis, kappa_axis,
+                                                 _ptr(quotient_out), _ptr(remainder_out)))
 
     # -- verify ------------------------------------------------------------------------------
     def vk_from_trapdoor(self, tau_bytes, m=TC_MAX_ORDER):

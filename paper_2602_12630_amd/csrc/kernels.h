@@ -1575,4 +1575,107 @@ struct PhiCanonical {
     }
 };
 
+/* ---- the coefficient route: interpolation along one axis, Algorithm 1 ------------------------ */
+/* Lines of length d along one axis of an (outer, d, inner) array of Montgomery Fr values, nodes zeta_k = k + 1.
+ * A workgroup owns `lines_per_wg` whole lines; a barrier separates the phases, values move between three
+ * arrays in global memory (buf[0] holds the input):
+ *   phases 0 .. d-2       divided differences, level l = phase + 1:  c_k <- (c_k - c_(k-1)) / l  for k >= l
+ *                         (equispaced nodes: zeta_k - zeta_(k-l) = l), ping-pong between buf[0] and buf[1];
+ *   phase d-1             a = (c_(d-1), 0, .., 0)
+ *   phases d .. 2d-2      step s = phase - (d-1), k = d-1-s:  a <- a (x - zeta_k) + c_k, i.e.
+ *                         a_i <- a_(i-1) - zeta_k a_i (+ c_k at i = 0), ping-pong between the two arrays
+ *                         that do not hold c.
+ * The host works out where c and the result end up (interp_result_buffer). */
+struct InterpAxis {
+    static constexpr int BLOCK = 1024;       /* a long line is bound by its 2d - 1 barriers: as many lanes as a workgroup has */
+    static constexpr size_t LDS_BYTES = 16;
+    fr_t* buf[3];
+    uint64_t outer, inner;
+    uint32_t d, lines_per_wg;
+    const fr_t* inv_int;       /* inv_int[l] = 1 / l, l = 1 .. d-1 */
+    const fr_t* zeta;          /* zeta[k] = k + 1 */
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t*) const {
+        uint64_t lines = outer * inner;
+        int cbuf = (int)((d - 1) & 1u);                  /* c after the d - 1 levels */
+        int pa = cbuf == 0 ? 1 : 0, pb = 2;              /* the two arrays of the expansion */
+        for (uint64_t idx = lane; idx < (uint64_t)lines_per_wg * d; idx += BLOCK) {
+            uint64_t line = (uint64_t)wg * lines_per_wg + idx / d;
+            uint32_t k = (uint32_t)(idx % d);
+            if (line >= lines) continue;
+            uint64_t base = (line / inner) * d * inner + line % inner;
+            uint64_t at = base + (uint64_t)k * inner;
+            if (ph + 1 < (int)d) {
+                uint32_t l = (uint32_t)ph + 1;
+                const fr_t* src = buf[ph & 1];
+                fr_t v = src[at];
+                if (k >= l) v = fr_mul(fr_sub(v, src[at - inner]), inv_int[l]);
+                buf[(ph + 1) & 1][at] = v;
+            } else if (ph + 1 == (int)d) {
+                buf[pa][at] = k == 0 ? buf[cbuf][base + (uint64_t)(d - 1) * inner] : fe_zero<FrParams>();
+            } else {
+                uint32_t s = (uint32_t)ph - (d - 1), kk = d - 1 - s;
+                const fr_t* old = buf[(s & 1u) ? pa : pb];
+                fr_t* nxt = buf[(s & 1u) ? pb : pa];
+                fr_t v = fr_neg(fr_mul(zeta[kk], old[at]));
+                v = fr_add(v, k ? old[at - inner] : buf[cbuf][base + (uint64_t)kk * inner]);
+                nxt[at] = v;
+            }
+        }
+    }
+};
+/* index (0..2) of the array that holds the coefficients after all 2d - 1 phases */
+TC_HD int interp_result_buffer(uint32_t d) {
+    int cbuf = (int)((d - 1) & 1u);
+    int pa = cbuf == 0 ? 1 : 0, pb = 2;
+    return ((d - 1) & 1u) ? pb : pa;
+}
+struct ScalarsToFr {           /* any scalar type -> Montgomery Fr */
+    const void* scalars;
+    int dtype;
+    fr_t* out;
+    TC_DEV void operator()(uint32_t t) const { out[t] = scalar_as_fr(scalars, dtype, t); }
+};
+struct FrToPlain {             /* Montgomery -> canonical 32 bytes */
+    const fr_t* in;
+    fr_plain* out;
+    TC_DEV void operator()(uint32_t t) const {
+        fr_t v = fe_to_plain(in[t]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[t].l[i] = v.l[i];
+    }
+};
+/* Algorithm 1 along one axis (App. A): lane = line; from the top degree down, the coefficient at degree c goes to
+ * degree c - 1 of the quotient and, times omega, into degree c - 1 of the remainder. */
+struct DivideAxis {
+    const fr_plain* coeffs;
+    uint64_t outer, inner;
+    uint32_t d;
+    uint32_t omega;
+    fr_plain* q;
+    fr_plain* r;
+    TC_DEV void operator()(uint32_t t) const {
+        uint64_t base = ((uint64_t)t / inner) * d * inner + (uint64_t)t % inner;
+        fr_t w = fe_from_u32<FrParams>(omega);
+        fr_t carry = fe_from_limbs<FrParams>(coeffs[base + (uint64_t)(d - 1) * inner].l);
+        fr_plain zero;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) zero.l[i] = 0;
+        q[base + (uint64_t)(d - 1) * inner] = zero;
+        for (uint32_t c = d - 1; c >= 1; --c) {
+            fr_t plain = fe_to_plain(carry);
+            fr_plain o;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o.l[i] = plain.l[i];
+            q[base + (uint64_t)(c - 1) * inner] = o;
+            r[base + (uint64_t)c * inner] = zero;
+            carry = fr_add(fe_from_limbs<FrParams>(coeffs[base + (uint64_t)(c - 1) * inner].l), fr_mul(w, carry));
+        }
+        fr_t plain = fe_to_plain(carry);
+        fr_plain o;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o.l[i] = plain.l[i];
+        r[base] = o;
+    }
+};
+
 }  // namespace tc

@@ -387,6 +387,7 @@ extern "C" int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, co
     *out = nullptr;
     uint64_t total = 0;
     if (!shape_ok(m, shape, &total)) return fail(ctx, TC_ERR_SHAPE, "bad shape");
+    if ((flags & TC_SRS_MONOMIAL) && flags != TC_SRS_MONOMIAL) return fail(ctx, TC_ERR_ARG, "the monomial SRS takes no other flag");
     if ((flags & TC_SRS_FIXED_BASE) && total > FB_MAX_BASES)
         return fail(ctx, TC_ERR_SHAPE, "fixed-base tables are limited to shapes with at most 64 entries");
     RT(rt::set_device(ctx->device));
@@ -428,7 +429,16 @@ extern "C" int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, co
         }
         fr_t sum_inv = fe_inv_fermat<FrParams>(sum);
         ell_off[j] = (uint32_t)ell_all.size();
-        for (uint32_t i = 0; i < d; ++i) ell_all.push_back(fr_mul(term[i], sum_inv));
+        if (flags & TC_SRS_MONOMIAL) {
+            /* the same generator kernel multiplies per-axis factors: powers of tau_j give the monomial SRS */
+            fr_t pw = fe_one<FrParams>();
+            for (uint32_t i = 0; i < d; ++i) {
+                ell_all.push_back(pw);
+                pw = fr_mul(pw, t);
+            }
+        } else {
+            for (uint32_t i = 0; i < d; ++i) ell_all.push_back(fr_mul(term[i], sum_inv));
+        }
         tab_off[j] = tab_all.size();
         tab_all.insert(tab_all.end(), inv_int.begin(), inv_int.end());
         tab_all.insert(tab_all.end(), beta.begin(), beta.end());
@@ -568,6 +578,33 @@ static int launch_coop(uint32_t groups, rt::stream_t st, const F& f) {
         attr_set = true;
     }
     hipLaunchKernelGGL((coop_kernel<F, BLOCK>), dim3(groups), dim3(BLOCK), F::LDS_BYTES, st, f);
+    return (int)hipGetLastError();
+}
+#endif
+
+/* cooperative launch whose number of phases is known only at run time */
+#if defined(TC_HOST_EMU)
+template <int BLOCK, class F>
+static int launch_coop_n(uint32_t groups, rt::stream_t, const F& f, int phases) {
+    std::vector<uint8_t> lds(F::LDS_BYTES);
+    for (uint32_t g = 0; g < groups; ++g)
+        for (int ph = 0; ph < phases; ++ph)
+            for (uint32_t lane = 0; lane < (uint32_t)BLOCK; ++lane) f.phase(ph, lane, g, lds.data());
+    return 0;
+}
+#else
+template <class F, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void coop_kernel_n(const F f, int phases) {
+    extern __shared__ __align__(16) uint8_t lds[];
+    for (int ph = 0; ph < phases; ++ph) {
+        f.phase(ph, threadIdx.x, blockIdx.x, lds);
+        __syncthreads();
+    }
+}
+template <int BLOCK, class F>
+static int launch_coop_n(uint32_t groups, rt::stream_t st, const F& f, int phases) {
+    if (!groups || phases <= 0) return 0;
+    hipLaunchKernelGGL((coop_kernel_n<F, BLOCK>), dim3(groups), dim3(BLOCK), F::LDS_BYTES, st, f, phases);
     return (int)hipGetLastError();
 }
 #endif
@@ -936,6 +973,7 @@ static int open_device(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, in
 static int check_open_args(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, int dtype, const uint32_t* kappa) {
     TRY(check_commit_args(ctx, srs, d_scalars, dtype));
     if (!kappa) return fail(ctx, TC_ERR_ARG, "null argument");
+    if (srs->flags & TC_SRS_MONOMIAL) return fail(ctx, TC_ERR_STATE, "openings need the Lagrange-basis SRS, this one is monomial");
     for (int a = 0; a < srs->m; ++a) {
         if (!srs->pts[a]) return fail(ctx, TC_ERR_STATE, "SRS was built without suffix tables");
         if (kappa[a] >= srs->shape[a]) return fail(ctx, TC_ERR_RANGE, "opening position outside the grid");
@@ -1153,6 +1191,7 @@ extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** 
     if (ns->m != desc->m) return fail(ctx, TC_ERR_SHAPE, "node SRS order differs from the grid order");
     for (int j = 0; j < desc->m; ++j)
         if (ns->shape[j] != desc->node_shape[j]) return fail(ctx, TC_ERR_SHAPE, "node SRS shape differs from node_shape");
+    if (ns->flags & TC_SRS_MONOMIAL) return fail(ctx, TC_ERR_STATE, "trees need the Lagrange-basis SRS, this one is monomial");
     bool more_than_one = false;
     for (int j = 0; j < desc->m; ++j) more_than_one = more_than_one || desc->node_shape[j] > 1;
     if (!more_than_one) return fail(ctx, TC_ERR_SHAPE, "node shape must have more than one entry");
@@ -1161,7 +1200,10 @@ extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** 
         if (desc->dtype != TC_I8 && desc->dtype != TC_I16) return fail(ctx, TC_ERR_ARG, "payload must be int8 or int16");
     } else if (desc->leaf_kind == TC_LEAF_TENSORS) {
         if (!desc->leaf_srs || !desc->d_leaf_scalars || !desc->leaf_dtype) return fail(ctx, TC_ERR_ARG, "leaf arrays missing");
-        for (uint64_t i = 0; i < n_payload; ++i) TRY(check_commit_args(ctx, desc->leaf_srs[i], desc->d_leaf_scalars[i], desc->leaf_dtype[i]));
+        for (uint64_t i = 0; i < n_payload; ++i) {
+            TRY(check_commit_args(ctx, desc->leaf_srs[i], desc->d_leaf_scalars[i], desc->leaf_dtype[i]));
+            if (desc->leaf_srs[i]->flags & TC_SRS_MONOMIAL) return fail(ctx, TC_ERR_STATE, "trees need the Lagrange-basis SRS, a leaf SRS is monomial");
+        }
     } else {
         return fail(ctx, TC_ERR_ARG, "bad leaf kind");
     }
@@ -1694,6 +1736,91 @@ extern "C" int tc_verify_path(tc_ctx* ctx, const tc_vk* vk, const tc_path* path,
     int rc = tc_verify_paths_batch(ctx, vk, 1, path, root, leaf_value, proof, proof_len, &proof_len, &result);
     if (rc != TC_OK) return rc;
     if (result != TC_OK) return fail(ctx, TC_ERR_VERIFY, "path rejected");
+    return TC_OK;
+}
+
+/* ======================================================================================= */
+/* The coefficient route: interpolation, Algorithm 1                                       */
+/* ======================================================================================= */
+static bool interp_shape_ok(int m, const uint32_t* shape, uint64_t* total) {
+    if (m < 1 || m > TC_MAX_INTERP_ORDER || !shape) return false;
+    uint64_t n = 1;
+    for (int j = 0; j < m; ++j) {
+        if (shape[j] == 0) return false;
+        n *= shape[j];
+        if (n > (1ull << 31) - 1) return false;
+    }
+    *total = n;
+    return true;
+}
+
+extern "C" int tc_interpolate(tc_ctx* ctx, int m, const uint32_t* shape, const void* d_scalars, int dtype, void* d_coeffs) {
+    if (!ctx) return TC_ERR_ARG;
+    if (!d_scalars || !d_coeffs) return fail(ctx, TC_ERR_ARG, "null argument");
+    if (!valid_dtype_scalar(dtype)) return fail(ctx, TC_ERR_ARG, "unsupported scalar dtype");
+    uint64_t n = 0;
+    if (!interp_shape_ok(m, shape, &n)) return fail(ctx, TC_ERR_SHAPE, "bad shape");
+    RT(rt::set_device(ctx->device));
+    TRY(ws_reset(ctx));
+    uint32_t dmax = 1;
+    for (int j = 0; j < m; ++j) dmax = std::max(dmax, shape[j]);
+    /* 1 / l and zeta_k = k + 1 up to the longest axis */
+    std::vector<fr_t> inv(dmax), zeta(dmax);
+    for (uint32_t i = 0; i < dmax; ++i) {
+        inv[i] = fe_from_u32<FrParams>(i ? i : 1);
+        zeta[i] = fe_from_u32<FrParams>(i + 1);
+    }
+    fr_batch_inverse(inv);
+    WS(d_inv, fr_t, dmax);
+    WS(d_zeta, fr_t, dmax);
+    RT(rt::memcpy_h2d(d_inv, inv.data(), sizeof(fr_t) * dmax, ctx->stream));
+    RT(rt::memcpy_h2d(d_zeta, zeta.data(), sizeof(fr_t) * dmax, ctx->stream));
+    fr_t* buf[3];
+    for (int i = 0; i < 3; ++i) {
+        buf[i] = ws_array<fr_t>(ctx, n);
+        if (!buf[i]) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed");
+    }
+    RT(rt::launch<256>(n, ctx->stream, ScalarsToFr{d_scalars, dtype, buf[0]}));
+    uint64_t outer = 1;
+    for (int j = 0; j < m; ++j) {
+        uint32_t d = shape[j];
+        uint64_t inner = n / (outer * d);
+        if (d > 1) {
+            InterpAxis k;
+            k.buf[0] = buf[0]; k.buf[1] = buf[1]; k.buf[2] = buf[2];
+            k.outer = outer; k.inner = inner; k.d = d;
+            k.lines_per_wg = d >= (uint32_t)InterpAxis::BLOCK ? 1u : (uint32_t)InterpAxis::BLOCK / d;
+            k.inv_int = d_inv; k.zeta = d_zeta;
+            uint64_t lines = outer * inner;
+            uint64_t groups = (lines + k.lines_per_wg - 1) / k.lines_per_wg;
+            RT((launch_coop_n<InterpAxis::BLOCK>((uint32_t)groups, ctx->stream, k, (int)(2 * d - 1))));
+            std::swap(buf[0], buf[interp_result_buffer(d)]);      /* the next axis reads what this one produced */
+        }
+        outer *= d;
+    }
+    RT(rt::launch<256>(n, ctx->stream, FrToPlain{buf[0], (fr_plain*)d_coeffs}));
+    RT(rt::stream_sync(ctx->stream));
+    return TC_OK;
+}
+
+extern "C" int tc_divide_by_linear(tc_ctx* ctx, int m, const uint32_t* shape, const void* d_coeffs, int axis,
+                                   uint32_t kappa_axis, void* d_quotient, void* d_remainder) {
+    if (!ctx) return TC_ERR_ARG;
+    if (!d_coeffs || !d_quotient || !d_remainder) return fail(ctx, TC_ERR_ARG, "null argument");
+    if (d_quotient == d_coeffs || d_remainder == d_coeffs || d_quotient == d_remainder) return fail(ctx, TC_ERR_ARG, "arrays may not alias");
+    uint64_t n = 0;
+    if (!interp_shape_ok(m, shape, &n)) return fail(ctx, TC_ERR_SHAPE, "bad shape");
+    if (axis < 0 || axis >= m) return fail(ctx, TC_ERR_ARG, "axis outside the shape");
+    if (kappa_axis >= shape[axis]) return fail(ctx, TC_ERR_RANGE, "position outside the grid");
+    RT(rt::set_device(ctx->device));
+    uint64_t outer = 1;
+    for (int j = 0; j < axis; ++j) outer *= shape[j];
+    uint32_t d = shape[axis];
+    uint64_t inner = n / (outer * d);
+    /* everything off the axis' degree 0 in r, and the whole of q, is written by the kernel; lines = outer * inner */
+    RT(rt::launch<64>(outer * inner, ctx->stream,
+                      DivideAxis{(const fr_plain*)d_coeffs, outer, inner, d, kappa_axis + 1u, (fr_plain*)d_quotient, (fr_plain*)d_remainder}));
+    RT(rt::stream_sync(ctx->stream));
     return TC_OK;
 }
 

@@ -575,3 +575,67 @@ def test_c5_batched_requests(T, ctx, node_srs):
             t.close()
         for s in srs_by_shape.values():
             s.close()
+
+
+def _coeff_list(t):
+    raw = t.cpu().numpy().tobytes()
+    return [int.from_bytes(raw[32 * i : 32 * (i + 1)], "little") for i in range(len(raw) // 32)]
+
+
+def test_coefficient_route(T, ctx):
+    """Interpolation to monomial coefficients and Algorithm 1 on the GPU against the oracle's literal route
+    (Def. 4.1 as printed), over the reshapes of N = 2^12 samples that Fig. 1 sweeps and the C1 shape; then
+    commitments and an opening through the monomial SRS against the Lagrange-basis route."""
+    import torch
+
+    rng = np.random.default_rng(31)
+    for shape in ((64, 64), (16, 16, 16), (8, 8, 8, 8), (4,) * 6, (2,) * 12, (256,), tc_inputs.C1_SHAPE, (300, 7)):
+        n = int(np.prod(shape))
+        X = rng.integers(-32768, 32768, size=shape).astype(np.int16)
+        coeffs = torch.empty(32 * n, dtype=torch.uint8, device="cuda")
+        ctx.interpolate(shape, to_device(X), T.TC_I16, coeffs)
+        want = tc.interpolate(X, shape)
+        assert _coeff_list(coeffs) == want, shape
+        axis = len(shape) - 1 if len(shape) > 1 else 0
+        kap = int(rng.integers(0, shape[axis]))
+        q = torch.empty_like(coeffs)
+        r = torch.empty_like(coeffs)
+        ctx.divide_by_linear(shape, coeffs, axis, kap, q, r)
+        qo, ro = tc.divide_by_linear(want, shape, axis, kap + 1)
+        assert _coeff_list(q) == qo and _coeff_list(r) == ro, shape
+    # the longest line of the sweep, N = 2^12 in one axis: the polynomial must reproduce the samples on the grid
+    X = rng.integers(-128, 128, size=(4096,)).astype(np.int8)
+    coeffs = torch.empty(32 * 4096, dtype=torch.uint8, device="cuda")
+    ctx.interpolate((4096,), to_device(X), T.TC_I8, coeffs)
+    a = _coeff_list(coeffs)
+    for k in (0, 1, 2, 777, 2048, 4094, 4095):
+        acc = 0
+        for c in reversed(a):
+            acc = (acc * (k + 1) + c) % R
+        assert acc == int(X[k]) % R, k
+    # commitments and a literal opening at the C1 shape
+    shape = tc_inputs.C1_SHAPE
+    pp = pps(shape)
+    mono = ctx.setup_from_trapdoor(TAU_BYTES, shape, T.TC_SRS_MONOMIAL)
+    lag = ctx.setup_from_trapdoor(TAU_BYTES, shape, T.TC_SRS_SUFFIX)
+    try:
+        X = tc_inputs.c1_tensor()
+        dX = to_device(X)
+        n = int(np.prod(shape))
+        coeffs = torch.empty(32 * n, dtype=torch.uint8, device="cuda")
+        ctx.interpolate(shape, dX, T.TC_I8, coeffs)
+        C = ctx.commit(mono, coeffs, T.TC_FR)
+        assert C == ctx.commit(lag, dX, T.TC_I8) == ec.g1_to_bytes(tc.commit(pp, X))
+        kappa = (1, 7, 12)
+        rem, proof = coeffs, []
+        for axis in range(3):
+            q, r = torch.empty_like(coeffs), torch.empty_like(coeffs)
+            ctx.divide_by_linear(shape, rem, axis, kappa[axis], q, r)
+            proof.append(ctx.commit(mono, q, T.TC_FR))
+            rem = r
+        y, pi = ctx.open(lag, dX, T.TC_I8, kappa)
+        assert proof == pi
+        assert _coeff_list(rem)[0] == ec.fr_from_bytes(y) == int(X[kappa]) % R and not any(_coeff_list(rem)[1:])
+    finally:
+        mono.close()
+        lag.close()

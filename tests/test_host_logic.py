@@ -279,3 +279,87 @@ def test_path_from_grid_matches_oracle_paths(emu):
             pos = tuple(x // d for x, d in zip(pos, node))
         got = [tuple(p.kappa[s][j] for j in range(2)) for s in range(3)]
         assert got == want[::-1]
+
+
+def _fr_array(n):
+    return np.zeros(32 * n, dtype=np.uint8)
+
+
+def _fr_list(buf):
+    raw = buf.tobytes()
+    return [int.from_bytes(raw[32 * i : 32 * (i + 1)], "little") for i in range(len(raw) // 32)]
+
+
+def test_emulated_coefficient_route(emu):
+    """The literal route of Def. 4.1 through the library: interpolation to monomial coefficients, Algorithm 1 on
+    the coefficient array, commitments against the monomial SRS -- each against the oracle's own literal route,
+    and the resulting group elements against the Lagrange-basis route."""
+    rng = np.random.default_rng(21)
+    for shape in ((5,), (3, 4), (2, 3, 2), (1, 4), (2, 2, 2, 2, 2), (7, 1, 3)):
+        n = int(np.prod(shape))
+        X = rng.integers(-128, 128, size=shape).astype(np.int8)
+        coeffs = _fr_array(n)
+        emu.interpolate(shape, X, T.TC_I8, coeffs)
+        want = tc.interpolate(X, shape)
+        assert _fr_list(coeffs) == want, shape
+        # Algorithm 1 along every axis at some position
+        for axis, d in enumerate(shape):
+            kap = int(rng.integers(0, d))
+            q, r = _fr_array(n), _fr_array(n)
+            emu.divide_by_linear(shape, coeffs, axis, kap, q, r)
+            qo, ro = tc.divide_by_linear(want, shape, axis, kap + 1)
+            assert _fr_list(q) == qo and _fr_list(r) == ro, (shape, axis)
+    # int16 and full-width inputs
+    X16 = rng.integers(-32768, 32768, size=(4, 3)).astype(np.int16)
+    c16 = _fr_array(12)
+    emu.interpolate((4, 3), X16, T.TC_I16, c16)
+    assert _fr_list(c16) == tc.interpolate(X16, (4, 3))
+    big = [int(v) for v in rng.integers(1, 2**62, size=6)]
+    big = [(v * v * v) % R for v in big]
+    cfr = _fr_array(6)
+    emu.interpolate((6,), fr_bytes_array(big), T.TC_FR, cfr)
+    assert _fr_list(cfr) == tc.interpolate(big, (6,))
+    # commitments and an opening through the monomial SRS
+    shape = (3, 4)
+    pp = pps(shape)
+    mono = emu.setup_from_trapdoor(TAU_BYTES, shape, T.TC_SRS_MONOMIAL)
+    lag = emu.setup_from_trapdoor(TAU_BYTES, shape, T.TC_SRS_SUFFIX)
+    try:
+        srs_mono = pp.srs_monomial()
+        for k in (0, 1, 5, 11):
+            assert mono.point(k) == ec.g1_to_bytes(srs_mono[k])
+        X = rng.integers(-128, 128, size=shape).astype(np.int8)
+        coeffs = _fr_array(12)
+        emu.interpolate(shape, X, T.TC_I8, coeffs)
+        C = emu.commit(mono, coeffs, T.TC_FR)
+        assert C == ec.g1_to_bytes(tc.commit_literal(pp, X)) == emu.commit(lag, X, T.TC_I8)
+        kappa = (2, 1)
+        yo, po = tc.open_literal(pp, X, kappa)
+        rem = coeffs
+        proof = []
+        for axis in range(2):
+            q, r = _fr_array(12), _fr_array(12)
+            emu.divide_by_linear(shape, rem, axis, kappa[axis], q, r)
+            proof.append(emu.commit(mono, q, T.TC_FR))
+            rem = r
+        assert proof == [ec.g1_to_bytes(p) for p in po]
+        assert _fr_list(rem)[0] == yo and not any(_fr_list(rem)[1:])
+        y, pi = emu.open(lag, X, T.TC_I8, kappa)        # the evaluation-form route gives the same proof
+        assert pi == proof and y == ec.fr_to_bytes(yo)
+        with pytest.raises(T.TcError) as err:
+            emu.open(mono, X, T.TC_I8, kappa)
+        assert err.value.code == T.binding.TC_ERR_STATE
+        with pytest.raises(T.TcError):
+            emu.setup_from_trapdoor(TAU_BYTES, shape, T.TC_SRS_MONOMIAL | T.TC_SRS_SUFFIX)
+    finally:
+        mono.close()
+        lag.close()
+    # argument errors
+    with pytest.raises(T.TcError):
+        emu.interpolate((2,) * 13, np.zeros(8192, dtype=np.int8), T.TC_I8, _fr_array(8192))
+    with pytest.raises(T.TcError):
+        emu.divide_by_linear((3, 4), coeffs, 2, 0, _fr_array(12), _fr_array(12))
+    with pytest.raises(T.TcError):
+        emu.divide_by_linear((3, 4), coeffs, 1, 4, _fr_array(12), _fr_array(12))
+    with pytest.raises(T.TcError):
+        emu.divide_by_linear((3, 4), coeffs, 1, 0, coeffs, _fr_array(12))
