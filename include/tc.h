@@ -218,6 +218,14 @@ int tc_verify_paths_batch(tc_ctx* ctx, const tc_vk* vk, int count, const tc_path
                           const uint8_t* leaf_values, const void* proofs, size_t proof_stride,
                           const size_t* proof_len, int* results);
 
+/* One entry changed by `delta` (new value minus old value): recomputes the commitments on its path only,
+ * reusing the rest of the tree (Sec. 4.2): C' = C + [delta] S[k] for the node (entries tree) or the leaf tensor
+ * (tensors tree: inner_index is the entry's position in that tensor, else NULL) that holds the entry, then
+ * C' = C + [phi(child') - phi(child)] S[k] level by level up to the root.  The caller writes the new value into
+ * its own payload / tensor buffer (before or after this call; openings read that buffer).  |delta| < 2^32.
+ * Blocked levels need the fixed-base node SRS (TC_ERR_STATE otherwise). */
+int tc_terkle_update(tc_ctx* ctx, tc_tree* tree, const uint32_t* leaf_index, const uint32_t* inner_index, int64_t delta);
+
 /* ---- the coefficient route: interpolation and Algorithm 1 on the device -----------------------
  *
  * Def. 4.1 commits to the monomial coefficients of the interpolant f_T; the hot path above never forms them

@@ -177,10 +177,11 @@ def verify_path(pps, root, shapes, leaf_value, steps):
             return False
         last = d == len(steps) - 1
         if last:
-            if child is not None or y != leaf_value % R:
+            if y != leaf_value % R:
                 return False
         else:
-            if child is None or y != phi(child):
+            # the child may be the identity (a node over zeros only): phi(O) = 0, and INF is None here
+            if y != phi(child):
                 return False
             C = child
     return True

@@ -103,6 +103,7 @@ def load_library(path=None):
         "tc_verify_paths_batch": (ctypes.c_int, [vp, vp, ctypes.c_int, ctypes.POINTER(tc_path), u8p, u8p, vp,
                                                  ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t),
                                                  ctypes.POINTER(ctypes.c_int)]),
+        "tc_terkle_update": (ctypes.c_int, [vp, vp, u32p, u32p, ctypes.c_int64]),
         "tc_interpolate": (ctypes.c_int, [vp, ctypes.c_int, u32p, vp, ctypes.c_int, vp]),
         "tc_divide_by_linear": (ctypes.c_int, [vp, ctypes.c_int, u32p, vp, ctypes.c_int, ctypes.c_uint32, vp, vp]),
         "tc_vkp_from_trapdoor": (ctypes.c_int, [u8p, ctypes.c_int, ctypes.POINTER(vp)]),
@@ -254,6 +255,11 @@ class Tree:
             self.ctx.handle, self.handle, count, _u32(flat_leaf), _u32(flat_inner) if inner_indices else None,
             buf, stride, lens))
         return [buf.raw[i * stride : i * stride + lens[i]] for i in range(count)]
+
+    def update(self, leaf_index, delta, inner_index=None):
+        """One entry changed by `delta` (the caller updates its own buffer): recompute the path and the root."""
+        self.ctx._check(self.ctx.lib.tc_terkle_update(self.ctx.handle, self.handle, _u32(leaf_index),
+                                                      _u32(inner_index) if inner_index is not None else None, int(delta)))
 
     def close(self):
         if self.handle:

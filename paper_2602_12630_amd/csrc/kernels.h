@@ -1678,4 +1678,46 @@ struct DivideAxis {
     }
 };
 
+/* ---- incremental update of one path (the structure is reused, Sec. 4.2) ---------------------- */
+/* One lane: the commitment of node `a` of a level moves by [s] B, where B is base `k` of a fixed-base table
+ * (nodes) or one SRS point (a leaf tensor) and s is a small signed integer (an entry changed) or the change of
+ * phi of the child below (read from `dphi`, written by the launch for the level below).  The new commitment
+ * and its phi replace the old ones; the change of phi goes to `dphi` for the level above. */
+struct UpdatePathNode {
+    g1_affine* C;              /* level array */
+    fr_plain* phi;
+    uint64_t a;
+    const g1_affine* table;    /* fixed-base table, or null */
+    uint32_t k;
+    const g1_affine* point;    /* single base when table is null */
+    int64_t small;             /* used when from_dphi == 0 */
+    int from_dphi;
+    fr_plain* dphi;            /* one value */
+    TC_DEV void operator()(uint32_t) const {
+        fr_t s;
+        if (from_dphi) {
+            s = fe_from_limbs<FrParams>(dphi->l);
+        } else {
+            uint64_t mag = (uint64_t)(small < 0 ? -small : small);
+            uint32_t w[8] = {(uint32_t)mag, (uint32_t)(mag >> 32), 0, 0, 0, 0, 0, 0};
+            s = fe_from_limbs<FrParams>(w);
+            if (small < 0) s = fr_neg(s);
+        }
+        fr_t plain = fe_to_plain(s);
+        g1_xyzz acc = xyzz_from_affine(C[a]);
+        if (table) acc = fb_mul_accumulate(acc, table, k, plain.l);
+        else acc = xyzz_add(acc, xyzz_mul_affine(plain.l, 256, *point));
+        g1_affine c = xyzz_to_affine(acc);
+        fr_t old_phi = fe_from_limbs<FrParams>(phi[a].l);
+        fr_t new_plain = phi_map(c);
+        fr_t diff = fe_to_plain(fr_sub(fe_from_limbs<FrParams>(new_plain.l), old_phi));
+        C[a] = c;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            phi[a].l[i] = new_plain.l[i];
+            dphi->l[i] = diff.l[i];
+        }
+    }
+};
+
 }  // namespace tc

@@ -1739,6 +1739,52 @@ extern "C" int tc_verify_path(tc_ctx* ctx, const tc_vk* vk, const tc_path* path,
     return TC_OK;
 }
 
+/* ---- incremental update --------------------------------------------------------------------- */
+extern "C" int tc_terkle_update(tc_ctx* ctx, tc_tree* tree, const uint32_t* leaf_index, const uint32_t* inner_index,
+                                int64_t delta) {
+    if (!ctx) return TC_ERR_ARG;
+    if (!tree || !leaf_index) return fail(ctx, TC_ERR_ARG, "null argument");
+    tc_tree* t = tree;
+    if (delta >= (1ll << 32) || delta <= -(1ll << 32)) return fail(ctx, TC_ERR_RANGE, "delta too large");
+    const tc_srs* ns = t->node_srs;
+    if (!ns->fb[0]) return fail(ctx, TC_ERR_STATE, "updates need the fixed-base node SRS");
+    int m = t->m;
+    for (int j = 0; j < m; ++j)
+        if (leaf_index[j] >= t->grid[j]) return fail(ctx, TC_ERR_RANGE, "leaf index outside the grid");
+    bool tensors = t->leaf_kind == TC_LEAF_TENSORS;
+    if (tensors && !inner_index) return fail(ctx, TC_ERR_ARG, "inner index missing");
+    RT(rt::set_device(ctx->device));
+    TRY(ws_reset(ctx));
+    WS(d_dphi, fr_plain, 1);
+    uint32_t pos[4] = {0, 0, 0, 0};
+    for (int j = 0; j < m; ++j) pos[j] = leaf_index[j];
+    int level = 0;
+    int from_dphi = 0;
+    if (tensors) {
+        uint64_t leaf_flat = flat_of(pos, t->grid, m);
+        const tc_srs* ls = t->leaf_srs[leaf_flat];
+        uint64_t inner_flat = 0;
+        for (int a = 0; a < ls->m; ++a) {
+            if (inner_index[a] >= ls->shape[a]) return fail(ctx, TC_ERR_RANGE, "inner index outside the leaf tensor");
+            inner_flat = inner_flat * ls->shape[a] + inner_index[a];
+        }
+        RT(rt::launch<64>(1, ctx->stream, UpdatePathNode{t->levels[0].C, t->levels[0].phi, leaf_flat, nullptr, 0,
+                                                         ls->pts[0] + inner_flat, delta, 0, d_dphi}));
+        level = 1;
+        from_dphi = 1;
+    }
+    for (; level < (int)t->levels.size(); ++level) {
+        uint32_t k[4] = {0, 0, 0, 0};
+        for (int j = 0; j < m; ++j) { k[j] = pos[j] % t->node_shape[j]; pos[j] /= t->node_shape[j]; }
+        uint64_t a = flat_of(pos, t->levels[level].grid, m);
+        uint32_t kf = (uint32_t)flat_of(k, t->node_shape, m);
+        RT(rt::launch<64>(1, ctx->stream, UpdatePathNode{t->levels[level].C, t->levels[level].phi, a, ns->fb[0], kf,
+                                                         nullptr, delta, from_dphi, d_dphi}));
+        from_dphi = 1;
+    }
+    return affine_to_host(ctx, t->levels.back().C, 1, t->root);
+}
+
 /* ======================================================================================= */
 /* The coefficient route: interpolation, Algorithm 1                                       */
 /* ======================================================================================= */

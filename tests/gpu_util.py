@@ -31,9 +31,9 @@ def fr_bytes_array(values):
 def serialize_steps(steps):
     """Oracle path steps -> the proof byte layout of the library (top level first)."""
     out = b""
-    for (_k, y, pi, child) in steps:
+    for i, (_k, y, pi, child) in enumerate(steps):
         out += b"".join(ec.g1_to_bytes(p) for p in pi) + ec.fr_to_bytes(y)
-        if child is not None:
+        if i + 1 < len(steps):                    # every step but the last carries the next commitment (may be the identity)
             out += ec.g1_to_bytes(child)
     return out
 

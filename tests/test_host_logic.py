@@ -363,3 +363,53 @@ def test_emulated_coefficient_route(emu):
         emu.divide_by_linear((3, 4), coeffs, 1, 4, _fr_array(12), _fr_array(12))
     with pytest.raises(T.TcError):
         emu.divide_by_linear((3, 4), coeffs, 1, 0, coeffs, _fr_array(12))
+
+
+def test_emulated_incremental_update(emu, node_srs):
+    """One entry changes: the library moves the commitments on its path only; the result must be the tree the
+    oracle builds from scratch over the changed payload -- every node, and the openings after the update."""
+    node, grid = (2, 2), (5, 7)
+    X = tc_inputs.int16_uniform(grid, 9)
+    tree = emu.terkle_build_entries(node_srs, X, T.TC_I16, grid, node)
+    vk = emu.vk_from_trapdoor(TAU_BYTES)
+    try:
+        for leaf, new in (((3, 4), -32768), ((0, 0), 32767), ((4, 6), 0), ((3, 4), 5)):
+            delta = int(new) - int(X[leaf])
+            X[leaf] = new                                     # the caller's buffer
+            tree.update(leaf, delta)
+            ot = terkle.build(pps, tc.as_flat_ints(X), grid, node)
+            for L in range(tree.levels):
+                g, n = tree.level_info(L)
+                for i in range(n):
+                    assert tree.node(L, i) == ec.g1_to_bytes(ot.levels[L]["C"][tc.multi_index(i, g)]), (leaf, L, i)
+            assert tree.root == ec.g1_to_bytes(ot.root)
+            proof = tree.open(leaf)
+            assert proof == serialize_steps(terkle.open_path(pps, ot, grid, node, leaf))
+            assert emu.verify_path(vk, tree.path(leaf), tree.root, ec.fr_to_bytes(int(new) % R), proof)
+        with pytest.raises(T.TcError):
+            tree.update((5, 0), 1)
+        with pytest.raises(T.TcError):
+            tree.update((0, 0), 1 << 32)
+    finally:
+        tree.close()
+    # a tensors tree: an entry inside a leaf tensor changes
+    shapes = [(2, 3), (4,), (2, 2, 2), (3, 2)]
+    rng = np.random.default_rng(17)
+    leaves = [rng.integers(-50, 50, size=s).astype(np.int8) for s in shapes]
+    srs = [emu.setup_from_trapdoor(TAU_BYTES, s, T.TC_SRS_SUFFIX) for s in shapes]
+    tree = emu.terkle_build_tensors(node_srs, srs, leaves, [T.TC_I8] * 4, (2, 2), node)
+    try:
+        leaves[2][1, 0, 1] += 9
+        tree.update((1, 0), 9, inner_index=(1, 0, 1))
+        ot = terkle.build(pps, [tc.as_flat_ints(t) for t in leaves], (2, 2), node, kind="tensors", leaf_shapes=shapes)
+        assert tree.root == ec.g1_to_bytes(ot.root)
+        for i in range(4):
+            assert tree.node(0, i) == ec.g1_to_bytes(ot.levels[0]["C"][tc.multi_index(i, (2, 2))])
+        proof = tree.open((1, 0), (1, 0, 1))
+        assert proof == serialize_steps(terkle.open_path(pps, ot, (2, 2), node, (1, 0), (1, 0, 1)))
+        with pytest.raises(T.TcError):
+            tree.update((1, 0), 1)                            # inner index missing
+    finally:
+        tree.close()
+        for s in srs:
+            s.close()

@@ -158,3 +158,20 @@ def test_golden_c1_matches_oracle():
         pi = [ec.g1_from_bytes(bytes.fromhex(h)) for h in o["pi"]]
         assert tc.verify(pp, C, tuple(o["kappa"]), y, pi)
         assert y == int(T[tuple(o["kappa"])]) % R
+
+
+def test_node_over_zeros_has_the_identity_as_commitment_and_still_verifies():
+    """A node whose tensor is all zero commits to the identity; it enters its parent as phi(O) = 0, and a path
+    through it must still verify (the child carried by the proof is the identity, not a missing child)."""
+    grid, node = (4, 4), (2, 2)
+    X = np.arange(16).reshape(grid) + 1
+    X[2:4, 2:4] = 0
+    tree = terkle.build(pps, tc.as_flat_ints(X), grid, node)
+    assert tree.levels[0]["C"][(1, 1)] is ec.INF
+    leaf = (3, 2)
+    steps = terkle.open_path(pps, tree, grid, node, leaf)
+    assert steps[0][3] is ec.INF and steps[0][1] == 0            # the top step opens phi(O) = 0 and carries O
+    assert terkle.verify_path(pps, tree.root, [node] * 2, 0, steps)
+    assert not terkle.verify_path(pps, tree.root, [node] * 2, 1, steps)
+    moved = [(steps[0][0], steps[0][1], steps[0][2], ec.G1)] + steps[1:]
+    assert not terkle.verify_path(pps, tree.root, [node] * 2, 0, moved)
