@@ -117,6 +117,61 @@ def coefficient_route(ctx, T, torch, with_oracle):
     return out
 
 
+def tree_scaling(ctx, T, torch, tau):
+    """The tree-scaling comparison of Fig. 4 as a workload: arity B = 64, 64^1 .. 64^4 int16 leaves, Terkle node
+    shapes (8,8) and (4,4,4) and the Verkle tree as node shape (64,): build, 8 openings in one batch, their
+    batch verification on the GPU, public verification of one path on the host, one incremental update."""
+    out = []
+    vk = ctx.vk_from_trapdoor(tau)
+    for node in ((8, 8), (4, 4, 4), (64,)):
+        m = len(node)
+        srs = ctx.setup_from_trapdoor(tau, node, T.TC_SRS_SUFFIX | T.TC_SRS_FIXED_BASE)
+        pv = T.PairingVerifier(tau, m)
+        for k in (1, 2, 3, 4):
+            grid = tuple(d**k for d in node)
+            n = 64**k
+            x = tc_inputs.int16_uniform(grid, 100 + k)
+            dx = torch.from_numpy(x).cuda()
+            leaves = tc_inputs.opening_positions(grid, 8, 7)
+            tree = ctx.terkle_build_entries(srs, dx, T.TC_I16, grid, node)
+            tree.close()
+            ctx.sync()
+
+            def clock(fn, reps=3):
+                best = None
+                for _ in range(reps):
+                    ctx.sync()
+                    t0 = time.perf_counter()
+                    r = fn()
+                    ctx.sync()
+                    dt = (time.perf_counter() - t0) * 1e3
+                    best = dt if best is None or dt < best else best
+                return best, r
+
+            build_ms, tree = clock(lambda: ctx.terkle_build_entries(srs, dx, T.TC_I16, grid, node), 1)
+            open_ms, proofs = clock(lambda: tree.open_batch(leaves))
+            paths = [tree.path(l) for l in leaves]
+            values = [(int(x[l]) % R_MODULUS).to_bytes(32, "little") for l in leaves]
+            verify_ms, ok = clock(lambda: ctx.verify_paths_batch(vk, paths, [tree.root] * 8, values, proofs))
+            assert all(ok)
+            t0 = time.perf_counter()
+            assert pv.verify_path(paths[0], tree.root, values[0], proofs[0])
+            public_ms = (time.perf_counter() - t0) * 1e3
+            root_before = tree.root
+            update_ms, _ = clock(lambda: tree.update(leaves[0], 1), 1)
+            assert tree.root != root_before
+            tree.update(leaves[0], -1)
+            assert tree.root == root_before
+            out.append({"node_shape": list(node), "leaves": n, "levels": tree.levels, "build_ms": build_ms,
+                        "open_8_paths_ms": open_ms, "verify_8_paths_gpu_ms": verify_ms, "verify_1_path_pairing_cpu_ms": public_ms,
+                        "update_1_entry_ms": update_ms})
+            tree.close()
+            del dx
+        pv.close()
+        srs.close()
+    return out
+
+
 def cpu_baseline(q, budget_s=12.0):
     """The oracle's naive multi-exponentiation (every term its own double-and-add) on the first
     entries of the same quantised tensor, on all host cores the box gives us."""
@@ -225,6 +280,8 @@ def main():
                     "(reference dispatch for scaling the HBM byte counters of a rocprofv3 --pmc run)")
     ap.add_argument("--in-flight", type=int, default=2, help="steps in flight: each has its own host thread, contexts, "
                     "streams and buffers; the K timed steps are dealt out to them (1 = one step after the other)")
+    ap.add_argument("--fig4", action="store_true", help="also run the arity-64 tree-scaling workload (64^1 .. 64^4 leaves, "
+                    "node shapes (8,8), (4,4,4), (64,)); needs about 12 GB of fixed-base tables")
     ap.add_argument("--serial", action="store_true", help="run the flat commitment and the tree build one after the other "
                     "on one stream instead of concurrently on two")
     args = ap.parse_args()
@@ -495,6 +552,8 @@ def main():
         assert ok_o
     tree.close()
     pv.close()
+    if args.fig4:
+        out["tree_scaling"] = tree_scaling(ctx, T, torch, tau)
     out["coefficient_route"] = coefficient_route(ctx, T, torch, not args.no_cpu_baseline)
     if not args.no_c3:
         out["terkle_build_llama2_7b_fwd"] = c3_forward(ctx, T, torch, node_srs, tau)

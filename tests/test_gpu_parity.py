@@ -639,3 +639,43 @@ def test_coefficient_route(T, ctx):
     finally:
         mono.close()
         lag.close()
+
+
+@pytest.mark.parametrize("node,grid", [((8, 8), (64, 64)), ((4, 4, 4), (16, 16, 16)), ((64,), (4096,)), ((8, 8), (70, 9))])
+def test_arity_64_trees(T, ctx, node, grid):
+    """The tree shapes of the paper's tree-scaling comparison (Fig. 4, B = 64): Terkle nodes (8,8) and (4,4,4),
+    and the Verkle tree as the order-1 node shape (64,), over 64^2 leaves (and a ragged grid): every node, paths,
+    batch verification, and an incremental update against the oracle's rebuild."""
+    X = tc_inputs.int16_uniform(grid, 11)
+    dX = to_device(X)
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, node, T.TC_SRS_SUFFIX | T.TC_SRS_FIXED_BASE)
+    tree = ctx.terkle_build_entries(srs, dX, T.TC_I16, grid, node)
+    try:
+        otree = terkle.build(pps, tc.as_flat_ints(X), grid, node)
+        _check_tree_against_oracle(ctx, tree, otree)
+        vk = ctx.vk_from_trapdoor(TAU_BYTES)
+        leaves = tc_inputs.opening_positions(grid, 3, 5) + [tuple(g - 1 for g in grid)]
+        proofs = tree.open_batch(leaves)
+        for leaf, proof in zip(leaves, proofs):
+            assert proof == serialize_steps(terkle.open_path(pps, otree, grid, node, leaf))
+        values = [ec.fr_to_bytes(int(X[l]) % R) for l in leaves]
+        paths = [tree.path(l) for l in leaves]
+        assert ctx.verify_paths_batch(vk, paths, [tree.root] * len(leaves), values, proofs) == [True] * len(leaves)
+        pv = T.PairingVerifier(TAU_BYTES, len(node))
+        assert pv.verify_path(paths[0], tree.root, values[0], proofs[0])
+        pv.close()
+        # one entry changes
+        leaf = leaves[1]
+        new = -int(X[leaf]) - 3
+        delta = new - int(X[leaf])
+        X[leaf] = new
+        dX.copy_(to_device(X))
+        tree.update(leaf, delta)
+        otree = terkle.build(pps, tc.as_flat_ints(X), grid, node)
+        _check_tree_against_oracle(ctx, tree, otree)
+        proof = tree.open(leaf)
+        assert proof == serialize_steps(terkle.open_path(pps, otree, grid, node, leaf))
+        assert ctx.verify_path(vk, tree.path(leaf), tree.root, ec.fr_to_bytes(new % R), proof)
+    finally:
+        tree.close()
+        srs.close()
