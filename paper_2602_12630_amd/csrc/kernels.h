@@ -991,6 +991,24 @@ struct NodeCommitSmall {
         out[a] = acc;
     }
 };
+/* the same for a bottom level of very few nodes: every child its own slot of a cooperative sum */
+struct NodeSmallSrc {
+    TreeGeom g;
+    const void* payload;
+    int dtype;
+    const g1_affine* table;
+    g1_xyzz* out;
+    TC_DEV uint32_t count(uint32_t) const { return g.B < 256u ? g.B : 256u; }
+    TC_DEV g1_xyzz load(uint32_t node, uint32_t i) const {
+        g1_xyzz acc = xyzz_identity();
+        for (uint32_t k = i; k < g.B; k += 256) {
+            int64_t f = child_index(g, node, k);
+            if (f >= 0) acc = fb_small_accumulate(acc, table, k, small_scalar(payload, dtype, (uint64_t)f));
+        }
+        return acc;
+    }
+    TC_DEV void store(uint32_t node, const g1_xyzz& r) const { out[node] = r; }
+};
 /* upper levels: lane = (node, child); the child's value is phi of the commitment below */
 struct NodeCommitFr {
     TreeGeom g;
@@ -1679,11 +1697,12 @@ struct DivideAxis {
 };
 
 /* ---- incremental update of one path (the structure is reused, Sec. 4.2) ---------------------- */
-/* One lane: the commitment of node `a` of a level moves by [s] B, where B is base `k` of a fixed-base table
- * (nodes) or one SRS point (a leaf tensor) and s is a small signed integer (an entry changed) or the change of
- * phi of the child below (read from `dphi`, written by the launch for the level below).  The new commitment
- * and its phi replace the old ones; the change of phi goes to `dphi` for the level above. */
-struct UpdatePathNode {
+/* The commitment of node `a` of a level moves by [s] B, where B is base `k` of a fixed-base table (nodes) or one
+ * SRS point (a leaf tensor) and s is a small signed integer (an entry changed) or the change of phi of the child
+ * below (read from `dphi`, written by the launch for the level below).  A cooperative sum adds the old
+ * commitment and the window terms of [s] B; its last lane standing normalises, replaces the commitment and its
+ * phi, and leaves the change of phi in `dphi` for the level above. */
+struct UpdatePathSrc {
     g1_affine* C;              /* level array */
     fr_plain* phi;
     uint64_t a;
@@ -1693,21 +1712,28 @@ struct UpdatePathNode {
     int64_t small;             /* used when from_dphi == 0 */
     int from_dphi;
     fr_plain* dphi;            /* one value */
-    TC_DEV void operator()(uint32_t) const {
-        fr_t s;
-        if (from_dphi) {
-            s = fe_from_limbs<FrParams>(dphi->l);
-        } else {
-            uint64_t mag = (uint64_t)(small < 0 ? -small : small);
-            uint32_t w[8] = {(uint32_t)mag, (uint32_t)(mag >> 32), 0, 0, 0, 0, 0, 0};
-            s = fe_from_limbs<FrParams>(w);
-            if (small < 0) s = fr_neg(s);
-        }
-        fr_t plain = fe_to_plain(s);
-        g1_xyzz acc = xyzz_from_affine(C[a]);
-        if (table) acc = fb_mul_accumulate(acc, table, k, plain.l);
-        else acc = xyzz_add(acc, xyzz_mul_affine(plain.l, 256, *point));
-        g1_affine c = xyzz_to_affine(acc);
+    TC_DEV fr_t scalar() const {
+        if (from_dphi) return fe_from_limbs<FrParams>(dphi->l);
+        uint64_t mag = (uint64_t)(small < 0 ? -small : small);
+        uint32_t w[8] = {(uint32_t)mag, (uint32_t)(mag >> 32), 0, 0, 0, 0, 0, 0};
+        fr_t s = fe_from_limbs<FrParams>(w);
+        return small < 0 ? fr_neg(s) : s;
+    }
+    TC_DEV uint32_t count(uint32_t) const { return table ? (uint32_t)FB_W + 1u : 2u; }
+    TC_DEV g1_xyzz load(uint32_t, uint32_t i) const {
+        if (i == 0) return xyzz_from_affine(C[a]);
+        fr_t plain = fe_to_plain(scalar());
+        if (!table) return xyzz_mul_affine(plain.l, 256, *point);
+        uint32_t w = i - 1, carry = 0;
+        int32_t d = 0;
+        for (uint32_t x = 0; x <= w; ++x) d = fr_window_digit(plain.l, (int)x, FB_C, carry);
+        if (!d) return xyzz_identity();
+        g1_affine p = table[((uint64_t)k * FB_W + w) * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u];
+        if (d < 0) p.y = fp_neg(p.y);
+        return xyzz_from_affine(p);
+    }
+    TC_DEV void store(uint32_t, const g1_xyzz& r) const {
+        g1_affine c = xyzz_to_affine(r);
         fr_t old_phi = fe_from_limbs<FrParams>(phi[a].l);
         fr_t new_plain = phi_map(c);
         fr_t diff = fe_to_plain(fr_sub(fe_from_limbs<FrParams>(new_plain.l), old_phi));

@@ -1294,7 +1294,10 @@ extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** 
                 bool bottom = (L == 0);
                 if (use_fb) {
                     int e;
-                    if (bottom) {
+                    if (bottom && lv.n <= COOP_LEVEL_NODES) {
+                        typedef CoopReduce<NodeSmallSrc> Sum;
+                        e = launch_coop<Sum::BLOCK>((uint32_t)lv.n, ctx->stream, Sum{NodeSmallSrc{g, t->d_payload, t->dtype, ns->fb[0], acc}});
+                    } else if (bottom) {
                         rt::event_t e0, e1;
                         prof_begin(ctx, TC_PROF_NODE_COMMIT, &e0, &e1);
                         e = rt::launch<64>(lv.n, ctx->stream, NodeCommitSmall{g, t->d_payload, t->dtype, ns->fb[0], acc});
@@ -1756,6 +1759,7 @@ extern "C" int tc_terkle_update(tc_ctx* ctx, tc_tree* tree, const uint32_t* leaf
     RT(rt::set_device(ctx->device));
     TRY(ws_reset(ctx));
     WS(d_dphi, fr_plain, 1);
+    typedef CoopReduce<UpdatePathSrc> Upd;
     uint32_t pos[4] = {0, 0, 0, 0};
     for (int j = 0; j < m; ++j) pos[j] = leaf_index[j];
     int level = 0;
@@ -1768,8 +1772,8 @@ extern "C" int tc_terkle_update(tc_ctx* ctx, tc_tree* tree, const uint32_t* leaf
             if (inner_index[a] >= ls->shape[a]) return fail(ctx, TC_ERR_RANGE, "inner index outside the leaf tensor");
             inner_flat = inner_flat * ls->shape[a] + inner_index[a];
         }
-        RT(rt::launch<64>(1, ctx->stream, UpdatePathNode{t->levels[0].C, t->levels[0].phi, leaf_flat, nullptr, 0,
-                                                         ls->pts[0] + inner_flat, delta, 0, d_dphi}));
+        RT((launch_coop<Upd::BLOCK>(1, ctx->stream, Upd{UpdatePathSrc{t->levels[0].C, t->levels[0].phi, leaf_flat, nullptr, 0,
+                                                                      ls->pts[0] + inner_flat, delta, 0, d_dphi}})));
         level = 1;
         from_dphi = 1;
     }
@@ -1778,8 +1782,8 @@ extern "C" int tc_terkle_update(tc_ctx* ctx, tc_tree* tree, const uint32_t* leaf
         for (int j = 0; j < m; ++j) { k[j] = pos[j] % t->node_shape[j]; pos[j] /= t->node_shape[j]; }
         uint64_t a = flat_of(pos, t->levels[level].grid, m);
         uint32_t kf = (uint32_t)flat_of(k, t->node_shape, m);
-        RT(rt::launch<64>(1, ctx->stream, UpdatePathNode{t->levels[level].C, t->levels[level].phi, a, ns->fb[0], kf,
-                                                         nullptr, delta, from_dphi, d_dphi}));
+        RT((launch_coop<Upd::BLOCK>(1, ctx->stream, Upd{UpdatePathSrc{t->levels[level].C, t->levels[level].phi, a, ns->fb[0], kf,
+                                                                      nullptr, delta, from_dphi, d_dphi}})));
         from_dphi = 1;
     }
     return affine_to_host(ctx, t->levels.back().C, 1, t->root);
