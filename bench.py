@@ -552,6 +552,22 @@ def main():
         assert ok_o
     tree.close()
     pv.close()
+    # the verifier's layer selection (Problem 4.5) on synthetic benefits: library O(M L) against the oracle's O(M L^2)
+    rng_sel = np.random.default_rng(9)
+    Lsel, Msel = 2000, 8
+    nu_s, phi_s = (rng_sel.random(Lsel) ** 3).tolist(), (1.0 + rng_sel.random(Lsel)).tolist()
+    beta_s = (50.0 + 50.0 * rng_sel.random(Msel)).tolist()
+    t0 = time.perf_counter()
+    val_s, _ = T.binding.select_layers(nu_s, phi_s, beta_s, lib)
+    sel_ms = (time.perf_counter() - t0) * 1e3
+    out["layer_selection"] = {"layers": Lsel, "verifiers": Msel, "ms": sel_ms, "where": "host CPU, one thread (incl. marshalling)"}
+    if not args.no_cpu_baseline:
+        from oracle import selector as osel
+        t0 = time.perf_counter()
+        table = osel.dp_naive(nu_s[:400], phi_s[:400], beta_s)
+        out["layer_selection"]["oracle_ms_400_layers"] = (time.perf_counter() - t0) * 1e3
+        v400, _ = T.binding.select_layers(nu_s[:400], phi_s[:400], beta_s, lib)
+        assert abs(v400 - table[Msel][400]) <= 1e-9 * max(1.0, abs(v400))
     if args.fig4:
         out["tree_scaling"] = tree_scaling(ctx, T, torch, tau)
     out["coefficient_route"] = coefficient_route(ctx, T, torch, not args.no_cpu_baseline)

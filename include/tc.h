@@ -275,6 +275,22 @@ int tc_verify_pairing(const tc_vkp* vkp, int m, const uint32_t* shape, const uin
 int tc_verify_path_pairing(const tc_vkp* vkp, const tc_path* path, const uint8_t root[96],
                            const uint8_t leaf_value[32], const void* proof, size_t proof_len);
 
+/* ---- layer selection (CPU only; the verifier's policy, Sec. 4.3) --------------------------------
+ * float64; no context, no GPU. */
+
+/* Hill estimator of the tail exponent on the chi largest of d eigenvalues (any order):
+ * alpha = 1 + chi / sum_{r=1..chi} ln(Lambda_{d-r+1} / Lambda_{d-chi}).  TC_ERR_ARG unless 1 <= chi < d and the
+ * eigenvalue Lambda_{d-chi} is positive and the tail is not flat. */
+int tc_hill_alpha(const double* eigenvalues, size_t d, size_t chi, double* out_alpha);
+/* nu_i = (alpha_max - alpha_i) / (alpha_max - alpha_min) * P_i / sum_j P_j (all zero when every alpha is equal) */
+int tc_layer_benefits(const double* alpha, const double* params, size_t n_layers, double* out_nu);
+/* Problem 4.5 by the dynamic program of App. D in O(M L) time: verifier k (budget beta[k]) takes no layers or one
+ * contiguous interval [out_start[k], out_end[k]] (0-based, inclusive; -1, -1 for none) of cost at most beta[k],
+ * intervals disjoint and in the order of the verifiers; out_value = total benefit.  The recursion also lets a
+ * verifier stay idle (DP[k-1, i]), which the printed one omits.  nu >= 0, phi > 0, beta >= 0 (TC_ERR_RANGE). */
+int tc_select_layers(size_t n_layers, const double* nu, const double* phi, size_t n_verifiers, const double* beta,
+                     double* out_value, int64_t* out_start, int64_t* out_end);
+
 #ifdef __cplusplus
 }
 #endif

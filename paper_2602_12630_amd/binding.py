@@ -106,6 +106,13 @@ def load_library(path=None):
         "tc_terkle_update": (ctypes.c_int, [vp, vp, u32p, u32p, ctypes.c_int64]),
         "tc_interpolate": (ctypes.c_int, [vp, ctypes.c_int, u32p, vp, ctypes.c_int, vp]),
         "tc_divide_by_linear": (ctypes.c_int, [vp, ctypes.c_int, u32p, vp, ctypes.c_int, ctypes.c_uint32, vp, vp]),
+        "tc_hill_alpha": (ctypes.c_int, [ctypes.POINTER(ctypes.c_double), ctypes.c_size_t, ctypes.c_size_t,
+                                         ctypes.POINTER(ctypes.c_double)]),
+        "tc_layer_benefits": (ctypes.c_int, [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), ctypes.c_size_t,
+                                             ctypes.POINTER(ctypes.c_double)]),
+        "tc_select_layers": (ctypes.c_int, [ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                            ctypes.c_size_t, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                            ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]),
         "tc_vkp_from_trapdoor": (ctypes.c_int, [u8p, ctypes.c_int, ctypes.POINTER(vp)]),
         "tc_vkp_destroy": (None, [vp]),
         "tc_vkp_get": (ctypes.c_int, [vp, ctypes.c_int, vp]),
@@ -120,6 +127,41 @@ def load_library(path=None):
     L._tc_signatures = sig
     _LIBS[path] = L
     return L
+
+
+def _f64(values):
+    values = [float(v) for v in values]
+    return (ctypes.c_double * max(len(values), 1))(*values)
+
+
+def hill_alpha(eigenvalues, chi, lib=None):
+    lib = lib or load_library()
+    out = ctypes.c_double()
+    rc = lib.tc_hill_alpha(_f64(eigenvalues), len(eigenvalues), chi, ctypes.byref(out))
+    if rc != TC_OK:
+        raise TcError(rc, "tc_hill_alpha")
+    return out.value
+
+
+def layer_benefits(alpha, params, lib=None):
+    lib = lib or load_library()
+    out = (ctypes.c_double * len(alpha))()
+    rc = lib.tc_layer_benefits(_f64(alpha), _f64(params), len(alpha), out)
+    if rc != TC_OK:
+        raise TcError(rc, "tc_layer_benefits")
+    return list(out)
+
+
+def select_layers(nu, phi, beta, lib=None):
+    """-> (value, [(start, end) or None per verifier])"""
+    lib = lib or load_library()
+    value = ctypes.c_double()
+    s = (ctypes.c_int64 * max(len(beta), 1))()
+    e = (ctypes.c_int64 * max(len(beta), 1))()
+    rc = lib.tc_select_layers(len(nu), _f64(nu), _f64(phi), len(beta), _f64(beta), ctypes.byref(value), s, e)
+    if rc != TC_OK:
+        raise TcError(rc, "tc_select_layers")
+    return value.value, [None if s[k] < 0 else (s[k], e[k]) for k in range(len(beta))]
 
 
 class PairingVerifier:

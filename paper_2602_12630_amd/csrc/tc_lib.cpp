@@ -16,6 +16,7 @@
 #include "../../include/tc.h"
 #include "kernels.h"
 #include "pairing.h"
+#include "selector.h"
 
 using namespace tc;
 
@@ -2019,4 +2020,27 @@ extern "C" int tc_verify_path_pairing(const tc_vkp* vkp, const tc_path* path, co
         }
     }
     return pairing_batch_check(vkp, B) ? TC_OK : TC_ERR_VERIFY;
+}
+
+/* ======================================================================================= */
+/* Layer selection: host only                                                              */
+/* ======================================================================================= */
+extern "C" int tc_hill_alpha(const double* eigenvalues, size_t d, size_t chi, double* out_alpha) {
+    return selector::hill_alpha(eigenvalues, d, chi, out_alpha) ? TC_OK : TC_ERR_ARG;
+}
+extern "C" int tc_layer_benefits(const double* alpha, const double* params, size_t n_layers, double* out_nu) {
+    if (!alpha || !params || !out_nu || !n_layers) return TC_ERR_ARG;
+    selector::benefits(alpha, params, n_layers, out_nu);
+    return TC_OK;
+}
+extern "C" int tc_select_layers(size_t n_layers, const double* nu, const double* phi, size_t n_verifiers, const double* beta,
+                                double* out_value, int64_t* out_start, int64_t* out_end) {
+    if (!nu || !phi || !beta || !out_value || !out_start || !out_end) return TC_ERR_ARG;
+    if (n_layers > 0x7FFFFFFEull) return TC_ERR_SHAPE;
+    for (size_t i = 0; i < n_layers; ++i)
+        if (!(nu[i] >= 0.0) || !(phi[i] > 0.0)) return TC_ERR_RANGE;
+    for (size_t k = 0; k < n_verifiers; ++k)
+        if (!(beta[k] >= 0.0)) return TC_ERR_RANGE;
+    *out_value = selector::select_layers(n_layers, nu, phi, n_verifiers, beta, out_start, out_end);
+    return TC_OK;
 }
