@@ -270,8 +270,8 @@ def c3_forward(ctx, T, torch, node_srs, tau, reps=3):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--lib", default=None, help="path of an alternative libtc.so (experiments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--openings", type=int, default=8)
@@ -432,6 +432,10 @@ def main():
     def deal(total):
         return [total // len(lanes) + (1 if i < total % len(lanes) else 0) for i in range(len(lanes))]
 
+    # priming, part of the untimed set-up: a fresh process on a fresh box needs more than a few steps before two
+    # lanes overlap fully (workspaces grow to their final size, code objects load, clocks and host threads settle)
+    PRIMING_STEPS = 12
+    run_steps([PRIMING_STEPS] * len(lanes))
     run_steps([args.warmup] * len(lanes))               # every lane warms up its own contexts
     torch.cuda.synchronize()
     # timed region: exactly `steps` steps, wall clock between two device synchronisations
@@ -492,7 +496,7 @@ def main():
                                "Terkle tree over 2^21 entries (139813 nodes) + %d path openings + verification" % args.openings,
                    "elements": n, "setup_s_untimed": setup_s,
                    "streams": "serial (one stream)" if args.serial else "flat commitment on a second stream, concurrent with tree build, openings and verification",
-                   "steps_in_flight": len(lanes)},
+                   "steps_in_flight": len(lanes), "priming_steps_per_lane_untimed": PRIMING_STEPS},
         "step_latency_ms": step_latency_ms,
         "phase_ms": phase_ms,
         "commit_only_elements_per_s": n / (commit_ms * 1e-3),
