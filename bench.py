@@ -278,7 +278,7 @@ def main():
     ap.add_argument("--no-c3", action="store_true", help="skip the LLaMA2-7B-shaped forward (second half of the metric)")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one plain copy kernel of 256 MiB "
                     "(reference dispatch for scaling the HBM byte counters of a rocprofv3 --pmc run)")
-    ap.add_argument("--in-flight", type=int, default=2, help="steps in flight: each has its own host thread, contexts, "
+    ap.add_argument("--in-flight", type=int, default=4, help="steps in flight: each has its own host thread, contexts, "
                     "streams and buffers; the K timed steps are dealt out to them (1 = one step after the other)")
     ap.add_argument("--fig4", action="store_true", help="also run the arity-64 tree-scaling workload (64^1 .. 64^4 leaves, "
                     "node shapes (8,8), (4,4,4), (64,)); needs about 12 GB of fixed-base tables")
