@@ -81,11 +81,15 @@ def pairing_constants():
     x3 = f2mul(f2mul(G2X, G2X), G2X)
     assert f2mul(G2Y, G2Y) == ((x3[0] + 4) % P_MOD, (x3[1] + 4) % P_MOD), "G2 generator is not on the twist"
     assert (P_MOD * P_MOD - 1) % 6 == 0
+    assert (P_MOD - 1) % 6 == 0
+    gamma1 = f2pow(xi, (P_MOD - 1) // 6)
     gamma = f2pow(xi, (P_MOD * P_MOD - 1) // 6)
     assert f2pow(gamma, 6) == (1, 0) and f2pow(gamma, 3) != (1, 0) and f2pow(gamma, 2) != (1, 0)
     assert (P_MOD**4 - P_MOD**2 + 1) % R_MOD == 0
     hard = (P_MOD**4 - P_MOD**2 + 1) // R_MOD
-    return gamma, hard
+    # three times the hard part splits over the curve parameter (checked here, used by the verifier)
+    assert 3 * hard == (Z - 1) ** 2 * (Z + P_MOD) * (Z * Z + P_MOD * P_MOD - 1) + 3
+    return gamma1, gamma, hard
 
 
 def limbs(x, n):
@@ -117,7 +121,7 @@ def main():
     here = os.path.dirname(os.path.abspath(__file__))
     Rp = 1 << 384
     LAM, BETA = endomorphism()
-    GAMMA, HARD = pairing_constants()
+    GAMMA1, GAMMA, HARD = pairing_constants()
     text = [
         "/* GENERATED by gen_constants.py -- do not edit.  BLS12-381 Montgomery constants,",
         " * 32-bit limbs, little-endian limb order.  Fp: R = 2^384; Fr: R = 2^256. */",
@@ -135,6 +139,8 @@ def main():
         "/* pairing (host side): G2 generator on the twist, Montgomery form, (c0, c1) of x then of y */",
         "static constexpr uint32_t G2_GEN[4][12] = {%s};"
         % ", ".join("{%s}" % limbs(v * Rp % P_MOD, 12) for v in (G2X[0], G2X[1], G2Y[0], G2Y[1])),
+        "/* (u + 1)^((p - 1) / 6), Montgomery form (c0, c1) */",
+        "static constexpr uint32_t FROB1_GAMMA[2][12] = {%s};" % ", ".join("{%s}" % limbs(v * Rp % P_MOD, 12) for v in GAMMA1),
         "/* (u + 1)^((p^2 - 1) / 6), Montgomery form (c0, c1) */",
         "static constexpr uint32_t FROB2_GAMMA[2][12] = {%s};" % ", ".join("{%s}" % limbs(v * Rp % P_MOD, 12) for v in GAMMA),
         "/* |z|, the loop length of the Miller function */",

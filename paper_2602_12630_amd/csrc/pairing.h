@@ -215,6 +215,42 @@ inline fp12 final_exponentiation(const fp12& f) {
     return r;
 }
 
+/* Three times the hard part splits over the curve parameter z:
+ *     3 (p^4 - p^2 + 1) / r = (z - 1)^2 (z + p) (z^2 + p^2 - 1) + 3,
+ * five powers by the 64-bit |z| and a few Frobenius maps instead of a 1268-bit power.  Since 3 does not divide
+ * r, the cube of the pairing value is 1 exactly when the value is: this is what the verifier computes.  After
+ * the easy part the element lies in the cyclotomic subgroup, where the inverse is the conjugate. */
+inline fp12 f12_frob1(const fp12& x) {     /* the p-power map: conjugate coefficients, times gamma1^k */
+    fp2 gamma{fp_from_mont(FROB1_GAMMA[0]), fp_from_mont(FROB1_GAMMA[1])};
+    fp12 r;
+    fp2 g = f2_one();
+    for (int k = 0; k < 6; ++k) {
+        fp2 cj{x.c[k].a, fp_neg(x.c[k].b)};
+        r.c[k] = k ? f2_mul(cj, g) : cj;
+        g = f2_mul(g, gamma);
+    }
+    return r;
+}
+inline fp12 cyclotomic_pow_z(const fp12& x) {      /* x^z for the negative curve parameter z */
+    fp12 r = x;
+    int top = 63;
+    while (!((BLS_Z_ABS >> top) & 1ull)) --top;
+    for (int i = top - 1; i >= 0; --i) {
+        r = f12_sqr(r);
+        if ((BLS_Z_ABS >> i) & 1ull) r = f12_mul(r, x);
+    }
+    return f12_conj(r);
+}
+inline fp12 final_exponentiation_cubed(const fp12& f) {
+    fp12 t = f12_mul(f12_conj(f), f12_inv(f));                   /* ^(p^6 - 1) */
+    t = f12_mul(f12_frob2(t), t);                                /* ^(p^2 + 1) */
+    fp12 a = f12_mul(cyclotomic_pow_z(t), f12_conj(t));          /* t^(z - 1) */
+    a = f12_mul(cyclotomic_pow_z(a), f12_conj(a));               /* t^((z - 1)^2) */
+    fp12 b = f12_mul(cyclotomic_pow_z(a), f12_frob1(a));         /* a^(z + p) */
+    fp12 c = f12_mul(f12_mul(cyclotomic_pow_z(cyclotomic_pow_z(b)), f12_frob2(b)), f12_conj(b));   /* b^(z^2 + p^2 - 1) */
+    return f12_mul(c, f12_mul(f12_sqr(t), t));
+}
+
 /* ---- G2, affine on the twist (identity: both coordinates zero) --------------------------- */
 struct g2_affine {
     fp2 x, y;
@@ -309,14 +345,19 @@ struct pair_t {
     g1_affine p;
     g2_affine q;
 };
-/* prod_i e(P_i, Q_i); pairs with an identity contribute 1 */
-inline fp12 pairing_product(const std::vector<pair_t>& pairs) {
+inline fp12 miller_product(const std::vector<pair_t>& pairs) {
     fp12 f = f12_one();
     for (const pair_t& pr : pairs) {
         if (affine_is_identity(pr.p) || g2_is_identity(pr.q)) continue;
         f = f12_mul(miller(pr.p, pr.q), f);
     }
-    return final_exponentiation(f);
+    return f;
+}
+/* prod_i e(P_i, Q_i); pairs with an identity contribute 1 */
+inline fp12 pairing_product(const std::vector<pair_t>& pairs) { return final_exponentiation(miller_product(pairs)); }
+/* whether prod_i e(P_i, Q_i) = 1, through the cube of the product */
+inline bool pairing_product_is_one(const std::vector<pair_t>& pairs) {
+    return f12_eq(final_exponentiation_cubed(miller_product(pairs)), f12_one());
 }
 /* 576 bytes: the twelve Fp coefficients of w^0 .. w^11 when u is written as w^6 - 1, 48 bytes little-endian each */
 inline void gt_to_bytes(const fp12& x, uint8_t out[576]) {

@@ -1972,7 +1972,7 @@ static bool pairing_batch_check(const tc_vkp* vkp, const PairingBatch& B) {
     std::vector<pairing::pair_t> pairs;
     pairs.push_back({xyzz_to_affine(B.h_term), pairing::g2_generator()});
     for (int i = 0; i < B.m_used; ++i) pairs.push_back({xyzz_to_affine(B.tau_term[i]), vkp->tau_h[i]});
-    return pairing::f12_eq(pairing::pairing_product(pairs), pairing::f12_one());
+    return pairing::pairing_product_is_one(pairs);
 }
 
 extern "C" int tc_verify_pairing(const tc_vkp* vkp, int m, const uint32_t* shape, const uint8_t commitment[96],

@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "../../paper_2602_12630_amd/csrc/kernels.h"
+#include "../../paper_2602_12630_amd/csrc/pairing.h"
 
 using namespace tc;
 
@@ -74,6 +75,25 @@ void hm_coop_reduce(const uint8_t* pts, uint32_t n, int spread, uint8_t* o) {
     for (int ph = 0; ph < K::PHASES; ++ph)
         for (uint32_t lane = 0; lane < (uint32_t)K::BLOCK; ++lane) k.phase(ph, lane, 0, lds.data());
     pt_store(o, xyzz_to_affine(r));
+}
+// the verifier's short final exponentiation against the plain one: must be its cube; also x^p, x^(p^2) by powers
+int hm_final_exponentiation_forms(const uint8_t* p, uint32_t k) {
+    using namespace tc::pairing;
+    uint32_t kk[1] = {k};
+    g2_affine q = g2_mul(kk, 32, g2_generator());
+    fp12 f = miller(pt_load(p), q);
+    fp12 e1 = final_exponentiation(f), e3 = final_exponentiation_cubed(f);
+    bool cube = f12_eq(f12_mul(f12_sqr(e1), e1), e3);
+    // Frobenius maps on an arbitrary element (the Miller value): compare with plain powers by p and p^2
+    fp12 xp = f12_one(), base = f;
+    for (int i = 0; i < 12 * 32; ++i) {                      // p, bit by bit from the limbs of the modulus
+        if ((FpParams::MOD[i >> 5] >> (i & 31)) & 1u) xp = f12_mul(xp, base);
+        base = f12_sqr(base);
+    }
+    bool frob1 = f12_eq(xp, f12_frob1(f));
+    bool frob2 = f12_eq(f12_frob1(f12_frob1(f)), f12_frob2(f));
+    bool inv = f12_eq(f12_mul(f, f12_inv(f)), f12_one());
+    return (cube ? 1 : 0) | (frob1 ? 2 : 0) | (frob2 ? 4 : 0) | (inv ? 8 : 0);
 }
 void hm_g1_generator(uint8_t* o) { pt_store(o, affine_generator()); }
 void hm_phi(const uint8_t* p, uint8_t* o) { fr_t v = phi_map(pt_load(p)); memcpy(o, v.l, 32); }

@@ -20,7 +20,7 @@ LIB = os.path.join(HERE, "hostmath", "libhostmath.so")
 
 @pytest.fixture(scope="module")
 def hm():
-    hdrs = [os.path.join(HERE, "..", "paper_2602_12630_amd", "csrc", h) for h in ("field.h", "g1.h", "constants.h", "kernels.h", "rt.h")]
+    hdrs = [os.path.join(HERE, "..", "paper_2602_12630_amd", "csrc", h) for h in ("field.h", "g1.h", "constants.h", "kernels.h", "rt.h", "pairing.h")]
     newest = max(os.path.getmtime(f) for f in [SRC] + hdrs)
     if not os.path.exists(LIB) or os.path.getmtime(LIB) < newest:
         subprocess.check_call(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-o", LIB, SRC])
@@ -149,6 +149,15 @@ def test_cooperative_reduction(hm):
             got = run(pts, spread)
             w = want(pts)
             assert (got is ec.INF and w is ec.INF) or got == w, (len(pts), spread)
+
+
+def test_pairing_building_blocks(hm):
+    """Inside the host pairing: the verifier's short final exponentiation is the cube of the plain one, the
+    p-power map equals the power by p, applying it twice equals the p^2-power map, inversion inverts."""
+    rng = random.Random(8)
+    for _ in range(2):
+        pt = ec.mul(rng.randrange(1, R), ec.G1)
+        assert hm.hm_final_exponentiation_forms(_pb(pt), rng.randrange(1, 1 << 32)) == 15
 
 
 def test_phi_map(hm):
