@@ -10,6 +10,7 @@
  */
 #pragma once
 #include <stdint.h>
+#include <string.h>
 
 #include "constants.h"
 
@@ -398,13 +399,59 @@ __device__ fp_t fp_mul(const fp_t& a, const fp_t& b);
 __device__ fp_t fp_sqr(const fp_t& a);
 __device__ fr_t fr_mul(const fr_t& a, const fr_t& b);
 #endif
+/* Host code multiplies in Fp on 64-bit limbs: the same Montgomery representation (R = 2^384; the bytes of an
+ * element are its little-endian value either way), about four times faster on a CPU than the 32-bit limbs that
+ * suit the GPU.  Used by everything the library computes on the host (set-up tables, the pairing verifier) and
+ * by the CPU builds of the kernels. */
+inline fp_t fp_mul_host64(const fp_t& a, const fp_t& b) {
+    typedef unsigned __int128 u128;
+    uint64_t q[6], x[6], y[6], t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int i = 0; i < 6; ++i) q[i] = (uint64_t)FpParams::MOD[2 * i] | ((uint64_t)FpParams::MOD[2 * i + 1] << 32);
+    uint64_t inv = 1;
+    for (int i = 0; i < 6; ++i) inv *= 2 - q[0] * inv;       /* Newton: q[0]^-1 mod 2^64 */
+    inv = 0 - inv;
+    memcpy(x, a.l, 48);
+    memcpy(y, b.l, 48);
+    for (int i = 0; i < 6; ++i) {
+        u128 c = 0;
+        for (int j = 0; j < 6; ++j) {
+            c += (u128)x[j] * y[i] + t[j];
+            t[j] = (uint64_t)c;
+            c >>= 64;
+        }
+        c += t[6];
+        t[6] = (uint64_t)c;
+        t[7] = (uint64_t)(c >> 64);
+        uint64_t m = t[0] * inv;
+        c = ((u128)m * q[0] + t[0]) >> 64;
+        for (int j = 1; j < 6; ++j) {
+            c += (u128)m * q[j] + t[j];
+            t[j - 1] = (uint64_t)c;
+            c >>= 64;
+        }
+        c += t[6];
+        t[5] = (uint64_t)c;
+        t[6] = t[7] + (uint64_t)(c >> 64);
+    }
+    uint64_t d[6];
+    u128 bw = 0;
+    for (int j = 0; j < 6; ++j) {                            /* t < 2 q: one conditional subtraction */
+        u128 s = (u128)t[j] - q[j] - (uint64_t)bw;
+        d[j] = (uint64_t)s;
+        bw = (s >> 64) & 1;
+    }
+    bool take = t[6] != 0 || bw == 0;
+    fp_t r;
+    memcpy(r.l, take ? d : t, 48);
+    return r;
+}
 #if defined(__HIPCC__)
-__host__ inline fp_t fp_mul(const fp_t& a, const fp_t& b) { return fe_mul<FpParams>(a, b); }
-__host__ inline fp_t fp_sqr(const fp_t& a) { return fe_mul<FpParams>(a, a); }
+__host__ inline fp_t fp_mul(const fp_t& a, const fp_t& b) { return fp_mul_host64(a, b); }
+__host__ inline fp_t fp_sqr(const fp_t& a) { return fp_mul_host64(a, a); }
 __host__ inline fr_t fr_mul(const fr_t& a, const fr_t& b) { return fe_mul<FrParams>(a, b); }
 #else
-inline fp_t fp_mul(const fp_t& a, const fp_t& b) { return fe_mul<FpParams>(a, b); }
-inline fp_t fp_sqr(const fp_t& a) { return fe_mul<FpParams>(a, a); }
+inline fp_t fp_mul(const fp_t& a, const fp_t& b) { return fp_mul_host64(a, b); }
+inline fp_t fp_sqr(const fp_t& a) { return fp_mul_host64(a, a); }
 inline fr_t fr_mul(const fr_t& a, const fr_t& b) { return fe_mul<FrParams>(a, b); }
 #endif
 /* overloads that pick the right product for generic helpers */

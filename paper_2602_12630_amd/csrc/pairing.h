@@ -31,56 +31,8 @@ inline fp_t fp_from_mont(const uint32_t* limbs) {     /* a constant stored in Mo
     return r;
 }
 
-/* Montgomery product on 64-bit limbs for the host (same R = 2^384, same representation as the 32-bit limbs of
- * the kernels: the bytes of an element are its little-endian value either way) */
-inline uint64_t fp_inv64() {
-    uint64_t p0 = (uint64_t)FpParams::MOD[0] | ((uint64_t)FpParams::MOD[1] << 32);
-    uint64_t x = 1;
-    for (int i = 0; i < 6; ++i) x *= 2 - p0 * x;      /* Newton: x = p0^-1 mod 2^64 */
-    return 0 - x;
-}
-inline fp_t pmul(const fp_t& a, const fp_t& b) {
-    typedef unsigned __int128 u128;
-    static const uint64_t inv = fp_inv64();
-    uint64_t x[6], y[6], q[6], t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    memcpy(x, a.l, 48);
-    memcpy(y, b.l, 48);
-    for (int i = 0; i < 6; ++i) q[i] = (uint64_t)FpParams::MOD[2 * i] | ((uint64_t)FpParams::MOD[2 * i + 1] << 32);
-    for (int i = 0; i < 6; ++i) {
-        u128 c = 0;
-        for (int j = 0; j < 6; ++j) {
-            c += (u128)x[j] * y[i] + t[j];
-            t[j] = (uint64_t)c;
-            c >>= 64;
-        }
-        c += t[6];
-        t[6] = (uint64_t)c;
-        t[7] = (uint64_t)(c >> 64);
-        uint64_t m = t[0] * inv;
-        c = ((u128)m * q[0] + t[0]) >> 64;
-        for (int j = 1; j < 6; ++j) {
-            c += (u128)m * q[j] + t[j];
-            t[j - 1] = (uint64_t)c;
-            c >>= 64;
-        }
-        c += t[6];
-        t[5] = (uint64_t)c;
-        t[6] = t[7] + (uint64_t)(c >> 64);
-    }
-    /* t < 2 q: one conditional subtraction */
-    uint64_t d[6];
-    u128 bw = 0;
-    for (int j = 0; j < 6; ++j) {
-        u128 s = (u128)t[j] - q[j] - (uint64_t)bw;
-        d[j] = (uint64_t)s;
-        bw = (s >> 64) & 1;
-    }
-    bool take = t[6] != 0 || bw == 0;
-    fp_t r;
-    memcpy(r.l, take ? d : t, 48);
-    return r;
-}
-inline fp_t psqr(const fp_t& a) { return pmul(a, a); }
+inline fp_t pmul(const fp_t& a, const fp_t& b) { return fp_mul_host64(a, b); }
+inline fp_t psqr(const fp_t& a) { return fp_mul_host64(a, a); }
 
 /* ---- Fp2 ------------------------------------------------------------------------------- */
 struct fp2 {

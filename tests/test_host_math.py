@@ -43,7 +43,8 @@ def test_fp_fr_arithmetic(hm):
     vals = edge_p + [rng.randrange(P) for _ in range(60)]
     for a in vals:
         for b in edge_p + [rng.randrange(P) for _ in range(4)]:
-            assert _call2(hm.hm_fp_mul, a, b, 48) == a * b % P
+            assert _call2(hm.hm_fp_mul, a, b, 48) == a * b % P                   # 64-bit limbs (host code)
+            assert _call2(hm.hm_fp_mul_limbs32, a, b, 48) == a * b % P           # the 32-bit-limb form of the kernels
             assert _call2(hm.hm_fp_add, a, b, 48) == (a + b) % P
             assert _call2(hm.hm_fp_sub, a, b, 48) == (a - b) % P
     edge_r = [0, 1, 2, R - 1, R - 2, (1 << 254), 0xFFFFFFFF]
