@@ -275,6 +275,13 @@ int tc_verify_pairing(const tc_vkp* vkp, int m, const uint32_t* shape, const uin
 int tc_verify_path_pairing(const tc_vkp* vkp, const tc_path* path, const uint8_t root[96],
                            const uint8_t leaf_value[32], const void* proof, size_t proof_len);
 
+/* Many paths at once, arguments as tc_verify_paths_batch: the equations of all well-formed paths are combined
+ * (random weights again) into one check, their G1 arithmetic spread over up to 16 host threads; only when that
+ * check fails are the paths verified one by one to find the wrong ones.  results[i] = TC_OK or TC_ERR_VERIFY. */
+int tc_verify_paths_pairing_batch(const tc_vkp* vkp, int count, const tc_path* paths, const uint8_t* roots,
+                                  const uint8_t* leaf_values, const void* proofs, size_t proof_stride,
+                                  const size_t* proof_len, int* results);
+
 /* ---- layer selection (CPU only; the verifier's policy, Sec. 4.3) --------------------------------
  * float64; no context, no GPU. */
 

@@ -119,6 +119,9 @@ def load_library(path=None):
         "tc_pairing": (ctypes.c_int, [u8p, u8p, vp]),
         "tc_verify_pairing": (ctypes.c_int, [vp, ctypes.c_int, u32p, u8p, u32p, u8p, u8p]),
         "tc_verify_path_pairing": (ctypes.c_int, [vp, ctypes.POINTER(tc_path), u8p, u8p, vp, ctypes.c_size_t]),
+        "tc_verify_paths_pairing_batch": (ctypes.c_int, [vp, ctypes.c_int, ctypes.POINTER(tc_path), u8p, u8p, vp,
+                                                         ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t),
+                                                         ctypes.POINTER(ctypes.c_int)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)              # AttributeError here = the library does not export a declared symbol
@@ -206,6 +209,19 @@ class PairingVerifier:
         if rc != TC_OK:
             raise TcError(rc, "tc_verify_path_pairing")
         return True
+
+    def verify_paths(self, paths, roots, leaf_values, proofs):
+        n = len(paths)
+        stride = max([len(p) for p in proofs] + [1])
+        buf = b"".join(p + bytes(stride - len(p)) for p in proofs)
+        lens = (ctypes.c_size_t * max(n, 1))(*[len(p) for p in proofs])
+        arr = (tc_path * max(n, 1))(*paths)
+        res = (ctypes.c_int * max(n, 1))()
+        rc = self.lib.tc_verify_paths_pairing_batch(self.handle, n, arr, b"".join(roots), b"".join(leaf_values), buf,
+                                                    stride, lens, res)
+        if rc != TC_OK:
+            raise TcError(rc, "tc_verify_paths_pairing_batch")
+        return [res[i] == TC_OK for i in range(n)]
 
     def close(self):
         if self.handle:

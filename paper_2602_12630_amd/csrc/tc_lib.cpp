@@ -10,6 +10,7 @@
 #include <new>
 #include <random>
 #include <string>
+#include <thread>
 #include <memory>
 #include <vector>
 
@@ -1986,40 +1987,101 @@ extern "C" int tc_verify_pairing(const tc_vkp* vkp, int m, const uint32_t* shape
     return pairing_batch_check(vkp, B) ? TC_OK : TC_ERR_VERIFY;
 }
 
-extern "C" int tc_verify_path_pairing(const tc_vkp* vkp, const tc_path* path, const uint8_t root[96],
-                                      const uint8_t leaf_value[32], const void* proof, size_t proof_len) {
-    if (!vkp || !path || !root || !leaf_value || !proof) return TC_ERR_ARG;
-    const tc_path& p = *path;
-    if (p.n_steps < 1 || p.n_steps > TC_MAX_STEPS) return TC_ERR_VERIFY;
+/* the structural checks and phi links of one path; its openings go into B.  false = reject */
+static bool pairing_path_add(const tc_vkp* vkp, PairingBatch* B, const tc_path& p, const uint8_t* root,
+                             const uint8_t* leaf_value, const uint8_t* proof, size_t proof_len) {
+    if (p.n_steps < 1 || p.n_steps > TC_MAX_STEPS) return false;
     size_t expect = 0;
     for (int s = 0; s < p.n_steps; ++s) {
-        if (p.m[s] < 1 || p.m[s] > vkp->m || !shape_ok(p.m[s], p.shape[s], nullptr)) return TC_ERR_VERIFY;
+        if (p.m[s] < 1 || p.m[s] > vkp->m || !shape_ok(p.m[s], p.shape[s], nullptr)) return false;
         for (int j = 0; j < p.m[s]; ++j)
-            if (p.kappa[s][j] >= p.shape[s][j]) return TC_ERR_VERIFY;
+            if (p.kappa[s][j] >= p.shape[s][j]) return false;
         expect += 96 * (size_t)p.m[s] + 32 + (s + 1 < p.n_steps ? 96 : 0);
     }
-    if (expect != proof_len) return TC_ERR_VERIFY;
-    const uint8_t* src = (const uint8_t*)proof;
+    if (expect != proof_len) return false;
+    const uint8_t* src = proof;
     const uint8_t* carried = root;
-    PairingBatch B;
     for (int s = 0; s < p.n_steps; ++s) {
         const uint8_t* pi = src;
         const uint8_t* y = src + 96 * (size_t)p.m[s];
         src = y + 32;
-        if (!pairing_batch_add(&B, p.m[s], carried, p.kappa[s], y, pi)) return TC_ERR_VERIFY;
+        if (!pairing_batch_add(B, p.m[s], carried, p.kappa[s], y, pi)) return false;
         if (s + 1 < p.n_steps) {
             /* the opened value is phi of the commitment carried to the next step */
             g1_affine child;
-            if (!g1_from_bytes_checked(src, &child)) return TC_ERR_VERIFY;
+            if (!g1_from_bytes_checked(src, &child)) return false;
             fr_t v = phi_map(child);
-            if (memcmp(v.l, y, 32) != 0) return TC_ERR_VERIFY;
+            if (memcmp(v.l, y, 32) != 0) return false;
             carried = src;
             src += 96;
         } else if (memcmp(y, leaf_value, 32) != 0) {
-            return TC_ERR_VERIFY;
+            return false;
         }
     }
+    return true;
+}
+
+extern "C" int tc_verify_path_pairing(const tc_vkp* vkp, const tc_path* path, const uint8_t root[96],
+                                      const uint8_t leaf_value[32], const void* proof, size_t proof_len) {
+    if (!vkp || !path || !root || !leaf_value || !proof) return TC_ERR_ARG;
+    PairingBatch B;
+    if (!pairing_path_add(vkp, &B, *path, root, leaf_value, (const uint8_t*)proof, proof_len)) return TC_ERR_VERIFY;
     return pairing_batch_check(vkp, B) ? TC_OK : TC_ERR_VERIFY;
+}
+
+extern "C" int tc_verify_paths_pairing_batch(const tc_vkp* vkp, int count, const tc_path* paths, const uint8_t* roots,
+                                             const uint8_t* leaf_values, const void* proofs, size_t proof_stride,
+                                             const size_t* proof_len, int* results) {
+    if (!vkp || count < 0 || (count && (!paths || !roots || !leaf_values || !proofs || !proof_len || !results))) return TC_ERR_ARG;
+    if (!count) return TC_OK;
+    /* the G1 work of the paths is spread over host threads, one running equation per thread */
+    unsigned nthreads = std::min<unsigned>(std::max(1u, std::thread::hardware_concurrency()), 16u);
+    nthreads = std::min<unsigned>(nthreads, (unsigned)count);
+    std::vector<PairingBatch> part(nthreads);
+    std::vector<uint8_t> structural(count, 0);
+    auto work = [&](unsigned t) {
+        for (int i = (int)t; i < count; i += (int)nthreads) {
+            PairingBatch mine;                       /* a malformed path must not poison the thread's equation */
+            bool ok = pairing_path_add(vkp, &mine, paths[i], roots + 96 * (size_t)i, leaf_values + 32 * (size_t)i,
+                                       (const uint8_t*)proofs + (size_t)i * proof_stride, proof_len[i]);
+            structural[i] = ok ? 1 : 0;
+            if (!ok) continue;
+            PairingBatch& P = part[t];
+            bool unit = P.count == 0;
+            uint32_t rho[4] = {1, 0, 0, 0};
+            if (!unit)
+                for (int j = 0; j < 4; ++j) rho[j] = (uint32_t)P.rng();
+            P.h_term = xyzz_add(P.h_term, weigh(mine.h_term, rho, unit));
+            for (int j = 0; j < mine.m_used; ++j) P.tau_term[j] = xyzz_add(P.tau_term[j], weigh(mine.tau_term[j], rho, unit));
+            P.m_used = std::max(P.m_used, mine.m_used);
+            ++P.count;
+        }
+    };
+    std::vector<std::thread> pool;
+    for (unsigned t = 1; t < nthreads; ++t) pool.emplace_back(work, t);
+    work(0);
+    for (auto& th : pool) th.join();
+    PairingBatch all;
+    for (unsigned t = 0; t < nthreads; ++t) {
+        if (!part[t].count) continue;
+        bool unit = all.count == 0;
+        uint32_t rho[4] = {1, 0, 0, 0};
+        if (!unit)
+            for (int j = 0; j < 4; ++j) rho[j] = (uint32_t)all.rng();
+        all.h_term = xyzz_add(all.h_term, weigh(part[t].h_term, rho, unit));
+        for (int j = 0; j < part[t].m_used; ++j) all.tau_term[j] = xyzz_add(all.tau_term[j], weigh(part[t].tau_term[j], rho, unit));
+        all.m_used = std::max(all.m_used, part[t].m_used);
+        ++all.count;
+    }
+    bool all_good = all.count == 0 || pairing_batch_check(vkp, all);
+    for (int i = 0; i < count; ++i) {
+        if (!structural[i]) { results[i] = TC_ERR_VERIFY; continue; }
+        if (all_good) { results[i] = TC_OK; continue; }
+        /* something in the batch is wrong: find out which paths, one by one */
+        results[i] = tc_verify_path_pairing(vkp, paths + i, roots + 96 * (size_t)i, leaf_values + 32 * (size_t)i,
+                                            (const uint8_t*)proofs + (size_t)i * proof_stride, proof_len[i]);
+    }
+    return TC_OK;
 }
 
 /* ======================================================================================= */

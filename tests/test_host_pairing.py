@@ -118,6 +118,24 @@ def test_paths_of_an_entries_tree(lib, verifier):
         flipped = bytearray(proof)
         flipped[len(proof) // 2] ^= 1
         assert not verifier.verify_path(path, root, value, bytes(flipped))
+    # all paths in one batch; then with one wrong value: only that path is rejected
+    leaves = [(0, 0), (4, 5), (2, 3), (1, 4), (3, 0)]
+    proofs = [serialize_steps(terkle.open_path(pps, tree, grid, node, l)) for l in leaves]
+    paths = [make_path(lib, grid, node, T.TC_LEAF_ENTRIES, l) for l in leaves]
+    values = [ec.fr_to_bytes(int(payload[l]) % R) for l in leaves]
+    assert verifier.verify_paths(paths, [root] * 5, values, proofs) == [True] * 5
+    bad_values = list(values)
+    bad_values[3] = ec.fr_to_bytes((int(payload[leaves[3]]) + 1) % R)
+    assert verifier.verify_paths(paths, [root] * 5, bad_values, proofs) == [True, True, True, False, True]
+    tampered = list(proofs)
+    t1 = bytearray(proofs[1])
+    t1[10] ^= 2                                   # a proof element off the curve
+    tampered[1] = bytes(t1)
+    moved = bytearray(proofs[4])
+    moved[0:96] = ec.g1_to_bytes(ec.G1)           # a proof element on the curve but wrong
+    tampered[4] = bytes(moved)
+    assert verifier.verify_paths(paths, [root] * 5, values, tampered) == [True, False, True, True, False]
+    assert verifier.verify_paths([], [], [], []) == []
     wrong = make_path(lib, grid, node, T.TC_LEAF_ENTRIES, (1, 1))
     assert not verifier.verify_path(wrong, root, ec.fr_to_bytes(int(payload[2, 3]) % R), proof)
 
