@@ -679,3 +679,33 @@ def test_arity_64_trees(T, ctx, node, grid):
     finally:
         tree.close()
         srs.close()
+
+
+def test_verification_in_chunks(T, ctx, node_srs):
+    """More steps than one pass of the verifier holds (4096): 1400 paths of 3 steps through a (64, 64) entries tree,
+    a few of them with a wrong value or a damaged proof; the verdicts must come out per path, in order."""
+    grid, node = (64, 64), tc_inputs.NODE_SHAPE
+    X = tc_inputs.int16_uniform(grid, 21)
+    tree = ctx.terkle_build_entries(node_srs, to_device(X), T.TC_I16, grid, node)
+    try:
+        otree = terkle.build(pps, tc.as_flat_ints(X), grid, node)
+        assert tree.root == ec.g1_to_bytes(otree.root)
+        rng = np.random.default_rng(22)
+        leaves = [(int(a), int(b)) for a, b in rng.integers(0, 64, size=(1400, 2))]
+        proofs = tree.open_batch(leaves)
+        for i in (0, 699, 1399):
+            assert proofs[i] == serialize_steps(terkle.open_path(pps, otree, grid, node, leaves[i]))
+        paths = [tree.path(l) for l in leaves]
+        values = [ec.fr_to_bytes(int(X[l]) % R) for l in leaves]
+        want = [True] * len(leaves)
+        for i in (3, 1365, 1366, 1399):                     # the last ones fall into the second pass
+            values[i] = ec.fr_to_bytes((int(X[leaves[i]]) + 1) % R)
+            want[i] = False
+        damaged = bytearray(proofs[1370])
+        damaged[100] ^= 1
+        proofs[1370] = bytes(damaged)
+        want[1370] = False
+        vk = ctx.vk_from_trapdoor(TAU_BYTES)
+        assert ctx.verify_paths_batch(vk, paths, [tree.root] * len(leaves), values, proofs) == want
+    finally:
+        tree.close()
