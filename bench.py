@@ -234,6 +234,8 @@ def c3_forward(ctx, T, torch, node_srs, tau, reps=3):
     inners = [tuple(int(rng.integers(0, d)) for d in shapes3[l[1]]) for l in leaves]
     vk = ctx.vk_from_trapdoor(tau)
     open_ms = verify_ms = public_ms = None
+    ctx.profile_read(T.binding.TC_PROF_BUCKET_ACC)      # drop what the C2 steps left
+    ctx.profile(True)
     for rep in range(reps + 1):
         t0 = time.perf_counter()
         for x, qv, inv in zip(xs, qs, invs):
@@ -242,6 +244,8 @@ def c3_forward(ctx, T, torch, node_srs, tau, reps=3):
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         if rep == reps:
+            acc_ms, acc_launches = ctx.profile_read(T.binding.TC_PROF_BUCKET_ACC)    # the builds only
+            ctx.profile(False)
             # the configuration's 64 random openings down to tensor entries, then their verification
             t1 = time.perf_counter()
             proofs = tree.open_batch(leaves, inners)
@@ -265,9 +269,15 @@ def c3_forward(ctx, T, torch, node_srs, tau, reps=3):
             times.append(dt * 1e3)
     for s in srs_by_shape.values():
         s.close()
+    nonzero = sum(int(torch.count_nonzero(q).item()) for q in qs)
+    acc_kernel_ms = acc_ms / max(acc_launches, 1)
+    achieved = nonzero * FP_MULS_PER_MIXED_ADD * MADS_PER_FP_MUL / (acc_kernel_ms * 1e-3)
     times.sort()
     ms = times[len(times) // 2]
-    return {"ms": ms, "elements": total, "elements_per_s": total / (ms * 1e-3), "tensors": len(xs), "reps": reps,
+    return {"ms": ms, "roofline": {"bound": "alu", "kernel": "AccAffine (all 96 leaf commitments in one launch)",
+                                   "kernel_ms": acc_kernel_ms, "launches": acc_launches, "mixed_additions_per_launch": nonzero,
+                                   "achieved": achieved / 1e12, "peak": PEAK_MADS_PER_S / 1e12, "frac": achieved / PEAK_MADS_PER_S,
+                                   "unit": "T 32x32->64 multiply-add/s"}, "elements": total, "elements_per_s": total / (ms * 1e-3), "tensors": len(xs), "reps": reps,
             "open_64_paths_ms": open_ms, "verify_64_paths_ms": verify_ms,
             "public_verify_64_paths_host_ms": public_ms,
             "workload": "C3: 96 whole-tensor leaves (314 572 800 int16 entries) + 11 upper nodes; then 64 random "
