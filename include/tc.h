@@ -6,6 +6,10 @@
  * Com) -> Terkle Tree of commitments (Sec. 4, Terkle Tree definition) ->
  * openings (Def. 4.1, Open; Terkle membership proof) -> path verification
  * (Def. 4.1, Ver in its sum form, checked with the trapdoor; Terkle verification).
+ * Beyond that path, further down in this header: incremental updates of a tree, the
+ * coefficient route of Def. 4.1 as printed (interpolation, Algorithm 1), and two parts
+ * that run on the host only, as the paper's verifier has no GPU: verification with the
+ * pairing and the layer selection of Sec. 4.3.
  *
  * Conventions
  *   - Every function returns TC_OK (0) or a negative TC_ERR_* code; nothing
