@@ -208,6 +208,23 @@ def test_encode_matches_oracle_quantisation(T, ctx):
         got = dst.cpu().numpy()
         finite = np.isfinite(x.reshape(-1))
         assert np.array_equal(got[finite], want[finite])
+    # buffers that are not 16-byte aligned take the element-wise kernel: same values
+    inv = float(quantize.inv_scale_for(x[np.isfinite(x)]))
+    src = torch.empty(x.size + 1, dtype=torch.int16, device="cuda")
+    src[1:] = to_device(x.view(np.int16)).reshape(-1)
+    dst = torch.empty(x.size + 3, dtype=torch.int16, device="cuda")
+    ctx.encode_tensor(src[1:], T.TC_F16, x.size, inv, dst[3:])
+    ctx.sync()
+    want = quantize.quantize_f16(np.where(np.isfinite(x), x, np.float16(0)), np.float32(inv)).reshape(-1)
+    finite = np.isfinite(x.reshape(-1))
+    assert np.array_equal(dst[3:].cpu().numpy()[finite], want[finite])
+    # pass-through copies of integer tensors, ragged lengths
+    for n, dt, code in ((1000003, np.int8, T.TC_I8), (77, np.int8, T.TC_I8), (500009, np.int16, T.TC_I16), (5, np.int16, T.TC_I16)):
+        v = np.random.default_rng(n).integers(-100, 100, size=n).astype(dt)
+        out = torch.empty(n, dtype=torch.int8 if dt == np.int8 else torch.int16, device="cuda")
+        ctx.encode_tensor(to_device(v), code, n, 1.0, out)
+        ctx.sync()
+        assert np.array_equal(out.cpu().numpy(), v)
     half = np.array([0.25, 0.75, 1.25, -0.25, -0.75], np.float16)
     dst = torch.empty(5, dtype=torch.int16, device="cuda")
     ctx.encode_tensor(to_device(half.view(np.int16)), T.TC_F16, 5, 2.0, dst)
