@@ -1047,9 +1047,10 @@ struct NodeCommitFr {
         out[t] = acc;
     }
 };
-/* upper levels, arity a power of two <= 64: a workgroup is one wave; a lane commits FB_W >> logH consecutive
- * windows of one child (B << logH <= 64 lanes per node, 64 / (B << logH) nodes per wave), then the partial
- * sums of a node are added pairwise through LDS.  logH = 0 (one lane per child) does the least work in
+/* upper levels, arity a power of two <= 64: a lane commits FB_W >> logH consecutive windows of one child
+ * (B << logH <= 64 lanes per node, BLOCK / (B << logH) nodes per workgroup), then the partial sums of a node are
+ * added pairwise through LDS.  Large levels take four waves per workgroup, so that most waves skip the later
+ * halving steps; small ones a single wave.  logH = 0 (one lane per child) does the least work in
  * total; a level of few nodes is bound by the depth of one lane's work instead and takes logH > 0. */
 template <int BLOCK>
 struct NodeCommitFrCoop {
@@ -1090,12 +1091,21 @@ struct NodeCommitFrCoop {
             buf[lane] = acc;
             return;
         }
+        /* pairwise sums, the active lanes packed to the front of the workgroup: whole waves drop out as the
+         * number of additions halves */
+        uint32_t per_node = 1u << logL;
         if (ph <= logL) {
-            uint32_t stride = 1u << (ph - 1);
-            if ((r & (2 * stride - 1)) == 0) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
+            uint32_t half = per_node >> ph;
+            if (lane < ((uint32_t)BLOCK >> ph)) {
+                uint32_t at = (lane / half) * per_node + lane % half;
+                buf[at] = xyzz_add(buf[at], buf[at + half]);
+            }
             return;
         }
-        if (ph == logL + 1 && r == 0 && a < n_nodes) out[a] = buf[lane];
+        if (ph == logL + 1 && lane < (uint32_t)BLOCK / per_node) {
+            uint64_t node = (uint64_t)wg * (BLOCK / per_node) + lane;
+            if (node < n_nodes) out[node] = buf[lane * per_node];
+        }
     }
 };
 /* levels of very few nodes: a node is the sum of its B * FB_W (child, window) table points */

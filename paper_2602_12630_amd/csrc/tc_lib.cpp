@@ -1331,8 +1331,12 @@ extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** 
                         uint64_t lanes = lv.n << (logB + logH);
                         rt::event_t e0, e1;
                         prof_begin(ctx, TC_PROF_NODE_COMMIT_UPPER, &e0, &e1);
-                        e = launch_coop<64>((uint32_t)((lanes + 63) / 64), ctx->stream,
-                                            NodeCommitFrCoop<64>{g, t->levels[L - 1].phi, ns->fb[0], lv.n, logB, logH, acc});
+                        if (logH == 0)      /* a level large enough to fill the chip: throughput counts */
+                            e = launch_coop<256>((uint32_t)((lanes + 255) / 256), ctx->stream,
+                                                 NodeCommitFrCoop<256>{g, t->levels[L - 1].phi, ns->fb[0], lv.n, logB, logH, acc});
+                        else
+                            e = launch_coop<64>((uint32_t)((lanes + 63) / 64), ctx->stream,
+                                                NodeCommitFrCoop<64>{g, t->levels[L - 1].phi, ns->fb[0], lv.n, logB, logH, acc});
                         prof_end(ctx, TC_PROF_NODE_COMMIT_UPPER, e0, e1);
                     } else {
                         g1_xyzz* part = ws_array<g1_xyzz>(ctx, lv.n * t->B);

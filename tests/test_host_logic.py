@@ -413,3 +413,21 @@ def test_emulated_incremental_update(emu, node_srs):
         tree.close()
         for s in srs:
             s.close()
+
+
+def test_emulated_tree_with_a_large_upper_level(emu, node_srs):
+    """A level of more than 512 nodes above the bottom takes the four-wave node kernel with packed halving steps."""
+    node, grid = (2, 2), (96, 100)
+    X = tc_inputs.int8_uniform(grid, 5)
+    tree = emu.terkle_build_entries(node_srs, X, T.TC_I8, grid, node)
+    try:
+        ot = terkle.build(pps, tc.as_flat_ints(X), grid, node)
+        g1, n1 = tree.level_info(1)
+        assert n1 > 512
+        for L in (1, 2):
+            g, n = tree.level_info(L)
+            for i in list(range(0, n, 37)) + [n - 1]:
+                assert tree.node(L, i) == ec.g1_to_bytes(ot.levels[L]["C"][tc.multi_index(i, g)]), (L, i)
+        assert tree.root == ec.g1_to_bytes(ot.root)
+    finally:
+        tree.close()
