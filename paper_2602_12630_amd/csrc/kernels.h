@@ -1318,6 +1318,23 @@ struct KappaRowDirect {        /* lane t: q[kap, t] = -(1/beta_kap) sum_{k != ka
         for (int i = 0; i < 8; ++i) q[t].l[i] = plain.l[i];
     }
 };
+/* Many small jobs of one kind in one launch: job j owns the lanes first[j] .. first[j + 1] and runs its own
+ * functor on them (the openings of a batch each have their own axes, positions and buffers). */
+template <class F>
+struct JobList {
+    const F* jobs;
+    const uint64_t* first;     /* njobs + 1 */
+    uint32_t njobs;
+    TC_DEV void operator()(uint32_t lane) const {
+        uint32_t lo = 0, hi = njobs;
+        while (hi - lo > 1) {
+            uint32_t mid = (lo + hi) / 2;
+            if (first[mid] <= lane) lo = mid;
+            else hi = mid;
+        }
+        jobs[lo]((uint32_t)(lane - first[lo]));
+    }
+};
 struct FillIdentity {
     g1_xyzz* out;
     TC_DEV void operator()(uint32_t t) const { out[t] = xyzz_identity(); }

@@ -867,6 +867,23 @@ struct OpenSpec {
  * that their window combinations (a chain of ~250 doublings each) proceed side by side.  Leading axes of
  * large small-integer tensors first go by rows: R_k = sum_t (T[k,t] - T[kap,t]) S[k,t] for every row
  * k != kap, two 9-bit digits per entry, all rows of all openings in shared launches. */
+/* one launch for a list of jobs of the same kind (lanes[j] lanes for job j) */
+template <int BLOCK, class F>
+static int launch_jobs(tc_ctx* ctx, const std::vector<F>& jobs, const std::vector<uint64_t>& lanes) {
+    if (jobs.empty()) return TC_OK;
+    std::vector<uint64_t> first(jobs.size() + 1, 0);
+    for (size_t j = 0; j < jobs.size(); ++j) first[j + 1] = first[j] + lanes[j];
+    if (first.back() > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "too many openings in one batch");
+    if (!first.back()) return TC_OK;
+    F* d_jobs = (F*)ws_alloc(ctx, sizeof(F) * jobs.size());
+    uint64_t* d_first = ws_array<uint64_t>(ctx, first.size());
+    if (!d_jobs || !d_first) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed");
+    RT(rt::memcpy_h2d(d_jobs, jobs.data(), sizeof(F) * jobs.size(), ctx->stream));
+    RT(rt::memcpy_h2d(d_first, first.data(), sizeof(uint64_t) * first.size(), ctx->stream));
+    RT(rt::launch<BLOCK>(first.back(), ctx->stream, JobList<F>{d_jobs, d_first, (uint32_t)jobs.size()}));
+    return TC_OK;
+}
+
 static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xyzz* pi, fr_plain* y) {
     struct AxisJob {
         int open, axis;
@@ -919,8 +936,15 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
         TRY(msm_engine_list(ctx, (int)row_prob.size(), row_prob.data(), row_dtype.data(), Rk));
         TRY(normalize(ctx, Rk, row_prob.size(), RkA));
     }
-    /* full-width problems */
+    /* full-width problems; the scalar work of all openings goes into six job lists, one launch each */
     std::vector<MsmProblem> fr_prob;
+    std::vector<RowWeights> j_rw;
+    std::vector<KappaWeights> j_kw;
+    std::vector<KappaRowDirect> j_krd;
+    std::vector<QuotientRows> j_qr;
+    std::vector<QuotientKappaPartial> j_qkp;
+    std::vector<QuotientKappaRow> j_qkr;
+    std::vector<uint64_t> n_rw, n_kw, n_krd, n_qr, n_qkp, n_qkr;
     for (auto& J : jobs) {
         const tc_srs* srs = spec[J.open].srs;
         const void* sc = spec[J.open].scalars;
@@ -931,9 +955,12 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
             WS(ck, fr_plain, rows);
             WS(wk, fr_t, J.d);
             WS(qk, fr_plain, J.inner);
-            RT(rt::launch<64>(rows, ctx->stream, RowWeights{srs->ax[J.axis], J.kap, ck}));
-            RT(rt::launch<64>(J.d, ctx->stream, KappaWeights{srs->ax[J.axis], J.kap, wk}));
-            RT(rt::launch<64>(J.inner, ctx->stream, KappaRowDirect{sc, dt, J.offset, J.d, J.kap, J.inner, srs->ax[J.axis], wk, qk}));
+            j_rw.push_back(RowWeights{srs->ax[J.axis], J.kap, ck});
+            n_rw.push_back(rows);
+            j_kw.push_back(KappaWeights{srs->ax[J.axis], J.kap, wk});
+            n_kw.push_back(J.d);
+            j_krd.push_back(KappaRowDirect{sc, dt, J.offset, J.d, J.kap, J.inner, srs->ax[J.axis], wk, qk});
+            n_krd.push_back(J.inner);
             MsmProblem A, B;
             A.pts = RkA + J.row0; A.scalars = ck; A.n = rows;
             B.pts = srs->pts[J.axis] + (uint64_t)J.kap * J.inner; B.scalars = qk; B.n = J.inner;
@@ -944,14 +971,23 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
             uint32_t chunks = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(64, 8192 / std::max<uint64_t>(J.inner, 1)));
             chunks = std::min<uint32_t>(chunks, J.d);
             WS(part, fr_t, (uint64_t)chunks * J.inner);
-            RT(rt::launch<128>(J.na, ctx->stream, QuotientRows{sc, dt, J.offset, J.d, J.kap, J.inner, srs->ax[J.axis], q}));
-            RT(rt::launch<128>((uint64_t)chunks * J.inner, ctx->stream, QuotientKappaPartial{J.d, J.kap, chunks, J.inner, srs->ax[J.axis], q, part}));
-            RT(rt::launch<128>(J.inner, ctx->stream, QuotientKappaRow{J.kap, chunks, J.inner, srs->ax[J.axis], part, q}));
+            j_qr.push_back(QuotientRows{sc, dt, J.offset, J.d, J.kap, J.inner, srs->ax[J.axis], q});
+            n_qr.push_back(J.na);
+            j_qkp.push_back(QuotientKappaPartial{J.d, J.kap, chunks, J.inner, srs->ax[J.axis], q, part});
+            n_qkp.push_back((uint64_t)chunks * J.inner);
+            j_qkr.push_back(QuotientKappaRow{J.kap, chunks, J.inner, srs->ax[J.axis], part, q});
+            n_qkr.push_back(J.inner);
             MsmProblem A;
             A.pts = srs->pts[J.axis]; A.scalars = q; A.n = J.na;
             fr_prob.push_back(A);
         }
     }
+    TRY((launch_jobs<64>(ctx, j_rw, n_rw)));
+    TRY((launch_jobs<64>(ctx, j_kw, n_kw)));
+    TRY((launch_jobs<64>(ctx, j_krd, n_krd)));
+    TRY((launch_jobs<128>(ctx, j_qr, n_qr)));
+    TRY((launch_jobs<128>(ctx, j_qkp, n_qkp)));
+    TRY((launch_jobs<128>(ctx, j_qkr, n_qkr)));
     /* sort the full-width problems by window plan so that equal plans are neighbours and share launches */
     std::vector<int> order(fr_prob.size());
     for (size_t i = 0; i < order.size(); ++i) order[i] = (int)i;
