@@ -713,52 +713,48 @@ struct RowColFinish {
 /* sum_k k B_k for a window of 256 buckets seen as a 16 x 16 matrix (k = 16 h + l + 1): row and column
  * sums first (one addition per bucket and direction), then two weighted sums over 16 elements:
  *     16 sum_h h R_h + sum_l (l + 1) C_l.
- * About 3 additions per bucket instead of the 16 of a weighted scan over all 256; one wave per window. */
+ * About 3 additions per bucket instead of the 16 of a weighted scan over all 256.  A wave takes two windows:
+ * 32 lanes each, 16 for the rows and 16 for the columns, so that no lane idles in the halving steps. */
 struct SmallWindowReduce256 {
     static constexpr int BLOCK = 64;
-    static constexpr int PHASES = 12;
+    static constexpr int PHASES = 11;
     static constexpr size_t LDS_BYTES = 2 * BLOCK * sizeof(g1_xyzz);
     const g1_xyzz* bucket;      /* windows * 256 */
+    uint32_t n_windows;
     g1_xyzz* out;               /* per window */
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         g1_xyzz* buf0 = (g1_xyzz*)lds;
         g1_xyzz* buf1 = buf0 + BLOCK;
-        const g1_xyzz* B = bucket + (uint64_t)wg * 256u;
-        uint32_t i = lane & 15u;
+        uint32_t win = lane >> 5, j = lane & 31u, i = lane & 15u;
+        uint32_t w = 2 * wg + win;
+        bool live = w < n_windows;
         if (ph == 0) {
-            uint32_t idx = (lane & 31u) >> 1, half = lane & 1u;
-            g1_xyzz acc;
-            if (lane < 32) {                 /* half a row */
-                const g1_xyzz* p = B + idx * 16u + half * 8u;
+            g1_xyzz acc = xyzz_identity();
+            if (live) {
+                const g1_xyzz* B = bucket + (uint64_t)w * 256u;
+                const g1_xyzz* p = j < 16 ? B + j * 16u : B + (j - 16u);      /* a row, or a column */
+                uint32_t step = j < 16 ? 1u : 16u;
                 acc = p[0];
-                for (int j = 1; j < 8; ++j) acc = xyzz_add(acc, p[j]);
-            } else {                         /* half a column */
-                const g1_xyzz* p = B + (half * 8u) * 16u + idx;
-                acc = p[0];
-                for (int j = 1; j < 8; ++j) acc = xyzz_add(acc, p[j * 16]);
+                for (uint32_t t = 1; t < 16; ++t) acc = xyzz_add(acc, p[t * step]);
             }
-            buf0[lane] = acc;
-        } else if (ph == 1) {
-            if ((lane & 1u) == 0) buf1[(lane < 32 ? 0u : 16u) + ((lane & 31u) >> 1)] = xyzz_add(buf0[lane], buf0[lane + 1]);
-        } else if (ph <= 5) {                /* suffix sums within each family of 16 */
-            int s = ph - 2;
+            buf1[lane] = acc;
+        } else if (ph <= 4) {                /* suffix sums within each family of 16 */
+            int s = ph - 1;
             g1_xyzz* cur = (s & 1) ? buf0 : buf1;
             g1_xyzz* nxt = (s & 1) ? buf1 : buf0;
             uint32_t stride = 1u << s;
-            if (lane < 32) {
-                g1_xyzz v = cur[lane];
-                if (i + stride < 16u) v = xyzz_add(v, cur[lane + stride]);
-                nxt[lane] = v;
-            }
-        } else if (ph == 6) {
-            if (lane == 0) buf0[32] = buf1[0];             /* S_R = sum of the row sums */
-        } else if (ph <= 10) {               /* sum of the suffix sums, in place */
-            uint32_t stride = 1u << (ph - 7);
-            if (lane < 32 && (i & (2 * stride - 1)) == 0) buf1[lane] = xyzz_add(buf1[lane], buf1[lane + stride]);
-        } else if (lane == 0) {
-            g1_xyzz t = xyzz_add(buf1[0], xyzz_neg(buf0[32]));   /* sum_h h R_h */
-            for (int j = 0; j < 4; ++j) t = xyzz_dbl(t);
-            out[wg] = xyzz_add(t, buf1[16]);
+            g1_xyzz v = cur[lane];
+            if (i + stride < 16u) v = xyzz_add(v, cur[lane + stride]);
+            nxt[lane] = v;
+        } else if (ph == 5) {                /* the suffix sums are in buf1 again; S_R = sum of the row sums */
+            if (j == 0) buf0[lane] = buf1[lane];
+        } else if (ph <= 9) {                /* sum of the suffix sums, in place */
+            uint32_t stride = 1u << (ph - 6);
+            if ((i & (2 * stride - 1)) == 0) buf1[lane] = xyzz_add(buf1[lane], buf1[lane + stride]);
+        } else if (j == 0 && live) {
+            g1_xyzz t = xyzz_add(buf1[lane], xyzz_neg(buf0[lane]));   /* sum_h h R_h */
+            for (int d = 0; d < 4; ++d) t = xyzz_dbl(t);
+            out[w] = xyzz_add(t, buf1[lane + 16]);
         }
     }
 };
@@ -1339,11 +1335,12 @@ struct FillIdentity {
     g1_xyzz* out;
     TC_DEV void operator()(uint32_t t) const { out[t] = xyzz_identity(); }
 };
-struct AddTwo {
-    const g1_xyzz* a;
-    const g1_xyzz* b;
+/* out = res[a] (+ res[b] when b >= 0): where the proof elements of a batch of openings end up */
+struct CollectResult {
+    const g1_xyzz* res;
+    int32_t a, b;
     g1_xyzz* out;
-    TC_DEV void operator()(uint32_t t) const { out[t] = xyzz_add(a[t], b[t]); }
+    TC_DEV void operator()(uint32_t) const { *out = b >= 0 ? xyzz_add(res[a], res[b]) : res[a]; }
 };
 
 /* y = e(T[f]) as canonical bytes */

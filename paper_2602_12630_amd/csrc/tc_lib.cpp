@@ -641,7 +641,7 @@ static int scan_counts(tc_ctx* ctx, const uint32_t* cnt, uint32_t n, uint32_t L,
 static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb, g1_xyzz* wsum) {
     if (nb == 256 && W >= 512) {
         /* many small windows (row problems of openings): throughput matters, not depth */
-        RT((launch_coop<SmallWindowReduce256::BLOCK>((uint32_t)W, ctx->stream, SmallWindowReduce256{bucket, wsum})));
+        RT((launch_coop<SmallWindowReduce256::BLOCK>(((uint32_t)W + 1) / 2, ctx->stream, SmallWindowReduce256{bucket, (uint32_t)W, wsum})));
         return TC_OK;
     }
     if (nb == 128 || nb == 256) {
@@ -894,6 +894,7 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
         int fr0;            /* first full-width problem */
     };
     std::vector<AxisJob> jobs;
+    std::vector<FetchScalar> j_fetch;
     std::vector<MsmProblem> row_prob;
     std::vector<int> row_dtype;
     for (int o = 0; o < count; ++o) {
@@ -924,8 +925,9 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
             jobs.push_back(J);
             offset += (uint64_t)J.kap * J.inner;
         }
-        RT(rt::launch<64>(1, ctx->stream, FetchScalar{spec[o].scalars, spec[o].dtype, offset, y + o}));
+        j_fetch.push_back(FetchScalar{spec[o].scalars, spec[o].dtype, offset, y + o});
     }
+    TRY((launch_jobs<64>(ctx, j_fetch, std::vector<uint64_t>(j_fetch.size(), 1))));
     /* rows: all R_k of all openings */
     g1_xyzz* Rk = nullptr;
     g1_affine* RkA = nullptr;
@@ -996,15 +998,13 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
     std::vector<int> fr_dtype(fr_prob.size(), TC_FR);
     for (size_t i = 0; i < order.size(); ++i) sorted_prob[i] = fr_prob[order[i]];
     WS(res_sorted, g1_xyzz, fr_prob.size());
-    WS(res, g1_xyzz, fr_prob.size());
     TRY(msm_engine_list(ctx, (int)sorted_prob.size(), sorted_prob.data(), fr_dtype.data(), res_sorted));
-    for (size_t i = 0; i < order.size(); ++i)
-        RT(rt::memcpy_d2d(res + order[i], res_sorted + i, sizeof(g1_xyzz), ctx->stream));
-    for (auto& J : jobs) {
-        g1_xyzz* dst = pi + (size_t)J.open * 4 + J.axis;
-        if (J.by_rows) RT(rt::launch<64>(1, ctx->stream, AddTwo{res + J.fr0, res + J.fr0 + 1, dst}));
-        else RT(rt::memcpy_d2d(dst, res + J.fr0, sizeof(g1_xyzz), ctx->stream));
-    }
+    std::vector<int32_t> where(fr_prob.size());           /* problem -> its place in the sorted results */
+    for (size_t i = 0; i < order.size(); ++i) where[order[i]] = (int32_t)i;
+    std::vector<CollectResult> j_out;
+    for (auto& J : jobs)
+        j_out.push_back(CollectResult{res_sorted, where[J.fr0], J.by_rows ? where[J.fr0 + 1] : -1, pi + (size_t)J.open * 4 + J.axis});
+    TRY((launch_jobs<64>(ctx, j_out, std::vector<uint64_t>(j_out.size(), 1))));
     return TC_OK;
 }
 
