@@ -711,9 +711,9 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     /* lanes of the first pass: enough sub-runs to fill the machine, at most 64 entries each */
     const uint64_t target_lanes = 262144;
     uint32_t L1 = (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(4, (items + target_lanes - 1) / target_lanes));
-    /* not longer than the average bucket: with many lightly loaded buckets a long sub-run leaves the lanes of a
-     * wave with very different amounts of work */
-    L1 = (uint32_t)std::min<uint64_t>(L1, std::max<uint64_t>(4, (items + nbk - 1) / nbk));
+    /* not longer than half the average bucket load: longer sub-runs leave the lanes of a wave with very
+     * different amounts of work (measured: C3 build 75.5 -> 74.0 ms, 64 openings of C3 182 -> 152 ms) */
+    L1 = (uint32_t)std::min<uint64_t>(L1, std::max<uint64_t>(4, (items + 2 * (uint64_t)nbk - 1) / (2 * (uint64_t)nbk)));
     const uint32_t L2 = 16;
 
     uint32_t max_count = 0;        /* largest bucket: fixes how many shrinking passes are needed */
