@@ -665,6 +665,26 @@ static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb
     return TC_OK;
 }
 
+/* one launch for a list of jobs of the same kind (lanes[j] lanes for job j) */
+template <int BLOCK, class F>
+static int launch_jobs(tc_ctx* ctx, const std::vector<F>& jobs, const std::vector<uint64_t>& lanes) {
+    if (jobs.empty()) return TC_OK;
+    std::vector<uint64_t> first(jobs.size() + 1, 0);
+    for (size_t j = 0; j < jobs.size(); ++j) first[j + 1] = first[j] + lanes[j];
+    if (first.back() > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "too many openings in one batch");
+    if (!first.back()) return TC_OK;
+    F* d_jobs = (F*)ws_alloc(ctx, sizeof(F) * jobs.size());
+    uint64_t* d_first = ws_array<uint64_t>(ctx, first.size());
+    if (!d_jobs || !d_first) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed");
+    RT(rt::memcpy_h2d(d_jobs, jobs.data(), sizeof(F) * jobs.size(), ctx->stream));
+    RT(rt::memcpy_h2d(d_first, first.data(), sizeof(uint64_t) * first.size(), ctx->stream));
+    RT(rt::launch<BLOCK>(first.back(), ctx->stream, JobList<F>{d_jobs, d_first, (uint32_t)jobs.size()}));
+    return TC_OK;
+}
+
+/* lanes of the bucket accumulation that are resident at once: 256 compute units x 4 SIMDs x 3 waves x 64 */
+static const uint64_t ACC_RESIDENT_LANES = 256ull * 4 * 3 * 64;
+
 /* One MSM problem: result = sum_i [e(s_i)] pts[i] over n terms */
 struct MsmProblem {
     const g1_affine* pts;
@@ -708,11 +728,15 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     for (int p = 0; p < count; ++p) h_tables[p] = prob[p].pts;
     RT(rt::memcpy_h2d(tables, h_tables.data(), sizeof(void*) * (size_t)count, ctx->stream));
 
-    /* lanes of the first pass: enough sub-runs to fill the machine, at most 64 entries each */
-    const uint64_t target_lanes = 262144;
+    /* Lanes of the first pass: sub-runs of at most L1 entries, about twice as many as the chip holds at once
+     * (the accumulation kernel keeps 3 waves per SIMD), so that the second round evens out what the first left
+     * uneven; at least 4 and at most 64 entries each.  Measured on the 2^21-entry int16 tensor: the kernel itself
+     * is fastest with the shortest sub-runs (the first entry of a sub-run is a copy, not an addition), the later
+     * passes with the longest, and steps in flight run equally fast from 4 to 13.  Not longer than half the
+     * average bucket load either: longer sub-runs leave the lanes of a wave with very different amounts of work
+     * (measured on openings of the LLaMA2-7B-shaped forward: 64 of them 182 -> 152 ms). */
+    const uint64_t target_lanes = 2 * ACC_RESIDENT_LANES;
     uint32_t L1 = (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(4, (items + target_lanes - 1) / target_lanes));
-    /* not longer than half the average bucket load: longer sub-runs leave the lanes of a wave with very
-     * different amounts of work (measured: C3 build 75.5 -> 74.0 ms, 64 openings of C3 182 -> 152 ms) */
     L1 = (uint32_t)std::min<uint64_t>(L1, std::max<uint64_t>(4, (items + 2 * (uint64_t)nbk - 1) / (2 * (uint64_t)nbk)));
     const uint32_t L2 = 16;
 
@@ -743,13 +767,20 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         else RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<32768>{d_prob, dtype, W, c, n_wg, M, start, sorted})));
     } else {
         RT(rt::launch<256>(nbk, ctx->stream, Fill32{cnt, 0u}));
-        for (int p = 0; p < count; ++p)
-            RT(rt::launch<256>(prob[p].n, ctx->stream, MsmCount{prob[p].scalars, dtype, W, c, nb, cnt + (size_t)p * nbk_pp}));
+        std::vector<MsmCount> j_count;
+        std::vector<MsmScatter> j_scatter;
+        std::vector<uint64_t> n_items;
+        for (int p = 0; p < count; ++p) {
+            j_count.push_back(MsmCount{prob[p].scalars, dtype, W, c, nb, cnt + (size_t)p * nbk_pp});
+            j_scatter.push_back(MsmScatter{prob[p].scalars, dtype, W, c, nb, start + (size_t)p * nbk_pp, cursor + (size_t)p * nbk_pp, sorted});
+            n_items.push_back(prob[p].n);
+        }
+        if (count == 1) RT(rt::launch<256>(prob[0].n, ctx->stream, j_count[0]));
+        else TRY((launch_jobs<256>(ctx, j_count, n_items)));
         TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, cursor, tot_a, tot_b, tot_max));
         RT(rt::memcpy_d2h(&max_count, tot_max + nchunks, 4, ctx->stream));
-        for (int p = 0; p < count; ++p)
-            RT(rt::launch<256>(prob[p].n, ctx->stream,
-                               MsmScatter{prob[p].scalars, dtype, W, c, nb, start + (size_t)p * nbk_pp, cursor + (size_t)p * nbk_pp, sorted}));
+        if (count == 1) RT(rt::launch<256>(prob[0].n, ctx->stream, j_scatter[0]));
+        else TRY((launch_jobs<256>(ctx, j_scatter, n_items)));
     }
 
     uint64_t max_part = items / L1 + nbk + 1;          /* upper bound on first-pass lanes */
@@ -870,23 +901,6 @@ struct OpenSpec {
  * that their window combinations (a chain of ~250 doublings each) proceed side by side.  Leading axes of
  * large small-integer tensors first go by rows: R_k = sum_t (T[k,t] - T[kap,t]) S[k,t] for every row
  * k != kap, two 9-bit digits per entry, all rows of all openings in shared launches. */
-/* one launch for a list of jobs of the same kind (lanes[j] lanes for job j) */
-template <int BLOCK, class F>
-static int launch_jobs(tc_ctx* ctx, const std::vector<F>& jobs, const std::vector<uint64_t>& lanes) {
-    if (jobs.empty()) return TC_OK;
-    std::vector<uint64_t> first(jobs.size() + 1, 0);
-    for (size_t j = 0; j < jobs.size(); ++j) first[j + 1] = first[j] + lanes[j];
-    if (first.back() > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "too many openings in one batch");
-    if (!first.back()) return TC_OK;
-    F* d_jobs = (F*)ws_alloc(ctx, sizeof(F) * jobs.size());
-    uint64_t* d_first = ws_array<uint64_t>(ctx, first.size());
-    if (!d_jobs || !d_first) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed");
-    RT(rt::memcpy_h2d(d_jobs, jobs.data(), sizeof(F) * jobs.size(), ctx->stream));
-    RT(rt::memcpy_h2d(d_first, first.data(), sizeof(uint64_t) * first.size(), ctx->stream));
-    RT(rt::launch<BLOCK>(first.back(), ctx->stream, JobList<F>{d_jobs, d_first, (uint32_t)jobs.size()}));
-    return TC_OK;
-}
-
 static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xyzz* pi, fr_plain* y) {
     struct AxisJob {
         int open, axis;
