@@ -341,6 +341,102 @@ __device__ __forceinline__ Fe<P> fe_sqr_dev(const Fe<P>& a) {
     r.l[N - 1] = (uint32_t)A.lo;
     return fe_reduce_once<P>(r, (uint32_t)(A.lo >> 32));
 }
+
+/* ---- Fp products on the FP64 pipe --------------------------------------------------------------
+ * gfx950 issues a double-precision fused multiply-add every cycle per lane, a 32 x 32 + 64 integer
+ * multiply-add every fourth.  An Fp element is therefore re-cut into 16 limbs of 24 bits held as
+ * doubles: a limb product is below 2^48, and a whole column of the product scan -- at most 16 terms
+ * a_i b_j (the top limbs of values below the modulus have 21 bits), 16 terms m_i p_j and the carry of
+ * the previous column -- stays below 2^53, so every fused multiply-add is exact in any rounding
+ * mode and needs no carry handling.  16 x 24 = 12 x 32 bits: the Montgomery radix is the same 2^384,
+ * and the result is bit for bit that of the integer routine. */
+template <int J>
+constexpr double fp_mod_limb24() {
+    /* bits 24 J .. 24 J + 23 of the modulus */
+    int bit = 24 * J, w = bit / 32, sh = bit % 32;
+    uint64_t v = (uint64_t)FpParams::MOD[w] >> sh;
+    if (sh > 8 && w + 1 < FpParams::N) v |= (uint64_t)FpParams::MOD[w + 1] << (32 - sh);
+    return (double)(uint32_t)(v & 0xFFFFFFu);
+}
+__device__ __forceinline__ void fp_to_limbs24(const fp_t& a, double (&x)[16]) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        uint32_t w0 = a.l[3 * g], w1 = a.l[3 * g + 1], w2 = a.l[3 * g + 2];
+        x[4 * g] = (double)(w0 & 0xFFFFFFu);
+        x[4 * g + 1] = (double)(__builtin_amdgcn_alignbit(w1, w0, 24) & 0xFFFFFFu);
+        x[4 * g + 2] = (double)(__builtin_amdgcn_alignbit(w2, w1, 16) & 0xFFFFFFu);
+        x[4 * g + 3] = (double)(w2 >> 8);
+    }
+}
+/* a b 2^-384 mod p from the limbs of a and b; `square` says that b is a (the cross terms are taken once, doubled) */
+template <bool SQUARE>
+__device__ __forceinline__ fp_t fp_mont_limbs24(const double (&a)[16], const double (&b)[16]) {
+    const double P24[16] = {fp_mod_limb24<0>(), fp_mod_limb24<1>(), fp_mod_limb24<2>(), fp_mod_limb24<3>(),
+                            fp_mod_limb24<4>(), fp_mod_limb24<5>(), fp_mod_limb24<6>(), fp_mod_limb24<7>(),
+                            fp_mod_limb24<8>(), fp_mod_limb24<9>(), fp_mod_limb24<10>(), fp_mod_limb24<11>(),
+                            fp_mod_limb24<12>(), fp_mod_limb24<13>(), fp_mod_limb24<14>(), fp_mod_limb24<15>()};
+    const double PINV = (double)(FpParams::INV & 0xFFFFFFu);       /* -p^-1 mod 2^24 */
+    const double DOWN = 0x1p-24, UP = 0x1p24;
+    double m[16];
+    double a2[16];
+    if (SQUARE) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) a2[i] = a[i] + a[i];
+    }
+    uint32_t r[16];
+    double carry = 0.0;
+#pragma unroll
+    for (int k = 0; k < 31; ++k) {
+        double S = carry;
+        const int lo = k < 16 ? 0 : k - 15, hi = k < 16 ? k : 15;
+        if (SQUARE) {
+#pragma unroll
+            for (int i = lo; i < k - i; ++i) S = __builtin_fma(a2[i], a[k - i], S);
+            if ((k & 1) == 0) S = __builtin_fma(a[k / 2], a[k / 2], S);
+        } else {
+#pragma unroll
+            for (int i = lo; i <= hi; ++i) S = __builtin_fma(a[i], b[k - i], S);
+        }
+        if (k < 16) {
+#pragma unroll
+            for (int i = 0; i < k; ++i) S = __builtin_fma(m[i], P24[k - i], S);
+            double t = __builtin_floor(S * DOWN);
+            double low = __builtin_fma(-t, UP, S);                 /* S mod 2^24 */
+            double q = low * PINV;
+            double tq = __builtin_floor(q * DOWN);
+            m[k] = __builtin_fma(-tq, UP, q);                      /* the multiple of p that clears the column's low limb */
+            S = __builtin_fma(m[k], P24[0], S);
+            carry = S * DOWN;
+        } else {
+#pragma unroll
+            for (int i = lo; i <= 15; ++i) S = __builtin_fma(m[i], P24[k - i], S);
+            double t = __builtin_floor(S * DOWN);
+            r[k - 16] = (uint32_t)__builtin_fma(-t, UP, S);
+            carry = t;
+        }
+    }
+    r[15] = (uint32_t)carry;
+    fp_t out;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        uint32_t l0 = r[4 * g], l1 = r[4 * g + 1], l2 = r[4 * g + 2], l3 = r[4 * g + 3];
+        out.l[3 * g] = l0 | (l1 << 24);
+        out.l[3 * g + 1] = (l1 >> 8) | (l2 << 16);
+        out.l[3 * g + 2] = (l2 >> 16) | (l3 << 8);
+    }
+    return fe_reduce_once<FpParams>(out, 0u);
+}
+__device__ __forceinline__ fp_t fp_mul_f64_dev(const fp_t& a, const fp_t& b) {
+    double x[16], y[16];
+    fp_to_limbs24(a, x);
+    fp_to_limbs24(b, y);
+    return fp_mont_limbs24<false>(x, y);
+}
+__device__ __forceinline__ fp_t fp_sqr_f64_dev(const fp_t& a) {
+    double x[16];
+    fp_to_limbs24(a, x);
+    return fp_mont_limbs24<true>(x, x);
+}
 #endif
 
 /* plain (non-Montgomery) comparison a > b on limbs */
@@ -393,11 +489,39 @@ __device__ __forceinline__ fr_t fr_mul(const fr_t& a, const fr_t& b) {
     return fr_mul_call(u32x4{a.l[0], a.l[1], a.l[2], a.l[3]}, u32x4{a.l[4], a.l[5], a.l[6], a.l[7]},
                        u32x4{b.l[0], b.l[1], b.l[2], b.l[3]}, u32x4{b.l[4], b.l[5], b.l[6], b.l[7]});
 }
+/* Products for kernels whose cost is depth, not volume: a wave that is alone on its SIMD finishes the FP64
+ * form sooner (measured per product: 1.75 us against 2.3 us; its multiply-adds do not wait for one another),
+ * while a chip full of waves gets through fewer of them a second (44 G against 53 G). */
+__device__ __attribute__((noinline)) fp_t fp_mul_lat_call(u32x4 a0, u32x4 a1, u32x4 a2, u32x4 b0, u32x4 b1, u32x4 b2) {
+    fp_t a, b;
+    a.l[0] = a0.x; a.l[1] = a0.y; a.l[2] = a0.z; a.l[3] = a0.w; a.l[4] = a1.x; a.l[5] = a1.y; a.l[6] = a1.z; a.l[7] = a1.w;
+    a.l[8] = a2.x; a.l[9] = a2.y; a.l[10] = a2.z; a.l[11] = a2.w;
+    b.l[0] = b0.x; b.l[1] = b0.y; b.l[2] = b0.z; b.l[3] = b0.w; b.l[4] = b1.x; b.l[5] = b1.y; b.l[6] = b1.z; b.l[7] = b1.w;
+    b.l[8] = b2.x; b.l[9] = b2.y; b.l[10] = b2.z; b.l[11] = b2.w;
+    return fp_mul_f64_dev(a, b);
+}
+__device__ __attribute__((noinline)) fp_t fp_sqr_lat_call(u32x4 a0, u32x4 a1, u32x4 a2) {
+    fp_t a;
+    a.l[0] = a0.x; a.l[1] = a0.y; a.l[2] = a0.z; a.l[3] = a0.w; a.l[4] = a1.x; a.l[5] = a1.y; a.l[6] = a1.z; a.l[7] = a1.w;
+    a.l[8] = a2.x; a.l[9] = a2.y; a.l[10] = a2.z; a.l[11] = a2.w;
+    return fp_sqr_f64_dev(a);
+}
+__device__ __forceinline__ fp_t fp_mul_lat(const fp_t& a, const fp_t& b) {
+    return fp_mul_lat_call(u32x4{a.l[0], a.l[1], a.l[2], a.l[3]}, u32x4{a.l[4], a.l[5], a.l[6], a.l[7]},
+                           u32x4{a.l[8], a.l[9], a.l[10], a.l[11]}, u32x4{b.l[0], b.l[1], b.l[2], b.l[3]},
+                           u32x4{b.l[4], b.l[5], b.l[6], b.l[7]}, u32x4{b.l[8], b.l[9], b.l[10], b.l[11]});
+}
+__device__ __forceinline__ fp_t fp_sqr_lat(const fp_t& a) {
+    return fp_sqr_lat_call(u32x4{a.l[0], a.l[1], a.l[2], a.l[3]}, u32x4{a.l[4], a.l[5], a.l[6], a.l[7]},
+                           u32x4{a.l[8], a.l[9], a.l[10], a.l[11]});
+}
 #elif defined(__HIPCC__)
 /* host pass of hipcc: the device bodies exist only in the device pass */
 __device__ fp_t fp_mul(const fp_t& a, const fp_t& b);
 __device__ fp_t fp_sqr(const fp_t& a);
 __device__ fr_t fr_mul(const fr_t& a, const fr_t& b);
+__device__ fp_t fp_mul_lat(const fp_t& a, const fp_t& b);
+__device__ fp_t fp_sqr_lat(const fp_t& a);
 #endif
 /* Host code multiplies in Fp on 64-bit limbs: the same Montgomery representation (R = 2^384; the bytes of an
  * element are its little-endian value either way), about four times faster on a CPU than the 32-bit limbs that
@@ -449,10 +573,14 @@ inline fp_t fp_mul_host64(const fp_t& a, const fp_t& b) {
 __host__ inline fp_t fp_mul(const fp_t& a, const fp_t& b) { return fp_mul_host64(a, b); }
 __host__ inline fp_t fp_sqr(const fp_t& a) { return fp_mul_host64(a, a); }
 __host__ inline fr_t fr_mul(const fr_t& a, const fr_t& b) { return fe_mul<FrParams>(a, b); }
+__host__ inline fp_t fp_mul_lat(const fp_t& a, const fp_t& b) { return fp_mul_host64(a, b); }
+__host__ inline fp_t fp_sqr_lat(const fp_t& a) { return fp_mul_host64(a, a); }
 #else
 inline fp_t fp_mul(const fp_t& a, const fp_t& b) { return fp_mul_host64(a, b); }
 inline fp_t fp_sqr(const fp_t& a) { return fp_mul_host64(a, a); }
 inline fr_t fr_mul(const fr_t& a, const fr_t& b) { return fe_mul<FrParams>(a, b); }
+inline fp_t fp_mul_lat(const fp_t& a, const fp_t& b) { return fp_mul_host64(a, b); }
+inline fp_t fp_sqr_lat(const fp_t& a) { return fp_mul_host64(a, a); }
 #endif
 /* overloads that pick the right product for generic helpers */
 TC_HD fp_t fe_mulx(const fp_t& a, const fp_t& b) { return fp_mul(a, b); }

@@ -1540,12 +1540,12 @@ struct VerifyChain {
         int level = (ph - 1) % 3;
         if (level == 0) {
             if (wave == 0) {
-                fp_t A = fp_sqr(ld(lds, FX, l));
+                fp_t A = fp_sqr_lat(ld(lds, FX, l));
                 st(lds, FE, l, fp_add(fp_dbl(A), A));
             } else if (wave == 1) {
-                st(lds, FB, l, fp_sqr(ld(lds, FY, l)));
+                st(lds, FB, l, fp_sqr_lat(ld(lds, FY, l)));
             } else {
-                fp_t Z3 = fp_dbl(fp_mul(ld(lds, FY, l), ld(lds, FZ, l)));
+                fp_t Z3 = fp_dbl(fp_mul_lat(ld(lds, FY, l), ld(lds, FZ, l)));
                 st(lds, FZ, l, Z3);
                 if (live) out[b].Z = Z3;
             }
@@ -1553,12 +1553,12 @@ struct VerifyChain {
         }
         if (level == 1) {
             if (wave == 0) {
-                st(lds, FF, l, fp_sqr(ld(lds, FE, l)));
+                st(lds, FF, l, fp_sqr_lat(ld(lds, FE, l)));
             } else if (wave == 1) {
-                fp_t C = fp_sqr(ld(lds, FB, l));
+                fp_t C = fp_sqr_lat(ld(lds, FB, l));
                 st(lds, FC8, l, fp_dbl(fp_dbl(fp_dbl(C))));
             } else {
-                fp_t XB = fp_mul(ld(lds, FX, l), ld(lds, FB, l));
+                fp_t XB = fp_mul_lat(ld(lds, FX, l), ld(lds, FB, l));
                 st(lds, FD, l, fp_dbl(fp_dbl(XB)));
             }
             return;
@@ -1566,7 +1566,7 @@ struct VerifyChain {
         if (wave == 0) {
             fp_t D = ld(lds, FD, l);
             fp_t X3 = fp_sub(fp_sub(ld(lds, FF, l), D), D);
-            fp_t Y3 = fp_sub(fp_mul(ld(lds, FE, l), fp_sub(D, X3)), ld(lds, FC8, l));
+            fp_t Y3 = fp_sub(fp_mul_lat(ld(lds, FE, l), fp_sub(D, X3)), ld(lds, FC8, l));
             st(lds, FX, l, X3);
             st(lds, FY, l, Y3);
             if (live) {
