@@ -42,7 +42,7 @@ PEAK_MADS_PER_S = 256 * 4 * 16 * 2.4e9 / 2
 R_MODULUS = 0x73EDA753299D7D483339D80809A1D80553BDA402FFFE5BFEFFFFFFFF00000001      # group order (embedding of negatives)
 # HBM bytes moved by one AccAffine launch at this workload (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # 256 MiB copy kernel; the runs and the scale factors are in profiles/c2_hbm_traffic_pmc.txt)
-ACC_AFFINE_TRAFFIC_BYTES = 4.911e8
+ACC_AFFINE_TRAFFIC_BYTES = 5.010e8
 
 
 def hip_event_timer():

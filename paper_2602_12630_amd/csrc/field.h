@@ -342,14 +342,18 @@ __device__ __forceinline__ Fe<P> fe_sqr_dev(const Fe<P>& a) {
     return fe_reduce_once<P>(r, (uint32_t)(A.lo >> 32));
 }
 
+#endif
+
 /* ---- Fp products on the FP64 pipe --------------------------------------------------------------
- * gfx950 issues a double-precision fused multiply-add every cycle per lane, a 32 x 32 + 64 integer
- * multiply-add every fourth.  An Fp element is therefore re-cut into 16 limbs of 24 bits held as
- * doubles: a limb product is below 2^48, and a whole column of the product scan -- at most 16 terms
- * a_i b_j (the top limbs of values below the modulus have 21 bits), 16 terms m_i p_j and the carry of
- * the previous column -- stays below 2^53, so every fused multiply-add is exact in any rounding
- * mode and needs no carry handling.  16 x 24 = 12 x 32 bits: the Montgomery radix is the same 2^384,
- * and the result is bit for bit that of the integer routine. */
+ * gfx950 issues double-precision fused multiply-adds at twice the rate of 32 x 32 + 64 integer multiply-adds,
+ * and they need no carry instructions.  An Fp element is re-cut into 16 limbs of 24 bits held as doubles: a
+ * limb product is below 2^48, and a whole column of the product scan -- at most 16 terms a_i b_j (the top
+ * limbs of values below the modulus have 21 bits), 16 terms m_i p_j and the carry of the previous column --
+ * stays below 2^53, so every fused multiply-add is exact in any rounding mode.  16 x 24 = 12 x 32 bits: the
+ * Montgomery radix is the same 2^384, and the result is bit for bit that of the integer routine.
+ * 512 multiply-adds replace 300 integer ones and their 300 carry additions: a full chip gets through fewer
+ * products a second this way (measured 44 G against 53 G), a wave alone on its SIMD finishes one sooner
+ * (1.75 us against 2.3 us), because the multiply-adds of a column do not wait for a carry. */
 template <int J>
 constexpr double fp_mod_limb24() {
     /* bits 24 J .. 24 J + 23 of the modulus */
@@ -358,19 +362,19 @@ constexpr double fp_mod_limb24() {
     if (sh > 8 && w + 1 < FpParams::N) v |= (uint64_t)FpParams::MOD[w + 1] << (32 - sh);
     return (double)(uint32_t)(v & 0xFFFFFFu);
 }
-__device__ __forceinline__ void fp_to_limbs24(const fp_t& a, double (&x)[16]) {
+TC_HD void fp_to_limbs24(const fp_t& a, double (&x)[16]) {
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         uint32_t w0 = a.l[3 * g], w1 = a.l[3 * g + 1], w2 = a.l[3 * g + 2];
         x[4 * g] = (double)(w0 & 0xFFFFFFu);
-        x[4 * g + 1] = (double)(__builtin_amdgcn_alignbit(w1, w0, 24) & 0xFFFFFFu);
-        x[4 * g + 2] = (double)(__builtin_amdgcn_alignbit(w2, w1, 16) & 0xFFFFFFu);
+        x[4 * g + 1] = (double)(((w0 >> 24) | (w1 << 8)) & 0xFFFFFFu);
+        x[4 * g + 2] = (double)(((w1 >> 16) | (w2 << 16)) & 0xFFFFFFu);
         x[4 * g + 3] = (double)(w2 >> 8);
     }
 }
 /* a b 2^-384 mod p from the limbs of a and b; `square` says that b is a (the cross terms are taken once, doubled) */
 template <bool SQUARE>
-__device__ __forceinline__ fp_t fp_mont_limbs24(const double (&a)[16], const double (&b)[16]) {
+TC_HD fp_t fp_mont_limbs24(const double (&a)[16], const double (&b)[16]) {
     const double P24[16] = {fp_mod_limb24<0>(), fp_mod_limb24<1>(), fp_mod_limb24<2>(), fp_mod_limb24<3>(),
                             fp_mod_limb24<4>(), fp_mod_limb24<5>(), fp_mod_limb24<6>(), fp_mod_limb24<7>(),
                             fp_mod_limb24<8>(), fp_mod_limb24<9>(), fp_mod_limb24<10>(), fp_mod_limb24<11>(),
@@ -426,18 +430,17 @@ __device__ __forceinline__ fp_t fp_mont_limbs24(const double (&a)[16], const dou
     }
     return fe_reduce_once<FpParams>(out, 0u);
 }
-__device__ __forceinline__ fp_t fp_mul_f64_dev(const fp_t& a, const fp_t& b) {
+TC_HD fp_t fp_mul_f64(const fp_t& a, const fp_t& b) {
     double x[16], y[16];
     fp_to_limbs24(a, x);
     fp_to_limbs24(b, y);
     return fp_mont_limbs24<false>(x, y);
 }
-__device__ __forceinline__ fp_t fp_sqr_f64_dev(const fp_t& a) {
+TC_HD fp_t fp_sqr_f64(const fp_t& a) {
     double x[16];
     fp_to_limbs24(a, x);
     return fp_mont_limbs24<true>(x, x);
 }
-#endif
 
 /* plain (non-Montgomery) comparison a > b on limbs */
 template <int N>
@@ -498,13 +501,13 @@ __device__ __attribute__((noinline)) fp_t fp_mul_lat_call(u32x4 a0, u32x4 a1, u3
     a.l[8] = a2.x; a.l[9] = a2.y; a.l[10] = a2.z; a.l[11] = a2.w;
     b.l[0] = b0.x; b.l[1] = b0.y; b.l[2] = b0.z; b.l[3] = b0.w; b.l[4] = b1.x; b.l[5] = b1.y; b.l[6] = b1.z; b.l[7] = b1.w;
     b.l[8] = b2.x; b.l[9] = b2.y; b.l[10] = b2.z; b.l[11] = b2.w;
-    return fp_mul_f64_dev(a, b);
+    return fp_mul_f64(a, b);
 }
 __device__ __attribute__((noinline)) fp_t fp_sqr_lat_call(u32x4 a0, u32x4 a1, u32x4 a2) {
     fp_t a;
     a.l[0] = a0.x; a.l[1] = a0.y; a.l[2] = a0.z; a.l[3] = a0.w; a.l[4] = a1.x; a.l[5] = a1.y; a.l[6] = a1.z; a.l[7] = a1.w;
     a.l[8] = a2.x; a.l[9] = a2.y; a.l[10] = a2.z; a.l[11] = a2.w;
-    return fp_sqr_f64_dev(a);
+    return fp_sqr_f64(a);
 }
 __device__ __forceinline__ fp_t fp_mul_lat(const fp_t& a, const fp_t& b) {
     return fp_mul_lat_call(u32x4{a.l[0], a.l[1], a.l[2], a.l[3]}, u32x4{a.l[4], a.l[5], a.l[6], a.l[7]},

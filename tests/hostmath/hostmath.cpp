@@ -21,6 +21,8 @@ static void pt_store(uint8_t* b, const g1_affine& p) { uint32_t w[24]; affine_to
 extern "C" {
 void hm_fp_mul(const uint8_t* a, const uint8_t* b, uint8_t* o) { fp_store(o, fp_mul(fp_load(a), fp_load(b))); }
 void hm_fp_mul_limbs32(const uint8_t* a, const uint8_t* b, uint8_t* o) { fp_store(o, fe_mul<FpParams>(fp_load(a), fp_load(b))); }
+void hm_fp_mul_f64(const uint8_t* a, const uint8_t* b, uint8_t* o) { fp_store(o, fp_mul_f64(fp_load(a), fp_load(b))); }
+void hm_fp_sqr_f64(const uint8_t* a, const uint8_t*, uint8_t* o) { fp_store(o, fp_sqr_f64(fp_load(a))); }
 void hm_fp_add(const uint8_t* a, const uint8_t* b, uint8_t* o) { fp_store(o, fp_add(fp_load(a), fp_load(b))); }
 void hm_fp_sub(const uint8_t* a, const uint8_t* b, uint8_t* o) { fp_store(o, fp_sub(fp_load(a), fp_load(b))); }
 void hm_fp_inv(const uint8_t* a, uint8_t* o) { fp_store(o, fe_inv_fermat<FpParams>(fp_load(a))); }

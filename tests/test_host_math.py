@@ -37,14 +37,34 @@ def _call2(fn, a, b, n):
     return int.from_bytes(bytes(out), "little")
 
 
+def test_fp64_product_columns_stay_exact():
+    """The FP64 form of the Fp product sums whole columns of 24-bit limb products in a double: the largest
+    column any two operands below the modulus can produce, with the reduction terms and the carry, must stay
+    below 2^53."""
+    top = P >> 360                                   # the 16th limb of an operand is at most that of the modulus
+    limb = (1 << 24) - 1
+    p24 = [(P >> (24 * j)) & limb for j in range(16)]
+    worst, carry = 0, 0
+    for k in range(31):
+        lo, hi = max(0, k - 15), min(k, 15)
+        ab = sum((top if i == 15 else limb) * (top if k - i == 15 else limb) for i in range(lo, hi + 1))
+        mp = sum(limb * p24[k - i] for i in range(lo, hi + 1))
+        column = ab + mp + carry
+        worst = max(worst, column)
+        carry = column >> 24
+    assert worst < 1 << 53
+
+
 def test_fp_fr_arithmetic(hm):
     rng = random.Random(1)
-    edge_p = [0, 1, 2, P - 1, P - 2, (P - 1) // 2, (1 << 380), 0xFFFFFFFF, (1 << 352) - 1]
+    edge_p = [0, 1, 2, P - 1, P - 2, (P - 1) // 2, (1 << 380), 0xFFFFFFFF, (1 << 352) - 1, (1 << 380) - 1]
     vals = edge_p + [rng.randrange(P) for _ in range(60)]
     for a in vals:
         for b in edge_p + [rng.randrange(P) for _ in range(4)]:
             assert _call2(hm.hm_fp_mul, a, b, 48) == a * b % P                   # 64-bit limbs (host code)
             assert _call2(hm.hm_fp_mul_limbs32, a, b, 48) == a * b % P           # the 32-bit-limb form of the kernels
+            assert _call2(hm.hm_fp_mul_f64, a, b, 48) == a * b % P               # 24-bit limbs in doubles (doubling chains)
+            assert _call2(hm.hm_fp_sqr_f64, a, b, 48) == a * a % P
             assert _call2(hm.hm_fp_add, a, b, 48) == (a + b) % P
             assert _call2(hm.hm_fp_sub, a, b, 48) == (a - b) % P
     edge_r = [0, 1, 2, R - 1, R - 2, (1 << 254), 0xFFFFFFFF]
