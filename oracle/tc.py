@@ -241,6 +241,103 @@ def interpolate(T, shape):
     return a
 
 
+# --- the three interpolation forms of App. C, one axis at a time ------------------------------
+# Each turns the d grid values of a line into the monomial coefficients (low degree first) of the
+# line's interpolant; `interpolate_form` applies one of them along every axis in turn.  They are
+# algorithms for the result that `interpolate` writes out from the definition.
+def _poly_times_linear(poly, root):
+    """poly(X) * (X - root)."""
+    out = [0] * (len(poly) + 1)
+    for e, c in enumerate(poly):
+        out[e + 1] = (out[e + 1] + c) % R
+        out[e] = (out[e] - c * root) % R
+    return out
+
+
+def line_newton(vals):
+    """Newton form: divided differences a_r = f[zeta_0..zeta_r], then sum_r a_r N_r(X) with
+    N_r(X) = prod_{t<r} (X - zeta_t), expanded into monomials."""
+    d = len(vals)
+    z = grid_nodes(d)
+    a = [v % R for v in vals]
+    for level in range(1, d):
+        for k in range(d - 1, level - 1, -1):
+            a[k] = (a[k] - a[k - 1]) * ec.fr_inv((z[k] - z[k - level]) % R) % R
+    coeffs = [0] * d
+    basis = [1]                                    # N_0
+    for r in range(d):
+        for e, c in enumerate(basis):
+            coeffs[e] = (coeffs[e] + a[r] * c) % R
+        basis = _poly_times_linear(basis, z[r])    # N_{r+1}
+    return coeffs
+
+
+def line_gregory(vals):
+    """Gregory (Newton-Gregory forward) form on the equispaced grid, h = 1: forward differences
+    Delta^r T[0], then sum_r binom(s, r) Delta^r T[0] with s = X - zeta_0, expanded into monomials."""
+    d = len(vals)
+    z = grid_nodes(d)
+    assert all(z[k + 1] - z[k] == 1 for k in range(d - 1))
+    diff = [v % R for v in vals]
+    delta = [diff[0]]
+    for _ in range(1, d):
+        diff = [(diff[k + 1] - diff[k]) % R for k in range(len(diff) - 1)]
+        delta.append(diff[0])
+    coeffs = [0] * d
+    binom = [1]                                    # binom(s, 0) as a polynomial in X
+    for r in range(d):
+        for e, c in enumerate(binom):
+            coeffs[e] = (coeffs[e] + delta[r] * c) % R
+        # binom(s, r+1) = binom(s, r) * (s - r) / (r + 1),  s - r = X - zeta_0 - r
+        binom = [c * ec.fr_inv(r + 1) % R for c in _poly_times_linear(binom, z[0] + r)]
+    return coeffs
+
+
+def line_barycentric(vals):
+    """Barycentric form: f(X) = M(X) sum_l beta_l T_l / (X - zeta_l) with M(X) = prod_r (X - zeta_r)
+    (the denominator sum_r beta_r / (X - zeta_r) of App. C equals 1 / M(X)); each M(X) / (X - zeta_l)
+    by synthetic division."""
+    d = len(vals)
+    z = grid_nodes(d)
+    beta = bary_weights(d)
+    master = [1]
+    for r in range(d):
+        master = _poly_times_linear(master, z[r])
+    coeffs = [0] * d
+    for l in range(d):
+        w = vals[l] % R * beta[l] % R
+        quotient = [0] * d                          # M(X) / (X - zeta_l), degree d - 1
+        carry = 0
+        for e in range(d, 0, -1):
+            carry = (master[e] + carry * z[l]) % R
+            quotient[e - 1] = carry
+        for e in range(d):
+            coeffs[e] = (coeffs[e] + w * quotient[e]) % R
+    return coeffs
+
+
+INTERPOLATION_FORMS = {"newton": line_newton, "gregory": line_gregory, "barycentric": line_barycentric}
+
+
+def interpolate_form(T, shape, form):
+    """Monomial coefficients of f_T through one of the forms of App. C, axis by axis."""
+    line = INTERPOLATION_FORMS[form]
+    shape = tuple(shape)
+    a = [embed(v) for v in as_flat_ints(T)]
+    st = strides(shape)
+    n = prod(shape)
+    for j, d in enumerate(shape):
+        out = [0] * n
+        for base in range(n):
+            if (base // st[j]) % d != 0:
+                continue
+            res = line([a[base + i * st[j]] for i in range(d)])
+            for e in range(d):
+                out[base + e * st[j]] = res[e]
+        a = out
+    return a
+
+
 def eval_poly(coeffs, shape, x):
     """f(x_1..x_m) from the lexicographic coefficient array."""
     total = 0

@@ -83,6 +83,21 @@ def test_brute_force_interpolation_and_commitment(shape):
     assert cbind.commit(pp, T, 2) == expect
 
 
+@pytest.mark.parametrize("shape", SHAPES + [(9,), (1,), (4, 1, 3)])
+@pytest.mark.parametrize("form", sorted(tc.INTERPOLATION_FORMS))
+def test_interpolation_forms_of_app_c(shape, form):
+    """Newton, Gregory and barycentric interpolation (App. C) are three ways to the same polynomial: each
+    must return the coefficients of the brute-force Vandermonde solve, and a textbook special case each."""
+    T = tc_inputs.int16_uniform(shape, 300 + len(shape))
+    assert tc.interpolate_form(T, shape, form) == brute_force_coeffs(T, shape)
+    line = tc.INTERPOLATION_FORMS[form]
+    # samples of X^2 on the nodes 1, 2, 3, 4: coefficients (0, 0, 1, 0); a constant line: (c, 0, 0)
+    assert line([1, 4, 9, 16]) == [0, 0, 1, 0]
+    assert line([7, 7, 7]) == [7, 0, 0]
+    # the line through (1, 3) and (2, 5) is 1 + 2 X
+    assert line([3, 5]) == [1, 2]
+
+
 def test_monomial_srs_is_the_setup_of_def_4_1():
     pp = tc.setup((2, 3), TAU)
     M = pp.srs_monomial()
