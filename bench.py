@@ -83,7 +83,8 @@ class Events:
 
 def coefficient_route(ctx, T, torch, with_oracle):
     """Interpolation to monomial coefficients (the first step of Com as Def. 4.1 prints it, bypassed by the hot
-    path): the sweep of Fig. 1, N = 2^12 samples reshaped to order-m grids, and the C2 activation; one Fr product
+    path): the sweep of Fig. 1, N = 2^12 samples reshaped to order-m grids, in Newton form (`gpu_ms`) and in the
+    Gregory and barycentric forms of App. C, and the C2 activation; one Fr product
     = 2 * 8^2 + 8 = 136 multiply-adds, an axis of length d costs 2 (d - 1) products per entry."""
     from oracle import tc as otc
 
@@ -100,6 +101,16 @@ def coefficient_route(ctx, T, torch, with_oracle):
             ctx.interpolate(shape, dx, T.TC_I16, coeffs)
         torch.cuda.synchronize()
         line = {"m": len(shape), "shape": list(shape), "gpu_ms": (time.perf_counter() - t0) * 1e3 / 3}
+        for form, name in ((T.TC_INTERP_GREGORY, "gregory"), (T.TC_INTERP_BARYCENTRIC, "barycentric")):
+            other = torch.empty_like(coeffs)
+            ctx.interpolate_form(shape, dx, T.TC_I16, form, other)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(3):
+                ctx.interpolate_form(shape, dx, T.TC_I16, form, other)
+            torch.cuda.synchronize()
+            line["gpu_ms_" + name] = (time.perf_counter() - t1) * 1e3 / 3
+            assert torch.equal(other, coeffs), (shape, name)
         if with_oracle and len(shape) >= 2:
             t1 = time.perf_counter()
             want = otc.interpolate(x, shape)

@@ -242,6 +242,17 @@ int tc_terkle_update(tc_ctx* ctx, tc_tree* tree, const uint32_t* leaf_index, con
  * expansion of the nested products).  m <= TC_MAX_INTERP_ORDER axes; the scalars as in tc_commit. */
 #define TC_MAX_INTERP_ORDER 12
 int tc_interpolate(tc_ctx* ctx, int m, const uint32_t* shape, const void* d_scalars, int dtype, void* d_coeffs);
+/* The same coefficients through one of the three interpolation forms of App. C, the comparison of Fig. 1:
+ * Newton (divided differences; what tc_interpolate uses), Gregory (forward differences Delta^k T[0] on the
+ * equispaced grid, weights binom(X - zeta_0, k)) or barycentric (weights beta_l, the interpolant assembled as
+ * sum_l beta_l T_l prod_(r != l) (X - zeta_r) node by node).  All three return the identical array; they differ
+ * in their steps and running time.  The barycentric form needs five Fr arrays of the tensor's size as
+ * workspace, the others three.  Unknown form: TC_ERR_ARG. */
+#define TC_INTERP_NEWTON 0
+#define TC_INTERP_GREGORY 1
+#define TC_INTERP_BARYCENTRIC 2
+int tc_interpolate_form(tc_ctx* ctx, int m, const uint32_t* shape, const void* d_scalars, int dtype, int form,
+                        void* d_coeffs);
 /* Algorithm 1 (App. A): f = q (x_axis - omega) + r with omega = kappa_axis + 1 and r free of x_axis, on the
  * coefficient arrays; d_quotient and d_remainder have the full shape (zeros at the top degree of the axis in q,
  * at every positive degree in r) and may not alias d_coeffs. */

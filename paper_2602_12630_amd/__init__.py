@@ -8,6 +8,9 @@ from .binding import (  # noqa: F401
     TC_FR,
     TC_I8,
     TC_I16,
+    TC_INTERP_BARYCENTRIC,
+    TC_INTERP_GREGORY,
+    TC_INTERP_NEWTON,
     TC_LEAF_ENTRIES,
     TC_LEAF_TENSORS,
     TC_OK,

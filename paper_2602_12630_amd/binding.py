@@ -11,6 +11,7 @@ TC_OK = 0
 TC_ERR_ARG, TC_ERR_SHAPE, TC_ERR_RANGE, TC_ERR_NOMEM, TC_ERR_HIP, TC_ERR_VERIFY, TC_ERR_STATE = -1, -2, -3, -4, -5, -6, -7
 TC_I8, TC_I16, TC_FR, TC_F16 = 1, 2, 3, 4
 TC_SRS_SUFFIX, TC_SRS_FIXED_BASE, TC_SRS_MONOMIAL = 1, 2, 4
+TC_INTERP_NEWTON, TC_INTERP_GREGORY, TC_INTERP_BARYCENTRIC = 0, 1, 2
 TC_LEAF_ENTRIES, TC_LEAF_TENSORS = 0, 1
 TC_PROF_BUCKET_ACC, TC_PROF_NODE_COMMIT, TC_PROF_NODE_COMMIT_UPPER, TC_PROF_VERIFY_CHAIN = 0, 1, 2, 3
 TC_MAX_ORDER, TC_MAX_STEPS = 4, 16
@@ -105,6 +106,7 @@ def load_library(path=None):
                                                  ctypes.POINTER(ctypes.c_int)]),
         "tc_terkle_update": (ctypes.c_int, [vp, vp, u32p, u32p, ctypes.c_int64]),
         "tc_interpolate": (ctypes.c_int, [vp, ctypes.c_int, u32p, vp, ctypes.c_int, vp]),
+        "tc_interpolate_form": (ctypes.c_int, [vp, ctypes.c_int, u32p, vp, ctypes.c_int, ctypes.c_int, vp]),
         "tc_divide_by_linear": (ctypes.c_int, [vp, ctypes.c_int, u32p, vp, ctypes.c_int, ctypes.c_uint32, vp, vp]),
         "tc_hill_alpha": (ctypes.c_int, [ctypes.POINTER(ctypes.c_double), ctypes.c_size_t, ctypes.c_size_t,
                                          ctypes.POINTER(ctypes.c_double)]),
@@ -394,6 +396,9 @@ class Context:
     # -- coefficient route -----------------------------------------------------------------------
     def interpolate(self, shape, scalars, dtype, coeffs_out):
         self._check(self.lib.tc_interpolate(self.handle, len(shape), _u32(shape), _ptr(scalars), dtype, _ptr(coeffs_out)))
+
+    def interpolate_form(self, shape, scalars, dtype, form, coeffs_out):
+        self._check(self.lib.tc_interpolate_form(self.handle, len(shape), _u32(shape), _ptr(scalars), dtype, form, _ptr(coeffs_out)))
 
     def divide_by_linear(self, shape, coeffs, axis, kappa_axis, quotient_out, remainder_out):
         self._check(self.lib.tc_divide_by_linear(self.handle, len(shape), _u32(shape), _ptr(coeffs), axis, kappa_axis,

@@ -1651,7 +1651,10 @@ struct PhiCanonical {
  *   phases d .. 2d-2      step s = phase - (d-1), k = d-1-s:  a <- a (x - zeta_k) + c_k, i.e.
  *                         a_i <- a_(i-1) - zeta_k a_i (+ c_k at i = 0), ping-pong between the two arrays
  *                         that do not hold c.
- * The host works out where c and the result end up (interp_result_buffer). */
+ * The host works out where c and the result end up (interp_result_buffer).
+ * Gregory form (inv_fact set): the levels take plain forward differences, c_k <- c_k - c_(k-1), so that
+ * c_k = Delta^k T[0], and the expansion reads c_k / k!, the coefficient of N_k in
+ * sum_k binom(X - zeta_0, k) Delta^k T[0] (h = 1). */
 struct InterpAxis {
     static constexpr int BLOCK = 1024;       /* a long line is bound by its 2d - 1 barriers: as many lanes as a workgroup has */
     static constexpr size_t LDS_BYTES = 16;
@@ -1660,6 +1663,11 @@ struct InterpAxis {
     uint32_t d, lines_per_wg;
     const fr_t* inv_int;       /* inv_int[l] = 1 / l, l = 1 .. d-1 */
     const fr_t* zeta;          /* zeta[k] = k + 1 */
+    const fr_t* inv_fact;      /* Gregory form (null for Newton): inv_fact[l] = 1 / l! */
+    TC_DEV fr_t newton_coefficient(const fr_t* c, uint64_t base, uint32_t k) const {
+        fr_t v = c[base + (uint64_t)k * inner];
+        return inv_fact ? fr_mul(v, inv_fact[k]) : v;
+    }
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t*) const {
         uint64_t lines = outer * inner;
         int cbuf = (int)((d - 1) & 1u);                  /* c after the d - 1 levels */
@@ -1674,16 +1682,19 @@ struct InterpAxis {
                 uint32_t l = (uint32_t)ph + 1;
                 const fr_t* src = buf[ph & 1];
                 fr_t v = src[at];
-                if (k >= l) v = fr_mul(fr_sub(v, src[at - inner]), inv_int[l]);
+                if (k >= l) {
+                    v = fr_sub(v, src[at - inner]);
+                    if (!inv_fact) v = fr_mul(v, inv_int[l]);
+                }
                 buf[(ph + 1) & 1][at] = v;
             } else if (ph + 1 == (int)d) {
-                buf[pa][at] = k == 0 ? buf[cbuf][base + (uint64_t)(d - 1) * inner] : fe_zero<FrParams>();
+                buf[pa][at] = k == 0 ? newton_coefficient(buf[cbuf], base, d - 1) : fe_zero<FrParams>();
             } else {
                 uint32_t s = (uint32_t)ph - (d - 1), kk = d - 1 - s;
                 const fr_t* old = buf[(s & 1u) ? pa : pb];
                 fr_t* nxt = buf[(s & 1u) ? pb : pa];
                 fr_t v = fr_neg(fr_mul(zeta[kk], old[at]));
-                v = fr_add(v, k ? old[at - inner] : buf[cbuf][base + (uint64_t)kk * inner]);
+                v = fr_add(v, k ? old[at - inner] : newton_coefficient(buf[cbuf], base, kk));
                 nxt[at] = v;
             }
         }
@@ -1695,6 +1706,50 @@ TC_HD int interp_result_buffer(uint32_t d) {
     int pa = cbuf == 0 ? 1 : 0, pb = 2;
     return ((d - 1) & 1u) ? pb : pa;
 }
+/* Barycentric form (App. C) of the same interpolation: f(X) = sum_l w_l prod_(r != l) (X - zeta_r) with
+ * w_l = beta_l T_l.  Built node by node: with M_n = prod_(r < n) (X - zeta_r) and P_n the sum restricted to the
+ * first n nodes, P_(n+1) = (X - zeta_n) P_n + w_n M_n and M_(n+1) = (X - zeta_n) M_n.  Lane = coefficient k of a
+ * line; phase 0 forms w (in place) and sets P_0 = 0, M_0 = 1; phase n + 1 takes step n, P and M each moving
+ * between two arrays.  After d steps the coefficients are in p[d & 1]. */
+struct InterpAxisBarycentric {
+    static constexpr int BLOCK = 1024;
+    static constexpr size_t LDS_BYTES = 16;
+    fr_t* w;                   /* the values on entry */
+    fr_t* p[2];
+    fr_t* mm[2];
+    uint64_t outer, inner;
+    uint32_t d, lines_per_wg;
+    const fr_t* beta;          /* beta[l] = 1 / prod_(r != l) (zeta_l - zeta_r) */
+    const fr_t* zeta;          /* zeta[k] = k + 1 */
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t*) const {
+        uint64_t lines = outer * inner;
+        for (uint64_t idx = lane; idx < (uint64_t)lines_per_wg * d; idx += BLOCK) {
+            uint64_t line = (uint64_t)wg * lines_per_wg + idx / d;
+            uint32_t k = (uint32_t)(idx % d);
+            if (line >= lines) continue;
+            uint64_t base = (line / inner) * d * inner + line % inner;
+            uint64_t at = base + (uint64_t)k * inner;
+            if (ph == 0) {
+                w[at] = fr_mul(w[at], beta[k]);
+                p[0][at] = fe_zero<FrParams>();
+                mm[0][at] = k == 0 ? fe_one<FrParams>() : fe_zero<FrParams>();
+                continue;
+            }
+            uint32_t n = (uint32_t)ph - 1;
+            const fr_t* po = p[n & 1u];
+            const fr_t* mo = mm[n & 1u];
+            fr_t m_here = mo[at];
+            fr_t pv = fr_add(fr_neg(fr_mul(zeta[n], po[at])), fr_mul(w[base + (uint64_t)n * inner], m_here));
+            fr_t mv = fr_neg(fr_mul(zeta[n], m_here));
+            if (k) {
+                pv = fr_add(pv, po[at - inner]);
+                mv = fr_add(mv, mo[at - inner]);
+            }
+            p[(n + 1) & 1u][at] = pv;
+            mm[(n + 1) & 1u][at] = mv;
+        }
+    }
+};
 struct ScalarsToFr {           /* any scalar type -> Montgomery Fr */
     const void* scalars;
     int dtype;

@@ -24,6 +24,8 @@ namespace rt {
 typedef void* stream_t;
 inline int dev_malloc(void** p, size_t n) { *p = malloc(n ? n : 1); return *p ? 0 : 2; }
 inline int dev_free(void* p) { free(p); return 0; }
+inline int host_pinned_malloc(void** p, size_t n) { *p = malloc(n ? n : 1); return *p ? 0 : 2; }
+inline int host_pinned_free(void* p) { free(p); return 0; }
 inline int memcpy_h2d(void* d, const void* s, size_t n, stream_t) { memcpy(d, s, n); return 0; }
 inline int memcpy_d2h(void* d, const void* s, size_t n, stream_t) { memcpy(d, s, n); return 0; }
 inline int memcpy_d2d(void* d, const void* s, size_t n, stream_t) { memmove(d, s, n); return 0; }
@@ -64,6 +66,8 @@ namespace rt {
 typedef hipStream_t stream_t;
 inline int dev_malloc(void** p, size_t n) { return (int)hipMalloc(p, n ? n : 1); }
 inline int dev_free(void* p) { return (int)hipFree(p); }
+inline int host_pinned_malloc(void** p, size_t n) { return (int)hipHostMalloc(p, n ? n : 1, hipHostMallocDefault); }
+inline int host_pinned_free(void* p) { return (int)hipHostFree(p); }
 inline int memcpy_h2d(void* d, const void* s, size_t n, stream_t st) { return (int)hipMemcpyAsync(d, s, n, hipMemcpyHostToDevice, st); }
 inline int memcpy_d2h(void* d, const void* s, size_t n, stream_t st) { return (int)hipMemcpyAsync(d, s, n, hipMemcpyDeviceToHost, st); }
 inline int memcpy_d2d(void* d, const void* s, size_t n, stream_t st) { return (int)hipMemcpyAsync(d, s, n, hipMemcpyDeviceToDevice, st); }

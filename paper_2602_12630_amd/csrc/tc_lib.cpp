@@ -39,12 +39,22 @@ struct TreePool {
     bool closed = false;
 };
 
+/* Pinned host memory that small host arrays pass through on their way to the device (job lists, tables of
+ * pointers, verification steps): a copy from pageable memory makes the host wait until the stream has reached it,
+ * a copy from pinned memory does not.  Slots are handed out in order and reused only after the stream has been
+ * waited for. */
+struct Staging {
+    uint8_t* base = nullptr;
+    size_t cap = 0, off = 0;
+};
+
 struct tc_ctx {
     std::shared_ptr<TreePool> tree_pool = std::make_shared<TreePool>();
     int device = 0;
     rt::stream_t stream = nullptr;
     std::string err;
     Arena ws;
+    Staging staging;
     g1_affine* gtable = nullptr;       /* fixed-base table of the generator */
     bool profiling = false;
     std::vector<std::pair<rt::event_t, rt::event_t>> prof[TC_PROF_KINDS];
@@ -116,12 +126,42 @@ static int fail_hip(tc_ctx* ctx, int e, const char* where) {
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+/* wait for the context's stream; every staged host array has been consumed by then */
+static int ctx_sync(tc_ctx* ctx) {
+    RT(rt::stream_sync(ctx->stream));
+    ctx->staging.off = 0;
+    return TC_OK;
+}
+/* dst (device) <- src (host, any memory, free again on return), asynchronous on the context's stream */
+static int h2d(tc_ctx* ctx, void* dst, const void* src, size_t bytes) {
+    if (!bytes) return TC_OK;
+    Staging& S = ctx->staging;
+    size_t need = (bytes + 63) / 64 * 64;
+    if (S.off + need > S.cap) {
+        TRY(ctx_sync(ctx));
+        if (need > S.cap) {
+            if (S.base) rt::host_pinned_free(S.base);
+            S.base = nullptr;
+            S.cap = 0;
+            size_t want = std::max<size_t>(2 * need, (size_t)1 << 20);
+            void* p = nullptr;
+            if (rt::host_pinned_malloc(&p, want) != 0) return fail(ctx, TC_ERR_NOMEM, "pinned host allocation failed");
+            S.base = (uint8_t*)p;
+            S.cap = want;
+        }
+    }
+    memcpy(S.base + S.off, src, bytes);
+    RT(rt::memcpy_h2d(dst, S.base + S.off, bytes, ctx->stream));
+    S.off += need;
+    return TC_OK;
+}
+
 /* Workspace: a slab that grows to the largest demand seen; within one API call allocations
  * are bump-pointer, overflow goes to one-off blocks released at the next reset. */
 static int ws_reset(tc_ctx* ctx) {
     Arena& A = ctx->ws;
     if (!A.extra.empty() || A.demand > A.cap) {
-        RT(rt::stream_sync(ctx->stream));
+        TRY(ctx_sync(ctx));
         for (void* p : A.extra) rt::dev_free(p);
         A.extra.clear();
         if (A.demand > A.cap) {
@@ -231,6 +271,7 @@ extern "C" void tc_ctx_destroy(tc_ctx* ctx) {
     for (void* p : ctx->ws.extra) rt::dev_free(p);
     if (ctx->ws.base) rt::dev_free(ctx->ws.base);
     if (ctx->gtable) rt::dev_free(ctx->gtable);
+    if (ctx->staging.base) rt::host_pinned_free(ctx->staging.base);
     if (ctx->tree_pool->block) rt::dev_free(ctx->tree_pool->block);
     ctx->tree_pool->block = nullptr;
     ctx->tree_pool->cap = 0;
@@ -261,7 +302,7 @@ extern "C" int tc_ctx_profile_read(tc_ctx* ctx, int kind, double* total_ms, uint
     if (!ctx) return TC_ERR_ARG;
     if (kind < 0 || kind >= TC_PROF_KINDS || !total_ms || !launches) return fail(ctx, TC_ERR_ARG, "bad argument");
     RT(rt::set_device(ctx->device));
-    RT(rt::stream_sync(ctx->stream));
+    TRY(ctx_sync(ctx));
     double tot = 0;
     for (auto& pr : ctx->prof[kind]) {
         float ms = 0;
@@ -278,7 +319,7 @@ extern "C" int tc_ctx_profile_read(tc_ctx* ctx, int kind, double* total_ms, uint
 extern "C" const char* tc_last_error(const tc_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 extern "C" int tc_ctx_sync(tc_ctx* ctx) {
     if (!ctx) return TC_ERR_ARG;
-    RT(rt::stream_sync(ctx->stream));
+    TRY(ctx_sync(ctx));
     return TC_OK;
 }
 
@@ -298,14 +339,14 @@ static int points_to_host(tc_ctx* ctx, const g1_xyzz* d_in, uint32_t n, uint8_t*
     TRY(normalize(ctx, d_in, n, aff));
     RT(rt::launch<64>(n, ctx->stream, ToCanonical{aff, can}));
     RT(rt::memcpy_d2h(out, can, 96ull * n, ctx->stream));
-    RT(rt::stream_sync(ctx->stream));
+    TRY(ctx_sync(ctx));
     return TC_OK;
 }
 static int affine_to_host(tc_ctx* ctx, const g1_affine* d_in, uint32_t n, uint8_t* out) {
     WS(can, uint32_t, 24ull * n);
     RT(rt::launch<64>(n, ctx->stream, ToCanonical{d_in, can}));
     RT(rt::memcpy_d2h(out, can, 96ull * n, ctx->stream));
-    RT(rt::stream_sync(ctx->stream));
+    TRY(ctx_sync(ctx));
     return TC_OK;
 }
 
@@ -676,8 +717,8 @@ static int launch_jobs(tc_ctx* ctx, const std::vector<F>& jobs, const std::vecto
     F* d_jobs = (F*)ws_alloc(ctx, sizeof(F) * jobs.size());
     uint64_t* d_first = ws_array<uint64_t>(ctx, first.size());
     if (!d_jobs || !d_first) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed");
-    RT(rt::memcpy_h2d(d_jobs, jobs.data(), sizeof(F) * jobs.size(), ctx->stream));
-    RT(rt::memcpy_h2d(d_first, first.data(), sizeof(uint64_t) * first.size(), ctx->stream));
+    TRY(h2d(ctx, d_jobs, jobs.data(), sizeof(F) * jobs.size()));
+    TRY(h2d(ctx, d_first, first.data(), sizeof(uint64_t) * first.size()));
     RT(rt::launch<BLOCK>(first.back(), ctx->stream, JobList<F>{d_jobs, d_first, (uint32_t)jobs.size()}));
     return TC_OK;
 }
@@ -726,7 +767,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     WS(tables, const g1_affine*, (uint32_t)count);
     std::vector<const g1_affine*> h_tables(count);
     for (int p = 0; p < count; ++p) h_tables[p] = prob[p].pts;
-    RT(rt::memcpy_h2d(tables, h_tables.data(), sizeof(void*) * (size_t)count, ctx->stream));
+    TRY(h2d(ctx, tables, h_tables.data(), sizeof(void*) * (size_t)count));
 
     /* Lanes of the first pass: sub-runs of at most L1 entries, about twice as many as the chip holds at once
      * (the accumulation kernel keeps 3 waves per SIMD), so that the second round evens out what the first left
@@ -753,7 +794,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         }
         WS(d_prob, TileProblem, (uint32_t)count);
         WS(M, uint32_t, (uint64_t)count * n_wg * nbk_pp);
-        RT(rt::memcpy_h2d(d_prob, h_prob.data(), sizeof(TileProblem) * (size_t)count, ctx->stream));
+        TRY(h2d(ctx, d_prob, h_prob.data(), sizeof(TileProblem) * (size_t)count));
         uint32_t groups = (uint32_t)count * n_wg;
         if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, CountTile<128>{d_prob, dtype, W, c, n_wg, M})));
         else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, CountTile<512>{d_prob, dtype, W, c, n_wg, M})));
@@ -796,7 +837,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     }
 
     /* Middle passes shrink the per-bucket partial count by L2 until at most L2 remain. */
-    RT(rt::stream_sync(ctx->stream));
+    TRY(ctx_sync(ctx));
     if (max_count > max_items) return fail(ctx, TC_ERR_STATE, "internal: bucket count exceeds the term count");
     uint64_t worst = ((uint64_t)max_count + L1 - 1) / L1;
     g1_xyzz *cur = bufA, *nxt = bufB;
@@ -1122,7 +1163,7 @@ static int verify_steps(tc_ctx* ctx, const tc_vk* vk, const std::vector<VerifySt
     uint32_t chunk = n < VERIFY_CHUNK_STEPS ? n : VERIFY_CHUNK_STEPS;
     WS(d_chain, g1_jac, (uint64_t)chunk * VERIFY_CHAINS * VERIFY_BITS);
     WS(d_part, g1_xyzz, (uint64_t)chunk * VERIFY_MAX_GROUPS);
-    RT(rt::memcpy_h2d(d_steps, steps.data(), sizeof(VerifyStep) * n, ctx->stream));
+    TRY(h2d(ctx, d_steps, steps.data(), sizeof(VerifyStep) * n));
     RT(rt::launch<256>(n, ctx->stream, Fill32{d_ok, 1u}));
     for (uint32_t c0 = 0; c0 < n; c0 += chunk) {       /* the chain buffer serves one chunk of steps after the other */
         uint32_t cn = n - c0 < chunk ? n - c0 : chunk;
@@ -1140,7 +1181,7 @@ static int verify_steps(tc_ctx* ctx, const tc_vk* vk, const std::vector<VerifySt
         RT((launch_coop<Decide::BLOCK>(cn, ctx->stream, Decide{VerifyDecideSrc{d_part, groups, d_ok + c0}})));
     }
     RT(rt::memcpy_d2h(ok.data(), d_ok, 4ull * n, ctx->stream));
-    RT(rt::stream_sync(ctx->stream));
+    TRY(ctx_sync(ctx));
     return TC_OK;
 }
 
@@ -1595,8 +1636,8 @@ extern "C" int tc_terkle_open_batch(tc_ctx* ctx, const tc_tree* t, int count, co
             while ((2u << logH) < (uint32_t)FB_W) ++logH;
             if ((((uint64_t)jobs * terms) << logH) > 0xFFFFFFFFull) return fail(ctx, TC_ERR_ARG, "too many openings in one batch");
             WS(d_terms, g1_xyzz, ((uint64_t)jobs * terms) << logH);
-            RT(rt::memcpy_h2d(d_jobs, hj.data(), sizeof(NodeOpenJob) * jobs, ctx->stream));
-            RT(rt::memcpy_h2d(d_seg, seg.data(), 4 * seg.size(), ctx->stream));
+            TRY(h2d(ctx, d_jobs, hj.data(), sizeof(NodeOpenJob) * jobs));
+            TRY(h2d(ctx, d_seg, seg.data(), 4 * seg.size()));
             k.jobs = d_jobs;
             k.out = d_terms;
             k.y_out = d_y;
@@ -1671,11 +1712,11 @@ extern "C" int tc_terkle_open_batch(tc_ctx* ctx, const tc_tree* t, int count, co
             for (uint32_t w = 0; w < n_child; ++w) src[w] = t->levels[want[w].first].C + want[w].second;
             WS(d_src, const g1_affine*, n_child);
             WS(can, uint32_t, 24ull * n_child);
-            RT(rt::memcpy_h2d(d_src, src.data(), sizeof(const g1_affine*) * n_child, ctx->stream));
+            TRY(h2d(ctx, d_src, src.data(), sizeof(const g1_affine*) * n_child));
             RT(rt::launch<64>(n_child, ctx->stream, ToCanonicalGather{d_src, can}));
             h_child.resize(96ull * n_child);
             RT(rt::memcpy_d2h(h_child.data(), can, 96ull * n_child, ctx->stream));
-            RT(rt::stream_sync(ctx->stream));
+            TRY(ctx_sync(ctx));
         }
     }
     /* assemble, top level first */
@@ -1782,10 +1823,10 @@ extern "C" int tc_verify_paths_batch(tc_ctx* ctx, const tc_vk* vk, int count, co
             if (!child_bytes[s].empty()) memcpy(&pts[24ull * s], child_bytes[s].data(), 96);
         WS(d_pts, uint32_t, 24ull * ns);
         WS(d_phi, fr_plain, ns);
-        RT(rt::memcpy_h2d(d_pts, pts.data(), 96ull * ns, ctx->stream));
+        TRY(h2d(ctx, d_pts, pts.data(), 96ull * ns));
         RT(rt::launch<64>(ns, ctx->stream, PhiCanonical{d_pts, d_phi}));
         RT(rt::memcpy_d2h(h_phi.data(), d_phi, 32ull * ns, ctx->stream));
-        RT(rt::stream_sync(ctx->stream));
+        TRY(ctx_sync(ctx));
     }
     for (int i = 0; i < count; ++i) {
         if (malformed[i]) { results[i] = TC_ERR_VERIFY; continue; }
@@ -1874,53 +1915,82 @@ static bool interp_shape_ok(int m, const uint32_t* shape, uint64_t* total) {
     return true;
 }
 
-extern "C" int tc_interpolate(tc_ctx* ctx, int m, const uint32_t* shape, const void* d_scalars, int dtype, void* d_coeffs) {
+extern "C" int tc_interpolate_form(tc_ctx* ctx, int m, const uint32_t* shape, const void* d_scalars, int dtype, int form,
+                                   void* d_coeffs) {
     if (!ctx) return TC_ERR_ARG;
     if (!d_scalars || !d_coeffs) return fail(ctx, TC_ERR_ARG, "null argument");
     if (!valid_dtype_scalar(dtype)) return fail(ctx, TC_ERR_ARG, "unsupported scalar dtype");
+    if (form != TC_INTERP_NEWTON && form != TC_INTERP_GREGORY && form != TC_INTERP_BARYCENTRIC)
+        return fail(ctx, TC_ERR_ARG, "unknown interpolation form");
     uint64_t n = 0;
     if (!interp_shape_ok(m, shape, &n)) return fail(ctx, TC_ERR_SHAPE, "bad shape");
     RT(rt::set_device(ctx->device));
     TRY(ws_reset(ctx));
     uint32_t dmax = 1;
     for (int j = 0; j < m; ++j) dmax = std::max(dmax, shape[j]);
-    /* 1 / l and zeta_k = k + 1 up to the longest axis */
-    std::vector<fr_t> inv(dmax), zeta(dmax);
+    /* 1 / l, 1 / l! and zeta_k = k + 1 up to the longest axis */
+    std::vector<fr_t> inv(dmax), zeta(dmax), inv_fact(dmax);
     for (uint32_t i = 0; i < dmax; ++i) {
         inv[i] = fe_from_u32<FrParams>(i ? i : 1);
         zeta[i] = fe_from_u32<FrParams>(i + 1);
     }
     fr_batch_inverse(inv);
+    inv_fact[0] = fe_one<FrParams>();
+    for (uint32_t i = 1; i < dmax; ++i) inv_fact[i] = fr_mul(inv_fact[i - 1], inv[i]);
     WS(d_inv, fr_t, dmax);
     WS(d_zeta, fr_t, dmax);
-    RT(rt::memcpy_h2d(d_inv, inv.data(), sizeof(fr_t) * dmax, ctx->stream));
-    RT(rt::memcpy_h2d(d_zeta, zeta.data(), sizeof(fr_t) * dmax, ctx->stream));
-    fr_t* buf[3];
-    for (int i = 0; i < 3; ++i) {
+    WS(d_aux, fr_t, dmax);             /* 1 / l! (Gregory) or the weights beta of the current axis (barycentric) */
+    TRY(h2d(ctx, d_inv, inv.data(), sizeof(fr_t) * dmax));
+    TRY(h2d(ctx, d_zeta, zeta.data(), sizeof(fr_t) * dmax));
+    if (form == TC_INTERP_GREGORY) TRY(h2d(ctx, d_aux, inv_fact.data(), sizeof(fr_t) * dmax));
+    const int nbuf = form == TC_INTERP_BARYCENTRIC ? 5 : 3;
+    fr_t* buf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+    for (int i = 0; i < nbuf; ++i) {
         buf[i] = ws_array<fr_t>(ctx, n);
         if (!buf[i]) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed");
     }
     RT(rt::launch<256>(n, ctx->stream, ScalarsToFr{d_scalars, dtype, buf[0]}));
+    std::vector<fr_t> beta;
     uint64_t outer = 1;
     for (int j = 0; j < m; ++j) {
         uint32_t d = shape[j];
         uint64_t inner = n / (outer * d);
-        if (d > 1) {
+        uint64_t lines = outer * inner;
+        uint32_t lines_per_wg = d >= (uint32_t)InterpAxis::BLOCK ? 1u : (uint32_t)InterpAxis::BLOCK / d;
+        uint64_t groups = (lines + lines_per_wg - 1) / lines_per_wg;
+        if (d > 1 && form == TC_INTERP_BARYCENTRIC) {
+            /* beta_l = (-1)^(d-1-l) / (l! (d-1-l)!) on the nodes 1 .. d */
+            beta.resize(d);
+            for (uint32_t l = 0; l < d; ++l) {
+                beta[l] = fr_mul(inv_fact[l], inv_fact[d - 1 - l]);
+                if ((d - 1 - l) & 1u) beta[l] = fr_neg(beta[l]);
+            }
+            /* the previous axis' launch may still read its weights: the copy is ordered behind it on the stream */
+            TRY(h2d(ctx, d_aux, beta.data(), sizeof(fr_t) * d));
+            InterpAxisBarycentric k;
+            k.w = buf[0]; k.p[0] = buf[1]; k.p[1] = buf[2]; k.mm[0] = buf[3]; k.mm[1] = buf[4];
+            k.outer = outer; k.inner = inner; k.d = d; k.lines_per_wg = lines_per_wg;
+            k.beta = d_aux; k.zeta = d_zeta;
+            RT((launch_coop_n<InterpAxisBarycentric::BLOCK>((uint32_t)groups, ctx->stream, k, (int)(d + 1))));
+            std::swap(buf[0], buf[1 + (d & 1u)]);
+        } else if (d > 1) {
             InterpAxis k;
             k.buf[0] = buf[0]; k.buf[1] = buf[1]; k.buf[2] = buf[2];
-            k.outer = outer; k.inner = inner; k.d = d;
-            k.lines_per_wg = d >= (uint32_t)InterpAxis::BLOCK ? 1u : (uint32_t)InterpAxis::BLOCK / d;
+            k.outer = outer; k.inner = inner; k.d = d; k.lines_per_wg = lines_per_wg;
             k.inv_int = d_inv; k.zeta = d_zeta;
-            uint64_t lines = outer * inner;
-            uint64_t groups = (lines + k.lines_per_wg - 1) / k.lines_per_wg;
+            k.inv_fact = form == TC_INTERP_GREGORY ? d_aux : nullptr;
             RT((launch_coop_n<InterpAxis::BLOCK>((uint32_t)groups, ctx->stream, k, (int)(2 * d - 1))));
             std::swap(buf[0], buf[interp_result_buffer(d)]);      /* the next axis reads what this one produced */
         }
         outer *= d;
     }
     RT(rt::launch<256>(n, ctx->stream, FrToPlain{buf[0], (fr_plain*)d_coeffs}));
-    RT(rt::stream_sync(ctx->stream));
+    TRY(ctx_sync(ctx));
     return TC_OK;
+}
+
+extern "C" int tc_interpolate(tc_ctx* ctx, int m, const uint32_t* shape, const void* d_scalars, int dtype, void* d_coeffs) {
+    return tc_interpolate_form(ctx, m, shape, d_scalars, dtype, TC_INTERP_NEWTON, d_coeffs);
 }
 
 extern "C" int tc_divide_by_linear(tc_ctx* ctx, int m, const uint32_t* shape, const void* d_coeffs, int axis,
@@ -1940,7 +2010,7 @@ extern "C" int tc_divide_by_linear(tc_ctx* ctx, int m, const uint32_t* shape, co
     /* everything off the axis' degree 0 in r, and the whole of q, is written by the kernel; lines = outer * inner */
     RT(rt::launch<64>(outer * inner, ctx->stream,
                       DivideAxis{(const fr_plain*)d_coeffs, outer, inner, d, kappa_axis + 1u, (fr_plain*)d_quotient, (fr_plain*)d_remainder}));
-    RT(rt::stream_sync(ctx->stream));
+    TRY(ctx_sync(ctx));
     return TC_OK;
 }
 

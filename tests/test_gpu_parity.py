@@ -613,6 +613,10 @@ def test_coefficient_route(T, ctx):
         ctx.interpolate(shape, to_device(X), T.TC_I16, coeffs)
         want = tc.interpolate(X, shape)
         assert _coeff_list(coeffs) == want, shape
+        for form in (T.TC_INTERP_NEWTON, T.TC_INTERP_GREGORY, T.TC_INTERP_BARYCENTRIC):     # the three forms of App. C
+            by_form = torch.empty_like(coeffs)
+            ctx.interpolate_form(shape, to_device(X), T.TC_I16, form, by_form)
+            assert _coeff_list(by_form) == want, (shape, form)
         axis = len(shape) - 1 if len(shape) > 1 else 0
         kap = int(rng.integers(0, shape[axis]))
         q = torch.empty_like(coeffs)
@@ -630,6 +634,10 @@ def test_coefficient_route(T, ctx):
         for c in reversed(a):
             acc = (acc * (k + 1) + c) % R
         assert acc == int(X[k]) % R, k
+    for form in (T.TC_INTERP_GREGORY, T.TC_INTERP_BARYCENTRIC):
+        by_form = torch.empty_like(coeffs)
+        ctx.interpolate_form((4096,), to_device(X), T.TC_I8, form, by_form)
+        assert _coeff_list(by_form) == a, form
     # commitments and a literal opening at the C1 shape
     shape = tc_inputs.C1_SHAPE
     pp = pps(shape)

@@ -302,6 +302,11 @@ def test_emulated_coefficient_route(emu):
         emu.interpolate(shape, X, T.TC_I8, coeffs)
         want = tc.interpolate(X, shape)
         assert _fr_list(coeffs) == want, shape
+        # the three forms of App. C, each against the oracle's own version of that form
+        for form, name in ((T.TC_INTERP_NEWTON, "newton"), (T.TC_INTERP_GREGORY, "gregory"), (T.TC_INTERP_BARYCENTRIC, "barycentric")):
+            by_form = _fr_array(n)
+            emu.interpolate_form(shape, X, T.TC_I8, form, by_form)
+            assert _fr_list(by_form) == tc.interpolate_form(X, shape, name) == want, (shape, name)
         # Algorithm 1 along every axis at some position
         for axis, d in enumerate(shape):
             kap = int(rng.integers(0, d))
@@ -319,6 +324,8 @@ def test_emulated_coefficient_route(emu):
     cfr = _fr_array(6)
     emu.interpolate((6,), fr_bytes_array(big), T.TC_FR, cfr)
     assert _fr_list(cfr) == tc.interpolate(big, (6,))
+    with pytest.raises(T.TcError):
+        emu.interpolate_form((4, 3), X16, T.TC_I16, 3, c16)
     # commitments and an opening through the monomial SRS
     shape = (3, 4)
     pp = pps(shape)
