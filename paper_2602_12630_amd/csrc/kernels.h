@@ -697,6 +697,49 @@ struct RowColSums {
         }
     }
 };
+/* The same sums for launches with many windows, where SIMD time matters more than depth: four rows (columns) per
+ * wave, sixteen lanes each, 16 (8) buckets per lane one after the other and four halving steps -- twice the depth of
+ * RowColSums, 2.8 times less SIMD time. */
+struct RowColSumsPacked {
+    static constexpr int BLOCK = 64;
+    static constexpr int PHASES = 6;           /* serial part, 4 halving steps, store */
+    static constexpr size_t LDS_BYTES = BLOCK * sizeof(g1_xyzz);
+    static constexpr uint32_t GROUPS = 32 + 64;
+    const g1_xyzz* bucket;      /* windows * 32768 */
+    g1_xyzz* rows;              /* windows * 256: entries 128..255 of a window are the identity */
+    g1_xyzz* cols;              /* windows * 256 */
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        g1_xyzz* buf = (g1_xyzz*)lds;
+        uint32_t w = wg / GROUPS, g = wg % GROUPS;
+        uint32_t sub = lane >> 4, j = lane & 15u;
+        const g1_xyzz* base = bucket + (uint64_t)w * 32768u;
+        if (ph == 0) {
+            g1_xyzz acc;
+            if (g < 32) {                      /* row 4 g + sub: lane takes 16 neighbouring buckets */
+                const g1_xyzz* p = base + (g * 4u + sub) * 256u + j * 16u;
+                acc = p[0];
+                for (int i = 1; i < 16; ++i) acc = xyzz_add(acc, p[i]);
+            } else {                           /* column 4 (g - 32) + sub: lane takes 8 of the 128 rows */
+                const g1_xyzz* p = base + ((g - 32u) * 4u + sub) + (uint64_t)(j * 8u) * 256u;
+                acc = p[0];
+                for (int i = 1; i < 8; ++i) acc = xyzz_add(acc, p[(uint64_t)i * 256u]);
+            }
+            buf[lane] = acc;
+            return;
+        }
+        if (ph <= 4) {
+            uint32_t stride = 8u >> (ph - 1);
+            if (j < stride) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
+            return;
+        }
+        if (j == 0) {
+            if (g < 32) rows[(uint64_t)w * 256 + g * 4u + sub] = buf[lane];
+            else cols[(uint64_t)w * 256 + (g - 32u) * 4u + sub] = buf[lane];
+        } else if (j == 1 && g < 32) {
+            rows[(uint64_t)w * 256 + 128 + g * 4u + sub] = xyzz_identity();
+        }
+    }
+};
 /* one lane per window: 256 (W_R - S_R) + W_C */
 struct RowColFinish {
     const g1_xyzz* w_rows;      /* sum_h (h + 1) R_h */

@@ -678,6 +678,9 @@ static int scan_counts(tc_ctx* ctx, const uint32_t* cnt, uint32_t n, uint32_t L,
     return TC_OK;
 }
 
+/* from this many 32768-bucket windows on, a launch fills the chip with the packed row / column sums */
+static const int ROWCOL_PACKED_WINDOWS = 8;
+
 /* sum_k k B_k for every window of `bucket` (W windows of nb buckets) -> wsum[W] */
 static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb, g1_xyzz* wsum) {
     if (nb == 256 && W >= 512) {
@@ -699,7 +702,10 @@ static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb
     WS(cols, g1_xyzz, 256ull * W);
     WS(w_rc, g1_xyzz, 2u * (uint32_t)W);     /* [0, W): columns, [W, 2W): rows */
     WS(s_rc, g1_xyzz, 2u * (uint32_t)W);
-    RT((launch_coop<RowColSums::BLOCK>((uint32_t)W * RowColSums::GROUPS, ctx->stream, RowColSums{bucket, rows, cols})));
+    if (W >= ROWCOL_PACKED_WINDOWS)
+        RT((launch_coop<RowColSumsPacked::BLOCK>((uint32_t)W * RowColSumsPacked::GROUPS, ctx->stream, RowColSumsPacked{bucket, rows, cols})));
+    else
+        RT((launch_coop<RowColSums::BLOCK>((uint32_t)W * RowColSums::GROUPS, ctx->stream, RowColSums{bucket, rows, cols})));
     RT((launch_coop<256>(2u * (uint32_t)W, ctx->stream,
                          WeightedBlockSum<256>{cols, 256u * (uint32_t)W, w_rc, s_rc, rows, (uint32_t)W})));
     RT(rt::launch<64>((uint32_t)W, ctx->stream, RowColFinish{w_rc + W, s_rc + W, w_rc, wsum}));

@@ -100,6 +100,14 @@ def test_emulated_commit_open_verify(emu):
         assert not emu.verify(vk, shape, C, kappa, ec.fr_to_bytes((yo + 1) % R), pi)
     both = emu.commit_batch([srs, srs], [X16, X8], [T.TC_I16, T.TC_I8])
     assert both == [ec.g1_to_bytes(tc.commit(pp, X16)), ec.g1_to_bytes(tc.commit(pp, X8))]
+    # nine int16 tensors in one batch: launches with that many 32768-bucket windows take the packed row / column sums
+    rng = np.random.default_rng(77)
+    many = [rng.integers(-32767, 32768, size=shape).astype(np.int16) for _ in range(9)]
+    many[3][...] = 0
+    many[5].reshape(-1)[:] = 32767
+    many[6].reshape(-1)[:] = -32767
+    got = emu.commit_batch([srs] * 9, many, [T.TC_I16] * 9)
+    assert got == [ec.g1_to_bytes(tc.commit(pp, X)) for X in many]
     srs.close()
 
 
