@@ -202,6 +202,33 @@ TC_HD int32_t tile_value(const TileProblem& P, int dtype, uint64_t i) {
     if (P.sub) v -= small_scalar(P.sub, dtype, i);
     return v;
 }
+/* every term i of [lo, hi) with its value v: each(i, v).  A plain int8 / int16 problem whose scalars are 16-byte
+ * aligned at `lo` goes sixteen bytes per lane and step (a lane that fetches one small value per step spends its
+ * time waiting for it); what is left over, and every other problem, goes term by term. */
+template <int BLOCK, class Each>
+TC_DEV void tile_terms(const TileProblem& P, int dtype, uint64_t lo, uint64_t hi, uint32_t lane, const Each& each) {
+    if (lo >= hi) return;                  /* a tile past the end of its problem */
+    uint64_t rest = lo;
+    uint32_t esz = dtype == DT_I8 ? 1u : 2u;
+    if (!P.sub && (dtype == DT_I8 || dtype == DT_I16) && (((uintptr_t)P.scalars + lo * esz) & 15u) == 0) {
+        uint32_t per = 16u / esz;
+        uint64_t chunks = (hi - lo) / per;
+        const Words16* src = (const Words16*)((const uint8_t*)P.scalars + lo * esz);
+        for (uint64_t ch = lane; ch < chunks; ch += BLOCK) {
+            Words16 x = src[ch];
+            uint64_t i = lo + ch * per;
+            if (esz == 2u) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) each(i + k, (int32_t)(int16_t)(x.w[k >> 1] >> (16 * (k & 1))));
+            } else {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) each(i + k, (int32_t)(int8_t)(x.w[k >> 2] >> (8 * (k & 3))));
+            }
+        }
+        rest = lo + chunks * per;
+    }
+    for (uint64_t i = rest + lane; i < hi; i += BLOCK) each(i, tile_value(P, dtype, i));
+}
 template <int NBK>            /* keys per problem = windows * buckets per window */
 struct CountTile {
     static constexpr int BLOCK = 1024;
@@ -220,14 +247,13 @@ struct CountTile {
         } else if (ph == 1) {
             const TileProblem P = prob[p];
             uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
-            for (uint64_t i = lo + lane; i < hi; i += BLOCK) {
-                int32_t v = tile_value(P, dtype, i);
+            tile_terms<BLOCK>(P, dtype, lo, hi, lane, [&](uint64_t, int32_t v) {
                 uint32_t mag = (uint32_t)(v < 0 ? -v : v), carry = 0;
                 for (int w = 0; w < W; ++w) {
                     int32_t d = W == 1 ? (int32_t)mag : small_window_digit(mag, w, c, carry);
                     if (d) atomic_add_u32(&hist[(uint32_t)w * nb + (uint32_t)(d < 0 ? -d : d) - 1u], 1u);
                 }
-            }
+            });
         } else {
             uint32_t* row = M + (uint64_t)wg * NBK;
             for (uint32_t k = lane; k < (uint32_t)NBK; k += BLOCK) row[k] = hist[k];
@@ -272,8 +298,7 @@ struct ScatterTile {
         } else {
             const TileProblem P = prob[p];
             uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
-            for (uint64_t i = lo + lane; i < hi; i += BLOCK) {
-                int32_t v = tile_value(P, dtype, i);
+            tile_terms<BLOCK>(P, dtype, lo, hi, lane, [&](uint64_t i, int32_t v) {
                 uint32_t mag = (uint32_t)(v < 0 ? -v : v), carry = 0;
                 for (int w = 0; w < W; ++w) {
                     int32_t d = W == 1 ? (int32_t)mag : small_window_digit(mag, w, c, carry);
@@ -283,7 +308,7 @@ struct ScatterTile {
                         sorted[pos] = (uint32_t)i | (negative ? 0x80000000u : 0u);
                     }
                 }
-            }
+            });
         }
     }
 };

@@ -796,7 +796,8 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
             h_prob[p].scalars = prob[p].scalars;
             h_prob[p].sub = prob[p].sub;
             h_prob[p].n = prob[p].n;
-            h_prob[p].tile = (uint32_t)((prob[p].n + n_wg - 1) / n_wg);
+            /* a multiple of 16 terms, so that a tile of an aligned int8 / int16 array starts on a 16-byte boundary */
+            h_prob[p].tile = (uint32_t)(((prob[p].n + n_wg - 1) / n_wg + 15) / 16 * 16);
         }
         WS(d_prob, TileProblem, (uint32_t)count);
         WS(M, uint32_t, (uint64_t)count * n_wg * nbk_pp);

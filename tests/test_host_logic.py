@@ -111,6 +111,29 @@ def test_emulated_commit_open_verify(emu):
     srs.close()
 
 
+def test_emulated_two_pass_scatter(emu):
+    """Launches of many 16-bit terms sort them into buckets in two passes (coarse bins, then buckets); the CPU
+    build of the kernels takes that route from 2^12 terms on.  Commitments of such tensors, alone and as a batch
+    whose tiles are ragged, against the oracle's closed form; extreme and repeated values, a tensor of zeros."""
+    shape = (48, 131)
+    pp = pps(shape)
+    srs = emu.setup_from_trapdoor(TAU_BYTES, shape, 0)
+    rng = np.random.default_rng(9)
+    gauss = np.clip(np.rint(rng.standard_normal(shape) * 7000), -32767, 32767).astype(np.int16)
+    edge = rng.integers(-32768, 32768, size=shape).astype(np.int16)
+    edge.reshape(-1)[::7] = 0
+    edge.reshape(-1)[1::97] = -32768
+    edge.reshape(-1)[2::89] = 32767
+    edge.reshape(-1)[3::5] = 255                       # one bucket on a bin boundary, heavily loaded
+    edge.reshape(-1)[4::11] = -256
+    zeros = np.zeros(shape, np.int16)
+    for X in (gauss, edge):
+        assert emu.commit(srs, X, T.TC_I16) == ec.g1_to_bytes(tc.commit(pp, X))
+    got = emu.commit_batch([srs] * 3, [gauss, zeros, edge], [T.TC_I16] * 3)
+    assert got == [ec.g1_to_bytes(tc.commit(pp, X)) for X in (gauss, zeros, edge)]
+    srs.close()
+
+
 def test_emulated_open_by_rows(emu):
     """Openings along a leading axis of a larger tensor take the row-wise route (17-bit numerators as two
     9-bit digits per entry); same bytes as the oracle's closed form."""
