@@ -204,13 +204,14 @@ TC_HD int32_t tile_value(const TileProblem& P, int dtype, uint64_t i) {
 }
 /* every term i of [lo, hi) with its value v: each(i, v).  A plain int8 / int16 problem whose scalars are 16-byte
  * aligned at `lo` goes sixteen bytes per lane and step (a lane that fetches one small value per step spends its
- * time waiting for it); what is left over, and every other problem, goes term by term. */
-template <int BLOCK, class Each>
+ * time waiting for it); what is left over, and every other problem, goes term by term.  WIDE = false leaves the
+ * wide path out of kernels that only ever see two-digit difference problems (it would cost them registers). */
+template <int BLOCK, bool WIDE, class Each>
 TC_DEV void tile_terms(const TileProblem& P, int dtype, uint64_t lo, uint64_t hi, uint32_t lane, const Each& each) {
     if (lo >= hi) return;                  /* a tile past the end of its problem */
     uint64_t rest = lo;
     uint32_t esz = dtype == DT_I8 ? 1u : 2u;
-    if (!P.sub && (dtype == DT_I8 || dtype == DT_I16) && (((uintptr_t)P.scalars + lo * esz) & 15u) == 0) {
+    if (WIDE && !P.sub && (dtype == DT_I8 || dtype == DT_I16) && (((uintptr_t)P.scalars + lo * esz) & 15u) == 0) {
         uint32_t per = 16u / esz;
         uint64_t chunks = (hi - lo) / per;
         const Words16* src = (const Words16*)((const uint8_t*)P.scalars + lo * esz);
@@ -247,7 +248,7 @@ struct CountTile {
         } else if (ph == 1) {
             const TileProblem P = prob[p];
             uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
-            tile_terms<BLOCK>(P, dtype, lo, hi, lane, [&](uint64_t, int32_t v) {
+            tile_terms<BLOCK, NBK != 512>(P, dtype, lo, hi, lane, [&](uint64_t, int32_t v) {
                 uint32_t mag = (uint32_t)(v < 0 ? -v : v), carry = 0;
                 for (int w = 0; w < W; ++w) {
                     int32_t d = W == 1 ? (int32_t)mag : small_window_digit(mag, w, c, carry);
@@ -298,7 +299,7 @@ struct ScatterTile {
         } else {
             const TileProblem P = prob[p];
             uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
-            tile_terms<BLOCK>(P, dtype, lo, hi, lane, [&](uint64_t i, int32_t v) {
+            tile_terms<BLOCK, NBK != 512>(P, dtype, lo, hi, lane, [&](uint64_t i, int32_t v) {
                 uint32_t mag = (uint32_t)(v < 0 ? -v : v), carry = 0;
                 for (int w = 0; w < W; ++w) {
                     int32_t d = W == 1 ? (int32_t)mag : small_window_digit(mag, w, c, carry);
