@@ -137,6 +137,33 @@ def test_special_tensors(T, ctx):
         srs.close()
 
 
+def test_scalars_at_any_alignment(T, ctx):
+    """The count / scatter kernels read sixteen bytes of scalars per lane where a tile starts on a 16-byte boundary
+    and fall back to single values elsewhere: the same tensor at byte offsets 0, 2, 6 and 16 (int16) and 0, 1, 5
+    (int8) of a device buffer, and a length that is no multiple of the chunk, against the oracle."""
+    import torch
+
+    shape = (61, 97)                                   # 5917 terms: tiles of 32 terms, ragged last tile
+    n = shape[0] * shape[1]
+    pp = pps(shape)
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, 0)
+    try:
+        X16 = tc_inputs.int16_uniform(shape, 71, -32768, 32767)
+        X8 = tc_inputs.int8_uniform(shape, 72)
+        want16 = ec.g1_to_bytes(cbind.commit(pp, X16, nthreads=8))
+        want8 = ec.g1_to_bytes(cbind.commit(pp, X8, nthreads=8))
+        for off in (0, 1, 3, 8):
+            buf = torch.zeros(n + 16, dtype=torch.int16, device="cuda")
+            buf[off : off + n] = torch.from_numpy(X16.reshape(-1)).cuda()
+            assert ctx.commit(srs, buf[off : off + n], T.TC_I16) == want16, off
+        for off in (0, 1, 5):
+            buf = torch.zeros(n + 16, dtype=torch.int8, device="cuda")
+            buf[off : off + n] = torch.from_numpy(X8.reshape(-1)).cuda()
+            assert ctx.commit(srs, buf[off : off + n], T.TC_I8) == want8, off
+    finally:
+        srs.close()
+
+
 def test_degenerate_bucket_loads_at_size(T, ctx):
     """All terms in one bucket (constant tensor) and two-valued tensors at a size where the engine
     needs its shrinking passes; closed forms: constant c => [c]G, and linearity for the two-valued one."""

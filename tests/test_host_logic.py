@@ -111,10 +111,10 @@ def test_emulated_commit_open_verify(emu):
     srs.close()
 
 
-def test_emulated_two_pass_scatter(emu):
-    """Launches of many 16-bit terms sort them into buckets in two passes (coarse bins, then buckets); the CPU
-    build of the kernels takes that route from 2^12 terms on.  Commitments of such tensors, alone and as a batch
-    whose tiles are ragged, against the oracle's closed form; extreme and repeated values, a tensor of zeros."""
+def test_emulated_int16_commits_over_several_tiles(emu):
+    """Tensors of a few thousand 16-bit terms span several ragged tiles of the count / scatter kernels, which read
+    sixteen bytes per lane where a tile is aligned and single values elsewhere.  Commitments alone, as a batch, and
+    from a buffer at an odd offset, against the oracle's closed form; extreme and repeated values, a tensor of zeros."""
     shape = (48, 131)
     pp = pps(shape)
     srs = emu.setup_from_trapdoor(TAU_BYTES, shape, 0)
@@ -124,13 +124,17 @@ def test_emulated_two_pass_scatter(emu):
     edge.reshape(-1)[::7] = 0
     edge.reshape(-1)[1::97] = -32768
     edge.reshape(-1)[2::89] = 32767
-    edge.reshape(-1)[3::5] = 255                       # one bucket on a bin boundary, heavily loaded
+    edge.reshape(-1)[3::5] = 255                       # one heavily loaded bucket
     edge.reshape(-1)[4::11] = -256
     zeros = np.zeros(shape, np.int16)
     for X in (gauss, edge):
         assert emu.commit(srs, X, T.TC_I16) == ec.g1_to_bytes(tc.commit(pp, X))
     got = emu.commit_batch([srs] * 3, [gauss, zeros, edge], [T.TC_I16] * 3)
     assert got == [ec.g1_to_bytes(tc.commit(pp, X)) for X in (gauss, zeros, edge)]
+    for off in (1, 3, 8):
+        buf = np.zeros(gauss.size + 16, np.int16)
+        buf[off : off + gauss.size] = gauss.reshape(-1)
+        assert emu.commit(srs, buf[off : off + gauss.size], T.TC_I16) == ec.g1_to_bytes(tc.commit(pp, gauss)), off
     srs.close()
 
 
