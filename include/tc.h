@@ -30,6 +30,13 @@
  *     0-based; position i on an axis is the evaluation node zeta = i + 1.
  *   - One trapdoor vector (tau_1..tau_4) serves every shape of a context: axis
  *     j of any shape uses tau_j.
+ *   - A context (its stream, workspace and staging memory) serves one host
+ *     thread at a time; different contexts may be used from different threads
+ *     at once, also on the same GPU and with shared tc_srs / tc_vk objects,
+ *     which are read-only once built.  A tree belongs to the context that
+ *     built it.  Kernels of contexts on different streams overlap only as far
+ *     as the HIP runtime has hardware queues for them (GPU_MAX_HW_QUEUES, read
+ *     when the runtime starts; its default is 4).
  */
 #ifndef TC_H_
 #define TC_H_
