@@ -375,8 +375,8 @@ __device__ __forceinline__ Fe<P> fe_sqr_dev(const Fe<P>& a) {
  * stays below 2^53, so every fused multiply-add is exact in any rounding mode.  16 x 24 = 12 x 32 bits: the
  * Montgomery radix is the same 2^384, and the result is bit for bit that of the integer routine.
  * 512 multiply-adds replace 300 integer ones and their 300 carry additions: a full chip gets through fewer
- * products a second this way (measured 44 G against 53 G), a wave alone on its SIMD finishes one sooner
- * (1.75 us against 2.3 us), because the multiply-adds of a column do not wait for a carry. */
+ * products a second this way (measured 46 G against 61 G); a wave alone on its SIMD finishes a product about as
+ * fast as with the integer form (1.74 us against 1.71 us) and a square sooner (1.31 us against 1.70 us). */
 template <int J>
 constexpr double fp_mod_limb24() {
     /* bits 24 J .. 24 J + 23 of the modulus */
@@ -515,9 +515,8 @@ __device__ __forceinline__ fr_t fr_mul(const fr_t& a, const fr_t& b) {
     return fr_mul_call(u32x4{a.l[0], a.l[1], a.l[2], a.l[3]}, u32x4{a.l[4], a.l[5], a.l[6], a.l[7]},
                        u32x4{b.l[0], b.l[1], b.l[2], b.l[3]}, u32x4{b.l[4], b.l[5], b.l[6], b.l[7]});
 }
-/* Products for kernels whose cost is depth, not volume: a wave that is alone on its SIMD finishes the FP64
- * form sooner (measured per product: 1.75 us against 2.3 us; its multiply-adds do not wait for one another),
- * while a chip full of waves gets through fewer of them a second (44 G against 53 G). */
+/* Products for kernels whose cost is depth, not volume (the doubling chains of batch verification ran 8 % faster
+ * with this form than with the integer one); a chip full of waves gets through fewer of them a second. */
 __device__ __attribute__((noinline)) fp_t fp_mul_lat_call(u32x4 a0, u32x4 a1, u32x4 a2, u32x4 b0, u32x4 b1, u32x4 b2) {
     fp_t a, b;
     a.l[0] = a0.x; a.l[1] = a0.y; a.l[2] = a0.z; a.l[3] = a0.w; a.l[4] = a1.x; a.l[5] = a1.y; a.l[6] = a1.z; a.l[7] = a1.w;
