@@ -20,8 +20,8 @@ import time
 
 # Steps in flight run on streams of their own, and streams that share a hardware queue run their kernels one
 # after the other.  HIP's default of 4 queues per process caps the overlap of this path's many short,
-# latency-bound kernels (measured: 2.69 ms per step with 4 queues and 4 steps in flight, 2.03 ms with 16 and
-# 12).  The runtime reads the variable when it starts, so it is set before anything loads HIP
+# latency-bound kernels (measured with the kernels of that day: 2.69 ms per step with 4 queues and 4 steps in
+# flight, 2.03 ms with 16 and 12).  The runtime reads the variable when it starts, so it is set before anything loads HIP
 # (TC_BENCH_HW_QUEUES overrides the count).
 os.environ["GPU_MAX_HW_QUEUES"] = os.environ.get("TC_BENCH_HW_QUEUES", "16")
 
