@@ -324,31 +324,29 @@ __device__ __forceinline__ Fe<P> fe_mul_dev(const Fe<P>& a, const Fe<P>& b) {
     r.l[N - 1] = (uint32_t)A.lo;
     return fe_reduce_once<P>(r, (uint32_t)(A.lo >> 32));
 }
-/* Square: the cross products a_i a_j (i < j) of a column are collected once and doubled. */
+/* Square.  a^2 = sum_j a_j 2^(32 j) (a_j 2^(32 j) + 2 (a mod 2^(32 j))), and the limbs of 2 (a mod 2^(32 j)) are
+ * those of d = 2 a below position j plus, at position j, the bit c_j that a_(j-1) loses in the doubling (2 a fits
+ * in the same number of limbs: the modulus leaves the top bit of the top limb free).  So column k collects
+ * d_i a_j for i < j, i + j = k and, for even k, a_(k/2)^2 + c_(k/2) a_(k/2): the cross products are taken once
+ * with a pre-doubled operand instead of being doubled column by column. */
 template <class P>
 __device__ __forceinline__ Fe<P> fe_sqr_dev(const Fe<P>& a) {
     constexpr int N = P::N;
+    static_assert((P::MOD[N - 1] >> 31) == 0, "the doubled operand must fit in N limbs");
     Acc96P A{0, 0, 0, false};
-    uint32_t m[N];
+    uint32_t m[N], d[N];
     Fe<P> r;
+    d[0] = a.l[0] << 1;
+#pragma unroll
+    for (int i = 1; i < N; ++i) d[i] = __builtin_amdgcn_alignbit(a.l[i], a.l[i - 1], 31);
 #pragma unroll
     for (int k = 0; k < 2 * N - 1; ++k) {
-        Acc96P C{0, 0, 0, false};
 #pragma unroll
-        for (int i = (k < N ? 0 : k - N + 1); i < k - i; ++i) macp_vv(C, a.l[i], a.l[k - i]);
-        flush(C);
-        {
-            uint32_t c0 = (uint32_t)C.lo, c1 = (uint32_t)(C.lo >> 32), c2 = C.hi;
-            uint32_t d0 = c0 << 1;
-            uint32_t d1 = __builtin_amdgcn_alignbit(c1, c0, 31);
-            uint32_t d2 = __builtin_amdgcn_alignbit(c2, c1, 31);
-            lanemask_t cy;
-            uint32_t lo0 = add_co((uint32_t)A.lo, d0, cy);
-            uint32_t lo1 = addc_co((uint32_t)(A.lo >> 32), d1, cy);
-            A.hi = addc_co(A.hi, d2, cy);
-            A.lo = ((uint64_t)lo1 << 32) | lo0;
+        for (int i = (k < N ? 0 : k - N + 1); i < k - i; ++i) macp_vv(A, d[i], a.l[k - i]);
+        if ((k & 1) == 0) {
+            macp_vv(A, a.l[k / 2], a.l[k / 2]);
+            if (k) macp_vv(A, a.l[k / 2], a.l[k / 2 - 1] >> 31);       /* c_(k/2), formed here: registers are scarce */
         }
-        if ((k & 1) == 0) macp_vv(A, a.l[k / 2], a.l[k / 2]);
         if (k < N) {
 #pragma unroll
             for (int i = 0; i < k; ++i) macp_vs(A, m[i], P::MOD[k - i]);
@@ -364,7 +362,6 @@ __device__ __forceinline__ Fe<P> fe_sqr_dev(const Fe<P>& a) {
     r.l[N - 1] = (uint32_t)A.lo;
     return fe_reduce_once<P>(r, (uint32_t)(A.lo >> 32));
 }
-
 #endif
 
 /* ---- Fp products on the FP64 pipe --------------------------------------------------------------
