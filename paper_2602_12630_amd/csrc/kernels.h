@@ -1721,9 +1721,11 @@ struct PhiCanonical {
  *                         a_i <- a_(i-1) - zeta_k a_i (+ c_k at i = 0), ping-pong between the two arrays
  *                         that do not hold c.
  * The host works out where c and the result end up (interp_result_buffer).
- * Gregory form (inv_fact set): the levels take plain forward differences, c_k <- c_k - c_(k-1), so that
+ * Gregory form (a second instantiation, so that the Newton kernel keeps its register count and with it two
+ * workgroups per CU): the levels take plain forward differences, c_k <- c_k - c_(k-1), so that
  * c_k = Delta^k T[0], and the expansion reads c_k / k!, the coefficient of N_k in
  * sum_k binom(X - zeta_0, k) Delta^k T[0] (h = 1). */
+template <bool GREGORY>
 struct InterpAxis {
     static constexpr int BLOCK = 1024;       /* a long line is bound by its 2d - 1 barriers: as many lanes as a workgroup has */
     static constexpr size_t LDS_BYTES = 16;
@@ -1732,10 +1734,10 @@ struct InterpAxis {
     uint32_t d, lines_per_wg;
     const fr_t* inv_int;       /* inv_int[l] = 1 / l, l = 1 .. d-1 */
     const fr_t* zeta;          /* zeta[k] = k + 1 */
-    const fr_t* inv_fact;      /* Gregory form (null for Newton): inv_fact[l] = 1 / l! */
+    const fr_t* inv_fact;      /* Gregory form only: inv_fact[l] = 1 / l! */
     TC_DEV fr_t newton_coefficient(const fr_t* c, uint64_t base, uint32_t k) const {
         fr_t v = c[base + (uint64_t)k * inner];
-        return inv_fact ? fr_mul(v, inv_fact[k]) : v;
+        return GREGORY ? fr_mul(v, inv_fact[k]) : v;
     }
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t*) const {
         uint64_t lines = outer * inner;
@@ -1753,7 +1755,7 @@ struct InterpAxis {
                 fr_t v = src[at];
                 if (k >= l) {
                     v = fr_sub(v, src[at - inner]);
-                    if (!inv_fact) v = fr_mul(v, inv_int[l]);
+                    if (!GREGORY) v = fr_mul(v, inv_int[l]);
                 }
                 buf[(ph + 1) & 1][at] = v;
             } else if (ph + 1 == (int)d) {

@@ -1963,7 +1963,7 @@ extern "C" int tc_interpolate_form(tc_ctx* ctx, int m, const uint32_t* shape, co
         uint32_t d = shape[j];
         uint64_t inner = n / (outer * d);
         uint64_t lines = outer * inner;
-        uint32_t lines_per_wg = d >= (uint32_t)InterpAxis::BLOCK ? 1u : (uint32_t)InterpAxis::BLOCK / d;
+        uint32_t lines_per_wg = d >= (uint32_t)InterpAxis<false>::BLOCK ? 1u : (uint32_t)InterpAxis<false>::BLOCK / d;
         uint64_t groups = (lines + lines_per_wg - 1) / lines_per_wg;
         if (d > 1 && form == TC_INTERP_BARYCENTRIC) {
             /* beta_l = (-1)^(d-1-l) / (l! (d-1-l)!) on the nodes 1 .. d */
@@ -1981,12 +1981,19 @@ extern "C" int tc_interpolate_form(tc_ctx* ctx, int m, const uint32_t* shape, co
             RT((launch_coop_n<InterpAxisBarycentric::BLOCK>((uint32_t)groups, ctx->stream, k, (int)(d + 1))));
             std::swap(buf[0], buf[1 + (d & 1u)]);
         } else if (d > 1) {
-            InterpAxis k;
-            k.buf[0] = buf[0]; k.buf[1] = buf[1]; k.buf[2] = buf[2];
-            k.outer = outer; k.inner = inner; k.d = d; k.lines_per_wg = lines_per_wg;
-            k.inv_int = d_inv; k.zeta = d_zeta;
-            k.inv_fact = form == TC_INTERP_GREGORY ? d_aux : nullptr;
-            RT((launch_coop_n<InterpAxis::BLOCK>((uint32_t)groups, ctx->stream, k, (int)(2 * d - 1))));
+            if (form == TC_INTERP_GREGORY) {
+                InterpAxis<true> k;
+                k.buf[0] = buf[0]; k.buf[1] = buf[1]; k.buf[2] = buf[2];
+                k.outer = outer; k.inner = inner; k.d = d; k.lines_per_wg = lines_per_wg;
+                k.inv_int = d_inv; k.zeta = d_zeta; k.inv_fact = d_aux;
+                RT((launch_coop_n<InterpAxis<true>::BLOCK>((uint32_t)groups, ctx->stream, k, (int)(2 * d - 1))));
+            } else {
+                InterpAxis<false> k;
+                k.buf[0] = buf[0]; k.buf[1] = buf[1]; k.buf[2] = buf[2];
+                k.outer = outer; k.inner = inner; k.d = d; k.lines_per_wg = lines_per_wg;
+                k.inv_int = d_inv; k.zeta = d_zeta; k.inv_fact = nullptr;
+                RT((launch_coop_n<InterpAxis<false>::BLOCK>((uint32_t)groups, ctx->stream, k, (int)(2 * d - 1))));
+            }
             std::swap(buf[0], buf[interp_result_buffer(d)]);      /* the next axis reads what this one produced */
         }
         outer *= d;
