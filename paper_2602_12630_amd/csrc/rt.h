@@ -81,7 +81,7 @@ inline int event_elapsed_ms(event_t a, event_t b, float* ms) {
     int e = (int)hipEventSynchronize(b);
     return e ? e : (int)hipEventElapsedTime(ms, a, b);
 }
-inline void event_destroy(event_t e) { hipEventDestroy(e); }
+inline void event_destroy(event_t e) { (void)hipEventDestroy(e); }
 inline int last_error() { return (int)hipGetLastError(); }
 inline const char* error_string(int e) { return hipGetErrorString((hipError_t)e); }
 template <int BLOCK, class F>

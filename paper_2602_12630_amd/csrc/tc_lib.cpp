@@ -627,8 +627,9 @@ static int launch_coop(uint32_t groups, rt::stream_t st, const F& f) {
     if (!groups) return 0;
     static bool attr_set = false;
     if (!attr_set) {
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&coop_kernel<F, BLOCK>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)F::LDS_BYTES);
+        int e = (int)hipFuncSetAttribute(reinterpret_cast<const void*>(&coop_kernel<F, BLOCK>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)F::LDS_BYTES);
+        if (e) return e;
         attr_set = true;
     }
     hipLaunchKernelGGL((coop_kernel<F, BLOCK>), dim3(groups), dim3(BLOCK), F::LDS_BYTES, st, f);
