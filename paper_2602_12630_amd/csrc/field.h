@@ -863,8 +863,8 @@ TC_HD Fe<P> fe_inv_gcd(const Fe<P>& x) {
             f0 -= f1 & (int32_t)odd;
             g0 -= g1 & (int32_t)odd;
             xa >>= 1;
-            f1 <<= 1;
-            g1 <<= 1;
+            f1 = (int32_t)((uint32_t)f1 << 1);          /* doubling of a possibly negative factor */
+            g1 = (int32_t)((uint32_t)g1 << 1);
         }
         /* (a, b) <- (a f0 + b g0, a f1 + b g1) / 2^30, exact; then make both non-negative */
         uint32_t na[N + 1], nbv[N + 1];
