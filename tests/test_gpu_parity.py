@@ -693,6 +693,36 @@ def test_coefficient_route(T, ctx):
         lag.close()
 
 
+def test_coefficient_route_at_the_size_the_bench_times(T, ctx):
+    """Interpolation of the whole 512 x 4096 activation, the size bench.py times: the three forms of App. C return
+    the same coefficient array, and the polynomial reproduces sampled entries of the tensor (what can be computed
+    one by one on the CPU at this size)."""
+    import torch
+
+    shape = tc_inputs.C2_SHAPE
+    x = tc_inputs.c2_activation()
+    q = np.clip(np.rint(x.astype(np.float32) * 1000.0), -32767, 32767).astype(np.int16)
+    dq = to_device(q)
+    n = q.size
+    newton = torch.empty(32 * n, dtype=torch.uint8, device="cuda")
+    ctx.interpolate(shape, dq, T.TC_I16, newton)
+    for form in (T.TC_INTERP_GREGORY, T.TC_INTERP_BARYCENTRIC):
+        other = torch.empty_like(newton)
+        ctx.interpolate_form(shape, dq, T.TC_I16, form, other)
+        assert torch.equal(other, newton), form
+        del other
+    raw = newton.cpu().numpy().reshape(shape[0], shape[1], 32)
+    for (i, j) in ((0, 0), (511, 4095), (137, 2049)):
+        # f(i + 1, j + 1) by Horner: along axis 1 for every row of coefficients, then along axis 0
+        acc = 0
+        for a in range(shape[0] - 1, -1, -1):
+            row = 0
+            for b in range(shape[1] - 1, -1, -1):
+                row = (row * (j + 1) + int.from_bytes(raw[a, b].tobytes(), "little")) % R
+            acc = (acc * (i + 1) + row) % R
+        assert acc == int(q[i, j]) % R, (i, j)
+
+
 @pytest.mark.parametrize("node,grid", [((8, 8), (64, 64)), ((4, 4, 4), (16, 16, 16)), ((64,), (4096,)), ((8, 8), (70, 9))])
 def test_arity_64_trees(T, ctx, node, grid):
     """The tree shapes of the paper's tree-scaling comparison (Fig. 4, B = 64): Terkle nodes (8,8) and (4,4,4),
