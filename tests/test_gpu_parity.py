@@ -440,6 +440,30 @@ def test_c2_tree_sampled_nodes_and_paths(T, ctx, node_srs):
             assert not terkle.verify_path(pps, root, [node] * 6, int(q[leaf]) + 1, steps)
         vals = [ec.fr_to_bytes(int(q[l]) % R) for l in leaves]
         assert ctx.verify_paths_batch(vk, [tree.path(l) for l in leaves], [tree.root] * 8, vals, proofs) == [True] * 8
+        # incremental updates at this size: two entries change (one to an extreme value); the updated tree must
+        # equal a fresh build over the changed payload on the whole path, the oracle recomputes the bottom node,
+        # and the old proof of that leaf no longer verifies while a new one does
+        for leaf, new in ((leaves[0], -32767), (leaves[3], int(q[leaves[3]]) + 1)):
+            delta = new - int(q[leaf])
+            q[leaf] = new
+            dq.copy_(to_device(q))
+            tree.update(leaf, delta)
+            fresh = ctx.terkle_build_entries(node_srs, dq, T.TC_I16, shape, node)
+            try:
+                a = leaf
+                for level in range(6):
+                    grid, _ = tree.level_info(level)
+                    a = (a[0] // 4, a[1] // 4)
+                    index = a[0] * grid[1] + a[1]
+                    assert tree.node(level, index) == fresh.node(level, index), (leaf, level)
+                assert tree.root == fresh.root
+            finally:
+                fresh.close()
+            bottom = (leaf[0] // 4, leaf[1] // 4)
+            assert tree.node(0, bottom[0] * 1024 + bottom[1]) == ec.g1_to_bytes(oracle_node(0, bottom))
+            proof = tree.open(leaf)
+            assert ctx.verify_path(vk, tree.path(leaf), tree.root, ec.fr_to_bytes(new % R), proof)
+        assert not ctx.verify_path(vk, tree.path(leaves[0]), tree.root, vals[0], proofs[0])
     finally:
         tree.close()
 
