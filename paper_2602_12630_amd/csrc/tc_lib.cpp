@@ -100,6 +100,11 @@ struct tc_tree {
 struct tc_vk {
     int m = 0;
     uint8_t tau[4][32];
+    /* tau_i - (kappa + 1), split for the curve endomorphism, for the positions of small node shapes:
+     * the steps of a tree path ask for the same few scalars over and over */
+    static const uint32_t SPLIT_CACHE = 64;
+    uint32_t k1[4][SPLIT_CACHE][4];
+    uint32_t k2[4][SPLIT_CACHE][4];
 };
 
 /* ======================================================================================= */
@@ -1113,21 +1118,6 @@ extern "C" int tc_open(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, in
 /* ======================================================================================= */
 /* Ver                                                                                     */
 /* ======================================================================================= */
-extern "C" int tc_vk_from_trapdoor(const uint8_t* tau, int m, tc_vk** out) {
-    if (!tau || !out || m < 1 || m > TC_MAX_ORDER) return TC_ERR_ARG;
-    *out = nullptr;
-    uint32_t w[8];
-    for (int j = 0; j < m; ++j)
-        if (!fr_bytes_canonical(tau + 32 * j, w)) return TC_ERR_RANGE;
-    tc_vk* vk = new (std::nothrow) tc_vk();
-    if (!vk) return TC_ERR_NOMEM;
-    vk->m = m;
-    memcpy(vk->tau, tau, 32 * (size_t)m);
-    *out = vk;
-    return TC_OK;
-}
-extern "C" void tc_vk_destroy(tc_vk* vk) { delete vk; }
-
 /* k = k2 * lambda + k1 with 0 <= k1 < lambda < 2^128 (k < r < lambda^2 + lambda + 1, so k2 < 2^128) */
 static void glv_split(const uint32_t k[8], uint32_t k1[4], uint32_t k2[4]) {
     typedef unsigned __int128 u128;
@@ -1146,13 +1136,39 @@ static void glv_split(const uint32_t k[8], uint32_t k1[4], uint32_t k2[4]) {
         k2[i] = (uint32_t)(q >> (32 * i));
     }
 }
+/* k = tau_i - (kappa + 1) mod r, split */
+static void step_scalar(const tc_vk* vk, int i, uint32_t kappa, uint32_t k1[4], uint32_t k2[4]) {
+    uint32_t w[8];
+    memcpy(w, vk->tau[i], 32);
+    fr_t k = fe_to_plain(fr_sub(fe_from_limbs<FrParams>(w), fe_from_u32<FrParams>(kappa + 1u)));
+    glv_split(k.l, k1, k2);
+}
+extern "C" int tc_vk_from_trapdoor(const uint8_t* tau, int m, tc_vk** out) {
+    if (!tau || !out || m < 1 || m > TC_MAX_ORDER) return TC_ERR_ARG;
+    *out = nullptr;
+    uint32_t w[8];
+    for (int j = 0; j < m; ++j)
+        if (!fr_bytes_canonical(tau + 32 * j, w)) return TC_ERR_RANGE;
+    tc_vk* vk = new (std::nothrow) tc_vk();
+    if (!vk) return TC_ERR_NOMEM;
+    vk->m = m;
+    memcpy(vk->tau, tau, 32 * (size_t)m);
+    for (int i = 0; i < m; ++i)
+        for (uint32_t kappa = 0; kappa < tc_vk::SPLIT_CACHE; ++kappa) step_scalar(vk, i, kappa, vk->k1[i][kappa], vk->k2[i][kappa]);
+    *out = vk;
+    return TC_OK;
+}
+extern "C" void tc_vk_destroy(tc_vk* vk) { delete vk; }
+
 /* fills the split scalars of a step: k_i = tau_i - (kappa_i + 1) mod r */
 static void fill_step_scalars(const tc_vk* vk, const uint32_t* kappa, VerifyStep* st) {
     for (int i = 0; i < st->m; ++i) {
-        uint32_t w[8];
-        memcpy(w, vk->tau[i], 32);
-        fr_t k = fe_to_plain(fr_sub(fe_from_limbs<FrParams>(w), fe_from_u32<FrParams>(kappa[i] + 1u)));
-        glv_split(k.l, st->k1[i], st->k2[i]);
+        if (kappa[i] < tc_vk::SPLIT_CACHE) {
+            memcpy(st->k1[i], vk->k1[i][kappa[i]], 16);
+            memcpy(st->k2[i], vk->k2[i][kappa[i]], 16);
+        } else {
+            step_scalar(vk, i, kappa[i], st->k1[i], st->k2[i]);
+        }
     }
 }
 
