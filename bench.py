@@ -305,7 +305,7 @@ def c3_forward(ctx, T, torch, node_srs, tau, reps=3):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=120)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--lib", default=None, help="path of an alternative libtc.so (experiments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
