@@ -253,6 +253,7 @@ def c3_forward(ctx, T, torch, node_srs, tau, reps=3):
     vk = ctx.vk_from_trapdoor(tau)
     open_ms = verify_ms = public_ms = None
     ctx.profile_read(T.binding.TC_PROF_BUCKET_ACC)      # drop what the C2 steps left
+    ctx.profile_units(T.binding.TC_PROF_BUCKET_ACC)
     ctx.profile(True)
     for rep in range(reps + 1):
         t0 = time.perf_counter()
@@ -263,6 +264,7 @@ def c3_forward(ctx, T, torch, node_srs, tau, reps=3):
         dt = time.perf_counter() - t0
         if rep == reps:
             acc_ms, acc_launches = ctx.profile_read(T.binding.TC_PROF_BUCKET_ACC)    # the builds only
+            acc_executed = ctx.profile_units(T.binding.TC_PROF_BUCKET_ACC) / max(acc_launches, 1)
             ctx.profile(False)
             # the configuration's 64 random openings down to tensor entries, then their verification
             t1 = time.perf_counter()
@@ -294,6 +296,8 @@ def c3_forward(ctx, T, torch, node_srs, tau, reps=3):
     ms = times[len(times) // 2]
     return {"ms": ms, "roofline": {"bound": "alu", "kernel": "AccAffine (all 96 leaf commitments in one launch)",
                                    "kernel_ms": acc_kernel_ms, "launches": acc_launches, "mixed_additions_per_launch": nonzero,
+                                   "mixed_additions_executed_per_launch": acc_executed,
+                                   "frac_executed": acc_executed * FP_MULS_PER_MIXED_ADD * MADS_PER_FP_MUL / (acc_kernel_ms * 1e-3) / PEAK_MADS_PER_S,
                                    "achieved": achieved / 1e12, "peak": PEAK_MADS_PER_S / 1e12, "frac": achieved / PEAK_MADS_PER_S,
                                    "unit": "T 32x32->64 multiply-add/s"}, "elements": total, "elements_per_s": total / (ms * 1e-3), "tensors": len(xs), "reps": reps,
             "open_64_paths_ms": open_ms, "verify_64_paths_ms": verify_ms,
@@ -506,6 +510,7 @@ def main():
     # algorithmic work per launch = one mixed addition per non-zero entry.
     nonzero = int(np.count_nonzero(q))
     acc_ms, acc_launches = ctx.profile_read(T.binding.TC_PROF_BUCKET_ACC)
+    acc_executed = ctx.profile_units(T.binding.TC_PROF_BUCKET_ACC) / max(acc_launches, 1)
     node_ms, node_launches = ctx.profile_read(T.binding.TC_PROF_NODE_COMMIT)
     upper_ms, upper_launches = ctx.profile_read(T.binding.TC_PROF_NODE_COMMIT_UPPER)
     chain_ms, chain_launches = ctx.profile_read(T.binding.TC_PROF_VERIFY_CHAIN)
@@ -541,6 +546,10 @@ def main():
                      "traffic_unit": "HBM bytes per launch (fetch + write)",
                      "kernel": "AccAffine (bucket accumulation of tc_commit)", "kernel_ms": kern_ms,
                      "launches": acc_launches, "mixed_additions_per_launch": nonzero,
+                     # of the one addition per non-zero entry that the method needs, the launch itself executes
+                     # this many (the first entry of a sub-run is a copy; the passes after it add the sub-runs up)
+                     "mixed_additions_executed_per_launch": acc_executed,
+                     "frac_executed": acc_executed * FP_MULS_PER_MIXED_ADD * MADS_PER_FP_MUL / (kern_ms * 1e-3) / PEAK_MADS_PER_S,
                      "node_commit_kernel_ms": node_ms / max(node_launches, 1)},
     }
     # the other long launches of a step, with the same accounting (a squaring counted as a product); the upper

@@ -94,6 +94,10 @@ int tc_ctx_sync(tc_ctx* ctx);
 #define TC_PROF_KINDS 4
 int tc_ctx_profile(tc_ctx* ctx, int enable);
 int tc_ctx_profile_read(tc_ctx* ctx, int kind, double* total_ms, uint64_t* launches);
+/* Work that the bracketed launches of a kind performed since the last call (then reset).  TC_PROF_BUCKET_ACC: the
+ * mixed additions executed -- the non-zero terms minus the sub-runs they were cut into (the first term of a
+ * sub-run is copied, and the sums of the sub-runs are added up by the passes that follow); 0 for the other kinds. */
+int tc_ctx_profile_units(tc_ctx* ctx, int kind, uint64_t* units);
 
 /* ---- Setup (Def. 4.1, Setup) -- test-only trusted setup from a known trapdoor -- */
 

@@ -77,6 +77,7 @@ def load_library(path=None):
         "tc_ctx_profile": (ctypes.c_int, [vp, ctypes.c_int]),
         "tc_ctx_profile_read": (ctypes.c_int, [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                                ctypes.POINTER(ctypes.c_uint64)]),
+        "tc_ctx_profile_units": (ctypes.c_int, [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64)]),
         "tc_setup_from_trapdoor": (ctypes.c_int, [vp, u8p, ctypes.c_int, u32p, ctypes.c_uint32, ctypes.POINTER(vp)]),
         "tc_srs_destroy": (None, [vp]),
         "tc_srs_size": (ctypes.c_uint64, [vp, ctypes.c_int]),
@@ -353,6 +354,11 @@ class Context:
         ms, n = ctypes.c_double(), ctypes.c_uint64()
         self._check(self.lib.tc_ctx_profile_read(self.handle, kind, ctypes.byref(ms), ctypes.byref(n)))
         return ms.value, int(n.value)
+
+    def profile_units(self, kind):
+        units = ctypes.c_uint64()
+        self._check(self.lib.tc_ctx_profile_units(self.handle, kind, ctypes.byref(units)))
+        return int(units.value)
 
     def close(self):
         for vk in self._vk.values():

@@ -58,6 +58,7 @@ struct tc_ctx {
     g1_affine* gtable = nullptr;       /* fixed-base table of the generator */
     bool profiling = false;
     std::vector<std::pair<rt::event_t, rt::event_t>> prof[TC_PROF_KINDS];
+    uint64_t prof_units[TC_PROF_KINDS] = {0, 0, 0, 0};
 };
 
 struct tc_srs {
@@ -319,6 +320,13 @@ extern "C" int tc_ctx_profile_read(tc_ctx* ctx, int kind, double* total_ms, uint
     *total_ms = tot;
     *launches = ctx->prof[kind].size();
     ctx->prof[kind].clear();
+    return TC_OK;
+}
+extern "C" int tc_ctx_profile_units(tc_ctx* ctx, int kind, uint64_t* units) {
+    if (!ctx) return TC_ERR_ARG;
+    if (kind < 0 || kind >= TC_PROF_KINDS || !units) return fail(ctx, TC_ERR_ARG, "bad argument");
+    *units = ctx->prof_units[kind];
+    ctx->prof_units[kind] = 0;
     return TC_OK;
 }
 extern "C" const char* tc_last_error(const tc_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
@@ -850,7 +858,13 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     }
 
     /* Middle passes shrink the per-bucket partial count by L2 until at most L2 remain. */
+    uint32_t acc_terms = 0, acc_lanes = 0;             /* non-zero digits and sub-runs of the first pass (profiling only) */
+    if (ctx->profiling) {
+        RT(rt::memcpy_d2h(&acc_terms, tot_a + nchunks, 4, ctx->stream));
+        RT(rt::memcpy_d2h(&acc_lanes, tot_b + nchunks, 4, ctx->stream));
+    }
     TRY(ctx_sync(ctx));
+    if (ctx->profiling && acc_terms >= acc_lanes) ctx->prof_units[TC_PROF_BUCKET_ACC] += acc_terms - acc_lanes;
     if (max_count > max_items) return fail(ctx, TC_ERR_STATE, "internal: bucket count exceeds the term count");
     uint64_t worst = ((uint64_t)max_count + L1 - 1) / L1;
     g1_xyzz *cur = bufA, *nxt = bufB;
