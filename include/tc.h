@@ -140,6 +140,22 @@ int tc_commit(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, int dtype, 
 int tc_commit_batch(tc_ctx* ctx, int count, const tc_srs* const* srs, const void* const* d_scalars,
                     const int* dtype, uint8_t* out_g1);
 
+/* tc_commit for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  The same commitment by the same kernels, but this call allocates nothing (no device memory,
+ * no pinned memory, no events), reads nothing back and never waits for the stream: every intermediate lives in a
+ * static device array of TC_STATIC_SCRATCH_BYTES that is part of the library (each GPU the library runs on holds
+ * its copy until the process ends), and the canonical commitment is written to d_out_g1, a DEVICE buffer of 96
+ * bytes (4-byte aligned) that is valid once the context's stream has reached this point.
+ * Limits: dtype TC_I8 or TC_I16; at most TC_STATIC_MAX_TERMS entries (TC_ERR_SHAPE beyond that).
+ * All contexts on one GPU share that GPU's array, which keeps the last call's contents: calls that overlap on one
+ * GPU (different streams, different threads) race and must be serialised by the caller. */
+#define TC_STATIC_MAX_TERMS (1u << 18)
+#define TC_STATIC_SCRATCH_BYTES (32u << 20)
+int tc_commit_static(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, int dtype, void* d_out_g1);
+/* Number of allocations and releases of device or pinned host memory that the library has asked the HIP runtime
+ * for since it was loaded (all contexts): a test hook for the promise above. */
+uint64_t tc_alloc_calls(void);
+
 /* ---- Open (Def. 4.1, Open; Algorithm 1 in evaluation form) ----------------------- */
 
 /* Opens T at grid position kappa: y = T[kappa] and pi_i = g^{q_i(tau)}, i = 1..m, with

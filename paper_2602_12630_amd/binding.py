@@ -15,6 +15,7 @@ TC_INTERP_NEWTON, TC_INTERP_GREGORY, TC_INTERP_BARYCENTRIC = 0, 1, 2
 TC_LEAF_ENTRIES, TC_LEAF_TENSORS = 0, 1
 TC_PROF_BUCKET_ACC, TC_PROF_NODE_COMMIT, TC_PROF_NODE_COMMIT_UPPER, TC_PROF_VERIFY_CHAIN = 0, 1, 2, 3
 TC_MAX_ORDER, TC_MAX_STEPS = 4, 16
+TC_STATIC_MAX_TERMS, TC_STATIC_SCRATCH_BYTES = 1 << 18, 32 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ERR_NAMES = {-1: "TC_ERR_ARG", -2: "TC_ERR_SHAPE", -3: "TC_ERR_RANGE", -4: "TC_ERR_NOMEM", -5: "TC_ERR_HIP",
@@ -86,6 +87,8 @@ def load_library(path=None):
         "tc_commit": (ctypes.c_int, [vp, vp, vp, ctypes.c_int, vp]),
         "tc_commit_batch": (ctypes.c_int, [vp, ctypes.c_int, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                            ctypes.POINTER(ctypes.c_int), vp]),
+        "tc_commit_static": (ctypes.c_int, [vp, vp, vp, ctypes.c_int, vp]),
+        "tc_alloc_calls": (ctypes.c_uint64, []),
         "tc_open": (ctypes.c_int, [vp, vp, vp, ctypes.c_int, u32p, vp, vp]),
         "tc_vk_from_trapdoor": (ctypes.c_int, [u8p, ctypes.c_int, ctypes.POINTER(vp)]),
         "tc_vk_destroy": (None, [vp]),
@@ -392,6 +395,13 @@ class Context:
         c = (ctypes.c_int * max(n, 1))(*dtypes)
         self._check(self.lib.tc_commit_batch(self.handle, n, a, b, c, out))
         return [out.raw[96 * i : 96 * (i + 1)] for i in range(n)]
+
+    def commit_static(self, srs, scalars, dtype, out):
+        """The commitment without any allocation; `out` is a device buffer of 96 bytes, written asynchronously."""
+        self._check(self.lib.tc_commit_static(self.handle, srs.handle, _ptr(scalars), dtype, _ptr(out)))
+
+    def alloc_calls(self):
+        return int(self.lib.tc_alloc_calls())
 
     def open(self, srs, scalars, dtype, kappa):
         y = ctypes.create_string_buffer(32)

@@ -33,6 +33,15 @@ struct Fill32 {
     TC_DEV void operator()(uint32_t t) const { dst[t] = value; }
 };
 
+/* a few words from the kernel's arguments to device memory (lane i writes word i) */
+struct PokeWords {
+    static constexpr uint32_t MAXW = 12;
+    uint32_t* dst;
+    uint32_t n;
+    uint32_t w[MAXW];
+    TC_DEV void operator()(uint32_t t) const { dst[t] = w[t]; }
+};
+
 /* fp16 -> int16 by one float multiply, round-half-even, clamp; or pass-through copies */
 struct EncodeF16 {
     const uint16_t* src;

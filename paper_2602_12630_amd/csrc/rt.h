@@ -17,15 +17,27 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
+
+namespace tc {
+namespace rt {
+/* every allocation or release of device or pinned host memory that the library asks the runtime for */
+inline std::atomic<uint64_t>& alloc_calls() {
+    static std::atomic<uint64_t> n{0};
+    return n;
+}
+}  // namespace rt
+}  // namespace tc
+
 #if defined(TC_HOST_EMU)
 
 namespace tc {
 namespace rt {
 typedef void* stream_t;
-inline int dev_malloc(void** p, size_t n) { *p = malloc(n ? n : 1); return *p ? 0 : 2; }
-inline int dev_free(void* p) { free(p); return 0; }
-inline int host_pinned_malloc(void** p, size_t n) { *p = malloc(n ? n : 1); return *p ? 0 : 2; }
-inline int host_pinned_free(void* p) { free(p); return 0; }
+inline int dev_malloc(void** p, size_t n) { ++alloc_calls(); *p = malloc(n ? n : 1); return *p ? 0 : 2; }
+inline int dev_free(void* p) { ++alloc_calls(); free(p); return 0; }
+inline int host_pinned_malloc(void** p, size_t n) { ++alloc_calls(); *p = malloc(n ? n : 1); return *p ? 0 : 2; }
+inline int host_pinned_free(void* p) { ++alloc_calls(); free(p); return 0; }
 inline int memcpy_h2d(void* d, const void* s, size_t n, stream_t) { memcpy(d, s, n); return 0; }
 inline int memcpy_d2h(void* d, const void* s, size_t n, stream_t) { memcpy(d, s, n); return 0; }
 inline int memcpy_d2d(void* d, const void* s, size_t n, stream_t) { memmove(d, s, n); return 0; }
@@ -64,10 +76,10 @@ __global__ __launch_bounds__(BLOCK) void kernel(const F f, uint32_t n) {
 
 namespace rt {
 typedef hipStream_t stream_t;
-inline int dev_malloc(void** p, size_t n) { return (int)hipMalloc(p, n ? n : 1); }
-inline int dev_free(void* p) { return (int)hipFree(p); }
-inline int host_pinned_malloc(void** p, size_t n) { return (int)hipHostMalloc(p, n ? n : 1, hipHostMallocDefault); }
-inline int host_pinned_free(void* p) { return (int)hipHostFree(p); }
+inline int dev_malloc(void** p, size_t n) { ++alloc_calls(); return (int)hipMalloc(p, n ? n : 1); }
+inline int dev_free(void* p) { ++alloc_calls(); return (int)hipFree(p); }
+inline int host_pinned_malloc(void** p, size_t n) { ++alloc_calls(); return (int)hipHostMalloc(p, n ? n : 1, hipHostMallocDefault); }
+inline int host_pinned_free(void* p) { ++alloc_calls(); return (int)hipHostFree(p); }
 inline int memcpy_h2d(void* d, const void* s, size_t n, stream_t st) { return (int)hipMemcpyAsync(d, s, n, hipMemcpyHostToDevice, st); }
 inline int memcpy_d2h(void* d, const void* s, size_t n, stream_t st) { return (int)hipMemcpyAsync(d, s, n, hipMemcpyDeviceToHost, st); }
 inline int memcpy_d2d(void* d, const void* s, size_t n, stream_t st) { return (int)hipMemcpyAsync(d, s, n, hipMemcpyDeviceToDevice, st); }

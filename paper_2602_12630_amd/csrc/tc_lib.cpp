@@ -12,6 +12,7 @@
 #include <string>
 #include <thread>
 #include <memory>
+#include <mutex>
 #include <vector>
 
 #include "../../include/tc.h"
@@ -21,6 +22,37 @@
 
 using namespace tc;
 
+/* Scratch memory of the entry point that allocates nothing (tc_commit_static): one array per GPU, part of the
+ * code object, held until the process ends.  In host code the array's name is only a stand-in: the address on a
+ * device comes from hipGetSymbolAddress, once per device, and only that pointer is ever handed to a kernel. */
+#if defined(TC_HOST_EMU)
+alignas(256) static uint8_t tc_static_scratch[TC_STATIC_SCRATCH_BYTES];
+#else
+static __device__ __align__(256) uint8_t tc_static_scratch[TC_STATIC_SCRATCH_BYTES];
+#endif
+static const int MAX_DEVICES = 64;
+static std::mutex g_scratch_lock;
+static uint8_t* g_scratch_ptr[MAX_DEVICES];        /* per device: where its copy of the array lives */
+/* address of the static scratch on `device`, which must be the current device */
+static int static_scratch_address(int device, uint8_t** out) {
+    *out = nullptr;
+    if (device < 0 || device >= MAX_DEVICES) return 1;
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (!g_scratch_ptr[device]) {
+#if defined(TC_HOST_EMU)
+        g_scratch_ptr[device] = tc_static_scratch;
+#else
+        void* ptr = nullptr;
+        int e = (int)hipGetSymbolAddress(&ptr, HIP_SYMBOL(tc_static_scratch));
+        if (e) return e;
+        if (!ptr) return 1;
+        g_scratch_ptr[device] = (uint8_t*)ptr;
+#endif
+    }
+    *out = g_scratch_ptr[device];
+    return 0;
+}
+
 /* ======================================================================================= */
 /* objects                                                                                 */
 /* ======================================================================================= */
@@ -28,6 +60,7 @@ struct Arena {
     uint8_t* base = nullptr;
     size_t cap = 0, off = 0, demand = 0;
     std::vector<void*> extra;
+    bool fixed = false;            /* a block that never grows: a request that does not fit fails instead of allocating */
 };
 
 /* The level arrays of the last destroyed tree, kept for the next build: allocating and freeing device memory
@@ -54,6 +87,9 @@ struct tc_ctx {
     rt::stream_t stream = nullptr;
     std::string err;
     Arena ws;
+    Arena ws_static;                   /* the device's static scratch array, for the entry point that allocates nothing */
+    Arena* wsp = &ws;                  /* the workspace that the current call draws from */
+    bool static_mode = false;          /* set for the duration of such a call: no allocation, no wait for the stream */
     Staging staging;
     g1_affine* gtable = nullptr;       /* fixed-base table of the generator */
     bool profiling = false;
@@ -162,6 +198,23 @@ static int h2d(tc_ctx* ctx, void* dst, const void* src, size_t bytes) {
     return TC_OK;
 }
 
+/* The same for a few words when the call may not allocate (the staging buffer may have to grow) nor wait: the
+ * words travel as kernel arguments, one launch per PokeWords::MAXW of them. */
+static int upload_small(tc_ctx* ctx, void* dst, const void* src, size_t bytes) {
+    if (!ctx->static_mode) return h2d(ctx, dst, src, bytes);
+    if (bytes % 4) return fail(ctx, TC_ERR_STATE, "internal: upload not a whole number of words");
+    size_t words = bytes / 4;
+    for (size_t i = 0; i < words; i += PokeWords::MAXW) {
+        PokeWords k;
+        k.dst = (uint32_t*)dst + i;
+        k.n = (uint32_t)std::min<size_t>(PokeWords::MAXW, words - i);
+        memset(k.w, 0, sizeof k.w);
+        memcpy(k.w, (const uint8_t*)src + 4 * i, 4 * (size_t)k.n);
+        RT(rt::launch<64>(k.n, ctx->stream, k));
+    }
+    return TC_OK;
+}
+
 /* Workspace: a slab that grows to the largest demand seen; within one API call allocations
  * are bump-pointer, overflow goes to one-off blocks released at the next reset. */
 static int ws_reset(tc_ctx* ctx) {
@@ -187,7 +240,7 @@ static int ws_reset(tc_ctx* ctx) {
     return TC_OK;
 }
 static void* ws_alloc(tc_ctx* ctx, size_t bytes) {
-    Arena& A = ctx->ws;
+    Arena& A = *ctx->wsp;
     bytes = align_up(bytes ? bytes : 1, 256);
     A.demand += bytes;
     if (A.off + bytes <= A.cap) {
@@ -195,6 +248,7 @@ static void* ws_alloc(tc_ctx* ctx, size_t bytes) {
         A.off += bytes;
         return p;
     }
+    if (A.fixed) return nullptr;
     void* p = nullptr;
     if (rt::dev_malloc(&p, bytes) != 0) return nullptr;
     A.extra.push_back(p);
@@ -249,26 +303,41 @@ static void fr_batch_inverse(std::vector<fr_t>& v) {       /* every entry non-ze
 /* context                                                                                 */
 /* ======================================================================================= */
 extern "C" int tc_ctx_create(tc_ctx** out, int device, void* hip_stream) {
-    if (!out) return TC_ERR_ARG;
-    *out = nullptr;
-    tc_ctx* ctx = new (std::nothrow) tc_ctx();
-    if (!ctx) return TC_ERR_NOMEM;
-    ctx->device = device;
-    ctx->stream = (rt::stream_t)hip_stream;
-    int e = rt::set_device(device);
-    if (e) {
-        delete ctx;
-        return TC_ERR_HIP;
+    try {
+        if (!out) return TC_ERR_ARG;
+        *out = nullptr;
+        tc_ctx* ctx = new (std::nothrow) tc_ctx();
+        if (!ctx) return TC_ERR_NOMEM;
+        ctx->device = device;
+        ctx->stream = (rt::stream_t)hip_stream;
+        int e = rt::set_device(device);
+        if (e) {
+            delete ctx;
+            return TC_ERR_HIP;
+        }
+        /* probe: a tiny allocation proves that a device is really there */
+        void* p = nullptr;
+        if (rt::dev_malloc(&p, 256) != 0) {
+            delete ctx;
+            return TC_ERR_HIP;
+        }
+        rt::dev_free(p);
+        /* this device's static scratch, for tc_commit_static */
+        uint8_t* scratch = nullptr;
+        if (static_scratch_address(device, &scratch) != 0) {
+            delete ctx;
+            return TC_ERR_HIP;
+        }
+        ctx->ws_static.base = scratch;
+        ctx->ws_static.cap = TC_STATIC_SCRATCH_BYTES;
+        ctx->ws_static.fixed = true;
+        *out = ctx;
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return TC_ERR_NOMEM;
+    } catch (...) {
+        return TC_ERR_STATE;
     }
-    /* probe: a tiny allocation proves that a device is really there */
-    void* p = nullptr;
-    if (rt::dev_malloc(&p, 256) != 0) {
-        delete ctx;
-        return TC_ERR_HIP;
-    }
-    rt::dev_free(p);
-    *out = ctx;
-    return TC_OK;
 }
 extern "C" void tc_ctx_destroy(tc_ctx* ctx) {
     if (!ctx) return;
@@ -289,51 +358,75 @@ extern "C" void tc_ctx_destroy(tc_ctx* ctx) {
 /* measurement hooks */
 static void prof_begin(tc_ctx* ctx, int kind, rt::event_t* a, rt::event_t* b) {
     *a = *b = nullptr;
-    if (!ctx->profiling) return;
+    if (!ctx->profiling || ctx->static_mode) return;
     if (rt::event_create(a) || rt::event_create(b)) return;
     rt::event_record(*a, ctx->stream);
     (void)kind;
 }
 static void prof_end(tc_ctx* ctx, int kind, rt::event_t a, rt::event_t b) {
-    if (!ctx->profiling || !a || !b) return;
+    if (!ctx->profiling || ctx->static_mode || !a || !b) return;
     rt::event_record(b, ctx->stream);
     ctx->prof[kind].push_back({a, b});
 }
 extern "C" int tc_ctx_profile(tc_ctx* ctx, int enable) {
-    if (!ctx) return TC_ERR_ARG;
-    ctx->profiling = enable != 0;
-    return TC_OK;
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        ctx->profiling = enable != 0;
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
 }
 extern "C" int tc_ctx_profile_read(tc_ctx* ctx, int kind, double* total_ms, uint64_t* launches) {
-    if (!ctx) return TC_ERR_ARG;
-    if (kind < 0 || kind >= TC_PROF_KINDS || !total_ms || !launches) return fail(ctx, TC_ERR_ARG, "bad argument");
-    RT(rt::set_device(ctx->device));
-    TRY(ctx_sync(ctx));
-    double tot = 0;
-    for (auto& pr : ctx->prof[kind]) {
-        float ms = 0;
-        RT(rt::event_elapsed_ms(pr.first, pr.second, &ms));
-        tot += ms;
-        rt::event_destroy(pr.first);
-        rt::event_destroy(pr.second);
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (kind < 0 || kind >= TC_PROF_KINDS || !total_ms || !launches) return fail(ctx, TC_ERR_ARG, "bad argument");
+        RT(rt::set_device(ctx->device));
+        TRY(ctx_sync(ctx));
+        double tot = 0;
+        for (auto& pr : ctx->prof[kind]) {
+            float ms = 0;
+            RT(rt::event_elapsed_ms(pr.first, pr.second, &ms));
+            tot += ms;
+            rt::event_destroy(pr.first);
+            rt::event_destroy(pr.second);
+        }
+        *total_ms = tot;
+        *launches = ctx->prof[kind].size();
+        ctx->prof[kind].clear();
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
     }
-    *total_ms = tot;
-    *launches = ctx->prof[kind].size();
-    ctx->prof[kind].clear();
-    return TC_OK;
 }
 extern "C" int tc_ctx_profile_units(tc_ctx* ctx, int kind, uint64_t* units) {
-    if (!ctx) return TC_ERR_ARG;
-    if (kind < 0 || kind >= TC_PROF_KINDS || !units) return fail(ctx, TC_ERR_ARG, "bad argument");
-    *units = ctx->prof_units[kind];
-    ctx->prof_units[kind] = 0;
-    return TC_OK;
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (kind < 0 || kind >= TC_PROF_KINDS || !units) return fail(ctx, TC_ERR_ARG, "bad argument");
+        *units = ctx->prof_units[kind];
+        ctx->prof_units[kind] = 0;
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
 }
 extern "C" const char* tc_last_error(const tc_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 extern "C" int tc_ctx_sync(tc_ctx* ctx) {
-    if (!ctx) return TC_ERR_ARG;
-    TRY(ctx_sync(ctx));
-    return TC_OK;
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        TRY(ctx_sync(ctx));
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
 }
 
 /* ======================================================================================= */
@@ -437,180 +530,222 @@ extern "C" uint64_t tc_srs_size(const tc_srs* srs, int first_axis) {
 
 static const uint32_t FB_MAX_BASES = 64;
 
-extern "C" int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, const uint32_t* shape, uint32_t flags,
-                                      tc_srs** out) {
-    if (!ctx || !tau || !out) return ctx ? fail(ctx, TC_ERR_ARG, "null argument") : TC_ERR_ARG;
-    *out = nullptr;
-    uint64_t total = 0;
-    if (!shape_ok(m, shape, &total)) return fail(ctx, TC_ERR_SHAPE, "bad shape");
-    if ((flags & TC_SRS_MONOMIAL) && flags != TC_SRS_MONOMIAL) return fail(ctx, TC_ERR_ARG, "the monomial SRS takes no other flag");
-    if ((flags & TC_SRS_FIXED_BASE) && total > FB_MAX_BASES)
-        return fail(ctx, TC_ERR_SHAPE, "fixed-base tables are limited to shapes with at most 64 entries");
-    RT(rt::set_device(ctx->device));
-    TRY(ws_reset(ctx));
-
-    /* per-axis Lagrange values at tau_j (barycentric form, App. C) and the tables Open needs */
-    std::vector<fr_t> ell_all, tab_all;
-    uint32_t ell_off[4] = {0, 0, 0, 0};
+/* What Open needs per axis, public constants of the grid {1..d}: 1 / j, the barycentric weights of App. C
+ * beta_i = 1 / prod_(k != i) (zeta_i - zeta_k) = (-1)^(d-1-i) / (i! (d-1-i)!), and 1 / beta_i (Montgomery form). */
+static void axis_constants(uint32_t d, std::vector<fr_t>& inv_int, std::vector<fr_t>& beta, std::vector<fr_t>& beta_inv) {
+    std::vector<fr_t> fact(d);
+    inv_int.resize(d);
+    beta.resize(d);
+    beta_inv.resize(d);
+    fact[0] = fe_one<FrParams>();
+    for (uint32_t i = 1; i < d; ++i) fact[i] = fr_mul(fact[i - 1], fe_from_u32<FrParams>(i));
+    for (uint32_t i = 0; i < d; ++i) {
+        fr_t den = fr_mul(fact[i], fact[d - 1 - i]);
+        if ((d - 1 - i) & 1u) den = fr_neg(den);
+        beta_inv[i] = den;
+        beta[i] = den;
+        inv_int[i] = fe_from_u32<FrParams>(i ? i : 1);
+    }
+    fr_batch_inverse(beta);
+    fr_batch_inverse(inv_int);
+}
+/* puts those tables of every axis of srs->shape on the device (srs->axis_mem, srs->ax) */
+static int srs_upload_axis_tables(tc_ctx* ctx, tc_srs* srs) {
+    std::vector<fr_t> tab_all;
     size_t tab_off[4] = {0, 0, 0, 0};
-    for (int j = 0; j < m; ++j) {
-        uint32_t w[8];
-        if (!fr_bytes_canonical(tau + 32 * j, w)) return fail(ctx, TC_ERR_RANGE, "trapdoor is not a canonical Fr element");
-        bool small = true;
-        for (int i = 1; i < 8; ++i) small = small && w[i] == 0;
-        if (small && w[0] <= shape[j]) return fail(ctx, TC_ERR_RANGE, "trapdoor is zero or lies on the grid");
-        uint32_t d = shape[j];
-        fr_t t = fe_from_limbs<FrParams>(w);
-        /* beta_i = 1 / (i! (d-1-i)! (-1)^(d-1-i)) */
-        std::vector<fr_t> fact(d), beta(d), beta_inv(d), diff(d), inv_int(d);
-        fact[0] = fe_one<FrParams>();
-        for (uint32_t i = 1; i < d; ++i) fact[i] = fr_mul(fact[i - 1], fe_from_u32<FrParams>(i));
-        for (uint32_t i = 0; i < d; ++i) {
-            fr_t den = fr_mul(fact[i], fact[d - 1 - i]);
-            if ((d - 1 - i) & 1u) den = fr_neg(den);
-            beta_inv[i] = den;
-            beta[i] = den;
-            diff[i] = fr_sub(t, fe_from_u32<FrParams>(i + 1));
-            inv_int[i] = fe_from_u32<FrParams>(i ? i : 1);
-        }
-        fr_batch_inverse(beta);
-        std::vector<fr_t> diff_inv = diff;
-        fr_batch_inverse(diff_inv);
-        fr_batch_inverse(inv_int);
-        fr_t sum = fe_zero<FrParams>();
-        std::vector<fr_t> term(d);
-        for (uint32_t i = 0; i < d; ++i) {
-            term[i] = fr_mul(beta[i], diff_inv[i]);
-            sum = fr_add(sum, term[i]);
-        }
-        fr_t sum_inv = fe_inv_fermat<FrParams>(sum);
-        ell_off[j] = (uint32_t)ell_all.size();
-        if (flags & TC_SRS_MONOMIAL) {
-            /* the same generator kernel multiplies per-axis factors: powers of tau_j give the monomial SRS */
-            fr_t pw = fe_one<FrParams>();
-            for (uint32_t i = 0; i < d; ++i) {
-                ell_all.push_back(pw);
-                pw = fr_mul(pw, t);
-            }
-        } else {
-            for (uint32_t i = 0; i < d; ++i) ell_all.push_back(fr_mul(term[i], sum_inv));
-        }
+    for (int j = 0; j < srs->m; ++j) {
+        std::vector<fr_t> inv_int, beta, beta_inv;
+        axis_constants(srs->shape[j], inv_int, beta, beta_inv);
         tab_off[j] = tab_all.size();
         tab_all.insert(tab_all.end(), inv_int.begin(), inv_int.end());
         tab_all.insert(tab_all.end(), beta.begin(), beta.end());
         tab_all.insert(tab_all.end(), beta_inv.begin(), beta_inv.end());
     }
-
-    TRY(ensure_gtable(ctx));
-    tc_srs* srs = new (std::nothrow) tc_srs();
-    if (!srs) return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
-    srs->m = m;
-    srs->flags = flags;
-    for (int j = 0; j < m; ++j) srs->shape[j] = shape[j];
-    int rc = TC_OK;
-    void* d_ell = nullptr;
-    do {
-        void* p = nullptr;
-        if (rt::dev_malloc(&p, tab_all.size() * sizeof(fr_t)) != 0 || rt::dev_malloc(&d_ell, ell_all.size() * sizeof(fr_t)) != 0) {
-            if (p) rt::dev_free(p);
-            rc = fail(ctx, TC_ERR_NOMEM, "SRS table allocation failed");
-            break;
-        }
-        srs->axis_mem = (fr_t*)p;
-        int e = rt::memcpy_h2d(p, tab_all.data(), tab_all.size() * sizeof(fr_t), ctx->stream);
-        if (!e) e = rt::memcpy_h2d(d_ell, ell_all.data(), ell_all.size() * sizeof(fr_t), ctx->stream);
-        if (!e) e = rt::stream_sync(ctx->stream);
-        if (e) { rc = fail_hip(ctx, e, "SRS table upload"); break; }
-        for (int j = 0; j < m; ++j) {
-            uint32_t d = shape[j];
-            srs->ax[j].inv_int = srs->axis_mem + tab_off[j];
-            srs->ax[j].beta = srs->axis_mem + tab_off[j] + d;
-            srs->ax[j].beta_inv = srs->axis_mem + tab_off[j] + 2 * (size_t)d;
-        }
-        int last_axis = (flags & TC_SRS_SUFFIX) ? m - 1 : 0;
-        const uint64_t slab = 1ull << 20;
-        void* tmp = nullptr;
-        if (rt::dev_malloc(&tmp, (size_t)std::min<uint64_t>(slab, total) * sizeof(g1_xyzz)) != 0) {
-            rc = fail(ctx, TC_ERR_NOMEM, "SRS scratch allocation failed");
-            break;
-        }
-        for (int a = 0; a <= last_axis && rc == TC_OK; ++a) {
-            uint64_t na = 1;
-            for (int j = a; j < m; ++j) na *= shape[j];
-            srs->n[a] = na;
-            void* q = nullptr;
-            if (rt::dev_malloc(&q, (size_t)na * sizeof(g1_affine)) != 0) { rc = fail(ctx, TC_ERR_NOMEM, "SRS allocation failed"); break; }
-            srs->pts[a] = (g1_affine*)q;
-            SrsGen gen;
-            gen.shape.m = m;
-            for (int j = 0; j < 4; ++j) { gen.shape.d[j] = j < m ? shape[j] : 1; gen.ell_off[j] = ell_off[j]; }
-            gen.first_axis = a;
-            gen.ell = (const fr_t*)d_ell;
-            gen.gtable = ctx->gtable;
-            gen.out = (g1_xyzz*)tmp;
-            for (uint64_t i0 = 0; i0 < na && rc == TC_OK; i0 += slab) {
-                uint64_t cnt = std::min(slab, na - i0);
-                gen.i0 = i0;
-                e = rt::launch<64>(cnt, ctx->stream, gen);
-                if (e) { rc = fail_hip(ctx, e, "SrsGen"); break; }
-                rc = normalize(ctx, (g1_xyzz*)tmp, cnt, srs->pts[a] + i0);
-            }
-            if (rc == TC_OK && (flags & TC_SRS_FIXED_BASE)) rc = build_fixed_base_table(ctx, srs->pts[a], (uint32_t)na, &srs->fb[a]);
-        }
-        e = rt::stream_sync(ctx->stream);
-        if (e && rc == TC_OK) rc = fail_hip(ctx, e, "SRS generation");
-        rt::dev_free(tmp);
-    } while (0);
-    if (d_ell) rt::dev_free(d_ell);
-    if (rc != TC_OK) {
-        tc_srs_destroy(srs);
-        return rc;
+    void* p = nullptr;
+    if (rt::dev_malloc(&p, tab_all.size() * sizeof(fr_t)) != 0) return fail(ctx, TC_ERR_NOMEM, "SRS table allocation failed");
+    srs->axis_mem = (fr_t*)p;
+    int e = rt::memcpy_h2d(p, tab_all.data(), tab_all.size() * sizeof(fr_t), ctx->stream);
+    if (!e) e = rt::stream_sync(ctx->stream);         /* tab_all goes out of scope on return */
+    if (e) return fail_hip(ctx, e, "SRS table upload");
+    for (int j = 0; j < srs->m; ++j) {
+        uint32_t d = srs->shape[j];
+        srs->ax[j].inv_int = srs->axis_mem + tab_off[j];
+        srs->ax[j].beta = srs->axis_mem + tab_off[j] + d;
+        srs->ax[j].beta_inv = srs->axis_mem + tab_off[j] + 2 * (size_t)d;
     }
-    *out = srs;
     return TC_OK;
+}
+static bool srs_flags_ok(uint32_t flags) {
+    if (flags & ~(TC_SRS_SUFFIX | TC_SRS_FIXED_BASE | TC_SRS_MONOMIAL)) return false;
+    return !(flags & TC_SRS_MONOMIAL) || flags == TC_SRS_MONOMIAL;
+}
+
+extern "C" int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, const uint32_t* shape, uint32_t flags,
+                                      tc_srs** out) {
+    try {
+        if (!ctx || !tau || !out) return ctx ? fail(ctx, TC_ERR_ARG, "null argument") : TC_ERR_ARG;
+        *out = nullptr;
+        uint64_t total = 0;
+        if (!shape_ok(m, shape, &total)) return fail(ctx, TC_ERR_SHAPE, "bad shape");
+        if (!srs_flags_ok(flags)) return fail(ctx, TC_ERR_ARG, "unknown flag, or the monomial SRS combined with another flag");
+        if ((flags & TC_SRS_FIXED_BASE) && total > FB_MAX_BASES)
+            return fail(ctx, TC_ERR_SHAPE, "fixed-base tables are limited to shapes with at most 64 entries");
+        RT(rt::set_device(ctx->device));
+        TRY(ws_reset(ctx));
+
+        /* per-axis Lagrange values at tau_j (barycentric form, App. C) */
+        std::vector<fr_t> ell_all;
+        uint32_t ell_off[4] = {0, 0, 0, 0};
+        for (int j = 0; j < m; ++j) {
+            uint32_t w[8];
+            if (!fr_bytes_canonical(tau + 32 * j, w)) return fail(ctx, TC_ERR_RANGE, "trapdoor is not a canonical Fr element");
+            bool small = true;
+            for (int i = 1; i < 8; ++i) small = small && w[i] == 0;
+            if (small && w[0] <= shape[j]) return fail(ctx, TC_ERR_RANGE, "trapdoor is zero or lies on the grid");
+            uint32_t d = shape[j];
+            fr_t t = fe_from_limbs<FrParams>(w);
+            std::vector<fr_t> inv_int, beta, beta_inv, diff_inv(d), term(d);
+            axis_constants(d, inv_int, beta, beta_inv);
+            for (uint32_t i = 0; i < d; ++i) diff_inv[i] = fr_sub(t, fe_from_u32<FrParams>(i + 1));
+            fr_batch_inverse(diff_inv);
+            fr_t sum = fe_zero<FrParams>();
+            for (uint32_t i = 0; i < d; ++i) {
+                term[i] = fr_mul(beta[i], diff_inv[i]);
+                sum = fr_add(sum, term[i]);
+            }
+            fr_t sum_inv = fe_inv_fermat<FrParams>(sum);
+            ell_off[j] = (uint32_t)ell_all.size();
+            if (flags & TC_SRS_MONOMIAL) {
+                /* the same generator kernel multiplies per-axis factors: powers of tau_j give the monomial SRS */
+                fr_t pw = fe_one<FrParams>();
+                for (uint32_t i = 0; i < d; ++i) {
+                    ell_all.push_back(pw);
+                    pw = fr_mul(pw, t);
+                }
+            } else {
+                for (uint32_t i = 0; i < d; ++i) ell_all.push_back(fr_mul(term[i], sum_inv));
+            }
+        }
+
+        TRY(ensure_gtable(ctx));
+        tc_srs* srs = new (std::nothrow) tc_srs();
+        if (!srs) return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+        srs->m = m;
+        srs->flags = flags;
+        for (int j = 0; j < m; ++j) srs->shape[j] = shape[j];
+        int rc = TC_OK;
+        void* d_ell = nullptr;
+        do {
+            rc = srs_upload_axis_tables(ctx, srs);
+            if (rc) break;
+            if (rt::dev_malloc(&d_ell, ell_all.size() * sizeof(fr_t)) != 0) {
+                rc = fail(ctx, TC_ERR_NOMEM, "SRS table allocation failed");
+                break;
+            }
+            int e = rt::memcpy_h2d(d_ell, ell_all.data(), ell_all.size() * sizeof(fr_t), ctx->stream);
+            if (!e) e = rt::stream_sync(ctx->stream);
+            if (e) { rc = fail_hip(ctx, e, "SRS table upload"); break; }
+            int last_axis = (flags & TC_SRS_SUFFIX) ? m - 1 : 0;
+            const uint64_t slab = 1ull << 20;
+            void* tmp = nullptr;
+            if (rt::dev_malloc(&tmp, (size_t)std::min<uint64_t>(slab, total) * sizeof(g1_xyzz)) != 0) {
+                rc = fail(ctx, TC_ERR_NOMEM, "SRS scratch allocation failed");
+                break;
+            }
+            for (int a = 0; a <= last_axis && rc == TC_OK; ++a) {
+                uint64_t na = 1;
+                for (int j = a; j < m; ++j) na *= shape[j];
+                srs->n[a] = na;
+                void* q = nullptr;
+                if (rt::dev_malloc(&q, (size_t)na * sizeof(g1_affine)) != 0) { rc = fail(ctx, TC_ERR_NOMEM, "SRS allocation failed"); break; }
+                srs->pts[a] = (g1_affine*)q;
+                SrsGen gen;
+                gen.shape.m = m;
+                for (int j = 0; j < 4; ++j) { gen.shape.d[j] = j < m ? shape[j] : 1; gen.ell_off[j] = ell_off[j]; }
+                gen.first_axis = a;
+                gen.ell = (const fr_t*)d_ell;
+                gen.gtable = ctx->gtable;
+                gen.out = (g1_xyzz*)tmp;
+                for (uint64_t i0 = 0; i0 < na && rc == TC_OK; i0 += slab) {
+                    uint64_t cnt = std::min(slab, na - i0);
+                    gen.i0 = i0;
+                    e = rt::launch<64>(cnt, ctx->stream, gen);
+                    if (e) { rc = fail_hip(ctx, e, "SrsGen"); break; }
+                    rc = normalize(ctx, (g1_xyzz*)tmp, cnt, srs->pts[a] + i0);
+                }
+                if (rc == TC_OK && (flags & TC_SRS_FIXED_BASE)) rc = build_fixed_base_table(ctx, srs->pts[a], (uint32_t)na, &srs->fb[a]);
+            }
+            e = rt::stream_sync(ctx->stream);
+            if (e && rc == TC_OK) rc = fail_hip(ctx, e, "SRS generation");
+            rt::dev_free(tmp);
+        } while (0);
+        if (d_ell) rt::dev_free(d_ell);
+        if (rc != TC_OK) {
+            tc_srs_destroy(srs);
+            return rc;
+        }
+        *out = srs;
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
 }
 
 extern "C" int tc_srs_get_point(tc_ctx* ctx, const tc_srs* srs, int first_axis, uint64_t index, uint8_t out_g1[96]) {
-    if (!ctx || !srs || !out_g1) return ctx ? fail(ctx, TC_ERR_ARG, "null argument") : TC_ERR_ARG;
-    if (first_axis < 0 || first_axis >= srs->m || !srs->pts[first_axis]) return fail(ctx, TC_ERR_STATE, "table not present");
-    if (index >= srs->n[first_axis]) return fail(ctx, TC_ERR_RANGE, "index outside the table");
-    RT(rt::set_device(ctx->device));
-    TRY(ws_reset(ctx));
-    return affine_to_host(ctx, srs->pts[first_axis] + index, 1, out_g1);
+    try {
+        if (!ctx || !srs || !out_g1) return ctx ? fail(ctx, TC_ERR_ARG, "null argument") : TC_ERR_ARG;
+        if (first_axis < 0 || first_axis >= srs->m || !srs->pts[first_axis]) return fail(ctx, TC_ERR_STATE, "table not present");
+        if (index >= srs->n[first_axis]) return fail(ctx, TC_ERR_RANGE, "index outside the table");
+        RT(rt::set_device(ctx->device));
+        TRY(ws_reset(ctx));
+        return affine_to_host(ctx, srs->pts[first_axis] + index, 1, out_g1);
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
 }
 
 /* ======================================================================================= */
 /* encode                                                                                  */
 /* ======================================================================================= */
 extern "C" int tc_encode_tensor(tc_ctx* ctx, const void* d_src, int src_dtype, size_t n, float inv_scale, void* d_dst) {
-    if (!ctx) return TC_ERR_ARG;
-    if ((!d_src || !d_dst) && n) return fail(ctx, TC_ERR_ARG, "null buffer");
-    if (n > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "tensor too large");
-    RT(rt::set_device(ctx->device));
-    /* the bulk goes 16 bytes per lane when both buffers allow it, the remainder element by element */
-    bool aligned = (((uintptr_t)d_src | (uintptr_t)d_dst) & 15u) == 0;
-    switch (src_dtype) {
-        case TC_F16: {
-            if (!(inv_scale == inv_scale) || inv_scale < 0) return fail(ctx, TC_ERR_RANGE, "inv_scale must be a non-negative number");
-            size_t bulk = aligned ? n / 8 : 0;
-            RT(rt::launch<256>(bulk, ctx->stream, EncodeF16x8{(const Words16*)d_src, (Words16*)d_dst, inv_scale}));
-            RT(rt::launch<256>(n - 8 * bulk, ctx->stream, EncodeF16{(const uint16_t*)d_src + 8 * bulk, (int16_t*)d_dst + 8 * bulk, inv_scale}));
-            return TC_OK;
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if ((!d_src || !d_dst) && n) return fail(ctx, TC_ERR_ARG, "null buffer");
+        if (n > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "tensor too large");
+        RT(rt::set_device(ctx->device));
+        /* the bulk goes 16 bytes per lane when both buffers allow it, the remainder element by element */
+        bool aligned = (((uintptr_t)d_src | (uintptr_t)d_dst) & 15u) == 0;
+        switch (src_dtype) {
+            case TC_F16: {
+                if (!(inv_scale == inv_scale) || inv_scale < 0) return fail(ctx, TC_ERR_RANGE, "inv_scale must be a non-negative number");
+                size_t bulk = aligned ? n / 8 : 0;
+                RT(rt::launch<256>(bulk, ctx->stream, EncodeF16x8{(const Words16*)d_src, (Words16*)d_dst, inv_scale}));
+                RT(rt::launch<256>(n - 8 * bulk, ctx->stream, EncodeF16{(const uint16_t*)d_src + 8 * bulk, (int16_t*)d_dst + 8 * bulk, inv_scale}));
+                return TC_OK;
+            }
+            case TC_I8: {
+                size_t bulk = aligned ? n / 16 : 0;
+                RT(rt::launch<256>(bulk, ctx->stream, Copy128{(const Words16*)d_src, (Words16*)d_dst}));
+                RT(rt::launch<256>(n - 16 * bulk, ctx->stream, Copy8{(const uint8_t*)d_src + 16 * bulk, (uint8_t*)d_dst + 16 * bulk}));
+                return TC_OK;
+            }
+            case TC_I16: {
+                size_t bulk = aligned ? n / 8 : 0;
+                RT(rt::launch<256>(bulk, ctx->stream, Copy128{(const Words16*)d_src, (Words16*)d_dst}));
+                RT(rt::launch<256>(n - 8 * bulk, ctx->stream, Copy16{(const uint16_t*)d_src + 8 * bulk, (uint16_t*)d_dst + 8 * bulk}));
+                return TC_OK;
+            }
+            default:
+                return fail(ctx, TC_ERR_ARG, "unsupported source dtype");
         }
-        case TC_I8: {
-            size_t bulk = aligned ? n / 16 : 0;
-            RT(rt::launch<256>(bulk, ctx->stream, Copy128{(const Words16*)d_src, (Words16*)d_dst}));
-            RT(rt::launch<256>(n - 16 * bulk, ctx->stream, Copy8{(const uint8_t*)d_src + 16 * bulk, (uint8_t*)d_dst + 16 * bulk}));
-            return TC_OK;
-        }
-        case TC_I16: {
-            size_t bulk = aligned ? n / 8 : 0;
-            RT(rt::launch<256>(bulk, ctx->stream, Copy128{(const Words16*)d_src, (Words16*)d_dst}));
-            RT(rt::launch<256>(n - 8 * bulk, ctx->stream, Copy16{(const uint16_t*)d_src + 8 * bulk, (uint16_t*)d_dst + 8 * bulk}));
-            return TC_OK;
-        }
-        default:
-            return fail(ctx, TC_ERR_ARG, "unsupported source dtype");
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
     }
 }
 
@@ -638,13 +773,14 @@ __global__ __launch_bounds__(BLOCK) void coop_kernel(const F f) {
 template <int BLOCK, class F>
 static int launch_coop(uint32_t groups, rt::stream_t st, const F& f) {
     if (!groups) return 0;
-    static bool attr_set = false;
-    if (!attr_set) {
-        int e = (int)hipFuncSetAttribute(reinterpret_cast<const void*>(&coop_kernel<F, BLOCK>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)F::LDS_BYTES);
-        if (e) return e;
-        attr_set = true;
-    }
+    /* once per kernel, whichever host thread comes first (contexts of several threads share the kernels) */
+    static std::once_flag attr_once;
+    static int attr_error = 0;
+    std::call_once(attr_once, [] {
+        attr_error = (int)hipFuncSetAttribute(reinterpret_cast<const void*>(&coop_kernel<F, BLOCK>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)F::LDS_BYTES);
+    });
+    if (attr_error) return attr_error;
     hipLaunchKernelGGL((coop_kernel<F, BLOCK>), dim3(groups), dim3(BLOCK), F::LDS_BYTES, st, f);
     return (int)hipGetLastError();
 }
@@ -743,6 +879,11 @@ static int launch_jobs(tc_ctx* ctx, const std::vector<F>& jobs, const std::vecto
     return TC_OK;
 }
 
+/* plan of a call that may not allocate (tc_commit_static): entries per sub-run of the first pass and tiles of the
+ * counting sort, chosen so that TC_STATIC_MAX_TERMS terms fit into TC_STATIC_SCRATCH_BYTES */
+static const uint32_t STATIC_L1 = 16;
+static const uint32_t STATIC_TILES = 16;
+
 /* lanes of the bucket accumulation that are resident at once: 256 compute units x 4 SIMDs x 3 waves x 64 */
 static const uint64_t ACC_RESIDENT_LANES = 256ull * 4 * 3 * 64;
 
@@ -785,9 +926,15 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     WS(tot_max, uint32_t, nchunks + 1);
     WS(sorted, uint32_t, items ? items : 1);
     WS(tables, const g1_affine*, (uint32_t)count);
-    std::vector<const g1_affine*> h_tables(count);
-    for (int p = 0; p < count; ++p) h_tables[p] = prob[p].pts;
-    TRY(h2d(ctx, tables, h_tables.data(), sizeof(void*) * (size_t)count));
+    {
+        const g1_affine* one = prob[0].pts;            /* a single problem needs no host array */
+        std::vector<const g1_affine*> many;
+        if (count > 1) {
+            many.resize(count);
+            for (int p = 0; p < count; ++p) many[p] = prob[p].pts;
+        }
+        TRY(upload_small(ctx, tables, count > 1 ? many.data() : &one, sizeof(void*) * (size_t)count));
+    }
 
     /* Lanes of the first pass: sub-runs of at most L1 entries, about twice as many as the chip holds at once
      * (the accumulation kernel keeps 3 waves per SIMD), so that the second round evens out what the first left
@@ -799,14 +946,20 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     const uint64_t target_lanes = 2 * ACC_RESIDENT_LANES;
     uint32_t L1 = (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(4, (items + target_lanes - 1) / target_lanes));
     L1 = (uint32_t)std::min<uint64_t>(L1, std::max<uint64_t>(4, (items + 2 * (uint64_t)nbk - 1) / (2 * (uint64_t)nbk)));
+    if (ctx->static_mode) L1 = STATIC_L1;      /* fewer, longer sub-runs: the partial sums must fit the static scratch */
     const uint32_t L2 = 16;
 
     uint32_t max_count = 0;        /* largest bucket: fixes how many shrinking passes are needed */
     if (dtype != TC_FR) {
         /* small scalars (one or two digits per term): tile histograms in LDS, no global atomics */
         uint32_t n_wg = (uint32_t)std::min<uint64_t>(256, std::max<uint64_t>(8, 4096 / (uint64_t)count));
-        std::vector<TileProblem> h_prob(count);
+        if (ctx->static_mode) n_wg = STATIC_TILES;     /* the tile histograms are n_wg rows of the key space */
+        TileProblem one;
+        std::vector<TileProblem> many;
+        if (count > 1) many.resize(count);
+        TileProblem* h_prob = count > 1 ? many.data() : &one;
         for (int p = 0; p < count; ++p) {
+            memset((void*)&h_prob[p], 0, sizeof(TileProblem));
             h_prob[p].scalars = prob[p].scalars;
             h_prob[p].sub = prob[p].sub;
             h_prob[p].n = prob[p].n;
@@ -815,7 +968,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         }
         WS(d_prob, TileProblem, (uint32_t)count);
         WS(M, uint32_t, (uint64_t)count * n_wg * nbk_pp);
-        TRY(h2d(ctx, d_prob, h_prob.data(), sizeof(TileProblem) * (size_t)count));
+        TRY(upload_small(ctx, d_prob, h_prob, sizeof(TileProblem) * (size_t)count));
         uint32_t groups = (uint32_t)count * n_wg;
         if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, CountTile<128>{d_prob, dtype, W, c, n_wg, M})));
         else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, CountTile<512>{d_prob, dtype, W, c, n_wg, M})));
@@ -823,11 +976,12 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         else return fail(ctx, TC_ERR_STATE, "internal: unsupported key count");
         RT(rt::launch<256>(nbk, ctx->stream, TileColumnScan{nbk_pp, n_wg, M, cnt}));
         TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, nullptr, tot_a, tot_b, tot_max));
-        RT(rt::memcpy_d2h(&max_count, tot_max + nchunks, 4, ctx->stream));
+        if (!ctx->static_mode) RT(rt::memcpy_d2h(&max_count, tot_max + nchunks, 4, ctx->stream));
         if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<128>{d_prob, dtype, W, c, n_wg, M, start, sorted})));
         else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<512>{d_prob, dtype, W, c, n_wg, M, start, sorted})));
         else RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<32768>{d_prob, dtype, W, c, n_wg, M, start, sorted})));
     } else {
+        if (ctx->static_mode) return fail(ctx, TC_ERR_STATE, "internal: full-width scalars in a call that may not allocate");
         RT(rt::launch<256>(nbk, ctx->stream, Fill32{cnt, 0u}));
         std::vector<MsmCount> j_count;
         std::vector<MsmScatter> j_scatter;
@@ -859,11 +1013,17 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
 
     /* Middle passes shrink the per-bucket partial count by L2 until at most L2 remain. */
     uint32_t acc_terms = 0, acc_lanes = 0;             /* non-zero digits and sub-runs of the first pass (profiling only) */
-    if (ctx->profiling) {
+    if (ctx->profiling && !ctx->static_mode) {
         RT(rt::memcpy_d2h(&acc_terms, tot_a + nchunks, 4, ctx->stream));
         RT(rt::memcpy_d2h(&acc_lanes, tot_b + nchunks, 4, ctx->stream));
     }
-    TRY(ctx_sync(ctx));
+    if (ctx->static_mode) {
+        /* no wait for the stream: the passes are planned for the fullest bucket there could be, one that holds every
+         * term of the largest problem (a pass over buckets that are already down to few partial sums copies them) */
+        max_count = (uint32_t)max_items;
+    } else {
+        TRY(ctx_sync(ctx));
+    }
     if (ctx->profiling && acc_terms >= acc_lanes) ctx->prof_units[TC_PROF_BUCKET_ACC] += acc_terms - acc_lanes;
     if (max_count > max_items) return fail(ctx, TC_ERR_STATE, "internal: bucket count exceeds the term count");
     uint64_t worst = ((uint64_t)max_count + L1 - 1) / L1;
@@ -916,9 +1076,9 @@ static int msm_engine_list(tc_ctx* ctx, int count, const MsmProblem* prob, const
             buckets += (uint64_t)W << (c - 1);
             ++j;
         }
-        size_t mark = ctx->ws.off;
+        size_t mark = ctx->wsp->off;
         TRY(msm_engine_multi(ctx, j - i, prob + i, dtype[i], W, c, results + i));
-        ctx->ws.off = mark;            /* scratch is reusable by the next batch: the stream orders the kernels */
+        ctx->wsp->off = mark;            /* scratch is reusable by the next batch: the stream orders the kernels */
         i = j;
     }
     return TC_OK;
@@ -933,23 +1093,81 @@ static int check_commit_args(tc_ctx* ctx, const tc_srs* srs, const void* d_scala
 
 extern "C" int tc_commit_batch(tc_ctx* ctx, int count, const tc_srs* const* srs, const void* const* d_scalars,
                                const int* dtype, uint8_t* out_g1) {
-    if (!ctx) return TC_ERR_ARG;
-    if (count < 0 || (count && (!srs || !d_scalars || !dtype || !out_g1))) return fail(ctx, TC_ERR_ARG, "null argument");
-    for (int i = 0; i < count; ++i) TRY(check_commit_args(ctx, srs[i], d_scalars[i], dtype[i]));
-    if (!count) return TC_OK;
-    RT(rt::set_device(ctx->device));
-    TRY(ws_reset(ctx));
-    WS(results, g1_xyzz, (uint32_t)count);
-    std::vector<MsmProblem> prob(count);
-    for (int i = 0; i < count; ++i) prob[i] = MsmProblem{srs[i]->pts[0], d_scalars[i], srs[i]->n[0]};
-    TRY(msm_engine_list(ctx, count, prob.data(), dtype, results));
-    return points_to_host(ctx, results, (uint32_t)count, out_g1);
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (count < 0 || (count && (!srs || !d_scalars || !dtype || !out_g1))) return fail(ctx, TC_ERR_ARG, "null argument");
+        for (int i = 0; i < count; ++i) TRY(check_commit_args(ctx, srs[i], d_scalars[i], dtype[i]));
+        if (!count) return TC_OK;
+        RT(rt::set_device(ctx->device));
+        TRY(ws_reset(ctx));
+        WS(results, g1_xyzz, (uint32_t)count);
+        std::vector<MsmProblem> prob(count);
+        for (int i = 0; i < count; ++i) prob[i] = MsmProblem{srs[i]->pts[0], d_scalars[i], srs[i]->n[0]};
+        TRY(msm_engine_list(ctx, count, prob.data(), dtype, results));
+        return points_to_host(ctx, results, (uint32_t)count, out_g1);
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
 }
 extern "C" int tc_commit(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, int dtype, uint8_t out_g1[96]) {
-    if (!ctx) return TC_ERR_ARG;
-    if (!out_g1) return fail(ctx, TC_ERR_ARG, "null argument");
-    return tc_commit_batch(ctx, 1, &srs, &d_scalars, &dtype, out_g1);
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!out_g1) return fail(ctx, TC_ERR_ARG, "null argument");
+        return tc_commit_batch(ctx, 1, &srs, &d_scalars, &dtype, out_g1);
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
 }
+
+/* The commitment for callers that cannot allocate: the same kernels as tc_commit, every intermediate in the
+ * device's static scratch array, the table pointer and the tile description sent as kernel arguments, the passes
+ * over the partial sums planned from the term count alone (no value is read back, the stream is never waited for),
+ * and the canonical bytes written to the caller's device buffer. */
+struct StaticModeGuard {
+    tc_ctx* ctx;
+    explicit StaticModeGuard(tc_ctx* c) : ctx(c) {
+        ctx->wsp = &ctx->ws_static;
+        ctx->ws_static.off = 0;
+        ctx->ws_static.demand = 0;
+        ctx->static_mode = true;
+    }
+    ~StaticModeGuard() {
+        ctx->wsp = &ctx->ws;
+        ctx->static_mode = false;
+    }
+};
+extern "C" int tc_commit_static(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, int dtype, void* d_out_g1) {
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!d_out_g1) return fail(ctx, TC_ERR_ARG, "null argument");
+        if (((uintptr_t)d_out_g1 & 3u) != 0) return fail(ctx, TC_ERR_ARG, "the output buffer must be 4-byte aligned");
+        TRY(check_commit_args(ctx, srs, d_scalars, dtype));
+        if (dtype != TC_I8 && dtype != TC_I16) return fail(ctx, TC_ERR_ARG, "tc_commit_static takes int8 or int16 scalars");
+        if (srs->n[0] > TC_STATIC_MAX_TERMS)
+            return fail(ctx, TC_ERR_SHAPE, "tc_commit_static: the tensor has more than TC_STATIC_MAX_TERMS entries");
+        if (!ctx->ws_static.base) return fail(ctx, TC_ERR_STATE, "static scratch not available");
+        RT(rt::set_device(ctx->device));
+        StaticModeGuard guard(ctx);
+        WS(result, g1_xyzz, 1);
+        WS(aff, g1_affine, 1);
+        int W, c;
+        msm_config(dtype, srs->n[0], &W, &c);
+        MsmProblem one{srs->pts[0], d_scalars, srs->n[0]};
+        TRY(msm_engine_multi(ctx, 1, &one, dtype, W, c, result));
+        TRY(normalize(ctx, result, 1, aff));
+        RT(rt::launch<64>(1, ctx->stream, ToCanonical{aff, (uint32_t*)d_out_g1}));
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
+}
+extern "C" uint64_t tc_alloc_calls(void) { return rt::alloc_calls().load(); }
 
 /* ======================================================================================= */
 /* Open                                                                                    */
@@ -1117,16 +1335,22 @@ static int check_open_args(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars
 
 extern "C" int tc_open(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, int dtype, const uint32_t* kappa,
                        uint8_t out_y[32], uint8_t* out_pi) {
-    if (!ctx) return TC_ERR_ARG;
-    if (!out_y || !out_pi) return fail(ctx, TC_ERR_ARG, "null argument");
-    TRY(check_open_args(ctx, srs, d_scalars, dtype, kappa));
-    RT(rt::set_device(ctx->device));
-    TRY(ws_reset(ctx));
-    WS(pi, g1_xyzz, 4);
-    WS(y, fr_plain, 1);
-    TRY(open_device(ctx, srs, d_scalars, dtype, kappa, pi, y));
-    RT(rt::memcpy_d2h(out_y, y, 32, ctx->stream));
-    return points_to_host(ctx, pi, (uint32_t)srs->m, out_pi);
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!out_y || !out_pi) return fail(ctx, TC_ERR_ARG, "null argument");
+        TRY(check_open_args(ctx, srs, d_scalars, dtype, kappa));
+        RT(rt::set_device(ctx->device));
+        TRY(ws_reset(ctx));
+        WS(pi, g1_xyzz, 4);
+        WS(y, fr_plain, 1);
+        TRY(open_device(ctx, srs, d_scalars, dtype, kappa, pi, y));
+        RT(rt::memcpy_d2h(out_y, y, 32, ctx->stream));
+        return points_to_host(ctx, pi, (uint32_t)srs->m, out_pi);
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
 }
 
 /* ======================================================================================= */
@@ -1158,19 +1382,25 @@ static void step_scalar(const tc_vk* vk, int i, uint32_t kappa, uint32_t k1[4], 
     glv_split(k.l, k1, k2);
 }
 extern "C" int tc_vk_from_trapdoor(const uint8_t* tau, int m, tc_vk** out) {
-    if (!tau || !out || m < 1 || m > TC_MAX_ORDER) return TC_ERR_ARG;
-    *out = nullptr;
-    uint32_t w[8];
-    for (int j = 0; j < m; ++j)
-        if (!fr_bytes_canonical(tau + 32 * j, w)) return TC_ERR_RANGE;
-    tc_vk* vk = new (std::nothrow) tc_vk();
-    if (!vk) return TC_ERR_NOMEM;
-    vk->m = m;
-    memcpy(vk->tau, tau, 32 * (size_t)m);
-    for (int i = 0; i < m; ++i)
-        for (uint32_t kappa = 0; kappa < tc_vk::SPLIT_CACHE; ++kappa) step_scalar(vk, i, kappa, vk->k1[i][kappa], vk->k2[i][kappa]);
-    *out = vk;
-    return TC_OK;
+    try {
+        if (!tau || !out || m < 1 || m > TC_MAX_ORDER) return TC_ERR_ARG;
+        *out = nullptr;
+        uint32_t w[8];
+        for (int j = 0; j < m; ++j)
+            if (!fr_bytes_canonical(tau + 32 * j, w)) return TC_ERR_RANGE;
+        tc_vk* vk = new (std::nothrow) tc_vk();
+        if (!vk) return TC_ERR_NOMEM;
+        vk->m = m;
+        memcpy(vk->tau, tau, 32 * (size_t)m);
+        for (int i = 0; i < m; ++i)
+            for (uint32_t kappa = 0; kappa < tc_vk::SPLIT_CACHE; ++kappa) step_scalar(vk, i, kappa, vk->k1[i][kappa], vk->k2[i][kappa]);
+        *out = vk;
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return TC_ERR_NOMEM;
+    } catch (...) {
+        return TC_ERR_STATE;
+    }
 }
 extern "C" void tc_vk_destroy(tc_vk* vk) { delete vk; }
 
@@ -1225,24 +1455,30 @@ static int verify_steps(tc_ctx* ctx, const tc_vk* vk, const std::vector<VerifySt
 
 extern "C" int tc_verify(tc_ctx* ctx, const tc_vk* vk, int m, const uint32_t* shape, const uint8_t commitment[96],
                          const uint32_t* kappa, const uint8_t y[32], const uint8_t* pi) {
-    if (!ctx) return TC_ERR_ARG;
-    if (!vk || !shape || !commitment || !kappa || !y || !pi) return fail(ctx, TC_ERR_ARG, "null argument");
-    if (!shape_ok(m, shape, nullptr) || m > vk->m) return fail(ctx, TC_ERR_SHAPE, "bad shape");
-    for (int j = 0; j < m; ++j)
-        if (kappa[j] >= shape[j]) return fail(ctx, TC_ERR_RANGE, "opening position outside the grid");
-    RT(rt::set_device(ctx->device));
-    TRY(ws_reset(ctx));
-    std::vector<VerifyStep> steps(1);
-    memset(&steps[0], 0, sizeof(VerifyStep));
-    memcpy(steps[0].C, commitment, 96);
-    memcpy(steps[0].y, y, 32);
-    for (int j = 0; j < m; ++j) memcpy(steps[0].pi[j], pi + 96 * j, 96);
-    steps[0].m = m;
-    fill_step_scalars(vk, kappa, &steps[0]);
-    std::vector<uint32_t> ok;
-    TRY(verify_steps(ctx, vk, steps, ok));
-    if (!ok[0]) return fail(ctx, TC_ERR_VERIFY, "opening rejected");
-    return TC_OK;
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!vk || !shape || !commitment || !kappa || !y || !pi) return fail(ctx, TC_ERR_ARG, "null argument");
+        if (!shape_ok(m, shape, nullptr) || m > vk->m) return fail(ctx, TC_ERR_SHAPE, "bad shape");
+        for (int j = 0; j < m; ++j)
+            if (kappa[j] >= shape[j]) return fail(ctx, TC_ERR_RANGE, "opening position outside the grid");
+        RT(rt::set_device(ctx->device));
+        TRY(ws_reset(ctx));
+        std::vector<VerifyStep> steps(1);
+        memset(&steps[0], 0, sizeof(VerifyStep));
+        memcpy(steps[0].C, commitment, 96);
+        memcpy(steps[0].y, y, 32);
+        for (int j = 0; j < m; ++j) memcpy(steps[0].pi[j], pi + 96 * j, 96);
+        steps[0].m = m;
+        fill_step_scalars(vk, kappa, &steps[0]);
+        std::vector<uint32_t> ok;
+        TRY(verify_steps(ctx, vk, steps, ok));
+        if (!ok[0]) return fail(ctx, TC_ERR_VERIFY, "opening rejected");
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
 }
 
 /* ======================================================================================= */
@@ -1266,25 +1502,43 @@ extern "C" void tc_tree_destroy(tc_tree* tree) {
     delete tree;
 }
 extern "C" int tc_terkle_root(const tc_tree* tree, uint8_t out_g1[96]) {
-    if (!tree || !out_g1) return TC_ERR_ARG;
-    memcpy(out_g1, tree->root, 96);
-    return TC_OK;
+    try {
+        if (!tree || !out_g1) return TC_ERR_ARG;
+        memcpy(out_g1, tree->root, 96);
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return TC_ERR_NOMEM;
+    } catch (...) {
+        return TC_ERR_STATE;
+    }
 }
 extern "C" int tc_terkle_levels(const tc_tree* tree) { return tree ? (int)tree->levels.size() : TC_ERR_ARG; }
 extern "C" int tc_terkle_level_info(const tc_tree* tree, int level, uint32_t* grid, uint64_t* n_nodes) {
-    if (!tree || level < 0 || level >= (int)tree->levels.size()) return TC_ERR_ARG;
-    if (grid)
-        for (int j = 0; j < tree->m; ++j) grid[j] = tree->levels[level].grid[j];
-    if (n_nodes) *n_nodes = tree->levels[level].n;
-    return TC_OK;
+    try {
+        if (!tree || level < 0 || level >= (int)tree->levels.size()) return TC_ERR_ARG;
+        if (grid)
+            for (int j = 0; j < tree->m; ++j) grid[j] = tree->levels[level].grid[j];
+        if (n_nodes) *n_nodes = tree->levels[level].n;
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return TC_ERR_NOMEM;
+    } catch (...) {
+        return TC_ERR_STATE;
+    }
 }
 extern "C" int tc_terkle_node(tc_ctx* ctx, const tc_tree* tree, int level, uint64_t index, uint8_t out_g1[96]) {
-    if (!ctx) return TC_ERR_ARG;
-    if (!tree || !out_g1 || level < 0 || level >= (int)tree->levels.size()) return fail(ctx, TC_ERR_ARG, "bad argument");
-    if (index >= tree->levels[level].n) return fail(ctx, TC_ERR_RANGE, "node index outside the level");
-    RT(rt::set_device(ctx->device));
-    TRY(ws_reset(ctx));
-    return affine_to_host(ctx, tree->levels[level].C + index, 1, out_g1);
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!tree || !out_g1 || level < 0 || level >= (int)tree->levels.size()) return fail(ctx, TC_ERR_ARG, "bad argument");
+        if (index >= tree->levels[level].n) return fail(ctx, TC_ERR_RANGE, "node index outside the level");
+        RT(rt::set_device(ctx->device));
+        TRY(ws_reset(ctx));
+        return affine_to_host(ctx, tree->levels[level].C + index, 1, out_g1);
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
 }
 
 static TreeGeom make_geom(const tc_tree* t, const uint32_t* below, const uint32_t* grid) {
@@ -1325,245 +1579,257 @@ struct GatherNodeFr {
 };
 
 extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** out) {
-    if (!ctx) return TC_ERR_ARG;
-    if (!desc || !out) return fail(ctx, TC_ERR_ARG, "null argument");
-    *out = nullptr;
-    uint64_t n_payload = 0, B = 0;
-    if (!shape_ok(desc->m, desc->grid, &n_payload) || !shape_ok(desc->m, desc->node_shape, &B))
-        return fail(ctx, TC_ERR_SHAPE, "bad grid or node shape");
-    const tc_srs* ns = desc->node_srs;
-    if (!ns) return fail(ctx, TC_ERR_ARG, "node SRS missing");
-    if (ns->m != desc->m) return fail(ctx, TC_ERR_SHAPE, "node SRS order differs from the grid order");
-    for (int j = 0; j < desc->m; ++j)
-        if (ns->shape[j] != desc->node_shape[j]) return fail(ctx, TC_ERR_SHAPE, "node SRS shape differs from node_shape");
-    if (ns->flags & TC_SRS_MONOMIAL) return fail(ctx, TC_ERR_STATE, "trees need the Lagrange-basis SRS, this one is monomial");
-    bool more_than_one = false;
-    for (int j = 0; j < desc->m; ++j) more_than_one = more_than_one || desc->node_shape[j] > 1;
-    if (!more_than_one) return fail(ctx, TC_ERR_SHAPE, "node shape must have more than one entry");
-    if (desc->leaf_kind == TC_LEAF_ENTRIES) {
-        if (!desc->d_payload) return fail(ctx, TC_ERR_ARG, "payload missing");
-        if (desc->dtype != TC_I8 && desc->dtype != TC_I16) return fail(ctx, TC_ERR_ARG, "payload must be int8 or int16");
-    } else if (desc->leaf_kind == TC_LEAF_TENSORS) {
-        if (!desc->leaf_srs || !desc->d_leaf_scalars || !desc->leaf_dtype) return fail(ctx, TC_ERR_ARG, "leaf arrays missing");
-        for (uint64_t i = 0; i < n_payload; ++i) {
-            TRY(check_commit_args(ctx, desc->leaf_srs[i], desc->d_leaf_scalars[i], desc->leaf_dtype[i]));
-            if (desc->leaf_srs[i]->flags & TC_SRS_MONOMIAL) return fail(ctx, TC_ERR_STATE, "trees need the Lagrange-basis SRS, a leaf SRS is monomial");
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!desc || !out) return fail(ctx, TC_ERR_ARG, "null argument");
+        *out = nullptr;
+        uint64_t n_payload = 0, B = 0;
+        if (!shape_ok(desc->m, desc->grid, &n_payload) || !shape_ok(desc->m, desc->node_shape, &B))
+            return fail(ctx, TC_ERR_SHAPE, "bad grid or node shape");
+        const tc_srs* ns = desc->node_srs;
+        if (!ns) return fail(ctx, TC_ERR_ARG, "node SRS missing");
+        if (ns->m != desc->m) return fail(ctx, TC_ERR_SHAPE, "node SRS order differs from the grid order");
+        for (int j = 0; j < desc->m; ++j)
+            if (ns->shape[j] != desc->node_shape[j]) return fail(ctx, TC_ERR_SHAPE, "node SRS shape differs from node_shape");
+        if (ns->flags & TC_SRS_MONOMIAL) return fail(ctx, TC_ERR_STATE, "trees need the Lagrange-basis SRS, this one is monomial");
+        bool more_than_one = false;
+        for (int j = 0; j < desc->m; ++j) more_than_one = more_than_one || desc->node_shape[j] > 1;
+        if (!more_than_one) return fail(ctx, TC_ERR_SHAPE, "node shape must have more than one entry");
+        if (desc->leaf_kind == TC_LEAF_ENTRIES) {
+            if (!desc->d_payload) return fail(ctx, TC_ERR_ARG, "payload missing");
+            if (desc->dtype != TC_I8 && desc->dtype != TC_I16) return fail(ctx, TC_ERR_ARG, "payload must be int8 or int16");
+        } else if (desc->leaf_kind == TC_LEAF_TENSORS) {
+            if (!desc->leaf_srs || !desc->d_leaf_scalars || !desc->leaf_dtype) return fail(ctx, TC_ERR_ARG, "leaf arrays missing");
+            for (uint64_t i = 0; i < n_payload; ++i) {
+                TRY(check_commit_args(ctx, desc->leaf_srs[i], desc->d_leaf_scalars[i], desc->leaf_dtype[i]));
+                if (desc->leaf_srs[i]->flags & TC_SRS_MONOMIAL) return fail(ctx, TC_ERR_STATE, "trees need the Lagrange-basis SRS, a leaf SRS is monomial");
+            }
+        } else {
+            return fail(ctx, TC_ERR_ARG, "bad leaf kind");
         }
-    } else {
-        return fail(ctx, TC_ERR_ARG, "bad leaf kind");
-    }
-    RT(rt::set_device(ctx->device));
-    TRY(ws_reset(ctx));
+        RT(rt::set_device(ctx->device));
+        TRY(ws_reset(ctx));
 
-    tc_tree* t = new (std::nothrow) tc_tree();
-    if (!t) return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
-    t->m = desc->m;
-    t->B = (uint32_t)B;
-    t->node_srs = ns;
-    t->leaf_kind = desc->leaf_kind;
-    t->d_payload = desc->d_payload;
-    t->dtype = desc->dtype;
-    for (int j = 0; j < desc->m; ++j) { t->grid[j] = desc->grid[j]; t->node_shape[j] = desc->node_shape[j]; }
-    if (desc->leaf_kind == TC_LEAF_TENSORS) {
-        t->leaf_srs.assign(desc->leaf_srs, desc->leaf_srs + n_payload);
-        t->leaf_scalars.assign(desc->d_leaf_scalars, desc->d_leaf_scalars + n_payload);
-        t->leaf_dtype.assign(desc->leaf_dtype, desc->leaf_dtype + n_payload);
-    }
-    /* level grids, bottom-up */
-    {
-        uint32_t g[4] = {1, 1, 1, 1};
-        for (int j = 0; j < t->m; ++j) g[j] = t->grid[j];
-        bool first = true;
-        for (;;) {
-            bool blocked = !(first && t->leaf_kind == TC_LEAF_TENSORS);
-            TreeLevel lv;
-            lv.n = 1;
-            bool all_one = true;
-            for (int j = 0; j < t->m; ++j) {
-                lv.grid[j] = blocked ? (g[j] + t->node_shape[j] - 1) / t->node_shape[j] : g[j];
-                lv.n *= lv.grid[j];
-                all_one = all_one && lv.grid[j] == 1;
-                g[j] = lv.grid[j];
-            }
-            t->levels.push_back(lv);
-            first = false;
-            if (all_one) break;
-            if (t->levels.size() >= MAX_LEVELS) {
-                delete t;
-                return fail(ctx, TC_ERR_SHAPE, "tree too deep");
-            }
+        tc_tree* t = new (std::nothrow) tc_tree();
+        if (!t) return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+        t->m = desc->m;
+        t->B = (uint32_t)B;
+        t->node_srs = ns;
+        t->leaf_kind = desc->leaf_kind;
+        t->d_payload = desc->d_payload;
+        t->dtype = desc->dtype;
+        for (int j = 0; j < desc->m; ++j) { t->grid[j] = desc->grid[j]; t->node_shape[j] = desc->node_shape[j]; }
+        if (desc->leaf_kind == TC_LEAF_TENSORS) {
+            t->leaf_srs.assign(desc->leaf_srs, desc->leaf_srs + n_payload);
+            t->leaf_scalars.assign(desc->d_leaf_scalars, desc->d_leaf_scalars + n_payload);
+            t->leaf_dtype.assign(desc->leaf_dtype, desc->leaf_dtype + n_payload);
         }
-    }
-    int rc = TC_OK;
-    {
-        size_t total = 0;
-        for (auto& lv : t->levels) total += ((size_t)lv.n * sizeof(g1_affine) + 255) / 256 * 256 + ((size_t)lv.n * sizeof(fr_plain) + 255) / 256 * 256;
-        t->pool = ctx->tree_pool;
-        if (ctx->tree_pool->block && ctx->tree_pool->cap >= total) {
-            t->block = ctx->tree_pool->block;
-            t->block_cap = ctx->tree_pool->cap;
-            ctx->tree_pool->block = nullptr;
-            ctx->tree_pool->cap = 0;
-        } else if (rt::dev_malloc(&t->block, total) == 0) {
-            t->block_cap = total;
-        } else {
-            t->block = nullptr;
-        }
-        if (!t->block) {
-            rc = fail(ctx, TC_ERR_NOMEM, "tree level allocation failed");
-        } else {
-            uint8_t* at = (uint8_t*)t->block;
-            for (auto& lv : t->levels) {
-                lv.C = (g1_affine*)at;
-                at += ((size_t)lv.n * sizeof(g1_affine) + 255) / 256 * 256;
-                lv.phi = (fr_plain*)at;
-                at += ((size_t)lv.n * sizeof(fr_plain) + 255) / 256 * 256;
-            }
-        }
-    }
-    bool use_fb = ns->fb[0] != nullptr;
-    for (size_t L = 0; L < t->levels.size() && rc == TC_OK; ++L) {
-        TreeLevel& lv = t->levels[L];
-        size_t mark = ctx->ws.off;
-        do {
-            if (lv.n > 0xFFFFFFFFull / t->B) { rc = fail(ctx, TC_ERR_SHAPE, "level too large"); break; }
-            g1_xyzz* acc = ws_array<g1_xyzz>(ctx, lv.n);
-            if (!acc) { rc = fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed"); break; }
-            if (L == 0 && t->leaf_kind == TC_LEAF_TENSORS) {
-                std::vector<MsmProblem> prob(lv.n);
-                for (uint64_t i = 0; i < lv.n; ++i) prob[i] = MsmProblem{t->leaf_srs[i]->pts[0], t->leaf_scalars[i], t->leaf_srs[i]->n[0]};
-                rc = msm_engine_list(ctx, (int)lv.n, prob.data(), t->leaf_dtype.data(), acc);
-            } else {
-                const uint32_t* below = L == 0 ? t->grid : t->levels[L - 1].grid;
-                TreeGeom g = make_geom(t, below, lv.grid);
-                bool bottom = (L == 0);
-                if (use_fb) {
-                    int e;
-                    if (bottom && lv.n <= COOP_LEVEL_NODES) {
-                        typedef CoopReduce<NodeSmallSrc> Sum;
-                        e = launch_coop<Sum::BLOCK>((uint32_t)lv.n, ctx->stream, Sum{NodeSmallSrc{g, t->d_payload, t->dtype, ns->fb[0], acc}});
-                    } else if (bottom) {
-                        rt::event_t e0, e1;
-                        prof_begin(ctx, TC_PROF_NODE_COMMIT, &e0, &e1);
-                        e = rt::launch<64>(lv.n, ctx->stream, NodeCommitSmall{g, t->d_payload, t->dtype, ns->fb[0], acc});
-                        prof_end(ctx, TC_PROF_NODE_COMMIT, e0, e1);
-                    } else if (lv.n <= COOP_LEVEL_NODES) {
-                        rt::event_t e0, e1;
-                        prof_begin(ctx, TC_PROF_NODE_COMMIT_UPPER, &e0, &e1);
-                        /* very few nodes: every (child, window) term its own lane, sums shared by four waves */
-                        typedef CoopReduce<NodeWindowSrc> Sum;
-                        e = launch_coop<Sum::BLOCK>((uint32_t)lv.n, ctx->stream, Sum{NodeWindowSrc{g, t->levels[L - 1].phi, ns->fb[0], acc}});
-                        prof_end(ctx, TC_PROF_NODE_COMMIT_UPPER, e0, e1);
-                    } else if ((t->B & (t->B - 1)) == 0 && t->B <= 64) {
-                        int logB = 0;
-                        while ((1u << logB) < t->B) ++logB;
-                        /* few nodes: one lane's depth is the cost, spread the windows of a child over lanes too */
-                        int logH = 0;
-                        while (logB + logH < 6 && (2 << logH) <= FB_W && (lv.n << (logB + logH + 1)) <= SPLIT_LEVEL_LANES) ++logH;
-                        uint64_t lanes = lv.n << (logB + logH);
-                        rt::event_t e0, e1;
-                        prof_begin(ctx, TC_PROF_NODE_COMMIT_UPPER, &e0, &e1);
-                        if (logH == 0)      /* a level large enough to fill the chip: throughput counts */
-                            e = launch_coop<256>((uint32_t)((lanes + 255) / 256), ctx->stream,
-                                                 NodeCommitFrCoop<256>{g, t->levels[L - 1].phi, ns->fb[0], lv.n, logB, logH, acc});
-                        else
-                            e = launch_coop<64>((uint32_t)((lanes + 63) / 64), ctx->stream,
-                                                NodeCommitFrCoop<64>{g, t->levels[L - 1].phi, ns->fb[0], lv.n, logB, logH, acc});
-                        prof_end(ctx, TC_PROF_NODE_COMMIT_UPPER, e0, e1);
-                    } else {
-                        g1_xyzz* part = ws_array<g1_xyzz>(ctx, lv.n * t->B);
-                        if (!part) { rc = fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed"); break; }
-                        e = rt::launch<64>(lv.n * t->B, ctx->stream, NodeCommitFr{g, t->levels[L - 1].phi, ns->fb[0], part});
-                        if (!e) e = rt::launch<64>(lv.n, ctx->stream, SumGroups{part, t->B, acc});
-                    }
-                    if (e) { rc = fail_hip(ctx, e, "node commit"); break; }
-                } else {
-                    /* large node shapes: every node is its own MSM over the gathered children */
-                    size_t esz = bottom ? dtype_size(t->dtype) : 32;
-                    void* z = ws_alloc(ctx, (size_t)t->B * esz);
-                    if (!z) { rc = fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed"); break; }
-                    for (uint64_t a = 0; a < lv.n && rc == TC_OK; ++a) {
-                        int e = bottom ? rt::launch<64>(t->B, ctx->stream, GatherNodeSmall{g, t->d_payload, t->dtype, a, z})
-                                       : rt::launch<64>(t->B, ctx->stream, GatherNodeFr{g, t->levels[L - 1].phi, a, (fr_plain*)z});
-                        if (e) { rc = fail_hip(ctx, e, "gather"); break; }
-                        size_t mk = ctx->ws.off;
-                        rc = msm_engine(ctx, ns->pts[0], z, bottom ? t->dtype : TC_FR, t->B, acc + a);
-                        ctx->ws.off = mk;
-                    }
-                    if (rc) break;
+        /* level grids, bottom-up */
+        {
+            uint32_t g[4] = {1, 1, 1, 1};
+            for (int j = 0; j < t->m; ++j) g[j] = t->grid[j];
+            bool first = true;
+            for (;;) {
+                bool blocked = !(first && t->leaf_kind == TC_LEAF_TENSORS);
+                TreeLevel lv;
+                lv.n = 1;
+                bool all_one = true;
+                for (int j = 0; j < t->m; ++j) {
+                    lv.grid[j] = blocked ? (g[j] + t->node_shape[j] - 1) / t->node_shape[j] : g[j];
+                    lv.n *= lv.grid[j];
+                    all_one = all_one && lv.grid[j] == 1;
+                    g[j] = lv.grid[j];
+                }
+                t->levels.push_back(lv);
+                first = false;
+                if (all_one) break;
+                if (t->levels.size() >= MAX_LEVELS) {
+                    delete t;
+                    return fail(ctx, TC_ERR_SHAPE, "tree too deep");
                 }
             }
-            if (rc) break;
-            rc = normalize(ctx, acc, lv.n, lv.C);
-            if (rc) break;
-            int e = rt::launch<64>(lv.n, ctx->stream, PhiKernel{lv.C, lv.phi});
-            if (e) rc = fail_hip(ctx, e, "phi");
-        } while (0);
-        ctx->ws.off = mark;
+        }
+        int rc = TC_OK;
+        {
+            size_t total = 0;
+            for (auto& lv : t->levels) total += ((size_t)lv.n * sizeof(g1_affine) + 255) / 256 * 256 + ((size_t)lv.n * sizeof(fr_plain) + 255) / 256 * 256;
+            t->pool = ctx->tree_pool;
+            if (ctx->tree_pool->block && ctx->tree_pool->cap >= total) {
+                t->block = ctx->tree_pool->block;
+                t->block_cap = ctx->tree_pool->cap;
+                ctx->tree_pool->block = nullptr;
+                ctx->tree_pool->cap = 0;
+            } else if (rt::dev_malloc(&t->block, total) == 0) {
+                t->block_cap = total;
+            } else {
+                t->block = nullptr;
+            }
+            if (!t->block) {
+                rc = fail(ctx, TC_ERR_NOMEM, "tree level allocation failed");
+            } else {
+                uint8_t* at = (uint8_t*)t->block;
+                for (auto& lv : t->levels) {
+                    lv.C = (g1_affine*)at;
+                    at += ((size_t)lv.n * sizeof(g1_affine) + 255) / 256 * 256;
+                    lv.phi = (fr_plain*)at;
+                    at += ((size_t)lv.n * sizeof(fr_plain) + 255) / 256 * 256;
+                }
+            }
+        }
+        bool use_fb = ns->fb[0] != nullptr;
+        for (size_t L = 0; L < t->levels.size() && rc == TC_OK; ++L) {
+            TreeLevel& lv = t->levels[L];
+            size_t mark = ctx->wsp->off;
+            do {
+                if (lv.n > 0xFFFFFFFFull / t->B) { rc = fail(ctx, TC_ERR_SHAPE, "level too large"); break; }
+                g1_xyzz* acc = ws_array<g1_xyzz>(ctx, lv.n);
+                if (!acc) { rc = fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed"); break; }
+                if (L == 0 && t->leaf_kind == TC_LEAF_TENSORS) {
+                    std::vector<MsmProblem> prob(lv.n);
+                    for (uint64_t i = 0; i < lv.n; ++i) prob[i] = MsmProblem{t->leaf_srs[i]->pts[0], t->leaf_scalars[i], t->leaf_srs[i]->n[0]};
+                    rc = msm_engine_list(ctx, (int)lv.n, prob.data(), t->leaf_dtype.data(), acc);
+                } else {
+                    const uint32_t* below = L == 0 ? t->grid : t->levels[L - 1].grid;
+                    TreeGeom g = make_geom(t, below, lv.grid);
+                    bool bottom = (L == 0);
+                    if (use_fb) {
+                        int e;
+                        if (bottom && lv.n <= COOP_LEVEL_NODES) {
+                            typedef CoopReduce<NodeSmallSrc> Sum;
+                            e = launch_coop<Sum::BLOCK>((uint32_t)lv.n, ctx->stream, Sum{NodeSmallSrc{g, t->d_payload, t->dtype, ns->fb[0], acc}});
+                        } else if (bottom) {
+                            rt::event_t e0, e1;
+                            prof_begin(ctx, TC_PROF_NODE_COMMIT, &e0, &e1);
+                            e = rt::launch<64>(lv.n, ctx->stream, NodeCommitSmall{g, t->d_payload, t->dtype, ns->fb[0], acc});
+                            prof_end(ctx, TC_PROF_NODE_COMMIT, e0, e1);
+                        } else if (lv.n <= COOP_LEVEL_NODES) {
+                            rt::event_t e0, e1;
+                            prof_begin(ctx, TC_PROF_NODE_COMMIT_UPPER, &e0, &e1);
+                            /* very few nodes: every (child, window) term its own lane, sums shared by four waves */
+                            typedef CoopReduce<NodeWindowSrc> Sum;
+                            e = launch_coop<Sum::BLOCK>((uint32_t)lv.n, ctx->stream, Sum{NodeWindowSrc{g, t->levels[L - 1].phi, ns->fb[0], acc}});
+                            prof_end(ctx, TC_PROF_NODE_COMMIT_UPPER, e0, e1);
+                        } else if ((t->B & (t->B - 1)) == 0 && t->B <= 64) {
+                            int logB = 0;
+                            while ((1u << logB) < t->B) ++logB;
+                            /* few nodes: one lane's depth is the cost, spread the windows of a child over lanes too */
+                            int logH = 0;
+                            while (logB + logH < 6 && (2 << logH) <= FB_W && (lv.n << (logB + logH + 1)) <= SPLIT_LEVEL_LANES) ++logH;
+                            uint64_t lanes = lv.n << (logB + logH);
+                            rt::event_t e0, e1;
+                            prof_begin(ctx, TC_PROF_NODE_COMMIT_UPPER, &e0, &e1);
+                            if (logH == 0)      /* a level large enough to fill the chip: throughput counts */
+                                e = launch_coop<256>((uint32_t)((lanes + 255) / 256), ctx->stream,
+                                                     NodeCommitFrCoop<256>{g, t->levels[L - 1].phi, ns->fb[0], lv.n, logB, logH, acc});
+                            else
+                                e = launch_coop<64>((uint32_t)((lanes + 63) / 64), ctx->stream,
+                                                    NodeCommitFrCoop<64>{g, t->levels[L - 1].phi, ns->fb[0], lv.n, logB, logH, acc});
+                            prof_end(ctx, TC_PROF_NODE_COMMIT_UPPER, e0, e1);
+                        } else {
+                            g1_xyzz* part = ws_array<g1_xyzz>(ctx, lv.n * t->B);
+                            if (!part) { rc = fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed"); break; }
+                            e = rt::launch<64>(lv.n * t->B, ctx->stream, NodeCommitFr{g, t->levels[L - 1].phi, ns->fb[0], part});
+                            if (!e) e = rt::launch<64>(lv.n, ctx->stream, SumGroups{part, t->B, acc});
+                        }
+                        if (e) { rc = fail_hip(ctx, e, "node commit"); break; }
+                    } else {
+                        /* large node shapes: every node is its own MSM over the gathered children */
+                        size_t esz = bottom ? dtype_size(t->dtype) : 32;
+                        void* z = ws_alloc(ctx, (size_t)t->B * esz);
+                        if (!z) { rc = fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed"); break; }
+                        for (uint64_t a = 0; a < lv.n && rc == TC_OK; ++a) {
+                            int e = bottom ? rt::launch<64>(t->B, ctx->stream, GatherNodeSmall{g, t->d_payload, t->dtype, a, z})
+                                           : rt::launch<64>(t->B, ctx->stream, GatherNodeFr{g, t->levels[L - 1].phi, a, (fr_plain*)z});
+                            if (e) { rc = fail_hip(ctx, e, "gather"); break; }
+                            size_t mk = ctx->wsp->off;
+                            rc = msm_engine(ctx, ns->pts[0], z, bottom ? t->dtype : TC_FR, t->B, acc + a);
+                            ctx->wsp->off = mk;
+                        }
+                        if (rc) break;
+                    }
+                }
+                if (rc) break;
+                rc = normalize(ctx, acc, lv.n, lv.C);
+                if (rc) break;
+                int e = rt::launch<64>(lv.n, ctx->stream, PhiKernel{lv.C, lv.phi});
+                if (e) rc = fail_hip(ctx, e, "phi");
+            } while (0);
+            ctx->wsp->off = mark;
+        }
+        if (rc == TC_OK) rc = affine_to_host(ctx, t->levels.back().C, 1, t->root);
+        if (rc != TC_OK) {
+            rt::stream_sync(ctx->stream);
+            tc_tree_destroy(t);
+            return rc;
+        }
+        *out = t;
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
     }
-    if (rc == TC_OK) rc = affine_to_host(ctx, t->levels.back().C, 1, t->root);
-    if (rc != TC_OK) {
-        rt::stream_sync(ctx->stream);
-        tc_tree_destroy(t);
-        return rc;
-    }
-    *out = t;
-    return TC_OK;
 }
 
 /* ---- paths ------------------------------------------------------------------------------ */
 extern "C" int tc_path_from_grid(int m, const uint32_t* grid, const uint32_t* node_shape, int leaf_kind,
                                  const uint32_t* leaf_index, int inner_m, const uint32_t* inner_shape,
                                  const uint32_t* inner_index, tc_path* out) {
-    if (!grid || !node_shape || !leaf_index || !out) return TC_ERR_ARG;
-    if (!shape_ok(m, grid, nullptr) || !shape_ok(m, node_shape, nullptr)) return TC_ERR_SHAPE;
-    if (leaf_kind != TC_LEAF_ENTRIES && leaf_kind != TC_LEAF_TENSORS) return TC_ERR_ARG;
-    bool grow = false;
-    for (int j = 0; j < m; ++j) {
-        if (leaf_index[j] >= grid[j]) return TC_ERR_RANGE;
-        grow = grow || node_shape[j] > 1;
-    }
-    if (!grow) return TC_ERR_SHAPE;
-    /* bottom-up, then reversed */
-    uint32_t pos[4] = {0, 0, 0, 0}, g[4] = {1, 1, 1, 1};
-    for (int j = 0; j < m; ++j) { pos[j] = leaf_index[j]; g[j] = grid[j]; }
-    std::vector<std::vector<uint32_t>> kap;
-    bool first = true;
-    for (;;) {
-        bool blocked = !(first && leaf_kind == TC_LEAF_TENSORS);
-        bool all_one = true;
-        if (blocked) {
-            std::vector<uint32_t> k(4, 0);
-            for (int j = 0; j < m; ++j) {
-                k[j] = pos[j] % node_shape[j];
-                pos[j] /= node_shape[j];
-                g[j] = (g[j] + node_shape[j] - 1) / node_shape[j];
+    try {
+        if (!grid || !node_shape || !leaf_index || !out) return TC_ERR_ARG;
+        if (!shape_ok(m, grid, nullptr) || !shape_ok(m, node_shape, nullptr)) return TC_ERR_SHAPE;
+        if (leaf_kind != TC_LEAF_ENTRIES && leaf_kind != TC_LEAF_TENSORS) return TC_ERR_ARG;
+        bool grow = false;
+        for (int j = 0; j < m; ++j) {
+            if (leaf_index[j] >= grid[j]) return TC_ERR_RANGE;
+            grow = grow || node_shape[j] > 1;
+        }
+        if (!grow) return TC_ERR_SHAPE;
+        /* bottom-up, then reversed */
+        uint32_t pos[4] = {0, 0, 0, 0}, g[4] = {1, 1, 1, 1};
+        for (int j = 0; j < m; ++j) { pos[j] = leaf_index[j]; g[j] = grid[j]; }
+        std::vector<std::vector<uint32_t>> kap;
+        bool first = true;
+        for (;;) {
+            bool blocked = !(first && leaf_kind == TC_LEAF_TENSORS);
+            bool all_one = true;
+            if (blocked) {
+                std::vector<uint32_t> k(4, 0);
+                for (int j = 0; j < m; ++j) {
+                    k[j] = pos[j] % node_shape[j];
+                    pos[j] /= node_shape[j];
+                    g[j] = (g[j] + node_shape[j] - 1) / node_shape[j];
+                }
+                kap.push_back(k);
             }
-            kap.push_back(k);
+            for (int j = 0; j < m; ++j) all_one = all_one && g[j] == 1;
+            first = false;
+            if (all_one) break;
+            if (kap.size() >= TC_MAX_STEPS - 1) return TC_ERR_SHAPE;
         }
-        for (int j = 0; j < m; ++j) all_one = all_one && g[j] == 1;
-        first = false;
-        if (all_one) break;
-        if (kap.size() >= TC_MAX_STEPS - 1) return TC_ERR_SHAPE;
-    }
-    memset(out, 0, sizeof *out);
-    int s = 0;
-    for (size_t i = kap.size(); i-- > 0; ++s) {
-        out->m[s] = m;
-        for (int j = 0; j < m; ++j) { out->shape[s][j] = node_shape[j]; out->kappa[s][j] = kap[i][j]; }
-    }
-    if (leaf_kind == TC_LEAF_TENSORS) {
-        if (!inner_shape || !inner_index || !shape_ok(inner_m, inner_shape, nullptr)) return TC_ERR_ARG;
-        out->m[s] = inner_m;
-        for (int j = 0; j < inner_m; ++j) {
-            if (inner_index[j] >= inner_shape[j]) return TC_ERR_RANGE;
-            out->shape[s][j] = inner_shape[j];
-            out->kappa[s][j] = inner_index[j];
+        memset(out, 0, sizeof *out);
+        int s = 0;
+        for (size_t i = kap.size(); i-- > 0; ++s) {
+            out->m[s] = m;
+            for (int j = 0; j < m; ++j) { out->shape[s][j] = node_shape[j]; out->kappa[s][j] = kap[i][j]; }
         }
-        ++s;
+        if (leaf_kind == TC_LEAF_TENSORS) {
+            if (!inner_shape || !inner_index || !shape_ok(inner_m, inner_shape, nullptr)) return TC_ERR_ARG;
+            out->m[s] = inner_m;
+            for (int j = 0; j < inner_m; ++j) {
+                if (inner_index[j] >= inner_shape[j]) return TC_ERR_RANGE;
+                out->shape[s][j] = inner_shape[j];
+                out->kappa[s][j] = inner_index[j];
+            }
+            ++s;
+        }
+        out->n_steps = s;
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return TC_ERR_NOMEM;
+    } catch (...) {
+        return TC_ERR_STATE;
     }
-    out->n_steps = s;
-    return TC_OK;
 }
 
 static uint64_t flat_of(const uint32_t* idx, const uint32_t* grid, int m) {
@@ -1574,368 +1840,398 @@ static uint64_t flat_of(const uint32_t* idx, const uint32_t* grid, int m) {
 
 extern "C" int tc_terkle_open_batch(tc_ctx* ctx, const tc_tree* t, int count, const uint32_t* leaf_index,
                                     const uint32_t* inner_index, void* proof_buf, size_t proof_stride, size_t* proof_len) {
-    if (!ctx) return TC_ERR_ARG;
-    if (!t || count < 0 || (count && (!leaf_index || !proof_buf || !proof_len))) return fail(ctx, TC_ERR_ARG, "null argument");
-    if (t->leaf_kind == TC_LEAF_TENSORS && count && !inner_index) return fail(ctx, TC_ERR_ARG, "inner index missing");
-    if (!count) return TC_OK;
-    const tc_srs* ns = t->node_srs;
-    int m = t->m;
-    for (int a = 0; a < m; ++a)
-        if (!ns->pts[a]) return fail(ctx, TC_ERR_STATE, "node SRS was built without suffix tables");
-    RT(rt::set_device(ctx->device));
-    TRY(ws_reset(ctx));
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!t || count < 0 || (count && (!leaf_index || !proof_buf || !proof_len))) return fail(ctx, TC_ERR_ARG, "null argument");
+        if (t->leaf_kind == TC_LEAF_TENSORS && count && !inner_index) return fail(ctx, TC_ERR_ARG, "inner index missing");
+        if (!count) return TC_OK;
+        const tc_srs* ns = t->node_srs;
+        int m = t->m;
+        for (int a = 0; a < m; ++a)
+            if (!ns->pts[a]) return fail(ctx, TC_ERR_STATE, "node SRS was built without suffix tables");
+        RT(rt::set_device(ctx->device));
+        TRY(ws_reset(ctx));
 
-    int first_blocked = t->leaf_kind == TC_LEAF_TENSORS ? 1 : 0;
-    int n_blocked = (int)t->levels.size() - first_blocked;
-    bool use_fb = ns->fb[0] != nullptr;
-    for (int a = 0; a < m && use_fb; ++a) use_fb = ns->fb[a] != nullptr;
+        int first_blocked = t->leaf_kind == TC_LEAF_TENSORS ? 1 : 0;
+        int n_blocked = (int)t->levels.size() - first_blocked;
+        bool use_fb = ns->fb[0] != nullptr;
+        for (int a = 0; a < m && use_fb; ++a) use_fb = ns->fb[a] != nullptr;
 
-    /* per path: node index and kappa at every blocked level (bottom-up), leaf flat index */
-    struct PathInfo { std::vector<uint64_t> node; std::vector<std::vector<uint32_t>> kap; uint64_t leaf_flat; const uint32_t* inner; };
-    std::vector<PathInfo> P(count);
-    const uint32_t* inner_cursor = inner_index;
-    for (int i = 0; i < count; ++i) {
-        const uint32_t* li = leaf_index + (size_t)i * m;
-        for (int j = 0; j < m; ++j)
-            if (li[j] >= t->grid[j]) return fail(ctx, TC_ERR_RANGE, "leaf index outside the grid");
-        uint32_t pos[4] = {0, 0, 0, 0};
-        for (int j = 0; j < m; ++j) pos[j] = li[j];
-        P[i].leaf_flat = flat_of(pos, t->grid, m);
-        for (int b = 0; b < n_blocked; ++b) {
-            std::vector<uint32_t> k(4, 0);
-            for (int j = 0; j < m; ++j) { k[j] = pos[j] % t->node_shape[j]; pos[j] /= t->node_shape[j]; }
-            P[i].node.push_back(flat_of(pos, t->levels[first_blocked + b].grid, m));
-            P[i].kap.push_back(k);
-        }
-        if (t->leaf_kind == TC_LEAF_TENSORS) {
-            const tc_srs* ls = t->leaf_srs[P[i].leaf_flat];
-            for (int a = 0; a < ls->m; ++a) {
-                if (!ls->pts[a]) return fail(ctx, TC_ERR_STATE, "leaf SRS was built without suffix tables");
-                if (inner_cursor[a] >= ls->shape[a]) return fail(ctx, TC_ERR_RANGE, "inner index outside the leaf tensor");
-            }
-            P[i].inner = inner_cursor;
-            inner_cursor += ls->m;
-        }
-    }
-    /* proof sizes */
-    std::vector<size_t> need(count);
-    for (int i = 0; i < count; ++i) {
-        size_t bytes = (size_t)n_blocked * (96 * (size_t)m + 32 + 96);
-        if (t->leaf_kind == TC_LEAF_TENSORS) bytes += 96 * (size_t)t->leaf_srs[P[i].leaf_flat]->m + 32;
-        else bytes -= 96;                               /* the bottom step carries no child commitment */
-        need[i] = bytes;
-        proof_len[i] = bytes;
-        if (bytes > proof_stride) return fail(ctx, TC_ERR_ARG, "proof buffer too small");
-    }
-
-    /* blocked levels: pi and y for every (path, level) */
-    uint32_t jobs = (uint32_t)count * (uint32_t)n_blocked;
-    std::vector<uint8_t> h_pi((size_t)jobs * m * 96), h_y((size_t)jobs * 32);
-    if (jobs) {
-        WS(d_pi, g1_xyzz, (uint64_t)jobs * m);
-        WS(d_y, fr_plain, jobs);
-        if (use_fb) {
-            NodeOpenTerms k;
-            memset((void*)&k, 0, sizeof k);
-            k.node.m = m;
-            uint32_t terms = 0;
-            for (int j = 0; j < 4; ++j) k.node.d[j] = j < m ? t->node_shape[j] : 1;
-            for (int a = 0; a < m; ++a) {
-                k.axis_first[a] = terms;
-                terms += (uint32_t)ns->n[a];
-                k.ax[a] = ns->ax[a];
-                k.table[a] = ns->fb[a];
-            }
-            for (int a = m; a <= 4; ++a) k.axis_first[a] = terms;
-            k.terms_per_job = terms;
+        /* per path: node index and kappa at every blocked level (bottom-up), leaf flat index */
+        struct PathInfo { std::vector<uint64_t> node; std::vector<std::vector<uint32_t>> kap; uint64_t leaf_flat; const uint32_t* inner; };
+        std::vector<PathInfo> P(count);
+        const uint32_t* inner_cursor = inner_index;
+        for (int i = 0; i < count; ++i) {
+            const uint32_t* li = leaf_index + (size_t)i * m;
+            for (int j = 0; j < m; ++j)
+                if (li[j] >= t->grid[j]) return fail(ctx, TC_ERR_RANGE, "leaf index outside the grid");
+            uint32_t pos[4] = {0, 0, 0, 0};
+            for (int j = 0; j < m; ++j) pos[j] = li[j];
+            P[i].leaf_flat = flat_of(pos, t->grid, m);
             for (int b = 0; b < n_blocked; ++b) {
-                int L = first_blocked + b;
-                const uint32_t* below = L == 0 ? t->grid : t->levels[L - 1].grid;
-                k.lv[b].g = make_geom(t, below, t->levels[L].grid);
-                k.lv[b].payload = L == 0 ? t->d_payload : nullptr;
-                k.lv[b].dtype = t->dtype;
-                k.lv[b].below = L == 0 ? nullptr : t->levels[L - 1].phi;
+                std::vector<uint32_t> k(4, 0);
+                for (int j = 0; j < m; ++j) { k[j] = pos[j] % t->node_shape[j]; pos[j] /= t->node_shape[j]; }
+                P[i].node.push_back(flat_of(pos, t->levels[first_blocked + b].grid, m));
+                P[i].kap.push_back(k);
             }
-            std::vector<NodeOpenJob> hj(jobs);
-            std::vector<uint32_t> seg((size_t)jobs * m + 1);
-            for (int i = 0; i < count; ++i)
-                for (int b = 0; b < n_blocked; ++b) {
-                    uint32_t j = (uint32_t)i * n_blocked + b;
-                    hj[j].node = P[i].node[b];
-                    for (int a = 0; a < 4; ++a) hj[j].kappa[a] = P[i].kap[b][a];
-                    hj[j].level = b;
-                    hj[j].term0 = j * terms;
-                    for (int a = 0; a < m; ++a) seg[(size_t)j * m + a] = j * terms + k.axis_first[a];
+            if (t->leaf_kind == TC_LEAF_TENSORS) {
+                const tc_srs* ls = t->leaf_srs[P[i].leaf_flat];
+                for (int a = 0; a < ls->m; ++a) {
+                    if (!ls->pts[a]) return fail(ctx, TC_ERR_STATE, "leaf SRS was built without suffix tables");
+                    if (inner_cursor[a] >= ls->shape[a]) return fail(ctx, TC_ERR_RANGE, "inner index outside the leaf tensor");
                 }
-            seg[(size_t)jobs * m] = jobs * terms;
-            WS(d_jobs, NodeOpenJob, jobs);
-            WS(d_seg, uint32_t, (uint64_t)jobs * m + 1);
-            int logH = 0;
-            while ((2u << logH) < (uint32_t)FB_W) ++logH;
-            if ((((uint64_t)jobs * terms) << logH) > 0xFFFFFFFFull) return fail(ctx, TC_ERR_ARG, "too many openings in one batch");
-            WS(d_terms, g1_xyzz, ((uint64_t)jobs * terms) << logH);
-            TRY(h2d(ctx, d_jobs, hj.data(), sizeof(NodeOpenJob) * jobs));
-            TRY(h2d(ctx, d_seg, seg.data(), 4 * seg.size()));
-            k.jobs = d_jobs;
-            k.out = d_terms;
-            k.y_out = d_y;
-            k.logH = logH;
-            RT(rt::launch<64>(((uint64_t)jobs * terms) << logH, ctx->stream, k));
-            typedef CoopReduce<SegmentSrc> Sum;
-            RT((launch_coop<Sum::BLOCK>(jobs * (uint32_t)m, ctx->stream, Sum{SegmentSrc{d_terms, d_seg, 1u << logH, d_pi}})));
-        } else {
-            /* large node shapes: gather the node tensor and open it like any tensor */
+                P[i].inner = inner_cursor;
+                inner_cursor += ls->m;
+            }
+        }
+        /* proof sizes */
+        std::vector<size_t> need(count);
+        for (int i = 0; i < count; ++i) {
+            size_t bytes = (size_t)n_blocked * (96 * (size_t)m + 32 + 96);
+            if (t->leaf_kind == TC_LEAF_TENSORS) bytes += 96 * (size_t)t->leaf_srs[P[i].leaf_flat]->m + 32;
+            else bytes -= 96;                               /* the bottom step carries no child commitment */
+            need[i] = bytes;
+            proof_len[i] = bytes;
+            if (bytes > proof_stride) return fail(ctx, TC_ERR_ARG, "proof buffer too small");
+        }
+
+        /* blocked levels: pi and y for every (path, level) */
+        uint32_t jobs = (uint32_t)count * (uint32_t)n_blocked;
+        std::vector<uint8_t> h_pi((size_t)jobs * m * 96), h_y((size_t)jobs * 32);
+        if (jobs) {
+            WS(d_pi, g1_xyzz, (uint64_t)jobs * m);
+            WS(d_y, fr_plain, jobs);
+            if (use_fb) {
+                NodeOpenTerms k;
+                memset((void*)&k, 0, sizeof k);
+                k.node.m = m;
+                uint32_t terms = 0;
+                for (int j = 0; j < 4; ++j) k.node.d[j] = j < m ? t->node_shape[j] : 1;
+                for (int a = 0; a < m; ++a) {
+                    k.axis_first[a] = terms;
+                    terms += (uint32_t)ns->n[a];
+                    k.ax[a] = ns->ax[a];
+                    k.table[a] = ns->fb[a];
+                }
+                for (int a = m; a <= 4; ++a) k.axis_first[a] = terms;
+                k.terms_per_job = terms;
+                for (int b = 0; b < n_blocked; ++b) {
+                    int L = first_blocked + b;
+                    const uint32_t* below = L == 0 ? t->grid : t->levels[L - 1].grid;
+                    k.lv[b].g = make_geom(t, below, t->levels[L].grid);
+                    k.lv[b].payload = L == 0 ? t->d_payload : nullptr;
+                    k.lv[b].dtype = t->dtype;
+                    k.lv[b].below = L == 0 ? nullptr : t->levels[L - 1].phi;
+                }
+                std::vector<NodeOpenJob> hj(jobs);
+                std::vector<uint32_t> seg((size_t)jobs * m + 1);
+                for (int i = 0; i < count; ++i)
+                    for (int b = 0; b < n_blocked; ++b) {
+                        uint32_t j = (uint32_t)i * n_blocked + b;
+                        hj[j].node = P[i].node[b];
+                        for (int a = 0; a < 4; ++a) hj[j].kappa[a] = P[i].kap[b][a];
+                        hj[j].level = b;
+                        hj[j].term0 = j * terms;
+                        for (int a = 0; a < m; ++a) seg[(size_t)j * m + a] = j * terms + k.axis_first[a];
+                    }
+                seg[(size_t)jobs * m] = jobs * terms;
+                WS(d_jobs, NodeOpenJob, jobs);
+                WS(d_seg, uint32_t, (uint64_t)jobs * m + 1);
+                int logH = 0;
+                while ((2u << logH) < (uint32_t)FB_W) ++logH;
+                if ((((uint64_t)jobs * terms) << logH) > 0xFFFFFFFFull) return fail(ctx, TC_ERR_ARG, "too many openings in one batch");
+                WS(d_terms, g1_xyzz, ((uint64_t)jobs * terms) << logH);
+                TRY(h2d(ctx, d_jobs, hj.data(), sizeof(NodeOpenJob) * jobs));
+                TRY(h2d(ctx, d_seg, seg.data(), 4 * seg.size()));
+                k.jobs = d_jobs;
+                k.out = d_terms;
+                k.y_out = d_y;
+                k.logH = logH;
+                RT(rt::launch<64>(((uint64_t)jobs * terms) << logH, ctx->stream, k));
+                typedef CoopReduce<SegmentSrc> Sum;
+                RT((launch_coop<Sum::BLOCK>(jobs * (uint32_t)m, ctx->stream, Sum{SegmentSrc{d_terms, d_seg, 1u << logH, d_pi}})));
+            } else {
+                /* large node shapes: gather the node tensor and open it like any tensor */
+                for (int i = 0; i < count; ++i)
+                    for (int b = 0; b < n_blocked; ++b) {
+                        int L = first_blocked + b;
+                        uint32_t j = (uint32_t)i * n_blocked + b;
+                        const uint32_t* below = L == 0 ? t->grid : t->levels[L - 1].grid;
+                        TreeGeom g = make_geom(t, below, t->levels[L].grid);
+                        size_t mk = ctx->wsp->off;
+                        bool bottom = L == 0;
+                        void* z = ws_alloc(ctx, (size_t)t->B * (bottom ? dtype_size(t->dtype) : 32));
+                        if (!z) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed");
+                        if (bottom) RT(rt::launch<64>(t->B, ctx->stream, GatherNodeSmall{g, t->d_payload, t->dtype, P[i].node[b], z}));
+                        else RT(rt::launch<64>(t->B, ctx->stream, GatherNodeFr{g, t->levels[L - 1].phi, P[i].node[b], (fr_plain*)z}));
+                        uint32_t kap[4];
+                        for (int a = 0; a < 4; ++a) kap[a] = P[i].kap[b][a];
+                        TRY(open_device(ctx, ns, z, bottom ? t->dtype : TC_FR, kap, d_pi + (uint64_t)j * m, d_y + j));
+                        ctx->wsp->off = mk;
+                    }
+            }
+            RT(rt::memcpy_d2h(h_y.data(), d_y, 32ull * jobs, ctx->stream));
+            TRY(points_to_host(ctx, d_pi, jobs * (uint32_t)m, h_pi.data()));
+        }
+        /* leaf tensors: all openings in one batch */
+        std::vector<std::vector<uint8_t>> leaf_part(count);
+        if (t->leaf_kind == TC_LEAF_TENSORS) {
+            std::vector<OpenSpec> specs(count);
+            for (int i = 0; i < count; ++i) {
+                const tc_srs* ls = t->leaf_srs[P[i].leaf_flat];
+                specs[i].srs = ls;
+                specs[i].scalars = t->leaf_scalars[P[i].leaf_flat];
+                specs[i].dtype = t->leaf_dtype[P[i].leaf_flat];
+                for (int a = 0; a < 4; ++a) specs[i].kappa[a] = a < ls->m ? P[i].inner[a] : 0;
+            }
+            WS(pi, g1_xyzz, 4ull * count);
+            WS(y, fr_plain, (uint32_t)count);
+            RT(rt::launch<64>(4ull * count, ctx->stream, FillIdentity{pi}));     /* slots of unused axes */
+            TRY(open_device_batch(ctx, count, specs.data(), pi, y));
+            std::vector<uint8_t> hy(32ull * count), hp(96ull * 4 * count);
+            RT(rt::memcpy_d2h(hy.data(), y, 32ull * count, ctx->stream));
+            TRY(points_to_host(ctx, pi, 4u * (uint32_t)count, hp.data()));
+            for (int i = 0; i < count; ++i) {
+                int lm = specs[i].srs->m;
+                leaf_part[i].resize(96 * (size_t)lm + 32);
+                memcpy(leaf_part[i].data(), hp.data() + 96ull * 4 * i, 96 * (size_t)lm);
+                memcpy(leaf_part[i].data() + 96 * (size_t)lm, hy.data() + 32ull * i, 32);
+            }
+        }
+        /* child commitments along the paths */
+        uint32_t n_child = 0;
+        std::vector<uint8_t> h_child;
+        {
+            /* for blocked level b (0 = lowest blocked) the child is the node of the level below on the path */
+            std::vector<std::pair<int, uint64_t>> want;     /* (level, node) */
             for (int i = 0; i < count; ++i)
                 for (int b = 0; b < n_blocked; ++b) {
                     int L = first_blocked + b;
-                    uint32_t j = (uint32_t)i * n_blocked + b;
-                    const uint32_t* below = L == 0 ? t->grid : t->levels[L - 1].grid;
-                    TreeGeom g = make_geom(t, below, t->levels[L].grid);
-                    size_t mk = ctx->ws.off;
-                    bool bottom = L == 0;
-                    void* z = ws_alloc(ctx, (size_t)t->B * (bottom ? dtype_size(t->dtype) : 32));
-                    if (!z) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed");
-                    if (bottom) RT(rt::launch<64>(t->B, ctx->stream, GatherNodeSmall{g, t->d_payload, t->dtype, P[i].node[b], z}));
-                    else RT(rt::launch<64>(t->B, ctx->stream, GatherNodeFr{g, t->levels[L - 1].phi, P[i].node[b], (fr_plain*)z}));
-                    uint32_t kap[4];
-                    for (int a = 0; a < 4; ++a) kap[a] = P[i].kap[b][a];
-                    TRY(open_device(ctx, ns, z, bottom ? t->dtype : TC_FR, kap, d_pi + (uint64_t)j * m, d_y + j));
-                    ctx->ws.off = mk;
+                    if (L == 0) continue;
+                    uint64_t child = (b == 0) ? P[i].leaf_flat : P[i].node[b - 1];
+                    want.push_back({L - 1, child});
                 }
-        }
-        RT(rt::memcpy_d2h(h_y.data(), d_y, 32ull * jobs, ctx->stream));
-        TRY(points_to_host(ctx, d_pi, jobs * (uint32_t)m, h_pi.data()));
-    }
-    /* leaf tensors: all openings in one batch */
-    std::vector<std::vector<uint8_t>> leaf_part(count);
-    if (t->leaf_kind == TC_LEAF_TENSORS) {
-        std::vector<OpenSpec> specs(count);
-        for (int i = 0; i < count; ++i) {
-            const tc_srs* ls = t->leaf_srs[P[i].leaf_flat];
-            specs[i].srs = ls;
-            specs[i].scalars = t->leaf_scalars[P[i].leaf_flat];
-            specs[i].dtype = t->leaf_dtype[P[i].leaf_flat];
-            for (int a = 0; a < 4; ++a) specs[i].kappa[a] = a < ls->m ? P[i].inner[a] : 0;
-        }
-        WS(pi, g1_xyzz, 4ull * count);
-        WS(y, fr_plain, (uint32_t)count);
-        RT(rt::launch<64>(4ull * count, ctx->stream, FillIdentity{pi}));     /* slots of unused axes */
-        TRY(open_device_batch(ctx, count, specs.data(), pi, y));
-        std::vector<uint8_t> hy(32ull * count), hp(96ull * 4 * count);
-        RT(rt::memcpy_d2h(hy.data(), y, 32ull * count, ctx->stream));
-        TRY(points_to_host(ctx, pi, 4u * (uint32_t)count, hp.data()));
-        for (int i = 0; i < count; ++i) {
-            int lm = specs[i].srs->m;
-            leaf_part[i].resize(96 * (size_t)lm + 32);
-            memcpy(leaf_part[i].data(), hp.data() + 96ull * 4 * i, 96 * (size_t)lm);
-            memcpy(leaf_part[i].data() + 96 * (size_t)lm, hy.data() + 32ull * i, 32);
-        }
-    }
-    /* child commitments along the paths */
-    uint32_t n_child = 0;
-    std::vector<uint8_t> h_child;
-    {
-        /* for blocked level b (0 = lowest blocked) the child is the node of the level below on the path */
-        std::vector<std::pair<int, uint64_t>> want;     /* (level, node) */
-        for (int i = 0; i < count; ++i)
-            for (int b = 0; b < n_blocked; ++b) {
-                int L = first_blocked + b;
-                if (L == 0) continue;
-                uint64_t child = (b == 0) ? P[i].leaf_flat : P[i].node[b - 1];
-                want.push_back({L - 1, child});
-            }
-        n_child = (uint32_t)want.size();
-        if (n_child) {
-            std::vector<const g1_affine*> src(n_child);
-            for (uint32_t w = 0; w < n_child; ++w) src[w] = t->levels[want[w].first].C + want[w].second;
-            WS(d_src, const g1_affine*, n_child);
-            WS(can, uint32_t, 24ull * n_child);
-            TRY(h2d(ctx, d_src, src.data(), sizeof(const g1_affine*) * n_child));
-            RT(rt::launch<64>(n_child, ctx->stream, ToCanonicalGather{d_src, can}));
-            h_child.resize(96ull * n_child);
-            RT(rt::memcpy_d2h(h_child.data(), can, 96ull * n_child, ctx->stream));
-            TRY(ctx_sync(ctx));
-        }
-    }
-    /* assemble, top level first */
-    uint32_t child_cursor = 0;
-    for (int i = 0; i < count; ++i) {
-        uint8_t* dst = (uint8_t*)proof_buf + (size_t)i * proof_stride;
-        /* children were queued bottom-up for this path */
-        uint32_t n_child_i = 0;
-        for (int b = 0; b < n_blocked; ++b)
-            if (first_blocked + b > 0) ++n_child_i;
-        for (int b = n_blocked - 1; b >= 0; --b) {
-            uint32_t j = (uint32_t)i * n_blocked + b;
-            memcpy(dst, h_pi.data() + (size_t)j * m * 96, 96 * (size_t)m);
-            dst += 96 * (size_t)m;
-            memcpy(dst, h_y.data() + 32 * (size_t)j, 32);
-            dst += 32;
-            if (first_blocked + b > 0) {
-                uint32_t slot = child_cursor + (uint32_t)(b - (first_blocked ? 0 : 1));
-                memcpy(dst, h_child.data() + 96ull * slot, 96);
-                dst += 96;
+            n_child = (uint32_t)want.size();
+            if (n_child) {
+                std::vector<const g1_affine*> src(n_child);
+                for (uint32_t w = 0; w < n_child; ++w) src[w] = t->levels[want[w].first].C + want[w].second;
+                WS(d_src, const g1_affine*, n_child);
+                WS(can, uint32_t, 24ull * n_child);
+                TRY(h2d(ctx, d_src, src.data(), sizeof(const g1_affine*) * n_child));
+                RT(rt::launch<64>(n_child, ctx->stream, ToCanonicalGather{d_src, can}));
+                h_child.resize(96ull * n_child);
+                RT(rt::memcpy_d2h(h_child.data(), can, 96ull * n_child, ctx->stream));
+                TRY(ctx_sync(ctx));
             }
         }
-        child_cursor += n_child_i;
-        if (t->leaf_kind == TC_LEAF_TENSORS) {
-            memcpy(dst, leaf_part[i].data(), leaf_part[i].size());
-            dst += leaf_part[i].size();
+        /* assemble, top level first */
+        uint32_t child_cursor = 0;
+        for (int i = 0; i < count; ++i) {
+            uint8_t* dst = (uint8_t*)proof_buf + (size_t)i * proof_stride;
+            /* children were queued bottom-up for this path */
+            uint32_t n_child_i = 0;
+            for (int b = 0; b < n_blocked; ++b)
+                if (first_blocked + b > 0) ++n_child_i;
+            for (int b = n_blocked - 1; b >= 0; --b) {
+                uint32_t j = (uint32_t)i * n_blocked + b;
+                memcpy(dst, h_pi.data() + (size_t)j * m * 96, 96 * (size_t)m);
+                dst += 96 * (size_t)m;
+                memcpy(dst, h_y.data() + 32 * (size_t)j, 32);
+                dst += 32;
+                if (first_blocked + b > 0) {
+                    uint32_t slot = child_cursor + (uint32_t)(b - (first_blocked ? 0 : 1));
+                    memcpy(dst, h_child.data() + 96ull * slot, 96);
+                    dst += 96;
+                }
+            }
+            child_cursor += n_child_i;
+            if (t->leaf_kind == TC_LEAF_TENSORS) {
+                memcpy(dst, leaf_part[i].data(), leaf_part[i].size());
+                dst += leaf_part[i].size();
+            }
+            if ((size_t)(dst - ((uint8_t*)proof_buf + (size_t)i * proof_stride)) != need[i]) return fail(ctx, TC_ERR_STATE, "internal: proof size mismatch");
         }
-        if ((size_t)(dst - ((uint8_t*)proof_buf + (size_t)i * proof_stride)) != need[i]) return fail(ctx, TC_ERR_STATE, "internal: proof size mismatch");
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
     }
-    return TC_OK;
 }
 
 extern "C" int tc_terkle_open(tc_ctx* ctx, const tc_tree* tree, const uint32_t* leaf_index, const uint32_t* inner_index,
                               void* proof_buf, size_t* proof_len) {
-    if (!ctx) return TC_ERR_ARG;
-    if (!proof_len) return fail(ctx, TC_ERR_ARG, "null argument");
-    size_t cap = *proof_len;
-    return tc_terkle_open_batch(ctx, tree, 1, leaf_index, inner_index, proof_buf, cap, proof_len);
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!proof_len) return fail(ctx, TC_ERR_ARG, "null argument");
+        size_t cap = *proof_len;
+        return tc_terkle_open_batch(ctx, tree, 1, leaf_index, inner_index, proof_buf, cap, proof_len);
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
 }
 
 /* ---- path verification --------------------------------------------------------------------- */
 extern "C" int tc_verify_paths_batch(tc_ctx* ctx, const tc_vk* vk, int count, const tc_path* paths, const uint8_t* roots,
                                      const uint8_t* leaf_values, const void* proofs, size_t proof_stride,
                                      const size_t* proof_len, int* results) {
-    if (!ctx) return TC_ERR_ARG;
-    if (!vk || count < 0 || (count && (!paths || !roots || !leaf_values || !proofs || !proof_len || !results)))
-        return fail(ctx, TC_ERR_ARG, "null argument");
-    if (!count) return TC_OK;
-    RT(rt::set_device(ctx->device));
-    TRY(ws_reset(ctx));
-    std::vector<VerifyStep> steps;
-    std::vector<int> first_step(count + 1, 0);
-    std::vector<uint8_t> malformed(count, 0);
-    std::vector<std::vector<uint8_t>> child_bytes;        /* per step: commitment carried to the next step (or empty) */
-    for (int i = 0; i < count; ++i) {
-        const tc_path& p = paths[i];
-        first_step[i] = (int)steps.size();
-        const uint8_t* src = (const uint8_t*)proofs + (size_t)i * proof_stride;
-        size_t expect = 0;
-        bool bad = p.n_steps < 1 || p.n_steps > TC_MAX_STEPS;
-        for (int s = 0; s < p.n_steps && !bad; ++s) {
-            if (p.m[s] < 1 || p.m[s] > vk->m || !shape_ok(p.m[s], p.shape[s], nullptr)) bad = true;
-            else {
-                for (int j = 0; j < p.m[s]; ++j) bad = bad || p.kappa[s][j] >= p.shape[s][j];
-                expect += 96 * (size_t)p.m[s] + 32 + (s + 1 < p.n_steps ? 96 : 0);
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!vk || count < 0 || (count && (!paths || !roots || !leaf_values || !proofs || !proof_len || !results)))
+            return fail(ctx, TC_ERR_ARG, "null argument");
+        if (!count) return TC_OK;
+        RT(rt::set_device(ctx->device));
+        TRY(ws_reset(ctx));
+        std::vector<VerifyStep> steps;
+        std::vector<int> first_step(count + 1, 0);
+        std::vector<uint8_t> malformed(count, 0);
+        std::vector<std::vector<uint8_t>> child_bytes;        /* per step: commitment carried to the next step (or empty) */
+        for (int i = 0; i < count; ++i) {
+            const tc_path& p = paths[i];
+            first_step[i] = (int)steps.size();
+            const uint8_t* src = (const uint8_t*)proofs + (size_t)i * proof_stride;
+            size_t expect = 0;
+            bool bad = p.n_steps < 1 || p.n_steps > TC_MAX_STEPS;
+            for (int s = 0; s < p.n_steps && !bad; ++s) {
+                if (p.m[s] < 1 || p.m[s] > vk->m || !shape_ok(p.m[s], p.shape[s], nullptr)) bad = true;
+                else {
+                    for (int j = 0; j < p.m[s]; ++j) bad = bad || p.kappa[s][j] >= p.shape[s][j];
+                    expect += 96 * (size_t)p.m[s] + 32 + (s + 1 < p.n_steps ? 96 : 0);
+                }
+            }
+            if (bad || expect != proof_len[i]) {
+                malformed[i] = 1;
+                continue;
+            }
+            const uint8_t* carried = roots + 96 * (size_t)i;
+            for (int s = 0; s < p.n_steps; ++s) {
+                VerifyStep st;
+                memset(&st, 0, sizeof st);
+                st.m = p.m[s];
+                memcpy(st.C, carried, 96);
+                for (int j = 0; j < st.m; ++j) {
+                    memcpy(st.pi[j], src, 96);
+                    src += 96;
+                }
+                fill_step_scalars(vk, p.kappa[s], &st);
+                memcpy(st.y, src, 32);
+                src += 32;
+                steps.push_back(st);
+                if (s + 1 < p.n_steps) {
+                    child_bytes.emplace_back(src, src + 96);
+                    carried = src;
+                    src += 96;
+                } else {
+                    child_bytes.emplace_back();
+                }
             }
         }
-        if (bad || expect != proof_len[i]) {
-            malformed[i] = 1;
-            continue;
+        first_step[count] = (int)steps.size();
+        std::vector<uint32_t> ok;
+        TRY(verify_steps(ctx, vk, steps, ok));
+        /* phi of every carried commitment, on the device */
+        uint32_t ns = (uint32_t)steps.size();
+        std::vector<uint8_t> h_phi(32ull * (ns ? ns : 1), 0);
+        if (ns) {
+            std::vector<uint32_t> pts(24ull * ns, 0);
+            for (uint32_t s = 0; s < ns; ++s)
+                if (!child_bytes[s].empty()) memcpy(&pts[24ull * s], child_bytes[s].data(), 96);
+            WS(d_pts, uint32_t, 24ull * ns);
+            WS(d_phi, fr_plain, ns);
+            TRY(h2d(ctx, d_pts, pts.data(), 96ull * ns));
+            RT(rt::launch<64>(ns, ctx->stream, PhiCanonical{d_pts, d_phi}));
+            RT(rt::memcpy_d2h(h_phi.data(), d_phi, 32ull * ns, ctx->stream));
+            TRY(ctx_sync(ctx));
         }
-        const uint8_t* carried = roots + 96 * (size_t)i;
-        for (int s = 0; s < p.n_steps; ++s) {
-            VerifyStep st;
-            memset(&st, 0, sizeof st);
-            st.m = p.m[s];
-            memcpy(st.C, carried, 96);
-            for (int j = 0; j < st.m; ++j) {
-                memcpy(st.pi[j], src, 96);
-                src += 96;
+        for (int i = 0; i < count; ++i) {
+            if (malformed[i]) { results[i] = TC_ERR_VERIFY; continue; }
+            bool good = true;
+            for (int s = first_step[i]; s < first_step[i + 1]; ++s) {
+                good = good && ok[s];
+                bool last = s + 1 == first_step[i + 1];
+                const uint8_t* yb = (const uint8_t*)steps[s].y;
+                if (last) good = good && memcmp(yb, leaf_values + 32 * (size_t)i, 32) == 0;
+                else good = good && memcmp(yb, &h_phi[32ull * s], 32) == 0;
             }
-            fill_step_scalars(vk, p.kappa[s], &st);
-            memcpy(st.y, src, 32);
-            src += 32;
-            steps.push_back(st);
-            if (s + 1 < p.n_steps) {
-                child_bytes.emplace_back(src, src + 96);
-                carried = src;
-                src += 96;
-            } else {
-                child_bytes.emplace_back();
-            }
+            results[i] = good ? TC_OK : TC_ERR_VERIFY;
         }
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
     }
-    first_step[count] = (int)steps.size();
-    std::vector<uint32_t> ok;
-    TRY(verify_steps(ctx, vk, steps, ok));
-    /* phi of every carried commitment, on the device */
-    uint32_t ns = (uint32_t)steps.size();
-    std::vector<uint8_t> h_phi(32ull * (ns ? ns : 1), 0);
-    if (ns) {
-        std::vector<uint32_t> pts(24ull * ns, 0);
-        for (uint32_t s = 0; s < ns; ++s)
-            if (!child_bytes[s].empty()) memcpy(&pts[24ull * s], child_bytes[s].data(), 96);
-        WS(d_pts, uint32_t, 24ull * ns);
-        WS(d_phi, fr_plain, ns);
-        TRY(h2d(ctx, d_pts, pts.data(), 96ull * ns));
-        RT(rt::launch<64>(ns, ctx->stream, PhiCanonical{d_pts, d_phi}));
-        RT(rt::memcpy_d2h(h_phi.data(), d_phi, 32ull * ns, ctx->stream));
-        TRY(ctx_sync(ctx));
-    }
-    for (int i = 0; i < count; ++i) {
-        if (malformed[i]) { results[i] = TC_ERR_VERIFY; continue; }
-        bool good = true;
-        for (int s = first_step[i]; s < first_step[i + 1]; ++s) {
-            good = good && ok[s];
-            bool last = s + 1 == first_step[i + 1];
-            const uint8_t* yb = (const uint8_t*)steps[s].y;
-            if (last) good = good && memcmp(yb, leaf_values + 32 * (size_t)i, 32) == 0;
-            else good = good && memcmp(yb, &h_phi[32ull * s], 32) == 0;
-        }
-        results[i] = good ? TC_OK : TC_ERR_VERIFY;
-    }
-    return TC_OK;
 }
 
 extern "C" int tc_verify_path(tc_ctx* ctx, const tc_vk* vk, const tc_path* path, const uint8_t root[96],
                               const uint8_t leaf_value[32], const void* proof, size_t proof_len) {
-    if (!ctx) return TC_ERR_ARG;
-    int result = TC_ERR_VERIFY;
-    int rc = tc_verify_paths_batch(ctx, vk, 1, path, root, leaf_value, proof, proof_len, &proof_len, &result);
-    if (rc != TC_OK) return rc;
-    if (result != TC_OK) return fail(ctx, TC_ERR_VERIFY, "path rejected");
-    return TC_OK;
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        int result = TC_ERR_VERIFY;
+        int rc = tc_verify_paths_batch(ctx, vk, 1, path, root, leaf_value, proof, proof_len, &proof_len, &result);
+        if (rc != TC_OK) return rc;
+        if (result != TC_OK) return fail(ctx, TC_ERR_VERIFY, "path rejected");
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
 }
 
 /* ---- incremental update --------------------------------------------------------------------- */
 extern "C" int tc_terkle_update(tc_ctx* ctx, tc_tree* tree, const uint32_t* leaf_index, const uint32_t* inner_index,
                                 int64_t delta) {
-    if (!ctx) return TC_ERR_ARG;
-    if (!tree || !leaf_index) return fail(ctx, TC_ERR_ARG, "null argument");
-    tc_tree* t = tree;
-    if (delta >= (1ll << 32) || delta <= -(1ll << 32)) return fail(ctx, TC_ERR_RANGE, "delta too large");
-    const tc_srs* ns = t->node_srs;
-    if (!ns->fb[0]) return fail(ctx, TC_ERR_STATE, "updates need the fixed-base node SRS");
-    int m = t->m;
-    for (int j = 0; j < m; ++j)
-        if (leaf_index[j] >= t->grid[j]) return fail(ctx, TC_ERR_RANGE, "leaf index outside the grid");
-    bool tensors = t->leaf_kind == TC_LEAF_TENSORS;
-    if (tensors && !inner_index) return fail(ctx, TC_ERR_ARG, "inner index missing");
-    RT(rt::set_device(ctx->device));
-    TRY(ws_reset(ctx));
-    WS(d_dphi, fr_plain, 1);
-    typedef CoopReduce<UpdatePathSrc> Upd;
-    uint32_t pos[4] = {0, 0, 0, 0};
-    for (int j = 0; j < m; ++j) pos[j] = leaf_index[j];
-    int level = 0;
-    int from_dphi = 0;
-    if (tensors) {
-        uint64_t leaf_flat = flat_of(pos, t->grid, m);
-        const tc_srs* ls = t->leaf_srs[leaf_flat];
-        uint64_t inner_flat = 0;
-        for (int a = 0; a < ls->m; ++a) {
-            if (inner_index[a] >= ls->shape[a]) return fail(ctx, TC_ERR_RANGE, "inner index outside the leaf tensor");
-            inner_flat = inner_flat * ls->shape[a] + inner_index[a];
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!tree || !leaf_index) return fail(ctx, TC_ERR_ARG, "null argument");
+        tc_tree* t = tree;
+        if (delta >= (1ll << 32) || delta <= -(1ll << 32)) return fail(ctx, TC_ERR_RANGE, "delta too large");
+        const tc_srs* ns = t->node_srs;
+        if (!ns->fb[0]) return fail(ctx, TC_ERR_STATE, "updates need the fixed-base node SRS");
+        int m = t->m;
+        for (int j = 0; j < m; ++j)
+            if (leaf_index[j] >= t->grid[j]) return fail(ctx, TC_ERR_RANGE, "leaf index outside the grid");
+        bool tensors = t->leaf_kind == TC_LEAF_TENSORS;
+        if (tensors && !inner_index) return fail(ctx, TC_ERR_ARG, "inner index missing");
+        RT(rt::set_device(ctx->device));
+        TRY(ws_reset(ctx));
+        WS(d_dphi, fr_plain, 1);
+        typedef CoopReduce<UpdatePathSrc> Upd;
+        uint32_t pos[4] = {0, 0, 0, 0};
+        for (int j = 0; j < m; ++j) pos[j] = leaf_index[j];
+        int level = 0;
+        int from_dphi = 0;
+        if (tensors) {
+            uint64_t leaf_flat = flat_of(pos, t->grid, m);
+            const tc_srs* ls = t->leaf_srs[leaf_flat];
+            uint64_t inner_flat = 0;
+            for (int a = 0; a < ls->m; ++a) {
+                if (inner_index[a] >= ls->shape[a]) return fail(ctx, TC_ERR_RANGE, "inner index outside the leaf tensor");
+                inner_flat = inner_flat * ls->shape[a] + inner_index[a];
+            }
+            RT((launch_coop<Upd::BLOCK>(1, ctx->stream, Upd{UpdatePathSrc{t->levels[0].C, t->levels[0].phi, leaf_flat, nullptr, 0,
+                                                                          ls->pts[0] + inner_flat, delta, 0, d_dphi}})));
+            level = 1;
+            from_dphi = 1;
         }
-        RT((launch_coop<Upd::BLOCK>(1, ctx->stream, Upd{UpdatePathSrc{t->levels[0].C, t->levels[0].phi, leaf_flat, nullptr, 0,
-                                                                      ls->pts[0] + inner_flat, delta, 0, d_dphi}})));
-        level = 1;
-        from_dphi = 1;
+        for (; level < (int)t->levels.size(); ++level) {
+            uint32_t k[4] = {0, 0, 0, 0};
+            for (int j = 0; j < m; ++j) { k[j] = pos[j] % t->node_shape[j]; pos[j] /= t->node_shape[j]; }
+            uint64_t a = flat_of(pos, t->levels[level].grid, m);
+            uint32_t kf = (uint32_t)flat_of(k, t->node_shape, m);
+            RT((launch_coop<Upd::BLOCK>(1, ctx->stream, Upd{UpdatePathSrc{t->levels[level].C, t->levels[level].phi, a, ns->fb[0], kf,
+                                                                          nullptr, delta, from_dphi, d_dphi}})));
+            from_dphi = 1;
+        }
+        return affine_to_host(ctx, t->levels.back().C, 1, t->root);
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
     }
-    for (; level < (int)t->levels.size(); ++level) {
-        uint32_t k[4] = {0, 0, 0, 0};
-        for (int j = 0; j < m; ++j) { k[j] = pos[j] % t->node_shape[j]; pos[j] /= t->node_shape[j]; }
-        uint64_t a = flat_of(pos, t->levels[level].grid, m);
-        uint32_t kf = (uint32_t)flat_of(k, t->node_shape, m);
-        RT((launch_coop<Upd::BLOCK>(1, ctx->stream, Upd{UpdatePathSrc{t->levels[level].C, t->levels[level].phi, a, ns->fb[0], kf,
-                                                                      nullptr, delta, from_dphi, d_dphi}})));
-        from_dphi = 1;
-    }
-    return affine_to_host(ctx, t->levels.back().C, 1, t->root);
 }
 
 /* ======================================================================================= */
@@ -1955,108 +2251,126 @@ static bool interp_shape_ok(int m, const uint32_t* shape, uint64_t* total) {
 
 extern "C" int tc_interpolate_form(tc_ctx* ctx, int m, const uint32_t* shape, const void* d_scalars, int dtype, int form,
                                    void* d_coeffs) {
-    if (!ctx) return TC_ERR_ARG;
-    if (!d_scalars || !d_coeffs) return fail(ctx, TC_ERR_ARG, "null argument");
-    if (!valid_dtype_scalar(dtype)) return fail(ctx, TC_ERR_ARG, "unsupported scalar dtype");
-    if (form != TC_INTERP_NEWTON && form != TC_INTERP_GREGORY && form != TC_INTERP_BARYCENTRIC)
-        return fail(ctx, TC_ERR_ARG, "unknown interpolation form");
-    uint64_t n = 0;
-    if (!interp_shape_ok(m, shape, &n)) return fail(ctx, TC_ERR_SHAPE, "bad shape");
-    RT(rt::set_device(ctx->device));
-    TRY(ws_reset(ctx));
-    uint32_t dmax = 1;
-    for (int j = 0; j < m; ++j) dmax = std::max(dmax, shape[j]);
-    /* 1 / l, 1 / l! and zeta_k = k + 1 up to the longest axis */
-    std::vector<fr_t> inv(dmax), zeta(dmax), inv_fact(dmax);
-    for (uint32_t i = 0; i < dmax; ++i) {
-        inv[i] = fe_from_u32<FrParams>(i ? i : 1);
-        zeta[i] = fe_from_u32<FrParams>(i + 1);
-    }
-    fr_batch_inverse(inv);
-    inv_fact[0] = fe_one<FrParams>();
-    for (uint32_t i = 1; i < dmax; ++i) inv_fact[i] = fr_mul(inv_fact[i - 1], inv[i]);
-    WS(d_inv, fr_t, dmax);
-    WS(d_zeta, fr_t, dmax);
-    WS(d_aux, fr_t, dmax);             /* 1 / l! (Gregory) or the weights beta of the current axis (barycentric) */
-    TRY(h2d(ctx, d_inv, inv.data(), sizeof(fr_t) * dmax));
-    TRY(h2d(ctx, d_zeta, zeta.data(), sizeof(fr_t) * dmax));
-    if (form == TC_INTERP_GREGORY) TRY(h2d(ctx, d_aux, inv_fact.data(), sizeof(fr_t) * dmax));
-    const int nbuf = form == TC_INTERP_BARYCENTRIC ? 5 : 3;
-    fr_t* buf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
-    for (int i = 0; i < nbuf; ++i) {
-        buf[i] = ws_array<fr_t>(ctx, n);
-        if (!buf[i]) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed");
-    }
-    RT(rt::launch<256>(n, ctx->stream, ScalarsToFr{d_scalars, dtype, buf[0]}));
-    std::vector<fr_t> beta;
-    uint64_t outer = 1;
-    for (int j = 0; j < m; ++j) {
-        uint32_t d = shape[j];
-        uint64_t inner = n / (outer * d);
-        uint64_t lines = outer * inner;
-        uint32_t lines_per_wg = d >= (uint32_t)InterpAxis<false>::BLOCK ? 1u : (uint32_t)InterpAxis<false>::BLOCK / d;
-        uint64_t groups = (lines + lines_per_wg - 1) / lines_per_wg;
-        if (d > 1 && form == TC_INTERP_BARYCENTRIC) {
-            /* beta_l = (-1)^(d-1-l) / (l! (d-1-l)!) on the nodes 1 .. d */
-            beta.resize(d);
-            for (uint32_t l = 0; l < d; ++l) {
-                beta[l] = fr_mul(inv_fact[l], inv_fact[d - 1 - l]);
-                if ((d - 1 - l) & 1u) beta[l] = fr_neg(beta[l]);
-            }
-            /* the previous axis' launch may still read its weights: the copy is ordered behind it on the stream */
-            TRY(h2d(ctx, d_aux, beta.data(), sizeof(fr_t) * d));
-            InterpAxisBarycentric k;
-            k.w = buf[0]; k.p[0] = buf[1]; k.p[1] = buf[2]; k.mm[0] = buf[3]; k.mm[1] = buf[4];
-            k.outer = outer; k.inner = inner; k.d = d; k.lines_per_wg = lines_per_wg;
-            k.beta = d_aux; k.zeta = d_zeta;
-            RT((launch_coop_n<InterpAxisBarycentric::BLOCK>((uint32_t)groups, ctx->stream, k, (int)(d + 1))));
-            std::swap(buf[0], buf[1 + (d & 1u)]);
-        } else if (d > 1) {
-            if (form == TC_INTERP_GREGORY) {
-                InterpAxis<true> k;
-                k.buf[0] = buf[0]; k.buf[1] = buf[1]; k.buf[2] = buf[2];
-                k.outer = outer; k.inner = inner; k.d = d; k.lines_per_wg = lines_per_wg;
-                k.inv_int = d_inv; k.zeta = d_zeta; k.inv_fact = d_aux;
-                RT((launch_coop_n<InterpAxis<true>::BLOCK>((uint32_t)groups, ctx->stream, k, (int)(2 * d - 1))));
-            } else {
-                InterpAxis<false> k;
-                k.buf[0] = buf[0]; k.buf[1] = buf[1]; k.buf[2] = buf[2];
-                k.outer = outer; k.inner = inner; k.d = d; k.lines_per_wg = lines_per_wg;
-                k.inv_int = d_inv; k.zeta = d_zeta; k.inv_fact = nullptr;
-                RT((launch_coop_n<InterpAxis<false>::BLOCK>((uint32_t)groups, ctx->stream, k, (int)(2 * d - 1))));
-            }
-            std::swap(buf[0], buf[interp_result_buffer(d)]);      /* the next axis reads what this one produced */
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!d_scalars || !d_coeffs) return fail(ctx, TC_ERR_ARG, "null argument");
+        if (!valid_dtype_scalar(dtype)) return fail(ctx, TC_ERR_ARG, "unsupported scalar dtype");
+        if (form != TC_INTERP_NEWTON && form != TC_INTERP_GREGORY && form != TC_INTERP_BARYCENTRIC)
+            return fail(ctx, TC_ERR_ARG, "unknown interpolation form");
+        uint64_t n = 0;
+        if (!interp_shape_ok(m, shape, &n)) return fail(ctx, TC_ERR_SHAPE, "bad shape");
+        RT(rt::set_device(ctx->device));
+        TRY(ws_reset(ctx));
+        uint32_t dmax = 1;
+        for (int j = 0; j < m; ++j) dmax = std::max(dmax, shape[j]);
+        /* 1 / l, 1 / l! and zeta_k = k + 1 up to the longest axis */
+        std::vector<fr_t> inv(dmax), zeta(dmax), inv_fact(dmax);
+        for (uint32_t i = 0; i < dmax; ++i) {
+            inv[i] = fe_from_u32<FrParams>(i ? i : 1);
+            zeta[i] = fe_from_u32<FrParams>(i + 1);
         }
-        outer *= d;
+        fr_batch_inverse(inv);
+        inv_fact[0] = fe_one<FrParams>();
+        for (uint32_t i = 1; i < dmax; ++i) inv_fact[i] = fr_mul(inv_fact[i - 1], inv[i]);
+        WS(d_inv, fr_t, dmax);
+        WS(d_zeta, fr_t, dmax);
+        WS(d_aux, fr_t, dmax);             /* 1 / l! (Gregory) or the weights beta of the current axis (barycentric) */
+        TRY(h2d(ctx, d_inv, inv.data(), sizeof(fr_t) * dmax));
+        TRY(h2d(ctx, d_zeta, zeta.data(), sizeof(fr_t) * dmax));
+        if (form == TC_INTERP_GREGORY) TRY(h2d(ctx, d_aux, inv_fact.data(), sizeof(fr_t) * dmax));
+        const int nbuf = form == TC_INTERP_BARYCENTRIC ? 5 : 3;
+        fr_t* buf[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+        for (int i = 0; i < nbuf; ++i) {
+            buf[i] = ws_array<fr_t>(ctx, n);
+            if (!buf[i]) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed");
+        }
+        RT(rt::launch<256>(n, ctx->stream, ScalarsToFr{d_scalars, dtype, buf[0]}));
+        std::vector<fr_t> beta;
+        uint64_t outer = 1;
+        for (int j = 0; j < m; ++j) {
+            uint32_t d = shape[j];
+            uint64_t inner = n / (outer * d);
+            uint64_t lines = outer * inner;
+            uint32_t lines_per_wg = d >= (uint32_t)InterpAxis<false>::BLOCK ? 1u : (uint32_t)InterpAxis<false>::BLOCK / d;
+            uint64_t groups = (lines + lines_per_wg - 1) / lines_per_wg;
+            if (d > 1 && form == TC_INTERP_BARYCENTRIC) {
+                /* beta_l = (-1)^(d-1-l) / (l! (d-1-l)!) on the nodes 1 .. d */
+                beta.resize(d);
+                for (uint32_t l = 0; l < d; ++l) {
+                    beta[l] = fr_mul(inv_fact[l], inv_fact[d - 1 - l]);
+                    if ((d - 1 - l) & 1u) beta[l] = fr_neg(beta[l]);
+                }
+                /* the previous axis' launch may still read its weights: the copy is ordered behind it on the stream */
+                TRY(h2d(ctx, d_aux, beta.data(), sizeof(fr_t) * d));
+                InterpAxisBarycentric k;
+                k.w = buf[0]; k.p[0] = buf[1]; k.p[1] = buf[2]; k.mm[0] = buf[3]; k.mm[1] = buf[4];
+                k.outer = outer; k.inner = inner; k.d = d; k.lines_per_wg = lines_per_wg;
+                k.beta = d_aux; k.zeta = d_zeta;
+                RT((launch_coop_n<InterpAxisBarycentric::BLOCK>((uint32_t)groups, ctx->stream, k, (int)(d + 1))));
+                std::swap(buf[0], buf[1 + (d & 1u)]);
+            } else if (d > 1) {
+                if (form == TC_INTERP_GREGORY) {
+                    InterpAxis<true> k;
+                    k.buf[0] = buf[0]; k.buf[1] = buf[1]; k.buf[2] = buf[2];
+                    k.outer = outer; k.inner = inner; k.d = d; k.lines_per_wg = lines_per_wg;
+                    k.inv_int = d_inv; k.zeta = d_zeta; k.inv_fact = d_aux;
+                    RT((launch_coop_n<InterpAxis<true>::BLOCK>((uint32_t)groups, ctx->stream, k, (int)(2 * d - 1))));
+                } else {
+                    InterpAxis<false> k;
+                    k.buf[0] = buf[0]; k.buf[1] = buf[1]; k.buf[2] = buf[2];
+                    k.outer = outer; k.inner = inner; k.d = d; k.lines_per_wg = lines_per_wg;
+                    k.inv_int = d_inv; k.zeta = d_zeta; k.inv_fact = nullptr;
+                    RT((launch_coop_n<InterpAxis<false>::BLOCK>((uint32_t)groups, ctx->stream, k, (int)(2 * d - 1))));
+                }
+                std::swap(buf[0], buf[interp_result_buffer(d)]);      /* the next axis reads what this one produced */
+            }
+            outer *= d;
+        }
+        RT(rt::launch<256>(n, ctx->stream, FrToPlain{buf[0], (fr_plain*)d_coeffs}));
+        TRY(ctx_sync(ctx));
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
     }
-    RT(rt::launch<256>(n, ctx->stream, FrToPlain{buf[0], (fr_plain*)d_coeffs}));
-    TRY(ctx_sync(ctx));
-    return TC_OK;
 }
 
 extern "C" int tc_interpolate(tc_ctx* ctx, int m, const uint32_t* shape, const void* d_scalars, int dtype, void* d_coeffs) {
-    return tc_interpolate_form(ctx, m, shape, d_scalars, dtype, TC_INTERP_NEWTON, d_coeffs);
+    try {
+        return tc_interpolate_form(ctx, m, shape, d_scalars, dtype, TC_INTERP_NEWTON, d_coeffs);
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
 }
 
 extern "C" int tc_divide_by_linear(tc_ctx* ctx, int m, const uint32_t* shape, const void* d_coeffs, int axis,
                                    uint32_t kappa_axis, void* d_quotient, void* d_remainder) {
-    if (!ctx) return TC_ERR_ARG;
-    if (!d_coeffs || !d_quotient || !d_remainder) return fail(ctx, TC_ERR_ARG, "null argument");
-    if (d_quotient == d_coeffs || d_remainder == d_coeffs || d_quotient == d_remainder) return fail(ctx, TC_ERR_ARG, "arrays may not alias");
-    uint64_t n = 0;
-    if (!interp_shape_ok(m, shape, &n)) return fail(ctx, TC_ERR_SHAPE, "bad shape");
-    if (axis < 0 || axis >= m) return fail(ctx, TC_ERR_ARG, "axis outside the shape");
-    if (kappa_axis >= shape[axis]) return fail(ctx, TC_ERR_RANGE, "position outside the grid");
-    RT(rt::set_device(ctx->device));
-    uint64_t outer = 1;
-    for (int j = 0; j < axis; ++j) outer *= shape[j];
-    uint32_t d = shape[axis];
-    uint64_t inner = n / (outer * d);
-    /* everything off the axis' degree 0 in r, and the whole of q, is written by the kernel; lines = outer * inner */
-    RT(rt::launch<64>(outer * inner, ctx->stream,
-                      DivideAxis{(const fr_plain*)d_coeffs, outer, inner, d, kappa_axis + 1u, (fr_plain*)d_quotient, (fr_plain*)d_remainder}));
-    TRY(ctx_sync(ctx));
-    return TC_OK;
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!d_coeffs || !d_quotient || !d_remainder) return fail(ctx, TC_ERR_ARG, "null argument");
+        if (d_quotient == d_coeffs || d_remainder == d_coeffs || d_quotient == d_remainder) return fail(ctx, TC_ERR_ARG, "arrays may not alias");
+        uint64_t n = 0;
+        if (!interp_shape_ok(m, shape, &n)) return fail(ctx, TC_ERR_SHAPE, "bad shape");
+        if (axis < 0 || axis >= m) return fail(ctx, TC_ERR_ARG, "axis outside the shape");
+        if (kappa_axis >= shape[axis]) return fail(ctx, TC_ERR_RANGE, "position outside the grid");
+        RT(rt::set_device(ctx->device));
+        uint64_t outer = 1;
+        for (int j = 0; j < axis; ++j) outer *= shape[j];
+        uint32_t d = shape[axis];
+        uint64_t inner = n / (outer * d);
+        /* everything off the axis' degree 0 in r, and the whole of q, is written by the kernel; lines = outer * inner */
+        RT(rt::launch<64>(outer * inner, ctx->stream,
+                          DivideAxis{(const fr_plain*)d_coeffs, outer, inner, d, kappa_axis + 1u, (fr_plain*)d_quotient, (fr_plain*)d_remainder}));
+        TRY(ctx_sync(ctx));
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
 }
 
 /* ======================================================================================= */
@@ -2068,28 +2382,40 @@ struct tc_vkp {
 };
 
 extern "C" int tc_vkp_from_trapdoor(const uint8_t* tau, int m, tc_vkp** out) {
-    if (!tau || !out || m < 1 || m > TC_MAX_ORDER) return TC_ERR_ARG;
-    *out = nullptr;
-    tc_vkp* vkp = new (std::nothrow) tc_vkp();
-    if (!vkp) return TC_ERR_NOMEM;
-    vkp->m = m;
-    pairing::g2_affine h = pairing::g2_generator();
-    for (int j = 0; j < m; ++j) {
-        uint32_t w[8];
-        if (!fr_bytes_canonical(tau + 32 * j, w)) {
-            delete vkp;
-            return TC_ERR_RANGE;
+    try {
+        if (!tau || !out || m < 1 || m > TC_MAX_ORDER) return TC_ERR_ARG;
+        *out = nullptr;
+        tc_vkp* vkp = new (std::nothrow) tc_vkp();
+        if (!vkp) return TC_ERR_NOMEM;
+        vkp->m = m;
+        pairing::g2_affine h = pairing::g2_generator();
+        for (int j = 0; j < m; ++j) {
+            uint32_t w[8];
+            if (!fr_bytes_canonical(tau + 32 * j, w)) {
+                delete vkp;
+                return TC_ERR_RANGE;
+            }
+            vkp->tau_h[j] = pairing::g2_mul(w, 256, h);
         }
-        vkp->tau_h[j] = pairing::g2_mul(w, 256, h);
+        *out = vkp;
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return TC_ERR_NOMEM;
+    } catch (...) {
+        return TC_ERR_STATE;
     }
-    *out = vkp;
-    return TC_OK;
 }
 extern "C" void tc_vkp_destroy(tc_vkp* vkp) { delete vkp; }
 extern "C" int tc_vkp_get(const tc_vkp* vkp, int axis, uint8_t out_g2[192]) {
-    if (!vkp || !out_g2 || axis < -1 || axis >= vkp->m) return TC_ERR_ARG;
-    pairing::g2_to_bytes(axis < 0 ? pairing::g2_generator() : vkp->tau_h[axis], out_g2);
-    return TC_OK;
+    try {
+        if (!vkp || !out_g2 || axis < -1 || axis >= vkp->m) return TC_ERR_ARG;
+        pairing::g2_to_bytes(axis < 0 ? pairing::g2_generator() : vkp->tau_h[axis], out_g2);
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return TC_ERR_NOMEM;
+    } catch (...) {
+        return TC_ERR_STATE;
+    }
 }
 
 /* canonical bytes -> affine point on E; false when not canonical or not on the curve */
@@ -2102,11 +2428,17 @@ static bool g1_from_bytes_checked(const uint8_t* b, g1_affine* out) {
 }
 
 extern "C" int tc_pairing(const uint8_t p_g1[96], const uint8_t q_g2[192], uint8_t out_gt[576]) {
-    if (!p_g1 || !q_g2 || !out_gt) return TC_ERR_ARG;
-    pairing::pair_t pr;
-    if (!g1_from_bytes_checked(p_g1, &pr.p) || !pairing::g2_from_bytes(q_g2, &pr.q)) return TC_ERR_RANGE;
-    pairing::gt_to_bytes(pairing::pairing_product({pr}), out_gt);
-    return TC_OK;
+    try {
+        if (!p_g1 || !q_g2 || !out_gt) return TC_ERR_ARG;
+        pairing::pair_t pr;
+        if (!g1_from_bytes_checked(p_g1, &pr.p) || !pairing::g2_from_bytes(q_g2, &pr.q)) return TC_ERR_RANGE;
+        pairing::gt_to_bytes(pairing::pairing_product({pr}), out_gt);
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return TC_ERR_NOMEM;
+    } catch (...) {
+        return TC_ERR_STATE;
+    }
 }
 
 /* Every opening's equation, moved to fixed second arguments,
@@ -2161,13 +2493,19 @@ static bool pairing_batch_check(const tc_vkp* vkp, const PairingBatch& B) {
 
 extern "C" int tc_verify_pairing(const tc_vkp* vkp, int m, const uint32_t* shape, const uint8_t commitment[96],
                                  const uint32_t* kappa, const uint8_t y[32], const uint8_t* pi) {
-    if (!vkp || !shape || !commitment || !kappa || !y || !pi) return TC_ERR_ARG;
-    if (!shape_ok(m, shape, nullptr) || m > vkp->m) return TC_ERR_SHAPE;
-    for (int j = 0; j < m; ++j)
-        if (kappa[j] >= shape[j]) return TC_ERR_RANGE;
-    PairingBatch B;
-    if (!pairing_batch_add(&B, m, commitment, kappa, y, pi)) return TC_ERR_VERIFY;
-    return pairing_batch_check(vkp, B) ? TC_OK : TC_ERR_VERIFY;
+    try {
+        if (!vkp || !shape || !commitment || !kappa || !y || !pi) return TC_ERR_ARG;
+        if (!shape_ok(m, shape, nullptr) || m > vkp->m) return TC_ERR_SHAPE;
+        for (int j = 0; j < m; ++j)
+            if (kappa[j] >= shape[j]) return TC_ERR_RANGE;
+        PairingBatch B;
+        if (!pairing_batch_add(&B, m, commitment, kappa, y, pi)) return TC_ERR_VERIFY;
+        return pairing_batch_check(vkp, B) ? TC_OK : TC_ERR_VERIFY;
+    } catch (const std::bad_alloc&) {
+        return TC_ERR_NOMEM;
+    } catch (...) {
+        return TC_ERR_STATE;
+    }
 }
 
 /* the structural checks and phi links of one path; its openings go into B.  false = reject */
@@ -2206,86 +2544,116 @@ static bool pairing_path_add(const tc_vkp* vkp, PairingBatch* B, const tc_path& 
 
 extern "C" int tc_verify_path_pairing(const tc_vkp* vkp, const tc_path* path, const uint8_t root[96],
                                       const uint8_t leaf_value[32], const void* proof, size_t proof_len) {
-    if (!vkp || !path || !root || !leaf_value || !proof) return TC_ERR_ARG;
-    PairingBatch B;
-    if (!pairing_path_add(vkp, &B, *path, root, leaf_value, (const uint8_t*)proof, proof_len)) return TC_ERR_VERIFY;
-    return pairing_batch_check(vkp, B) ? TC_OK : TC_ERR_VERIFY;
+    try {
+        if (!vkp || !path || !root || !leaf_value || !proof) return TC_ERR_ARG;
+        PairingBatch B;
+        if (!pairing_path_add(vkp, &B, *path, root, leaf_value, (const uint8_t*)proof, proof_len)) return TC_ERR_VERIFY;
+        return pairing_batch_check(vkp, B) ? TC_OK : TC_ERR_VERIFY;
+    } catch (const std::bad_alloc&) {
+        return TC_ERR_NOMEM;
+    } catch (...) {
+        return TC_ERR_STATE;
+    }
 }
 
 extern "C" int tc_verify_paths_pairing_batch(const tc_vkp* vkp, int count, const tc_path* paths, const uint8_t* roots,
                                              const uint8_t* leaf_values, const void* proofs, size_t proof_stride,
                                              const size_t* proof_len, int* results) {
-    if (!vkp || count < 0 || (count && (!paths || !roots || !leaf_values || !proofs || !proof_len || !results))) return TC_ERR_ARG;
-    if (!count) return TC_OK;
-    /* the G1 work of the paths is spread over host threads, one running equation per thread */
-    unsigned nthreads = std::min<unsigned>(std::max(1u, std::thread::hardware_concurrency()), 16u);
-    nthreads = std::min<unsigned>(nthreads, (unsigned)count);
-    std::vector<PairingBatch> part(nthreads);
-    std::vector<uint8_t> structural(count, 0);
-    auto work = [&](unsigned t) {
-        for (int i = (int)t; i < count; i += (int)nthreads) {
-            PairingBatch mine;                       /* a malformed path must not poison the thread's equation */
-            bool ok = pairing_path_add(vkp, &mine, paths[i], roots + 96 * (size_t)i, leaf_values + 32 * (size_t)i,
-                                       (const uint8_t*)proofs + (size_t)i * proof_stride, proof_len[i]);
-            structural[i] = ok ? 1 : 0;
-            if (!ok) continue;
-            PairingBatch& P = part[t];
-            bool unit = P.count == 0;
+    try {
+        if (!vkp || count < 0 || (count && (!paths || !roots || !leaf_values || !proofs || !proof_len || !results))) return TC_ERR_ARG;
+        if (!count) return TC_OK;
+        /* the G1 work of the paths is spread over host threads, one running equation per thread */
+        unsigned nthreads = std::min<unsigned>(std::max(1u, std::thread::hardware_concurrency()), 16u);
+        nthreads = std::min<unsigned>(nthreads, (unsigned)count);
+        std::vector<PairingBatch> part(nthreads);
+        std::vector<uint8_t> structural(count, 0);
+        auto work = [&](unsigned t) {
+            for (int i = (int)t; i < count; i += (int)nthreads) {
+                PairingBatch mine;                       /* a malformed path must not poison the thread's equation */
+                bool ok = pairing_path_add(vkp, &mine, paths[i], roots + 96 * (size_t)i, leaf_values + 32 * (size_t)i,
+                                           (const uint8_t*)proofs + (size_t)i * proof_stride, proof_len[i]);
+                structural[i] = ok ? 1 : 0;
+                if (!ok) continue;
+                PairingBatch& P = part[t];
+                bool unit = P.count == 0;
+                uint32_t rho[4] = {1, 0, 0, 0};
+                if (!unit)
+                    for (int j = 0; j < 4; ++j) rho[j] = (uint32_t)P.rng();
+                P.h_term = xyzz_add(P.h_term, weigh(mine.h_term, rho, unit));
+                for (int j = 0; j < mine.m_used; ++j) P.tau_term[j] = xyzz_add(P.tau_term[j], weigh(mine.tau_term[j], rho, unit));
+                P.m_used = std::max(P.m_used, mine.m_used);
+                ++P.count;
+            }
+        };
+        std::vector<std::thread> pool;
+        for (unsigned t = 1; t < nthreads; ++t) pool.emplace_back(work, t);
+        work(0);
+        for (auto& th : pool) th.join();
+        PairingBatch all;
+        for (unsigned t = 0; t < nthreads; ++t) {
+            if (!part[t].count) continue;
+            bool unit = all.count == 0;
             uint32_t rho[4] = {1, 0, 0, 0};
             if (!unit)
-                for (int j = 0; j < 4; ++j) rho[j] = (uint32_t)P.rng();
-            P.h_term = xyzz_add(P.h_term, weigh(mine.h_term, rho, unit));
-            for (int j = 0; j < mine.m_used; ++j) P.tau_term[j] = xyzz_add(P.tau_term[j], weigh(mine.tau_term[j], rho, unit));
-            P.m_used = std::max(P.m_used, mine.m_used);
-            ++P.count;
+                for (int j = 0; j < 4; ++j) rho[j] = (uint32_t)all.rng();
+            all.h_term = xyzz_add(all.h_term, weigh(part[t].h_term, rho, unit));
+            for (int j = 0; j < part[t].m_used; ++j) all.tau_term[j] = xyzz_add(all.tau_term[j], weigh(part[t].tau_term[j], rho, unit));
+            all.m_used = std::max(all.m_used, part[t].m_used);
+            ++all.count;
         }
-    };
-    std::vector<std::thread> pool;
-    for (unsigned t = 1; t < nthreads; ++t) pool.emplace_back(work, t);
-    work(0);
-    for (auto& th : pool) th.join();
-    PairingBatch all;
-    for (unsigned t = 0; t < nthreads; ++t) {
-        if (!part[t].count) continue;
-        bool unit = all.count == 0;
-        uint32_t rho[4] = {1, 0, 0, 0};
-        if (!unit)
-            for (int j = 0; j < 4; ++j) rho[j] = (uint32_t)all.rng();
-        all.h_term = xyzz_add(all.h_term, weigh(part[t].h_term, rho, unit));
-        for (int j = 0; j < part[t].m_used; ++j) all.tau_term[j] = xyzz_add(all.tau_term[j], weigh(part[t].tau_term[j], rho, unit));
-        all.m_used = std::max(all.m_used, part[t].m_used);
-        ++all.count;
+        bool all_good = all.count == 0 || pairing_batch_check(vkp, all);
+        for (int i = 0; i < count; ++i) {
+            if (!structural[i]) { results[i] = TC_ERR_VERIFY; continue; }
+            if (all_good) { results[i] = TC_OK; continue; }
+            /* something in the batch is wrong: find out which paths, one by one */
+            results[i] = tc_verify_path_pairing(vkp, paths + i, roots + 96 * (size_t)i, leaf_values + 32 * (size_t)i,
+                                                (const uint8_t*)proofs + (size_t)i * proof_stride, proof_len[i]);
+        }
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return TC_ERR_NOMEM;
+    } catch (...) {
+        return TC_ERR_STATE;
     }
-    bool all_good = all.count == 0 || pairing_batch_check(vkp, all);
-    for (int i = 0; i < count; ++i) {
-        if (!structural[i]) { results[i] = TC_ERR_VERIFY; continue; }
-        if (all_good) { results[i] = TC_OK; continue; }
-        /* something in the batch is wrong: find out which paths, one by one */
-        results[i] = tc_verify_path_pairing(vkp, paths + i, roots + 96 * (size_t)i, leaf_values + 32 * (size_t)i,
-                                            (const uint8_t*)proofs + (size_t)i * proof_stride, proof_len[i]);
-    }
-    return TC_OK;
 }
 
 /* ======================================================================================= */
 /* Layer selection: host only                                                              */
 /* ======================================================================================= */
 extern "C" int tc_hill_alpha(const double* eigenvalues, size_t d, size_t chi, double* out_alpha) {
-    return selector::hill_alpha(eigenvalues, d, chi, out_alpha) ? TC_OK : TC_ERR_ARG;
+    try {
+        return selector::hill_alpha(eigenvalues, d, chi, out_alpha) ? TC_OK : TC_ERR_ARG;
+    } catch (const std::bad_alloc&) {
+        return TC_ERR_NOMEM;
+    } catch (...) {
+        return TC_ERR_STATE;
+    }
 }
 extern "C" int tc_layer_benefits(const double* alpha, const double* params, size_t n_layers, double* out_nu) {
-    if (!alpha || !params || !out_nu || !n_layers) return TC_ERR_ARG;
-    selector::benefits(alpha, params, n_layers, out_nu);
-    return TC_OK;
+    try {
+        if (!alpha || !params || !out_nu || !n_layers) return TC_ERR_ARG;
+        selector::benefits(alpha, params, n_layers, out_nu);
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return TC_ERR_NOMEM;
+    } catch (...) {
+        return TC_ERR_STATE;
+    }
 }
 extern "C" int tc_select_layers(size_t n_layers, const double* nu, const double* phi, size_t n_verifiers, const double* beta,
                                 double* out_value, int64_t* out_start, int64_t* out_end) {
-    if (!nu || !phi || !beta || !out_value || !out_start || !out_end) return TC_ERR_ARG;
-    if (n_layers > 0x7FFFFFFEull) return TC_ERR_SHAPE;
-    for (size_t i = 0; i < n_layers; ++i)
-        if (!(nu[i] >= 0.0) || !(phi[i] > 0.0)) return TC_ERR_RANGE;
-    for (size_t k = 0; k < n_verifiers; ++k)
-        if (!(beta[k] >= 0.0)) return TC_ERR_RANGE;
-    *out_value = selector::select_layers(n_layers, nu, phi, n_verifiers, beta, out_start, out_end);
-    return TC_OK;
+    try {
+        if (!nu || !phi || !beta || !out_value || !out_start || !out_end) return TC_ERR_ARG;
+        if (n_layers > 0x7FFFFFFEull) return TC_ERR_SHAPE;
+        for (size_t i = 0; i < n_layers; ++i)
+            if (!(nu[i] >= 0.0) || !(phi[i] > 0.0)) return TC_ERR_RANGE;
+        for (size_t k = 0; k < n_verifiers; ++k)
+            if (!(beta[k] >= 0.0)) return TC_ERR_RANGE;
+        *out_value = selector::select_layers(n_layers, nu, phi, n_verifiers, beta, out_start, out_end);
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return TC_ERR_NOMEM;
+    } catch (...) {
+        return TC_ERR_STATE;
+    }
 }

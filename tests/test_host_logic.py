@@ -473,3 +473,55 @@ def test_emulated_tree_with_a_large_upper_level(emu, node_srs):
         assert tree.root == ec.g1_to_bytes(ot.root)
     finally:
         tree.close()
+
+
+def test_emulated_commit_static(emu):
+    """The entry point that allocates nothing, on the host-emulation build: same bytes as tc_commit on a tensor of
+    several tiles and then on a smaller one (the scratch keeps the first call's contents), a degenerate tensor whose
+    single bucket needs every planned pass, no allocation by the library during the calls, the maximum size within
+    the static scratch, and the limits refused with an error."""
+    lib = emu.lib
+    big, small = (96, 131), (7, 33)
+    srs_big = emu.setup_from_trapdoor(TAU_BYTES, big, 0)
+    srs_small = emu.setup_from_trapdoor(TAU_BYTES, small, 0)
+    Xb = tc_inputs.int16_uniform(big, 21, -32768, 32767)
+    Xs8 = tc_inputs.int8_uniform(small, 22)
+    want_big, want_small = emu.commit(srs_big, Xb, T.TC_I16), emu.commit(srs_small, Xs8, T.TC_I8)
+    same = np.full(big, 3, np.int16)                      # one bucket holds all 12576 terms
+    want_same = emu.commit(srs_big, same, T.TC_I16)
+    out = np.zeros(96, np.uint8)
+    before = emu.alloc_calls()
+    for srs, X, dt, want in ((srs_big, Xb, T.TC_I16, want_big), (srs_small, Xs8, T.TC_I8, want_small),
+                             (srs_big, same, T.TC_I16, want_same), (srs_small, Xs8, T.TC_I8, want_small)):
+        out[:] = 0xEE
+        emu.commit_static(srs, X, dt, out)
+        assert out.tobytes() == want
+    assert emu.alloc_calls() == before, "tc_commit_static allocated or released memory"
+    # errors: full-width scalars, a misaligned output, a tensor beyond the limit
+    fr = fr_bytes_array([1] * (7 * 33))
+    with pytest.raises(T.TcError) as e:
+        emu.commit_static(srs_small, fr, T.TC_FR, out)
+    assert e.value.code == T.binding.TC_ERR_ARG
+    with pytest.raises(T.TcError) as e:
+        emu.commit_static(srs_small, Xs8, T.TC_I8, out.ctypes.data + 1)
+    assert e.value.code == T.binding.TC_ERR_ARG
+    srs_big.close()
+    srs_small.close()
+
+
+@pytest.mark.slow
+def test_emulated_commit_static_at_its_limit(emu):
+    """TC_STATIC_MAX_TERMS int16 entries fit the static scratch (the call would fail with TC_ERR_NOMEM otherwise) and
+    one entry more is refused.  The SRS of the emulation is slow to generate, so both tables are 1-D slices."""
+    n = T.binding.TC_STATIC_MAX_TERMS
+    srs = emu.setup_from_trapdoor(TAU_BYTES, (n,), 0)
+    X = tc_inputs.int16_uniform((n,), 23, -32768, 32767)
+    out = np.zeros(96, np.uint8)
+    emu.commit_static(srs, X, T.TC_I16, out)
+    assert out.tobytes() == emu.commit(srs, X, T.TC_I16)
+    srs.close()
+    srs = emu.setup_from_trapdoor(TAU_BYTES, (n + 1,), 0)
+    with pytest.raises(T.TcError) as e:
+        emu.commit_static(srs, np.zeros(n + 1, np.int16), T.TC_I16, out)
+    assert e.value.code == T.binding.TC_ERR_SHAPE and "TC_STATIC_MAX_TERMS" in str(e.value)
+    srs.close()
