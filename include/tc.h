@@ -99,6 +99,20 @@ int tc_ctx_profile_read(tc_ctx* ctx, int kind, double* total_ms, uint64_t* launc
  * sub-run is copied, and the sums of the sub-runs are added up by the passes that follow); 0 for the other kinds. */
 int tc_ctx_profile_units(tc_ctx* ctx, int kind, uint64_t* units);
 
+/* What the GPU's integer ALUs sustain, measured in place (the denominator of a roofline fraction for this path,
+ * whose work is 32 x 32 + 64 -> 64 bit multiply-adds): a register-only loop with exactly `waves_per_simd` (1..8)
+ * waves resident on every SIMD of the chip, timed with HIP events on the context's stream.
+ *   TC_ALU_MAD        multiply-adds/s of independent v_mad_u64_u32 chains;
+ *   TC_ALU_MAD_CARRY  the same with the carry of every multiply-add added into a third word, the pair of
+ *                     instructions that a limb product of the field multiplication costs;
+ *   TC_ALU_FP_MUL / TC_ALU_FP_SQR   Fp products / squarings per second of the library's own routines in a chain
+ *                     (one product = 300 multiply-adds, one squaring 234). */
+#define TC_ALU_MAD 0
+#define TC_ALU_MAD_CARRY 1
+#define TC_ALU_FP_MUL 2
+#define TC_ALU_FP_SQR 3
+int tc_ctx_alu_rate(tc_ctx* ctx, int kind, int waves_per_simd, double* out_per_s);
+
 /* ---- Setup (Def. 4.1, Setup) -- test-only trusted setup from a known trapdoor -- */
 
 #define TC_SRS_SUFFIX 1u     /* also build the suffix tables S^(a), a = 1..m-1, needed by tc_open */
@@ -123,6 +137,20 @@ uint64_t tc_srs_size(const tc_srs* srs, int first_axis);
 /* Copies one SRS point to the host in canonical form (inspection / spot checks). */
 int tc_srs_get_point(tc_ctx* ctx, const tc_srs* srs, int first_axis, uint64_t index, uint8_t out_g1[96]);
 
+/* The public parameters as a flat file (Def. 4.1, Setup publishes pp = (srs, Omega): the SRS outlives the process
+ * that made it).  Layout, little-endian: "TCSRS\0\0\0", u32 version (1), u32 curve (1 = BLS12-381 G1), u32 basis
+ * (0 Lagrange image, 1 monomial), u32 flags, u32 m, u32 shape[4], u32 reserved, u64 point count; then the tables
+ * S^(0) .. S^(m-1) that the SRS holds, canonical 96-byte points.  Fixed-base tables and the grid constants are not
+ * stored: the import rebuilds them.
+ * Export: on entry *len is the capacity of host_buf, on return the size of the file; host_buf = NULL only asks for
+ * the size; a buffer that is too small gives TC_ERR_ARG.
+ * Import: builds an SRS equal to the exported one on this context's GPU.  A truncated or overlong buffer, a wrong
+ * magic / version / curve, flags, shape or point count that do not fit together give TC_ERR_ARG or TC_ERR_SHAPE; a
+ * point that is not canonical or not on the curve gives TC_ERR_RANGE.  (That the points are the powers of a
+ * trapdoor nobody knows is the trusted party's promise; no check here can replace it.) */
+int tc_srs_export(tc_ctx* ctx, const tc_srs* srs, void* host_buf, size_t* len);
+int tc_srs_import(tc_ctx* ctx, const void* host_buf, size_t len, tc_srs** out);
+
 /* ---- encode (quantisation + field embedding of the synthetic workloads) ------- */
 
 /* d_src: n elements of `src_dtype`.  TC_F16: q = clamp(rint(float(x) * inv_scale), -32767, 32767)
@@ -130,6 +158,15 @@ int tc_srs_get_point(tc_ctx* ctx, const tc_srs* srs, int first_axis, uint64_t in
  * unchanged to d_dst (same type).  The embedding e(q) = q mod r (negatives as r - |q|) is applied
  * inside the commitment kernels: -|q| P is computed as |q| (-P). */
 int tc_encode_tensor(tc_ctx* ctx, const void* d_src, int src_dtype, size_t n, float inv_scale, void* d_dst);
+/* The per-tensor scale of that rule, computed where the tensor is: d_inv_scale[0] (DEVICE memory, one float32,
+ * 4-byte aligned) = float32(32767) / float32(amax), amax the largest magnitude among the finite values of the n
+ * fp16 values at d_src; 0 when there is no non-zero finite value (every entry then quantises to 0).  Infinities and
+ * NaNs do not count towards amax (they quantise to +-32767 and 0).  One pass over the tensor, asynchronous on the
+ * context's stream; nothing is read back. */
+int tc_quant_scale(tc_ctx* ctx, const void* d_src, size_t n, float* d_inv_scale);
+/* tc_encode_tensor with the scale taken from device memory (what tc_quant_scale wrote, by launches that precede
+ * this one on the stream): quantisation without a round trip to the host. */
+int tc_encode_tensor_scaled(tc_ctx* ctx, const void* d_src, int src_dtype, size_t n, const float* d_inv_scale, void* d_dst);
 
 /* ---- Com (Def. 4.1, Com) -------------------------------------------------------- */
 
@@ -208,6 +245,20 @@ int tc_terkle_levels(const tc_tree* tree);
 int tc_terkle_level_info(const tc_tree* tree, int level, uint32_t* grid, uint64_t* n_nodes);
 /* Commitment of node `index` (row-major in the level grid) in canonical form. */
 int tc_terkle_node(tc_ctx* ctx, const tc_tree* tree, int level, uint64_t index, uint8_t out_g1[96]);
+
+/* A built tree as a flat file, so that a later process can serve openings without rebuilding (Sec. 4: the tree is
+ * built once per inference and opened on demand).  Layout, little-endian: "TCTREE\0\0", u32 version (1), u32 curve,
+ * u32 m, u32 grid[4], u32 node_shape[4], u32 leaf kind, u32 levels, u32 reserved, u64 node count; then the canonical
+ * 96-byte commitments of every node, level by level from the bottom, row-major in each level's grid.
+ * Export: size protocol as tc_srs_export.
+ * Import: `desc` describes the same tree as for tc_terkle_build (grid, node shape, node SRS, payload or leaf
+ * tensors and their SRS on this GPU -- pointers and handles do not survive a process); the file must have been
+ * written for that grid, node shape and leaf kind (TC_ERR_SHAPE otherwise; TC_ERR_ARG for a truncated, overlong or
+ * foreign buffer; TC_ERR_RANGE for a point not on the curve).  The commitments are taken from the file, phi values
+ * are recomputed; nothing checks that they are the commitments of the payload -- openings from a wrong file are
+ * rejected by the verifier, as any wrong proof is. */
+int tc_terkle_export(tc_ctx* ctx, const tc_tree* tree, void* host_buf, size_t* len);
+int tc_terkle_import(tc_ctx* ctx, const tc_tree_desc* desc, const void* host_buf, size_t len, tc_tree** out);
 
 /* Path of a payload position.  Steps run from the root down.  Step s opens a tensor of shape
  * shape[s] (order m[s]) at kappa[s]. */

@@ -125,3 +125,25 @@ def f_at_tau(T, shape, ell, nthreads=1):
 def commit(pp, T, nthreads=1):
     """C_T = [f_T(tau)] G with the field sum and the scalar multiplication both in C."""
     return g1_mul(f_at_tau(T, pp.shape, pp.ell, nthreads), ec.G1)
+
+
+def open_(pp, T, kappa, nthreads=1):
+    """Open (Def. 4.1) under a known trapdoor, the same closed form as tc.open_: R_i = r_i(tau) is the slice of T
+    with its first i indices fixed to kappa, contracted with the Lagrange values of the remaining axes;
+    q_i(tau) = (R_{i-1} - R_i) / (tau_i - omega_i); pi_i = [q_i(tau)] G.  The field sums and the scalar
+    multiplications run in C (large int8 / int16 tensors); returns (y, [pi_1 .. pi_m])."""
+    kappa = tuple(int(k) for k in kappa)
+    if len(kappa) != pp.m or any(not (0 <= k < d) for k, d in zip(kappa, pp.shape)):
+        raise ValueError("opening index outside the grid")
+    sub = np.ascontiguousarray(T).reshape(pp.shape)
+    Rs = []
+    for i in range(pp.m):
+        Rs.append(f_at_tau(sub, pp.shape[i:], pp.ell[i:], nthreads))
+        sub = sub[kappa[i]]
+    Rs.append(int(sub) % ec.R)
+    proof = []
+    for i in range(pp.m):
+        omega_i = kappa[i] + 1                       # the grid node of position kappa_i
+        q = (Rs[i] - Rs[i + 1]) * ec.fr_inv(pp.tau[i] - omega_i) % ec.R
+        proof.append(g1_mul(q, ec.G1))
+    return Rs[pp.m], proof

@@ -15,6 +15,7 @@ TC_INTERP_NEWTON, TC_INTERP_GREGORY, TC_INTERP_BARYCENTRIC = 0, 1, 2
 TC_LEAF_ENTRIES, TC_LEAF_TENSORS = 0, 1
 TC_PROF_BUCKET_ACC, TC_PROF_NODE_COMMIT, TC_PROF_NODE_COMMIT_UPPER, TC_PROF_VERIFY_CHAIN = 0, 1, 2, 3
 TC_MAX_ORDER, TC_MAX_STEPS = 4, 16
+TC_ALU_MAD, TC_ALU_MAD_CARRY, TC_ALU_FP_MUL, TC_ALU_FP_SQR = 0, 1, 2, 3
 TC_STATIC_MAX_TERMS, TC_STATIC_SCRATCH_BYTES = 1 << 18, 32 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -79,11 +80,18 @@ def load_library(path=None):
         "tc_ctx_profile_read": (ctypes.c_int, [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                                ctypes.POINTER(ctypes.c_uint64)]),
         "tc_ctx_profile_units": (ctypes.c_int, [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64)]),
+        "tc_ctx_alu_rate": (ctypes.c_int, [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]),
         "tc_setup_from_trapdoor": (ctypes.c_int, [vp, u8p, ctypes.c_int, u32p, ctypes.c_uint32, ctypes.POINTER(vp)]),
         "tc_srs_destroy": (None, [vp]),
         "tc_srs_size": (ctypes.c_uint64, [vp, ctypes.c_int]),
         "tc_srs_get_point": (ctypes.c_int, [vp, vp, ctypes.c_int, ctypes.c_uint64, vp]),
+        "tc_srs_export": (ctypes.c_int, [vp, vp, vp, ctypes.POINTER(ctypes.c_size_t)]),
+        "tc_srs_import": (ctypes.c_int, [vp, vp, ctypes.c_size_t, ctypes.POINTER(vp)]),
+        "tc_terkle_export": (ctypes.c_int, [vp, vp, vp, ctypes.POINTER(ctypes.c_size_t)]),
+        "tc_terkle_import": (ctypes.c_int, [vp, ctypes.POINTER(tc_tree_desc), vp, ctypes.c_size_t, ctypes.POINTER(vp)]),
         "tc_encode_tensor": (ctypes.c_int, [vp, vp, ctypes.c_int, ctypes.c_size_t, ctypes.c_float, vp]),
+        "tc_quant_scale": (ctypes.c_int, [vp, vp, ctypes.c_size_t, vp]),
+        "tc_encode_tensor_scaled": (ctypes.c_int, [vp, vp, ctypes.c_int, ctypes.c_size_t, vp, vp]),
         "tc_commit": (ctypes.c_int, [vp, vp, vp, ctypes.c_int, vp]),
         "tc_commit_batch": (ctypes.c_int, [vp, ctypes.c_int, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                            ctypes.POINTER(ctypes.c_int), vp]),
@@ -263,6 +271,14 @@ class Srs:
         self.ctx._check(self.ctx.lib.tc_srs_get_point(self.ctx.handle, self.handle, first_axis, index, out))
         return out.raw
 
+    def export(self):
+        """The SRS as the bytes of its flat file."""
+        n = ctypes.c_size_t(0)
+        self.ctx._check(self.ctx.lib.tc_srs_export(self.ctx.handle, self.handle, None, ctypes.byref(n)))
+        buf = ctypes.create_string_buffer(n.value)
+        self.ctx._check(self.ctx.lib.tc_srs_export(self.ctx.handle, self.handle, buf, ctypes.byref(n)))
+        return buf.raw[: n.value]
+
     def close(self):
         if self.handle:
             self.ctx.lib.tc_srs_destroy(self.handle)
@@ -320,6 +336,14 @@ class Tree:
             buf, stride, lens))
         return [buf.raw[i * stride : i * stride + lens[i]] for i in range(count)]
 
+    def export(self):
+        """Every node commitment of the tree as the bytes of its flat file."""
+        n = ctypes.c_size_t(0)
+        self.ctx._check(self.ctx.lib.tc_terkle_export(self.ctx.handle, self.handle, None, ctypes.byref(n)))
+        buf = ctypes.create_string_buffer(n.value)
+        self.ctx._check(self.ctx.lib.tc_terkle_export(self.ctx.handle, self.handle, buf, ctypes.byref(n)))
+        return buf.raw[: n.value]
+
     def update(self, leaf_index, delta, inner_index=None):
         """One entry changed by `delta` (the caller updates its own buffer): recompute the path and the root."""
         self.ctx._check(self.ctx.lib.tc_terkle_update(self.ctx.handle, self.handle, _u32(leaf_index),
@@ -363,6 +387,12 @@ class Context:
         self._check(self.lib.tc_ctx_profile_units(self.handle, kind, ctypes.byref(units)))
         return int(units.value)
 
+    def alu_rate(self, kind, waves_per_simd):
+        """multiply-adds/s (kinds 0, 1) or Fp products/s (kinds 2, 3) with that many waves on every SIMD"""
+        out = ctypes.c_double()
+        self._check(self.lib.tc_ctx_alu_rate(self.handle, kind, waves_per_simd, ctypes.byref(out)))
+        return out.value
+
     def close(self):
         for vk in self._vk.values():
             self.lib.tc_vk_destroy(vk)
@@ -378,9 +408,25 @@ class Context:
         self._check(self.lib.tc_setup_from_trapdoor(self.handle, bytes(tau_bytes), m, _u32(shape), flags, ctypes.byref(h)))
         return Srs(self, h, shape, flags)
 
+    def srs_import(self, data):
+        """An SRS from the bytes that Srs.export wrote (shape and flags come from the file)."""
+        h = ctypes.c_void_p()
+        data = bytes(data)
+        self._check(self.lib.tc_srs_import(self.handle, data, len(data), ctypes.byref(h)))
+        m = int.from_bytes(data[24:28], "little")
+        shape = tuple(int.from_bytes(data[28 + 4 * j : 32 + 4 * j], "little") for j in range(m))
+        return Srs(self, h, shape, int.from_bytes(data[20:24], "little"))
+
     # -- encode / commit / open ------------------------------------------------------------
     def encode_tensor(self, src, src_dtype, n, inv_scale, dst):
         self._check(self.lib.tc_encode_tensor(self.handle, _ptr(src), src_dtype, n, float(inv_scale), _ptr(dst)))
+
+    def quant_scale(self, src, n, inv_scale_out):
+        """inv_scale_out: device buffer of one float32 that receives 32767 / max|x| over the n fp16 values of src."""
+        self._check(self.lib.tc_quant_scale(self.handle, _ptr(src), n, _ptr(inv_scale_out)))
+
+    def encode_tensor_scaled(self, src, src_dtype, n, inv_scale_dev, dst):
+        self._check(self.lib.tc_encode_tensor_scaled(self.handle, _ptr(src), src_dtype, n, _ptr(inv_scale_dev), _ptr(dst)))
 
     def commit(self, srs, scalars, dtype):
         out = ctypes.create_string_buffer(96)
@@ -440,7 +486,17 @@ class Context:
         return True
 
     # -- Terkle ------------------------------------------------------------------------------
-    def terkle_build_entries(self, node_srs, payload, dtype, grid, node_shape):
+    def _tree(self, d, keep, grid, node_shape, leaf_kind, leaf_shapes, file_bytes):
+        """tc_terkle_build, or tc_terkle_import when the bytes of an exported tree are given."""
+        h = ctypes.c_void_p()
+        if file_bytes is None:
+            self._check(self.lib.tc_terkle_build(self.handle, ctypes.byref(d), ctypes.byref(h)))
+        else:
+            file_bytes = bytes(file_bytes)
+            self._check(self.lib.tc_terkle_import(self.handle, ctypes.byref(d), file_bytes, len(file_bytes), ctypes.byref(h)))
+        return Tree(self, h, keep, grid, node_shape, leaf_kind, leaf_shapes)
+
+    def terkle_build_entries(self, node_srs, payload, dtype, grid, node_shape, from_file=None):
         d = tc_tree_desc()
         d.m = len(grid)
         for j, (g, s) in enumerate(zip(grid, node_shape)):
@@ -449,11 +505,9 @@ class Context:
         d.leaf_kind = TC_LEAF_ENTRIES
         d.d_payload = _ptr(payload)
         d.dtype = dtype
-        h = ctypes.c_void_p()
-        self._check(self.lib.tc_terkle_build(self.handle, ctypes.byref(d), ctypes.byref(h)))
-        return Tree(self, h, (d, payload, node_srs), grid, node_shape, TC_LEAF_ENTRIES)
+        return self._tree(d, (d, payload, node_srs), grid, node_shape, TC_LEAF_ENTRIES, None, from_file)
 
-    def terkle_build_tensors(self, node_srs, leaf_srs, leaf_scalars, leaf_dtypes, grid, node_shape):
+    def terkle_build_tensors(self, node_srs, leaf_srs, leaf_scalars, leaf_dtypes, grid, node_shape, from_file=None):
         n = len(leaf_srs)
         d = tc_tree_desc()
         d.m = len(grid)
@@ -465,10 +519,8 @@ class Context:
         b = (ctypes.c_void_p * n)(*[_ptr(s) for s in leaf_scalars])
         c = (ctypes.c_int * n)(*leaf_dtypes)
         d.leaf_srs, d.d_leaf_scalars, d.leaf_dtype = a, b, c
-        h = ctypes.c_void_p()
-        self._check(self.lib.tc_terkle_build(self.handle, ctypes.byref(d), ctypes.byref(h)))
-        return Tree(self, h, (d, a, b, c, leaf_scalars, leaf_srs, node_srs), grid, node_shape, TC_LEAF_TENSORS,
-                    [s.shape for s in leaf_srs])
+        return self._tree(d, (d, a, b, c, leaf_scalars, leaf_srs, node_srs), grid, node_shape, TC_LEAF_TENSORS,
+                          [s.shape for s in leaf_srs], from_file)
 
     def path_from_grid(self, grid, node_shape, leaf_kind, leaf_index, inner_shape=None, inner_index=None):
         p = tc_path()

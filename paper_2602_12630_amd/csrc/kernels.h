@@ -47,6 +47,7 @@ struct EncodeF16 {
     const uint16_t* src;
     int16_t* dst;
     float inv_scale;
+    const float* inv_scale_dev;     /* when set, the scale is read from device memory (written by the launches before) */
     TC_DEV static float half_to_float(uint16_t h) {
         uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
         uint32_t exp = (h >> 10) & 0x1Fu;
@@ -78,7 +79,7 @@ struct EncodeF16 {
         if (r < -32767.0f) r = -32767.0f;
         return (int16_t)r;
     }
-    TC_DEV void operator()(uint32_t t) const { dst[t] = quantise(src[t], inv_scale); }
+    TC_DEV void operator()(uint32_t t) const { dst[t] = quantise(src[t], inv_scale_dev ? *inv_scale_dev : inv_scale); }
 };
 /* the same, eight values per lane through 16-byte loads and stores (both buffers 16-byte aligned): a lane that
  * moves two bytes at a time leaves most of the HBM rate unused */
@@ -87,15 +88,82 @@ struct EncodeF16x8 {
     const Words16* src;
     Words16* dst;
     float inv_scale;
+    const float* inv_scale_dev;
     TC_DEV void operator()(uint32_t t) const {
         Words16 in = src[t], out;
+        float s = inv_scale_dev ? *inv_scale_dev : inv_scale;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            uint32_t lo = (uint16_t)EncodeF16::quantise((uint16_t)(in.w[i] & 0xFFFFu), inv_scale);
-            uint32_t hi = (uint16_t)EncodeF16::quantise((uint16_t)(in.w[i] >> 16), inv_scale);
+            uint32_t lo = (uint16_t)EncodeF16::quantise((uint16_t)(in.w[i] & 0xFFFFu), s);
+            uint32_t hi = (uint16_t)EncodeF16::quantise((uint16_t)(in.w[i] >> 16), s);
             out.w[i] = lo | (hi << 16);
         }
         dst[t] = out;
+    }
+};
+/* Per-tensor scale of the quantisation: the largest magnitude among the finite fp16 values, then
+ * inv_scale = float32(32767) / float32(amax) (0 for a tensor without a non-zero finite value).  Magnitudes of finite
+ * halves order like their bit patterns without the sign bit, so the maximum is taken on 15-bit integers: a lane
+ * runs over 16-byte pieces with the stride of the whole launch, a workgroup combines its lanes in LDS, and one
+ * atomic maximum per workgroup lands in `result`, which the last kernel turns into the scale in place. */
+TC_HD uint32_t half_magnitude_if_finite(uint32_t h) {
+    uint32_t mag = h & 0x7FFFu;
+    return mag < 0x7C00u ? mag : 0u;          /* exponent 31: infinities and NaNs do not count */
+}
+struct AbsMaxF16 {
+    static constexpr int BLOCK = 256;
+    static constexpr int PHASES = 3;
+    static constexpr size_t LDS_BYTES = 16;
+    const uint16_t* src;
+    uint64_t n;
+    uint32_t groups;
+    uint32_t* result;          /* zeroed before the launch */
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        uint32_t* wmax = (uint32_t*)lds;
+        if (ph == 0) {
+            if (lane == 0) wmax[0] = 0;
+            return;
+        }
+        if (ph == 2) {
+            if (lane == 0 && wmax[0]) atomic_max_u32(result, wmax[0]);
+            return;
+        }
+        uint32_t best = 0;
+        /* elements before the first 16-byte boundary and after the last whole piece go one by one (workgroup 0) */
+        uint64_t head = (16u - ((uintptr_t)src & 15u)) & 15u;
+        head = head / 2 < n ? head / 2 : n;
+        uint64_t chunks = (n - head) / 8;
+        const Words16* body = (const Words16*)(src + head);
+        for (uint64_t ch = (uint64_t)wg * BLOCK + lane; ch < chunks; ch += (uint64_t)groups * BLOCK) {
+            Words16 x = body[ch];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint32_t a = half_magnitude_if_finite(x.w[i] & 0xFFFFu), b = half_magnitude_if_finite(x.w[i] >> 16);
+                best = a > best ? a : best;
+                best = b > best ? b : best;
+            }
+        }
+        if (wg == 0) {
+            for (uint64_t i = lane; i < head; i += BLOCK) {
+                uint32_t a = half_magnitude_if_finite(src[i]);
+                best = a > best ? a : best;
+            }
+            for (uint64_t i = head + 8 * chunks + lane; i < n; i += BLOCK) {
+                uint32_t a = half_magnitude_if_finite(src[i]);
+                best = a > best ? a : best;
+            }
+        }
+        if (best) atomic_max_u32(wmax, best);
+    }
+};
+struct InvScaleFromAbsMax {        /* one lane: the 15-bit magnitude in *result becomes the float scale, in place */
+    uint32_t* result;
+    TC_DEV void operator()(uint32_t) const {
+        float amax = EncodeF16::half_to_float((uint16_t)*result);
+        float inv = amax > 0.0f ? 32767.0f / amax : 0.0f;
+        uint32_t bits;
+        memcpy(&bits, &inv, 4);
+        *result = bits;
     }
 };
 struct Copy128 {
@@ -1708,6 +1776,18 @@ struct VerifyDecideSrc {       /* workgroup = step: the partial sums must cancel
     }
 };
 constexpr uint32_t VERIFY_MAX_GROUPS = VERIFY_CHAINS / 2 + 1;
+/* canonical bytes -> affine point in Montgomery form; a point that is not canonical or not on the curve clears *ok */
+struct FromCanonicalChecked {
+    const uint32_t* in;     /* 24 words per point */
+    g1_affine* out;
+    uint32_t* ok;
+    TC_DEV void operator()(uint32_t t) const {
+        const uint32_t* w = in + 24 * (uint64_t)t;
+        g1_affine p = affine_from_canonical(w);
+        if (!limbs_gt<12>(FpParams::MOD, w) || !limbs_gt<12>(FpParams::MOD, w + 12) || !affine_on_curve(p)) atomic_and_u32(ok, 0u);
+        out[t] = p;
+    }
+};
 /* phi of canonical commitments (the verifier's side of "the opened value matches the next commitment") */
 struct PhiCanonical {
     const uint32_t* pts;       /* 24 words each */

@@ -299,6 +299,68 @@ static void fr_batch_inverse(std::vector<fr_t>& v) {       /* every entry non-ze
     }
 }
 
+/* ---- cooperative launches: a workgroup runs the phases of a functor with a barrier after each ---------- */
+#if defined(TC_HOST_EMU)
+template <int BLOCK, class F>
+static int launch_coop(uint32_t groups, rt::stream_t, const F& f) {
+    std::vector<uint8_t> lds(F::LDS_BYTES);
+    for (uint32_t g = 0; g < groups; ++g)
+        for (int ph = 0; ph < F::PHASES; ++ph)
+            for (uint32_t lane = 0; lane < (uint32_t)BLOCK; ++lane) f.phase(ph, lane, g, lds.data());
+    return 0;
+}
+#else
+template <class F, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void coop_kernel(const F f) {
+    extern __shared__ __align__(16) uint8_t lds[];
+    for (int ph = 0; ph < F::PHASES; ++ph) {
+        f.phase(ph, threadIdx.x, blockIdx.x, lds);
+        __syncthreads();
+    }
+}
+template <int BLOCK, class F>
+static int launch_coop(uint32_t groups, rt::stream_t st, const F& f) {
+    if (!groups) return 0;
+    /* once per kernel, whichever host thread comes first (contexts of several threads share the kernels) */
+    static std::once_flag attr_once;
+    static int attr_error = 0;
+    std::call_once(attr_once, [] {
+        attr_error = (int)hipFuncSetAttribute(reinterpret_cast<const void*>(&coop_kernel<F, BLOCK>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)F::LDS_BYTES);
+    });
+    if (attr_error) return attr_error;
+    hipLaunchKernelGGL((coop_kernel<F, BLOCK>), dim3(groups), dim3(BLOCK), F::LDS_BYTES, st, f);
+    return (int)hipGetLastError();
+}
+#endif
+
+/* cooperative launch whose number of phases is known only at run time */
+#if defined(TC_HOST_EMU)
+template <int BLOCK, class F>
+static int launch_coop_n(uint32_t groups, rt::stream_t, const F& f, int phases) {
+    std::vector<uint8_t> lds(F::LDS_BYTES);
+    for (uint32_t g = 0; g < groups; ++g)
+        for (int ph = 0; ph < phases; ++ph)
+            for (uint32_t lane = 0; lane < (uint32_t)BLOCK; ++lane) f.phase(ph, lane, g, lds.data());
+    return 0;
+}
+#else
+template <class F, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void coop_kernel_n(const F f, int phases) {
+    extern __shared__ __align__(16) uint8_t lds[];
+    for (int ph = 0; ph < phases; ++ph) {
+        f.phase(ph, threadIdx.x, blockIdx.x, lds);
+        __syncthreads();
+    }
+}
+template <int BLOCK, class F>
+static int launch_coop_n(uint32_t groups, rt::stream_t st, const F& f, int phases) {
+    if (!groups || phases <= 0) return 0;
+    hipLaunchKernelGGL((coop_kernel_n<F, BLOCK>), dim3(groups), dim3(BLOCK), F::LDS_BYTES, st, f, phases);
+    return (int)hipGetLastError();
+}
+#endif
+
 /* ======================================================================================= */
 /* context                                                                                 */
 /* ======================================================================================= */
@@ -416,6 +478,99 @@ extern "C" int tc_ctx_profile_units(tc_ctx* ctx, int kind, uint64_t* units) {
         return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
     }
 }
+/* ---- measurement: what the integer ALUs sustain ------------------------------------------------------------
+ * Register-only loops at a chosen number of waves per SIMD.  A workgroup is four waves, one per SIMD of a compute
+ * unit; it asks for so much LDS that exactly `waves_per_simd` workgroups fit a compute unit, and the launch has
+ * that many workgroups per compute unit, so every one of them is resident from start to end. */
+#if !defined(TC_HOST_EMU)
+template <int KIND>
+__global__ __launch_bounds__(256) void alu_rate_kernel(uint32_t iters, uint32_t* sink) {
+#if defined(__HIP_DEVICE_COMPILE__)          /* the body uses device-only instructions; the host pass needs the symbol alone */
+    uint32_t t = blockIdx.x * 256u + threadIdx.x;
+    uint32_t out = 0;
+    if (KIND == TC_ALU_MAD || KIND == TC_ALU_MAD_CARRY) {
+        /* eight independent chains, as the columns of a product give the scheduler independent work */
+        uint64_t acc[8];
+        uint32_t hi[8];
+        uint32_t a = t * 2654435761u | 1u, b = (t + 12345u) * 40503u | 1u;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { acc[i] = t + (uint32_t)i; hi[i] = 0; }
+        for (uint32_t it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                uint64_t carry;
+                asm volatile("v_mad_u64_u32 %0, %1, %2, %3, %0" : "+v"(acc[i]), "=s"(carry) : "v"(a), "v"(b));
+                if (KIND == TC_ALU_MAD_CARRY) carry_into(hi[i], carry);     /* the third word of a 96-bit column sum */
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out ^= (uint32_t)acc[i] ^ (uint32_t)(acc[i] >> 32) ^ hi[i];
+    } else {
+        fp_t x = fe_one<FpParams>(), y = fe_one<FpParams>();
+        x.l[0] ^= t;
+        y.l[1] ^= t * 7u;
+        for (uint32_t it = 0; it < iters; ++it) {
+#pragma unroll 1
+            for (int i = 0; i < 8; ++i) x = KIND == TC_ALU_FP_MUL ? fp_mul(x, y) : fp_sqr(x);
+        }
+#pragma unroll
+        for (int i = 0; i < 12; ++i) out ^= x.l[i];
+    }
+    if (out == 0x9E3779B9u) sink[0] = t;        /* keeps the loops alive; practically never taken */
+#endif
+}
+#endif
+
+extern "C" int tc_ctx_alu_rate(tc_ctx* ctx, int kind, int waves_per_simd, double* out_per_s) {
+    if (!ctx) return TC_ERR_ARG;
+    if (!out_per_s || kind < 0 || kind > TC_ALU_FP_SQR) return fail(ctx, TC_ERR_ARG, "bad argument");
+    if (waves_per_simd < 1 || waves_per_simd > 8) return fail(ctx, TC_ERR_ARG, "waves_per_simd must be 1..8");
+#if defined(TC_HOST_EMU)
+    return fail(ctx, TC_ERR_HIP, "no GPU in the host emulation");
+#else
+    RT(rt::set_device(ctx->device));
+    hipDeviceProp_t prop;
+    RT((int)hipGetDeviceProperties(&prop, ctx->device));
+    uint32_t cus = (uint32_t)prop.multiProcessorCount;
+    size_t lds_per_cu = prop.maxSharedMemoryPerMultiProcessor ? prop.maxSharedMemoryPerMultiProcessor : 65536;
+    /* a workgroup may not ask for more than sharedMemPerBlock; one that asks for more than half the compute
+     * unit's LDS still has the compute unit to itself */
+    size_t lds = std::min<size_t>(lds_per_cu / (size_t)waves_per_simd, prop.sharedMemPerBlock) / 1024 * 1024;
+    if (lds * ((size_t)waves_per_simd + 1) <= lds_per_cu) return fail(ctx, TC_ERR_STATE, "cannot pin that many waves per SIMD on this device");
+    TRY(ws_reset(ctx));
+    WS(sink, uint32_t, 1);
+    uint32_t groups = cus * (uint32_t)waves_per_simd;
+    bool mads = kind == TC_ALU_MAD || kind == TC_ALU_MAD_CARRY;
+    uint32_t iters = mads ? 16384u : 256u;
+    rt::event_t e0 = nullptr, e1 = nullptr;
+    if (rt::event_create(&e0) || rt::event_create(&e1)) return fail(ctx, TC_ERR_HIP, "event creation failed");
+    int rc = TC_OK;
+    for (int rep = 0; rep < 2 && rc == TC_OK; ++rep) {       /* the first run warms up, the second is timed */
+        rt::event_record(e0, ctx->stream);
+        void (*k)(uint32_t, uint32_t*) = kind == TC_ALU_MAD         ? alu_rate_kernel<TC_ALU_MAD>
+                                         : kind == TC_ALU_MAD_CARRY ? alu_rate_kernel<TC_ALU_MAD_CARRY>
+                                         : kind == TC_ALU_FP_MUL    ? alu_rate_kernel<TC_ALU_FP_MUL>
+                                                                    : alu_rate_kernel<TC_ALU_FP_SQR>;
+        int e = (int)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (!e) {
+            hipLaunchKernelGGL(k, dim3(groups), dim3(256), lds, ctx->stream, iters, sink);
+            e = (int)hipGetLastError();
+        }
+        rt::event_record(e1, ctx->stream);
+        if (e) rc = fail_hip(ctx, e, "alu_rate_kernel");
+        if (rc == TC_OK && (e = rt::stream_sync(ctx->stream)) != 0) rc = fail_hip(ctx, e, "alu_rate_kernel");
+    }
+    float ms = 0;
+    if (rc == TC_OK && rt::event_elapsed_ms(e0, e1, &ms) != 0) rc = fail(ctx, TC_ERR_HIP, "event timing failed");
+    rt::event_destroy(e0);
+    rt::event_destroy(e1);
+    if (rc != TC_OK) return rc;
+    double ops = (double)groups * 256.0 * (double)iters * 8.0;
+    *out_per_s = ops / ((double)ms * 1e-3);
+    return TC_OK;
+#endif
+}
+
 extern "C" const char* tc_last_error(const tc_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 extern "C" int tc_ctx_sync(tc_ctx* ctx) {
     try {
@@ -693,6 +848,160 @@ extern "C" int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, co
     }
 }
 
+/* ---- the public parameters as a flat file (Def. 4.1, Setup publishes pp = (srs, Omega)) ----------------------
+ * Header (little-endian), then the tables S^(0) .. S^(last) one after the other, canonical 96-byte points:
+ *     0  char[8]  "TCSRS\0\0\0"
+ *     8  u32      format version (1)
+ *    12  u32      curve (1 = BLS12-381, points in G1)
+ *    16  u32      basis (0 = Lagrange image of the monomial SRS on the grid prod {1..d_j}, 1 = monomial)
+ *    20  u32      flags the SRS was built with (suffix tables are stored, fixed-base tables are rebuilt on import)
+ *    24  u32      m
+ *    28  u32[4]   shape (unused axes 1)
+ *    44  u32      reserved (0)
+ *    48  u64      number of points that follow
+ *    56  ...      points */
+static const char SRS_MAGIC[8] = {'T', 'C', 'S', 'R', 'S', 0, 0, 0};
+static const size_t SRS_HEADER_BYTES = 56;
+static const uint32_t FILE_VERSION = 1, CURVE_BLS12_381_G1 = 1;
+/* points move between the device and the caller's buffer in pieces of this many */
+static const uint64_t IO_CHUNK_POINTS = 1ull << 18;
+
+static void put_u32(uint8_t* p, uint32_t v) { memcpy(p, &v, 4); }
+static void put_u64(uint8_t* p, uint64_t v) { memcpy(p, &v, 8); }
+static uint32_t get_u32(const uint8_t* p) { uint32_t v; memcpy(&v, p, 4); return v; }
+static uint64_t get_u64(const uint8_t* p) { uint64_t v; memcpy(&v, p, 8); return v; }
+
+/* device affine points -> canonical bytes in host memory, in pieces through the workspace */
+static int export_points(tc_ctx* ctx, const g1_affine* d_pts, uint64_t n, uint8_t* out) {
+    uint64_t chunk = std::min<uint64_t>(n ? n : 1, IO_CHUNK_POINTS);
+    WS(can, uint32_t, 24ull * chunk);
+    for (uint64_t i0 = 0; i0 < n; i0 += chunk) {
+        uint64_t cnt = std::min(chunk, n - i0);
+        RT(rt::launch<64>(cnt, ctx->stream, ToCanonical{d_pts + i0, can}));
+        RT(rt::memcpy_d2h(out + 96ull * i0, can, 96ull * cnt, ctx->stream));
+        TRY(ctx_sync(ctx));                      /* the piece of workspace is reused */
+    }
+    return TC_OK;
+}
+/* canonical bytes in host memory -> device affine points; every point must be canonical and on the curve */
+static int import_points(tc_ctx* ctx, const uint8_t* in, uint64_t n, g1_affine* d_pts) {
+    uint64_t chunk = std::min<uint64_t>(n ? n : 1, IO_CHUNK_POINTS);
+    WS(can, uint32_t, 24ull * chunk);
+    WS(d_ok, uint32_t, 1);
+    RT(rt::launch<64>(1, ctx->stream, Fill32{d_ok, 1u}));
+    for (uint64_t i0 = 0; i0 < n; i0 += chunk) {
+        uint64_t cnt = std::min(chunk, n - i0);
+        RT(rt::memcpy_h2d(can, in + 96ull * i0, 96ull * cnt, ctx->stream));
+        RT(rt::launch<64>(cnt, ctx->stream, FromCanonicalChecked{can, d_pts + i0, d_ok}));
+        TRY(ctx_sync(ctx));                      /* the caller's buffer may be pageable: the copy has read it by now */
+    }
+    uint32_t ok = 0;
+    RT(rt::memcpy_d2h(&ok, d_ok, 4, ctx->stream));
+    TRY(ctx_sync(ctx));
+    if (!ok) return fail(ctx, TC_ERR_RANGE, "a point is not canonical or not on the curve");
+    return TC_OK;
+}
+
+extern "C" int tc_srs_export(tc_ctx* ctx, const tc_srs* srs, void* host_buf, size_t* len) {
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!srs || !len) return fail(ctx, TC_ERR_ARG, "null argument");
+        uint64_t count = 0;
+        for (int a = 0; a < srs->m; ++a)
+            if (srs->pts[a]) count += srs->n[a];
+        size_t need = SRS_HEADER_BYTES + 96 * (size_t)count;
+        size_t cap = *len;
+        *len = need;
+        if (!host_buf) return TC_OK;                /* size query */
+        if (cap < need) return fail(ctx, TC_ERR_ARG, "buffer too small for the SRS (needed size returned in *len)");
+        RT(rt::set_device(ctx->device));
+        TRY(ws_reset(ctx));
+        uint8_t* o = (uint8_t*)host_buf;
+        memset(o, 0, SRS_HEADER_BYTES);
+        memcpy(o, SRS_MAGIC, 8);
+        put_u32(o + 8, FILE_VERSION);
+        put_u32(o + 12, CURVE_BLS12_381_G1);
+        put_u32(o + 16, (srs->flags & TC_SRS_MONOMIAL) ? 1u : 0u);
+        put_u32(o + 20, srs->flags);
+        put_u32(o + 24, (uint32_t)srs->m);
+        for (int j = 0; j < 4; ++j) put_u32(o + 28 + 4 * j, j < srs->m ? srs->shape[j] : 1u);
+        put_u64(o + 48, count);
+        o += SRS_HEADER_BYTES;
+        for (int a = 0; a < srs->m; ++a) {
+            if (!srs->pts[a]) continue;
+            TRY(export_points(ctx, srs->pts[a], srs->n[a], o));
+            o += 96 * (size_t)srs->n[a];
+        }
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
+}
+
+extern "C" int tc_srs_import(tc_ctx* ctx, const void* host_buf, size_t len, tc_srs** out) {
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!host_buf || !out) return fail(ctx, TC_ERR_ARG, "null argument");
+        *out = nullptr;
+        const uint8_t* in = (const uint8_t*)host_buf;
+        if (len < SRS_HEADER_BYTES) return fail(ctx, TC_ERR_ARG, "SRS file truncated: no complete header");
+        if (memcmp(in, SRS_MAGIC, 8) != 0) return fail(ctx, TC_ERR_ARG, "not an SRS file");
+        if (get_u32(in + 8) != FILE_VERSION) return fail(ctx, TC_ERR_ARG, "unknown SRS file version");
+        if (get_u32(in + 12) != CURVE_BLS12_381_G1) return fail(ctx, TC_ERR_ARG, "the SRS file is for another curve");
+        uint32_t basis = get_u32(in + 16), flags = get_u32(in + 20), m = get_u32(in + 24);
+        uint32_t shape[4];
+        for (int j = 0; j < 4; ++j) shape[j] = get_u32(in + 28 + 4 * j);
+        uint64_t count = get_u64(in + 48), total = 0;
+        if (m < 1 || m > TC_MAX_ORDER || !shape_ok((int)m, shape, &total)) return fail(ctx, TC_ERR_SHAPE, "bad shape in the SRS file");
+        for (uint32_t j = m; j < 4; ++j)
+            if (shape[j] != 1) return fail(ctx, TC_ERR_SHAPE, "bad shape in the SRS file");
+        if (!srs_flags_ok(flags) || basis > 1 || (basis == 1) != ((flags & TC_SRS_MONOMIAL) != 0))
+            return fail(ctx, TC_ERR_ARG, "bad flags or basis kind in the SRS file");
+        if ((flags & TC_SRS_FIXED_BASE) && total > FB_MAX_BASES)
+            return fail(ctx, TC_ERR_SHAPE, "fixed-base tables are limited to shapes with at most 64 entries");
+        int last_axis = (flags & TC_SRS_SUFFIX) ? (int)m - 1 : 0;
+        uint64_t expect = 0, n[4] = {0, 0, 0, 0};
+        for (int a = 0; a <= last_axis; ++a) {
+            n[a] = 1;
+            for (uint32_t j = (uint32_t)a; j < m; ++j) n[a] *= shape[j];
+            expect += n[a];
+        }
+        if (count != expect) return fail(ctx, TC_ERR_ARG, "point count in the SRS file does not match its shape and flags");
+        if (len != SRS_HEADER_BYTES + 96 * (size_t)count) return fail(ctx, TC_ERR_ARG, "SRS file truncated or too long for its point count");
+        RT(rt::set_device(ctx->device));
+        TRY(ws_reset(ctx));
+        tc_srs* srs = new (std::nothrow) tc_srs();
+        if (!srs) return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+        srs->m = (int)m;
+        srs->flags = flags;
+        for (uint32_t j = 0; j < m; ++j) srs->shape[j] = shape[j];
+        int rc = srs_upload_axis_tables(ctx, srs);
+        const uint8_t* src = in + SRS_HEADER_BYTES;
+        for (int a = 0; a <= last_axis && rc == TC_OK; ++a) {
+            srs->n[a] = n[a];
+            void* q = nullptr;
+            if (rt::dev_malloc(&q, (size_t)n[a] * sizeof(g1_affine)) != 0) { rc = fail(ctx, TC_ERR_NOMEM, "SRS allocation failed"); break; }
+            srs->pts[a] = (g1_affine*)q;
+            rc = import_points(ctx, src, n[a], srs->pts[a]);
+            src += 96 * (size_t)n[a];
+            if (rc == TC_OK && (flags & TC_SRS_FIXED_BASE)) rc = build_fixed_base_table(ctx, srs->pts[a], (uint32_t)n[a], &srs->fb[a]);
+        }
+        if (rc != TC_OK) {
+            rt::stream_sync(ctx->stream);
+            tc_srs_destroy(srs);
+            return rc;
+        }
+        *out = srs;
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
+}
+
 extern "C" int tc_srs_get_point(tc_ctx* ctx, const tc_srs* srs, int first_axis, uint64_t index, uint8_t out_g1[96]) {
     try {
         if (!ctx || !srs || !out_g1) return ctx ? fail(ctx, TC_ERR_ARG, "null argument") : TC_ERR_ARG;
@@ -711,108 +1020,68 @@ extern "C" int tc_srs_get_point(tc_ctx* ctx, const tc_srs* srs, int first_axis, 
 /* ======================================================================================= */
 /* encode                                                                                  */
 /* ======================================================================================= */
-extern "C" int tc_encode_tensor(tc_ctx* ctx, const void* d_src, int src_dtype, size_t n, float inv_scale, void* d_dst) {
-    try {
-        if (!ctx) return TC_ERR_ARG;
-        if ((!d_src || !d_dst) && n) return fail(ctx, TC_ERR_ARG, "null buffer");
-        if (n > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "tensor too large");
-        RT(rt::set_device(ctx->device));
-        /* the bulk goes 16 bytes per lane when both buffers allow it, the remainder element by element */
-        bool aligned = (((uintptr_t)d_src | (uintptr_t)d_dst) & 15u) == 0;
-        switch (src_dtype) {
-            case TC_F16: {
-                if (!(inv_scale == inv_scale) || inv_scale < 0) return fail(ctx, TC_ERR_RANGE, "inv_scale must be a non-negative number");
-                size_t bulk = aligned ? n / 8 : 0;
-                RT(rt::launch<256>(bulk, ctx->stream, EncodeF16x8{(const Words16*)d_src, (Words16*)d_dst, inv_scale}));
-                RT(rt::launch<256>(n - 8 * bulk, ctx->stream, EncodeF16{(const uint16_t*)d_src + 8 * bulk, (int16_t*)d_dst + 8 * bulk, inv_scale}));
-                return TC_OK;
-            }
-            case TC_I8: {
-                size_t bulk = aligned ? n / 16 : 0;
-                RT(rt::launch<256>(bulk, ctx->stream, Copy128{(const Words16*)d_src, (Words16*)d_dst}));
-                RT(rt::launch<256>(n - 16 * bulk, ctx->stream, Copy8{(const uint8_t*)d_src + 16 * bulk, (uint8_t*)d_dst + 16 * bulk}));
-                return TC_OK;
-            }
-            case TC_I16: {
-                size_t bulk = aligned ? n / 8 : 0;
-                RT(rt::launch<256>(bulk, ctx->stream, Copy128{(const Words16*)d_src, (Words16*)d_dst}));
-                RT(rt::launch<256>(n - 8 * bulk, ctx->stream, Copy16{(const uint16_t*)d_src + 8 * bulk, (uint16_t*)d_dst + 8 * bulk}));
-                return TC_OK;
-            }
-            default:
-                return fail(ctx, TC_ERR_ARG, "unsupported source dtype");
+static int encode_tensor(tc_ctx* ctx, const void* d_src, int src_dtype, size_t n, float inv_scale, const float* d_inv_scale,
+                         void* d_dst) {
+    if ((!d_src || !d_dst) && n) return fail(ctx, TC_ERR_ARG, "null buffer");
+    if (n > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "tensor too large");
+    RT(rt::set_device(ctx->device));
+    /* the bulk goes 16 bytes per lane when both buffers allow it, the remainder element by element */
+    bool aligned = (((uintptr_t)d_src | (uintptr_t)d_dst) & 15u) == 0;
+    switch (src_dtype) {
+        case TC_F16: {
+            if (!d_inv_scale && (!(inv_scale == inv_scale) || inv_scale < 0)) return fail(ctx, TC_ERR_RANGE, "inv_scale must be a non-negative number");
+            size_t bulk = aligned ? n / 8 : 0;
+            RT(rt::launch<256>(bulk, ctx->stream, EncodeF16x8{(const Words16*)d_src, (Words16*)d_dst, inv_scale, d_inv_scale}));
+            RT(rt::launch<256>(n - 8 * bulk, ctx->stream,
+                               EncodeF16{(const uint16_t*)d_src + 8 * bulk, (int16_t*)d_dst + 8 * bulk, inv_scale, d_inv_scale}));
+            return TC_OK;
         }
-    } catch (const std::bad_alloc&) {
-        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
-    } catch (...) {
-        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+        case TC_I8: {
+            size_t bulk = aligned ? n / 16 : 0;
+            RT(rt::launch<256>(bulk, ctx->stream, Copy128{(const Words16*)d_src, (Words16*)d_dst}));
+            RT(rt::launch<256>(n - 16 * bulk, ctx->stream, Copy8{(const uint8_t*)d_src + 16 * bulk, (uint8_t*)d_dst + 16 * bulk}));
+            return TC_OK;
+        }
+        case TC_I16: {
+            size_t bulk = aligned ? n / 8 : 0;
+            RT(rt::launch<256>(bulk, ctx->stream, Copy128{(const Words16*)d_src, (Words16*)d_dst}));
+            RT(rt::launch<256>(n - 8 * bulk, ctx->stream, Copy16{(const uint16_t*)d_src + 8 * bulk, (uint16_t*)d_dst + 8 * bulk}));
+            return TC_OK;
+        }
+        default:
+            return fail(ctx, TC_ERR_ARG, "unsupported source dtype");
     }
+}
+extern "C" int tc_encode_tensor(tc_ctx* ctx, const void* d_src, int src_dtype, size_t n, float inv_scale, void* d_dst) {
+    if (!ctx) return TC_ERR_ARG;
+    return encode_tensor(ctx, d_src, src_dtype, n, inv_scale, nullptr, d_dst);
+}
+extern "C" int tc_encode_tensor_scaled(tc_ctx* ctx, const void* d_src, int src_dtype, size_t n, const float* d_inv_scale,
+                                       void* d_dst) {
+    if (!ctx) return TC_ERR_ARG;
+    if (!d_inv_scale) return fail(ctx, TC_ERR_ARG, "null scale");
+    return encode_tensor(ctx, d_src, src_dtype, n, 0.0f, d_inv_scale, d_dst);
+}
+/* at most this many workgroups take part in the maximum (each ends in one atomic) */
+static const uint32_t ABSMAX_MAX_GROUPS = 2048;
+extern "C" int tc_quant_scale(tc_ctx* ctx, const void* d_src, size_t n, float* d_inv_scale) {
+    if (!ctx) return TC_ERR_ARG;
+    if (!d_inv_scale || (!d_src && n)) return fail(ctx, TC_ERR_ARG, "null buffer");
+    if (((uintptr_t)d_src & 1u) || ((uintptr_t)d_inv_scale & 3u)) return fail(ctx, TC_ERR_ARG, "misaligned buffer");
+    if (n > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "tensor too large");
+    RT(rt::set_device(ctx->device));
+    uint32_t* result = (uint32_t*)d_inv_scale;
+    RT(rt::launch<64>(1, ctx->stream, Fill32{result, 0u}));
+    uint32_t groups = (uint32_t)std::min<uint64_t>(ABSMAX_MAX_GROUPS, (n / 8 + AbsMaxF16::BLOCK - 1) / AbsMaxF16::BLOCK);
+    if (groups == 0) groups = 1;
+    if (n) RT((launch_coop<AbsMaxF16::BLOCK>(groups, ctx->stream, AbsMaxF16{(const uint16_t*)d_src, (uint64_t)n, groups, result})));
+    RT(rt::launch<64>(1, ctx->stream, InvScaleFromAbsMax{result}));
+    return TC_OK;
 }
 
 /* ======================================================================================= */
 /* MSM engine                                                                              */
 /* ======================================================================================= */
-#if defined(TC_HOST_EMU)
-template <int BLOCK, class F>
-static int launch_coop(uint32_t groups, rt::stream_t, const F& f) {
-    std::vector<uint8_t> lds(F::LDS_BYTES);
-    for (uint32_t g = 0; g < groups; ++g)
-        for (int ph = 0; ph < F::PHASES; ++ph)
-            for (uint32_t lane = 0; lane < (uint32_t)BLOCK; ++lane) f.phase(ph, lane, g, lds.data());
-    return 0;
-}
-#else
-template <class F, int BLOCK>
-__global__ __launch_bounds__(BLOCK) void coop_kernel(const F f) {
-    extern __shared__ __align__(16) uint8_t lds[];
-    for (int ph = 0; ph < F::PHASES; ++ph) {
-        f.phase(ph, threadIdx.x, blockIdx.x, lds);
-        __syncthreads();
-    }
-}
-template <int BLOCK, class F>
-static int launch_coop(uint32_t groups, rt::stream_t st, const F& f) {
-    if (!groups) return 0;
-    /* once per kernel, whichever host thread comes first (contexts of several threads share the kernels) */
-    static std::once_flag attr_once;
-    static int attr_error = 0;
-    std::call_once(attr_once, [] {
-        attr_error = (int)hipFuncSetAttribute(reinterpret_cast<const void*>(&coop_kernel<F, BLOCK>),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)F::LDS_BYTES);
-    });
-    if (attr_error) return attr_error;
-    hipLaunchKernelGGL((coop_kernel<F, BLOCK>), dim3(groups), dim3(BLOCK), F::LDS_BYTES, st, f);
-    return (int)hipGetLastError();
-}
-#endif
-
-/* cooperative launch whose number of phases is known only at run time */
-#if defined(TC_HOST_EMU)
-template <int BLOCK, class F>
-static int launch_coop_n(uint32_t groups, rt::stream_t, const F& f, int phases) {
-    std::vector<uint8_t> lds(F::LDS_BYTES);
-    for (uint32_t g = 0; g < groups; ++g)
-        for (int ph = 0; ph < phases; ++ph)
-            for (uint32_t lane = 0; lane < (uint32_t)BLOCK; ++lane) f.phase(ph, lane, g, lds.data());
-    return 0;
-}
-#else
-template <class F, int BLOCK>
-__global__ __launch_bounds__(BLOCK) void coop_kernel_n(const F f, int phases) {
-    extern __shared__ __align__(16) uint8_t lds[];
-    for (int ph = 0; ph < phases; ++ph) {
-        f.phase(ph, threadIdx.x, blockIdx.x, lds);
-        __syncthreads();
-    }
-}
-template <int BLOCK, class F>
-static int launch_coop_n(uint32_t groups, rt::stream_t st, const F& f, int phases) {
-    if (!groups || phases <= 0) return 0;
-    hipLaunchKernelGGL((coop_kernel_n<F, BLOCK>), dim3(groups), dim3(BLOCK), F::LDS_BYTES, st, f, phases);
-    return (int)hipGetLastError();
-}
-#endif
-
 /* a tree level of at most this many nodes (two workgroups per compute unit) takes the cooperative sums */
 static const uint64_t COOP_LEVEL_NODES = 512;
 /* a tree level spreads the windows of a child over lanes as long as it stays within this many lanes (two waves per SIMD) */
@@ -1578,104 +1847,119 @@ struct GatherNodeFr {
     }
 };
 
+/* Checks a tree description and lays the tree out: level grids bottom-up and one device block for the commitments
+ * and phi values of every level (taken from the context's pool when it is large enough).  Nothing is computed. */
+static int tree_prepare(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** out) {
+    *out = nullptr;
+    uint64_t n_payload = 0, B = 0;
+    if (!shape_ok(desc->m, desc->grid, &n_payload) || !shape_ok(desc->m, desc->node_shape, &B))
+        return fail(ctx, TC_ERR_SHAPE, "bad grid or node shape");
+    const tc_srs* ns = desc->node_srs;
+    if (!ns) return fail(ctx, TC_ERR_ARG, "node SRS missing");
+    if (ns->m != desc->m) return fail(ctx, TC_ERR_SHAPE, "node SRS order differs from the grid order");
+    for (int j = 0; j < desc->m; ++j)
+        if (ns->shape[j] != desc->node_shape[j]) return fail(ctx, TC_ERR_SHAPE, "node SRS shape differs from node_shape");
+    if (ns->flags & TC_SRS_MONOMIAL) return fail(ctx, TC_ERR_STATE, "trees need the Lagrange-basis SRS, this one is monomial");
+    bool more_than_one = false;
+    for (int j = 0; j < desc->m; ++j) more_than_one = more_than_one || desc->node_shape[j] > 1;
+    if (!more_than_one) return fail(ctx, TC_ERR_SHAPE, "node shape must have more than one entry");
+    if (desc->leaf_kind == TC_LEAF_ENTRIES) {
+        if (!desc->d_payload) return fail(ctx, TC_ERR_ARG, "payload missing");
+        if (desc->dtype != TC_I8 && desc->dtype != TC_I16) return fail(ctx, TC_ERR_ARG, "payload must be int8 or int16");
+    } else if (desc->leaf_kind == TC_LEAF_TENSORS) {
+        if (!desc->leaf_srs || !desc->d_leaf_scalars || !desc->leaf_dtype) return fail(ctx, TC_ERR_ARG, "leaf arrays missing");
+        for (uint64_t i = 0; i < n_payload; ++i) {
+            TRY(check_commit_args(ctx, desc->leaf_srs[i], desc->d_leaf_scalars[i], desc->leaf_dtype[i]));
+            if (desc->leaf_srs[i]->flags & TC_SRS_MONOMIAL) return fail(ctx, TC_ERR_STATE, "trees need the Lagrange-basis SRS, a leaf SRS is monomial");
+        }
+    } else {
+        return fail(ctx, TC_ERR_ARG, "bad leaf kind");
+    }
+    RT(rt::set_device(ctx->device));
+    TRY(ws_reset(ctx));
+
+    tc_tree* t = new (std::nothrow) tc_tree();
+    if (!t) return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    t->m = desc->m;
+    t->B = (uint32_t)B;
+    t->node_srs = ns;
+    t->leaf_kind = desc->leaf_kind;
+    t->d_payload = desc->d_payload;
+    t->dtype = desc->dtype;
+    for (int j = 0; j < desc->m; ++j) { t->grid[j] = desc->grid[j]; t->node_shape[j] = desc->node_shape[j]; }
+    if (desc->leaf_kind == TC_LEAF_TENSORS) {
+        t->leaf_srs.assign(desc->leaf_srs, desc->leaf_srs + n_payload);
+        t->leaf_scalars.assign(desc->d_leaf_scalars, desc->d_leaf_scalars + n_payload);
+        t->leaf_dtype.assign(desc->leaf_dtype, desc->leaf_dtype + n_payload);
+    }
+    /* level grids, bottom-up */
+    {
+        uint32_t g[4] = {1, 1, 1, 1};
+        for (int j = 0; j < t->m; ++j) g[j] = t->grid[j];
+        bool first = true;
+        for (;;) {
+            bool blocked = !(first && t->leaf_kind == TC_LEAF_TENSORS);
+            TreeLevel lv;
+            lv.n = 1;
+            bool all_one = true;
+            for (int j = 0; j < t->m; ++j) {
+                lv.grid[j] = blocked ? (g[j] + t->node_shape[j] - 1) / t->node_shape[j] : g[j];
+                lv.n *= lv.grid[j];
+                all_one = all_one && lv.grid[j] == 1;
+                g[j] = lv.grid[j];
+            }
+            t->levels.push_back(lv);
+            first = false;
+            if (all_one) break;
+            if (t->levels.size() >= MAX_LEVELS) {
+                delete t;
+                return fail(ctx, TC_ERR_SHAPE, "tree too deep");
+            }
+        }
+    }
+    int rc = TC_OK;
+    {
+        size_t total = 0;
+        for (auto& lv : t->levels) total += ((size_t)lv.n * sizeof(g1_affine) + 255) / 256 * 256 + ((size_t)lv.n * sizeof(fr_plain) + 255) / 256 * 256;
+        t->pool = ctx->tree_pool;
+        if (ctx->tree_pool->block && ctx->tree_pool->cap >= total) {
+            t->block = ctx->tree_pool->block;
+            t->block_cap = ctx->tree_pool->cap;
+            ctx->tree_pool->block = nullptr;
+            ctx->tree_pool->cap = 0;
+        } else if (rt::dev_malloc(&t->block, total) == 0) {
+            t->block_cap = total;
+        } else {
+            t->block = nullptr;
+        }
+        if (!t->block) {
+            rc = fail(ctx, TC_ERR_NOMEM, "tree level allocation failed");
+        } else {
+            uint8_t* at = (uint8_t*)t->block;
+            for (auto& lv : t->levels) {
+                lv.C = (g1_affine*)at;
+                at += ((size_t)lv.n * sizeof(g1_affine) + 255) / 256 * 256;
+                lv.phi = (fr_plain*)at;
+                at += ((size_t)lv.n * sizeof(fr_plain) + 255) / 256 * 256;
+            }
+        }
+    }
+    if (rc != TC_OK) {
+        tc_tree_destroy(t);
+        return rc;
+    }
+    *out = t;
+    return TC_OK;
+}
+
 extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** out) {
     try {
         if (!ctx) return TC_ERR_ARG;
         if (!desc || !out) return fail(ctx, TC_ERR_ARG, "null argument");
-        *out = nullptr;
-        uint64_t n_payload = 0, B = 0;
-        if (!shape_ok(desc->m, desc->grid, &n_payload) || !shape_ok(desc->m, desc->node_shape, &B))
-            return fail(ctx, TC_ERR_SHAPE, "bad grid or node shape");
-        const tc_srs* ns = desc->node_srs;
-        if (!ns) return fail(ctx, TC_ERR_ARG, "node SRS missing");
-        if (ns->m != desc->m) return fail(ctx, TC_ERR_SHAPE, "node SRS order differs from the grid order");
-        for (int j = 0; j < desc->m; ++j)
-            if (ns->shape[j] != desc->node_shape[j]) return fail(ctx, TC_ERR_SHAPE, "node SRS shape differs from node_shape");
-        if (ns->flags & TC_SRS_MONOMIAL) return fail(ctx, TC_ERR_STATE, "trees need the Lagrange-basis SRS, this one is monomial");
-        bool more_than_one = false;
-        for (int j = 0; j < desc->m; ++j) more_than_one = more_than_one || desc->node_shape[j] > 1;
-        if (!more_than_one) return fail(ctx, TC_ERR_SHAPE, "node shape must have more than one entry");
-        if (desc->leaf_kind == TC_LEAF_ENTRIES) {
-            if (!desc->d_payload) return fail(ctx, TC_ERR_ARG, "payload missing");
-            if (desc->dtype != TC_I8 && desc->dtype != TC_I16) return fail(ctx, TC_ERR_ARG, "payload must be int8 or int16");
-        } else if (desc->leaf_kind == TC_LEAF_TENSORS) {
-            if (!desc->leaf_srs || !desc->d_leaf_scalars || !desc->leaf_dtype) return fail(ctx, TC_ERR_ARG, "leaf arrays missing");
-            for (uint64_t i = 0; i < n_payload; ++i) {
-                TRY(check_commit_args(ctx, desc->leaf_srs[i], desc->d_leaf_scalars[i], desc->leaf_dtype[i]));
-                if (desc->leaf_srs[i]->flags & TC_SRS_MONOMIAL) return fail(ctx, TC_ERR_STATE, "trees need the Lagrange-basis SRS, a leaf SRS is monomial");
-            }
-        } else {
-            return fail(ctx, TC_ERR_ARG, "bad leaf kind");
-        }
-        RT(rt::set_device(ctx->device));
-        TRY(ws_reset(ctx));
-
-        tc_tree* t = new (std::nothrow) tc_tree();
-        if (!t) return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
-        t->m = desc->m;
-        t->B = (uint32_t)B;
-        t->node_srs = ns;
-        t->leaf_kind = desc->leaf_kind;
-        t->d_payload = desc->d_payload;
-        t->dtype = desc->dtype;
-        for (int j = 0; j < desc->m; ++j) { t->grid[j] = desc->grid[j]; t->node_shape[j] = desc->node_shape[j]; }
-        if (desc->leaf_kind == TC_LEAF_TENSORS) {
-            t->leaf_srs.assign(desc->leaf_srs, desc->leaf_srs + n_payload);
-            t->leaf_scalars.assign(desc->d_leaf_scalars, desc->d_leaf_scalars + n_payload);
-            t->leaf_dtype.assign(desc->leaf_dtype, desc->leaf_dtype + n_payload);
-        }
-        /* level grids, bottom-up */
-        {
-            uint32_t g[4] = {1, 1, 1, 1};
-            for (int j = 0; j < t->m; ++j) g[j] = t->grid[j];
-            bool first = true;
-            for (;;) {
-                bool blocked = !(first && t->leaf_kind == TC_LEAF_TENSORS);
-                TreeLevel lv;
-                lv.n = 1;
-                bool all_one = true;
-                for (int j = 0; j < t->m; ++j) {
-                    lv.grid[j] = blocked ? (g[j] + t->node_shape[j] - 1) / t->node_shape[j] : g[j];
-                    lv.n *= lv.grid[j];
-                    all_one = all_one && lv.grid[j] == 1;
-                    g[j] = lv.grid[j];
-                }
-                t->levels.push_back(lv);
-                first = false;
-                if (all_one) break;
-                if (t->levels.size() >= MAX_LEVELS) {
-                    delete t;
-                    return fail(ctx, TC_ERR_SHAPE, "tree too deep");
-                }
-            }
-        }
+        tc_tree* t = nullptr;
+        TRY(tree_prepare(ctx, desc, &t));
+        const tc_srs* ns = t->node_srs;
         int rc = TC_OK;
-        {
-            size_t total = 0;
-            for (auto& lv : t->levels) total += ((size_t)lv.n * sizeof(g1_affine) + 255) / 256 * 256 + ((size_t)lv.n * sizeof(fr_plain) + 255) / 256 * 256;
-            t->pool = ctx->tree_pool;
-            if (ctx->tree_pool->block && ctx->tree_pool->cap >= total) {
-                t->block = ctx->tree_pool->block;
-                t->block_cap = ctx->tree_pool->cap;
-                ctx->tree_pool->block = nullptr;
-                ctx->tree_pool->cap = 0;
-            } else if (rt::dev_malloc(&t->block, total) == 0) {
-                t->block_cap = total;
-            } else {
-                t->block = nullptr;
-            }
-            if (!t->block) {
-                rc = fail(ctx, TC_ERR_NOMEM, "tree level allocation failed");
-            } else {
-                uint8_t* at = (uint8_t*)t->block;
-                for (auto& lv : t->levels) {
-                    lv.C = (g1_affine*)at;
-                    at += ((size_t)lv.n * sizeof(g1_affine) + 255) / 256 * 256;
-                    lv.phi = (fr_plain*)at;
-                    at += ((size_t)lv.n * sizeof(fr_plain) + 255) / 256 * 256;
-                }
-            }
-        }
         bool use_fb = ns->fb[0] != nullptr;
         for (size_t L = 0; L < t->levels.size() && rc == TC_OK; ++L) {
             TreeLevel& lv = t->levels[L];
@@ -1757,6 +2041,111 @@ extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** 
             ctx->wsp->off = mark;
         }
         if (rc == TC_OK) rc = affine_to_host(ctx, t->levels.back().C, 1, t->root);
+        if (rc != TC_OK) {
+            rt::stream_sync(ctx->stream);
+            tc_tree_destroy(t);
+            return rc;
+        }
+        *out = t;
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
+}
+
+/* ---- a tree as a flat file: the commitments of every node, so that openings can be served by a later process ----
+ * Header (little-endian), then the levels bottom-up, each the canonical 96-byte commitments of its nodes, row-major
+ * in the level's grid:
+ *     0  char[8]  "TCTREE\0\0"
+ *     8  u32      format version (1)
+ *    12  u32      curve (1 = BLS12-381, commitments in G1)
+ *    16  u32      m
+ *    20  u32[4]   payload grid (unused axes 1)
+ *    36  u32[4]   node shape
+ *    52  u32      leaf kind (TC_LEAF_ENTRIES / TC_LEAF_TENSORS)
+ *    56  u32      number of levels
+ *    60  u32      reserved (0)
+ *    64  u64      number of commitments that follow (all levels)
+ *    72  ...      commitments */
+static const char TREE_MAGIC[8] = {'T', 'C', 'T', 'R', 'E', 'E', 0, 0};
+static const size_t TREE_HEADER_BYTES = 72;
+
+extern "C" int tc_terkle_export(tc_ctx* ctx, const tc_tree* tree, void* host_buf, size_t* len) {
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!tree || !len) return fail(ctx, TC_ERR_ARG, "null argument");
+        uint64_t count = 0;
+        for (auto& lv : tree->levels) count += lv.n;
+        size_t need = TREE_HEADER_BYTES + 96 * (size_t)count;
+        size_t cap = *len;
+        *len = need;
+        if (!host_buf) return TC_OK;                /* size query */
+        if (cap < need) return fail(ctx, TC_ERR_ARG, "buffer too small for the tree (needed size returned in *len)");
+        RT(rt::set_device(ctx->device));
+        TRY(ws_reset(ctx));
+        uint8_t* o = (uint8_t*)host_buf;
+        memset(o, 0, TREE_HEADER_BYTES);
+        memcpy(o, TREE_MAGIC, 8);
+        put_u32(o + 8, FILE_VERSION);
+        put_u32(o + 12, CURVE_BLS12_381_G1);
+        put_u32(o + 16, (uint32_t)tree->m);
+        for (int j = 0; j < 4; ++j) {
+            put_u32(o + 20 + 4 * j, j < tree->m ? tree->grid[j] : 1u);
+            put_u32(o + 36 + 4 * j, j < tree->m ? tree->node_shape[j] : 1u);
+        }
+        put_u32(o + 52, (uint32_t)tree->leaf_kind);
+        put_u32(o + 56, (uint32_t)tree->levels.size());
+        put_u64(o + 64, count);
+        o += TREE_HEADER_BYTES;
+        for (auto& lv : tree->levels) {
+            TRY(export_points(ctx, lv.C, lv.n, o));
+            o += 96 * (size_t)lv.n;
+        }
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
+}
+
+extern "C" int tc_terkle_import(tc_ctx* ctx, const tc_tree_desc* desc, const void* host_buf, size_t len, tc_tree** out) {
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (!desc || !host_buf || !out) return fail(ctx, TC_ERR_ARG, "null argument");
+        *out = nullptr;
+        const uint8_t* in = (const uint8_t*)host_buf;
+        if (len < TREE_HEADER_BYTES) return fail(ctx, TC_ERR_ARG, "tree file truncated: no complete header");
+        if (memcmp(in, TREE_MAGIC, 8) != 0) return fail(ctx, TC_ERR_ARG, "not a tree file");
+        if (get_u32(in + 8) != FILE_VERSION) return fail(ctx, TC_ERR_ARG, "unknown tree file version");
+        if (get_u32(in + 12) != CURVE_BLS12_381_G1) return fail(ctx, TC_ERR_ARG, "the tree file is for another curve");
+        tc_tree* t = nullptr;
+        TRY(tree_prepare(ctx, desc, &t));
+        int rc = TC_OK;
+        do {
+            bool same = get_u32(in + 16) == (uint32_t)t->m && get_u32(in + 52) == (uint32_t)t->leaf_kind &&
+                        get_u32(in + 56) == (uint32_t)t->levels.size();
+            for (int j = 0; j < 4 && same; ++j)
+                same = get_u32(in + 20 + 4 * j) == (j < t->m ? t->grid[j] : 1u) &&
+                       get_u32(in + 36 + 4 * j) == (j < t->m ? t->node_shape[j] : 1u);
+            if (!same) { rc = fail(ctx, TC_ERR_SHAPE, "the tree file was written for another grid, node shape or leaf kind"); break; }
+            uint64_t count = 0;
+            for (auto& lv : t->levels) count += lv.n;
+            if (get_u64(in + 64) != count) { rc = fail(ctx, TC_ERR_ARG, "node count in the tree file does not match its shape"); break; }
+            if (len != TREE_HEADER_BYTES + 96 * (size_t)count) { rc = fail(ctx, TC_ERR_ARG, "tree file truncated or too long for its node count"); break; }
+            const uint8_t* src = in + TREE_HEADER_BYTES;
+            for (auto& lv : t->levels) {
+                rc = import_points(ctx, src, lv.n, lv.C);
+                if (rc) break;
+                int e = rt::launch<64>(lv.n, ctx->stream, PhiKernel{lv.C, lv.phi});
+                if (e) { rc = fail_hip(ctx, e, "phi"); break; }
+                src += 96 * (size_t)lv.n;
+            }
+            if (rc) break;
+            rc = affine_to_host(ctx, t->levels.back().C, 1, t->root);
+        } while (0);
         if (rc != TC_OK) {
             rt::stream_sync(ctx->stream);
             tc_tree_destroy(t);

@@ -1,9 +1,13 @@
 """Helpers shared by the GPU parity tests: device buffers through torch, oracle-side caches."""
+import os
+import time
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 
 import tc_inputs
 from oracle import bls12_381 as ec
-from oracle import tc
+from oracle import cbind, tc
 
 TAU = tc_inputs.trapdoors()
 TAU_BYTES = tc_inputs.trapdoor_bytes()
@@ -55,3 +59,26 @@ def parse_proof(path, proof):
         shapes.append(tuple(path.shape[s][j] for j in range(m)))
     assert off == len(proof)
     return steps, shapes
+
+
+# ---- oracle work on all host cores --------------------------------------------------------------------
+# numpy's generators and ufuncs and the C oracle (through ctypes) all release the interpreter lock, so a pool of
+# threads keeps the machine's cores busy; the GPU machine gives a test 16 of them whatever os.cpu_count() says.
+HOST_THREADS = min(16, os.cpu_count() or 1)
+
+
+def oracle_pool():
+    cbind.lib()                                    # load the C oracle before several threads ask for it
+    return ThreadPoolExecutor(max_workers=HOST_THREADS)
+
+
+class Stopwatch:
+    """Prints what a long test is doing and how long each part took (the GPU machine takes silence for a hang)."""
+
+    def __init__(self, name):
+        self.name, self.t0, self.last = name, time.time(), time.time()
+
+    def lap(self, what):
+        now = time.time()
+        print("%s: %s (%.1f s, %.1f s since start)" % (self.name, what, now - self.last, now - self.t0), flush=True)
+        self.last = now

@@ -12,7 +12,7 @@ from oracle import bls12_381 as ec
 from oracle import cbind, quantize, tc, terkle
 from oracle.bls12_381 import R
 
-from gpu_util import TAU_BYTES, fr_bytes_array, parse_proof, pps, serialize_steps, to_device
+from gpu_util import HOST_THREADS, TAU_BYTES, Stopwatch, fr_bytes_array, oracle_pool, parse_proof, pps, serialize_steps, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -259,6 +259,44 @@ def test_encode_matches_oracle_quantisation(T, ctx):
     assert dst.cpu().tolist() == [0, 2, 2, 0, -2]
 
 
+def test_quant_scale_on_device(T, ctx):
+    """The per-tensor scale computed by the library (one pass over the fp16 tensor, result left in device memory):
+    bit-equal to the oracle's float32(32767) / amax on the single-layer activation, on tensors of the LLaMA2-7B
+    forward's two shapes, all zeros, a single outlier, ragged and unaligned buffers, non-finite values left out;
+    then the quantisation that reads it from device memory equals the oracle's tensor."""
+    import torch
+
+    rng = np.random.default_rng(41)
+    cases = [tc_inputs.c2_activation(), tc_inputs.f16_normal((512, 11008), 77), np.zeros((129, 7), np.float16)]
+    outlier = (rng.standard_normal(100003) * 0.001).astype(np.float16)
+    outlier[99999] = np.float16(12.5)
+    cases.append(outlier)
+    odd = rng.standard_normal(8 * 256 * 5 + 3).astype(np.float16)
+    odd[[5, 6000]] = [np.inf, np.nan]
+    cases.append(odd)
+    cases.append(np.array([np.nan], np.float16))
+    scale = torch.full((4,), -1.0, dtype=torch.float32, device="cuda")
+    for x in cases:
+        flat = x.reshape(-1)
+        finite = flat[np.isfinite(flat)]
+        want = quantize.inv_scale_for(finite) if finite.size else np.float32(0)
+        for offset in (0, 3):
+            buf = torch.zeros(flat.size + 8, dtype=torch.int16, device="cuda")
+            buf[offset : offset + flat.size] = to_device(flat.view(np.int16))
+            src = buf[offset : offset + flat.size]
+            ctx.quant_scale(src, flat.size, scale[1:])
+            ctx.sync()
+            got = scale[1:2].cpu().numpy()
+            assert got.view(np.uint32)[0] == np.float32(want).view(np.uint32), (x.shape, offset, got[0], want)
+            dst = torch.empty(flat.size, dtype=torch.int16, device="cuda")
+            ctx.encode_tensor_scaled(src, T.TC_F16, flat.size, scale[1:], dst)
+            ctx.sync()
+            ref = quantize.quantize_f16(np.where(np.isfinite(flat), flat, np.float16(0)), want)
+            ok = np.isfinite(flat)
+            assert np.array_equal(dst.cpu().numpy()[ok], ref[ok])
+    assert scale[0].item() == -1.0 and scale[2].item() == -1.0        # only the one float was written
+
+
 def _check_tree_against_oracle(ctx, tree, otree):
     assert tree.levels == len(otree.levels)
     for L in range(tree.levels):
@@ -340,6 +378,63 @@ def test_tensors_tree_small(T, ctx, node_srs):
             s.close()
 
 
+def test_srs_and_tree_files(T, ctx, node_srs):
+    """Def. 4.1 Setup publishes pp: an SRS written out and read back commits and opens like the one it came from
+    (points equal to the oracle's); the node SRS read back rebuilds its fixed-base tables; a tree built, saved,
+    loaded and opened gives the oracle's proofs; damaged files give error codes."""
+    B = T.binding
+    shape = (37, 53)
+    pp = pps(shape)
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, T.TC_SRS_SUFFIX)
+    data = srs.export()
+    assert len(data) == 56 + 96 * (37 * 53 + 53)
+    for i in (0, 1, 52, 53, 1000, 37 * 53 - 1):
+        point = cbind.g1_mul(pp.lagrange_scalar(tc.multi_index(i, shape)), ec.G1)
+        assert data[56 + 96 * i : 56 + 96 * (i + 1)] == ec.g1_to_bytes(point)
+    back = ctx.srs_import(data)
+    X = tc_inputs.int16_uniform(shape, 12, -32768, 32767)
+    dX = to_device(X)
+    want = ec.g1_to_bytes(cbind.commit(pp, X))
+    assert ctx.commit(srs, dX, T.TC_I16) == want and ctx.commit(back, dX, T.TC_I16) == want
+    assert all(back.point(i, a) == srs.point(i, a) for a, idx in ((0, (0, 7, 1960)), (1, (0, 52))) for i in idx)
+    kappa = (36, 17)
+    yo, po = tc.open_(pp, X, kappa)
+    y, pi = ctx.open(back, dX, T.TC_I16, kappa)
+    assert y == ec.fr_to_bytes(yo) and pi == [ec.g1_to_bytes(p) for p in po]
+    back.close()
+    for blob, code in ((data[:-1], B.TC_ERR_ARG), (data[:30], B.TC_ERR_ARG), (b"X" + data[1:], B.TC_ERR_ARG),
+                       (data[:12] + (9).to_bytes(4, "little") + data[16:], B.TC_ERR_ARG),
+                       (data[:48] + (5).to_bytes(8, "little") + data[56:], B.TC_ERR_ARG),
+                       (data[:24] + (9).to_bytes(4, "little") + data[28:], B.TC_ERR_SHAPE),
+                       (data[:200] + bytes([data[200] ^ 4]) + data[201:], B.TC_ERR_RANGE)):
+        with pytest.raises(T.TcError) as e:
+            ctx.srs_import(blob)
+        assert e.value.code == code, (e.value.code, code)
+    srs.close()
+    # the node SRS through a file: the import rebuilds the fixed-base tables that trees use
+    node, grid = tc_inputs.NODE_SHAPE, (37, 53)
+    node_back = ctx.srs_import(node_srs.export())
+    tree = ctx.terkle_build_entries(node_back, dX, T.TC_I16, grid, node)
+    otree = terkle.build(pps, tc.as_flat_ints(X), grid, node)
+    assert tree.root == ec.g1_to_bytes(otree.root)
+    blob = tree.export()
+    assert blob[-96:] == ec.g1_to_bytes(otree.root)
+    tree.close()
+    loaded = ctx.terkle_build_entries(node_srs, dX, T.TC_I16, grid, node, from_file=blob)
+    try:
+        _check_tree_against_oracle(ctx, loaded, otree)
+        for leaf in [(0, 0), (36, 52), (20, 31)]:
+            assert loaded.open(leaf) == serialize_steps(terkle.open_path(pps, otree, grid, node, leaf))
+        for bad, code in ((blob[:-96], B.TC_ERR_ARG), (blob[:36] + (5).to_bytes(4, "little") + blob[40:], B.TC_ERR_SHAPE),
+                          (blob[:80] + bytes([blob[80] ^ 1]) + blob[81:], B.TC_ERR_RANGE)):
+            with pytest.raises(T.TcError) as e:
+                ctx.terkle_build_entries(node_srs, dX, T.TC_I16, grid, node, from_file=bad)
+            assert e.value.code == code, (e.value.code, code)
+    finally:
+        loaded.close()
+        node_back.close()
+
+
 def test_c1_single_level_tree(T, ctx, c1):
     srs, X, dX = c1
     shape = tc_inputs.C1_SHAPE
@@ -387,12 +482,14 @@ def test_c2_activation_commit(T, ctx):
         srs.close()
 
 
-def test_c2_tree_sampled_nodes_and_paths(T, ctx, node_srs):
+def test_c2_tree_every_node_and_paths(T, ctx, node_srs):
     """Config 2, tree form at full size: (4,4) tree over the 2^21 quantised entries, 139 813 nodes.
-    The oracle recomputes sampled nodes of the three lowest levels from the payload alone, checks
-    level sizes, and its own verifier accepts the GPU's membership proofs against the GPU's root."""
+    The oracle recomputes EVERY node of every level and the root from the payload alone (closed form per node:
+    field sum, then one scalar multiplication in the C oracle, on all host cores), its own verifier accepts the
+    GPU's membership proofs, and whole proofs equal the oracle's byte for byte."""
     import torch
 
+    watch = Stopwatch("config 2 tree")
     shape, node = tc_inputs.C2_SHAPE, tc_inputs.NODE_SHAPE
     x = tc_inputs.c2_activation()
     q = quantize.quantize_f16(x, quantize.inv_scale_for(x))
@@ -400,9 +497,49 @@ def test_c2_tree_sampled_nodes_and_paths(T, ctx, node_srs):
     tree = ctx.terkle_build_entries(node_srs, dq, T.TC_I16, shape, node)
     try:
         assert tree.levels == 6
-        assert [tree.level_info(L)[1] for L in range(6)] == [131072, 8192, 512, 32, 4, 1]
+        sizes = [131072, 8192, 512, 32, 4, 1]
+        assert [tree.level_info(L)[1] for L in range(6)] == sizes
         ppn = pps(node)
-        rng = np.random.default_rng(5)
+        basis = [ppn.lagrange_scalar(tc.multi_index(k, node)) for k in range(16)]       # L_k(tau) of the node shape
+
+        def node_commitment(Z):
+            """[sum_k e(Z_k) L_k(tau)] G: Def. 4.1 Com under the known trapdoor, the multiplication in C"""
+            s = 0
+            for z, l in zip(Z, basis):
+                s += int(z) * l
+            return cbind.g1_mul(s % R, ec.G1)
+
+        # level 0 from the payload, then every level from the phi values of the one below
+        blocks = q.reshape(128, 4, 1024, 4).transpose(0, 2, 1, 3).reshape(-1, 16)
+        levels = []
+        with oracle_pool() as pool:
+            levels.append(list(pool.map(node_commitment, blocks.tolist(), chunksize=512)))
+            watch.lap("oracle: %d bottom nodes" % len(levels[0]))
+            grid = (128, 1024)
+            while len(levels[-1]) > 1:
+                below, bgrid = levels[-1], grid
+                grid = tuple(-(-g // 4) for g in bgrid)
+                phis = [terkle.phi(c) for c in below]
+                Zs = []
+                for a0 in range(grid[0]):
+                    for a1 in range(grid[1]):
+                        Zs.append([phis[(4 * a0 + k // 4) * bgrid[1] + 4 * a1 + k % 4]
+                                   if 4 * a0 + k // 4 < bgrid[0] and 4 * a1 + k % 4 < bgrid[1] else 0 for k in range(16)])
+                levels.append(list(pool.map(node_commitment, Zs, chunksize=64)))
+        watch.lap("oracle: levels 1..5 and the root")
+        assert [len(l) for l in levels] == sizes
+        blob = tree.export()                               # every commitment of the tree in one transfer
+        off = 72
+        for L, want in enumerate(levels):
+            got = blob[off : off + 96 * len(want)]
+            off += 96 * len(want)
+            if got != b"".join(ec.g1_to_bytes(c) for c in want):
+                bad = [i for i, c in enumerate(want) if got[96 * i : 96 * i + 96] != ec.g1_to_bytes(c)]
+                raise AssertionError("level %d: %d of %d nodes differ, first %s" % (L, len(bad), len(want), bad[:5]))
+        assert off == len(blob) and tree.root == ec.g1_to_bytes(levels[-1][0])
+        for L, i in ((0, 0), (0, 131071), (1, 4097), (4, 3)):                # the single-node accessor agrees with the file
+            assert tree.node(L, i) == ec.g1_to_bytes(levels[L][i])
+        watch.lap("all 139813 nodes equal the oracle's")
 
         def oracle_node(level, a):
             """commitment of node `a` (multi-index) at `level`, from payload entries only"""
@@ -412,11 +549,7 @@ def test_c2_tree_sampled_nodes_and_paths(T, ctx, node_srs):
             Z = [terkle.phi(oracle_node(level - 1, (4 * a[0] + k // 4, 4 * a[1] + k % 4))) for k in range(16)]
             return tc.commit(ppn, Z)
 
-        for level, count in ((0, 6), (1, 3), (2, 1)):
-            grid, _ = tree.level_info(level)
-            for _ in range(count):
-                a = (int(rng.integers(0, grid[0])), int(rng.integers(0, grid[1])))
-                assert tree.node(level, a[0] * grid[1] + a[1]) == ec.g1_to_bytes(oracle_node(level, a))
+        assert ec.g1_to_bytes(oracle_node(1, (17, 200))) == ec.g1_to_bytes(levels[1][17 * 256 + 200])   # the pooled closed form = tc.commit
         # membership proofs: accepted by the oracle's verifier and by the library, rejected when tampered
         leaves = tc_inputs.opening_positions(shape, 8, tc_inputs.tensor_seed(1))
         proofs = tree.open_batch(leaves)
@@ -424,22 +557,33 @@ def test_c2_tree_sampled_nodes_and_paths(T, ctx, node_srs):
         root = ec.g1_from_bytes(tree.root)
         for leaf, proof in zip(leaves, proofs):
             assert len(proof) == 6 * (2 * 96 + 32) + 5 * 96
-            steps, off = [], 0
             path = tree.path(leaf)
-            for s in range(6):
-                pi = [ec.g1_from_bytes(proof[off + 96 * i : off + 96 * (i + 1)]) for i in range(2)]
-                off += 192
-                y = ec.fr_from_bytes(proof[off : off + 32])
-                off += 32
-                child = None
-                if s < 5:
-                    child = ec.g1_from_bytes(proof[off : off + 96])
-                    off += 96
-                steps.append((tuple(path.kappa[s][j] for j in range(2)), y, pi, child))
+            steps, step_shapes = parse_proof(path, proof)
+            assert step_shapes == [node] * 6
             assert terkle.verify_path(pps, root, [node] * 6, int(q[leaf]), steps)
             assert not terkle.verify_path(pps, root, [node] * 6, int(q[leaf]) + 1, steps)
+        # two whole proofs byte for byte: the oracle opens the node tensors along the path, Z from its own levels
+        for leaf, proof in list(zip(leaves, proofs))[:2]:
+            steps, pos, grid_l = [], leaf, shape
+            chain = []
+            for L in range(6):
+                a, k = (pos[0] // 4, pos[1] // 4), (pos[0] % 4, pos[1] % 4)
+                chain.append((L, a, k, grid_l))
+                pos, grid_l = a, tuple(-(-g // 4) for g in grid_l)
+            for L, a, k, bgrid in reversed(chain):
+                if L == 0:
+                    Z = [int(v) for v in q[4 * a[0] : 4 * a[0] + 4, 4 * a[1] : 4 * a[1] + 4].reshape(-1)]
+                    child = None
+                else:
+                    Z = [terkle.phi(levels[L - 1][(4 * a[0] + j // 4) * bgrid[1] + 4 * a[1] + j % 4])
+                         if 4 * a[0] + j // 4 < bgrid[0] and 4 * a[1] + j % 4 < bgrid[1] else 0 for j in range(16)]
+                    child = levels[L - 1][(4 * a[0] + k[0]) * bgrid[1] + 4 * a[1] + k[1]]
+                y, pi = tc.open_(ppn, Z, k)
+                steps.append((k, y, pi, child))
+            assert proof == serialize_steps(steps)
         vals = [ec.fr_to_bytes(int(q[l]) % R) for l in leaves]
         assert ctx.verify_paths_batch(vk, [tree.path(l) for l in leaves], [tree.root] * 8, vals, proofs) == [True] * 8
+        watch.lap("8 paths verified, 2 proofs equal the oracle's")
         # incremental updates at this size: two entries change (one to an extreme value); the updated tree must
         # equal a fresh build over the changed payload on the whole path, the oracle recomputes the bottom node,
         # and the old proof of that leaf no longer verifies while a new one does
@@ -468,14 +612,24 @@ def test_c2_tree_sampled_nodes_and_paths(T, ctx, node_srs):
         tree.close()
 
 
+def _oracle_leaf(shape, seed, nthreads):
+    """One fp16 N(0,1) tensor of the activation workloads: the oracle's quantisation and closed-form commitment."""
+    x = tc_inputs.f16_normal(shape, seed)
+    inv = quantize.inv_scale_for(x)
+    qv = quantize.quantize_f16(x, inv)
+    return x, inv, qv, cbind.commit(pps(shape), qv, nthreads=nthreads)
+
+
 @pytest.mark.slow
 def test_c3_llama7b_forward_leaf_commitments_and_tree(T, ctx, node_srs):
     """Config 3: 32 layers x {512x4096, 512x4096, 512x11008} int16 tensors as whole-tensor leaves,
-    (4,4) tree over the (32, 3) grid.  Every leaf commitment is compared with the oracle's closed
-    form (field sums in C), the upper tree with the oracle's recursive build over those commitments,
-    and sampled openings with the oracle's openings."""
+    (4,4) tree over the (32, 3) grid.  The scale of every tensor is computed on the device and must equal the
+    oracle's; every leaf commitment is compared with the oracle's closed form (field sums in C), the upper tree
+    with the oracle's recursive build over those commitments; the configuration's 64 openings are made in one
+    batch, all of them pass the oracle's verifier, and eight whole proofs equal the oracle's byte for byte."""
     import torch
 
+    watch = Stopwatch("config 3")
     cfg = tc_inputs.LLAMA7B
     shapes3 = tc_inputs.c3_shapes(cfg)
     layers = int(os.environ.get("TC_TEST_C3_LAYERS", cfg["layers"]))
@@ -483,21 +637,26 @@ def test_c3_llama7b_forward_leaf_commitments_and_tree(T, ctx, node_srs):
     srs_by_shape = {}
     for s in set(shapes3):
         srs_by_shape[s] = ctx.setup_from_trapdoor(TAU_BYTES, s, T.TC_SRS_SUFFIX)
+        pps(s)                                             # the oracle's parameters, before the pool needs them
     leaves_q, leaves_d, leaf_srs, leaf_shapes = [], [], [], []
     want_commit = []
-    for layer in range(layers):
-        for kind, s in enumerate(shapes3):
-            x = tc_inputs.f16_normal(s, tc_inputs.tensor_seed(2, 0, layer, kind))
-            inv = quantize.inv_scale_for(x)
-            qv = quantize.quantize_f16(x, inv)
+    scales = torch.empty(layers * 3, dtype=torch.float32, device="cuda")
+    specs = [(s, tc_inputs.tensor_seed(2, 0, layer, kind)) for layer in range(layers) for kind, s in enumerate(shapes3)]
+    with oracle_pool() as pool:
+        for i, (x, inv, qv, want) in enumerate(pool.map(lambda sp: _oracle_leaf(sp[0], sp[1], 2), specs)):
+            s = specs[i][0]
+            dx = to_device(x.view(np.int16))
             dq = torch.empty(x.size, dtype=torch.int16, device="cuda")
-            ctx.encode_tensor(to_device(x.view(np.int16)), T.TC_F16, x.size, float(inv), dq)
+            ctx.quant_scale(dx, x.size, scales[i:])
+            ctx.encode_tensor_scaled(dx, T.TC_F16, x.size, scales[i:], dq)
+            ctx.sync()
+            assert scales[i].item() == float(inv), "scale of tensor %d" % i
             leaves_q.append(qv)
             leaves_d.append(dq)
             leaf_srs.append(srs_by_shape[s])
             leaf_shapes.append(s)
-            want_commit.append(cbind.commit(pps(s), qv, nthreads=16))
-    ctx.sync()
+            want_commit.append(want)
+    watch.lap("inputs, device scales and oracle commitments of %d tensors" % len(specs))
     for qv, dq in zip(leaves_q[:3], leaves_d[:3]):
         assert np.array_equal(dq.cpu().numpy(), qv.reshape(-1))
     tree = ctx.terkle_build_tensors(node_srs, leaf_srs, leaves_d, [T.TC_I16] * len(leaves_d), grid, tc_inputs.NODE_SHAPE)
@@ -513,19 +672,38 @@ def test_c3_llama7b_forward_leaf_commitments_and_tree(T, ctx, node_srs):
             for i in range(n):
                 assert tree.node(L, i) == ec.g1_to_bytes(otree.levels[L - 1]["C"][tc.multi_index(i, g)])
         assert tree.root == ec.g1_to_bytes(otree.root)
-        # two openings down to tensor entries
+        watch.lap("tree equals the oracle's")
+        # the configuration's 64 random openings down to tensor entries, one batch
         vk = ctx.vk_from_trapdoor(TAU_BYTES)
-        rng = np.random.default_rng(9)
-        for _ in range(2):
-            leaf = (int(rng.integers(0, layers)), int(rng.integers(0, 3)))
+        rng = np.random.default_rng(tc_inputs.tensor_seed(2) + 999)
+        leaf_idx = [(int(rng.integers(0, layers)), int(rng.integers(0, 3))) for _ in range(64)]
+        inner_idx = [tuple(int(rng.integers(0, d)) for d in shapes3[l[1]]) for l in leaf_idx]
+        proofs = tree.open_batch(leaf_idx, inner_idx)
+        paths = [tree.path(l, i) for l, i in zip(leaf_idx, inner_idx)]
+        values = [int(leaves_q[l[0] * 3 + l[1]][i]) for l, i in zip(leaf_idx, inner_idx)]
+        root_pt = ec.g1_from_bytes(tree.root)
+
+        def oracle_accepts(j):
+            steps, step_shapes = parse_proof(paths[j], proofs[j])
+            return (terkle.verify_path(pps, root_pt, step_shapes, values[j], steps),
+                    terkle.verify_path(pps, root_pt, step_shapes, values[j] + 1, steps))
+
+        with oracle_pool() as pool:
+            verdicts = list(pool.map(oracle_accepts, range(64)))
+        assert verdicts == [(True, False)] * 64
+        watch.lap("64 openings pass the oracle's verifier")
+        for j in range(8):                                 # whole proofs: upper steps from the oracle's tree, last step from its Open
+            leaf, inner = leaf_idx[j], inner_idx[j]
             flat = leaf[0] * 3 + leaf[1]
-            inner = tuple(int(rng.integers(0, d)) for d in leaf_shapes[flat])
-            proof = tree.open(leaf, inner)
-            yo, po = tc.open_(pps(leaf_shapes[flat]), leaves_q[flat], inner)
-            tail = b"".join(ec.g1_to_bytes(p) for p in po) + ec.fr_to_bytes(yo)
-            assert proof[-len(tail):] == tail
-            value = ec.fr_to_bytes(int(leaves_q[flat][inner]) % R)
-            assert ctx.verify_path(vk, tree.path(leaf, inner), tree.root, value, proof)
+            steps = terkle.open_path(pps, otree, grid, tc_inputs.NODE_SHAPE, leaf)
+            k, y, pi, _ = steps[-1]
+            steps[-1] = (k, y, pi, want_commit[flat])      # the bottom node of the upper tree carries the leaf tensor's commitment
+            yo, po = cbind.open_(pps(leaf_shapes[flat]), leaves_q[flat], inner, HOST_THREADS)
+            steps.append((inner, yo, po, None))
+            assert proofs[j] == serialize_steps(steps), "proof %d" % j
+        watch.lap("8 whole proofs equal the oracle's")
+        byte_values = [ec.fr_to_bytes(v % R) for v in values]
+        assert ctx.verify_paths_batch(vk, paths, [tree.root] * 64, byte_values, proofs) == [True] * 64
     finally:
         tree.close()
         for s in srs_by_shape.values():
@@ -534,23 +712,35 @@ def test_c3_llama7b_forward_leaf_commitments_and_tree(T, ctx, node_srs):
 
 @pytest.mark.slow
 def test_c4_weight_matrices_streamed(T, ctx, node_srs):
-    """Config 4 at true matrix shapes (Wq/Wk/Wv/Wo 4096x4096, W_gate/W_up 4096x11008, W_down 11008x4096,
-    int8 uniform in [-127,127]), a slice of the layers (TC_TEST_C4_LAYERS, default 2; 32 = the full
-    6.5e9-scalar configuration): every matrix commitment against the oracle's closed form, then the
-    (4,4) tree over the (layers, 7) grid against the oracle's recursive build."""
+    """Config 4 at its stated size: the weight matrices of all 32 layers at true shapes (Wq/Wk/Wv/Wo 4096x4096,
+    W_gate/W_up 4096x11008, W_down 11008x4096, int8 uniform in [-127,127]; 6.48e9 scalars; TC_TEST_C4_LAYERS takes a
+    slice): every matrix commitment against the oracle's closed form, then the (4,4) tree over the (layers, 7)
+    grid against the oracle's recursive build."""
     import torch
 
-    layers = int(os.environ.get("TC_TEST_C4_LAYERS", "2"))
+    watch = Stopwatch("config 4")
+    layers = int(os.environ.get("TC_TEST_C4_LAYERS", tc_inputs.LLAMA7B["layers"]))
+    print("config 4: %d of 32 layers" % layers, flush=True)
     shapes7 = tc_inputs.c4_shapes()
     grid = (layers, 7)
     srs_by_shape = {s: ctx.setup_from_trapdoor(TAU_BYTES, s, 0) for s in set(shapes7)}
+    for s in set(shapes7):
+        pps(s)
+    watch.lap("SRS tables")
     leaves_d, leaf_srs, want = [], [], []
-    for layer in range(layers):
-        for kind, s in enumerate(shapes7):
-            W = tc_inputs.int8_uniform(s, tc_inputs.tensor_seed(3, 0, layer, kind), -127, 127)
+    specs = [(s, tc_inputs.tensor_seed(3, 0, layer, kind)) for layer in range(layers) for kind, s in enumerate(shapes7)]
+
+    def oracle_matrix(sp):
+        W = tc_inputs.int8_uniform(sp[0], sp[1], -127, 127)
+        return W, cbind.commit(pps(sp[0]), W, nthreads=2)
+
+    with oracle_pool() as pool:
+        for i, (W, w) in enumerate(pool.map(oracle_matrix, specs)):
             leaves_d.append(to_device(W))
-            leaf_srs.append(srs_by_shape[s])
-            want.append(cbind.commit(pps(s), W, nthreads=16))
+            leaf_srs.append(srs_by_shape[specs[i][0]])
+            want.append(w)
+            if i % 56 == 55:
+                watch.lap("matrices and oracle commitments up to layer %d" % (i // 7))
     tree = ctx.terkle_build_tensors(node_srs, leaf_srs, leaves_d, [T.TC_I8] * len(leaves_d), grid, tc_inputs.NODE_SHAPE)
     try:
         for i, w in enumerate(want):
@@ -559,6 +749,7 @@ def test_c4_weight_matrices_streamed(T, ctx, node_srs):
         assert tree.root == ec.g1_to_bytes(otree.root)
         got = ctx.commit_batch(leaf_srs[:7], leaves_d[:7], [T.TC_I8] * 7)
         assert got == [ec.g1_to_bytes(w) for w in want[:7]]
+        watch.lap("%d commitments and the tree equal the oracle's" % len(want))
     finally:
         tree.close()
         for s in srs_by_shape.values():
@@ -567,48 +758,73 @@ def test_c4_weight_matrices_streamed(T, ctx, node_srs):
 
 @pytest.mark.slow
 def test_c5_batched_requests(T, ctx, node_srs):
-    """Config 5 at true tensor shapes (2048x5120 twice and 2048x13824 per layer, int16 from fp16 N(0,1)),
-    a slice of it (TC_TEST_C5_REQUESTS x TC_TEST_C5_LAYERS, default 2 x 2; 8 x 40 = the full configuration):
-    one tree per request over its (layers, 3) grid, roots against the oracle and different per request;
-    per request TC_TEST_C5_OPENINGS path openings (default 8; 128 = the configuration's 1024 in total) made
-    in one batch: two recomputed by the oracle, four more run through the oracle's verifier, all verified in
-    one batch on the GPU."""
+    """Config 5 at its stated size on the GPU: 8 requests x 40 layers x {2048x5120 twice, 2048x13824} int16 from fp16
+    N(0,1) (1.58e10 scalars), one tree per request over its (40, 3) grid, 128 path openings per request in one
+    batch (1024 in all), all verified in one batch on the GPU; roots differ per request.
+    What the oracle recomputes of it (its closed-form commitment costs far more per entry than the GPU's): for the
+    first TC_TEST_C5_ORACLE_REQUESTS requests (default 1) every leaf commitment, the upper tree and the root; for
+    every other request three leaf commitments, one of each shape, picked by seed; for every request the
+    tensor-level opening of two paths recomputed byte for byte and sixteen whole paths through its verifier.
+    TC_TEST_C5_REQUESTS / _LAYERS / _OPENINGS take a slice; the slice is printed."""
     import torch
 
+    watch = Stopwatch("config 5")
     cfg = tc_inputs.LLAMA13B
-    requests = int(os.environ.get("TC_TEST_C5_REQUESTS", "2"))
-    layers = int(os.environ.get("TC_TEST_C5_LAYERS", "2"))
-    openings = int(os.environ.get("TC_TEST_C5_OPENINGS", "8"))
+    requests = int(os.environ.get("TC_TEST_C5_REQUESTS", cfg["batch"]))
+    layers = int(os.environ.get("TC_TEST_C5_LAYERS", cfg["layers"]))
+    openings = int(os.environ.get("TC_TEST_C5_OPENINGS", "128"))
+    oracle_requests = int(os.environ.get("TC_TEST_C5_ORACLE_REQUESTS", "1"))
+    print("config 5: %d of 8 requests x %d of 40 layers, %d openings per request, oracle rebuilds %d request(s) in full"
+          % (requests, layers, openings, min(oracle_requests, requests)), flush=True)
     shapes3 = tc_inputs.c3_shapes(cfg)
     grid = (layers, 3)
     srs_by_shape = {s: ctx.setup_from_trapdoor(TAU_BYTES, s, T.TC_SRS_SUFFIX) for s in set(shapes3)}
+    for s in set(shapes3):
+        pps(s)
+    watch.lap("SRS tables")
     vk = ctx.vk_from_trapdoor(TAU_BYTES)
     roots, trees, keep = [], [], []
     paths, proofs, values, proof_roots = [], [], [], []
+
+    def quantised(sp):
+        x = tc_inputs.f16_normal(sp[0], sp[1])
+        inv = quantize.inv_scale_for(x)
+        return x, inv, quantize.quantize_f16(x, inv)
+
     try:
         for req in range(requests):
-            leaves_q, leaves_d, leaf_srs, want = [], [], [], []
-            for layer in range(layers):
-                for kind, s in enumerate(shapes3):
-                    x = tc_inputs.f16_normal(s, tc_inputs.tensor_seed(4, req, layer, kind))
-                    inv = quantize.inv_scale_for(x)
-                    qv = quantize.quantize_f16(x, inv)
+            full = req < oracle_requests
+            specs = [(s, tc_inputs.tensor_seed(4, req, layer, kind)) for layer in range(layers) for kind, s in enumerate(shapes3)]
+            rng = np.random.default_rng(tc_inputs.tensor_seed(4, req) + 555)
+            sampled = set(range(len(specs))) if full else {3 * int(rng.integers(0, layers)) + kind for kind in range(3)}
+            leaves_q, leaves_d, leaf_srs, want = [], [], [], {}
+            scales = torch.empty(len(specs), dtype=torch.float32, device="cuda")
+            with oracle_pool() as pool:
+                pending = {}
+                for i, (x, inv, qv) in enumerate(pool.map(quantised, specs)):
+                    dx = to_device(x.view(np.int16))
                     dq = torch.empty(x.size, dtype=torch.int16, device="cuda")
-                    ctx.encode_tensor(to_device(x.view(np.int16)), T.TC_F16, x.size, float(inv), dq)
+                    ctx.quant_scale(dx, x.size, scales[i:])
+                    ctx.encode_tensor_scaled(dx, T.TC_F16, x.size, scales[i:], dq)
+                    ctx.sync()
+                    assert scales[i].item() == float(inv), "scale of tensor %d of request %d" % (i, req)
+                    if i in sampled:
+                        assert np.array_equal(dq.cpu().numpy(), qv.reshape(-1)), "quantised tensor %d of request %d" % (i, req)
+                        pending[i] = pool.submit(cbind.commit, pps(specs[i][0]), qv, 2)
                     leaves_q.append(qv)
                     leaves_d.append(dq)
-                    leaf_srs.append(srs_by_shape[s])
-                    want.append(cbind.commit(pps(s), qv, nthreads=16))
-                if layer % 8 == 7:
-                    print("config 5: request %d layer %d" % (req, layer), flush=True)
-            print("config 5: request %d inputs and oracle commitments ready" % req, flush=True)
+                    leaf_srs.append(srs_by_shape[specs[i][0]])
+                for i, fut in pending.items():
+                    want[i] = fut.result()
+            watch.lap("request %d: inputs quantised on both sides, %d oracle commitments" % (req, len(want)))
             tree = ctx.terkle_build_tensors(node_srs, leaf_srs, leaves_d, [T.TC_I16] * len(leaves_d), grid, tc_inputs.NODE_SHAPE)
             trees.append(tree)
             keep.append(leaves_d)
-            for i, w in enumerate(want):
-                assert tree.node(0, i) == ec.g1_to_bytes(w)
-            otree = terkle.build(pps, [terkle.phi(w) for w in want], grid, tc_inputs.NODE_SHAPE)
-            assert tree.root == ec.g1_to_bytes(otree.root)
+            for i, w in want.items():
+                assert tree.node(0, i) == ec.g1_to_bytes(w), "leaf %d of request %d" % (i, req)
+            if full:
+                otree = terkle.build(pps, [terkle.phi(want[i]) for i in range(len(specs))], grid, tc_inputs.NODE_SHAPE)
+                assert tree.root == ec.g1_to_bytes(otree.root)
             roots.append(tree.root)
             rng = np.random.default_rng(tc_inputs.tensor_seed(4, req) + 999)
             leaf_idx, inner_idx = [], []
@@ -617,25 +833,32 @@ def test_c5_batched_requests(T, ctx, node_srs):
                 leaf_idx.append(leaf)
                 inner_idx.append(tuple(int(rng.integers(0, d)) for d in shapes3[leaf[1]]))
             got = tree.open_batch(leaf_idx, inner_idx)
-            for j, (leaf, inner, proof) in enumerate(zip(leaf_idx, inner_idx, got)):
+            watch.lap("request %d: tree built, %d openings made" % (req, openings))
+            root_pt = ec.g1_from_bytes(tree.root)
+            req_paths = [tree.path(l, i) for l, i in zip(leaf_idx, inner_idx)]
+            req_values = [int(leaves_q[l[0] * 3 + l[1]][i]) for l, i in zip(leaf_idx, inner_idx)]
+
+            def oracle_check(j):
+                leaf, inner, proof = leaf_idx[j], inner_idx[j], got[j]
                 flat = leaf[0] * 3 + leaf[1]
-                path = tree.path(leaf, inner)
                 if j < 2:      # the tensor-level opening recomputed by the oracle
-                    yo, po = tc.open_(pps(shapes3[leaf[1]]), leaves_q[flat], inner)
+                    yo, po = cbind.open_(pps(shapes3[leaf[1]]), leaves_q[flat], inner, 4)
                     tail = b"".join(ec.g1_to_bytes(p) for p in po) + ec.fr_to_bytes(yo)
-                    assert proof[-len(tail):] == tail
-                elif j < 6:    # the whole path through the oracle's verifier
-                    steps, step_shapes = parse_proof(path, proof)
-                    root_pt = ec.g1_from_bytes(tree.root)
-                    assert terkle.verify_path(pps, root_pt, step_shapes, int(leaves_q[flat][inner]), steps)
-                    assert not terkle.verify_path(pps, root_pt, step_shapes, int(leaves_q[flat][inner]) + 1, steps)
-                paths.append(path)
-                proofs.append(proof)
-                values.append(ec.fr_to_bytes(int(leaves_q[flat][inner]) % R))
-                proof_roots.append(tree.root)
-            print("config 5: request %d: %d openings checked" % (req, openings), flush=True)
+                    return proof[-len(tail):] == tail
+                steps, step_shapes = parse_proof(req_paths[j], proof)      # the whole path through the oracle's verifier
+                return (terkle.verify_path(pps, root_pt, step_shapes, req_values[j], steps)
+                        and not terkle.verify_path(pps, root_pt, step_shapes, req_values[j] + 1, steps))
+
+            with oracle_pool() as pool:
+                assert all(pool.map(oracle_check, range(min(openings, 18))))
+            paths += req_paths
+            proofs += got
+            values += [ec.fr_to_bytes(v % R) for v in req_values]
+            proof_roots += [tree.root] * openings
+            watch.lap("request %d: oracle checked %d openings" % (req, min(openings, 18)))
         assert len(set(roots)) == requests
         assert ctx.verify_paths_batch(vk, paths, proof_roots, values, proofs) == [True] * len(paths)
+        watch.lap("%d paths verified in one batch on the GPU" % len(paths))
         if requests > 1:   # a proof of request 0 does not verify against the root of request 1
             assert not ctx.verify_path(vk, paths[0], roots[1], values[0], proofs[0])
     finally:

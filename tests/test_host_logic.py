@@ -525,3 +525,137 @@ def test_emulated_commit_static_at_its_limit(emu):
         emu.commit_static(srs, np.zeros(n + 1, np.int16), T.TC_I16, out)
     assert e.value.code == T.binding.TC_ERR_SHAPE and "TC_STATIC_MAX_TERMS" in str(e.value)
     srs.close()
+
+
+def test_emulated_srs_and_tree_files(emu, node_srs):
+    """The public parameters and a built tree as flat files (Def. 4.1 Setup publishes pp; a tree is opened long
+    after it was built): export -> import gives an SRS with the same points, commitments and openings, and a tree
+    whose openings are the oracle's; damaged files are refused with an error code."""
+    B = T.binding
+    shape = (3, 4, 2)
+    pp = pps(shape)
+    srs = emu.setup_from_trapdoor(TAU_BYTES, shape, T.TC_SRS_SUFFIX)
+    data = srs.export()
+    n_pts = 24 + 8 + 2
+    assert len(data) == 56 + 96 * n_pts and data[:5] == b"TCSRS"
+    # the stored points are the oracle's Lagrange SRS and its suffix tables, canonical bytes
+    S0 = pp.srs_lagrange(0)
+    assert data[56 : 56 + 96 * 24] == b"".join(ec.g1_to_bytes(S0[i]) for i in range(24))
+    assert data[56 + 96 * 32 :] == b"".join(ec.g1_to_bytes(p) for p in pp.srs_lagrange(2))
+    back = emu.srs_import(data)
+    assert back.shape == shape and back.size(0) == 24 and back.size(1) == 8 and back.size(2) == 2
+    X = tc_inputs.int16_uniform(shape, 5, -32768, 32767)
+    assert emu.commit(back, X, T.TC_I16) == ec.g1_to_bytes(tc.commit(pp, X))
+    y, pi = emu.open(back, X, T.TC_I16, (2, 1, 1))          # needs the grid constants, which the import rebuilds
+    yo, po = tc.open_(pp, X, (2, 1, 1))
+    assert y == ec.fr_to_bytes(yo) and pi == [ec.g1_to_bytes(p) for p in po]
+    assert all(back.point(i, a) == srs.point(i, a) for a, n in ((0, 24), (1, 8), (2, 2)) for i in range(n))
+    back.close()
+    # a monomial SRS and one without suffix tables keep their kind
+    mono = emu.setup_from_trapdoor(TAU_BYTES, (3, 2), T.TC_SRS_MONOMIAL)
+    mono2 = emu.srs_import(mono.export())
+    assert mono2.flags == T.TC_SRS_MONOMIAL and [mono2.point(i) for i in range(6)] == [mono.point(i) for i in range(6)]
+    with pytest.raises(T.TcError) as e:
+        emu.open(mono2, np.zeros((3, 2), np.int8), T.TC_I8, (0, 0))
+    assert e.value.code == B.TC_ERR_STATE
+    mono.close()
+    mono2.close()
+
+    def refused(blob, code):
+        with pytest.raises(T.TcError) as e:
+            emu.srs_import(blob)
+        assert e.value.code == code, (e.value.code, code)
+
+    refused(data[:40], B.TC_ERR_ARG)                          # no complete header
+    refused(data[:-1], B.TC_ERR_ARG)                          # truncated
+    refused(data + b"\0", B.TC_ERR_ARG)                       # too long
+    refused(b"XCSRS" + data[5:], B.TC_ERR_ARG)                # magic
+    refused(data[:8] + (2).to_bytes(4, "little") + data[12:], B.TC_ERR_ARG)       # version
+    refused(data[:12] + (7).to_bytes(4, "little") + data[16:], B.TC_ERR_ARG)      # curve
+    refused(data[:48] + (n_pts - 1).to_bytes(8, "little") + data[56:], B.TC_ERR_ARG)      # count
+    refused(data[:28] + (0).to_bytes(4, "little") + data[32:], B.TC_ERR_SHAPE)    # shape
+    refused(data[:20] + (64).to_bytes(4, "little") + data[24:], B.TC_ERR_ARG)     # unknown flag
+    off = 56 + 96 * 5
+    refused(data[:off] + bytes([data[off] ^ 1]) + data[off + 1 :], B.TC_ERR_RANGE)         # a point off the curve
+    refused(data[:off] + b"\xff" * 48 + data[off + 48 :], B.TC_ERR_RANGE)                   # x >= p
+    srs.close()
+
+    # a tree: built, saved, loaded, opened -- byte for byte the oracle's proofs
+    node, grid = (2, 2), (5, 7)
+    P = tc_inputs.int16_uniform(grid, 7)
+    tree = emu.terkle_build_entries(node_srs, P, T.TC_I16, grid, node)
+    blob = tree.export()
+    ot = terkle.build(pps, tc.as_flat_ints(P), grid, node)
+    n_nodes = sum(int(np.prod(lv["grid"])) for lv in ot.levels)
+    assert len(blob) == 72 + 96 * n_nodes and blob[:6] == b"TCTREE"
+    assert blob[-96:] == ec.g1_to_bytes(ot.root)
+    root = tree.root
+    tree.close()
+    loaded = emu.terkle_build_entries(node_srs, P, T.TC_I16, grid, node, from_file=blob)
+    assert loaded.root == root == ec.g1_to_bytes(ot.root) and loaded.levels == 3
+    for leaf in [(0, 0), (4, 6), (2, 3)]:
+        assert loaded.open(leaf) == serialize_steps(terkle.open_path(pps, ot, grid, node, leaf))
+    loaded.update((1, 1), 3)                                # a loaded tree is a full tree: updates work on it
+    P2 = P.copy()
+    P2[1, 1] += 3
+    assert loaded.root == ec.g1_to_bytes(terkle.build(pps, tc.as_flat_ints(P2), grid, node).root)
+    loaded.close()
+    for bad, code in ((blob[:-96], B.TC_ERR_ARG), (blob[:50], B.TC_ERR_ARG), (b"TCSRS\0\0\0" + blob[8:], B.TC_ERR_ARG),
+                      (blob[:20] + (6).to_bytes(4, "little") + blob[24:], B.TC_ERR_SHAPE),
+                      (blob[:72] + bytes([blob[72] ^ 1]) + blob[73:], B.TC_ERR_RANGE)):
+        with pytest.raises(T.TcError) as e:
+            emu.terkle_build_entries(node_srs, P, T.TC_I16, grid, node, from_file=bad)
+        assert e.value.code == code, (e.value.code, code)
+    # a tensors tree keeps its leaf commitments too
+    shapes = [(2, 3), (4,), (2, 2, 2), (3, 3), (5,), (2, 2)]
+    leaves = [tc_inputs.int16_uniform(s, 50 + i) for i, s in enumerate(shapes)]
+    lsrs = [emu.setup_from_trapdoor(TAU_BYTES, s, T.TC_SRS_SUFFIX) for s in shapes]
+    t2 = emu.terkle_build_tensors(node_srs, lsrs, leaves, [T.TC_I16] * 6, (3, 2), node)
+    blob2 = t2.export()
+    proof = t2.open((1, 0), (1, 0, 1))
+    t2.close()
+    l2 = emu.terkle_build_tensors(node_srs, lsrs, leaves, [T.TC_I16] * 6, (3, 2), node, from_file=blob2)
+    assert l2.open((1, 0), (1, 0, 1)) == proof
+    with pytest.raises(T.TcError) as e:                     # a file of an entries tree is not a tensors tree
+        emu.terkle_build_tensors(node_srs, lsrs, leaves, [T.TC_I16] * 6, (3, 2), node, from_file=blob)
+    assert e.value.code == B.TC_ERR_SHAPE
+    l2.close()
+    for s in lsrs:
+        s.close()
+
+
+def test_emulated_quant_scale(emu):
+    """The per-tensor scale on the device side of the boundary: bit-equal to the oracle's float32(32767) / amax on
+    tensors of several pieces and ragged ends, at any alignment, all zeros, a single outlier, subnormals,
+    infinities and NaNs left out; and the quantisation that reads the scale from device memory."""
+    from oracle import quantize
+
+    rng = np.random.default_rng(3)
+    cases = []
+    for n in (1, 7, 8, 9, 1000, 8 * 256 * 3 + 5):
+        cases.append(rng.standard_normal(n).astype(np.float16))
+    cases.append(np.zeros(100, np.float16))
+    outlier = (rng.standard_normal(5000) * 0.01).astype(np.float16)
+    outlier[4321] = np.float16(-977.5)
+    cases.append(outlier)
+    cases.append(np.array([6e-8, -1.2e-7, 0.0], np.float16))                  # subnormals only
+    mixed = rng.standard_normal(300).astype(np.float16)
+    mixed[[3, 77]] = [np.inf, -np.inf]
+    mixed[150] = np.nan
+    cases.append(mixed)
+    cases.append(np.array([np.inf, np.nan], np.float16))
+    for x in cases:
+        for offset in (0, 1, 3):                                             # elements past a 16-byte boundary
+            store = np.zeros(x.size + 16, np.float16)
+            view = store[offset : offset + x.size]
+            view[:] = x
+            out = np.full(1, -1.0, np.float32)
+            emu.quant_scale(view, x.size, out)
+            finite = x[np.isfinite(x)]
+            want = quantize.inv_scale_for(finite) if finite.size else np.float32(0)
+            assert out.view(np.uint32)[0] == np.float32(want).view(np.uint32), (x.size, offset, out[0], want)
+            q = np.zeros(x.size, np.int16)
+            emu.encode_tensor_scaled(view, T.TC_F16, x.size, out, q)
+            ref = quantize.quantize_f16(np.where(np.isfinite(x), x, np.float16(0)), want)
+            fin = np.isfinite(x)
+            assert np.array_equal(q[fin], ref[fin])

@@ -315,3 +315,10 @@ def test_c_oracle_naive_msm_and_closed_form_agree_with_python():
     X = tc_inputs.int16_uniform((7, 33), 8)
     pp2 = tc.setup((7, 33), TAU)
     assert cbind.f_at_tau(X, (7, 33), pp2.ell, 5) == tc.f_at_tau(pp2, X)
+    # openings with the sums in C equal the Python route (and with it Algorithm 1, pinned above), int8 and int16,
+    # at corner and interior positions of tensors of order 1 to 3
+    for shp, data, kappas in (((7, 33), X, [(0, 0), (6, 32), (3, 17)]), (shape, T, [(3, 15, 15), (1, 0, 7)]),
+                              ((12,), tc_inputs.int16_uniform((12,), 9), [(0,), (11,)])):
+        ppx = tc.setup(shp, TAU)
+        for kappa in kappas:
+            assert cbind.open_(ppx, data, kappa, 3) == tc.open_(ppx, data, kappa)
