@@ -761,10 +761,10 @@ def test_c5_batched_requests(T, ctx, node_srs):
     """Config 5 at its stated size on the GPU: 8 requests x 40 layers x {2048x5120 twice, 2048x13824} int16 from fp16
     N(0,1) (1.58e10 scalars), one tree per request over its (40, 3) grid, 128 path openings per request in one
     batch (1024 in all), all verified in one batch on the GPU; roots differ per request.
-    What the oracle recomputes of it (its closed-form commitment costs far more per entry than the GPU's): for the
-    first TC_TEST_C5_ORACLE_REQUESTS requests (default 1) every leaf commitment, the upper tree and the root; for
-    every other request three leaf commitments, one of each shape, picked by seed; for every request the
-    tensor-level opening of two paths recomputed byte for byte and sixteen whole paths through its verifier.
+    The oracle recomputes every leaf commitment (closed form, field sums in C on all host cores), the upper tree and
+    the root of every request (TC_TEST_C5_ORACLE_REQUESTS, default all 8, limits that to the first requests; the
+    others then get three sampled leaf commitments, one of each shape, picked by seed); for every request the
+    tensor-level opening of two paths is recomputed byte for byte and sixteen whole paths go through its verifier.
     TC_TEST_C5_REQUESTS / _LAYERS / _OPENINGS take a slice; the slice is printed."""
     import torch
 
@@ -773,7 +773,7 @@ def test_c5_batched_requests(T, ctx, node_srs):
     requests = int(os.environ.get("TC_TEST_C5_REQUESTS", cfg["batch"]))
     layers = int(os.environ.get("TC_TEST_C5_LAYERS", cfg["layers"]))
     openings = int(os.environ.get("TC_TEST_C5_OPENINGS", "128"))
-    oracle_requests = int(os.environ.get("TC_TEST_C5_ORACLE_REQUESTS", "1"))
+    oracle_requests = int(os.environ.get("TC_TEST_C5_ORACLE_REQUESTS", cfg["batch"]))
     print("config 5: %d of 8 requests x %d of 40 layers, %d openings per request, oracle rebuilds %d request(s) in full"
           % (requests, layers, openings, min(oracle_requests, requests)), flush=True)
     shapes3 = tc_inputs.c3_shapes(cfg)
