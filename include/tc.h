@@ -113,6 +113,14 @@ int tc_ctx_profile_units(tc_ctx* ctx, int kind, uint64_t* units);
 #define TC_ALU_FP_SQR 3
 int tc_ctx_alu_rate(tc_ctx* ctx, int kind, int waves_per_simd, double* out_per_s);
 
+/* Test hook: one field operation per element on device arrays of raw limbs, little-endian 32-bit words, values
+ * below the modulus (12 words per Fp element, 8 per Fr element), the Montgomery representatives that the kernels
+ * keep in registers (radix R = 2^384 for Fp, 2^256 for Fr).  out[i] = op(a[i], b[i]), asynchronous on the context's
+ * stream:  0 a b / R (the integer product routine)   1 a^2 / R   2, 3 the same through the FP64 pipe
+ *          4 R^2 / a (inverse of a Montgomery representative, a != 0)   5 a b / R in Fr   6 a + b   7 a - b
+ *          8 R^2 / a in Fr.                      b is ignored by the one-operand operations but must be valid. */
+int tc_ctx_field_op(tc_ctx* ctx, int op, const void* d_a, const void* d_b, size_t n, void* d_out);
+
 /* ---- Setup (Def. 4.1, Setup) -- test-only trusted setup from a known trapdoor -- */
 
 #define TC_SRS_SUFFIX 1u     /* also build the suffix tables S^(a), a = 1..m-1, needed by tc_open */

@@ -389,25 +389,26 @@ def commit(pp, T):
 
 # --- Algorithm 1 (App. A): divide by (x_i - v) on the lexicographic array --------
 def divide_by_linear(a, shape, axis, v):
-    """Return (q, r) with f = q (x_axis - v) + r and r free of x_axis.
+    """Return (q, r) with f = q (x_axis - v) + r and r free of x_axis (the post-condition App. A states).
 
-    Works down from the top degree of x_axis: a coefficient at degree c is
-    moved one degree lower (times v) into the remainder and recorded at degree
-    c - 1 of the quotient."""
+    Seen along `axis`, the lexicographic array is a bundle of lines: fixing every other index leaves the
+    coefficients c_0 .. c_{d-1} of a univariate polynomial in x_axis whose coefficients are monomials in the other
+    variables, and dividing f by (x_axis - v) divides every line on its own.  One line, by the division of a
+    univariate polynomial by a monic linear factor: the quotient's top coefficient is c_{d-1}, every lower one is
+    q_{k-1} = c_k + v q_k, and what is left at degree 0 is the remainder c_0 + v q_0 = (the line's value at v)."""
     d = shape[axis]
     st = strides(shape)[axis]
     n = prod(shape)
-    r = [c % R for c in a]
     q = [0] * n
-    for c in range(d - 1, 0, -1):
-        for f in range(n):
-            if (f // st) % d != c:
-                continue
-            lower = f - st
-            coeff = r[f]
-            r[f] = 0
-            r[lower] = (r[lower] + v * coeff) % R
-            q[lower] = (q[lower] + coeff) % R
+    r = [0] * n
+    for base in range(n):
+        if (base // st) % d != 0:
+            continue                                  # `base` addresses degree 0 of a line; its degree k sits at base + k st
+        carry = 0                                     # q_k, starting above the top degree
+        for k in range(d - 1, 0, -1):
+            carry = (a[base + k * st] + v * carry) % R
+            q[base + (k - 1) * st] = carry
+        r[base] = (a[base] + v * carry) % R
     return q, r
 
 

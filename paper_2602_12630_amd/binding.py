@@ -81,6 +81,7 @@ def load_library(path=None):
                                                ctypes.POINTER(ctypes.c_uint64)]),
         "tc_ctx_profile_units": (ctypes.c_int, [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64)]),
         "tc_ctx_alu_rate": (ctypes.c_int, [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]),
+        "tc_ctx_field_op": (ctypes.c_int, [vp, ctypes.c_int, vp, vp, ctypes.c_size_t, vp]),
         "tc_setup_from_trapdoor": (ctypes.c_int, [vp, u8p, ctypes.c_int, u32p, ctypes.c_uint32, ctypes.POINTER(vp)]),
         "tc_srs_destroy": (None, [vp]),
         "tc_srs_size": (ctypes.c_uint64, [vp, ctypes.c_int]),
@@ -386,6 +387,9 @@ class Context:
         units = ctypes.c_uint64()
         self._check(self.lib.tc_ctx_profile_units(self.handle, kind, ctypes.byref(units)))
         return int(units.value)
+
+    def field_op(self, op, a, b, n, out):
+        self._check(self.lib.tc_ctx_field_op(self.handle, op, _ptr(a), _ptr(b), n, _ptr(out)))
 
     def alu_rate(self, kind, waves_per_simd):
         """multiply-adds/s (kinds 0, 1) or Fp products/s (kinds 2, 3) with that many waves on every SIMD"""

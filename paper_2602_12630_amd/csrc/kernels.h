@@ -42,6 +42,42 @@ struct PokeWords {
     TC_DEV void operator()(uint32_t t) const { dst[t] = w[t]; }
 };
 
+/* Test hook: one field operation per lane on raw limb arrays (Montgomery representatives as they sit in
+ * registers), so that the device forms of the arithmetic can be compared with big-integer arithmetic directly. */
+enum { FOP_FP_MUL = 0, FOP_FP_SQR = 1, FOP_FP_MUL_F64 = 2, FOP_FP_SQR_F64 = 3, FOP_FP_INV = 4, FOP_FR_MUL = 5,
+       FOP_FP_ADD = 6, FOP_FP_SUB = 7, FOP_FR_INV = 8, FOP_COUNT = 9 };
+struct FieldOp {
+    int op;
+    const uint32_t* a;      /* 12 limbs per element (8 for the Fr operations) */
+    const uint32_t* b;
+    uint32_t* out;
+    TC_DEV void operator()(uint32_t t) const {
+        if (op == FOP_FR_MUL || op == FOP_FR_INV) {
+            fr_t x, y;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { x.l[i] = a[8 * (uint64_t)t + i]; y.l[i] = b[8 * (uint64_t)t + i]; }
+            fr_t r = op == FOP_FR_MUL ? fr_mul(x, y) : fe_inv_gcd<FrParams>(x);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) out[8 * (uint64_t)t + i] = r.l[i];
+            return;
+        }
+        fp_t x, y, r;
+#pragma unroll
+        for (int i = 0; i < 12; ++i) { x.l[i] = a[12 * (uint64_t)t + i]; y.l[i] = b[12 * (uint64_t)t + i]; }
+        switch (op) {
+            case FOP_FP_MUL: r = fp_mul(x, y); break;
+            case FOP_FP_SQR: r = fp_sqr(x); break;
+            case FOP_FP_MUL_F64: r = fp_mul_lat(x, y); break;
+            case FOP_FP_SQR_F64: r = fp_sqr_lat(x); break;
+            case FOP_FP_INV: r = fe_inv_gcd<FpParams>(x); break;
+            case FOP_FP_ADD: r = fp_add(x, y); break;
+            default: r = fp_sub(x, y); break;
+        }
+#pragma unroll
+        for (int i = 0; i < 12; ++i) out[12 * (uint64_t)t + i] = r.l[i];
+    }
+};
+
 /* fp16 -> int16 by one float multiply, round-half-even, clamp; or pass-through copies */
 struct EncodeF16 {
     const uint16_t* src;
@@ -557,8 +593,8 @@ struct AccFinal {
     g1_xyzz* bucket;
     TC_DEV void operator()(uint32_t b) const {
         uint32_t begin = start[b], end = start[b + 1];
-        g1_xyzz acc = xyzz_identity();
-        for (uint32_t i = begin; i < end; ++i) acc = xyzz_add(acc, in[i]);
+        g1_xyzz acc = begin < end ? in[begin] : xyzz_identity();
+        for (uint32_t i = begin + 1; i < end; ++i) acc = xyzz_add(acc, in[i]);
         bucket[b] = acc;
     }
 };

@@ -571,6 +571,15 @@ extern "C" int tc_ctx_alu_rate(tc_ctx* ctx, int kind, int waves_per_simd, double
 #endif
 }
 
+extern "C" int tc_ctx_field_op(tc_ctx* ctx, int op, const void* d_a, const void* d_b, size_t n, void* d_out) {
+    if (!ctx) return TC_ERR_ARG;
+    if (op < 0 || op >= FOP_COUNT || ((!d_a || !d_b || !d_out) && n)) return fail(ctx, TC_ERR_ARG, "bad argument");
+    if (n > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "too many elements");
+    RT(rt::set_device(ctx->device));
+    RT(rt::launch<64>(n, ctx->stream, FieldOp{op, (const uint32_t*)d_a, (const uint32_t*)d_b, (uint32_t*)d_out}));
+    return TC_OK;
+}
+
 extern "C" const char* tc_last_error(const tc_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 extern "C" int tc_ctx_sync(tc_ctx* ctx) {
     try {
@@ -1211,7 +1220,8 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
      * is fastest with the shortest sub-runs (the first entry of a sub-run is a copy, not an addition), the later
      * passes with the longest, and steps in flight run equally fast from 4 to 13.  Not longer than half the
      * average bucket load either: longer sub-runs leave the lanes of a wave with very different amounts of work
-     * (measured on openings of the LLaMA2-7B-shaped forward: 64 of them 182 -> 152 ms). */
+     * (measured on openings of the LLaMA2-7B-shaped forward: 64 of them 182 -> 152 ms; with today's kernels the
+     * whole average load does as well as half of it, 138 against 136 ms, and 1.5 or 2 times the load 145 and 163 ms). */
     const uint64_t target_lanes = 2 * ACC_RESIDENT_LANES;
     uint32_t L1 = (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(4, (items + target_lanes - 1) / target_lanes));
     L1 = (uint32_t)std::min<uint64_t>(L1, std::max<uint64_t>(4, (items + 2 * (uint64_t)nbk - 1) / (2 * (uint64_t)nbk)));
@@ -1299,6 +1309,9 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     g1_xyzz *cur = bufA, *nxt = bufB;
     uint32_t *cur_start = lstart, *nxt_start = lstart2;
     uint64_t lanes_bound = max_part;
+    /* (Leaving the middle passes out when the buckets outnumber the lanes the chip holds -- the last pass then
+     * sums up to 64 partial sums per bucket -- was measured and is worse: its lanes diverge with the bucket loads;
+     * 64 openings of the LLaMA2-7B-shaped forward 136 -> 206 ms, the build 69 -> 74 ms.) */
     while (worst > L2) {
         /* counts of this pass = number of partials per bucket = differences of cur_start */
         RT(rt::launch<256>(nbk, ctx->stream, DiffCounts{cur_start, cnt}));

@@ -82,3 +82,45 @@ class Stopwatch:
         now = time.time()
         print("%s: %s (%.1f s, %.1f s since start)" % (self.name, what, now - self.last, now - self.t0), flush=True)
         self.last = now
+
+
+def check_field_arithmetic(run, n_fp, n_fr):
+    """run(op, a_words, b_words, words_per_element) -> result words, for the operations of tc_ctx_field_op; every
+    result is compared with Python integers.  Operands are Montgomery representatives, i.e. plain residues."""
+    import random
+
+    P, Rr = ec.P, ec.R
+    RP, RR = 1 << 384, 1 << 256
+    rng = random.Random(11)
+    edge_p = [0, 1, 2, P - 1, P - 2, 1 << 380, (1 << 380) - 1, RP % P, (RP * RP) % P, (1 << 381) % P,
+              int("ffffffff" * 11, 16), 0xFFFFFFFF, 1 << 32, (P - 1) // 2, (P + 1) // 2]
+    a_vals = edge_p + [rng.randrange(P) for _ in range(n_fp)] + [x for x in edge_p for _ in edge_p]
+    b_vals = list(reversed(edge_p)) + [rng.randrange(P) for _ in range(n_fp)] + [y for _ in edge_p for y in edge_p]
+
+    def pack(vals, words):
+        return np.frombuffer(b"".join(int(v).to_bytes(4 * words, "little") for v in vals), dtype=np.uint32).copy()
+
+    def unpack(arr, words):
+        raw = np.ascontiguousarray(arr).tobytes()
+        return [int.from_bytes(raw[4 * words * i : 4 * words * (i + 1)], "little") for i in range(len(raw) // (4 * words))]
+
+    pa, pb = pack(a_vals, 12), pack(b_vals, 12)
+    rinv = pow(RP, -1, P)
+    expect = {0: lambda x, y: x * y * rinv % P, 1: lambda x, y: x * x * rinv % P, 2: lambda x, y: x * y * rinv % P,
+              3: lambda x, y: x * x * rinv % P, 6: lambda x, y: (x + y) % P, 7: lambda x, y: (x - y) % P}
+    for op, fn in expect.items():
+        got = unpack(run(op, pa, pb, 12), 12)
+        bad = [i for i in range(len(a_vals)) if got[i] != fn(a_vals[i], b_vals[i])]
+        assert not bad, "Fp operation %d: %d wrong, first operands %x, %x" % (op, len(bad), a_vals[bad[0]], b_vals[bad[0]])
+    nz = [v if v else 5 for v in a_vals]                       # inverse of a Montgomery representative: R^2 / a
+    got = unpack(run(4, pack(nz, 12), pack(nz, 12), 12), 12)
+    assert all(g == RP * RP * pow(v, -1, P) % P for g, v in zip(got, nz)), "Fp inverse"
+    edge_r = [0, 1, Rr - 1, RR % Rr, 1 << 254, (1 << 254) - 1, 0xFFFFFFFF]
+    ar = edge_r + [rng.randrange(Rr) for _ in range(n_fr)] + [x for x in edge_r for _ in edge_r]
+    br = list(reversed(edge_r)) + [rng.randrange(Rr) for _ in range(n_fr)] + [y for _ in edge_r for y in edge_r]
+    rrinv = pow(RR, -1, Rr)
+    got = unpack(run(5, pack(ar, 8), pack(br, 8), 8), 8)
+    assert all(g == x * y * rrinv % Rr for g, x, y in zip(got, ar, br)), "Fr product"
+    nzr = [v if v else 7 for v in ar]
+    got = unpack(run(8, pack(nzr, 8), pack(nzr, 8), 8), 8)
+    assert all(g == RR * RR * pow(v, -1, Rr) % Rr for g, v in zip(got, nzr)), "Fr inverse"

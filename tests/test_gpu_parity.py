@@ -12,7 +12,7 @@ from oracle import bls12_381 as ec
 from oracle import cbind, quantize, tc, terkle
 from oracle.bls12_381 import R
 
-from gpu_util import HOST_THREADS, TAU_BYTES, Stopwatch, fr_bytes_array, oracle_pool, parse_proof, pps, serialize_steps, to_device
+from gpu_util import HOST_THREADS, TAU_BYTES, Stopwatch, check_field_arithmetic, fr_bytes_array, oracle_pool, parse_proof, pps, serialize_steps, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -47,6 +47,23 @@ def c1(T, ctx):
     X = tc_inputs.c1_tensor()
     yield srs, X, to_device(X)
     srs.close()
+
+
+def test_device_field_arithmetic_against_integers(T, ctx):
+    """The device forms of the field arithmetic -- the product-scanning Montgomery product and square with inline
+    multiply-add / carry instructions, their exact FP64-pipe variants, the word-batched binary-GCD inverse, the
+    carry-chain addition and subtraction -- against Python integers, on edge operands (0, 1, p - 1, 2^380, the
+    Montgomery one, all-ones limbs below p, every pair of them) and a few thousand random ones."""
+    import torch
+
+    def run(op, a, b, words):
+        da, db = to_device(a), to_device(b)
+        out = torch.empty(a.size, dtype=torch.int32, device="cuda")
+        ctx.field_op(op, da, db, a.size // words, out)
+        ctx.sync()
+        return out.cpu().numpy().view(np.uint32)
+
+    check_field_arithmetic(run, 4096, 1024)
 
 
 def test_srs_points_match_oracle(ctx, c1):

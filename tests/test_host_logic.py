@@ -25,7 +25,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, ROOT)
 import __graft_entry__ as entry  # noqa: E402
 import paper_2602_12630_amd as T  # noqa: E402
-from gpu_util import TAU_BYTES, fr_bytes_array, pps, serialize_steps  # noqa: E402
+from gpu_util import TAU_BYTES, check_field_arithmetic, fr_bytes_array, pps, serialize_steps  # noqa: E402
 
 EMU = os.path.join(ROOT, "tests", "hostmath", "libtc_hostemu.so")
 
@@ -659,3 +659,15 @@ def test_emulated_quant_scale(emu):
             ref = quantize.quantize_f16(np.where(np.isfinite(x), x, np.float16(0)), want)
             fin = np.isfinite(x)
             assert np.array_equal(q[fin], ref[fin])
+
+
+def test_emulated_field_ops(emu):
+    """The field-operation hook on the host build (the portable forms of the same routines) against Python
+    integers: the check that the GPU test applies to the device forms, validated here without a GPU."""
+
+    def run(op, a, b, words):
+        out = np.zeros(a.size, np.uint32)
+        emu.field_op(op, a, b, a.size // words, out)
+        return out
+
+    check_field_arithmetic(run, 200, 100)
