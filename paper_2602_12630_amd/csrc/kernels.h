@@ -147,13 +147,22 @@ TC_HD uint32_t half_magnitude_if_finite(uint32_t h) {
     return mag < 0x7C00u ? mag : 0u;          /* exponent 31: infinities and NaNs do not count */
 }
 struct AbsMaxF16 {
-    static constexpr int BLOCK = 256;
+    static constexpr int BLOCK = 1024;
     static constexpr int PHASES = 3;
     static constexpr size_t LDS_BYTES = 16;
     const uint16_t* src;
     uint64_t n;
     uint32_t groups;
     uint32_t* result;          /* zeroed before the launch */
+    TC_DEV static uint32_t piece_max(const Words16& x, uint32_t best) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint32_t a = half_magnitude_if_finite(x.w[i] & 0xFFFFu), b = half_magnitude_if_finite(x.w[i] >> 16);
+            best = a > best ? a : best;
+            best = b > best ? b : best;
+        }
+        return best;
+    }
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         uint32_t* wmax = (uint32_t*)lds;
         if (ph == 0) {
@@ -161,6 +170,7 @@ struct AbsMaxF16 {
             return;
         }
         if (ph == 2) {
+            /* atomics on one address go through one after the other: a workgroup of 1024 lanes keeps them few */
             if (lane == 0 && wmax[0]) atomic_max_u32(result, wmax[0]);
             return;
         }
@@ -170,15 +180,13 @@ struct AbsMaxF16 {
         head = head / 2 < n ? head / 2 : n;
         uint64_t chunks = (n - head) / 8;
         const Words16* body = (const Words16*)(src + head);
-        for (uint64_t ch = (uint64_t)wg * BLOCK + lane; ch < chunks; ch += (uint64_t)groups * BLOCK) {
-            Words16 x = body[ch];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                uint32_t a = half_magnitude_if_finite(x.w[i] & 0xFFFFu), b = half_magnitude_if_finite(x.w[i] >> 16);
-                best = a > best ? a : best;
-                best = b > best ? b : best;
-            }
+        uint64_t stride = (uint64_t)groups * BLOCK;
+        uint64_t ch = (uint64_t)wg * BLOCK + lane;
+        for (; ch + stride < chunks; ch += 2 * stride) {      /* two loads in flight per lane */
+            Words16 x = body[ch], y = body[ch + stride];
+            best = piece_max(y, piece_max(x, best));
         }
+        if (ch < chunks) best = piece_max(body[ch], best);
         if (wg == 0) {
             for (uint64_t i = lane; i < head; i += BLOCK) {
                 uint32_t a = half_magnitude_if_finite(src[i]);

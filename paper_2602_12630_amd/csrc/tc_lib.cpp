@@ -1071,8 +1071,8 @@ extern "C" int tc_encode_tensor_scaled(tc_ctx* ctx, const void* d_src, int src_d
     if (!d_inv_scale) return fail(ctx, TC_ERR_ARG, "null scale");
     return encode_tensor(ctx, d_src, src_dtype, n, 0.0f, d_inv_scale, d_dst);
 }
-/* at most this many workgroups take part in the maximum (each ends in one atomic) */
-static const uint32_t ABSMAX_MAX_GROUPS = 2048;
+/* at most this many workgroups take part in the maximum (each ends in one atomic): one per compute unit */
+static const uint32_t ABSMAX_MAX_GROUPS = 256;
 extern "C" int tc_quant_scale(tc_ctx* ctx, const void* d_src, size_t n, float* d_inv_scale) {
     if (!ctx) return TC_ERR_ARG;
     if (!d_inv_scale || (!d_src && n)) return fail(ctx, TC_ERR_ARG, "null buffer");
@@ -1220,8 +1220,9 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
      * is fastest with the shortest sub-runs (the first entry of a sub-run is a copy, not an addition), the later
      * passes with the longest, and steps in flight run equally fast from 4 to 13.  Not longer than half the
      * average bucket load either: longer sub-runs leave the lanes of a wave with very different amounts of work
-     * (measured on openings of the LLaMA2-7B-shaped forward: 64 of them 182 -> 152 ms; with today's kernels the
-     * whole average load does as well as half of it, 138 against 136 ms, and 1.5 or 2 times the load 145 and 163 ms). */
+     * (measured on the 64 openings of the LLaMA2-7B-shaped forward, row buckets of 16 entries on average: sub-runs
+     * of 8 and 16 entries 136 and 138 ms, of 24 and 32 entries 145 and 163 ms; on that forward's build, 101 entries
+     * per bucket: sub-runs of 50 entries and one middle pass 69.2 ms, of 64 entries and no middle pass 70.3 ms). */
     const uint64_t target_lanes = 2 * ACC_RESIDENT_LANES;
     uint32_t L1 = (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(4, (items + target_lanes - 1) / target_lanes));
     L1 = (uint32_t)std::min<uint64_t>(L1, std::max<uint64_t>(4, (items + 2 * (uint64_t)nbk - 1) / (2 * (uint64_t)nbk)));
