@@ -47,8 +47,8 @@ FORMULA_PEAK_MADS_PER_S = 256 * 4 * 16 * 2.4e9 / 2
 R_MODULUS = 0x73EDA753299D7D483339D80809A1D80553BDA402FFFE5BFEFFFFFFFF00000001      # group order (embedding of negatives)
 # HBM bytes moved by the bucket-accumulation launch of one LLaMA2-7B-shaped build (rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE of `bench.py --only-c3-build`, scaled by a 256 MiB copy kernel; runs and scale factors in
-# profiles/c3_build_hbm_traffic_pmc.txt).  None until that profile exists for the current kernel.
-ACC_TRAFFIC_BYTES_C3 = None
+# profiles/c3_build_hbm_traffic_pmc.txt).
+ACC_TRAFFIC_BYTES_C3 = 9.185e10
 
 
 # ----------------------------------------------------------------------------------------------------------
@@ -406,6 +406,7 @@ def bench_c2_step(ctx, T, torch, lib, node_srs, tau, steps, warmup, in_flight, o
                 self.ctx.close()
 
     lanes = [Lane(ctx)] + [Lane(None) for _ in range(max(1, in_flight) - 1)]
+    serial = len(lanes) == 1          # one step at a time: the flat commitment runs on the same stream as the rest
     hip = hip_event_timer()
     phases = {"encode": Events(hip), "commit": Events(hip), "tree": Events(hip), "open": Events(hip), "verify": Events(hip)}
 
@@ -431,7 +432,7 @@ def bench_c2_step(ctx, T, torch, lib, node_srs, tau, steps, warmup, in_flight, o
             return out
 
         timed("encode", lambda: quantise(lane))
-        if record:
+        if record or serial:
             C = timed("commit", lambda: lctx.commit(srs, dq, T.TC_I16))
             tree = timed("tree", lambda: lctx.terkle_build_entries(node_srs, dq, T.TC_I16, shape, node))
         else:
@@ -741,6 +742,8 @@ def main():
                     "node shapes (8,8), (4,4,4), (64,)); needs about 12 GB of fixed-base tables")
     ap.add_argument("--only-c3-build", type=int, default=0, metavar="N", help="profiling mode: set-up, N quantise + build "
                     "passes of the LLaMA2-7B-shaped forward, nothing else")
+    ap.add_argument("--only-c2-step", action="store_true", help="profiling mode: set-up and the single-layer leg alone "
+                    "(--c2-steps, --in-flight; --in-flight 1 runs one step after the other)")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one plain copy kernel of 256 MiB "
                     "(reference dispatch for scaling the HBM byte counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
@@ -773,6 +776,13 @@ def main():
         del cal_src, cal_dst
     if args.only_c3_build:
         only_c3_build(ctx, T, torch, node_srs, tau, args.only_c3_build)
+        node_srs.close()
+        ctx.close()
+        return
+    if args.only_c2_step:
+        leg, _ = bench_c2_step(ctx, T, torch, lib, node_srs, tau, args.c2_steps, max(args.warmup, 2), args.in_flight, args.openings,
+                               FORMULA_PEAK_MADS_PER_S)
+        print(json.dumps({"mode": "only-c2-step", "c2_step": leg}))
         node_srs.close()
         ctx.close()
         return
