@@ -106,11 +106,14 @@ int tc_ctx_profile_units(tc_ctx* ctx, int kind, uint64_t* units);
  *   TC_ALU_MAD_CARRY  the same with the carry of every multiply-add added into a third word, the pair of
  *                     instructions that a limb product of the field multiplication costs;
  *   TC_ALU_FP_MUL / TC_ALU_FP_SQR   Fp products / squarings per second of the library's own routines in a chain
- *                     (one product = 300 multiply-adds, one squaring 234). */
+ *                     (one product = 300 multiply-adds, one squaring 234);
+ *   TC_ALU_FP_MUL_F64 / TC_ALU_FP_SQR_F64   the same for the exact variants on the FP64 pipe. */
 #define TC_ALU_MAD 0
 #define TC_ALU_MAD_CARRY 1
 #define TC_ALU_FP_MUL 2
 #define TC_ALU_FP_SQR 3
+#define TC_ALU_FP_MUL_F64 4
+#define TC_ALU_FP_SQR_F64 5
 int tc_ctx_alu_rate(tc_ctx* ctx, int kind, int waves_per_simd, double* out_per_s);
 
 /* Test hook: one field operation per element on device arrays of raw limbs, little-endian 32-bit words, values

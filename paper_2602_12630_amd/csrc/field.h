@@ -389,8 +389,8 @@ __device__ __forceinline__ Fe<P> fe_sqr_dev(const Fe<P>& a) {
  * stays below 2^53, so every fused multiply-add is exact in any rounding mode.  16 x 24 = 12 x 32 bits: the
  * Montgomery radix is the same 2^384, and the result is bit for bit that of the integer routine.
  * 512 multiply-adds replace 300 integer ones and their 300 carry additions: a full chip gets through fewer
- * products a second this way (measured 46 G against 61 G); a wave alone on its SIMD finishes a product about as
- * fast as with the integer form (1.74 us against 1.71 us) and a square a little sooner (1.31 us against 1.45 us). */
+ * products a second this way; a wave alone on its SIMD finishes a product about as fast as with the integer form
+ * and a square a little sooner (tc_ctx_alu_rate measures all four). */
 template <int J>
 constexpr double fp_mod_limb24() {
     /* bits 24 J .. 24 J + 23 of the modulus */

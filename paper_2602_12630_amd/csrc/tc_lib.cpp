@@ -511,7 +511,8 @@ __global__ __launch_bounds__(256) void alu_rate_kernel(uint32_t iters, uint32_t*
         y.l[1] ^= t * 7u;
         for (uint32_t it = 0; it < iters; ++it) {
 #pragma unroll 1
-            for (int i = 0; i < 8; ++i) x = KIND == TC_ALU_FP_MUL ? fp_mul(x, y) : fp_sqr(x);
+            for (int i = 0; i < 8; ++i)
+                x = KIND == TC_ALU_FP_MUL ? fp_mul(x, y) : KIND == TC_ALU_FP_SQR ? fp_sqr(x) : KIND == TC_ALU_FP_MUL_F64 ? fp_mul_lat(x, y) : fp_sqr_lat(x);
         }
 #pragma unroll
         for (int i = 0; i < 12; ++i) out ^= x.l[i];
@@ -523,7 +524,7 @@ __global__ __launch_bounds__(256) void alu_rate_kernel(uint32_t iters, uint32_t*
 
 extern "C" int tc_ctx_alu_rate(tc_ctx* ctx, int kind, int waves_per_simd, double* out_per_s) {
     if (!ctx) return TC_ERR_ARG;
-    if (!out_per_s || kind < 0 || kind > TC_ALU_FP_SQR) return fail(ctx, TC_ERR_ARG, "bad argument");
+    if (!out_per_s || kind < 0 || kind > TC_ALU_FP_SQR_F64) return fail(ctx, TC_ERR_ARG, "bad argument");
     if (waves_per_simd < 1 || waves_per_simd > 8) return fail(ctx, TC_ERR_ARG, "waves_per_simd must be 1..8");
 #if defined(TC_HOST_EMU)
     return fail(ctx, TC_ERR_HIP, "no GPU in the host emulation");
@@ -550,7 +551,9 @@ extern "C" int tc_ctx_alu_rate(tc_ctx* ctx, int kind, int waves_per_simd, double
         void (*k)(uint32_t, uint32_t*) = kind == TC_ALU_MAD         ? alu_rate_kernel<TC_ALU_MAD>
                                          : kind == TC_ALU_MAD_CARRY ? alu_rate_kernel<TC_ALU_MAD_CARRY>
                                          : kind == TC_ALU_FP_MUL    ? alu_rate_kernel<TC_ALU_FP_MUL>
-                                                                    : alu_rate_kernel<TC_ALU_FP_SQR>;
+                                         : kind == TC_ALU_FP_SQR    ? alu_rate_kernel<TC_ALU_FP_SQR>
+                                         : kind == TC_ALU_FP_MUL_F64 ? alu_rate_kernel<TC_ALU_FP_MUL_F64>
+                                                                     : alu_rate_kernel<TC_ALU_FP_SQR_F64>;
         int e = (int)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (!e) {
             hipLaunchKernelGGL(k, dim3(groups), dim3(256), lds, ctx->stream, iters, sink);
