@@ -90,7 +90,7 @@ class C3Forward:
         self.ctx, self.T, self.torch, self.node_srs = ctx, T, torch, node_srs
         cfg = tc_inputs.LLAMA7B
         self.shapes3 = tc_inputs.c3_shapes(cfg)
-        self.srs_by_shape = {s: ctx.setup_from_trapdoor(tau, s, T.TC_SRS_SUFFIX) for s in set(self.shapes3)}
+        self.srs_by_shape = {s: ctx.setup_from_trapdoor(tau, s, T.TC_SRS_SUFFIX | T.TC_SRS_OPEN_TABLE) for s in set(self.shapes3)}
         gen = torch.Generator(device="cuda")
         gen.manual_seed(tc_inputs.tensor_seed(2))
         self.xs, self.qs, self.leaf_srs = [], [], []

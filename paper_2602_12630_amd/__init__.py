@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     TC_OK,
     TC_SRS_FIXED_BASE,
     TC_SRS_MONOMIAL,
+    TC_SRS_OPEN_TABLE,
     TC_SRS_SUFFIX,
     Context,
     PairingVerifier,

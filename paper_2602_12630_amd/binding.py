@@ -10,7 +10,7 @@ import os
 TC_OK = 0
 TC_ERR_ARG, TC_ERR_SHAPE, TC_ERR_RANGE, TC_ERR_NOMEM, TC_ERR_HIP, TC_ERR_VERIFY, TC_ERR_STATE = -1, -2, -3, -4, -5, -6, -7
 TC_I8, TC_I16, TC_FR, TC_F16 = 1, 2, 3, 4
-TC_SRS_SUFFIX, TC_SRS_FIXED_BASE, TC_SRS_MONOMIAL = 1, 2, 4
+TC_SRS_SUFFIX, TC_SRS_FIXED_BASE, TC_SRS_MONOMIAL, TC_SRS_OPEN_TABLE = 1, 2, 4, 8
 TC_INTERP_NEWTON, TC_INTERP_GREGORY, TC_INTERP_BARYCENTRIC = 0, 1, 2
 TC_LEAF_ENTRIES, TC_LEAF_TENSORS = 0, 1
 TC_PROF_BUCKET_ACC, TC_PROF_NODE_COMMIT, TC_PROF_NODE_COMMIT_UPPER, TC_PROF_VERIFY_CHAIN = 0, 1, 2, 3

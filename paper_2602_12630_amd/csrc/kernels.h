@@ -1159,6 +1159,26 @@ struct SrsGen {                /* lane i: S^(a)[i] = [prod_{j>=a} l_j[i_j]] G */
     }
 };
 
+/* Factors of the opening table of the leading axis: lane kappa computes
+ *     g(kappa) = sum_(k != kappa) l_k(tau) / (zeta_k - zeta_kappa),     zeta_k - zeta_kappa = k - kappa,
+ * so that U[kappa, t] = sum_(k != kappa) S[k, t] / (zeta_k - zeta_kappa) = [g(kappa) prod_(j > 0) l_j[t_j]] G comes out of
+ * the SRS generator with g in the place of the leading axis' Lagrange values. */
+struct OpenTableFactors {
+    const fr_t* ell;           /* l_k(tau) of the leading axis, Montgomery */
+    const fr_t* inv_int;       /* 1 / j, j = 1 .. d-1 */
+    uint32_t d;
+    fr_t* out;
+    TC_DEV void operator()(uint32_t kappa) const {
+        fr_t pos = fe_zero<FrParams>(), neg = fe_zero<FrParams>();
+        for (uint32_t k = 0; k < d; ++k) {
+            if (k == kappa) continue;
+            fr_t t = fr_mul(ell[k], inv_int[k > kappa ? k - kappa : kappa - k]);
+            if (k > kappa) pos = fr_add(pos, t); else neg = fr_add(neg, t);
+        }
+        out[kappa] = fr_sub(pos, neg);
+    }
+};
+
 /* ---- Terkle node commitments ----------------------------------------------------------- */
 struct TreeGeom {
     int m;
@@ -1429,16 +1449,20 @@ struct QuotientKappaRow {    /* lane t */
  *   pi = sum_{k != kap} c_k R_k + sum_t q[kap, t] S[kap, t],   c_k = 1 / (zeta_k - zeta_kap),
  *   R_k = sum_t (T[k, t] - T[kap, t]) S[k, t]   (one small-scalar problem per row, 17-bit numerators),
  * so the bulk of the work is two 9-bit digits per entry instead of sixteen 16-bit windows. */
-struct RowWeights {            /* lane j: plain c_k for the j-th row other than kap */
+struct RowWeights {            /* plain c_k: lane j for the j-th row other than kap, or (all_rows) lane k for row k, 0 at kap */
     AxisTables ax;
     uint32_t kap;
+    int all_rows;
     fr_plain* out;
     TC_DEV void operator()(uint32_t j) const {
-        uint32_t k = j < kap ? j : j + 1;
-        uint32_t dist = k > kap ? k - kap : kap - k;
-        fr_t c = ax.inv_int[dist];
-        if (k < kap) c = fr_neg(c);
-        fr_t plain = fe_to_plain(c);
+        uint32_t k = all_rows ? j : (j < kap ? j : j + 1);
+        fr_t plain = fe_zero<FrParams>();
+        if (k != kap) {
+            uint32_t dist = k > kap ? k - kap : kap - k;
+            fr_t c = ax.inv_int[dist];
+            if (k < kap) c = fr_neg(c);
+            plain = fe_to_plain(c);
+        }
 #pragma unroll
         for (int i = 0; i < 8; ++i) out[j].l[i] = plain.l[i];
     }
@@ -1525,12 +1549,18 @@ struct FillIdentity {
     g1_xyzz* out;
     TC_DEV void operator()(uint32_t t) const { out[t] = xyzz_identity(); }
 };
-/* out = res[a] (+ res[b] when b >= 0): where the proof elements of a batch of openings end up */
+/* out = res[a] (+ res[b] when b >= 0) (- sub[c] when c >= 0): where the proof elements of a batch of openings end up */
 struct CollectResult {
     const g1_xyzz* res;
     int32_t a, b;
+    const g1_xyzz* sub;
+    int32_t c;
     g1_xyzz* out;
-    TC_DEV void operator()(uint32_t) const { *out = b >= 0 ? xyzz_add(res[a], res[b]) : res[a]; }
+    TC_DEV void operator()(uint32_t) const {
+        g1_xyzz r = b >= 0 ? xyzz_add(res[a], res[b]) : res[a];
+        if (c >= 0) r = xyzz_add(r, xyzz_neg(sub[c]));
+        *out = r;
+    }
 };
 
 /* y = e(T[f]) as canonical bytes */

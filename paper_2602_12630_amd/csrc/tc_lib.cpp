@@ -104,6 +104,7 @@ struct tc_srs {
     uint64_t n[4] = {0, 0, 0, 0};
     g1_affine* pts[4] = {nullptr, nullptr, nullptr, nullptr};
     g1_affine* fb[4] = {nullptr, nullptr, nullptr, nullptr};
+    g1_affine* open_tab = nullptr;      /* U[kappa, t] of the leading axis (TC_SRS_OPEN_TABLE), n[0] points */
     fr_t* axis_mem = nullptr;
     AxisTables ax[4];
 };
@@ -128,6 +129,9 @@ struct tc_tree {
     std::vector<const void*> leaf_scalars;
     std::vector<int> leaf_dtype;
     std::vector<TreeLevel> levels;
+    /* per leaf tensor: its row commitments once an opening has computed them (device memory, owned by the tree);
+     * filled in by openings, which take the tree as const */
+    mutable std::vector<g1_affine*> row_cache;
     void* block = nullptr;          /* one device allocation holds C and phi of every level */
     size_t block_cap = 0;
     std::shared_ptr<TreePool> pool;
@@ -688,6 +692,7 @@ extern "C" void tc_srs_destroy(tc_srs* srs) {
         if (srs->fb[a]) rt::dev_free(srs->fb[a]);
     }
     if (srs->axis_mem) rt::dev_free(srs->axis_mem);
+    if (srs->open_tab) rt::dev_free(srs->open_tab);
     delete srs;
 }
 extern "C" uint64_t tc_srs_size(const tc_srs* srs, int first_axis) {
@@ -743,7 +748,7 @@ static int srs_upload_axis_tables(tc_ctx* ctx, tc_srs* srs) {
     return TC_OK;
 }
 static bool srs_flags_ok(uint32_t flags) {
-    if (flags & ~(TC_SRS_SUFFIX | TC_SRS_FIXED_BASE | TC_SRS_MONOMIAL)) return false;
+    if (flags & ~(TC_SRS_SUFFIX | TC_SRS_FIXED_BASE | TC_SRS_MONOMIAL | TC_SRS_OPEN_TABLE)) return false;
     return !(flags & TC_SRS_MONOMIAL) || flags == TC_SRS_MONOMIAL;
 }
 
@@ -757,6 +762,7 @@ extern "C" int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, co
         if (!srs_flags_ok(flags)) return fail(ctx, TC_ERR_ARG, "unknown flag, or the monomial SRS combined with another flag");
         if ((flags & TC_SRS_FIXED_BASE) && total > FB_MAX_BASES)
             return fail(ctx, TC_ERR_SHAPE, "fixed-base tables are limited to shapes with at most 64 entries");
+        if ((flags & TC_SRS_OPEN_TABLE) && (m < 2 || shape[0] < 2)) return fail(ctx, TC_ERR_SHAPE, "the opening table needs a shape of order >= 2");
         RT(rt::set_device(ctx->device));
         TRY(ws_reset(ctx));
 
@@ -805,7 +811,8 @@ extern "C" int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, co
         do {
             rc = srs_upload_axis_tables(ctx, srs);
             if (rc) break;
-            if (rt::dev_malloc(&d_ell, ell_all.size() * sizeof(fr_t)) != 0) {
+            /* behind the Lagrange values: room for the factors g(kappa) of the opening table */
+            if (rt::dev_malloc(&d_ell, (ell_all.size() + shape[0]) * sizeof(fr_t)) != 0) {
                 rc = fail(ctx, TC_ERR_NOMEM, "SRS table allocation failed");
                 break;
             }
@@ -841,6 +848,30 @@ extern "C" int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, co
                     rc = normalize(ctx, (g1_xyzz*)tmp, cnt, srs->pts[a] + i0);
                 }
                 if (rc == TC_OK && (flags & TC_SRS_FIXED_BASE)) rc = build_fixed_base_table(ctx, srs->pts[a], (uint32_t)na, &srs->fb[a]);
+            }
+            if (rc == TC_OK && (flags & TC_SRS_OPEN_TABLE)) {
+                /* U = the generator run once more with g(kappa) in the place of the leading axis' Lagrange values */
+                fr_t* g = (fr_t*)d_ell + ell_all.size();
+                void* q = nullptr;
+                e = rt::launch<64>(shape[0], ctx->stream, OpenTableFactors{(const fr_t*)d_ell + ell_off[0], srs->ax[0].inv_int, shape[0], g});
+                if (e) rc = fail_hip(ctx, e, "OpenTableFactors");
+                else if (rt::dev_malloc(&q, (size_t)total * sizeof(g1_affine)) != 0) rc = fail(ctx, TC_ERR_NOMEM, "opening table allocation failed");
+                srs->open_tab = (g1_affine*)q;
+                SrsGen gen;
+                gen.shape.m = m;
+                for (int j = 0; j < 4; ++j) { gen.shape.d[j] = j < m ? shape[j] : 1; gen.ell_off[j] = ell_off[j]; }
+                gen.ell_off[0] = (uint32_t)ell_all.size();
+                gen.first_axis = 0;
+                gen.ell = (const fr_t*)d_ell;
+                gen.gtable = ctx->gtable;
+                gen.out = (g1_xyzz*)tmp;
+                for (uint64_t i0 = 0; i0 < total && rc == TC_OK; i0 += slab) {
+                    uint64_t cnt = std::min(slab, total - i0);
+                    gen.i0 = i0;
+                    e = rt::launch<64>(cnt, ctx->stream, gen);
+                    if (e) { rc = fail_hip(ctx, e, "SrsGen"); break; }
+                    rc = normalize(ctx, (g1_xyzz*)tmp, cnt, srs->open_tab + i0);
+                }
             }
             e = rt::stream_sync(ctx->stream);
             if (e && rc == TC_OK) rc = fail_hip(ctx, e, "SRS generation");
@@ -921,6 +952,7 @@ extern "C" int tc_srs_export(tc_ctx* ctx, const tc_srs* srs, void* host_buf, siz
         uint64_t count = 0;
         for (int a = 0; a < srs->m; ++a)
             if (srs->pts[a]) count += srs->n[a];
+        if (srs->open_tab) count += srs->n[0];
         size_t need = SRS_HEADER_BYTES + 96 * (size_t)count;
         size_t cap = *len;
         *len = need;
@@ -944,6 +976,7 @@ extern "C" int tc_srs_export(tc_ctx* ctx, const tc_srs* srs, void* host_buf, siz
             TRY(export_points(ctx, srs->pts[a], srs->n[a], o));
             o += 96 * (size_t)srs->n[a];
         }
+        if (srs->open_tab) TRY(export_points(ctx, srs->open_tab, srs->n[0], o));
         return TC_OK;
     } catch (const std::bad_alloc&) {
         return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
@@ -973,6 +1006,7 @@ extern "C" int tc_srs_import(tc_ctx* ctx, const void* host_buf, size_t len, tc_s
             return fail(ctx, TC_ERR_ARG, "bad flags or basis kind in the SRS file");
         if ((flags & TC_SRS_FIXED_BASE) && total > FB_MAX_BASES)
             return fail(ctx, TC_ERR_SHAPE, "fixed-base tables are limited to shapes with at most 64 entries");
+        if ((flags & TC_SRS_OPEN_TABLE) && (m < 2 || shape[0] < 2)) return fail(ctx, TC_ERR_SHAPE, "the opening table needs a shape of order >= 2");
         int last_axis = (flags & TC_SRS_SUFFIX) ? (int)m - 1 : 0;
         uint64_t expect = 0, n[4] = {0, 0, 0, 0};
         for (int a = 0; a <= last_axis; ++a) {
@@ -980,6 +1014,7 @@ extern "C" int tc_srs_import(tc_ctx* ctx, const void* host_buf, size_t len, tc_s
             for (uint32_t j = (uint32_t)a; j < m; ++j) n[a] *= shape[j];
             expect += n[a];
         }
+        if (flags & TC_SRS_OPEN_TABLE) expect += total;
         if (count != expect) return fail(ctx, TC_ERR_ARG, "point count in the SRS file does not match its shape and flags");
         if (len != SRS_HEADER_BYTES + 96 * (size_t)count) return fail(ctx, TC_ERR_ARG, "SRS file truncated or too long for its point count");
         RT(rt::set_device(ctx->device));
@@ -999,6 +1034,12 @@ extern "C" int tc_srs_import(tc_ctx* ctx, const void* host_buf, size_t len, tc_s
             rc = import_points(ctx, src, n[a], srs->pts[a]);
             src += 96 * (size_t)n[a];
             if (rc == TC_OK && (flags & TC_SRS_FIXED_BASE)) rc = build_fixed_base_table(ctx, srs->pts[a], (uint32_t)n[a], &srs->fb[a]);
+        }
+        if (rc == TC_OK && (flags & TC_SRS_OPEN_TABLE)) {
+            void* q = nullptr;
+            if (rt::dev_malloc(&q, (size_t)total * sizeof(g1_affine)) != 0) rc = fail(ctx, TC_ERR_NOMEM, "opening table allocation failed");
+            srs->open_tab = (g1_affine*)q;
+            if (rc == TC_OK) rc = import_points(ctx, src, total, srs->open_tab);
         }
         if (rc != TC_OK) {
             rt::stream_sync(ctx->stream);
@@ -1465,27 +1506,45 @@ struct OpenSpec {
     const void* scalars;
     int dtype;
     uint32_t kappa[4];
+    /* where the tensor's row commitments are kept between calls (a tree's slot for this leaf), or null: when the
+     * slot is empty and the opening computes them, it leaves a device array of srs->shape[0] affine points there */
+    g1_affine** row_cache = nullptr;
 };
 
 /* Openings of `count` tensors at once.  pi: count * 4 slots (m_i used), y: count values.
  * Every axis of every opening ends in full-width MSMs (quotient values against a suffix table, or the
  * row sums weighted by 1 / (zeta_k - zeta_kap)); all of them run through ONE list of problems so
  * that their window combinations (a chain of ~250 doublings each) proceed side by side.  Leading axes of
- * large small-integer tensors first go by rows: R_k = sum_t (T[k,t] - T[kap,t]) S[k,t] for every row
- * k != kap, two 9-bit digits per entry, all rows of all openings in shared launches. */
+ * large small-integer tensors first go by rows, two 9-bit digits per entry, all rows of all openings in shared
+ * launches.  Without the opening table: R_k = sum_t (T[k,t] - T[kap,t]) S[k,t] for every row k != kap, per opening.
+ * With it (leading axis of the whole tensor, TC_SRS_OPEN_TABLE):
+ *     pi_1 = sum_(k != kap) c_k A_k - sum_t T[kap,t] U[kap,t] + sum_t q[kap,t] S[kap,t],    c_k = 1 / (zeta_k - zeta_kap),
+ * where the row commitments A_k = sum_t T[k,t] S[k,t] do not depend on the position: they are computed once per
+ * tensor of the batch and kept in the caller's slot for later calls. */
 static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xyzz* pi, fr_plain* y) {
     struct AxisJob {
         int open, axis;
-        bool by_rows;
+        bool by_rows, use_table;
         uint64_t offset, inner, na;
         uint32_t d, kap;
-        size_t row0;        /* first row problem (by_rows) */
+        size_t row0;        /* first row problem (by_rows without the table) */
+        int tensor;         /* index into `tensors` (use_table) */
+        int small0;         /* the problem against row kap of the opening table (use_table) */
         int fr0;            /* first full-width problem */
     };
+    struct TensorRows {     /* a tensor whose row commitments this batch needs */
+        const tc_srs* srs;
+        const void* scalars;
+        g1_affine** slot;
+        const g1_affine* rows;     /* d affine points once known */
+        size_t row0;               /* first row problem when they are computed here */
+        bool computed;
+    };
     std::vector<AxisJob> jobs;
+    std::vector<TensorRows> tensors;
     std::vector<FetchScalar> j_fetch;
-    std::vector<MsmProblem> row_prob;
-    std::vector<int> row_dtype;
+    std::vector<MsmProblem> row_prob, small_prob;
+    std::vector<int> row_dtype, small_dtype;
     for (int o = 0; o < count; ++o) {
         const tc_srs* srs = spec[o].srs;
         uint64_t offset = 0;
@@ -1496,10 +1555,42 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
             if (J.na > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "slice too large");
             int dt = spec[o].dtype;
             J.by_rows = (dt == TC_I8 || dt == TC_I16) && J.d >= 2 && J.inner >= 2 && J.na >= 16384;
-            J.row0 = row_prob.size(); J.fr0 = 0;
-            if (J.by_rows) {
-                size_t esz = dtype_size(dt);
-                const uint8_t* base = (const uint8_t*)spec[o].scalars + offset * esz;
+            J.use_table = J.by_rows && a == 0 && srs->open_tab != nullptr;
+            J.row0 = row_prob.size(); J.fr0 = 0; J.tensor = -1; J.small0 = -1;
+            size_t esz = dtype_size(dt);
+            const uint8_t* base = (const uint8_t*)spec[o].scalars + offset * esz;
+            int two_digits = dt == TC_I8 ? DT_DIFF8 : DT_DIFF16;
+            if (J.use_table) {
+                for (size_t t = 0; t < tensors.size() && J.tensor < 0; ++t)
+                    if (tensors[t].srs == srs && tensors[t].scalars == spec[o].scalars) J.tensor = (int)t;
+                if (J.tensor < 0) {
+                    TensorRows R{srs, spec[o].scalars, spec[o].row_cache, nullptr, row_prob.size(), false};
+                    if (R.slot && *R.slot) {
+                        R.rows = *R.slot;
+                    } else {
+                        R.computed = true;
+                        for (uint32_t k = 0; k < J.d; ++k) {
+                            MsmProblem P;
+                            P.pts = srs->pts[0] + (uint64_t)k * J.inner;
+                            P.scalars = base + (uint64_t)k * J.inner * esz;
+                            P.n = J.inner;
+                            row_prob.push_back(P);
+                            row_dtype.push_back(two_digits);
+                        }
+                    }
+                    J.tensor = (int)tensors.size();
+                    tensors.push_back(R);
+                } else if (!tensors[J.tensor].slot) {
+                    tensors[J.tensor].slot = spec[o].row_cache;
+                }
+                MsmProblem P;            /* sum_t T[kap,t] U[kap,t] */
+                P.pts = srs->open_tab + (uint64_t)J.kap * J.inner;
+                P.scalars = base + (uint64_t)J.kap * J.inner * esz;
+                P.n = J.inner;
+                J.small0 = (int)small_prob.size();
+                small_prob.push_back(P);
+                small_dtype.push_back(two_digits);
+            } else if (J.by_rows) {
                 for (uint32_t j = 0; j + 1 < J.d; ++j) {
                     uint32_t k = j < J.kap ? j : j + 1;
                     MsmProblem P;
@@ -1508,7 +1599,7 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
                     P.sub = base + (uint64_t)J.kap * J.inner * esz;
                     P.n = J.inner;
                     row_prob.push_back(P);
-                    row_dtype.push_back(dt == TC_I8 ? DT_DIFF8 : DT_DIFF16);
+                    row_dtype.push_back(two_digits);
                 }
             }
             jobs.push_back(J);
@@ -1517,7 +1608,7 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
         j_fetch.push_back(FetchScalar{spec[o].scalars, spec[o].dtype, offset, y + o});
     }
     TRY((launch_jobs<64>(ctx, j_fetch, std::vector<uint64_t>(j_fetch.size(), 1))));
-    /* rows: all R_k of all openings */
+    /* rows: all R_k of all openings, all A_k of the tensors that still lack them */
     g1_xyzz* Rk = nullptr;
     g1_affine* RkA = nullptr;
     if (!row_prob.empty()) {
@@ -1526,6 +1617,25 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
         if (!Rk || !RkA) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed");
         TRY(msm_engine_list(ctx, (int)row_prob.size(), row_prob.data(), row_dtype.data(), Rk));
         TRY(normalize(ctx, Rk, row_prob.size(), RkA));
+    }
+    for (auto& R : tensors) {
+        if (!R.computed) continue;
+        R.rows = RkA + R.row0;
+        if (R.slot && !*R.slot) {       /* keep them for later calls; without memory for that they are simply not kept */
+            void* keep = nullptr;
+            size_t bytes = (size_t)R.srs->shape[0] * sizeof(g1_affine);
+            if (rt::dev_malloc(&keep, bytes) == 0) {
+                RT(rt::memcpy_d2d(keep, R.rows, bytes, ctx->stream));
+                *R.slot = (g1_affine*)keep;
+            }
+        }
+    }
+    /* the short problems against the opening table */
+    g1_xyzz* res_small = nullptr;
+    if (!small_prob.empty()) {
+        res_small = ws_array<g1_xyzz>(ctx, small_prob.size());
+        if (!res_small) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed");
+        TRY(msm_engine_list(ctx, (int)small_prob.size(), small_prob.data(), small_dtype.data(), res_small));
     }
     /* full-width problems; the scalar work of all openings goes into six job lists, one launch each */
     std::vector<MsmProblem> fr_prob;
@@ -1542,18 +1652,18 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
         int dt = spec[J.open].dtype;
         J.fr0 = (int)fr_prob.size();
         if (J.by_rows) {
-            uint32_t rows = J.d - 1;
+            uint32_t rows = J.use_table ? J.d : J.d - 1;       /* with the table: every row, weight 0 at kap */
             WS(ck, fr_plain, rows);
             WS(wk, fr_t, J.d);
             WS(qk, fr_plain, J.inner);
-            j_rw.push_back(RowWeights{srs->ax[J.axis], J.kap, ck});
+            j_rw.push_back(RowWeights{srs->ax[J.axis], J.kap, J.use_table ? 1 : 0, ck});
             n_rw.push_back(rows);
             j_kw.push_back(KappaWeights{srs->ax[J.axis], J.kap, wk});
             n_kw.push_back(J.d);
             j_krd.push_back(KappaRowDirect{sc, dt, J.offset, J.d, J.kap, J.inner, srs->ax[J.axis], wk, qk});
             n_krd.push_back(J.inner);
             MsmProblem A, B;
-            A.pts = RkA + J.row0; A.scalars = ck; A.n = rows;
+            A.pts = J.use_table ? tensors[J.tensor].rows : RkA + J.row0; A.scalars = ck; A.n = rows;
             B.pts = srs->pts[J.axis] + (uint64_t)J.kap * J.inner; B.scalars = qk; B.n = J.inner;
             fr_prob.push_back(A);
             fr_prob.push_back(B);
@@ -1592,7 +1702,8 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
     for (size_t i = 0; i < order.size(); ++i) where[order[i]] = (int32_t)i;
     std::vector<CollectResult> j_out;
     for (auto& J : jobs)
-        j_out.push_back(CollectResult{res_sorted, where[J.fr0], J.by_rows ? where[J.fr0 + 1] : -1, pi + (size_t)J.open * 4 + J.axis});
+        j_out.push_back(CollectResult{res_sorted, where[J.fr0], J.by_rows ? where[J.fr0 + 1] : -1, res_small, J.small0,
+                                      pi + (size_t)J.open * 4 + J.axis});
     TRY((launch_jobs<64>(ctx, j_out, std::vector<uint64_t>(j_out.size(), 1))));
     return TC_OK;
 }
@@ -1772,6 +1883,8 @@ extern "C" int tc_verify(tc_ctx* ctx, const tc_vk* vk, int m, const uint32_t* sh
 /* ======================================================================================= */
 extern "C" void tc_tree_destroy(tc_tree* tree) {
     if (!tree) return;
+    for (g1_affine* rows : tree->row_cache)
+        if (rows) rt::dev_free(rows);
     if (tree->block) {
         TreePool* pool = tree->pool.get();
         if (pool && !pool->closed && tree->block_cap > pool->cap) {
@@ -1908,6 +2021,7 @@ static int tree_prepare(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** out) {
         t->leaf_srs.assign(desc->leaf_srs, desc->leaf_srs + n_payload);
         t->leaf_scalars.assign(desc->d_leaf_scalars, desc->d_leaf_scalars + n_payload);
         t->leaf_dtype.assign(desc->leaf_dtype, desc->leaf_dtype + n_payload);
+        t->row_cache.assign(n_payload, nullptr);
     }
     /* level grids, bottom-up */
     {
@@ -2617,6 +2731,11 @@ extern "C" int tc_terkle_update(tc_ctx* ctx, tc_tree* tree, const uint32_t* leaf
             for (int a = 0; a < ls->m; ++a) {
                 if (inner_index[a] >= ls->shape[a]) return fail(ctx, TC_ERR_RANGE, "inner index outside the leaf tensor");
                 inner_flat = inner_flat * ls->shape[a] + inner_index[a];
+            }
+            if (t->row_cache[leaf_flat]) {           /* the tensor changes: its kept row commitments no longer hold */
+                TRY(ctx_sync(ctx));
+                rt::dev_free(t->row_cache[leaf_flat]);
+                t->row_cache[leaf_flat] = nullptr;
             }
             RT((launch_coop<Upd::BLOCK>(1, ctx->stream, Upd{UpdatePathSrc{t->levels[0].C, t->levels[0].phi, leaf_flat, nullptr, 0,
                                                                           ls->pts[0] + inner_flat, delta, 0, d_dphi}})));

@@ -198,13 +198,25 @@ def test_degenerate_bucket_loads_at_size(T, ctx):
         srs.close()
 
 
+@pytest.mark.parametrize("table", [False, True])
 @pytest.mark.parametrize("shape", [(64, 512), (5, 37, 100), (300, 64)])
-def test_open_by_rows_matches_oracle(T, ctx, shape):
+def test_open_by_rows_matches_oracle(T, ctx, shape, table):
     """Openings of tensors large enough for the row-wise route (two 9-bit digits per entry for the
-    leading axes) against the oracle's closed form; int16 incl. extreme differences, and int8."""
+    leading axes) against the oracle's closed form; int16 incl. extreme differences, and int8; without and with
+    the opening table (row commitments + one short problem against U; its entries checked from the definition)."""
     pp = pps(shape)
-    srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, T.TC_SRS_SUFFIX)
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, T.TC_SRS_SUFFIX | (T.TC_SRS_OPEN_TABLE if table else 0))
     try:
+        if table:
+            data = srs.export()
+            n_suffix = sum(tc.prod(shape[a:]) for a in range(len(shape)))
+            inner = tc.prod(shape[1:])
+            assert len(data) == 56 + 96 * (n_suffix + tc.prod(shape))
+            for kappa, t in ((0, 0), (shape[0] - 1, inner - 1), (shape[0] // 2, inner // 3)):
+                g = sum(pp.ell[0][k] * ec.fr_inv(k - kappa) for k in range(shape[0]) if k != kappa) % R
+                want = cbind.g1_mul(g * pp.lagrange_scalar(tc.multi_index(t, shape[1:]), 1) % R, ec.G1)
+                off = 56 + 96 * (n_suffix + kappa * inner + t)
+                assert data[off : off + 96] == ec.g1_to_bytes(want)
         X16 = tc_inputs.int16_uniform(shape, 3, -32768, 32767)
         flat = X16.reshape(shape[0], -1)
         flat[0, 0], flat[-1, -1] = -32768, 32767
@@ -653,7 +665,7 @@ def test_c3_llama7b_forward_leaf_commitments_and_tree(T, ctx, node_srs):
     grid = (layers, 3)
     srs_by_shape = {}
     for s in set(shapes3):
-        srs_by_shape[s] = ctx.setup_from_trapdoor(TAU_BYTES, s, T.TC_SRS_SUFFIX)
+        srs_by_shape[s] = ctx.setup_from_trapdoor(TAU_BYTES, s, T.TC_SRS_SUFFIX | T.TC_SRS_OPEN_TABLE)
         pps(s)                                             # the oracle's parameters, before the pool needs them
     leaves_q, leaves_d, leaf_srs, leaf_shapes = [], [], [], []
     want_commit = []
@@ -795,7 +807,7 @@ def test_c5_batched_requests(T, ctx, node_srs):
           % (requests, layers, openings, min(oracle_requests, requests)), flush=True)
     shapes3 = tc_inputs.c3_shapes(cfg)
     grid = (layers, 3)
-    srs_by_shape = {s: ctx.setup_from_trapdoor(TAU_BYTES, s, T.TC_SRS_SUFFIX) for s in set(shapes3)}
+    srs_by_shape = {s: ctx.setup_from_trapdoor(TAU_BYTES, s, T.TC_SRS_SUFFIX | T.TC_SRS_OPEN_TABLE) for s in set(shapes3)}
     for s in set(shapes3):
         pps(s)
     watch.lap("SRS tables")

@@ -671,3 +671,71 @@ def test_emulated_field_ops(emu):
         return out
 
     check_field_arithmetic(run, 200, 100)
+
+
+def test_emulated_open_with_the_opening_table(emu, node_srs):
+    """TC_SRS_OPEN_TABLE: the table's points are U[kappa, t] = sum_(k != kappa) S[k, t] / (zeta_k - zeta_kappa) (checked
+    against the oracle's group arithmetic on the Lagrange SRS), openings through it equal the oracle's byte for byte
+    (int16 and int8, corner and interior positions, equal rows), the table survives export / import, and a tensors
+    tree keeps the row commitments of a leaf between opening calls and drops them when the leaf is updated."""
+    B = T.binding
+    shape = (8, 2048)
+    pp = pps(shape)
+    srs = emu.setup_from_trapdoor(TAU_BYTES, shape, T.TC_SRS_SUFFIX | T.TC_SRS_OPEN_TABLE)
+    data = srs.export()
+    assert len(data) == 56 + 96 * (2 * 8 * 2048 + 2048)
+    # three entries of U from the definition, with the oracle's scalars: U[kappa, t] = [l_t(tau_2) sum_k l_k(tau_1) / (k - kappa)] G
+    for kappa, t in ((0, 0), (5, 1000), (7, 2047)):
+        g = sum(pp.ell[0][k] * ec.fr_inv(k - kappa) for k in range(8) if k != kappa) % R
+        want = ec.mul(g * pp.ell[1][t] % R, ec.G1)
+        off = 56 + 96 * (8 * 2048 + 2048 + kappa * 2048 + t)
+        assert data[off : off + 96] == ec.g1_to_bytes(want)
+    back = emu.srs_import(data)
+    X16 = tc_inputs.int16_uniform(shape, 3, -32768, 32767)
+    X16[0, 0], X16[7, 2047], X16[3, 77] = -32768, 32767, -32768
+    X16[4, :] = X16[3, :]
+    X8 = tc_inputs.int8_uniform(shape, 4)
+    for s in (srs, back):
+        for X, dt in ((X16, T.TC_I16), (X8, T.TC_I8)):
+            for kappa in [(3, 77), (0, 0), (7, 2047)]:
+                y, pi = emu.open(s, X, dt, kappa)
+                yo, po = tc.open_(pp, X, kappa)
+                assert y == ec.fr_to_bytes(yo) and pi == [ec.g1_to_bytes(p) for p in po]
+    back.close()
+    with pytest.raises(T.TcError) as e:
+        emu.setup_from_trapdoor(TAU_BYTES, (64,), T.TC_SRS_OPEN_TABLE)
+    assert e.value.code == B.TC_ERR_SHAPE
+    # a tensors tree: two leaves share the shape; several openings per call and over several calls; then an update
+    plain = emu.setup_from_trapdoor(TAU_BYTES, shape, T.TC_SRS_SUFFIX)
+    leaves = [X16.copy(), tc_inputs.int16_uniform(shape, 8), tc_inputs.int16_uniform(shape, 9)]
+    for lsrs in ([srs, srs, plain], [srs, srs, srs]):
+        tree = emu.terkle_build_tensors(node_srs, lsrs, leaves, [T.TC_I16] * 3, (3, 1), (2, 2))
+        ot_leaf = [tc.commit(pp, l) for l in leaves]
+        otree = terkle.build(pps, [terkle.phi(c) for c in ot_leaf], (3, 1), (2, 2))
+
+        def oracle_proof(leaf, inner, tensor):
+            steps = terkle.open_path(pps, otree, (3, 1), (2, 2), leaf)
+            k, y, pi, _ = steps[-1]
+            steps[-1] = (k, y, pi, tc.commit(pp, tensor))
+            yo, po = tc.open_(pp, tensor, inner)
+            steps.append((inner, yo, po, None))
+            return serialize_steps(steps)
+
+        assert tree.root == ec.g1_to_bytes(otree.root)
+        calls = [[((0, 0), (3, 77)), ((1, 0), (0, 5)), ((0, 0), (6, 2000)), ((2, 0), (2, 2))],     # leaf 0 twice in one call
+                 [((0, 0), (1, 1)), ((1, 0), (7, 2047))]]                                          # later call: kept rows
+        for batch in calls:
+            got = tree.open_batch([b[0] for b in batch], [b[1] for b in batch])
+            for (leaf, inner), proof in zip(batch, got):
+                assert proof == oracle_proof(leaf, inner, leaves[leaf[0]]), (leaf, inner)
+        # leaf 0 changes: its kept row commitments must not be used again
+        leaves[0][6, 2000] += 5
+        tree.update((0, 0), 5, (6, 2000))
+        ot_leaf[0] = tc.commit(pp, leaves[0])
+        otree = terkle.build(pps, [terkle.phi(c) for c in ot_leaf], (3, 1), (2, 2))
+        assert tree.root == ec.g1_to_bytes(otree.root)
+        assert tree.open((0, 0), (6, 1999)) == oracle_proof((0, 0), (6, 1999), leaves[0])
+        leaves[0][6, 2000] -= 5
+        tree.close()
+    plain.close()
+    srs.close()
