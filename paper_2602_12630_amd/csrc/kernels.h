@@ -20,7 +20,8 @@
 namespace tc {
 
 enum { DT_I8 = 1, DT_I16 = 2, DT_FR = 3, DT_F16 = 4,
-       DT_DIFF8 = 5, DT_DIFF16 = 6 /* internal: difference of two int8 / int16 arrays, two 9-bit signed digits */ };
+       DT_DIFF8 = 5, DT_DIFF16 = 6, /* internal: difference of two int8 / int16 arrays, two 9-bit signed digits */
+       DT_SPLIT16 = 7 /* internal: an int16 array as two 8-bit signed digits (problems too short for 32768 buckets) */ };
 
 struct alignas(16) fr_plain {           /* canonical (non-Montgomery) Fr value, 8 limbs */
     uint32_t l[8];
@@ -332,7 +333,7 @@ TC_DEV void tile_terms(const TileProblem& P, int dtype, uint64_t lo, uint64_t hi
     if (lo >= hi) return;                  /* a tile past the end of its problem */
     uint64_t rest = lo;
     uint32_t esz = dtype == DT_I8 ? 1u : 2u;
-    if (WIDE && !P.sub && (dtype == DT_I8 || dtype == DT_I16) && (((uintptr_t)P.scalars + lo * esz) & 15u) == 0) {
+    if (WIDE && !P.sub && (dtype == DT_I8 || dtype == DT_I16 || dtype == DT_SPLIT16) && (((uintptr_t)P.scalars + lo * esz) & 15u) == 0) {
         uint32_t per = 16u / esz;
         uint64_t chunks = (hi - lo) / per;
         const Words16* src = (const Words16*)((const uint8_t*)P.scalars + lo * esz);
@@ -531,6 +532,66 @@ struct ScanWrite {
         if (ch == nchunks - 1) {
             start[n] = tot_a[nchunks];
             lstart[n] = tot_b[nchunks];
+        }
+    }
+};
+/* The same prefix sums in one launch when there are few buckets (n <= MAX_N): one workgroup, every lane owns
+ * ceil(n / BLOCK) consecutive buckets.  The three launches above take about 100 us for 32768 buckets, most of it the
+ * serial loops of their few lanes; a flat commitment of 2^21 terms runs the scan once per pass. */
+struct ScanSmall {
+    static constexpr int BLOCK = 1024;
+    static constexpr int PHASES = 3;
+    static constexpr size_t LDS_BYTES = 3 * BLOCK * sizeof(uint32_t);
+    static constexpr uint32_t MAX_N = 65536;
+    const uint32_t* cnt;
+    uint32_t n, L;
+    uint32_t* start;       /* n + 1 */
+    uint32_t* lstart;      /* n + 1 */
+    uint32_t* zero_me;     /* optional */
+    uint32_t* total_a;     /* one value each: sum of cnt, sum of ceil(cnt / L), largest cnt */
+    uint32_t* total_b;
+    uint32_t* total_max;
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t, uint8_t* lds) const {
+        uint32_t* sa = (uint32_t*)lds;
+        uint32_t* sb = sa + BLOCK;
+        uint32_t* sm = sb + BLOCK;
+        uint32_t per = (n + BLOCK - 1) / BLOCK;
+        uint32_t lo = lane * per < n ? lane * per : n;
+        uint32_t hi = lo + per < n ? lo + per : n;
+        if (ph == 0) {
+            uint32_t a = 0, b = 0, mx = 0;
+            for (uint32_t i = lo; i < hi; ++i) {
+                uint32_t v = cnt[i];
+                a += v;
+                b += (v + L - 1) / L;
+                mx = v > mx ? v : mx;
+            }
+            sa[lane] = a; sb[lane] = b; sm[lane] = mx;
+        } else if (ph == 1) {
+            if (lane == 0) {
+                uint32_t a = 0, b = 0, mx = 0;
+                for (uint32_t i = 0; i < (uint32_t)BLOCK; ++i) {
+                    uint32_t va = sa[i], vb = sb[i];
+                    sa[i] = a; sb[i] = b;
+                    a += va; b += vb;
+                    mx = sm[i] > mx ? sm[i] : mx;
+                }
+                *total_a = a;
+                *total_b = b;
+                *total_max = mx;
+                start[n] = a;
+                lstart[n] = b;
+            }
+        } else {
+            uint32_t a = sa[lane], b = sb[lane];
+            for (uint32_t i = lo; i < hi; ++i) {
+                uint32_t v = cnt[i];
+                start[i] = a;
+                lstart[i] = b;
+                a += v;
+                b += (v + L - 1) / L;
+                if (zero_me) zero_me[i] = 0;
+            }
         }
     }
 };
@@ -909,7 +970,8 @@ struct SmallWindowReduce256 {
     static constexpr int BLOCK = 64;
     static constexpr int PHASES = 11;
     static constexpr size_t LDS_BYTES = 2 * BLOCK * sizeof(g1_xyzz);
-    const g1_xyzz* bucket;      /* windows * 256 */
+    const g1_xyzz* bucket;      /* windows * nb */
+    uint32_t nb;                /* buckets per window: 256, or 128 (the upper eight rows of the matrix are then empty) */
     uint32_t n_windows;
     g1_xyzz* out;               /* per window */
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
@@ -921,11 +983,11 @@ struct SmallWindowReduce256 {
         if (ph == 0) {
             g1_xyzz acc = xyzz_identity();
             if (live) {
-                const g1_xyzz* B = bucket + (uint64_t)w * 256u;
-                const g1_xyzz* p = j < 16 ? B + j * 16u : B + (j - 16u);      /* a row, or a column */
+                const g1_xyzz* B = bucket + (uint64_t)w * nb;
+                uint32_t first = j < 16 ? j * 16u : j - 16u;                  /* a row, or a column */
                 uint32_t step = j < 16 ? 1u : 16u;
-                acc = p[0];
-                for (uint32_t t = 1; t < 16; ++t) acc = xyzz_add(acc, p[t * step]);
+                if (first < nb) acc = B[first];
+                for (uint32_t t = 1; t < 16 && first + t * step < nb; ++t) acc = xyzz_add(acc, B[first + t * step]);
             }
             buf1[lane] = acc;
         } else if (ph <= 4) {                /* suffix sums within each family of 16 */

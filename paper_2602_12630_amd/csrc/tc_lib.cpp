@@ -1144,6 +1144,11 @@ static const uint64_t SPLIT_LEVEL_LANES = 131072;
 static int scan_counts(tc_ctx* ctx, const uint32_t* cnt, uint32_t n, uint32_t L, uint32_t* start, uint32_t* lstart,
                        uint32_t* zero_me, uint32_t* tot_a, uint32_t* tot_b, uint32_t* tot_max) {
     uint32_t nchunks = (n + SCAN_CHUNK - 1) / SCAN_CHUNK;
+    if (n <= ScanSmall::MAX_N) {          /* few buckets: one workgroup, one launch; the totals land where the chunked scan leaves them */
+        RT((launch_coop<ScanSmall::BLOCK>(1, ctx->stream,
+                                          ScanSmall{cnt, n, L, start, lstart, zero_me, tot_a + nchunks, tot_b + nchunks, tot_max + nchunks})));
+        return TC_OK;
+    }
     RT(rt::launch<64>(nchunks, ctx->stream, ScanChunkTotals{cnt, n, L, tot_a, tot_b, tot_max}));
     RT((launch_coop<ScanChunkOffsets::BLOCK>(1, ctx->stream, ScanChunkOffsets{nchunks, tot_a, tot_b, tot_max})));
     RT(rt::launch<64>(nchunks, ctx->stream, ScanWrite{cnt, n, L, tot_a, tot_b, nchunks, start, lstart, zero_me}));
@@ -1155,9 +1160,9 @@ static const int ROWCOL_PACKED_WINDOWS = 8;
 
 /* sum_k k B_k for every window of `bucket` (W windows of nb buckets) -> wsum[W] */
 static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb, g1_xyzz* wsum) {
-    if (nb == 256 && W >= 512) {
+    if ((nb == 256 || nb == 128) && W >= 512) {
         /* many small windows (row problems of openings): throughput matters, not depth */
-        RT((launch_coop<SmallWindowReduce256::BLOCK>(((uint32_t)W + 1) / 2, ctx->stream, SmallWindowReduce256{bucket, (uint32_t)W, wsum})));
+        RT((launch_coop<SmallWindowReduce256::BLOCK>(((uint32_t)W + 1) / 2, ctx->stream, SmallWindowReduce256{bucket, nb, (uint32_t)W, wsum})));
         return TC_OK;
     }
     if (nb == 128 || nb == 256) {
@@ -1220,6 +1225,7 @@ static void msm_config(int dtype, uint64_t n, int* W, int* c) {
     if (dtype == TC_I8) { *W = 1; *c = 8; }
     else if (dtype == TC_I16) { *W = 1; *c = 16; }
     else if (dtype == DT_DIFF8 || dtype == DT_DIFF16) { *W = 2; *c = 9; }
+    else if (dtype == DT_SPLIT16) { *W = 2; *c = 8; }
     else { *c = n >= 32768 ? 16 : 8; *W = 256 / *c; }
 }
 /* `count` problems of one scalar type and window plan, run through shared launches: the buckets of
@@ -1271,7 +1277,9 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     uint32_t L1 = (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(4, (items + target_lanes - 1) / target_lanes));
     L1 = (uint32_t)std::min<uint64_t>(L1, std::max<uint64_t>(4, (items + 2 * (uint64_t)nbk - 1) / (2 * (uint64_t)nbk)));
     if (ctx->static_mode) L1 = STATIC_L1;      /* fewer, longer sub-runs: the partial sums must fit the static scratch */
-    const uint32_t L2 = 16;
+    /* fan-in of the middle passes: with few buckets a pass costs the chain of additions of one lane, and shorter
+     * chains in more passes win (flat commitment of 2^21 terms: 2.74 / 2.70 / 2.59 / 3.08 ms with 16 / 8 / 4 / 2) */
+    const uint32_t L2 = nbk <= ScanSmall::MAX_N ? 4 : 16;
 
     uint32_t max_count = 0;        /* largest bucket: fixes how many shrinking passes are needed */
     if (dtype != TC_FR) {
@@ -1295,6 +1303,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         TRY(upload_small(ctx, d_prob, h_prob, sizeof(TileProblem) * (size_t)count));
         uint32_t groups = (uint32_t)count * n_wg;
         if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, CountTile<128>{d_prob, dtype, W, c, n_wg, M})));
+        else if (nbk_pp == 256) RT((launch_coop<1024>(groups, ctx->stream, CountTile<256>{d_prob, dtype, W, c, n_wg, M})));
         else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, CountTile<512>{d_prob, dtype, W, c, n_wg, M})));
         else if (nbk_pp == 32768) RT((launch_coop<1024>(groups, ctx->stream, CountTile<32768>{d_prob, dtype, W, c, n_wg, M})));
         else return fail(ctx, TC_ERR_STATE, "internal: unsupported key count");
@@ -1302,6 +1311,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, nullptr, tot_a, tot_b, tot_max));
         if (!ctx->static_mode) RT(rt::memcpy_d2h(&max_count, tot_max + nchunks, 4, ctx->stream));
         if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<128>{d_prob, dtype, W, c, n_wg, M, start, sorted})));
+        else if (nbk_pp == 256) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<256>{d_prob, dtype, W, c, n_wg, M, start, sorted})));
         else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<512>{d_prob, dtype, W, c, n_wg, M, start, sorted})));
         else RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<32768>{d_prob, dtype, W, c, n_wg, M, start, sorted})));
     } else {
@@ -1560,6 +1570,8 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
             size_t esz = dtype_size(dt);
             const uint8_t* base = (const uint8_t*)spec[o].scalars + offset * esz;
             int two_digits = dt == TC_I8 ? DT_DIFF8 : DT_DIFF16;
+            /* plain rows of the tensor (the table's route) are one 8-bit digit (int8) or two (int16) per entry */
+            int plain_digits = dt == TC_I8 ? TC_I8 : DT_SPLIT16;
             if (J.use_table) {
                 for (size_t t = 0; t < tensors.size() && J.tensor < 0; ++t)
                     if (tensors[t].srs == srs && tensors[t].scalars == spec[o].scalars) J.tensor = (int)t;
@@ -1575,7 +1587,7 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
                             P.scalars = base + (uint64_t)k * J.inner * esz;
                             P.n = J.inner;
                             row_prob.push_back(P);
-                            row_dtype.push_back(two_digits);
+                            row_dtype.push_back(plain_digits);
                         }
                     }
                     J.tensor = (int)tensors.size();
@@ -1589,7 +1601,7 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
                 P.n = J.inner;
                 J.small0 = (int)small_prob.size();
                 small_prob.push_back(P);
-                small_dtype.push_back(two_digits);
+                small_dtype.push_back(plain_digits);
             } else if (J.by_rows) {
                 for (uint32_t j = 0; j + 1 < J.d; ++j) {
                     uint32_t k = j < J.kap ? j : j + 1;
