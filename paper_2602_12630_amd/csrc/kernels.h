@@ -862,52 +862,67 @@ struct WeightedBlockSum {
     }
 };
 
-/* Row and column sums of a window's 128 x 256 bucket matrix (bucket k = 256 h + l + 1): workgroup g of
- * window w sums row h = g (g < 128: the 256 buckets with that high part) or column l = g - 128 (the 128
- * buckets with that low part), pairwise through LDS.  With R_h and C_l,
+/* Bucket reduction of a window of 32768 buckets seen as a 128 x 256 matrix (bucket k = 256 h + l + 1).  With the
+ * row sums R_h (the 256 buckets with that high part) and the column sums C_l (the 128 buckets with that low part),
  *     sum_k k B_k = 256 sum_h h R_h + sum_l (l + 1) C_l,
  * one plain addition per bucket and direction instead of a weighted scan over all of them. */
-struct RowColSums {
-    static constexpr int BLOCK = 64;
-    static constexpr int PHASES = 8;           /* serial part, 6 halving steps, store */
-    static constexpr size_t LDS_BYTES = BLOCK * sizeof(g1_xyzz);
-    static constexpr uint32_t GROUPS = 128 + 256;
-    const g1_xyzz* bucket;      /* windows * 32768 */
-    g1_xyzz* rows;              /* windows * 256: entries 128..255 of a window are the identity */
-    g1_xyzz* cols;              /* windows * 256 */
-    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
-        g1_xyzz* buf = (g1_xyzz*)lds;
-        uint32_t w = wg / GROUPS, g = wg % GROUPS;
+/* Launches with few windows (a lone commitment), where nothing but depth counts: every
+ * sum is a cooperative sum whose additions are shared by the four waves of a workgroup (CoopReduce), and the
+ * weights are taken bit by bit.  With R_h and C_l the row and column sums of the 128 x 256 bucket matrix,
+ *     sum_k k B_k = sum_(j=0..8) 2^j X_j + 256 sum_(j=0..6) 2^j Y_j,
+ *     X_j = sum of the C_l with bit j of l + 1 set,   Y_j = sum of the R_h with bit j of h set:
+ * one launch for the 384 row and column sums, one for the 16 bit sums, 16 independent chains of at most 14
+ * doublings, one sum of 16 points. */
+struct RowColSrc {             /* workgroup (w, g): g < 128 row g, else column g - 128 */
+    const g1_xyzz* bucket;     /* windows * 32768 */
+    g1_xyzz* rows;             /* windows * 256 (128 used) */
+    g1_xyzz* cols;             /* windows * 256 */
+    TC_DEV uint32_t count(uint32_t wg) const { return wg % 384u < 128u ? 256u : 128u; }
+    TC_DEV g1_xyzz load(uint32_t wg, uint32_t i) const {
+        uint32_t w = wg / 384u, g = wg % 384u;
         const g1_xyzz* base = bucket + (uint64_t)w * 32768u;
-        if (ph == 0) {
-            g1_xyzz acc;
-            if (g < 128) {                     /* row g: lane takes 4 neighbouring buckets */
-                const g1_xyzz* p = base + g * 256u + lane * 4u;
-                acc = p[0];
-                for (int i = 1; i < 4; ++i) acc = xyzz_add(acc, p[i]);
-            } else {                           /* column g - 128: lane takes 2 of the 128 rows */
-                const g1_xyzz* p = base + (g - 128);
-                acc = xyzz_add(p[(lane * 2u) * 256u], p[(lane * 2u + 1u) * 256u]);
-            }
-            buf[lane] = acc;
-            return;
-        }
-        if (ph <= 6) {
-            uint32_t stride = 32u >> (ph - 1);
-            if (lane < stride) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
-            return;
-        }
-        if (lane == 0) {
-            if (g < 128) rows[(uint64_t)w * 256 + g] = buf[0];
-            else cols[(uint64_t)w * 256 + (g - 128)] = buf[0];
-        } else if (lane == 1 && g < 128) {
-            rows[(uint64_t)w * 256 + 128 + g] = xyzz_identity();
-        }
+        return g < 128u ? base[g * 256u + i] : base[i * 256u + (g - 128u)];
+    }
+    TC_DEV void store(uint32_t wg, const g1_xyzz& r) const {
+        uint32_t w = wg / 384u, g = wg % 384u;
+        if (g < 128u) rows[(uint64_t)w * 256u + g] = r; else cols[(uint64_t)w * 256u + (g - 128u)] = r;
     }
 };
-/* The same sums for launches with many windows, where SIMD time matters more than depth: four rows (columns) per
- * wave, sixteen lanes each, 16 (8) buckets per lane one after the other and four halving steps -- twice the depth of
- * RowColSums, 2.8 times less SIMD time. */
+struct BitSumSrc {             /* workgroup (w, j): j < 9 the columns with bit j of l + 1, else the rows with bit j - 9 of h */
+    const g1_xyzz* rows;
+    const g1_xyzz* cols;
+    g1_xyzz* out;              /* windows * 16 */
+    TC_DEV uint32_t count(uint32_t wg) const { return wg % 16u < 9u ? 256u : 128u; }
+    TC_DEV g1_xyzz load(uint32_t wg, uint32_t i) const {
+        uint32_t w = wg / 16u, j = wg % 16u;
+        if (j < 9u) return (((i + 1u) >> j) & 1u) ? cols[(uint64_t)w * 256u + i] : xyzz_identity();
+        return ((i >> (j - 9u)) & 1u) ? rows[(uint64_t)w * 256u + i] : xyzz_identity();
+    }
+    TC_DEV void store(uint32_t wg, const g1_xyzz& r) const { out[wg] = r; }
+};
+struct BitSumScale {           /* lane (w, j): 2^j X_j for the columns, 2^(8 + j - 9) Y_(j-9) for the rows */
+    const g1_xyzz* in;
+    g1_xyzz* out;
+    TC_DEV void operator()(uint32_t t) const {
+        uint32_t j = t % 16u;
+        uint32_t e = j < 9u ? j : j - 9u + 8u;
+        g1_xyzz p = in[t];
+        for (uint32_t i = 0; i < e; ++i) p = xyzz_dbl(p);
+        out[t] = p;
+    }
+};
+struct GroupSumSrc {           /* out[g] = sum of in[g * group .. (g + 1) * group), group <= 256 */
+    const g1_xyzz* in;
+    uint32_t group;
+    g1_xyzz* out;
+    TC_DEV uint32_t count(uint32_t) const { return group; }
+    TC_DEV g1_xyzz load(uint32_t g, uint32_t i) const { return in[(uint64_t)g * group + i]; }
+    TC_DEV void store(uint32_t g, const g1_xyzz& r) const { out[g] = r; }
+};
+
+/* Row and column sums for launches with many windows, where SIMD time matters more than depth: four rows (columns)
+ * per wave, sixteen lanes each, 16 (8) buckets per lane one after the other and four halving steps; the weighted
+ * sums of the 256 column sums and 128 row sums then go through WeightedBlockSum<256> and RowColFinish. */
 struct RowColSumsPacked {
     static constexpr int BLOCK = 64;
     static constexpr int PHASES = 6;           /* serial part, 4 halving steps, store */

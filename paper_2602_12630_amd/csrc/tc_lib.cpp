@@ -1177,12 +1177,22 @@ static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb
     /* 128 x 256 bucket matrix: row / column sums, then two small weighted sums per window */
     WS(rows, g1_xyzz, 256ull * W);
     WS(cols, g1_xyzz, 256ull * W);
+    if (W < ROWCOL_PACKED_WINDOWS) {
+        /* few windows: depth is the cost; cooperative sums and bit-wise weights */
+        typedef CoopReduce<RowColSrc> RowCol;
+        typedef CoopReduce<BitSumSrc> BitSum;
+        typedef CoopReduce<GroupSumSrc> GroupSum;
+        WS(bits, g1_xyzz, 16u * (uint32_t)W);
+        WS(scaled, g1_xyzz, 16u * (uint32_t)W);
+        RT((launch_coop<RowCol::BLOCK>(384u * (uint32_t)W, ctx->stream, RowCol{RowColSrc{bucket, rows, cols}})));
+        RT((launch_coop<BitSum::BLOCK>(16u * (uint32_t)W, ctx->stream, BitSum{BitSumSrc{rows, cols, bits}})));
+        RT(rt::launch<64>(16u * (uint32_t)W, ctx->stream, BitSumScale{bits, scaled}));
+        RT((launch_coop<GroupSum::BLOCK>((uint32_t)W, ctx->stream, GroupSum{GroupSumSrc{scaled, 16u, wsum}})));
+        return TC_OK;
+    }
     WS(w_rc, g1_xyzz, 2u * (uint32_t)W);     /* [0, W): columns, [W, 2W): rows */
     WS(s_rc, g1_xyzz, 2u * (uint32_t)W);
-    if (W >= ROWCOL_PACKED_WINDOWS)
-        RT((launch_coop<RowColSumsPacked::BLOCK>((uint32_t)W * RowColSumsPacked::GROUPS, ctx->stream, RowColSumsPacked{bucket, rows, cols})));
-    else
-        RT((launch_coop<RowColSums::BLOCK>((uint32_t)W * RowColSums::GROUPS, ctx->stream, RowColSums{bucket, rows, cols})));
+    RT((launch_coop<RowColSumsPacked::BLOCK>((uint32_t)W * RowColSumsPacked::GROUPS, ctx->stream, RowColSumsPacked{bucket, rows, cols})));
     RT((launch_coop<256>(2u * (uint32_t)W, ctx->stream,
                          WeightedBlockSum<256>{cols, 256u * (uint32_t)W, w_rc, s_rc, rows, (uint32_t)W})));
     RT(rt::launch<64>((uint32_t)W, ctx->stream, RowColFinish{w_rc + W, s_rc + W, w_rc, wsum}));
