@@ -540,8 +540,9 @@ struct ScanWrite {
  * serial loops of their few lanes; a flat commitment of 2^21 terms runs the scan once per pass. */
 struct ScanSmall {
     static constexpr int BLOCK = 1024;
-    static constexpr int PHASES = 3;
-    static constexpr size_t LDS_BYTES = 3 * BLOCK * sizeof(uint32_t);
+    static constexpr int GROUP = 32;           /* lanes per group of the two-level scan over the lanes' sums */
+    static constexpr int PHASES = 5;
+    static constexpr size_t LDS_BYTES = (3 * BLOCK + 2 * (BLOCK / GROUP)) * sizeof(uint32_t);
     static constexpr uint32_t MAX_N = 65536;
     const uint32_t* cnt;
     uint32_t n, L;
@@ -555,10 +556,12 @@ struct ScanSmall {
         uint32_t* sa = (uint32_t*)lds;
         uint32_t* sb = sa + BLOCK;
         uint32_t* sm = sb + BLOCK;
+        uint32_t* ga = sm + BLOCK;             /* per group of lanes */
+        uint32_t* gb = ga + BLOCK / GROUP;
         uint32_t per = (n + BLOCK - 1) / BLOCK;
         uint32_t lo = lane * per < n ? lane * per : n;
         uint32_t hi = lo + per < n ? lo + per : n;
-        if (ph == 0) {
+        if (ph == 0) {                         /* every lane: sums over its own buckets */
             uint32_t a = 0, b = 0, mx = 0;
             for (uint32_t i = lo; i < hi; ++i) {
                 uint32_t v = cnt[i];
@@ -567,14 +570,25 @@ struct ScanSmall {
                 mx = v > mx ? v : mx;
             }
             sa[lane] = a; sb[lane] = b; sm[lane] = mx;
-        } else if (ph == 1) {
-            if (lane == 0) {
+        } else if (ph == 1) {                  /* one lane per group: exclusive prefix inside the group, the group's totals */
+            if (lane < (uint32_t)(BLOCK / GROUP)) {
                 uint32_t a = 0, b = 0, mx = 0;
-                for (uint32_t i = 0; i < (uint32_t)BLOCK; ++i) {
+                for (uint32_t i = lane * GROUP; i < (lane + 1) * GROUP; ++i) {
                     uint32_t va = sa[i], vb = sb[i];
                     sa[i] = a; sb[i] = b;
                     a += va; b += vb;
                     mx = sm[i] > mx ? sm[i] : mx;
+                }
+                ga[lane] = a; gb[lane] = b; sm[lane * GROUP] = mx;
+            }
+        } else if (ph == 2) {                  /* one lane: exclusive prefix over the groups, the grand totals */
+            if (lane == 0) {
+                uint32_t a = 0, b = 0, mx = 0;
+                for (uint32_t g = 0; g < (uint32_t)(BLOCK / GROUP); ++g) {
+                    uint32_t va = ga[g], vb = gb[g];
+                    ga[g] = a; gb[g] = b;
+                    a += va; b += vb;
+                    mx = sm[g * GROUP] > mx ? sm[g * GROUP] : mx;
                 }
                 *total_a = a;
                 *total_b = b;
@@ -582,6 +596,9 @@ struct ScanSmall {
                 start[n] = a;
                 lstart[n] = b;
             }
+        } else if (ph == 3) {
+            sa[lane] += ga[lane / GROUP];
+            sb[lane] += gb[lane / GROUP];
         } else {
             uint32_t a = sa[lane], b = sb[lane];
             for (uint32_t i = lo; i < hi; ++i) {
@@ -900,15 +917,94 @@ struct BitSumSrc {             /* workgroup (w, j): j < 9 the columns with bit j
     }
     TC_DEV void store(uint32_t wg, const g1_xyzz& r) const { out[wg] = r; }
 };
-struct BitSumScale {           /* lane (w, j): 2^j X_j for the columns, 2^(8 + j - 9) Y_(j-9) for the rows */
+/* lane (w, j): 2^j X_j for the columns, 2^(8 + j - 9) Y_(j-9) for the rows.  Up to 14 doublings in a row and only
+ * 16 chains per window: the nine products of an XYZZ doubling are shared by the four waves of a workgroup in three
+ * levels (V = (2Y)^2, A = X^2 | W = 2Y V, S = X V, (3A)^2, V ZZ | 3A (S - X3), W Y, W ZZZ), operands in LDS, a barrier
+ * after every level and one more for the subtraction that ends the doubling; a chain that has done its own number
+ * of doublings no longer takes the results.  ZZ = 0 (the identity) reproduces itself. */
+struct BitSumScale {
+    static constexpr int BLOCK = 256;
+    static constexpr int MAX_DOUBLINGS = 14;
+    enum { FX, FY, FZZ, FZZZ, FU, FV, FM, FW, FS, FMM, FT, FWY, FZZN, FZZZN, FX3, NFIELD };
+    static constexpr size_t LDS_BYTES = (size_t)NFIELD * 3 * 64 * 16;
+    static constexpr int PHASES = 1 + 4 * MAX_DOUBLINGS + 1;
     const g1_xyzz* in;
+    uint32_t n;                /* chains: 16 per window */
     g1_xyzz* out;
-    TC_DEV void operator()(uint32_t t) const {
+    TC_DEV static uint32_t doublings(uint32_t t) {
         uint32_t j = t % 16u;
-        uint32_t e = j < 9u ? j : j - 9u + 8u;
-        g1_xyzz p = in[t];
-        for (uint32_t i = 0; i < e; ++i) p = xyzz_dbl(p);
-        out[t] = p;
+        return j < 9u ? j : j - 9u + 8u;
+    }
+    TC_DEV static fp_t ld(const uint8_t* lds, int f, uint32_t l) {
+        const Quad16* q = (const Quad16*)lds;
+        fp_t r;
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            Quad16 t = q[(f * 3 + i) * 64 + l];
+            r.l[4 * i] = t.v[0]; r.l[4 * i + 1] = t.v[1]; r.l[4 * i + 2] = t.v[2]; r.l[4 * i + 3] = t.v[3];
+        }
+        return r;
+    }
+    TC_DEV static void st(uint8_t* lds, int f, uint32_t l, const fp_t& x) {
+        Quad16* q = (Quad16*)lds;
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            Quad16 t;
+            t.v[0] = x.l[4 * i]; t.v[1] = x.l[4 * i + 1]; t.v[2] = x.l[4 * i + 2]; t.v[3] = x.l[4 * i + 3];
+            q[(f * 3 + i) * 64 + l] = t;
+        }
+    }
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        uint32_t wave = lane >> 6, l = lane & 63u;
+        uint32_t t = wg * 64u + l;
+        bool live = t < n;
+        if (ph == 0) {
+            if (wave != 0) return;
+            g1_xyzz p = live ? in[t] : xyzz_identity();
+            st(lds, FX, l, p.X); st(lds, FY, l, p.Y); st(lds, FZZ, l, p.ZZ); st(lds, FZZZ, l, p.ZZZ);
+            st(lds, FU, l, fp_dbl(p.Y));
+            return;
+        }
+        if (ph == PHASES - 1) {
+            if (wave != 0 || !live) return;
+            g1_xyzz p;
+            p.X = ld(lds, FX, l); p.Y = ld(lds, FY, l); p.ZZ = ld(lds, FZZ, l); p.ZZZ = ld(lds, FZZZ, l);
+            out[t] = p;
+            return;
+        }
+        uint32_t d = (uint32_t)(ph - 1) / 4u + 1u;          /* the d-th doubling is in the making */
+        int level = (ph - 1) % 4;
+        if (level == 0) {
+            if (wave == 0) {
+                st(lds, FV, l, fp_sqr_lat(ld(lds, FU, l)));
+            } else if (wave == 1) {
+                fp_t A = fp_sqr_lat(ld(lds, FX, l));
+                st(lds, FM, l, fp_add(fp_dbl(A), A));
+            }
+        } else if (level == 1) {
+            if (wave == 0) st(lds, FW, l, fp_mul_lat(ld(lds, FU, l), ld(lds, FV, l)));
+            else if (wave == 1) st(lds, FS, l, fp_mul_lat(ld(lds, FX, l), ld(lds, FV, l)));
+            else if (wave == 2) st(lds, FMM, l, fp_sqr_lat(ld(lds, FM, l)));
+            else st(lds, FZZN, l, fp_mul_lat(ld(lds, FV, l), ld(lds, FZZ, l)));
+        } else if (level == 2) {
+            if (wave == 0) {
+                fp_t S = ld(lds, FS, l);
+                fp_t X3 = fp_sub(fp_sub(ld(lds, FMM, l), S), S);
+                st(lds, FX3, l, X3);
+                st(lds, FT, l, fp_mul_lat(ld(lds, FM, l), fp_sub(S, X3)));
+            } else if (wave == 1) {
+                st(lds, FWY, l, fp_mul_lat(ld(lds, FW, l), ld(lds, FY, l)));
+            } else if (wave == 2) {
+                st(lds, FZZZN, l, fp_mul_lat(ld(lds, FW, l), ld(lds, FZZZ, l)));
+            }
+        } else if (wave == 0 && live && d <= doublings(t)) {
+            fp_t Y3 = fp_sub(ld(lds, FT, l), ld(lds, FWY, l));
+            st(lds, FX, l, ld(lds, FX3, l));
+            st(lds, FY, l, Y3);
+            st(lds, FU, l, fp_dbl(Y3));
+            st(lds, FZZ, l, ld(lds, FZZN, l));
+            st(lds, FZZZ, l, ld(lds, FZZZN, l));
+        }
     }
 };
 struct GroupSumSrc {           /* out[g] = sum of in[g * group .. (g + 1) * group), group <= 256 */

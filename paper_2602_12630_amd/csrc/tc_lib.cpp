@@ -1186,7 +1186,7 @@ static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb
         WS(scaled, g1_xyzz, 16u * (uint32_t)W);
         RT((launch_coop<RowCol::BLOCK>(384u * (uint32_t)W, ctx->stream, RowCol{RowColSrc{bucket, rows, cols}})));
         RT((launch_coop<BitSum::BLOCK>(16u * (uint32_t)W, ctx->stream, BitSum{BitSumSrc{rows, cols, bits}})));
-        RT(rt::launch<64>(16u * (uint32_t)W, ctx->stream, BitSumScale{bits, scaled}));
+        RT((launch_coop<BitSumScale::BLOCK>((16u * (uint32_t)W + 63u) / 64u, ctx->stream, BitSumScale{bits, 16u * (uint32_t)W, scaled})));
         RT((launch_coop<GroupSum::BLOCK>((uint32_t)W, ctx->stream, GroupSum{GroupSumSrc{scaled, 16u, wsum}})));
         return TC_OK;
     }
