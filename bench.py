@@ -62,13 +62,16 @@ def alu_peak(ctx, T):
     out = {"unit": "32x32+64 multiply-adds/s", "formula": FORMULA_PEAK_MADS_PER_S,
            "formula_note": "256 CU x 4 SIMD x 16 lanes x 2.4 GHz / 2 (v_mad_u64_u32 at half rate)",
            "mad_u64_u32": {}, "mad_plus_carry_add": {}, "fp_mul_products_per_s": {}, "fp_sqr_squarings_per_s": {},
-           "fp_mul_f64_products_per_s": {}, "fp_sqr_f64_squarings_per_s": {}}
+           "fp_mul_f64_products_per_s": {}, "fp_sqr_f64_squarings_per_s": {},
+           "fp28_mul_products_per_s": {}, "fp28_sqr_squarings_per_s": {}}
     for w in (1, 2, 4, 8):
         out["mad_u64_u32"][str(w)] = ctx.alu_rate(B.TC_ALU_MAD, w)
         out["mad_plus_carry_add"][str(w)] = ctx.alu_rate(B.TC_ALU_MAD_CARRY, w)
     for w in (1, 2, 3, 4):
         out["fp_mul_products_per_s"][str(w)] = ctx.alu_rate(B.TC_ALU_FP_MUL, w)
         out["fp_sqr_squarings_per_s"][str(w)] = ctx.alu_rate(B.TC_ALU_FP_SQR, w)
+        out["fp28_mul_products_per_s"][str(w)] = ctx.alu_rate(B.TC_ALU_FP28_MUL, w)
+        out["fp28_sqr_squarings_per_s"][str(w)] = ctx.alu_rate(B.TC_ALU_FP28_SQR, w)
     for w in (1, 2):                                   # the FP64-pipe variants serve depth-bound chains of few waves
         out["fp_mul_f64_products_per_s"][str(w)] = ctx.alu_rate(B.TC_ALU_FP_MUL_F64, w)
         out["fp_sqr_f64_squarings_per_s"][str(w)] = ctx.alu_rate(B.TC_ALU_FP_SQR_F64, w)

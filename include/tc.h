@@ -107,13 +107,17 @@ int tc_ctx_profile_units(tc_ctx* ctx, int kind, uint64_t* units);
  *                     instructions that a limb product of the field multiplication costs;
  *   TC_ALU_FP_MUL / TC_ALU_FP_SQR   Fp products / squarings per second of the library's own routines in a chain
  *                     (one product = 300 multiply-adds, one squaring 234);
- *   TC_ALU_FP_MUL_F64 / TC_ALU_FP_SQR_F64   the same for the exact variants on the FP64 pipe. */
+ *   TC_ALU_FP_MUL_F64 / TC_ALU_FP_SQR_F64   the same for the exact variants on the FP64 pipe;
+ *   TC_ALU_FP28_MUL / TC_ALU_FP28_SQR     the same for the carry-free form of the bucket accumulation (14 signed limbs
+ *                     of 28 bits: 392 multiply-adds a product, 301 a squaring, no carry instructions). */
 #define TC_ALU_MAD 0
 #define TC_ALU_MAD_CARRY 1
 #define TC_ALU_FP_MUL 2
 #define TC_ALU_FP_SQR 3
 #define TC_ALU_FP_MUL_F64 4
 #define TC_ALU_FP_SQR_F64 5
+#define TC_ALU_FP28_MUL 6
+#define TC_ALU_FP28_SQR 7
 int tc_ctx_alu_rate(tc_ctx* ctx, int kind, int waves_per_simd, double* out_per_s);
 
 /* Test hook: one field operation per element on device arrays of raw limbs, little-endian 32-bit words, values
@@ -121,7 +125,12 @@ int tc_ctx_alu_rate(tc_ctx* ctx, int kind, int waves_per_simd, double* out_per_s
  * keep in registers (radix R = 2^384 for Fp, 2^256 for Fr).  out[i] = op(a[i], b[i]), asynchronous on the context's
  * stream:  0 a b / R (the integer product routine)   1 a^2 / R   2, 3 the same through the FP64 pipe
  *          4 R^2 / a (inverse of a Montgomery representative, a != 0)   5 a b / R in Fr   6 a + b   7 a - b
- *          8 R^2 / a in Fr.                      b is ignored by the one-operand operations but must be valid. */
+ *          8 R^2 / a in Fr
+ *          9 a b / R   10 a^2 / R   11 (a - b)(a + b) / R   12 (a - 2 b)(a - b) / R
+ *          13 ((a - b)(a + b) - b (a - b)) / R: the 28-bit-limb form of the bucket accumulation (operands re-cut, sums
+ *          and differences left unreduced with signed limbs, one product -- for 13 the difference of two products
+ *          under one reduction --, back to the canonical element).
+ * b is ignored by the one-operand operations but must be valid. */
 int tc_ctx_field_op(tc_ctx* ctx, int op, const void* d_a, const void* d_b, size_t n, void* d_out);
 
 /* ---- Setup (Def. 4.1, Setup) -- test-only trusted setup from a known trapdoor -- */

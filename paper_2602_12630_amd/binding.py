@@ -16,6 +16,7 @@ TC_LEAF_ENTRIES, TC_LEAF_TENSORS = 0, 1
 TC_PROF_BUCKET_ACC, TC_PROF_NODE_COMMIT, TC_PROF_NODE_COMMIT_UPPER, TC_PROF_VERIFY_CHAIN = 0, 1, 2, 3
 TC_MAX_ORDER, TC_MAX_STEPS = 4, 16
 TC_ALU_MAD, TC_ALU_MAD_CARRY, TC_ALU_FP_MUL, TC_ALU_FP_SQR, TC_ALU_FP_MUL_F64, TC_ALU_FP_SQR_F64 = 0, 1, 2, 3, 4, 5
+TC_ALU_FP28_MUL, TC_ALU_FP28_SQR = 6, 7
 TC_STATIC_MAX_TERMS, TC_STATIC_SCRATCH_BYTES = 1 << 18, 32 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

@@ -1,0 +1,204 @@
+/*
+ * A second form of Fp for the bucket accumulation: 14 signed limbs of 28 bits, Montgomery radix 2^392.
+ *
+ * Why: in the 12 x 32-bit form every limb product (v_mad_u64_u32) is followed by an addition that carries into the
+ * third word of the column sum, and every modular addition is a carry chain with a conditional subtraction.  With
+ * 28-bit limbs a whole column of the product scan -- 14 terms a_i b_j, 14 terms q_i p_j and the carry of the
+ * column before -- fits a signed 64-bit accumulator, so a product is 392 multiply-adds (v_mad_i64_i32) and no carry
+ * instructions, and an addition or subtraction is 14 independent limb operations: limbs may grow beyond 28 bits
+ * and go negative between products, and values need not lie in [0, p).
+ *
+ * A value is a limb vector l with value(l) = sum_j l_j 2^(28 j), standing for value(l) 2^-392 mod p.
+ *   "normal":  limbs 0..12 in [0, 2^28), limb 13 a small signed number (the sign of the value lives there);
+ *              what fp28_mul / fp28_sqr / fp28_carry return.
+ * Bounds (checked by the host tests on extreme operands): a product is exact as long as
+ *   14 max|a_j| max|b_j| + 14 * 2^56 + 2^36 < 2^63, e.g. limbs below 2^29.5 on both sides, or 2^30 against 2^29;
+ * its result lies in (a b / 2^392, a b / 2^392 + p), i.e. in (-p, 2 p) whenever |a b| < 2^392 p -- the radix
+ * leaves 11 bits of room above p, so sums of a few terms never need a reduction.
+ *
+ * Elements of the 32-bit form (Montgomery radix 2^384, canonical) enter by a re-cut of their bits moved up by 8
+ * places (value 2^8 stands for the same field element under the radix 2^392); they leave through a product with
+ * 2^384 mod p followed by the one full reduction of the path.
+ */
+#pragma once
+#include "field.h"
+
+namespace tc {
+
+struct fp28 {
+    int32_t l[14];
+};
+
+static constexpr int32_t FP28_MASK = (1 << 28) - 1;
+
+/* the limbs of a 2^8 for a canonical a: bits 28 j - 8 .. 28 j + 19 of a */
+TC_HD fp28 fp28_from_fp(const fp_t& a) {
+    fp28 r;
+    r.l[0] = (int32_t)((a.l[0] << 8) & (uint32_t)FP28_MASK);
+#pragma unroll
+    for (int j = 1; j < 14; ++j) {
+        const int o = 28 * j - 8, w = o >> 5, sh = o & 31;
+        uint32_t lo = a.l[w], hi = w + 1 < 12 ? a.l[w + 1] : 0u;
+        uint32_t v = sh ? (lo >> sh) | (hi << (32 - sh)) : lo;
+        r.l[j] = (int32_t)(v & (uint32_t)FP28_MASK);
+    }
+    return r;
+}
+
+TC_HD fp28 fp28_one() {
+    fp28 r;
+#pragma unroll
+    for (int j = 0; j < 14; ++j) r.l[j] = Fp28Params::ONE[j];
+    return r;
+}
+TC_HD fp28 fp28_add(const fp28& a, const fp28& b) {
+    fp28 r;
+#pragma unroll
+    for (int j = 0; j < 14; ++j) r.l[j] = a.l[j] + b.l[j];
+    return r;
+}
+TC_HD fp28 fp28_sub(const fp28& a, const fp28& b) {
+    fp28 r;
+#pragma unroll
+    for (int j = 0; j < 14; ++j) r.l[j] = a.l[j] - b.l[j];
+    return r;
+}
+/* same value, normal limbs (limbs of up to 31 bits either sign in, 28-bit limbs and a signed top limb out) */
+TC_HD fp28 fp28_carry(const fp28& a) {
+    fp28 r;
+    int32_t c = 0;
+#pragma unroll
+    for (int j = 0; j < 13; ++j) {
+        int32_t s = a.l[j] + c;
+        r.l[j] = s & FP28_MASK;
+        c = s >> 28;                       /* arithmetic: floor */
+    }
+    r.l[13] = a.l[13] + c;
+    return r;
+}
+
+/* a b 2^-392 (mod p) -- or a^2, or a b - c e -- with normal limbs, in (v / 2^392, v / 2^392 + p) for the integer v
+ * that is reduced.  Column k of the product scan collects a_i b_(k-i) (and -c_i e_(k-i)) and q_i p_(k-i); q_k is chosen
+ * so that the low 28 bits of the column vanish.  The difference of two products costs one reduction, not two; its
+ * column sums must obey the bound above with both products counted. */
+enum { FP28_MUL = 0, FP28_SQR = 1, FP28_MUL_SUB = 2 };
+template <int MODE>
+TC_HD fp28 fp28_mont(const fp28& a, const fp28& b, const fp28& c, const fp28& e) {
+    int64_t acc = 0;
+    int32_t q[14], d[14];
+    fp28 r;
+    if (MODE == FP28_SQR) {
+#pragma unroll
+        for (int i = 0; i < 14; ++i) d[i] = a.l[i] + a.l[i];        /* cross terms once, with a doubled operand */
+    }
+    if (MODE == FP28_MUL_SUB) {
+#pragma unroll
+        for (int i = 0; i < 14; ++i) d[i] = -c.l[i];
+    }
+#pragma unroll
+    for (int k = 0; k < 27; ++k) {
+        const int lo = k < 14 ? 0 : k - 13, hi = k < 14 ? k : 13;
+        if (MODE == FP28_SQR) {
+#pragma unroll
+            for (int i = lo; i < k - i; ++i) acc += (int64_t)d[i] * (int64_t)a.l[k - i];
+            if ((k & 1) == 0) acc += (int64_t)a.l[k / 2] * (int64_t)a.l[k / 2];
+        } else {
+#pragma unroll
+            for (int i = lo; i <= hi; ++i) acc += (int64_t)a.l[i] * (int64_t)b.l[k - i];
+        }
+        if (MODE == FP28_MUL_SUB) {
+#pragma unroll
+            for (int i = lo; i <= hi; ++i) acc += (int64_t)d[i] * (int64_t)e.l[k - i];
+        }
+        if (k < 14) {
+#pragma unroll
+            for (int i = 0; i < k; ++i) acc += (int64_t)q[i] * (int64_t)Fp28Params::MOD[k - i];
+            q[k] = (int32_t)(((uint32_t)acc * (uint32_t)Fp28Params::NINV) & (uint32_t)FP28_MASK);
+            acc += (int64_t)q[k] * (int64_t)Fp28Params::MOD[0];
+        } else {
+#pragma unroll
+            for (int i = lo; i <= 13; ++i) acc += (int64_t)q[i] * (int64_t)Fp28Params::MOD[k - i];
+            r.l[k - 14] = (int32_t)((uint32_t)acc & (uint32_t)FP28_MASK);
+        }
+        acc >>= 28;                        /* arithmetic: the accumulator is signed */
+    }
+    r.l[13] = (int32_t)acc;
+    return r;
+}
+/* expanded in place: for a kernel whose loop is a handful of products and nothing else (no operand shuffling around
+ * calls, and the scheduler sees across products) */
+TC_HD fp28 fp28_mul_inline(const fp28& a, const fp28& b) { return fp28_mont<FP28_MUL>(a, b, a, a); }
+TC_HD fp28 fp28_sqr_inline(const fp28& a) { return fp28_mont<FP28_SQR>(a, a, a, a); }
+TC_HD fp28 fp28_mul_sub_inline(const fp28& a, const fp28& b, const fp28& c, const fp28& e) { return fp28_mont<FP28_MUL_SUB>(a, b, c, e); }
+
+#if defined(__HIP_DEVICE_COMPILE__)
+/* real functions on the device, as for the 32-bit form: operands and result travel in VGPRs */
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+typedef int32_t i32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ fp28 fp28_unpack(i32x4 a0, i32x4 a1, i32x4 a2, i32x2 a3) {
+    fp28 a;
+    a.l[0] = a0.x; a.l[1] = a0.y; a.l[2] = a0.z; a.l[3] = a0.w; a.l[4] = a1.x; a.l[5] = a1.y; a.l[6] = a1.z; a.l[7] = a1.w;
+    a.l[8] = a2.x; a.l[9] = a2.y; a.l[10] = a2.z; a.l[11] = a2.w; a.l[12] = a3.x; a.l[13] = a3.y;
+    return a;
+}
+__device__ __attribute__((noinline)) fp28 fp28_mul_call(i32x4 a0, i32x4 a1, i32x4 a2, i32x2 a3, i32x4 b0, i32x4 b1, i32x4 b2, i32x2 b3) {
+    return fp28_mul_inline(fp28_unpack(a0, a1, a2, a3), fp28_unpack(b0, b1, b2, b3));
+}
+__device__ __attribute__((noinline)) fp28 fp28_sqr_call(i32x4 a0, i32x4 a1, i32x4 a2, i32x2 a3) {
+    return fp28_sqr_inline(fp28_unpack(a0, a1, a2, a3));
+}
+__device__ __forceinline__ fp28 fp28_mul(const fp28& a, const fp28& b) {
+    return fp28_mul_call(i32x4{a.l[0], a.l[1], a.l[2], a.l[3]}, i32x4{a.l[4], a.l[5], a.l[6], a.l[7]}, i32x4{a.l[8], a.l[9], a.l[10], a.l[11]},
+                         i32x2{a.l[12], a.l[13]}, i32x4{b.l[0], b.l[1], b.l[2], b.l[3]}, i32x4{b.l[4], b.l[5], b.l[6], b.l[7]},
+                         i32x4{b.l[8], b.l[9], b.l[10], b.l[11]}, i32x2{b.l[12], b.l[13]});
+}
+__device__ __forceinline__ fp28 fp28_sqr(const fp28& a) {
+    return fp28_sqr_call(i32x4{a.l[0], a.l[1], a.l[2], a.l[3]}, i32x4{a.l[4], a.l[5], a.l[6], a.l[7]}, i32x4{a.l[8], a.l[9], a.l[10], a.l[11]},
+                         i32x2{a.l[12], a.l[13]});
+}
+#elif defined(__HIPCC__)
+__device__ fp28 fp28_mul(const fp28& a, const fp28& b);
+__device__ fp28 fp28_sqr(const fp28& a);
+__host__ inline fp28 fp28_mul(const fp28& a, const fp28& b) { return fp28_mul_inline(a, b); }
+__host__ inline fp28 fp28_sqr(const fp28& a) { return fp28_sqr_inline(a); }
+#else
+inline fp28 fp28_mul(const fp28& a, const fp28& b) { return fp28_mul_inline(a, b); }
+inline fp28 fp28_sqr(const fp28& a) { return fp28_sqr_inline(a); }
+#endif
+
+/* the canonical element of the 32-bit form (radix 2^384) for a value with |value| < 2^392 */
+TC_HD fp_t fp28_to_fp(const fp28& a) {
+    fp28 to32;
+#pragma unroll
+    for (int j = 0; j < 14; ++j) to32.l[j] = Fp28Params::TO32[j];
+    fp28 t = fp28_mul(a, to32);            /* in (-p, 2 p) */
+    /* + p: non-negative, below 3 p < 2^383; limbs made normal on the way */
+    uint32_t u[14];
+    int32_t c = 0;
+#pragma unroll
+    for (int j = 0; j < 13; ++j) {
+        int32_t s = t.l[j] + Fp28Params::MOD[j] + c;
+        u[j] = (uint32_t)(s & FP28_MASK);
+        c = s >> 28;
+    }
+    u[13] = (uint32_t)(t.l[13] + Fp28Params::MOD[13] + c);
+    fp_t r;
+#pragma unroll
+    for (int i = 0; i < 12; ++i) {
+        const int o = 32 * i, j = o / 28, sh = o % 28;
+        uint32_t w = u[j] >> sh;
+        if (j + 1 < 14) w |= u[j + 1] << (28 - sh);
+        if (56 - sh < 32 && j + 2 < 14) w |= u[j + 2] << (56 - sh);
+        r.l[i] = w;
+    }
+    return fe_reduce_once<FpParams>(fe_reduce_once<FpParams>(r, 0u), 0u);
+}
+
+/* can the value be a multiple of p?  value = k p with |k| <= K forces (l_0 p^-1) mod 2^28 to be k mod 2^28; anything
+ * else (all but (2 K + 1) 2^-28 of the non-multiples) is certainly not zero in the field.  For |value| <= K p. */
+TC_HD bool fp28_maybe_zero(const fp28& a, uint32_t K) {
+    uint32_t k = ((uint32_t)a.l[0] * (uint32_t)Fp28Params::PINV + K) & (uint32_t)FP28_MASK;
+    return k <= 2u * K;
+}
+
+}  // namespace tc

@@ -117,6 +117,25 @@ def block(name, mod, n):
     return "\n".join(out)
 
 
+def limbs28(x, n=14):
+    return ", ".join("0x%07x" % ((x >> (28 * i)) & 0xFFFFFFF) for i in range(n))
+
+
+def block28():
+    """Fp in 14 limbs of 28 bits, Montgomery radix 2^392 (the accumulation kernel's second form of the field)."""
+    Rm = 1 << 392
+    out = []
+    out.append("struct Fp28Params {")
+    out.append("    static constexpr int N = 14;")
+    out.append("    static constexpr int32_t NINV = 0x%07x;              /* -p^-1 mod 2^28 */" % ((-pow(P_MOD, -1, 1 << 28)) % (1 << 28)))
+    out.append("    static constexpr int32_t PINV = 0x%07x;              /* p^-1 mod 2^28 */" % pow(P_MOD, -1, 1 << 28))
+    out.append("    static constexpr int32_t MOD[14] = {%s};" % limbs28(P_MOD))
+    out.append("    static constexpr int32_t ONE[14] = {%s};   /* 2^392 mod p */" % limbs28(Rm % P_MOD))
+    out.append("    static constexpr int32_t TO32[14] = {%s};  /* 2^384 mod p: a product with it leaves the 2^384 form */" % limbs28((1 << 384) % P_MOD))
+    out.append("};")
+    return "\n".join(out)
+
+
 def main():
     here = os.path.dirname(os.path.abspath(__file__))
     Rp = 1 << 384
@@ -130,6 +149,7 @@ def main():
         "namespace tc {",
         block("FpParams", P_MOD, 12),
         block("FrParams", R_MOD, 8),
+        block28(),
         "/* G1 generator, Montgomery form */",
         "static constexpr uint32_t G1_GEN_X[12] = {%s};" % limbs(GX * Rp % P_MOD, 12),
         "static constexpr uint32_t G1_GEN_Y[12] = {%s};" % limbs(GY * Rp % P_MOD, 12),

@@ -15,6 +15,7 @@
  */
 #pragma once
 #include "g1.h"
+#include "field28.h"
 #include "rt.h"
 
 namespace tc {
@@ -46,7 +47,11 @@ struct PokeWords {
 /* Test hook: one field operation per lane on raw limb arrays (Montgomery representatives as they sit in
  * registers), so that the device forms of the arithmetic can be compared with big-integer arithmetic directly. */
 enum { FOP_FP_MUL = 0, FOP_FP_SQR = 1, FOP_FP_MUL_F64 = 2, FOP_FP_SQR_F64 = 3, FOP_FP_INV = 4, FOP_FR_MUL = 5,
-       FOP_FP_ADD = 6, FOP_FP_SUB = 7, FOP_FR_INV = 8, FOP_COUNT = 9 };
+       FOP_FP_ADD = 6, FOP_FP_SUB = 7, FOP_FR_INV = 8,
+       /* through the 28-bit-limb form and back: a b, a^2, (a - b)(a + b), (a - 2 b)(a - b) (limbs grown and signed) */
+       FOP_FP28_MUL = 9, FOP_FP28_SQR = 10, FOP_FP28_DIFF_SUM = 11, FOP_FP28_GROWN = 12,
+       FOP_FP28_MUL_SUB = 13,      /* (a - b)(a + b) - b (a - b) under one reduction */
+       FOP_COUNT = 14 };
 struct FieldOp {
     int op;
     const uint32_t* a;      /* 12 limbs per element (8 for the Fr operations) */
@@ -72,6 +77,25 @@ struct FieldOp {
             case FOP_FP_SQR_F64: r = fp_sqr_lat(x); break;
             case FOP_FP_INV: r = fe_inv_gcd<FpParams>(x); break;
             case FOP_FP_ADD: r = fp_add(x, y); break;
+            case FOP_FP28_MUL: r = fp28_to_fp(fp28_mul(fp28_from_fp(x), fp28_from_fp(y))); break;
+            case FOP_FP28_SQR: r = fp28_to_fp(fp28_sqr(fp28_from_fp(x))); break;
+            case FOP_FP28_DIFF_SUM: {
+                fp28 X = fp28_from_fp(x), Y = fp28_from_fp(y);
+                r = fp28_to_fp(fp28_mul(fp28_sub(X, Y), fp28_add(X, Y)));
+                break;
+            }
+            case FOP_FP28_GROWN: {
+                fp28 X = fp28_from_fp(x), Y = fp28_from_fp(y);
+                fp28 D = fp28_sub(X, Y);
+                r = fp28_to_fp(fp28_mul(fp28_sub(D, Y), D));
+                break;
+            }
+            case FOP_FP28_MUL_SUB: {
+                fp28 X = fp28_from_fp(x), Y = fp28_from_fp(y);
+                fp28 D = fp28_sub(X, Y);
+                r = fp28_to_fp(fp28_mul_sub_inline(D, fp28_add(X, Y), Y, D));
+                break;
+            }
             default: r = fp_sub(x, y); break;
         }
 #pragma unroll
@@ -630,6 +654,33 @@ TC_HD uint32_t find_segment(const uint32_t* prefix, uint32_t n, uint32_t t) {
 }
 
 /* ---- MSM: balanced segmented sums per bucket -------------------------------------- */
+/* The accumulator lives in the 28-bit-limb form of the field (carry-free products and additions, expanded in place:
+ * the loop is 3542 multiply-adds and little else); points enter by a re-cut of their limbs, the sum leaves through
+ * one full reduction per coordinate.  The chord rule runs without its case distinctions.  A denominator that could
+ * be zero in the field (equal or opposite points) is told from its lowest limb; the lane then gives its sub-run up
+ * and enters it in a list, and a second launch (AccAffineRedo) sums the listed sub-runs with the 32-bit routine,
+ * which settles every case.  Of the harmless denominators all but about 2^-24 pass the test (the value of the
+ * denominator is bounded by a small multiple of p, and only multiples of p within the bound are suspects). */
+struct g1_xyzz28 {
+    fp28 X, Y, ZZ, ZZZ;
+};
+/* acc += (x2, y2), both finite; false (acc unusable) when the sum may be a doubling or the identity.
+ * `fresh` = regular additions since acc was a re-cut affine point, whose coordinates are 2^8 times larger than a
+ * reduced value: |P| <= 317 p in the first addition after it, <= 43 p in the second, <= 5 p from then on. */
+TC_HD bool xyzz28_madd_regular(g1_xyzz28& a, const fp28& x2, const fp28& y2, uint32_t fresh) {
+    fp28 P = fp28_sub(fp28_mul_inline(x2, a.ZZ), a.X);
+    if (fp28_maybe_zero(P, fresh == 0 ? 512u : fresh == 1 ? 64u : 8u)) return false;
+    fp28 R = fp28_sub(fp28_mul_inline(y2, a.ZZZ), a.Y);
+    fp28 PP = fp28_sqr_inline(P);
+    fp28 PPP = fp28_mul_inline(P, PP);
+    fp28 Q = fp28_mul_inline(a.X, PP);
+    fp28 X3 = fp28_carry(fp28_sub(fp28_sub(fp28_sub(fp28_sqr_inline(R), PPP), Q), Q));
+    a.Y = fp28_mul_sub_inline(R, fp28_sub(Q, X3), a.Y, PPP);          /* limbs below 2^29 against 2^28, twice */
+    a.ZZ = fp28_mul_inline(a.ZZ, PP);
+    a.ZZZ = fp28_mul_inline(a.ZZZ, PPP);
+    a.X = X3;
+    return true;
+}
 /* Lane t owns sub-run `t - lstart[b]` of bucket b: at most L entries, all of one bucket.
  * Output slot t, so the partial sums of bucket b are the slots lstart[b] .. lstart[b+1]. */
 struct AccAffine {
@@ -640,8 +691,67 @@ struct AccAffine {
     const uint32_t* lstart;
     uint32_t nbk, L;
     g1_xyzz* out;
+    uint32_t* redo_count;             /* zero before the launch */
+    uint32_t* redo_list;              /* room for every lane */
     TC_DEV void operator()(uint32_t t) const {
         if (t >= lstart[nbk]) return;
+        uint32_t b = find_segment(lstart, nbk, t);
+        uint32_t begin = start[b] + (t - lstart[b]) * L;
+        uint32_t end = begin + L < start[b + 1] ? begin + L : start[b + 1];
+        const g1_affine* pts = tables[b / nbk_pp];
+        if (end - begin == 1) {                                   /* a lone entry: no arithmetic */
+            uint32_t e = sorted[begin];
+            g1_affine p = pts[e & 0x7FFFFFFFu];
+            if (e >> 31) p.y = fp_neg(p.y);
+            out[t] = xyzz_from_affine(p);
+            return;
+        }
+        g1_xyzz28 acc;
+        bool have = false;                                        /* acc holds a point (the sum so far is not the identity) */
+        uint32_t fresh = 0;
+        for (uint32_t i = begin; i < end; ++i) {
+            uint32_t e = sorted[i];
+            g1_affine p = pts[e & 0x7FFFFFFFu];
+            if (affine_is_identity(p)) continue;
+            fp28 x2 = fp28_from_fp(p.x), y2 = fp28_from_fp(p.y);
+            if (e >> 31) y2 = fp28_sub(fp28{}, y2);
+            if (!have) {
+                acc.X = x2;
+                acc.Y = y2;
+                acc.ZZ = fp28_one();
+                acc.ZZZ = fp28_one();
+                have = true;
+                continue;
+            }
+            if (!xyzz28_madd_regular(acc, x2, y2, fresh)) {
+                redo_list[atomic_add_u32(redo_count, 1u)] = t;
+                return;
+            }
+            ++fresh;
+        }
+        g1_xyzz r;
+        if (!have) {
+            r = xyzz_identity();
+        } else {
+            r.X = fp28_to_fp(acc.X); r.Y = fp28_to_fp(acc.Y); r.ZZ = fp28_to_fp(acc.ZZ); r.ZZZ = fp28_to_fp(acc.ZZZ);
+        }
+        out[t] = r;
+    }
+};
+/* the sub-runs that AccAffine gave up, summed with every case of the group law */
+struct AccAffineRedo {
+    const g1_affine* const* tables;
+    uint32_t nbk_pp;
+    const uint32_t* sorted;
+    const uint32_t* start;
+    const uint32_t* lstart;
+    uint32_t nbk, L;
+    g1_xyzz* out;
+    const uint32_t* redo_count;
+    const uint32_t* redo_list;
+    TC_DEV void operator()(uint32_t lane) const {
+        if (lane >= *redo_count) return;
+        uint32_t t = redo_list[lane];
         uint32_t b = find_segment(lstart, nbk, t);
         uint32_t begin = start[b] + (t - lstart[b]) * L;
         uint32_t end = begin + L < start[b + 1] ? begin + L : start[b + 1];

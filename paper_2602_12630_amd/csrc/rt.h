@@ -56,6 +56,10 @@ inline int launch(uint64_t n, stream_t, const F& f) {
     for (uint64_t t = 0; t < n; ++t) f((uint32_t)t);
     return 0;
 }
+template <int BLOCK, int WAVES, class F>
+inline int launch_waves(uint64_t n, stream_t st, const F& f) {
+    return launch<BLOCK>(n, st, f);
+}
 }  // namespace rt
 inline uint32_t atomic_add_u32(uint32_t* p, uint32_t v) { uint32_t o = *p; *p += v; return o; }
 inline uint32_t atomic_and_u32(uint32_t* p, uint32_t v) { uint32_t o = *p; *p &= v; return o; }
@@ -70,6 +74,14 @@ namespace tc {
 
 template <class F, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void kernel(const F f, uint32_t n) {
+    uint32_t t = blockIdx.x * BLOCK + threadIdx.x;
+    if (t < n) f(t);
+}
+
+/* the same with the register budget of exactly WAVES waves per SIMD: a kernel that is one long stretch of
+ * straight-line arithmetic, where the compiler's own choice trades registers for spills */
+template <class F, int BLOCK, int WAVES>
+__global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES))) void kernel_waves(const F f, uint32_t n) {
     uint32_t t = blockIdx.x * BLOCK + threadIdx.x;
     if (t < n) f(t);
 }
@@ -102,6 +114,14 @@ inline int launch(uint64_t n, stream_t st, const F& f) {
     if (n > 0xFFFFFFFFull) return (int)hipErrorInvalidValue;
     uint32_t blocks = (uint32_t)((n + BLOCK - 1) / BLOCK);
     hipLaunchKernelGGL((kernel<F, BLOCK>), dim3(blocks), dim3(BLOCK), 0, st, f, (uint32_t)n);
+    return (int)hipGetLastError();
+}
+template <int BLOCK, int WAVES, class F>
+inline int launch_waves(uint64_t n, stream_t st, const F& f) {
+    if (n == 0) return 0;
+    if (n > 0xFFFFFFFFull) return (int)hipErrorInvalidValue;
+    uint32_t blocks = (uint32_t)((n + BLOCK - 1) / BLOCK);
+    hipLaunchKernelGGL((kernel_waves<F, BLOCK, WAVES>), dim3(blocks), dim3(BLOCK), 0, st, f, (uint32_t)n);
     return (int)hipGetLastError();
 }
 }  // namespace rt

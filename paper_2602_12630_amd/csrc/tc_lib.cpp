@@ -509,6 +509,16 @@ __global__ __launch_bounds__(256) void alu_rate_kernel(uint32_t iters, uint32_t*
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) out ^= (uint32_t)acc[i] ^ (uint32_t)(acc[i] >> 32) ^ hi[i];
+    } else if (KIND == TC_ALU_FP28_MUL || KIND == TC_ALU_FP28_SQR) {
+        fp28 x = fp28_one(), y = fp28_one();
+        x.l[0] ^= (int32_t)(t & 0xFFFFu);
+        y.l[1] ^= (int32_t)((t * 7u) & 0xFFFFu);
+        for (uint32_t it = 0; it < iters; ++it) {
+#pragma unroll 1
+            for (int i = 0; i < 8; ++i) x = KIND == TC_ALU_FP28_MUL ? fp28_mul(x, y) : fp28_sqr(x);
+        }
+#pragma unroll
+        for (int i = 0; i < 14; ++i) out ^= (uint32_t)x.l[i];
     } else {
         fp_t x = fe_one<FpParams>(), y = fe_one<FpParams>();
         x.l[0] ^= t;
@@ -528,7 +538,7 @@ __global__ __launch_bounds__(256) void alu_rate_kernel(uint32_t iters, uint32_t*
 
 extern "C" int tc_ctx_alu_rate(tc_ctx* ctx, int kind, int waves_per_simd, double* out_per_s) {
     if (!ctx) return TC_ERR_ARG;
-    if (!out_per_s || kind < 0 || kind > TC_ALU_FP_SQR_F64) return fail(ctx, TC_ERR_ARG, "bad argument");
+    if (!out_per_s || kind < 0 || kind > TC_ALU_FP28_SQR) return fail(ctx, TC_ERR_ARG, "bad argument");
     if (waves_per_simd < 1 || waves_per_simd > 8) return fail(ctx, TC_ERR_ARG, "waves_per_simd must be 1..8");
 #if defined(TC_HOST_EMU)
     return fail(ctx, TC_ERR_HIP, "no GPU in the host emulation");
@@ -557,7 +567,9 @@ extern "C" int tc_ctx_alu_rate(tc_ctx* ctx, int kind, int waves_per_simd, double
                                          : kind == TC_ALU_FP_MUL    ? alu_rate_kernel<TC_ALU_FP_MUL>
                                          : kind == TC_ALU_FP_SQR    ? alu_rate_kernel<TC_ALU_FP_SQR>
                                          : kind == TC_ALU_FP_MUL_F64 ? alu_rate_kernel<TC_ALU_FP_MUL_F64>
-                                                                     : alu_rate_kernel<TC_ALU_FP_SQR_F64>;
+                                         : kind == TC_ALU_FP_SQR_F64 ? alu_rate_kernel<TC_ALU_FP_SQR_F64>
+                                         : kind == TC_ALU_FP28_MUL   ? alu_rate_kernel<TC_ALU_FP28_MUL>
+                                                                     : alu_rate_kernel<TC_ALU_FP28_SQR>;
         int e = (int)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (!e) {
             hipLaunchKernelGGL(k, dim3(groups), dim3(256), lds, ctx->stream, iters, sink);
@@ -1348,12 +1360,17 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     WS(bufB, g1_xyzz, max_part / L2 + nbk + 1);
     WS(bucket, g1_xyzz, nbk);
     WS(wsum, g1_xyzz, (uint64_t)W * count);
+    WS(redo, uint32_t, max_part + 1);                  /* [0]: how many sub-runs the fast accumulation gave up; then which */
+    RT(rt::launch<64>(1, ctx->stream, Fill32{redo, 0u}));
     {
         rt::event_t e0, e1;
         prof_begin(ctx, TC_PROF_BUCKET_ACC, &e0, &e1);
-        RT(rt::launch<64>(max_part, ctx->stream, AccAffine{tables, nbk_pp, sorted, start, lstart, nbk, L1, bufA}));
+        RT((rt::launch_waves<64, 3>(max_part, ctx->stream, AccAffine{tables, nbk_pp, sorted, start, lstart, nbk, L1, bufA, redo, redo + 1})));
         prof_end(ctx, TC_PROF_BUCKET_ACC, e0, e1);
     }
+    /* sub-runs with equal or opposite points in them (and the odd false alarm): a handful in honest inputs; the
+     * launch has a lane for every sub-run because a degenerate input sends all of them here */
+    RT(rt::launch<64>(max_part, ctx->stream, AccAffineRedo{tables, nbk_pp, sorted, start, lstart, nbk, L1, bufA, redo, redo + 1}));
 
     /* Middle passes shrink the per-bucket partial count by L2 until at most L2 remain. */
     uint32_t acc_terms = 0, acc_lanes = 0;             /* non-zero digits and sub-runs of the first pass (profiling only) */

@@ -107,7 +107,11 @@ def check_field_arithmetic(run, n_fp, n_fr):
     pa, pb = pack(a_vals, 12), pack(b_vals, 12)
     rinv = pow(RP, -1, P)
     expect = {0: lambda x, y: x * y * rinv % P, 1: lambda x, y: x * x * rinv % P, 2: lambda x, y: x * y * rinv % P,
-              3: lambda x, y: x * x * rinv % P, 6: lambda x, y: (x + y) % P, 7: lambda x, y: (x - y) % P}
+              3: lambda x, y: x * x * rinv % P, 6: lambda x, y: (x + y) % P, 7: lambda x, y: (x - y) % P,
+              # the 28-bit-limb form of the bucket accumulation: unreduced sums and differences with signed limbs
+              9: lambda x, y: x * y * rinv % P, 10: lambda x, y: x * x * rinv % P,
+              11: lambda x, y: (x - y) * (x + y) * rinv % P, 12: lambda x, y: (x - 2 * y) * (x - y) * rinv % P,
+              13: lambda x, y: (x - y) * x * rinv % P}
     for op, fn in expect.items():
         got = unpack(run(op, pa, pb, 12), 12)
         bad = [i for i in range(len(a_vals)) if got[i] != fn(a_vals[i], b_vals[i])]
