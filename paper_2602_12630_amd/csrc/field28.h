@@ -17,8 +17,8 @@
  * leaves 11 bits of room above p, so sums of a few terms never need a reduction.
  *
  * Elements of the 32-bit form (Montgomery radix 2^384, canonical) enter by a re-cut of their bits moved up by 8
- * places (value 2^8 stands for the same field element under the radix 2^392); they leave through a product with
- * 2^384 mod p followed by the one full reduction of the path.
+ * places (value 2^8 stands for the same field element under the radix 2^392); they leave through a Montgomery step
+ * of those eight bits followed by the one full reduction of the path.
  */
 #pragma once
 #include "field.h"
@@ -147,6 +147,14 @@ __device__ __attribute__((noinline)) fp28 fp28_mul_call(i32x4 a0, i32x4 a1, i32x
 __device__ __attribute__((noinline)) fp28 fp28_sqr_call(i32x4 a0, i32x4 a1, i32x4 a2, i32x2 a3) {
     return fp28_sqr_inline(fp28_unpack(a0, a1, a2, a3));
 }
+__device__ __attribute__((noinline)) fp28 fp28_mul_sub_call(i32x4 a0, i32x4 a1, i32x4 a2, i32x2 a3, i32x4 b0, i32x4 b1, i32x4 b2, i32x2 b3,
+                                                            i32x4 c0, i32x4 c1, i32x4 c2, i32x2 c3, i32x4 e0, i32x4 e1, i32x4 e2, i32x2 e3) {
+    return fp28_mul_sub_inline(fp28_unpack(a0, a1, a2, a3), fp28_unpack(b0, b1, b2, b3), fp28_unpack(c0, c1, c2, c3), fp28_unpack(e0, e1, e2, e3));
+}
+#define TC_FP28_ARGS(a) i32x4{a.l[0], a.l[1], a.l[2], a.l[3]}, i32x4{a.l[4], a.l[5], a.l[6], a.l[7]}, i32x4{a.l[8], a.l[9], a.l[10], a.l[11]}, i32x2{a.l[12], a.l[13]}
+__device__ __forceinline__ fp28 fp28_mul_sub(const fp28& a, const fp28& b, const fp28& c, const fp28& e) {
+    return fp28_mul_sub_call(TC_FP28_ARGS(a), TC_FP28_ARGS(b), TC_FP28_ARGS(c), TC_FP28_ARGS(e));
+}
 __device__ __forceinline__ fp28 fp28_mul(const fp28& a, const fp28& b) {
     return fp28_mul_call(i32x4{a.l[0], a.l[1], a.l[2], a.l[3]}, i32x4{a.l[4], a.l[5], a.l[6], a.l[7]}, i32x4{a.l[8], a.l[9], a.l[10], a.l[11]},
                          i32x2{a.l[12], a.l[13]}, i32x4{b.l[0], b.l[1], b.l[2], b.l[3]}, i32x4{b.l[4], b.l[5], b.l[6], b.l[7]},
@@ -159,46 +167,82 @@ __device__ __forceinline__ fp28 fp28_sqr(const fp28& a) {
 #elif defined(__HIPCC__)
 __device__ fp28 fp28_mul(const fp28& a, const fp28& b);
 __device__ fp28 fp28_sqr(const fp28& a);
+__device__ fp28 fp28_mul_sub(const fp28& a, const fp28& b, const fp28& c, const fp28& e);
+__host__ inline fp28 fp28_mul_sub(const fp28& a, const fp28& b, const fp28& c, const fp28& e) { return fp28_mul_sub_inline(a, b, c, e); }
 __host__ inline fp28 fp28_mul(const fp28& a, const fp28& b) { return fp28_mul_inline(a, b); }
 __host__ inline fp28 fp28_sqr(const fp28& a) { return fp28_sqr_inline(a); }
 #else
 inline fp28 fp28_mul(const fp28& a, const fp28& b) { return fp28_mul_inline(a, b); }
 inline fp28 fp28_sqr(const fp28& a) { return fp28_sqr_inline(a); }
+inline fp28 fp28_mul_sub(const fp28& a, const fp28& b, const fp28& c, const fp28& e) { return fp28_mul_sub_inline(a, b, c, e); }
 #endif
 
-/* the canonical element of the 32-bit form (radix 2^384) for a value with |value| < 2^392 */
+/* The canonical element of the 32-bit form (radix 2^384) for a value v with -256 p <= v < 512 p.  The two radices
+ * differ by 2^8, so this is a Montgomery step of eight bits: a multiple q p with v + q p = 0 (mod 2^8), taken from
+ * 256 p .. 511 p so that the sum is not negative, then the shift; (v + q p) / 2^8 < 4 p. */
 TC_HD fp_t fp28_to_fp(const fp28& a) {
-    fp28 to32;
-#pragma unroll
-    for (int j = 0; j < 14; ++j) to32.l[j] = Fp28Params::TO32[j];
-    fp28 t = fp28_mul(a, to32);            /* in (-p, 2 p) */
-    /* + p: non-negative, below 3 p < 2^383; limbs made normal on the way */
+    int32_t q = (int32_t)((((uint32_t)a.l[0] * (uint32_t)Fp28Params::NINV) & 0xFFu) + 256u);
     uint32_t u[14];
-    int32_t c = 0;
+    int64_t c = 0;
 #pragma unroll
     for (int j = 0; j < 13; ++j) {
-        int32_t s = t.l[j] + Fp28Params::MOD[j] + c;
-        u[j] = (uint32_t)(s & FP28_MASK);
-        c = s >> 28;
+        c += (int64_t)q * (int64_t)Fp28Params::MOD[j] + (int64_t)a.l[j];
+        u[j] = (uint32_t)c & (uint32_t)FP28_MASK;
+        c >>= 28;
     }
-    u[13] = (uint32_t)(t.l[13] + Fp28Params::MOD[13] + c);
+    c += (int64_t)q * (int64_t)Fp28Params::MOD[13] + (int64_t)a.l[13];
+    u[13] = (uint32_t)c;                   /* below 2^26 */
     fp_t r;
 #pragma unroll
     for (int i = 0; i < 12; ++i) {
-        const int o = 32 * i, j = o / 28, sh = o % 28;
+        const int o = 32 * i + 8, j = o / 28, sh = o % 28;
         uint32_t w = u[j] >> sh;
         if (j + 1 < 14) w |= u[j + 1] << (28 - sh);
         if (56 - sh < 32 && j + 2 < 14) w |= u[j + 2] << (56 - sh);
         r.l[i] = w;
     }
-    return fe_reduce_once<FpParams>(fe_reduce_once<FpParams>(r, 0u), 0u);
+    return fe_reduce_once<FpParams>(fe_reduce_once<FpParams>(fe_reduce_once<FpParams>(r, 0u), 0u), 0u);
 }
 
-/* can the value be a multiple of p?  value = k p with |k| <= K forces (l_0 p^-1) mod 2^28 to be k mod 2^28; anything
- * else (all but (2 K + 1) 2^-28 of the non-multiples) is certainly not zero in the field.  For |value| <= K p. */
+/* is the value a multiple of p (zero in the field)?  For |value| <= K p, K < 2^20.  value = k p forces
+ * (l_0 p^-1) mod 2^28 = k mod 2^28, which all but (2 K + 1) 2^-28 of the other values fail at once; for a k that
+ * passes, value - k p is worked out limb by limb. */
+/* the same as a real function on the device: for the end of a kernel whose loop must keep its registers */
+#if defined(__HIP_DEVICE_COMPILE__)
+__device__ __attribute__((noinline)) fp_t fp28_to_fp_call(i32x4 a0, i32x4 a1, i32x4 a2, i32x2 a3) { return fp28_to_fp(fp28_unpack(a0, a1, a2, a3)); }
+__device__ __forceinline__ fp_t fp28_to_fp_outlined(const fp28& a) { return fp28_to_fp_call(TC_FP28_ARGS(a)); }
+#elif defined(__HIPCC__)
+__device__ fp_t fp28_to_fp_outlined(const fp28& a);
+__host__ inline fp_t fp28_to_fp_outlined(const fp28& a) { return fp28_to_fp(a); }
+#else
+inline fp_t fp28_to_fp_outlined(const fp28& a) { return fp28_to_fp(a); }
+#endif
+
+/* the first two limbs of that test only: no multiple of p is missed, and of the other values all but about
+ * (2 K + 1) 2^-56 are told apart -- for a loop that cannot afford the registers of the full test and has a slower
+ * path for whatever passes */
 TC_HD bool fp28_maybe_zero(const fp28& a, uint32_t K) {
-    uint32_t k = ((uint32_t)a.l[0] * (uint32_t)Fp28Params::PINV + K) & (uint32_t)FP28_MASK;
-    return k <= 2u * K;
+    uint32_t kk = ((uint32_t)a.l[0] * (uint32_t)Fp28Params::PINV + K) & (uint32_t)FP28_MASK;
+    if (kk > 2u * K) return false;
+    int32_t k = (int32_t)kk - (int32_t)K;
+    int64_t c = ((int64_t)a.l[0] - (int64_t)k * (int64_t)Fp28Params::MOD[0]) >> 28;        /* the low 28 bits are zero by the choice of k */
+    c += (int64_t)a.l[1] - (int64_t)k * (int64_t)Fp28Params::MOD[1];
+    return ((uint32_t)c & (uint32_t)FP28_MASK) == 0;
+}
+TC_HD bool fp28_is_zero(const fp28& a, uint32_t K) {
+    uint32_t kk = ((uint32_t)a.l[0] * (uint32_t)Fp28Params::PINV + K) & (uint32_t)FP28_MASK;
+    if (kk > 2u * K) return false;
+    int32_t k = (int32_t)kk - (int32_t)K;
+    int64_t c = 0;
+    uint32_t low = 0;
+#pragma unroll
+    for (int j = 0; j < 13; ++j) {
+        c += (int64_t)a.l[j] - (int64_t)k * (int64_t)Fp28Params::MOD[j];
+        low |= (uint32_t)c & (uint32_t)FP28_MASK;
+        c >>= 28;
+    }
+    c += (int64_t)a.l[13] - (int64_t)k * (int64_t)Fp28Params::MOD[13];
+    return low == 0 && c == 0;
 }
 
 }  // namespace tc

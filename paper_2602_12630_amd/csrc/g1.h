@@ -8,12 +8,21 @@
  *           identity is ZZ = 0.  Accumulators live in this form: adding an
  *           affine point costs 8 multiplications + 2 squarings.
  *
+ * Points are stored and handed around with coordinates in the 32-bit form of
+ * the field; the group law itself computes in the carry-free 28-bit form
+ * (field28.h): operands are re-cut on entry, sums and differences stay
+ * unreduced, a difference of two products shares one reduction, and each
+ * result coordinate is reduced once on the way out.  Values on entry are below
+ * 2^389 (315 p); the comments give the bounds that the zero tests and the way
+ * out rely on, in multiples of p.
+ *
  * Every addition handles the exceptional inputs (identity on either side,
  * equal points, opposite points) explicitly: sums of SRS points keyed by small
  * digits, constant tensors and the batched tree reductions do reach them.
  */
 #pragma once
 #include "field.h"
+#include "field28.h"
 
 namespace tc {
 
@@ -68,86 +77,162 @@ TC_HD g1_xyzz xyzz_neg(const g1_xyzz& p) {
     return r;
 }
 
-/* 2 (x, y) for an affine point, tangent rule in XYZZ form */
+struct g1_xyzz28 {
+    fp28 X, Y, ZZ, ZZZ;
+};
+TC_HD g1_xyzz28 xyzz28_from(const g1_xyzz& p) {
+    g1_xyzz28 r;
+    r.X = fp28_from_fp(p.X);
+    r.Y = fp28_from_fp(p.Y);
+    r.ZZ = fp28_from_fp(p.ZZ);
+    r.ZZZ = fp28_from_fp(p.ZZZ);
+    return r;
+}
+TC_HD g1_xyzz xyzz28_to(const g1_xyzz28& p) {
+    g1_xyzz r;
+    r.X = fp28_to_fp(p.X);
+    r.Y = fp28_to_fp(p.Y);
+    r.ZZ = fp28_to_fp(p.ZZ);
+    r.ZZZ = fp28_to_fp(p.ZZZ);
+    return r;
+}
+
+/* 2 P from (X, Y, ZZ, ZZZ) of a finite P with Y != 0, coordinates below 315 p, normal limbs.
+ * U <= 630 p, V <= 159 p, W <= 41 p, S <= 21 p, M <= 120 p, X3 in (-42 p, 7 p), Y3 in (-6 p, 4 p), ZZ3 <= 21 p, ZZZ3 <= 6 p. */
+TC_HD g1_xyzz28 xyzz28_dbl_finite(const g1_xyzz28& p) {
+    fp28 U = fp28_add(p.Y, p.Y);
+    fp28 V = fp28_sqr(U);
+    fp28 W = fp28_mul(U, V);
+    fp28 S = fp28_mul(p.X, V);
+    fp28 X2 = fp28_sqr(p.X);
+    fp28 M = fp28_carry(fp28_add(fp28_add(X2, X2), X2));
+    g1_xyzz28 r;
+    r.X = fp28_carry(fp28_sub(fp28_sub(fp28_sqr(M), S), S));
+    r.Y = fp28_mul_sub(M, fp28_sub(S, r.X), W, p.Y);
+    r.ZZ = fp28_mul(V, p.ZZ);
+    r.ZZZ = fp28_mul(W, p.ZZZ);
+    return r;
+}
+
+/* A running sum that stays in the 28-bit form between additions: loops convert once at the end.  `inf` says that
+ * the sum is the identity (v then holds nothing).  Every case of the group law is settled here. */
+struct xyzz_acc {
+    g1_xyzz28 v;
+    bool inf;
+};
+TC_HD xyzz_acc acc_identity() {
+    xyzz_acc a;
+    a.v.X = fp28{};
+    a.v.Y = fp28{};
+    a.v.ZZ = fp28{};
+    a.v.ZZZ = fp28{};
+    a.inf = true;
+    return a;
+}
+TC_HD xyzz_acc acc_from(const g1_xyzz& p) {
+    if (xyzz_is_identity(p)) return acc_identity();
+    xyzz_acc a;
+    a.v = xyzz28_from(p);
+    a.inf = false;
+    return a;
+}
+TC_HD g1_xyzz acc_result(const xyzz_acc& a) {
+    if (a.inf) return xyzz_identity();
+    g1_xyzz r = xyzz28_to(a.v);
+    if (fe_is_zero(r.ZZ)) return xyzz_identity();      /* a point of order two doubled: none on this curve */
+    return r;
+}
+/* a <- 2 a */
+TC_HD void acc_dbl(xyzz_acc& a) {
+    if (a.inf) return;
+    a.v = xyzz28_dbl_finite(a.v);
+}
+/* a <- a + q, q affine: chord rule, tangent rule for equal points, identity for opposite ones.
+ * With a below 315 p: U2, S2 <= 41 p, |P|, |R| <= 356 p, PP <= 52 p, PPP, Q <= 8 p, X3 in (-20 p, 52 p), Y3 within 12 p,
+ * ZZ3 <= 8 p, ZZZ3 <= 2 p. */
+TC_HD void acc_madd(xyzz_acc& a, const g1_affine& q, bool negate) {
+    if (affine_is_identity(q)) return;
+    fp28 x2 = fp28_from_fp(q.x), y2 = fp28_from_fp(q.y);
+    if (negate) y2 = fp28_sub(fp28{}, y2);
+    if (a.inf) {
+        a.v.X = x2;
+        a.v.Y = y2;
+        a.v.ZZ = fp28_one();
+        a.v.ZZZ = fp28_one();
+        a.inf = false;
+        return;
+    }
+    fp28 Pd = fp28_sub(fp28_mul(x2, a.v.ZZ), a.v.X);
+    fp28 Rd = fp28_sub(fp28_mul(y2, a.v.ZZZ), a.v.Y);
+    if (fp28_is_zero(Pd, 512u)) {
+        if (fp28_is_zero(Rd, 512u)) {
+            a.v.X = x2;
+            a.v.Y = y2;
+            a.v.ZZ = fp28_one();
+            a.v.ZZZ = fp28_one();
+            a.v = xyzz28_dbl_finite(a.v);
+        } else {
+            a.inf = true;
+        }
+        return;
+    }
+    fp28 PP = fp28_sqr(Pd);
+    fp28 PPP = fp28_mul(Pd, PP);
+    fp28 Q = fp28_mul(a.v.X, PP);
+    fp28 X3 = fp28_carry(fp28_sub(fp28_sub(fp28_sub(fp28_sqr(Rd), PPP), Q), Q));
+    a.v.Y = fp28_mul_sub(Rd, fp28_sub(Q, X3), a.v.Y, PPP);
+    a.v.ZZ = fp28_mul(a.v.ZZ, PP);
+    a.v.ZZZ = fp28_mul(a.v.ZZZ, PPP);
+    a.v.X = X3;
+}
+/* a <- a + b.  With both below 315 p: U, S <= 41 p, |P|, |R| <= 82 p, PP <= 4 p, PPP, Q <= 2 p, X3 in (-6 p, 4 p),
+ * Y3 within 2 p, ZZ3, ZZZ3 <= 2 p. */
+TC_HD void acc_add(xyzz_acc& a, const xyzz_acc& b) {
+    if (b.inf) return;
+    if (a.inf) { a = b; return; }
+    fp28 U1 = fp28_mul(a.v.X, b.v.ZZ);
+    fp28 S1 = fp28_mul(a.v.Y, b.v.ZZZ);
+    fp28 Pd = fp28_sub(fp28_mul(b.v.X, a.v.ZZ), U1);
+    fp28 Rd = fp28_sub(fp28_mul(b.v.Y, a.v.ZZZ), S1);
+    if (fp28_is_zero(Pd, 128u)) {
+        if (fp28_is_zero(Rd, 128u)) a.v = xyzz28_dbl_finite(a.v);
+        else a.inf = true;
+        return;
+    }
+    fp28 PP = fp28_sqr(Pd);
+    fp28 PPP = fp28_mul(Pd, PP);
+    fp28 Q = fp28_mul(U1, PP);
+    fp28 X3 = fp28_carry(fp28_sub(fp28_sub(fp28_sub(fp28_sqr(Rd), PPP), Q), Q));
+    a.v.Y = fp28_mul_sub(Rd, fp28_sub(Q, X3), S1, PPP);
+    a.v.ZZ = fp28_mul(fp28_mul(a.v.ZZ, b.v.ZZ), PP);
+    a.v.ZZZ = fp28_mul(fp28_mul(a.v.ZZZ, b.v.ZZZ), PPP);
+    a.v.X = X3;
+}
+
+/* the same on stored points (coordinates in the 32-bit form), one operation at a time */
 TC_HD g1_xyzz xyzz_dbl_affine(const g1_affine& p) {
-    if (affine_is_identity(p) || fe_is_zero(p.y)) return xyzz_identity();
-    fp_t U = fp_dbl(p.y);
-    fp_t V = fp_sqr(U);
-    fp_t W = fp_mul(U, V);
-    fp_t S = fp_mul(p.x, V);
-    fp_t X2 = fp_sqr(p.x);
-    fp_t M = fp_add(fp_dbl(X2), X2);
-    g1_xyzz r;
-    r.X = fp_sub(fp_sub(fp_sqr(M), S), S);
-    r.Y = fp_sub(fp_mul(M, fp_sub(S, r.X)), fp_mul(W, p.y));
-    r.ZZ = V;
-    r.ZZZ = W;
-    return r;
+    xyzz_acc a = acc_identity();
+    acc_madd(a, p, false);
+    acc_dbl(a);
+    return acc_result(a);
 }
-
-/* 2 P */
 TC_HD g1_xyzz xyzz_dbl(const g1_xyzz& p) {
-    if (xyzz_is_identity(p) || fe_is_zero(p.Y)) return xyzz_identity();
-    fp_t U = fp_dbl(p.Y);
-    fp_t V = fp_sqr(U);
-    fp_t W = fp_mul(U, V);
-    fp_t S = fp_mul(p.X, V);
-    fp_t X2 = fp_sqr(p.X);
-    fp_t M = fp_add(fp_dbl(X2), X2);
-    g1_xyzz r;
-    r.X = fp_sub(fp_sub(fp_sqr(M), S), S);
-    r.Y = fp_sub(fp_mul(M, fp_sub(S, r.X)), fp_mul(W, p.Y));
-    r.ZZ = fp_mul(V, p.ZZ);
-    r.ZZZ = fp_mul(W, p.ZZZ);
-    return r;
+    xyzz_acc a = acc_from(p);
+    acc_dbl(a);
+    return acc_result(a);
 }
-
-/* acc + q, q affine (chord rule); falls back to the tangent rule / identity when needed */
 TC_HD g1_xyzz xyzz_madd(const g1_xyzz& a, const g1_affine& q) {
     if (affine_is_identity(q)) return a;
-    if (xyzz_is_identity(a)) return xyzz_from_affine(q);
-    fp_t U2 = fp_mul(q.x, a.ZZ);
-    fp_t S2 = fp_mul(q.y, a.ZZZ);
-    fp_t Pd = fp_sub(U2, a.X);
-    fp_t Rd = fp_sub(S2, a.Y);
-    if (fe_is_zero(Pd)) {
-        if (fe_is_zero(Rd)) return xyzz_dbl_affine(q);
-        return xyzz_identity();
-    }
-    fp_t PP = fp_sqr(Pd);
-    fp_t PPP = fp_mul(Pd, PP);
-    fp_t Q = fp_mul(a.X, PP);
-    g1_xyzz r;
-    r.X = fp_sub(fp_sub(fp_sub(fp_sqr(Rd), PPP), Q), Q);
-    r.Y = fp_sub(fp_mul(Rd, fp_sub(Q, r.X)), fp_mul(a.Y, PPP));
-    r.ZZ = fp_mul(a.ZZ, PP);
-    r.ZZZ = fp_mul(a.ZZZ, PPP);
-    return r;
+    xyzz_acc A = acc_from(a);
+    acc_madd(A, q, false);
+    return acc_result(A);
 }
-
-/* a + b, both XYZZ */
 TC_HD g1_xyzz xyzz_add(const g1_xyzz& a, const g1_xyzz& b) {
     if (xyzz_is_identity(b)) return a;
     if (xyzz_is_identity(a)) return b;
-    fp_t U1 = fp_mul(a.X, b.ZZ);
-    fp_t U2 = fp_mul(b.X, a.ZZ);
-    fp_t S1 = fp_mul(a.Y, b.ZZZ);
-    fp_t S2 = fp_mul(b.Y, a.ZZZ);
-    fp_t Pd = fp_sub(U2, U1);
-    fp_t Rd = fp_sub(S2, S1);
-    if (fe_is_zero(Pd)) {
-        if (fe_is_zero(Rd)) return xyzz_dbl(a);
-        return xyzz_identity();
-    }
-    fp_t PP = fp_sqr(Pd);
-    fp_t PPP = fp_mul(Pd, PP);
-    fp_t Q = fp_mul(U1, PP);
-    g1_xyzz r;
-    r.X = fp_sub(fp_sub(fp_sub(fp_sqr(Rd), PPP), Q), Q);
-    r.Y = fp_sub(fp_mul(Rd, fp_sub(Q, r.X)), fp_mul(S1, PPP));
-    r.ZZ = fp_mul(fp_mul(a.ZZ, b.ZZ), PP);
-    r.ZZZ = fp_mul(fp_mul(a.ZZZ, b.ZZZ), PPP);
-    return r;
+    xyzz_acc A = acc_from(a);
+    acc_add(A, acc_from(b));
+    return acc_result(A);
 }
 
 /* affine from XYZZ given inv = 1 / (ZZ * ZZZ):  1/ZZ = inv ZZZ, 1/ZZZ = inv ZZ */
@@ -165,12 +250,12 @@ TC_HD g1_affine xyzz_to_affine(const g1_xyzz& p) {
 
 /* [k] P for a plain (non-Montgomery) scalar of `nbits` bits, MSB-first double-and-add */
 TC_HD g1_xyzz xyzz_mul_affine(const uint32_t* k, int nbits, const g1_affine& p) {
-    g1_xyzz acc = xyzz_identity();
+    xyzz_acc acc = acc_identity();
     for (int i = nbits - 1; i >= 0; --i) {
-        acc = xyzz_dbl(acc);
-        if ((k[i >> 5] >> (i & 31)) & 1u) acc = xyzz_madd(acc, p);
+        acc_dbl(acc);
+        if ((k[i >> 5] >> (i & 31)) & 1u) acc_madd(acc, p, false);
     }
-    return acc;
+    return acc_result(acc);
 }
 
 /* Jacobian coordinates (x = X / Z^2, y = Y / Z^3; identity: Z = 0): the doubling costs two products and five

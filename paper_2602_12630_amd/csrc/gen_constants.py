@@ -131,7 +131,6 @@ def block28():
     out.append("    static constexpr int32_t PINV = 0x%07x;              /* p^-1 mod 2^28 */" % pow(P_MOD, -1, 1 << 28))
     out.append("    static constexpr int32_t MOD[14] = {%s};" % limbs28(P_MOD))
     out.append("    static constexpr int32_t ONE[14] = {%s};   /* 2^392 mod p */" % limbs28(Rm % P_MOD))
-    out.append("    static constexpr int32_t TO32[14] = {%s};  /* 2^384 mod p: a product with it leaves the 2^384 form */" % limbs28((1 << 384) % P_MOD))
     out.append("};")
     return "\n".join(out)
 

@@ -15,7 +15,6 @@
  */
 #pragma once
 #include "g1.h"
-#include "field28.h"
 #include "rt.h"
 
 namespace tc {
@@ -656,20 +655,16 @@ TC_HD uint32_t find_segment(const uint32_t* prefix, uint32_t n, uint32_t t) {
 /* ---- MSM: balanced segmented sums per bucket -------------------------------------- */
 /* The accumulator lives in the 28-bit-limb form of the field (carry-free products and additions, expanded in place:
  * the loop is 3542 multiply-adds and little else); points enter by a re-cut of their limbs, the sum leaves through
- * one full reduction per coordinate.  The chord rule runs without its case distinctions.  A denominator that could
- * be zero in the field (equal or opposite points) is told from its lowest limb; the lane then gives its sub-run up
- * and enters it in a list, and a second launch (AccAffineRedo) sums the listed sub-runs with the 32-bit routine,
- * which settles every case.  Of the harmless denominators all but about 2^-24 pass the test (the value of the
- * denominator is bounded by a small multiple of p, and only multiples of p within the bound are suspects). */
-struct g1_xyzz28 {
-    fp28 X, Y, ZZ, ZZZ;
-};
+ * one full reduction per coordinate.  The chord rule runs without its case distinctions.  When its denominator may
+ * be zero in the field (equal or opposite points; told from its two lowest limbs, which practically no other value
+ * passes) the lane gives its sub-run up and enters it in a list, and a second launch (AccAffineRedo) sums the
+ * listed sub-runs with the routine that settles every case. */
 /* acc += (x2, y2), both finite; false (acc unusable) when the sum may be a doubling or the identity.
- * `fresh` = regular additions since acc was a re-cut affine point, whose coordinates are 2^8 times larger than a
- * reduced value: |P| <= 317 p in the first addition after it, <= 43 p in the second, <= 5 p from then on. */
-TC_HD bool xyzz28_madd_regular(g1_xyzz28& a, const fp28& x2, const fp28& y2, uint32_t fresh) {
+ * |P| <= 317 p in the first addition after acc was a re-cut affine point (coordinates 2^8 times larger than a
+ * reduced value), <= 43 p in the second, <= 5 p from then on. */
+TC_HD bool xyzz28_madd_regular(g1_xyzz28& a, const fp28& x2, const fp28& y2) {
     fp28 P = fp28_sub(fp28_mul_inline(x2, a.ZZ), a.X);
-    if (fp28_maybe_zero(P, fresh == 0 ? 512u : fresh == 1 ? 64u : 8u)) return false;
+    if (fp28_maybe_zero(P, 512u)) return false;
     fp28 R = fp28_sub(fp28_mul_inline(y2, a.ZZZ), a.Y);
     fp28 PP = fp28_sqr_inline(P);
     fp28 PPP = fp28_mul_inline(P, PP);
@@ -708,7 +703,6 @@ struct AccAffine {
         }
         g1_xyzz28 acc;
         bool have = false;                                        /* acc holds a point (the sum so far is not the identity) */
-        uint32_t fresh = 0;
         for (uint32_t i = begin; i < end; ++i) {
             uint32_t e = sorted[i];
             g1_affine p = pts[e & 0x7FFFFFFFu];
@@ -723,17 +717,17 @@ struct AccAffine {
                 have = true;
                 continue;
             }
-            if (!xyzz28_madd_regular(acc, x2, y2, fresh)) {
+            if (!xyzz28_madd_regular(acc, x2, y2)) {
                 redo_list[atomic_add_u32(redo_count, 1u)] = t;
                 return;
             }
-            ++fresh;
         }
         g1_xyzz r;
         if (!have) {
             r = xyzz_identity();
         } else {
-            r.X = fp28_to_fp(acc.X); r.Y = fp28_to_fp(acc.Y); r.ZZ = fp28_to_fp(acc.ZZ); r.ZZZ = fp28_to_fp(acc.ZZZ);
+            r.X = fp28_to_fp_outlined(acc.X); r.Y = fp28_to_fp_outlined(acc.Y);
+            r.ZZ = fp28_to_fp_outlined(acc.ZZ); r.ZZZ = fp28_to_fp_outlined(acc.ZZZ);
         }
         out[t] = r;
     }
@@ -749,21 +743,21 @@ struct AccAffineRedo {
     g1_xyzz* out;
     const uint32_t* redo_count;
     const uint32_t* redo_list;
+    uint32_t lanes;
     TC_DEV void operator()(uint32_t lane) const {
-        if (lane >= *redo_count) return;
-        uint32_t t = redo_list[lane];
-        uint32_t b = find_segment(lstart, nbk, t);
-        uint32_t begin = start[b] + (t - lstart[b]) * L;
-        uint32_t end = begin + L < start[b + 1] ? begin + L : start[b + 1];
-        const g1_affine* pts = tables[b / nbk_pp];
-        g1_xyzz acc = xyzz_identity();
-        for (uint32_t i = begin; i < end; ++i) {
-            uint32_t e = sorted[i];
-            g1_affine p = pts[e & 0x7FFFFFFFu];
-            if (e >> 31) p.y = fp_neg(p.y);
-            acc = xyzz_madd(acc, p);
+        for (uint32_t k = lane; k < *redo_count; k += lanes) {
+            uint32_t t = redo_list[k];
+            uint32_t b = find_segment(lstart, nbk, t);
+            uint32_t begin = start[b] + (t - lstart[b]) * L;
+            uint32_t end = begin + L < start[b + 1] ? begin + L : start[b + 1];
+            const g1_affine* pts = tables[b / nbk_pp];
+            xyzz_acc acc = acc_identity();
+            for (uint32_t i = begin; i < end; ++i) {
+                uint32_t e = sorted[i];
+                acc_madd(acc, pts[e & 0x7FFFFFFFu], (e >> 31) != 0);
+            }
+            out[t] = acc_result(acc);
         }
-        out[t] = acc;
     }
 };
 struct AccXyzz {
@@ -777,9 +771,10 @@ struct AccXyzz {
         uint32_t b = find_segment(lstart, nbk, t);
         uint32_t begin = start[b] + (t - lstart[b]) * L;
         uint32_t end = begin + L < start[b + 1] ? begin + L : start[b + 1];
-        g1_xyzz acc = in[begin];
-        for (uint32_t i = begin + 1; i < end; ++i) acc = xyzz_add(acc, in[i]);
-        out[t] = acc;
+        if (end - begin == 1) { out[t] = in[begin]; return; }
+        xyzz_acc acc = acc_from(in[begin]);
+        for (uint32_t i = begin + 1; i < end; ++i) acc_add(acc, acc_from(in[i]));
+        out[t] = acc_result(acc);
     }
 };
 /* last pass: one lane per bucket sums whatever partials remain (bounded by the pass plan) */
@@ -789,9 +784,10 @@ struct AccFinal {
     g1_xyzz* bucket;
     TC_DEV void operator()(uint32_t b) const {
         uint32_t begin = start[b], end = start[b + 1];
-        g1_xyzz acc = begin < end ? in[begin] : xyzz_identity();
-        for (uint32_t i = begin + 1; i < end; ++i) acc = xyzz_add(acc, in[i]);
-        bucket[b] = acc;
+        if (end - begin <= 1) { bucket[b] = begin < end ? in[begin] : xyzz_identity(); return; }
+        xyzz_acc acc = acc_from(in[begin]);
+        for (uint32_t i = begin + 1; i < end; ++i) acc_add(acc, acc_from(in[i]));
+        bucket[b] = acc_result(acc);
     }
 };
 
@@ -1143,17 +1139,17 @@ struct RowColSumsPacked {
         uint32_t sub = lane >> 4, j = lane & 15u;
         const g1_xyzz* base = bucket + (uint64_t)w * 32768u;
         if (ph == 0) {
-            g1_xyzz acc;
+            xyzz_acc acc;
             if (g < 32) {                      /* row 4 g + sub: lane takes 16 neighbouring buckets */
                 const g1_xyzz* p = base + (g * 4u + sub) * 256u + j * 16u;
-                acc = p[0];
-                for (int i = 1; i < 16; ++i) acc = xyzz_add(acc, p[i]);
+                acc = acc_from(p[0]);
+                for (int i = 1; i < 16; ++i) acc_add(acc, acc_from(p[i]));
             } else {                           /* column 4 (g - 32) + sub: lane takes 8 of the 128 rows */
                 const g1_xyzz* p = base + ((g - 32u) * 4u + sub) + (uint64_t)(j * 8u) * 256u;
-                acc = p[0];
-                for (int i = 1; i < 8; ++i) acc = xyzz_add(acc, p[(uint64_t)i * 256u]);
+                acc = acc_from(p[0]);
+                for (int i = 1; i < 8; ++i) acc_add(acc, acc_from(p[(uint64_t)i * 256u]));
             }
-            buf[lane] = acc;
+            buf[lane] = acc_result(acc);
             return;
         }
         if (ph <= 4) {
@@ -1176,9 +1172,11 @@ struct RowColFinish {
     const g1_xyzz* w_cols;      /* sum_l (l + 1) C_l */
     g1_xyzz* out;
     TC_DEV void operator()(uint32_t w) const {
-        g1_xyzz t = xyzz_add(w_rows[w], xyzz_neg(s_rows[w]));
-        for (int i = 0; i < 8; ++i) t = xyzz_dbl(t);
-        out[w] = xyzz_add(t, w_cols[w]);
+        xyzz_acc t = acc_from(w_rows[w]);
+        acc_add(t, acc_from(xyzz_neg(s_rows[w])));
+        for (int i = 0; i < 8; ++i) acc_dbl(t);
+        acc_add(t, acc_from(w_cols[w]));
+        out[w] = acc_result(t);
     }
 };
 
@@ -1202,15 +1200,14 @@ struct SmallWindowReduce256 {
         uint32_t w = 2 * wg + win;
         bool live = w < n_windows;
         if (ph == 0) {
-            g1_xyzz acc = xyzz_identity();
+            xyzz_acc acc = acc_identity();
             if (live) {
                 const g1_xyzz* B = bucket + (uint64_t)w * nb;
                 uint32_t first = j < 16 ? j * 16u : j - 16u;                  /* a row, or a column */
                 uint32_t step = j < 16 ? 1u : 16u;
-                if (first < nb) acc = B[first];
-                for (uint32_t t = 1; t < 16 && first + t * step < nb; ++t) acc = xyzz_add(acc, B[first + t * step]);
+                for (uint32_t t = 0; t < 16 && first + t * step < nb; ++t) acc_add(acc, acc_from(B[first + t * step]));
             }
-            buf1[lane] = acc;
+            buf1[lane] = acc_result(acc);
         } else if (ph <= 4) {                /* suffix sums within each family of 16 */
             int s = ph - 1;
             g1_xyzz* cur = (s & 1) ? buf0 : buf1;
@@ -1225,9 +1222,11 @@ struct SmallWindowReduce256 {
             uint32_t stride = 1u << (ph - 6);
             if ((i & (2 * stride - 1)) == 0) buf1[lane] = xyzz_add(buf1[lane], buf1[lane + stride]);
         } else if (j == 0 && live) {
-            g1_xyzz t = xyzz_add(buf1[lane], xyzz_neg(buf0[lane]));   /* sum_h h R_h */
-            for (int d = 0; d < 4; ++d) t = xyzz_dbl(t);
-            out[w] = xyzz_add(t, buf1[lane + 16]);
+            xyzz_acc t = acc_from(buf1[lane]);
+            acc_add(t, acc_from(xyzz_neg(buf0[lane])));                /* sum_h h R_h */
+            for (int d = 0; d < 4; ++d) acc_dbl(t);
+            acc_add(t, acc_from(buf1[lane + 16]));
+            out[w] = acc_result(t);
         }
     }
 };
@@ -1242,9 +1241,11 @@ struct WindowFinish {
     g1_xyzz* out;
     TC_DEV void operator()(uint32_t w) const {
         if (G == 1) { out[w] = w1[w]; return; }
-        g1_xyzz t = xyzz_add(w2[w], xyzz_neg(s2[w]));
-        for (int i = 0; i < log_block; ++i) t = xyzz_dbl(t);
-        out[w] = xyzz_add(t, w1[w]);
+        xyzz_acc t = acc_from(w2[w]);
+        acc_add(t, acc_from(xyzz_neg(s2[w])));
+        for (int i = 0; i < log_block; ++i) acc_dbl(t);
+        acc_add(t, acc_from(w1[w]));
+        out[w] = acc_result(t);
     }
 };
 /* One lane per problem: Horner over its windows, result = sum_w 2^(c w) Wsum_w */
@@ -1254,12 +1255,13 @@ struct WindowCombine {
     g1_xyzz* out;
     TC_DEV void operator()(uint32_t p) const {
         const g1_xyzz* ws = wsum + (uint64_t)p * W;
-        g1_xyzz acc = ws[W - 1];
+        if (W == 1) { out[p] = ws[0]; return; }
+        xyzz_acc acc = acc_from(ws[W - 1]);
         for (int w = W - 2; w >= 0; --w) {
-            for (int i = 0; i < c; ++i) acc = xyzz_dbl(acc);
-            acc = xyzz_add(acc, ws[w]);
+            for (int i = 0; i < c; ++i) acc_dbl(acc);
+            acc_add(acc, acc_from(ws[w]));
         }
-        out[p] = acc;
+        out[p] = acc_result(acc);
     }
 };
 
@@ -1354,17 +1356,12 @@ struct FbChunkFill {           /* lane (bw, chunk): multiples j0 .. j0 + 63 of w
 };
 
 /* acc += sum_w digit_w(v) * table[(k, w)] for a canonical Fr value v */
-TC_HD g1_xyzz fb_mul_accumulate(g1_xyzz acc, const g1_affine* table, uint32_t k, const uint32_t* v) {
+TC_HD void fb_mul_accumulate(xyzz_acc& acc, const g1_affine* table, uint32_t k, const uint32_t* v) {
     uint32_t carry = 0;
     for (int w = 0; w < FB_W; ++w) {
         int32_t d = fr_window_digit(v, w, FB_C, carry);
-        if (d) {
-            g1_affine p = table[((uint64_t)k * FB_W + w) * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u];
-            if (d < 0) p.y = fp_neg(p.y);
-            acc = xyzz_madd(acc, p);
-        }
+        if (d) acc_madd(acc, table[((uint64_t)k * FB_W + w) * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u], d < 0);
     }
-    return acc;
 }
 /* windows 2h and 2h + 1 only: digit_{2h}(v) table[(k, 2h)] + digit_{2h+1}(v) table[(k, 2h + 1)].  The digits are
  * found first (their carries come from the windows below), so that the two additions sit outside any loop
@@ -1377,26 +1374,22 @@ TC_HD g1_xyzz fb_window_pair(const g1_affine* table, uint32_t k, const uint32_t*
         if (w == (int)(2 * h)) d0 = d;
         if (w == (int)(2 * h + 1)) d1 = d;
     }
-    g1_xyzz acc = xyzz_identity();
+    xyzz_acc acc = acc_identity();
     for (int j = 0; j < 2; ++j) {
         int32_t d = j ? d1 : d0;
         g1_affine p = affine_identity();
-        if (d) {
-            p = table[((uint64_t)k * FB_W + 2 * h + j) * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u];
-            if (d < 0) p.y = fp_neg(p.y);
-        }
-        acc = xyzz_madd(acc, p);
+        if (d) p = table[((uint64_t)k * FB_W + 2 * h + j) * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u];
+        acc_madd(acc, p, d < 0);
     }
-    return acc;
+    return acc_result(acc);
 }
 /* same for a small signed integer |d| <= 2^15 (one lookup when the window is 16 bits wide) */
-TC_HD g1_xyzz fb_small_accumulate(g1_xyzz acc, const g1_affine* table, uint32_t k, int32_t d) {
-    if (!d) return acc;
+TC_HD void fb_small_accumulate(xyzz_acc& acc, const g1_affine* table, uint32_t k, int32_t d) {
+    if (!d) return;
     uint32_t mag = (uint32_t)(d < 0 ? -d : d);
     if (FB_C == 16) {
-        g1_affine p = table[((uint64_t)k * FB_W) * FB_NB + mag - 1u];
-        if (d < 0) p.y = fp_neg(p.y);
-        return xyzz_madd(acc, p);
+        acc_madd(acc, table[((uint64_t)k * FB_W) * FB_NB + mag - 1u], d < 0);
+        return;
     }
     uint32_t v[8] = {mag, 0, 0, 0, 0, 0, 0, 0};
     uint32_t carry = 0;
@@ -1404,12 +1397,9 @@ TC_HD g1_xyzz fb_small_accumulate(g1_xyzz acc, const g1_affine* table, uint32_t 
         int32_t dw = fr_window_digit(v, w, FB_C, carry);
         if (dw) {
             bool negative = (dw < 0) != (d < 0);
-            g1_affine p = table[((uint64_t)k * FB_W + w) * FB_NB + (uint32_t)(dw < 0 ? -dw : dw) - 1u];
-            if (negative) p.y = fp_neg(p.y);
-            acc = xyzz_madd(acc, p);
+            acc_madd(acc, table[((uint64_t)k * FB_W + w) * FB_NB + (uint32_t)(dw < 0 ? -dw : dw) - 1u], negative);
         }
     }
-    return acc;
 }
 
 /* ---- SRS generation (Def. 4.1 Setup, Lagrange image) ---------------------------------- */
@@ -1438,7 +1428,9 @@ struct SrsGen {                /* lane i: S^(a)[i] = [prod_{j>=a} l_j[i_j]] G */
         fr_t s = ell[ell_off[first_axis] + idx[first_axis]];
         for (int j = first_axis + 1; j < shape.m; ++j) s = fr_mul(s, ell[ell_off[j] + idx[j]]);
         fr_t plain = fe_to_plain(s);
-        out[t] = fb_mul_accumulate(xyzz_identity(), gtable, 0, plain.l);
+        xyzz_acc acc = acc_identity();
+        fb_mul_accumulate(acc, gtable, 0, plain.l);
+        out[t] = acc_result(acc);
     }
 };
 
@@ -1495,13 +1487,13 @@ struct NodeCommitSmall {
     const g1_affine* table;
     g1_xyzz* out;
     TC_DEV void operator()(uint32_t a) const {
-        g1_xyzz acc = xyzz_identity();
+        xyzz_acc acc = acc_identity();
         for (uint32_t k = 0; k < g.B; ++k) {
             int64_t f = child_index(g, a, k);
             if (f < 0) continue;
-            acc = fb_small_accumulate(acc, table, k, small_scalar(payload, dtype, (uint64_t)f));
+            fb_small_accumulate(acc, table, k, small_scalar(payload, dtype, (uint64_t)f));
         }
-        out[a] = acc;
+        out[a] = acc_result(acc);
     }
 };
 /* the same for a bottom level of very few nodes: every child its own slot of a cooperative sum */
@@ -1513,12 +1505,12 @@ struct NodeSmallSrc {
     g1_xyzz* out;
     TC_DEV uint32_t count(uint32_t) const { return g.B < 256u ? g.B : 256u; }
     TC_DEV g1_xyzz load(uint32_t node, uint32_t i) const {
-        g1_xyzz acc = xyzz_identity();
+        xyzz_acc acc = acc_identity();
         for (uint32_t k = i; k < g.B; k += 256) {
             int64_t f = child_index(g, node, k);
-            if (f >= 0) acc = fb_small_accumulate(acc, table, k, small_scalar(payload, dtype, (uint64_t)f));
+            if (f >= 0) fb_small_accumulate(acc, table, k, small_scalar(payload, dtype, (uint64_t)f));
         }
-        return acc;
+        return acc_result(acc);
     }
     TC_DEV void store(uint32_t node, const g1_xyzz& r) const { out[node] = r; }
 };
@@ -1531,9 +1523,9 @@ struct NodeCommitFr {
     TC_DEV void operator()(uint32_t t) const {
         uint32_t a = t / g.B, k = t % g.B;
         int64_t f = child_index(g, a, k);
-        g1_xyzz acc = xyzz_identity();
-        if (f >= 0) acc = fb_mul_accumulate(acc, table, k, below[f].l);
-        out[t] = acc;
+        xyzz_acc acc = acc_identity();
+        if (f >= 0) fb_mul_accumulate(acc, table, k, below[f].l);
+        out[t] = acc_result(acc);
     }
 };
 /* upper levels, arity a power of two <= 64: a lane commits FB_W >> logH consecutive windows of one child
@@ -1559,7 +1551,7 @@ struct NodeCommitFrCoop {
         uint32_t r = (uint32_t)(t & ((1u << logL) - 1u));
         if (ph == 0) {
             uint32_t k = r >> logH, h = r & ((1u << logH) - 1u);
-            g1_xyzz acc = xyzz_identity();
+            xyzz_acc acc = acc_identity();
             if (a < n_nodes) {
                 int64_t f = child_index(g, a, k);
                 if (f >= 0) {
@@ -1569,15 +1561,11 @@ struct NodeCommitFrCoop {
                     for (int w = 0; w < w0; ++w) (void)fr_window_digit(v, w, FB_C, carry);     /* carry into the first window */
                     for (int j = 0; j < per; ++j) {            /* the same trip count in every lane */
                         int32_t d = fr_window_digit(v, w0 + j, FB_C, carry);
-                        if (d) {
-                            g1_affine p = table[((uint64_t)k * FB_W + w0 + j) * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u];
-                            if (d < 0) p.y = fp_neg(p.y);
-                            acc = xyzz_madd(acc, p);
-                        }
+                        if (d) acc_madd(acc, table[((uint64_t)k * FB_W + w0 + j) * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u], d < 0);
                     }
                 }
             }
-            buf[lane] = acc;
+            buf[lane] = acc_result(acc);
             return;
         }
         /* pairwise sums, the active lanes packed to the front of the workgroup: whole waves drop out as the
@@ -1605,7 +1593,7 @@ struct NodeWindowSrc {
     g1_xyzz* out;               /* n_nodes */
     TC_DEV uint32_t count(uint32_t) const { return g.B * (uint32_t)FB_W < 256u ? g.B * (uint32_t)FB_W : 256u; }
     TC_DEV g1_xyzz load(uint32_t node, uint32_t i) const {
-        g1_xyzz acc = xyzz_identity();
+        xyzz_acc acc = acc_identity();
         for (uint32_t idx = i; idx < g.B * (uint32_t)FB_W; idx += 256) {
             uint32_t k = idx / (uint32_t)FB_W, w = idx % (uint32_t)FB_W;
             int64_t f = child_index(g, node, k);
@@ -1615,11 +1603,9 @@ struct NodeWindowSrc {
             int32_t d = 0;
             for (uint32_t x = 0; x <= w; ++x) d = fr_window_digit(v, (int)x, FB_C, carry);
             if (!d) continue;
-            g1_affine p = table[((uint64_t)k * FB_W + w) * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u];
-            if (d < 0) p.y = fp_neg(p.y);
-            acc = xyzz_madd(acc, p);
+            acc_madd(acc, table[((uint64_t)k * FB_W + w) * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u], d < 0);
         }
-        return acc;
+        return acc_result(acc);
     }
     TC_DEV void store(uint32_t node, const g1_xyzz& r) const { out[node] = r; }
 };
@@ -1630,9 +1616,9 @@ struct SumGroups {
     g1_xyzz* out;
     TC_DEV void operator()(uint32_t t) const {
         const g1_xyzz* p = in + (uint64_t)t * group;
-        g1_xyzz acc = p[0];
-        for (uint32_t i = 1; i < group; ++i) acc = xyzz_add(acc, p[i]);
-        out[t] = acc;
+        xyzz_acc acc = acc_from(p[0]);
+        for (uint32_t i = 1; i < group; ++i) acc_add(acc, acc_from(p[i]));
+        out[t] = acc_result(acc);
     }
 };
 /* out[t] = sum of segment t of `in`: the elements in[off[t] * scale .. off[t + 1] * scale) */
@@ -1647,9 +1633,10 @@ struct SegmentSrc {
     }
     TC_DEV g1_xyzz load(uint32_t t, uint32_t i) const {
         uint64_t lo = (uint64_t)off[t] * scale, hi = (uint64_t)off[t + 1] * scale;
-        g1_xyzz acc = in[lo + i];
-        for (uint64_t x = lo + i + 256; x < hi; x += 256) acc = xyzz_add(acc, in[x]);
-        return acc;
+        if (lo + i + 256 >= hi) return in[lo + i];
+        xyzz_acc acc = acc_from(in[lo + i]);
+        for (uint64_t x = lo + i + 256; x < hi; x += 256) acc_add(acc, acc_from(in[x]));
+        return acc_result(acc);
     }
     TC_DEV void store(uint32_t t, const g1_xyzz& r) const { out[t] = r; }
 };

@@ -1368,9 +1368,12 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         RT((rt::launch_waves<64, 3>(max_part, ctx->stream, AccAffine{tables, nbk_pp, sorted, start, lstart, nbk, L1, bufA, redo, redo + 1})));
         prof_end(ctx, TC_PROF_BUCKET_ACC, e0, e1);
     }
-    /* sub-runs with equal or opposite points in them (and the odd false alarm): a handful in honest inputs; the
-     * launch has a lane for every sub-run because a degenerate input sends all of them here */
-    RT(rt::launch<64>(max_part, ctx->stream, AccAffineRedo{tables, nbk_pp, sorted, start, lstart, nbk, L1, bufA, redo, redo + 1}));
+    /* sub-runs with equal or opposite points in them: none in honest inputs; a degenerate input sends every sub-run
+     * here, so the launch is as wide as the chip and its lanes stride over the list */
+    {
+        uint32_t redo_lanes = (uint32_t)std::min<uint64_t>(max_part, ACC_RESIDENT_LANES);
+        RT(rt::launch<64>(redo_lanes, ctx->stream, AccAffineRedo{tables, nbk_pp, sorted, start, lstart, nbk, L1, bufA, redo, redo + 1, redo_lanes}));
+    }
 
     /* Middle passes shrink the per-bucket partial count by L2 until at most L2 remain. */
     uint32_t acc_terms = 0, acc_lanes = 0;             /* non-zero digits and sub-runs of the first pass (profiling only) */

@@ -128,3 +128,52 @@ def check_field_arithmetic(run, n_fp, n_fr):
     nzr = [v if v else 7 for v in ar]
     got = unpack(run(8, pack(nzr, 8), pack(nzr, 8), 8), 8)
     assert all(g == RR * RR * pow(v, -1, Rr) % Rr for g, v in zip(got, nzr)), "Fr inverse"
+
+
+def check_repeated_points(ctx, upload):
+    """Commitments over public parameters in which most points repeat or are each other's negatives, with scalars of
+    few distinct values: the bucket sums then run into doublings, sums that cancel to the identity and additions to
+    the identity, the cases that the accumulation kernel's fast form of the chord rule hands to the slower routine.
+    Expected values: the C oracle's term-by-term sum over the same points.  `upload` puts a numpy array where the
+    context reads it (device memory, or the array itself on the host build)."""
+    import random
+
+    import paper_2602_12630_amd as T
+
+    shape = (32, 128)
+    n = 32 * 128
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, 0)
+    data = bytes(srs.export())
+    srs.close()
+    assert len(data) == 56 + 96 * n
+    pts = [data[56 + 96 * i : 56 + 96 * (i + 1)] for i in range(n)]
+
+    def neg(pt):
+        return pt[:48] + ((ec.P - int.from_bytes(pt[48:], "little")) % ec.P).to_bytes(48, "little")
+
+    rng = random.Random(5)
+    pool = pts[:6]
+    mixed = []
+    for i in range(n):
+        if rng.random() < 0.25:
+            mixed.append(pts[i])
+        else:
+            q = pool[rng.randrange(len(pool))]
+            mixed.append(q if rng.random() < 0.5 else neg(q))
+    same = [pts[0]] * n                                     # one point throughout: every addition is a doubling or a cancellation
+    nrng = np.random.default_rng(9)
+    cases = [
+        (mixed, nrng.integers(-3, 4, size=shape).astype(np.int8), T.TC_I8),
+        (mixed, nrng.choice(np.array([-700, -5, 5, 9, 700], np.int16), size=shape), T.TC_I16),
+        (mixed, nrng.integers(-32768, 32768, size=shape).astype(np.int16), T.TC_I16),
+        (same, nrng.integers(-2, 3, size=shape).astype(np.int8), T.TC_I8),
+        (same, np.full(shape, 77, np.int16), T.TC_I16),
+        (same, np.where(nrng.random(shape) < 0.5, 1, -1).astype(np.int8), T.TC_I8),
+    ]
+    for points, X, dtype in cases:
+        blob = b"".join(points)
+        back = ctx.srs_import(data[:56] + blob)
+        want, _ = cbind.msm_naive(X, blob, HOST_THREADS)
+        got = ctx.commit(back, upload(X), dtype)
+        back.close()
+        assert got == ec.g1_to_bytes(want), (dtype, X.reshape(-1)[:8])

@@ -12,7 +12,7 @@ from oracle import bls12_381 as ec
 from oracle import cbind, quantize, tc, terkle
 from oracle.bls12_381 import R
 
-from gpu_util import HOST_THREADS, TAU_BYTES, Stopwatch, check_field_arithmetic, fr_bytes_array, oracle_pool, parse_proof, pps, serialize_steps, to_device
+from gpu_util import HOST_THREADS, TAU_BYTES, Stopwatch, check_field_arithmetic, check_repeated_points, fr_bytes_array, oracle_pool, parse_proof, pps, serialize_steps, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -64,6 +64,12 @@ def test_device_field_arithmetic_against_integers(T, ctx):
         return out.cpu().numpy().view(np.uint32)
 
     check_field_arithmetic(run, 4096, 1024)
+
+
+def test_commit_over_repeated_points(ctx):
+    """Equal and opposite points inside the bucket sums: the sub-runs that the fast accumulation gives up and the
+    second launch redoes with every case of the group law (see check_repeated_points)."""
+    check_repeated_points(ctx, to_device)
 
 
 def test_srs_points_match_oracle(ctx, c1):
