@@ -126,7 +126,8 @@ TC_HD fp28 fp28_mont(const fp28& a, const fp28& b, const fp28& c, const fp28& e)
     return r;
 }
 /* expanded in place: for a kernel whose loop is a handful of products and nothing else (no operand shuffling around
- * calls, and the scheduler sees across products) */
+ * calls, and the scheduler sees across products).  The fused difference exists in this form only: the four operands
+ * of a call would not fit the 32 registers in which arguments travel. */
 TC_HD fp28 fp28_mul_inline(const fp28& a, const fp28& b) { return fp28_mont<FP28_MUL>(a, b, a, a); }
 TC_HD fp28 fp28_sqr_inline(const fp28& a) { return fp28_mont<FP28_SQR>(a, a, a, a); }
 TC_HD fp28 fp28_mul_sub_inline(const fp28& a, const fp28& b, const fp28& c, const fp28& e) { return fp28_mont<FP28_MUL_SUB>(a, b, c, e); }
@@ -147,14 +148,7 @@ __device__ __attribute__((noinline)) fp28 fp28_mul_call(i32x4 a0, i32x4 a1, i32x
 __device__ __attribute__((noinline)) fp28 fp28_sqr_call(i32x4 a0, i32x4 a1, i32x4 a2, i32x2 a3) {
     return fp28_sqr_inline(fp28_unpack(a0, a1, a2, a3));
 }
-__device__ __attribute__((noinline)) fp28 fp28_mul_sub_call(i32x4 a0, i32x4 a1, i32x4 a2, i32x2 a3, i32x4 b0, i32x4 b1, i32x4 b2, i32x2 b3,
-                                                            i32x4 c0, i32x4 c1, i32x4 c2, i32x2 c3, i32x4 e0, i32x4 e1, i32x4 e2, i32x2 e3) {
-    return fp28_mul_sub_inline(fp28_unpack(a0, a1, a2, a3), fp28_unpack(b0, b1, b2, b3), fp28_unpack(c0, c1, c2, c3), fp28_unpack(e0, e1, e2, e3));
-}
 #define TC_FP28_ARGS(a) i32x4{a.l[0], a.l[1], a.l[2], a.l[3]}, i32x4{a.l[4], a.l[5], a.l[6], a.l[7]}, i32x4{a.l[8], a.l[9], a.l[10], a.l[11]}, i32x2{a.l[12], a.l[13]}
-__device__ __forceinline__ fp28 fp28_mul_sub(const fp28& a, const fp28& b, const fp28& c, const fp28& e) {
-    return fp28_mul_sub_call(TC_FP28_ARGS(a), TC_FP28_ARGS(b), TC_FP28_ARGS(c), TC_FP28_ARGS(e));
-}
 __device__ __forceinline__ fp28 fp28_mul(const fp28& a, const fp28& b) {
     return fp28_mul_call(i32x4{a.l[0], a.l[1], a.l[2], a.l[3]}, i32x4{a.l[4], a.l[5], a.l[6], a.l[7]}, i32x4{a.l[8], a.l[9], a.l[10], a.l[11]},
                          i32x2{a.l[12], a.l[13]}, i32x4{b.l[0], b.l[1], b.l[2], b.l[3]}, i32x4{b.l[4], b.l[5], b.l[6], b.l[7]},
@@ -167,16 +161,33 @@ __device__ __forceinline__ fp28 fp28_sqr(const fp28& a) {
 #elif defined(__HIPCC__)
 __device__ fp28 fp28_mul(const fp28& a, const fp28& b);
 __device__ fp28 fp28_sqr(const fp28& a);
-__device__ fp28 fp28_mul_sub(const fp28& a, const fp28& b, const fp28& c, const fp28& e);
-__host__ inline fp28 fp28_mul_sub(const fp28& a, const fp28& b, const fp28& c, const fp28& e) { return fp28_mul_sub_inline(a, b, c, e); }
 __host__ inline fp28 fp28_mul(const fp28& a, const fp28& b) { return fp28_mul_inline(a, b); }
 __host__ inline fp28 fp28_sqr(const fp28& a) { return fp28_sqr_inline(a); }
 #else
 inline fp28 fp28_mul(const fp28& a, const fp28& b) { return fp28_mul_inline(a, b); }
 inline fp28 fp28_sqr(const fp28& a) { return fp28_sqr_inline(a); }
-inline fp28 fp28_mul_sub(const fp28& a, const fp28& b, const fp28& c, const fp28& e) { return fp28_mul_sub_inline(a, b, c, e); }
 #endif
 
+/* 12 words of 32 bits from the bits 8 .. 391 of a non-negative value with normal limbs */
+TC_HD fp_t fp28_pack_shr8(const uint32_t (&u)[14]) {
+    fp_t r;
+#pragma unroll
+    for (int i = 0; i < 12; ++i) {
+        const int o = 32 * i + 8, j = o / 28, sh = o % 28;
+        uint32_t w = u[j] >> sh;
+        if (j + 1 < 14) w |= u[j + 1] << (28 - sh);
+        if (56 - sh < 32 && j + 2 < 14) w |= u[j + 2] << (56 - sh);
+        r.l[i] = w;
+    }
+    return r;
+}
+/* fp28_from_fp undone: the element whose re-cut `a` is (no arithmetic: the limbs are slices of its bits) */
+TC_HD fp_t fp28_recut_to_fp(const fp28& a) {
+    uint32_t u[14];
+#pragma unroll
+    for (int j = 0; j < 14; ++j) u[j] = (uint32_t)a.l[j];
+    return fp28_pack_shr8(u);
+}
 /* The canonical element of the 32-bit form (radix 2^384) for a value v with -256 p <= v < 512 p.  The two radices
  * differ by 2^8, so this is a Montgomery step of eight bits: a multiple q p with v + q p = 0 (mod 2^8), taken from
  * 256 p .. 511 p so that the sum is not negative, then the shift; (v + q p) / 2^8 < 4 p. */
@@ -192,21 +203,10 @@ TC_HD fp_t fp28_to_fp(const fp28& a) {
     }
     c += (int64_t)q * (int64_t)Fp28Params::MOD[13] + (int64_t)a.l[13];
     u[13] = (uint32_t)c;                   /* below 2^26 */
-    fp_t r;
-#pragma unroll
-    for (int i = 0; i < 12; ++i) {
-        const int o = 32 * i + 8, j = o / 28, sh = o % 28;
-        uint32_t w = u[j] >> sh;
-        if (j + 1 < 14) w |= u[j + 1] << (28 - sh);
-        if (56 - sh < 32 && j + 2 < 14) w |= u[j + 2] << (56 - sh);
-        r.l[i] = w;
-    }
+    fp_t r = fp28_pack_shr8(u);
     return fe_reduce_once<FpParams>(fe_reduce_once<FpParams>(fe_reduce_once<FpParams>(r, 0u), 0u), 0u);
 }
 
-/* is the value a multiple of p (zero in the field)?  For |value| <= K p, K < 2^20.  value = k p forces
- * (l_0 p^-1) mod 2^28 = k mod 2^28, which all but (2 K + 1) 2^-28 of the other values fail at once; for a k that
- * passes, value - k p is worked out limb by limb. */
 /* the same as a real function on the device: for the end of a kernel whose loop must keep its registers */
 #if defined(__HIP_DEVICE_COMPILE__)
 __device__ __attribute__((noinline)) fp_t fp28_to_fp_call(i32x4 a0, i32x4 a1, i32x4 a2, i32x2 a3) { return fp28_to_fp(fp28_unpack(a0, a1, a2, a3)); }

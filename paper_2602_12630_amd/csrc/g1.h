@@ -97,28 +97,17 @@ TC_HD g1_xyzz xyzz28_to(const g1_xyzz28& p) {
     return r;
 }
 
-/* 2 P from (X, Y, ZZ, ZZZ) of a finite P with Y != 0, coordinates below 315 p, normal limbs.
- * U <= 630 p, V <= 159 p, W <= 41 p, S <= 21 p, M <= 120 p, X3 in (-42 p, 7 p), Y3 in (-6 p, 4 p), ZZ3 <= 21 p, ZZZ3 <= 6 p. */
-TC_HD g1_xyzz28 xyzz28_dbl_finite(const g1_xyzz28& p) {
-    fp28 U = fp28_add(p.Y, p.Y);
-    fp28 V = fp28_sqr(U);
-    fp28 W = fp28_mul(U, V);
-    fp28 S = fp28_mul(p.X, V);
-    fp28 X2 = fp28_sqr(p.X);
-    fp28 M = fp28_carry(fp28_add(fp28_add(X2, X2), X2));
-    g1_xyzz28 r;
-    r.X = fp28_carry(fp28_sub(fp28_sub(fp28_sqr(M), S), S));
-    r.Y = fp28_mul_sub(M, fp28_sub(S, r.X), W, p.Y);
-    r.ZZ = fp28_mul(V, p.ZZ);
-    r.ZZZ = fp28_mul(W, p.ZZZ);
-    return r;
-}
-
 /* A running sum that stays in the 28-bit form between additions: loops convert once at the end.  `inf` says that
- * the sum is the identity (v then holds nothing).  Every case of the group law is settled here. */
+ * the sum is the identity (v then holds nothing).  Every case of the group law is settled here.
+ *
+ * The products are calls (operands and result in registers), and calls keep their order: each one is placed where
+ * it ends the life of an operand, so that a caller holds about ten field elements across a call.  (Measured against
+ * whole operations as real functions with the products expanded in place and the sums passed by address: the tree
+ * levels and the partial-sum passes 5 to 12 % slower that way.) */
 struct xyzz_acc {
     g1_xyzz28 v;
     bool inf;
+    bool lone;      /* the sum is one affine point so far: X, Y are re-cuts of its coordinates, ZZ = ZZZ = 1; it leaves as it came */
 };
 TC_HD xyzz_acc acc_identity() {
     xyzz_acc a;
@@ -127,6 +116,7 @@ TC_HD xyzz_acc acc_identity() {
     a.v.ZZ = fp28{};
     a.v.ZZZ = fp28{};
     a.inf = true;
+    a.lone = false;
     return a;
 }
 TC_HD xyzz_acc acc_from(const g1_xyzz& p) {
@@ -134,34 +124,60 @@ TC_HD xyzz_acc acc_from(const g1_xyzz& p) {
     xyzz_acc a;
     a.v = xyzz28_from(p);
     a.inf = false;
+    a.lone = false;
     return a;
 }
 TC_HD g1_xyzz acc_result(const xyzz_acc& a) {
     if (a.inf) return xyzz_identity();
+    if (a.lone) {
+        g1_xyzz r;
+        r.X = fp28_recut_to_fp(a.v.X);
+        r.Y = fp28_recut_to_fp(a.v.Y);
+        r.ZZ = fe_one<FpParams>();
+        r.ZZZ = fe_one<FpParams>();
+        return r;
+    }
     g1_xyzz r = xyzz28_to(a.v);
     if (fe_is_zero(r.ZZ)) return xyzz_identity();      /* a point of order two doubled: none on this curve */
     return r;
 }
-/* a <- 2 a */
+
+/* a <- 2 a, from (X, Y, ZZ, ZZZ) of a finite point with Y != 0, coordinates below 315 p; X, ZZ, ZZZ with normal
+ * limbs, the limbs of Y (a difference of two products, or a negated coordinate) within 2^28 either way.
+ * U <= 630 p, V <= 159 p, W <= 41 p, S <= 21 p, M <= 120 p, X3 in (-42 p, 7 p), Y3 in (-6 p, 4 p), ZZ3 <= 21 p, ZZZ3 <= 6 p. */
 TC_HD void acc_dbl(xyzz_acc& a) {
     if (a.inf) return;
-    a.v = xyzz28_dbl_finite(a.v);
+    a.lone = false;
+    g1_xyzz28& p = a.v;
+    fp28 U = fp28_add(p.Y, p.Y);
+    fp28 V = fp28_sqr(U);
+    p.ZZ = fp28_mul(V, p.ZZ);
+    fp28 W = fp28_mul(U, V);
+    p.ZZZ = fp28_mul(W, p.ZZZ);
+    fp28 S = fp28_mul(p.X, V);
+    fp28 X2 = fp28_sqr(p.X);
+    fp28 M = fp28_carry(fp28_add(fp28_add(X2, X2), X2));
+    p.X = fp28_carry(fp28_sub(fp28_sub(fp28_sqr(M), S), S));
+    p.Y = fp28_sub(fp28_mul(M, fp28_sub(S, p.X)), fp28_mul(W, p.Y));
 }
-/* a <- a + q, q affine: chord rule, tangent rule for equal points, identity for opposite ones.
+
+/* a <- a + q (or a - q), q affine: chord rule, tangent rule for equal points, identity for opposite ones.
  * With a below 315 p: U2, S2 <= 41 p, |P|, |R| <= 356 p, PP <= 52 p, PPP, Q <= 8 p, X3 in (-20 p, 52 p), Y3 within 12 p,
  * ZZ3 <= 8 p, ZZZ3 <= 2 p. */
 TC_HD void acc_madd(xyzz_acc& a, const g1_affine& q, bool negate) {
     if (affine_is_identity(q)) return;
-    fp28 x2 = fp28_from_fp(q.x), y2 = fp28_from_fp(q.y);
-    if (negate) y2 = fp28_sub(fp28{}, y2);
     if (a.inf) {
-        a.v.X = x2;
-        a.v.Y = y2;
+        a.v.X = fp28_from_fp(q.x);
+        a.v.Y = fp28_from_fp(negate ? fp_neg(q.y) : q.y);
         a.v.ZZ = fp28_one();
         a.v.ZZZ = fp28_one();
         a.inf = false;
+        a.lone = true;
         return;
     }
+    a.lone = false;
+    fp28 x2 = fp28_from_fp(q.x), y2 = fp28_from_fp(q.y);
+    if (negate) y2 = fp28_sub(fp28{}, y2);
     fp28 Pd = fp28_sub(fp28_mul(x2, a.v.ZZ), a.v.X);
     fp28 Rd = fp28_sub(fp28_mul(y2, a.v.ZZZ), a.v.Y);
     if (fp28_is_zero(Pd, 512u)) {
@@ -170,43 +186,44 @@ TC_HD void acc_madd(xyzz_acc& a, const g1_affine& q, bool negate) {
             a.v.Y = y2;
             a.v.ZZ = fp28_one();
             a.v.ZZZ = fp28_one();
-            a.v = xyzz28_dbl_finite(a.v);
+            acc_dbl(a);
         } else {
             a.inf = true;
         }
         return;
     }
     fp28 PP = fp28_sqr(Pd);
+    a.v.ZZ = fp28_mul(a.v.ZZ, PP);
     fp28 PPP = fp28_mul(Pd, PP);
     fp28 Q = fp28_mul(a.v.X, PP);
-    fp28 X3 = fp28_carry(fp28_sub(fp28_sub(fp28_sub(fp28_sqr(Rd), PPP), Q), Q));
-    a.v.Y = fp28_mul_sub(Rd, fp28_sub(Q, X3), a.v.Y, PPP);
-    a.v.ZZ = fp28_mul(a.v.ZZ, PP);
     a.v.ZZZ = fp28_mul(a.v.ZZZ, PPP);
-    a.v.X = X3;
+    a.v.X = fp28_carry(fp28_sub(fp28_sub(fp28_sub(fp28_sqr(Rd), PPP), Q), Q));
+    a.v.Y = fp28_sub(fp28_mul(Rd, fp28_sub(Q, a.v.X)), fp28_mul(a.v.Y, PPP));
 }
 /* a <- a + b.  With both below 315 p: U, S <= 41 p, |P|, |R| <= 82 p, PP <= 4 p, PPP, Q <= 2 p, X3 in (-6 p, 4 p),
  * Y3 within 2 p, ZZ3, ZZZ3 <= 2 p. */
 TC_HD void acc_add(xyzz_acc& a, const xyzz_acc& b) {
     if (b.inf) return;
     if (a.inf) { a = b; return; }
+    a.lone = false;
     fp28 U1 = fp28_mul(a.v.X, b.v.ZZ);
-    fp28 S1 = fp28_mul(a.v.Y, b.v.ZZZ);
     fp28 Pd = fp28_sub(fp28_mul(b.v.X, a.v.ZZ), U1);
+    fp28 S1 = fp28_mul(a.v.Y, b.v.ZZZ);
     fp28 Rd = fp28_sub(fp28_mul(b.v.Y, a.v.ZZZ), S1);
     if (fp28_is_zero(Pd, 128u)) {
-        if (fp28_is_zero(Rd, 128u)) a.v = xyzz28_dbl_finite(a.v);
+        if (fp28_is_zero(Rd, 128u)) acc_dbl(a);
         else a.inf = true;
         return;
     }
+    a.v.ZZ = fp28_mul(a.v.ZZ, b.v.ZZ);
+    a.v.ZZZ = fp28_mul(a.v.ZZZ, b.v.ZZZ);
     fp28 PP = fp28_sqr(Pd);
+    a.v.ZZ = fp28_mul(a.v.ZZ, PP);
     fp28 PPP = fp28_mul(Pd, PP);
     fp28 Q = fp28_mul(U1, PP);
-    fp28 X3 = fp28_carry(fp28_sub(fp28_sub(fp28_sub(fp28_sqr(Rd), PPP), Q), Q));
-    a.v.Y = fp28_mul_sub(Rd, fp28_sub(Q, X3), S1, PPP);
-    a.v.ZZ = fp28_mul(fp28_mul(a.v.ZZ, b.v.ZZ), PP);
-    a.v.ZZZ = fp28_mul(fp28_mul(a.v.ZZZ, b.v.ZZZ), PPP);
-    a.v.X = X3;
+    a.v.ZZZ = fp28_mul(a.v.ZZZ, PPP);
+    a.v.X = fp28_carry(fp28_sub(fp28_sub(fp28_sub(fp28_sqr(Rd), PPP), Q), Q));
+    a.v.Y = fp28_sub(fp28_mul(Rd, fp28_sub(Q, a.v.X)), fp28_mul(S1, PPP));
 }
 
 /* the same on stored points (coordinates in the 32-bit form), one operation at a time */
@@ -233,6 +250,90 @@ TC_HD g1_xyzz xyzz_add(const g1_xyzz& a, const g1_xyzz& b) {
     xyzz_acc A = acc_from(a);
     acc_add(A, acc_from(b));
     return acc_result(A);
+}
+
+/* The same operations computed in the 32-bit form throughout, for kernels whose register budget is set by other
+ * things (the cooperative sums that keep their points in LDS): slower arithmetic, about 100 registers less. */
+/* 2 (x, y) for an affine point, tangent rule in XYZZ form */
+TC_HD g1_xyzz xyzz_dbl_affine32(const g1_affine& p) {
+    if (affine_is_identity(p) || fe_is_zero(p.y)) return xyzz_identity();
+    fp_t U = fp_dbl(p.y);
+    fp_t V = fp_sqr(U);
+    fp_t W = fp_mul(U, V);
+    fp_t S = fp_mul(p.x, V);
+    fp_t X2 = fp_sqr(p.x);
+    fp_t M = fp_add(fp_dbl(X2), X2);
+    g1_xyzz r;
+    r.X = fp_sub(fp_sub(fp_sqr(M), S), S);
+    r.Y = fp_sub(fp_mul(M, fp_sub(S, r.X)), fp_mul(W, p.y));
+    r.ZZ = V;
+    r.ZZZ = W;
+    return r;
+}
+
+/* 2 P */
+TC_HD g1_xyzz xyzz_dbl32(const g1_xyzz& p) {
+    if (xyzz_is_identity(p) || fe_is_zero(p.Y)) return xyzz_identity();
+    fp_t U = fp_dbl(p.Y);
+    fp_t V = fp_sqr(U);
+    fp_t W = fp_mul(U, V);
+    fp_t S = fp_mul(p.X, V);
+    fp_t X2 = fp_sqr(p.X);
+    fp_t M = fp_add(fp_dbl(X2), X2);
+    g1_xyzz r;
+    r.X = fp_sub(fp_sub(fp_sqr(M), S), S);
+    r.Y = fp_sub(fp_mul(M, fp_sub(S, r.X)), fp_mul(W, p.Y));
+    r.ZZ = fp_mul(V, p.ZZ);
+    r.ZZZ = fp_mul(W, p.ZZZ);
+    return r;
+}
+
+/* acc + q, q affine (chord rule); falls back to the tangent rule / identity when needed */
+TC_HD g1_xyzz xyzz_madd32(const g1_xyzz& a, const g1_affine& q) {
+    if (affine_is_identity(q)) return a;
+    if (xyzz_is_identity(a)) return xyzz_from_affine(q);
+    fp_t U2 = fp_mul(q.x, a.ZZ);
+    fp_t S2 = fp_mul(q.y, a.ZZZ);
+    fp_t Pd = fp_sub(U2, a.X);
+    fp_t Rd = fp_sub(S2, a.Y);
+    if (fe_is_zero(Pd)) {
+        if (fe_is_zero(Rd)) return xyzz_dbl_affine32(q);
+        return xyzz_identity();
+    }
+    fp_t PP = fp_sqr(Pd);
+    fp_t PPP = fp_mul(Pd, PP);
+    fp_t Q = fp_mul(a.X, PP);
+    g1_xyzz r;
+    r.X = fp_sub(fp_sub(fp_sub(fp_sqr(Rd), PPP), Q), Q);
+    r.Y = fp_sub(fp_mul(Rd, fp_sub(Q, r.X)), fp_mul(a.Y, PPP));
+    r.ZZ = fp_mul(a.ZZ, PP);
+    r.ZZZ = fp_mul(a.ZZZ, PPP);
+    return r;
+}
+
+/* a + b, both XYZZ */
+TC_HD g1_xyzz xyzz_add32(const g1_xyzz& a, const g1_xyzz& b) {
+    if (xyzz_is_identity(b)) return a;
+    if (xyzz_is_identity(a)) return b;
+    fp_t U1 = fp_mul(a.X, b.ZZ);
+    fp_t U2 = fp_mul(b.X, a.ZZ);
+    fp_t S1 = fp_mul(a.Y, b.ZZZ);
+    fp_t S2 = fp_mul(b.Y, a.ZZZ);
+    fp_t Pd = fp_sub(U2, U1);
+    fp_t Rd = fp_sub(S2, S1);
+    if (fe_is_zero(Pd)) {
+        if (fe_is_zero(Rd)) return xyzz_dbl32(a);
+        return xyzz_identity();
+    }
+    fp_t PP = fp_sqr(Pd);
+    fp_t PPP = fp_mul(Pd, PP);
+    fp_t Q = fp_mul(U1, PP);
+    g1_xyzz r;
+    r.X = fp_sub(fp_sub(fp_sub(fp_sqr(Rd), PPP), Q), Q);
+    r.Y = fp_sub(fp_mul(Rd, fp_sub(Q, r.X)), fp_mul(S1, PPP));
+    r.ZZ = fp_mul(fp_mul(a.ZZ, b.ZZ), PP);
+    r.ZZZ = fp_mul(fp_mul(a.ZZZ, b.ZZZ), PPP);
+    return r;
 }
 
 /* affine from XYZZ given inv = 1 / (ZZ * ZZZ):  1/ZZ = inv ZZZ, 1/ZZZ = inv ZZ */

@@ -928,7 +928,7 @@ struct CoopReduce {
                     } else if (flag_id[pr] == 2u) {
                         point_set(lds, a, point(lds, b));
                     } else if (flag_id[pr] == 0u) {             /* same x: the same point, or opposite ones */
-                        point_set(lds, a, flag_rz[pr] ? xyzz_dbl(point(lds, a)) : xyzz_identity());
+                        point_set(lds, a, flag_rz[pr] ? xyzz_dbl32(point(lds, a)) : xyzz_identity());
                     }
                 }
             }
@@ -1593,7 +1593,7 @@ struct NodeWindowSrc {
     g1_xyzz* out;               /* n_nodes */
     TC_DEV uint32_t count(uint32_t) const { return g.B * (uint32_t)FB_W < 256u ? g.B * (uint32_t)FB_W : 256u; }
     TC_DEV g1_xyzz load(uint32_t node, uint32_t i) const {
-        xyzz_acc acc = acc_identity();
+        g1_xyzz acc = xyzz_identity();
         for (uint32_t idx = i; idx < g.B * (uint32_t)FB_W; idx += 256) {
             uint32_t k = idx / (uint32_t)FB_W, w = idx % (uint32_t)FB_W;
             int64_t f = child_index(g, node, k);
@@ -1603,9 +1603,11 @@ struct NodeWindowSrc {
             int32_t d = 0;
             for (uint32_t x = 0; x <= w; ++x) d = fr_window_digit(v, (int)x, FB_C, carry);
             if (!d) continue;
-            acc_madd(acc, table[((uint64_t)k * FB_W + w) * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u], d < 0);
+            g1_affine p = table[((uint64_t)k * FB_W + w) * FB_NB + (uint32_t)(d < 0 ? -d : d) - 1u];
+            if (d < 0) p.y = fp_neg(p.y);
+            acc = xyzz_madd32(acc, p);
         }
-        return acc_result(acc);
+        return acc;
     }
     TC_DEV void store(uint32_t node, const g1_xyzz& r) const { out[node] = r; }
 };
@@ -1633,10 +1635,9 @@ struct SegmentSrc {
     }
     TC_DEV g1_xyzz load(uint32_t t, uint32_t i) const {
         uint64_t lo = (uint64_t)off[t] * scale, hi = (uint64_t)off[t + 1] * scale;
-        if (lo + i + 256 >= hi) return in[lo + i];
-        xyzz_acc acc = acc_from(in[lo + i]);
-        for (uint64_t x = lo + i + 256; x < hi; x += 256) acc_add(acc, acc_from(in[x]));
-        return acc_result(acc);
+        g1_xyzz acc = in[lo + i];
+        for (uint64_t x = lo + i + 256; x < hi; x += 256) acc = xyzz_add32(acc, in[x]);
+        return acc;
     }
     TC_DEV void store(uint32_t t, const g1_xyzz& r) const { out[t] = r; }
 };
