@@ -41,6 +41,10 @@ import tc_inputs  # noqa: E402
 # Montgomery product of 12 x 32-bit limbs = 2 * 12^2 + 12 = 300 32x32->64 multiply-adds.
 FP_MULS_PER_MIXED_ADD = 10
 MADS_PER_FP_MUL = 300
+# What the accumulation kernel issues per mixed addition: it computes in 14 limbs of 28 bits (no carry
+# instructions), 392 multiply-adds a product, 301 a squaring, 588 for the difference of two products under one
+# reduction: 6 products + 2 squarings + 1 such difference.
+MADS_ISSUED_PER_MIXED_ADD = 6 * 392 + 2 * 301 + 588
 # Integer-ALU peak by the formula: v_mad_u64_u32 at half the full vector rate, 256 CU x 4 SIMD x 16 lanes x
 # 2.4 GHz / 2.  Printed beside the rate that `alu_peak` measures in the same run, which is the denominator used.
 FORMULA_PEAK_MADS_PER_S = 256 * 4 * 16 * 2.4e9 / 2
@@ -232,6 +236,11 @@ def bench_c3(ctx, T, torch, node_srs, tau, steps, warmup, peak):
                      "nonzero_entries_per_launch": nonzero,
                      "peak_source": "alu_peak.used, measured in this run",
                      "frac_of_formula_peak": achieved / FORMULA_PEAK_MADS_PER_S,
+                     # the unit of `achieved` is the algorithm's count (10 Fp products x 300 multiply-adds at 32-bit
+                     # limbs); the kernel's own 28-bit-limb products issue more multiply-adds for the same addition
+                     "multiply_adds_issued_per_addition": MADS_ISSUED_PER_MIXED_ADD,
+                     "issue_frac": acc_executed * MADS_ISSUED_PER_MIXED_ADD / (kern_ms * 1e-3) / peak,
+                     "issue_frac_note": "multiply-adds the launch really issues over the measured multiply-add peak",
                      "build_frac": nonzero * per_add / (build_ms * 1e-3) / peak,
                      "build_frac_note": "one mixed addition per non-zero entry over the whole scale + quantise + build time"},
     }

@@ -83,6 +83,22 @@ const char* tc_last_error(const tc_ctx* ctx);
 /* Blocks until all work enqueued by this context has finished. */
 int tc_ctx_sync(tc_ctx* ctx);
 
+/* Tuning options of a context.  The paper's own parameters are the security level, the shape and the arity
+ * (Def. 4.1, Sec. 4); these are the knobs of this implementation of the multi-exponentiation.  0 = let the library
+ * choose (the default for all of them).  At tc_ctx_create each option takes its value from the environment
+ * variable named beside it when that is set to a valid number; tc_ctx_set_option overrides it afterwards.
+ * A value outside the stated range is refused with TC_ERR_ARG and changes nothing.  Results do not depend on any
+ * of them (the tests run the same commitments under several settings); tc_commit_static ignores them, its plan is
+ * fixed by its scratch limit. */
+#define TC_OPT_ACC_SUBRUN 0   /* TC_ACC_SUBRUN: entries per lane of the bucket accumulation, 1..64 */
+#define TC_OPT_ACC_FANIN 1    /* TC_ACC_FANIN: partial sums per lane in the passes after it, 2..64 */
+#define TC_OPT_FR_WINDOW 2    /* TC_FR_WINDOW: window width for full-width scalars, 8 or 16 bits */
+#define TC_OPT_CHECK_LEVEL 3  /* TC_CHECK_LEVEL: 1 = every commitment that tc_commit / tc_commit_batch hand back is checked to
+                                 lie on the curve (TC_ERR_STATE "internal" otherwise): a cheap guard while tuning */
+#define TC_OPT_COUNT 4
+int tc_ctx_set_option(tc_ctx* ctx, int option, int64_t value);
+int tc_ctx_get_option(const tc_ctx* ctx, int option, int64_t* value);
+
 /* Measurement hooks (for benchmarks; not part of the method).  With profiling enabled the
  * library brackets every launch of the selected kernel class with HIP events on the context's
  * stream; tc_ctx_profile_read synchronises, returns the summed duration and launch count since

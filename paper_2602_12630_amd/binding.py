@@ -17,6 +17,7 @@ TC_PROF_BUCKET_ACC, TC_PROF_NODE_COMMIT, TC_PROF_NODE_COMMIT_UPPER, TC_PROF_VERI
 TC_MAX_ORDER, TC_MAX_STEPS = 4, 16
 TC_ALU_MAD, TC_ALU_MAD_CARRY, TC_ALU_FP_MUL, TC_ALU_FP_SQR, TC_ALU_FP_MUL_F64, TC_ALU_FP_SQR_F64 = 0, 1, 2, 3, 4, 5
 TC_ALU_FP28_MUL, TC_ALU_FP28_SQR = 6, 7
+TC_OPT_ACC_SUBRUN, TC_OPT_ACC_FANIN, TC_OPT_FR_WINDOW, TC_OPT_CHECK_LEVEL = 0, 1, 2, 3
 TC_STATIC_MAX_TERMS, TC_STATIC_SCRATCH_BYTES = 1 << 18, 32 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -83,6 +84,8 @@ def load_library(path=None):
         "tc_ctx_profile_units": (ctypes.c_int, [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_uint64)]),
         "tc_ctx_alu_rate": (ctypes.c_int, [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]),
         "tc_ctx_field_op": (ctypes.c_int, [vp, ctypes.c_int, vp, vp, ctypes.c_size_t, vp]),
+        "tc_ctx_set_option": (ctypes.c_int, [vp, ctypes.c_int, ctypes.c_int64]),
+        "tc_ctx_get_option": (ctypes.c_int, [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]),
         "tc_setup_from_trapdoor": (ctypes.c_int, [vp, u8p, ctypes.c_int, u32p, ctypes.c_uint32, ctypes.POINTER(vp)]),
         "tc_srs_destroy": (None, [vp]),
         "tc_srs_size": (ctypes.c_uint64, [vp, ctypes.c_int]),
@@ -388,6 +391,16 @@ class Context:
         units = ctypes.c_uint64()
         self._check(self.lib.tc_ctx_profile_units(self.handle, kind, ctypes.byref(units)))
         return int(units.value)
+
+    def set_option(self, option, value):
+        self._check(self.lib.tc_ctx_set_option(self.handle, option, int(value)))
+
+    def get_option(self, option):
+        v = ctypes.c_int64()
+        rc = self.lib.tc_ctx_get_option(self.handle, option, ctypes.byref(v))
+        if rc != TC_OK:
+            raise TcError(rc, "bad option")
+        return int(v.value)
 
     def field_op(self, op, a, b, n, out):
         self._check(self.lib.tc_ctx_field_op(self.handle, op, _ptr(a), _ptr(b), n, _ptr(out)))

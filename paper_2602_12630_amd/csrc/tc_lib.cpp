@@ -95,6 +95,7 @@ struct tc_ctx {
     bool profiling = false;
     std::vector<std::pair<rt::event_t, rt::event_t>> prof[TC_PROF_KINDS];
     uint64_t prof_units[TC_PROF_KINDS] = {0, 0, 0, 0};
+    int64_t opt[TC_OPT_COUNT] = {0, 0, 0, 0};      /* tuning options, 0 = automatic */
 };
 
 struct tc_srs {
@@ -368,6 +369,38 @@ static int launch_coop_n(uint32_t groups, rt::stream_t st, const F& f, int phase
 /* ======================================================================================= */
 /* context                                                                                 */
 /* ======================================================================================= */
+static bool option_value_ok(int option, int64_t v) {
+    if (v == 0) return true;
+    switch (option) {
+        case TC_OPT_ACC_SUBRUN: return v >= 1 && v <= 64;
+        case TC_OPT_ACC_FANIN: return v >= 2 && v <= 64;
+        case TC_OPT_FR_WINDOW: return v == 8 || v == 16;
+        case TC_OPT_CHECK_LEVEL: return v == 1;
+        default: return false;
+    }
+}
+extern "C" int tc_ctx_set_option(tc_ctx* ctx, int option, int64_t value) {
+    if (!ctx) return TC_ERR_ARG;
+    if (option < 0 || option >= TC_OPT_COUNT || !option_value_ok(option, value)) return fail(ctx, TC_ERR_ARG, "unknown option or value out of range");
+    ctx->opt[option] = value;
+    return TC_OK;
+}
+extern "C" int tc_ctx_get_option(const tc_ctx* ctx, int option, int64_t* value) {
+    if (!ctx || !value || option < 0 || option >= TC_OPT_COUNT) return TC_ERR_ARG;
+    *value = ctx->opt[option];
+    return TC_OK;
+}
+static void options_from_environment(tc_ctx* ctx) {
+    static const char* const names[TC_OPT_COUNT] = {"TC_ACC_SUBRUN", "TC_ACC_FANIN", "TC_FR_WINDOW", "TC_CHECK_LEVEL"};
+    for (int o = 0; o < TC_OPT_COUNT; ++o) {
+        const char* text = getenv(names[o]);
+        if (!text || !*text) continue;
+        char* end = nullptr;
+        long long v = strtoll(text, &end, 10);
+        if (end && *end == 0 && option_value_ok(o, (int64_t)v)) ctx->opt[o] = (int64_t)v;
+    }
+}
+
 extern "C" int tc_ctx_create(tc_ctx** out, int device, void* hip_stream) {
     try {
         if (!out) return TC_ERR_ARG;
@@ -397,6 +430,7 @@ extern "C" int tc_ctx_create(tc_ctx** out, int device, void* hip_stream) {
         ctx->ws_static.base = scratch;
         ctx->ws_static.cap = TC_STATIC_SCRATCH_BYTES;
         ctx->ws_static.fixed = true;
+        options_from_environment(ctx);
         *out = ctx;
         return TC_OK;
     } catch (const std::bad_alloc&) {
@@ -1243,12 +1277,15 @@ struct MsmProblem {
     uint64_t n;
     const void* sub = nullptr;     /* DT_DIFF8 / DT_DIFF16: value = scalars[i] - sub[i] */
 };
-static void msm_config(int dtype, uint64_t n, int* W, int* c) {
+static void msm_config(const tc_ctx* ctx, int dtype, uint64_t n, int* W, int* c) {
     if (dtype == TC_I8) { *W = 1; *c = 8; }
     else if (dtype == TC_I16) { *W = 1; *c = 16; }
     else if (dtype == DT_DIFF8 || dtype == DT_DIFF16) { *W = 2; *c = 9; }
     else if (dtype == DT_SPLIT16) { *W = 2; *c = 8; }
-    else { *c = n >= 32768 ? 16 : 8; *W = 256 / *c; }
+    else {
+        *c = ctx->opt[TC_OPT_FR_WINDOW] ? (int)ctx->opt[TC_OPT_FR_WINDOW] : n >= 32768 ? 16 : 8;
+        *W = 256 / *c;
+    }
 }
 /* `count` problems of one scalar type and window plan, run through shared launches: the buckets of
  * problem p are the keys p * nbk .. (p + 1) * nbk of one big bucket space, so every pass (prefix
@@ -1298,10 +1335,11 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     const uint64_t target_lanes = 2 * ACC_RESIDENT_LANES;
     uint32_t L1 = (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(4, (items + target_lanes - 1) / target_lanes));
     L1 = (uint32_t)std::min<uint64_t>(L1, std::max<uint64_t>(4, (items + 2 * (uint64_t)nbk - 1) / (2 * (uint64_t)nbk)));
+    if (ctx->opt[TC_OPT_ACC_SUBRUN]) L1 = (uint32_t)ctx->opt[TC_OPT_ACC_SUBRUN];
     if (ctx->static_mode) L1 = STATIC_L1;      /* fewer, longer sub-runs: the partial sums must fit the static scratch */
     /* fan-in of the middle passes: with few buckets a pass costs the chain of additions of one lane, and shorter
      * chains in more passes win (flat commitment of 2^21 terms: 2.74 / 2.70 / 2.59 / 3.08 ms with 16 / 8 / 4 / 2) */
-    const uint32_t L2 = nbk <= ScanSmall::MAX_N ? 4 : 16;
+    const uint32_t L2 = ctx->opt[TC_OPT_ACC_FANIN] && !ctx->static_mode ? (uint32_t)ctx->opt[TC_OPT_ACC_FANIN] : nbk <= ScanSmall::MAX_N ? 4 : 16;
 
     uint32_t max_count = 0;        /* largest bucket: fixes how many shrinking passes are needed */
     if (dtype != TC_FR) {
@@ -1418,7 +1456,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
 /* result[0] = sum_i [e(s_i)] pts[i] */
 static int msm_engine(tc_ctx* ctx, const g1_affine* pts, const void* d_scalars, int dtype, uint64_t n, g1_xyzz* result) {
     int W, c;
-    msm_config(dtype, n, &W, &c);
+    msm_config(ctx, dtype, n, &W, &c);
     MsmProblem one{pts, d_scalars, n};
     return msm_engine_multi(ctx, 1, &one, dtype, W, c, result);
 }
@@ -1431,12 +1469,12 @@ static int msm_engine_list(tc_ctx* ctx, int count, const MsmProblem* prob, const
     int i = 0;
     while (i < count) {
         int W, c;
-        msm_config(dtype[i], prob[i].n, &W, &c);
+        msm_config(ctx, dtype[i], prob[i].n, &W, &c);
         uint64_t items = prob[i].n * (uint64_t)W, buckets = (uint64_t)W << (c - 1);
         int j = i + 1;
         while (j < count) {
             int W2, c2;
-            msm_config(dtype[j], prob[j].n, &W2, &c2);
+            msm_config(ctx, dtype[j], prob[j].n, &W2, &c2);
             if (dtype[j] != dtype[i] || W2 != W || c2 != c) break;
             if (items + prob[j].n * (uint64_t)W > max_batch_items || buckets + ((uint64_t)W << (c - 1)) > max_batch_buckets) break;
             items += prob[j].n * (uint64_t)W;
@@ -1471,7 +1509,18 @@ extern "C" int tc_commit_batch(tc_ctx* ctx, int count, const tc_srs* const* srs,
         std::vector<MsmProblem> prob(count);
         for (int i = 0; i < count; ++i) prob[i] = MsmProblem{srs[i]->pts[0], d_scalars[i], srs[i]->n[0]};
         TRY(msm_engine_list(ctx, count, prob.data(), dtype, results));
-        return points_to_host(ctx, results, (uint32_t)count, out_g1);
+        TRY(points_to_host(ctx, results, (uint32_t)count, out_g1));
+        if (ctx->opt[TC_OPT_CHECK_LEVEL] >= 1) {
+            for (int i = 0; i < count; ++i) {
+                const uint8_t* b = out_g1 + 96 * (size_t)i;
+                bool zero = true;
+                for (int j = 0; j < 96; ++j) zero = zero && b[j] == 0;
+                uint32_t w[24];
+                memcpy(w, b, 96);
+                if (!zero && !affine_on_curve(affine_from_canonical(w))) return fail(ctx, TC_ERR_STATE, "internal: a commitment is not on the curve");
+            }
+        }
+        return TC_OK;
     } catch (const std::bad_alloc&) {
         return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
     } catch (...) {
@@ -1522,7 +1571,7 @@ extern "C" int tc_commit_static(tc_ctx* ctx, const tc_srs* srs, const void* d_sc
         WS(result, g1_xyzz, 1);
         WS(aff, g1_affine, 1);
         int W, c;
-        msm_config(dtype, srs->n[0], &W, &c);
+        msm_config(ctx, dtype, srs->n[0], &W, &c);
         MsmProblem one{srs->pts[0], d_scalars, srs->n[0]};
         TRY(msm_engine_multi(ctx, 1, &one, dtype, W, c, result));
         TRY(normalize(ctx, result, 1, aff));

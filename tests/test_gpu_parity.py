@@ -66,6 +66,35 @@ def test_device_field_arithmetic_against_integers(T, ctx):
     check_field_arithmetic(run, 4096, 1024)
 
 
+def test_options_do_not_change_results(T, ctx):
+    """The same int16 and full-width commitments under several plans of the accumulation (entries per lane, fan-in of
+    the later passes, window width), with the on-curve guard switched on; the int16 one against the oracle."""
+    B = T.binding
+    shape = (64, 512)
+    pp = pps(shape)
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, 0)
+    X = tc_inputs.int16_uniform(shape, 21, -32768, 32767)
+    X.reshape(-1)[:5000] = 5
+    F = fr_bytes_array([(v * 0x1F3D5B79A2C4E6F1) % R for v in range(1, 64 * 512 + 1)])
+    dX, dF = to_device(X), to_device(F)
+    want16 = ec.g1_to_bytes(cbind.commit(pp, X, HOST_THREADS))
+    wantfr = None
+    try:
+        for sub, fan, win in ((0, 0, 0), (1, 2, 8), (3, 5, 16), (64, 64, 0)):
+            ctx.set_option(B.TC_OPT_ACC_SUBRUN, sub)
+            ctx.set_option(B.TC_OPT_ACC_FANIN, fan)
+            ctx.set_option(B.TC_OPT_FR_WINDOW, win)
+            ctx.set_option(B.TC_OPT_CHECK_LEVEL, 1)
+            assert ctx.commit(srs, dX, T.TC_I16) == want16, (sub, fan, win)
+            got = ctx.commit(srs, dF, T.TC_FR)
+            wantfr = wantfr or got
+            assert got == wantfr, (sub, fan, win)
+    finally:
+        for o in range(4):
+            ctx.set_option(o, 0)
+        srs.close()
+
+
 def test_commit_over_repeated_points(ctx):
     """Equal and opposite points inside the bucket sums: the sub-runs that the fast accumulation gives up and the
     second launch redoes with every case of the group law (see check_repeated_points)."""

@@ -673,6 +673,45 @@ def test_emulated_field_ops(emu):
     check_field_arithmetic(run, 200, 100)
 
 
+def test_emulated_options(emu, monkeypatch):
+    """Tuning options: refused outside their ranges, taken from the environment at context creation, and without
+    effect on results -- the same int16 and full-width commitments under several plans of the accumulation."""
+    B = T.binding
+    for opt, bad in ((B.TC_OPT_ACC_SUBRUN, 65), (B.TC_OPT_ACC_SUBRUN, -1), (B.TC_OPT_ACC_FANIN, 1), (B.TC_OPT_FR_WINDOW, 12),
+                     (B.TC_OPT_CHECK_LEVEL, 2), (17, 1)):
+        with pytest.raises(T.TcError) as e:
+            emu.set_option(opt, bad)
+        assert e.value.code == B.TC_ERR_ARG
+    assert [emu.get_option(o) for o in range(4)] == [0, 0, 0, 0]
+    monkeypatch.setenv("TC_ACC_SUBRUN", "7")
+    monkeypatch.setenv("TC_ACC_FANIN", "banana")
+    monkeypatch.setenv("TC_FR_WINDOW", "9")
+    other = T.Context(0, lib=emu.lib)
+    assert [other.get_option(o) for o in range(4)] == [7, 0, 0, 0]
+    other.close()
+    shape = (16, 256)
+    pp = pps(shape)
+    srs = emu.setup_from_trapdoor(TAU_BYTES, shape, 0)
+    X = tc_inputs.int16_uniform(shape, 21, -32768, 32767)
+    X.reshape(-1)[:700] = 5                                    # one full bucket: several passes over its partial sums
+    F = fr_bytes_array([(v * 0x1F3D5B79A2C4E6F1) % R for v in range(1, 16 * 256 + 1)])
+    want16, wantfr = ec.g1_to_bytes(tc.commit(pp, X)), None
+    try:
+        for sub, fan, win in ((0, 0, 0), (1, 2, 8), (3, 5, 16), (64, 64, 0)):
+            emu.set_option(B.TC_OPT_ACC_SUBRUN, sub)
+            emu.set_option(B.TC_OPT_ACC_FANIN, fan)
+            emu.set_option(B.TC_OPT_FR_WINDOW, win)
+            emu.set_option(B.TC_OPT_CHECK_LEVEL, 1)
+            assert emu.commit(srs, X, T.TC_I16) == want16, (sub, fan, win)
+            got = emu.commit(srs, F, T.TC_FR)
+            wantfr = wantfr or got
+            assert got == wantfr, (sub, fan, win)
+    finally:
+        for o in range(4):
+            emu.set_option(o, 0)
+    srs.close()
+
+
 def test_emulated_commit_over_repeated_points(emu):
     """Equal and opposite points inside the bucket sums (see check_repeated_points), on the host build."""
     check_repeated_points(emu, lambda a: a)
