@@ -52,7 +52,12 @@ R_MODULUS = 0x73EDA753299D7D483339D80809A1D80553BDA402FFFE5BFEFFFFFFFF00000001  
 # HBM bytes moved by the bucket-accumulation launch of one LLaMA2-7B-shaped build (rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE of `bench.py --only-c3-build`, scaled by a 256 MiB copy kernel; runs and scale factors in
 # profiles/c3_build_hbm_traffic_pmc.txt).
-ACC_TRAFFIC_BYTES_C3 = 9.185e10
+ACC_TRAFFIC_BYTES_C3 = 7.849e10
+# Vector instructions that the same launch issues per SIMD and clock, and per mixed addition (rocprofv3 --pmc
+# SQ_INSTS_VALU / GRBM_GUI_ACTIVE of the same command: profiles/c3_build_sq_counters_pmc.txt).  A 64-lane wave takes
+# four clocks of a 16-lane SIMD, so 0.25 is the most a SIMD can issue.
+ACC_VALU_PER_SIMD_CLK_C3 = 0.251
+ACC_VALU_PER_ADDITION_C3 = 5023
 
 
 # ----------------------------------------------------------------------------------------------------------
@@ -241,6 +246,11 @@ def bench_c3(ctx, T, torch, node_srs, tau, steps, warmup, peak):
                      "multiply_adds_issued_per_addition": MADS_ISSUED_PER_MIXED_ADD,
                      "issue_frac": acc_executed * MADS_ISSUED_PER_MIXED_ADD / (kern_ms * 1e-3) / peak,
                      "issue_frac_note": "multiply-adds the launch really issues over the measured multiply-add peak",
+                     "valu_issue": {"per_simd_clk": ACC_VALU_PER_SIMD_CLK_C3, "max": 0.25,
+                                    "vector_instructions_per_addition": ACC_VALU_PER_ADDITION_C3,
+                                    "source": "profiles/c3_build_sq_counters_pmc.txt",
+                                    "note": "the launch issues a vector instruction on every SIMD every four clocks: "
+                                            "only fewer instructions per addition can make it faster"},
                      "build_frac": nonzero * per_add / (build_ms * 1e-3) / peak,
                      "build_frac_note": "one mixed addition per non-zero entry over the whole scale + quantise + build time"},
     }
