@@ -72,6 +72,18 @@ def oracle_pool():
     return ThreadPoolExecutor(max_workers=HOST_THREADS)
 
 
+CAPTURE_MANAGER = None      # pytest's capture manager, set by conftest.py
+
+
+def progress(line):
+    """One line to the real stdout, whether or not pytest is capturing output."""
+    if CAPTURE_MANAGER is not None:
+        with CAPTURE_MANAGER.global_and_fixture_disabled():
+            print(line, flush=True)
+    else:
+        print(line, flush=True)
+
+
 class Stopwatch:
     """Prints what a long test is doing and how long each part took (the GPU machine takes silence for a hang)."""
 
@@ -80,7 +92,7 @@ class Stopwatch:
 
     def lap(self, what):
         now = time.time()
-        print("%s: %s (%.1f s, %.1f s since start)" % (self.name, what, now - self.last, now - self.t0), flush=True)
+        progress("%s: %s (%.1f s, %.1f s since start)" % (self.name, what, now - self.last, now - self.t0))
         self.last = now
 
 

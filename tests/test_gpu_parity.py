@@ -12,7 +12,7 @@ from oracle import bls12_381 as ec
 from oracle import cbind, quantize, tc, terkle
 from oracle.bls12_381 import R
 
-from gpu_util import HOST_THREADS, TAU_BYTES, Stopwatch, check_field_arithmetic, check_repeated_points, fr_bytes_array, oracle_pool, parse_proof, pps, serialize_steps, to_device
+from gpu_util import HOST_THREADS, TAU_BYTES, Stopwatch, check_field_arithmetic, check_repeated_points, fr_bytes_array, oracle_pool, parse_proof, pps, progress, serialize_steps, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -784,7 +784,7 @@ def test_c4_weight_matrices_streamed(T, ctx, node_srs):
 
     watch = Stopwatch("config 4")
     layers = int(os.environ.get("TC_TEST_C4_LAYERS", tc_inputs.LLAMA7B["layers"]))
-    print("config 4: %d of 32 layers" % layers, flush=True)
+    progress("config 4: %d of 32 layers" % layers)
     shapes7 = tc_inputs.c4_shapes()
     grid = (layers, 7)
     srs_by_shape = {s: ctx.setup_from_trapdoor(TAU_BYTES, s, 0) for s in set(shapes7)}
@@ -838,8 +838,8 @@ def test_c5_batched_requests(T, ctx, node_srs):
     layers = int(os.environ.get("TC_TEST_C5_LAYERS", cfg["layers"]))
     openings = int(os.environ.get("TC_TEST_C5_OPENINGS", "128"))
     oracle_requests = int(os.environ.get("TC_TEST_C5_ORACLE_REQUESTS", cfg["batch"]))
-    print("config 5: %d of 8 requests x %d of 40 layers, %d openings per request, oracle rebuilds %d request(s) in full"
-          % (requests, layers, openings, min(oracle_requests, requests)), flush=True)
+    progress("config 5: %d of 8 requests x %d of 40 layers, %d openings per request, oracle rebuilds %d request(s) in full"
+             % (requests, layers, openings, min(oracle_requests, requests)))
     shapes3 = tc_inputs.c3_shapes(cfg)
     grid = (layers, 3)
     srs_by_shape = {s: ctx.setup_from_trapdoor(TAU_BYTES, s, T.TC_SRS_SUFFIX | T.TC_SRS_OPEN_TABLE) for s in set(shapes3)}
