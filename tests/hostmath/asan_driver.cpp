@@ -233,6 +233,65 @@ int main() {
         std::free(d);
         tc_srs_destroy(node_srs);
     }
+    // --- the carry-free field form on extreme operands: UBSan stops the run on a signed overflow of a column sum or
+    //     of a limb, i.e. on a violated bound; the 28-bit-limb products must agree with the 32-bit routine
+    {
+        std::vector<fp_t> edge;
+        auto from_words = [](std::initializer_list<uint32_t> w) { fp_t x = fe_zero<FpParams>(); int i = 0; for (uint32_t v : w) x.l[i++] = v; return x; };
+        fp_t pm1, pm2, ones, half;
+        for (int i = 0; i < 12; ++i) { pm1.l[i] = FpParams::MOD[i]; pm2.l[i] = FpParams::MOD[i]; ones.l[i] = i < 11 ? 0xFFFFFFFFu : 0x19FFFFFFu; half.l[i] = FpParams::HALF[i]; }
+        pm1.l[0] -= 1;
+        pm2.l[0] -= 2;
+        edge.push_back(fe_zero<FpParams>());
+        edge.push_back(from_words({1}));
+        edge.push_back(pm1);
+        edge.push_back(pm2);
+        edge.push_back(ones);                                   // every 28-bit limb at its maximum, top limb as large as p allows
+        edge.push_back(half);
+        edge.push_back(fe_one<FpParams>());
+        edge.push_back(from_words({0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0x10000000u}));
+        edge.push_back(from_words({0xFFFFFFFFu, 0, 0xFFFFFFFFu, 0, 0xFFFFFFFFu, 0, 0xFFFFFFFFu, 0, 0xFFFFFFFFu, 0, 0xFFFFFFFFu, 0}));
+        std::vector<uint32_t> a, b;
+        for (const fp_t& x : edge)
+            for (const fp_t& y : edge) {
+                a.insert(a.end(), x.l, x.l + 12);
+                b.insert(b.end(), y.l, y.l + 12);
+            }
+        for (int i = 0; i < 64; ++i)
+            for (int j = 0; j < 12; ++j) {
+                a.push_back(j < 11 ? (uint32_t)rng() : (uint32_t)rng() % 0x1A000000u);
+                b.push_back(j < 11 ? (uint32_t)rng() : (uint32_t)rng() % 0x1A000000u);
+            }
+        const size_t n = a.size() / 12;
+        uint32_t *da = exact(a), *db = exact(b);
+        std::vector<std::vector<uint32_t>> out(14, std::vector<uint32_t>(a.size()));
+        for (int op : {0, 1, 6, 7, 9, 10, 11, 12, 13}) {
+            uint32_t* d = exact(out[op]);
+            CHECK(tc_ctx_field_op(ctx, op, da, db, n, d));
+            CHECK(tc_ctx_sync(ctx));
+            std::memcpy(out[op].data(), d, out[op].size() * 4);
+            std::free(d);
+        }
+        REQUIRE(out[9] == out[0]);                              // a b both ways
+        REQUIRE(out[10] == out[1]);                             // a^2 both ways
+        // (a - b)(a + b) = a^2 - b^2 needs b^2: the same call with the operands exchanged
+        std::vector<uint32_t> bsq(a.size()), diff(a.size());
+        {
+            uint32_t* d = exact(bsq);
+            CHECK(tc_ctx_field_op(ctx, 1, db, da, n, d));
+            CHECK(tc_ctx_sync(ctx));
+            uint32_t *e = exact(diff), *asq = exact(out[1]);
+            CHECK(tc_ctx_field_op(ctx, 7, asq, d, n, e));
+            CHECK(tc_ctx_sync(ctx));
+            std::memcpy(diff.data(), e, diff.size() * 4);
+            std::free(d);
+            std::free(e);
+            std::free(asq);
+        }
+        REQUIRE(out[11] == diff);
+        std::free(da);
+        std::free(db);
+    }
     tc_vk_destroy(vk);
     tc_ctx_destroy(ctx);
     std::puts("asan driver: ok");
