@@ -226,6 +226,28 @@ TC_HD void acc_add(xyzz_acc& a, const xyzz_acc& b) {
     a.v.Y = fp28_sub(fp28_mul(Rd, fp28_sub(Q, a.v.X)), fp28_mul(S1, PPP));
 }
 
+/* a <- a + b for two finite sums, the products expanded in place and the two products of Y under one reduction: for
+ * kernels whose loop is this addition and nothing else.  No case distinctions: false (a unusable) when the
+ * denominator of the chord rule may be zero in the field (equal or opposite points); the caller then takes the
+ * whole sum again with acc_add.  Bounds as for acc_add. */
+TC_HD bool acc_add_regular_expanded(g1_xyzz28& a, const g1_xyzz28& b) {
+    fp28 U1 = fp28_mul_inline(a.X, b.ZZ);
+    fp28 Pd = fp28_sub(fp28_mul_inline(b.X, a.ZZ), U1);
+    if (fp28_maybe_zero(Pd, 128u)) return false;
+    fp28 S1 = fp28_mul_inline(a.Y, b.ZZZ);
+    fp28 Rd = fp28_sub(fp28_mul_inline(b.Y, a.ZZZ), S1);
+    a.ZZ = fp28_mul_inline(a.ZZ, b.ZZ);
+    a.ZZZ = fp28_mul_inline(a.ZZZ, b.ZZZ);
+    fp28 PP = fp28_sqr_inline(Pd);
+    a.ZZ = fp28_mul_inline(a.ZZ, PP);
+    fp28 PPP = fp28_mul_inline(Pd, PP);
+    fp28 Q = fp28_mul_inline(U1, PP);
+    a.ZZZ = fp28_mul_inline(a.ZZZ, PPP);
+    a.X = fp28_carry(fp28_sub(fp28_sub(fp28_sub(fp28_sqr_inline(Rd), PPP), Q), Q));
+    a.Y = fp28_mul_sub_inline(Rd, fp28_sub(Q, a.X), S1, PPP);
+    return true;
+}
+
 /* the same on stored points (coordinates in the 32-bit form), one operation at a time */
 TC_HD g1_xyzz xyzz_dbl_affine(const g1_affine& p) {
     xyzz_acc a = acc_identity();

@@ -777,6 +777,87 @@ struct AccXyzz {
         out[t] = acc_result(acc);
     }
 };
+/* The same passes for launches that fill the chip: the general addition expanded in place in the 28-bit form, no
+ * call and no case distinction in the loop (as in AccAffine); a lane whose sum meets equal or opposite points gives
+ * it up and enters it in a list that AccXyzzRedo works off with the routine that settles every case.  `final` = one
+ * lane per bucket over all its partial sums (the last pass). */
+struct AccXyzzFast {
+    const g1_xyzz* in;
+    const uint32_t* start;
+    const uint32_t* lstart;
+    uint32_t nbk, L;
+    g1_xyzz* out;
+    uint32_t* redo_count;
+    uint32_t* redo_list;
+    bool final;
+    TC_DEV void operator()(uint32_t t) const {
+        uint32_t begin, end;
+        if (final) {
+            begin = start[t];
+            end = start[t + 1];
+        } else {
+            if (t >= lstart[nbk]) return;
+            uint32_t b = find_segment(lstart, nbk, t);
+            begin = start[b] + (t - lstart[b]) * L;
+            end = begin + L < start[b + 1] ? begin + L : start[b + 1];
+        }
+        if (end - begin <= 1) {
+            out[t] = begin < end ? in[begin] : xyzz_identity();
+            return;
+        }
+        g1_xyzz28 acc;
+        bool have = false;
+        for (uint32_t i = begin; i < end; ++i) {
+            g1_xyzz p = in[i];
+            if (xyzz_is_identity(p)) continue;
+            g1_xyzz28 q = xyzz28_from(p);
+            if (!have) {
+                acc = q;
+                have = true;
+                continue;
+            }
+            if (!acc_add_regular_expanded(acc, q)) {
+                redo_list[atomic_add_u32(redo_count, 1u)] = t;
+                return;
+            }
+        }
+        g1_xyzz r;
+        if (!have) {
+            r = xyzz_identity();
+        } else {
+            r.X = fp28_to_fp_outlined(acc.X); r.Y = fp28_to_fp_outlined(acc.Y);
+            r.ZZ = fp28_to_fp_outlined(acc.ZZ); r.ZZZ = fp28_to_fp_outlined(acc.ZZZ);
+        }
+        out[t] = r;
+    }
+};
+struct AccXyzzRedo {
+    const g1_xyzz* in;
+    const uint32_t* start;
+    const uint32_t* lstart;
+    uint32_t nbk, L;
+    g1_xyzz* out;
+    const uint32_t* redo_count;
+    const uint32_t* redo_list;
+    bool final;
+    uint32_t lanes;
+    TC_DEV void operator()(uint32_t lane) const {
+        for (uint32_t k = lane; k < *redo_count; k += lanes) {
+            uint32_t t = redo_list[k], begin, end;
+            if (final) {
+                begin = start[t];
+                end = start[t + 1];
+            } else {
+                uint32_t b = find_segment(lstart, nbk, t);
+                begin = start[b] + (t - lstart[b]) * L;
+                end = begin + L < start[b + 1] ? begin + L : start[b + 1];
+            }
+            xyzz_acc acc = acc_from(in[begin]);
+            for (uint32_t i = begin + 1; i < end; ++i) acc_add(acc, acc_from(in[i]));
+            out[t] = acc_result(acc);
+        }
+    }
+};
 /* last pass: one lane per bucket sums whatever partials remain (bounded by the pass plan) */
 struct AccFinal {
     const g1_xyzz* in;

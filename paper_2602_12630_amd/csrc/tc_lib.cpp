@@ -1267,6 +1267,14 @@ static int launch_jobs(tc_ctx* ctx, const std::vector<F>& jobs, const std::vecto
 static const uint32_t STATIC_L1 = 16;
 static const uint32_t STATIC_TILES = 16;
 
+/* passes over partial sums with at least this many lanes fill the chip and take the kernels with the addition expanded
+ * in place (and their second launch for the exceptional sums); smaller ones are bound by depth and launches */
+#if defined(TC_HOST_EMU)
+static const uint64_t FAST_PASS_LANES = 64;            /* the CPU build of the tests takes them from tiny sizes on */
+#else
+static const uint64_t FAST_PASS_LANES = 131072;
+#endif
+static const uint32_t MAX_ACC_PASSES = 8;
 /* lanes of the bucket accumulation that are resident at once: 256 compute units x 4 SIMDs x 3 waves x 64 */
 static const uint64_t ACC_RESIDENT_LANES = 256ull * 4 * 3 * 64;
 
@@ -1398,8 +1406,12 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     WS(bufB, g1_xyzz, max_part / L2 + nbk + 1);
     WS(bucket, g1_xyzz, nbk);
     WS(wsum, g1_xyzz, (uint64_t)W * count);
-    WS(redo, uint32_t, max_part + 1);                  /* [0]: how many sub-runs the fast accumulation gave up; then which */
+    /* lists of the lanes that a fast kernel gave up: [0] the count of the accumulation, [1 ..] which; the passes after
+     * it have their counts in redo_pass and reuse the list (a pass starts when the one before is done) */
+    WS(redo, uint32_t, max_part + 1);
+    WS(redo_pass, uint32_t, MAX_ACC_PASSES);
     RT(rt::launch<64>(1, ctx->stream, Fill32{redo, 0u}));
+    RT(rt::launch<64>(MAX_ACC_PASSES, ctx->stream, Fill32{redo_pass, 0u}));
     {
         rt::event_t e0, e1;
         prof_begin(ctx, TC_PROF_BUCKET_ACC, &e0, &e1);
@@ -1435,18 +1447,33 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     /* (Leaving the middle passes out when the buckets outnumber the lanes the chip holds -- the last pass then
      * sums up to 64 partial sums per bucket -- was measured and is worse: its lanes diverge with the bucket loads;
      * 64 openings of the LLaMA2-7B-shaped forward 136 -> 206 ms, the build 69 -> 74 ms.) */
+    uint32_t pass = 0;
     while (worst > L2) {
         /* counts of this pass = number of partials per bucket = differences of cur_start */
         RT(rt::launch<256>(nbk, ctx->stream, DiffCounts{cur_start, cnt}));
         TRY(scan_counts(ctx, cnt, nbk, L2, start, nxt_start, nullptr, tot_a, tot_b, tot_max));
         /* `start` now equals cur_start (prefix of the same counts) */
         lanes_bound = lanes_bound / L2 + nbk + 1;
-        RT(rt::launch<64>(lanes_bound, ctx->stream, AccXyzz{cur, cur_start, nxt_start, nbk, L2, nxt}));
+        if (lanes_bound >= FAST_PASS_LANES && pass + 1 < MAX_ACC_PASSES) {
+            uint32_t redo_lanes = (uint32_t)std::min<uint64_t>(lanes_bound, ACC_RESIDENT_LANES);
+            RT((rt::launch_waves<64, 2>(lanes_bound, ctx->stream, AccXyzzFast{cur, cur_start, nxt_start, nbk, L2, nxt, redo_pass + pass, redo + 1, false})));
+            RT(rt::launch<64>(redo_lanes, ctx->stream, AccXyzzRedo{cur, cur_start, nxt_start, nbk, L2, nxt, redo_pass + pass, redo + 1, false, redo_lanes}));
+            ++pass;
+        } else {
+            RT(rt::launch<64>(lanes_bound, ctx->stream, AccXyzz{cur, cur_start, nxt_start, nbk, L2, nxt}));
+        }
         std::swap(cur, nxt);
         std::swap(cur_start, nxt_start);
         worst = (worst + L2 - 1) / L2;
     }
-    RT(rt::launch<64>(nbk, ctx->stream, AccFinal{cur, cur_start, bucket}));
+    if (nbk >= FAST_PASS_LANES && nbk <= max_part) {
+        uint32_t redo_lanes = (uint32_t)std::min<uint64_t>(nbk, ACC_RESIDENT_LANES);
+        uint32_t* count = redo_pass + (MAX_ACC_PASSES - 1);
+        RT((rt::launch_waves<64, 2>(nbk, ctx->stream, AccXyzzFast{cur, cur_start, nullptr, nbk, 0, bucket, count, redo + 1, true})));
+        RT(rt::launch<64>(redo_lanes, ctx->stream, AccXyzzRedo{cur, cur_start, nullptr, nbk, 0, bucket, count, redo + 1, true, redo_lanes}));
+    } else {
+        RT(rt::launch<64>(nbk, ctx->stream, AccFinal{cur, cur_start, bucket}));
+    }
 
     TRY(reduce_windows(ctx, bucket, W * count, nb, wsum));
     RT(rt::launch<64>((uint32_t)count, ctx->stream, WindowCombine{wsum, W, c, results}));
