@@ -142,6 +142,30 @@ def check_field_arithmetic(run, n_fp, n_fr):
     assert all(g == RR * RR * pow(v, -1, Rr) % Rr for g, v in zip(got, nzr)), "Fr inverse"
 
 
+def check_one_point_throughout(ctx, upload, shape):
+    """Public parameters that are one and the same point at every position, at a size whose passes over the partial
+    sums fill the chip: every addition in them is a doubling or a cancellation, so every lane of the fast passes
+    gives up and the second launches redo them.  sum_i v_i P = [sum_i v_i] P."""
+    import paper_2602_12630_amd as T
+
+    n = int(np.prod(shape))
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, (2, 2), 0)
+    pt = srs.point(3)
+    srs.close()
+    big = ctx.setup_from_trapdoor(TAU_BYTES, shape, 0)
+    header = bytes(big.export()[:56])
+    big.close()
+    back = ctx.srs_import(header + pt * n)
+    P = ec.g1_from_bytes(pt)
+    nrng = np.random.default_rng(17)
+    for X, dtype in ((nrng.integers(-100, 101, size=shape).astype(np.int8), T.TC_I8),
+                     (nrng.integers(-3, 4, size=shape).astype(np.int16), T.TC_I16)):
+        total = int(X.astype(np.int64).sum())
+        want = ec.mul(total % ec.R, P)
+        assert ctx.commit(back, upload(X), dtype) == ec.g1_to_bytes(want), dtype
+    back.close()
+
+
 def check_repeated_points(ctx, upload):
     """Commitments over public parameters in which most points repeat or are each other's negatives, with scalars of
     few distinct values: the bucket sums then run into doublings, sums that cancel to the identity and additions to

@@ -12,7 +12,7 @@ from oracle import bls12_381 as ec
 from oracle import cbind, quantize, tc, terkle
 from oracle.bls12_381 import R
 
-from gpu_util import HOST_THREADS, TAU_BYTES, Stopwatch, check_field_arithmetic, check_repeated_points, fr_bytes_array, oracle_pool, parse_proof, pps, progress, serialize_steps, to_device
+from gpu_util import HOST_THREADS, TAU_BYTES, Stopwatch, check_field_arithmetic, check_one_point_throughout, check_repeated_points, fr_bytes_array, oracle_pool, parse_proof, pps, progress, serialize_steps, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -99,6 +99,12 @@ def test_commit_over_repeated_points(ctx):
     """Equal and opposite points inside the bucket sums: the sub-runs that the fast accumulation gives up and the
     second launch redoes with every case of the group law (see check_repeated_points)."""
     check_repeated_points(ctx, to_device)
+
+
+def test_commit_over_one_point_at_size(ctx):
+    """The same at 2^21 terms, where the passes over the partial sums take their chip-filling kernels: one point at
+    every position sends every lane of those passes to their second launch."""
+    check_one_point_throughout(ctx, to_device, (512, 4096))
 
 
 def test_srs_points_match_oracle(ctx, c1):

@@ -25,7 +25,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, ROOT)
 import __graft_entry__ as entry  # noqa: E402
 import paper_2602_12630_amd as T  # noqa: E402
-from gpu_util import TAU_BYTES, check_field_arithmetic, check_repeated_points, fr_bytes_array, pps, serialize_steps  # noqa: E402
+from gpu_util import TAU_BYTES, check_field_arithmetic, check_one_point_throughout, check_repeated_points, fr_bytes_array, pps, serialize_steps  # noqa: E402
 
 EMU = os.path.join(ROOT, "tests", "hostmath", "libtc_hostemu.so")
 
@@ -715,6 +715,7 @@ def test_emulated_options(emu, monkeypatch):
 def test_emulated_commit_over_repeated_points(emu):
     """Equal and opposite points inside the bucket sums (see check_repeated_points), on the host build."""
     check_repeated_points(emu, lambda a: a)
+    check_one_point_throughout(emu, lambda a: a, (16, 128))
 
 
 def test_emulated_open_with_the_opening_table(emu, node_srs):
