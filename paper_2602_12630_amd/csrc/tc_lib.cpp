@@ -1201,12 +1201,18 @@ static int scan_counts(tc_ctx* ctx, const uint32_t* cnt, uint32_t n, uint32_t L,
     return TC_OK;
 }
 
+/* from this many 128- or 256-bucket windows on (the row problems of openings), throughput matters and not depth */
+#if defined(TC_HOST_EMU)
+static const int SMALL_WINDOW_REDUCE_MIN = 8;          /* the CPU build of the tests reaches it with a handful of rows */
+#else
+static const int SMALL_WINDOW_REDUCE_MIN = 512;
+#endif
 /* from this many 32768-bucket windows on, a launch fills the chip with the packed row / column sums */
 static const int ROWCOL_PACKED_WINDOWS = 8;
 
 /* sum_k k B_k for every window of `bucket` (W windows of nb buckets) -> wsum[W] */
 static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb, g1_xyzz* wsum) {
-    if ((nb == 256 || nb == 128) && W >= 512) {
+    if ((nb == 256 || nb == 128) && W >= SMALL_WINDOW_REDUCE_MIN) {
         /* many small windows (row problems of openings): throughput matters, not depth */
         RT((launch_coop<SmallWindowReduce256::BLOCK>(((uint32_t)W + 1) / 2, ctx->stream, SmallWindowReduce256{bucket, nb, (uint32_t)W, wsum})));
         return TC_OK;
