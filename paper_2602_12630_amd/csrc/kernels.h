@@ -413,8 +413,20 @@ struct TileColumnScan {       /* lane = (problem, key) */
     TC_DEV void operator()(uint32_t t) const {
         uint32_t p = t / nb, key = t % nb;
         uint32_t* col = M + (uint64_t)p * n_wg * nb + key;
-        uint32_t off = 0;
-        for (uint32_t w = 0; w < n_wg; ++w) {
+        uint32_t off = 0, w = 0;
+        /* sixteen loads in flight: taken one at a time, each waits for the one before (a lone flat commitment with
+         * 256 tiles: 69 us that way) */
+        for (; w + 16 <= n_wg; w += 16) {
+            uint32_t v[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) v[k] = col[(uint64_t)(w + k) * nb];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                col[(uint64_t)(w + k) * nb] = off;
+                off += v[k];
+            }
+        }
+        for (; w < n_wg; ++w) {
             uint32_t v = col[(uint64_t)w * nb];
             col[(uint64_t)w * nb] = off;
             off += v;
@@ -575,6 +587,12 @@ struct ScanSmall {
     uint32_t* total_a;     /* one value each: sum of cnt, sum of ceil(cnt / L), largest cnt */
     uint32_t* total_b;
     uint32_t* total_max;
+    /* ceil(v / L) without a division per bucket: L <= 64, and floor(x / L) = (x * ceil(2^32 / L)) >> 32 for x < 2^26 */
+    TC_DEV uint32_t lanes_for(uint32_t v, uint32_t magic) const {
+        uint32_t x = v + L - 1;
+        return x < (1u << 26) ? (uint32_t)(((uint64_t)x * magic) >> 32) : x / L;
+    }
+    struct Quad { uint32_t v[4]; };
     TC_DEV void phase(int ph, uint32_t lane, uint32_t, uint8_t* lds) const {
         uint32_t* sa = (uint32_t*)lds;
         uint32_t* sb = sa + BLOCK;
@@ -584,13 +602,30 @@ struct ScanSmall {
         uint32_t per = (n + BLOCK - 1) / BLOCK;
         uint32_t lo = lane * per < n ? lane * per : n;
         uint32_t hi = lo + per < n ? lo + per : n;
+        uint32_t magic = L > 1 ? (uint32_t)(((1ull << 32) + L - 1) / L) : 0u;         /* L = 1: the quotient is the count itself */
+        /* a lane's buckets as 16-byte pieces when they are whole pieces (32768 buckets: 32 per lane) */
+        bool quads = (per & 3u) == 0 && hi - lo == per && (((uintptr_t)cnt | (uintptr_t)start | (uintptr_t)lstart) & 15u) == 0;
         if (ph == 0) {                         /* every lane: sums over its own buckets */
             uint32_t a = 0, b = 0, mx = 0;
-            for (uint32_t i = lo; i < hi; ++i) {
-                uint32_t v = cnt[i];
-                a += v;
-                b += (v + L - 1) / L;
-                mx = v > mx ? v : mx;
+            if (quads) {
+                const Quad* c4 = (const Quad*)(cnt + lo);
+                for (uint32_t i = 0; i < per / 4; ++i) {
+                    Quad q = c4[i];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        uint32_t v = q.v[k];
+                        a += v;
+                        b += L > 1 ? lanes_for(v, magic) : v;
+                        mx = v > mx ? v : mx;
+                    }
+                }
+            } else {
+                for (uint32_t i = lo; i < hi; ++i) {
+                    uint32_t v = cnt[i];
+                    a += v;
+                    b += L > 1 ? lanes_for(v, magic) : v;
+                    mx = v > mx ? v : mx;
+                }
             }
             sa[lane] = a; sb[lane] = b; sm[lane] = mx;
         } else if (ph == 1) {                  /* one lane per group: exclusive prefix inside the group, the group's totals */
@@ -624,13 +659,32 @@ struct ScanSmall {
             sb[lane] += gb[lane / GROUP];
         } else {
             uint32_t a = sa[lane], b = sb[lane];
-            for (uint32_t i = lo; i < hi; ++i) {
-                uint32_t v = cnt[i];
-                start[i] = a;
-                lstart[i] = b;
-                a += v;
-                b += (v + L - 1) / L;
-                if (zero_me) zero_me[i] = 0;
+            if (quads && !zero_me) {
+                const Quad* c4 = (const Quad*)(cnt + lo);
+                Quad* s4 = (Quad*)(start + lo);
+                Quad* l4 = (Quad*)(lstart + lo);
+                for (uint32_t i = 0; i < per / 4; ++i) {
+                    Quad q = c4[i], qs, ql;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        uint32_t v = q.v[k];
+                        qs.v[k] = a;
+                        ql.v[k] = b;
+                        a += v;
+                        b += L > 1 ? lanes_for(v, magic) : v;
+                    }
+                    s4[i] = qs;
+                    l4[i] = ql;
+                }
+            } else {
+                for (uint32_t i = lo; i < hi; ++i) {
+                    uint32_t v = cnt[i];
+                    start[i] = a;
+                    lstart[i] = b;
+                    a += v;
+                    b += L > 1 ? lanes_for(v, magic) : v;
+                    if (zero_me) zero_me[i] = 0;
+                }
             }
         }
     }
