@@ -368,7 +368,7 @@ TC_HD g1_affine xyzz_to_affine_with_inv(const g1_xyzz& p, const fp_t& inv) {
 }
 TC_HD g1_affine xyzz_to_affine(const g1_xyzz& p) {
     if (xyzz_is_identity(p)) return affine_identity();
-    return xyzz_to_affine_with_inv(p, fe_inv_gcd<FpParams>(fp_mul(p.ZZ, p.ZZZ)));
+    return xyzz_to_affine_with_inv(p, fp_inv28(fp_mul(p.ZZ, p.ZZZ)));
 }
 
 /* [k] P for a plain (non-Montgomery) scalar of `nbits` bits, MSB-first double-and-add */

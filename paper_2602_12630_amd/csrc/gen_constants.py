@@ -131,6 +131,10 @@ def block28():
     out.append("    static constexpr int32_t PINV = 0x%07x;              /* p^-1 mod 2^28 */" % pow(P_MOD, -1, 1 << 28))
     out.append("    static constexpr int32_t MOD[14] = {%s};" % limbs28(P_MOD))
     out.append("    static constexpr int32_t ONE[14] = {%s};   /* 2^392 mod p */" % limbs28(Rm % P_MOD))
+    rounds = -(-(2 * P_MOD.bit_length() - 1) // 28) + 1
+    out.append("    static constexpr int GCD_ROUNDS = %d;                /* ceil((2 len(p) - 1) / 28) + 1 rounds of 28 steps */" % rounds)
+    out.append("    static constexpr int32_t INV_FIX[14] = {%s};  /* 2^1168 mod p: 1 / a (mod p) -> the 28-bit form of R^2 / a, R = 2^384 */"
+               % limbs28(pow(2, 1168, P_MOD)))
     out.append("};")
     return "\n".join(out)
 

@@ -74,7 +74,7 @@ struct FieldOp {
             case FOP_FP_SQR: r = fp_sqr(x); break;
             case FOP_FP_MUL_F64: r = fp_mul_lat(x, y); break;
             case FOP_FP_SQR_F64: r = fp_sqr_lat(x); break;
-            case FOP_FP_INV: r = fe_inv_gcd<FpParams>(x); break;
+            case FOP_FP_INV: r = fp_inv28(x); break;
             case FOP_FP_ADD: r = fp_add(x, y); break;
             case FOP_FP28_MUL: r = fp28_to_fp(fp28_mul(fp28_from_fp(x), fp28_from_fp(y))); break;
             case FOP_FP28_SQR: r = fp28_to_fp(fp28_sqr(fp28_from_fp(x))); break;
@@ -1437,7 +1437,7 @@ struct BatchNormalize {
             out[i].x = run;                       /* product of z_lo .. z_{i-1} */
             if (!fe_is_zero(in[i].ZZ)) run = fp_mul(run, fp_mul(in[i].ZZ, in[i].ZZZ));
         }
-        fp_t inv = fe_inv_gcd<FpParams>(run);      /* run != 0: product of non-zero values */
+        fp_t inv = fp_inv28(run);                    /* run != 0: product of non-zero values */
         for (uint64_t i = hi; i-- > lo;) {
             g1_xyzz p = in[i];
             if (fe_is_zero(p.ZZ)) {
