@@ -2120,7 +2120,7 @@ TC_HD bool xyzz_equal(const g1_xyzz& a, const g1_xyzz& b) {
  * faster one after the other than three waves do side by side: wave 0 carries X and Y, wave 1 the powers of Y,
  * wave 2 Z and D = 4 X B; operands pass through LDS, a barrier after every level.  The chain computes in the
  * 28-bit-limb form of the field (a wave alone gets through those products 1.6 times as fast as through the 32-bit
- * ones: 0.81 -> 0.57 ms for the chains of eight paths): sums and small multiples are limb-wise and get one carry
+ * ones: 0.81 -> 0.60 ms for the chains of eight paths): sums and small multiples are limb-wise and get one carry
  * pass before they meet a product, nothing is reduced along the way.  The points that the chain keeps are in the
  * 32-bit form; wave 3 converts them, one coordinate per level, from copies that the other waves leave for it (X
  * and Y of a point in the slot of its parity, so that the next doubling may write while the last is still being

@@ -1343,7 +1343,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
      * is fastest with the shortest sub-runs (the first entry of a sub-run is a copy, not an addition), the later
      * passes with the longest, and steps in flight run equally fast from 4 to 13.  Not longer than half the
      * average bucket load either: longer sub-runs leave the lanes of a wave with very different amounts of work
-     * (measured on the 64 openings of the LLaMA2-7B-shaped forward, row buckets of 16 entries on average: sub-runs
+     * (measured, with the 32-bit-limb accumulation of the time, on the 64 openings of the LLaMA2-7B-shaped forward, row buckets of 16 entries on average: sub-runs
      * of 8 and 16 entries 136 and 138 ms, of 24 and 32 entries 145 and 163 ms; on that forward's build, 101 entries
      * per bucket: sub-runs of 50 entries and one middle pass 69.2 ms, of 64 entries and no middle pass 70.3 ms). */
     const uint64_t target_lanes = 2 * ACC_RESIDENT_LANES;
