@@ -159,8 +159,11 @@ int tc_ctx_field_op(tc_ctx* ctx, int op, const void* d_a, const void* d_b, size_
                                 a public linear image of the SRS.  With it an opening along the leading axis of a large
                                 int8 / int16 tensor splits into the tensor's row commitments sum_t T[k, t] S[k, t], which
                                 do not depend on the position (a tree keeps them per leaf tensor once computed), and one
-                                short multi-exponentiation against row kappa of U.  Shapes of order >= 2 only; without it
-                                tc_open does the same work per opening.  Results are identical either way. */
+                                short multi-exponentiation against row kappa of U.  The flag also keeps, behind the SRS
+                                table, a copy of it multiplied by 2^8 (a second public image of the same size): the two
+                                8-bit digits of an int16 entry then share one window of 128 buckets per row.  Shapes of
+                                order >= 2 only; without it tc_open does the same work per opening.  Results are
+                                identical either way. */
 #define TC_SRS_MONOMIAL 4u   /* the monomial SRS of Def. 4.1 itself, S[k] = [prod_j tau_j^(k_j)] G, instead of its
                                 Lagrange-basis image: for committing coefficient arrays (tc_interpolate,
                                 tc_divide_by_linear) with tc_commit; not combinable with the other flags, and
@@ -183,8 +186,8 @@ int tc_srs_get_point(tc_ctx* ctx, const tc_srs* srs, int first_axis, uint64_t in
 /* The public parameters as a flat file (Def. 4.1, Setup publishes pp = (srs, Omega): the SRS outlives the process
  * that made it).  Layout, little-endian: "TCSRS\0\0\0", u32 version (1), u32 curve (1 = BLS12-381 G1), u32 basis
  * (0 Lagrange image, 1 monomial), u32 flags, u32 m, u32 shape[4], u32 reserved, u64 point count; then the tables
- * S^(0) .. S^(m-1) that the SRS holds and, with TC_SRS_OPEN_TABLE, the opening table U, canonical 96-byte points.  Fixed-base tables and the grid constants are not
- * stored: the import rebuilds them.
+ * S^(0) .. S^(m-1) that the SRS holds and, with TC_SRS_OPEN_TABLE, the opening table U, canonical 96-byte points.
+ * Fixed-base tables, the grid constants and the 2^8-fold copy of S^(0) are not stored: the import rebuilds them.
  * Export: on entry *len is the capacity of host_buf, on return the size of the file; host_buf = NULL only asks for
  * the size; a buffer that is too small gives TC_ERR_ARG.
  * Import: builds an SRS equal to the exported one on this context's GPU.  A truncated or overlong buffer, a wrong

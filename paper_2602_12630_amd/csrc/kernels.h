@@ -21,7 +21,9 @@ namespace tc {
 
 enum { DT_I8 = 1, DT_I16 = 2, DT_FR = 3, DT_F16 = 4,
        DT_DIFF8 = 5, DT_DIFF16 = 6, /* internal: difference of two int8 / int16 arrays, two 9-bit signed digits */
-       DT_SPLIT16 = 7 /* internal: an int16 array as two 8-bit signed digits (problems too short for 32768 buckets) */ };
+       DT_SPLIT16 = 7, /* internal: an int16 array as two 8-bit signed digits (problems too short for 32768 buckets) */
+       DT_SPLIT16M = 8 /* internal: the same two digits sharing ONE window of 128 buckets: the high digit of term i takes
+                          the point i + shift of the table, which holds 2^8 times the point i */ };
 
 struct alignas(16) fr_plain {           /* canonical (non-Montgomery) Fr value, 8 limbs */
     uint32_t l[8];
@@ -341,6 +343,7 @@ struct TileProblem {
     const void* sub;          /* optional subtrahend array (same element type): value = scalars[i] - sub[i] */
     uint64_t n;
     uint32_t tile;            /* terms per workgroup */
+    uint32_t shift;           /* DT_SPLIT16M: digit w of term i is entered as point i + w * shift */
 };
 TC_HD int32_t tile_value(const TileProblem& P, int dtype, uint64_t i) {
     int32_t v = small_scalar(P.scalars, dtype, i);
@@ -356,7 +359,7 @@ TC_DEV void tile_terms(const TileProblem& P, int dtype, uint64_t lo, uint64_t hi
     if (lo >= hi) return;                  /* a tile past the end of its problem */
     uint64_t rest = lo;
     uint32_t esz = dtype == DT_I8 ? 1u : 2u;
-    if (WIDE && !P.sub && (dtype == DT_I8 || dtype == DT_I16 || dtype == DT_SPLIT16) && (((uintptr_t)P.scalars + lo * esz) & 15u) == 0) {
+    if (WIDE && !P.sub && (dtype == DT_I8 || dtype == DT_I16 || dtype == DT_SPLIT16 || dtype == DT_SPLIT16M) && (((uintptr_t)P.scalars + lo * esz) & 15u) == 0) {
         uint32_t per = 16u / esz;
         uint64_t chunks = (hi - lo) / per;
         const Words16* src = (const Words16*)((const uint8_t*)P.scalars + lo * esz);
@@ -387,7 +390,8 @@ struct CountTile {
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         uint32_t* hist = (uint32_t*)lds;
         uint32_t p = wg / n_wg, tl = wg % n_wg;
-        uint32_t nb = (uint32_t)NBK / (uint32_t)W;
+        const bool merged = dtype == DT_SPLIT16M;          /* all digits of a term share the one window */
+        uint32_t nb = merged ? 0u : (uint32_t)NBK / (uint32_t)W;
         if (ph == 0) {
             for (uint32_t k = lane; k < (uint32_t)NBK; k += BLOCK) hist[k] = 0;
         } else if (ph == 1) {
@@ -448,7 +452,8 @@ struct ScatterTile {
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         uint32_t* cur = (uint32_t*)lds;
         uint32_t p = wg / n_wg, tl = wg % n_wg;
-        uint32_t nb = (uint32_t)NBK / (uint32_t)W;
+        const bool merged = dtype == DT_SPLIT16M;
+        uint32_t nb = merged ? 0u : (uint32_t)NBK / (uint32_t)W;
         if (ph == 0) {
             const uint32_t* row = M + (uint64_t)wg * NBK;
             const uint32_t* st = start + (uint64_t)p * NBK;
@@ -463,7 +468,8 @@ struct ScatterTile {
                     if (d) {
                         uint32_t pos = atomic_add_u32(&cur[(uint32_t)w * nb + (uint32_t)(d < 0 ? -d : d) - 1u], 1u);
                         bool negative = (d < 0) != (v < 0);
-                        sorted[pos] = (uint32_t)i | (negative ? 0x80000000u : 0u);
+                        uint32_t idx = (uint32_t)i + (merged ? (uint32_t)w * P.shift : 0u);
+                        sorted[pos] = idx | (negative ? 0x80000000u : 0u);
                     }
                 }
             });
@@ -731,7 +737,21 @@ TC_HD bool xyzz28_madd_regular(g1_xyzz28& a, const fp28& x2, const fp28& y2) {
     return true;
 }
 /* Lane t owns sub-run `t - lstart[b]` of bucket b: at most L entries, all of one bucket.
- * Output slot t, so the partial sums of bucket b are the slots lstart[b] .. lstart[b+1]. */
+ * Output slot t, so the partial sums of bucket b are the slots lstart[b] .. lstart[b+1].
+ * The k = ceil(c / L) sub-runs of a bucket with c entries are equally long (to within one entry), not L, L, .., rest:
+ * the lanes of a wave run for as long as the longest of their sub-runs, and neighbouring lanes share a bucket or have
+ * buckets of similar loads. */
+TC_HD void subrun_bounds(const uint32_t* start, const uint32_t* lstart, uint32_t b, uint32_t t, uint32_t& begin, uint32_t& end) {
+    uint32_t s0 = start[b], c = start[b + 1] - s0;
+    uint32_t l0 = lstart[b], k = lstart[b + 1] - l0, j = t - l0;
+    if ((c | k) < 65536u) {                /* the usual case, without 64-bit divisions */
+        begin = s0 + j * c / k;
+        end = s0 + (j + 1u) * c / k;
+    } else {
+        begin = s0 + (uint32_t)((uint64_t)j * c / k);
+        end = s0 + (uint32_t)((uint64_t)(j + 1) * c / k);
+    }
+}
 struct AccAffine {
     const g1_affine* const* tables;   /* SRS table of problem p; bucket b belongs to problem b / nbk_pp */
     uint32_t nbk_pp;
@@ -745,8 +765,8 @@ struct AccAffine {
     TC_DEV void operator()(uint32_t t) const {
         if (t >= lstart[nbk]) return;
         uint32_t b = find_segment(lstart, nbk, t);
-        uint32_t begin = start[b] + (t - lstart[b]) * L;
-        uint32_t end = begin + L < start[b + 1] ? begin + L : start[b + 1];
+        uint32_t begin, end;
+        subrun_bounds(start, lstart, b, t, begin, end);
         const g1_affine* pts = tables[b / nbk_pp];
         if (end - begin == 1) {                                   /* a lone entry: no arithmetic */
             uint32_t e = sorted[begin];
@@ -802,8 +822,8 @@ struct AccAffineRedo {
         for (uint32_t k = lane; k < *redo_count; k += lanes) {
             uint32_t t = redo_list[k];
             uint32_t b = find_segment(lstart, nbk, t);
-            uint32_t begin = start[b] + (t - lstart[b]) * L;
-            uint32_t end = begin + L < start[b + 1] ? begin + L : start[b + 1];
+            uint32_t begin, end;
+            subrun_bounds(start, lstart, b, t, begin, end);
             const g1_affine* pts = tables[b / nbk_pp];
             xyzz_acc acc = acc_identity();
             for (uint32_t i = begin; i < end; ++i) {
@@ -1418,6 +1438,18 @@ struct WindowCombine {
             acc_add(acc, acc_from(ws[w]));
         }
         out[p] = acc_result(acc);
+    }
+};
+
+/* out[t] = 2^doublings * in[t]: the second half of a table whose high digits share the buckets of the low ones */
+struct ShiftPoints {
+    const g1_affine* in;
+    int doublings;
+    g1_xyzz* out;
+    TC_DEV void operator()(uint32_t t) const {
+        xyzz_acc acc = acc_from(xyzz_from_affine(in[t]));
+        for (int i = 0; i < doublings; ++i) acc_dbl(acc);
+        out[t] = acc_result(acc);
     }
 };
 

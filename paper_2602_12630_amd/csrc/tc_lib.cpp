@@ -106,6 +106,7 @@ struct tc_srs {
     g1_affine* pts[4] = {nullptr, nullptr, nullptr, nullptr};
     g1_affine* fb[4] = {nullptr, nullptr, nullptr, nullptr};
     g1_affine* open_tab = nullptr;      /* U[kappa, t] of the leading axis (TC_SRS_OPEN_TABLE), n[0] points */
+    bool shifted = false;               /* pts[0] has 2 n[0] points, the second half holding 2^8 times the first (TC_SRS_OPEN_TABLE) */
     fr_t* axis_mem = nullptr;
     AxisTables ax[4];
 };
@@ -798,6 +799,22 @@ static bool srs_flags_ok(uint32_t flags) {
     return !(flags & TC_SRS_MONOMIAL) || flags == TC_SRS_MONOMIAL;
 }
 
+/* Fills the second half of srs->pts[0] (allocated with 2 n[0] points) with 2^8 times the first: the row commitments
+ * of an int16 tensor then need one window of 128 buckets per row for both 8-bit digits of an entry (the high digit
+ * of entry i is entered as point n[0] + i), which halves the buckets that are reduced per row.  A public image of the
+ * SRS; not stored in the SRS file, the import computes it again.  `tmp` holds at least min(slab, n[0]) XYZZ points. */
+static const int SHIFT_BITS = 8;
+static int srs_build_shifted_half(tc_ctx* ctx, tc_srs* srs, g1_xyzz* tmp, uint64_t slab) {
+    uint64_t n0 = srs->n[0];
+    for (uint64_t i0 = 0; i0 < n0; i0 += slab) {
+        uint64_t cnt = std::min(slab, n0 - i0);
+        RT(rt::launch<64>(cnt, ctx->stream, ShiftPoints{srs->pts[0] + i0, SHIFT_BITS, tmp}));
+        TRY(normalize(ctx, tmp, cnt, srs->pts[0] + n0 + i0));
+    }
+    srs->shifted = true;
+    return TC_OK;
+}
+
 extern "C" int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, const uint32_t* shape, uint32_t flags,
                                       tc_srs** out) {
     try {
@@ -877,7 +894,8 @@ extern "C" int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, co
                 for (int j = a; j < m; ++j) na *= shape[j];
                 srs->n[a] = na;
                 void* q = nullptr;
-                if (rt::dev_malloc(&q, (size_t)na * sizeof(g1_affine)) != 0) { rc = fail(ctx, TC_ERR_NOMEM, "SRS allocation failed"); break; }
+                bool twice = a == 0 && (flags & TC_SRS_OPEN_TABLE) && na <= 0x3FFFFFFFull;      /* room for the shifted half */
+                if (rt::dev_malloc(&q, (size_t)na * (twice ? 2 : 1) * sizeof(g1_affine)) != 0) { rc = fail(ctx, TC_ERR_NOMEM, "SRS allocation failed"); break; }
                 srs->pts[a] = (g1_affine*)q;
                 SrsGen gen;
                 gen.shape.m = m;
@@ -894,6 +912,7 @@ extern "C" int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, co
                     rc = normalize(ctx, (g1_xyzz*)tmp, cnt, srs->pts[a] + i0);
                 }
                 if (rc == TC_OK && (flags & TC_SRS_FIXED_BASE)) rc = build_fixed_base_table(ctx, srs->pts[a], (uint32_t)na, &srs->fb[a]);
+                if (rc == TC_OK && twice) rc = srs_build_shifted_half(ctx, srs, (g1_xyzz*)tmp, std::min<uint64_t>(slab, total));
             }
             if (rc == TC_OK && (flags & TC_SRS_OPEN_TABLE)) {
                 /* U = the generator run once more with g(kappa) in the place of the leading axis' Lagrange values */
@@ -1075,11 +1094,21 @@ extern "C" int tc_srs_import(tc_ctx* ctx, const void* host_buf, size_t len, tc_s
         for (int a = 0; a <= last_axis && rc == TC_OK; ++a) {
             srs->n[a] = n[a];
             void* q = nullptr;
-            if (rt::dev_malloc(&q, (size_t)n[a] * sizeof(g1_affine)) != 0) { rc = fail(ctx, TC_ERR_NOMEM, "SRS allocation failed"); break; }
+            bool twice = a == 0 && (flags & TC_SRS_OPEN_TABLE) && n[a] <= 0x3FFFFFFFull;
+            if (rt::dev_malloc(&q, (size_t)n[a] * (twice ? 2 : 1) * sizeof(g1_affine)) != 0) { rc = fail(ctx, TC_ERR_NOMEM, "SRS allocation failed"); break; }
             srs->pts[a] = (g1_affine*)q;
             rc = import_points(ctx, src, n[a], srs->pts[a]);
             src += 96 * (size_t)n[a];
             if (rc == TC_OK && (flags & TC_SRS_FIXED_BASE)) rc = build_fixed_base_table(ctx, srs->pts[a], (uint32_t)n[a], &srs->fb[a]);
+            if (rc == TC_OK && twice) {
+                const uint64_t slab = std::min<uint64_t>(1ull << 20, n[a]);
+                void* tmp = nullptr;
+                if (rt::dev_malloc(&tmp, (size_t)slab * sizeof(g1_xyzz)) != 0) { rc = fail(ctx, TC_ERR_NOMEM, "SRS scratch allocation failed"); break; }
+                rc = srs_build_shifted_half(ctx, srs, (g1_xyzz*)tmp, slab);
+                int e = rt::stream_sync(ctx->stream);
+                if (e && rc == TC_OK) rc = fail_hip(ctx, e, "shifted SRS half");
+                rt::dev_free(tmp);
+            }
         }
         if (rc == TC_OK && (flags & TC_SRS_OPEN_TABLE)) {
             void* q = nullptr;
@@ -1290,12 +1319,16 @@ struct MsmProblem {
     const void* scalars;
     uint64_t n;
     const void* sub = nullptr;     /* DT_DIFF8 / DT_DIFF16: value = scalars[i] - sub[i] */
+    uint32_t shift = 0;            /* DT_SPLIT16M: pts[i + shift] = 2^8 pts[i] */
 };
+/* digits per term: one per window, except where the digits of a term share a window */
+static int msm_digits(int dtype, int W) { return dtype == DT_SPLIT16M ? 2 : W; }
 static void msm_config(const tc_ctx* ctx, int dtype, uint64_t n, int* W, int* c) {
     if (dtype == TC_I8) { *W = 1; *c = 8; }
     else if (dtype == TC_I16) { *W = 1; *c = 16; }
     else if (dtype == DT_DIFF8 || dtype == DT_DIFF16) { *W = 2; *c = 9; }
     else if (dtype == DT_SPLIT16) { *W = 2; *c = 8; }
+    else if (dtype == DT_SPLIT16M) { *W = 1; *c = 8; }
     else {
         *c = ctx->opt[TC_OPT_FR_WINDOW] ? (int)ctx->opt[TC_OPT_FR_WINDOW] : n >= 32768 ? 16 : 8;
         *W = 256 / *c;
@@ -1307,10 +1340,11 @@ static void msm_config(const tc_ctx* ctx, int dtype, uint64_t n, int* W, int* c)
 static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int dtype, int W, int c, g1_xyzz* results) {
     uint32_t nb = 1u << (c - 1);
     uint32_t nbk_pp = (uint32_t)W * nb;
+    const int D = msm_digits(dtype, W);
     uint64_t items = 0, max_items = 0;
     for (int p = 0; p < count; ++p) {
-        items += prob[p].n * (uint64_t)W;
-        max_items = std::max<uint64_t>(max_items, prob[p].n * (uint64_t)W);
+        items += prob[p].n * (uint64_t)D;
+        max_items = std::max<uint64_t>(max_items, prob[p].n * (uint64_t)D);
     }
     uint64_t nbk64 = (uint64_t)nbk_pp * (uint64_t)count;
     if (items > 0xFFFFFFF0ull || nbk64 > 0x7FFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "MSM batch too large");
@@ -1358,7 +1392,12 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     uint32_t max_count = 0;        /* largest bucket: fixes how many shrinking passes are needed */
     if (dtype != TC_FR) {
         /* small scalars (one or two digits per term): tile histograms in LDS, no global atomics */
-        uint32_t n_wg = (uint32_t)std::min<uint64_t>(256, std::max<uint64_t>(8, 4096 / (uint64_t)count));
+        /* tiles per problem: enough workgroups to fill the chip, but no tile so short that most of a workgroup's 1024
+         * lanes (sixteen bytes of scalars per lane and step) find nothing to do -- the rows of a batch of openings,
+         * tens of thousands of problems of a few thousand terms, are one tile each */
+        uint64_t max_terms = 0;
+        for (int p = 0; p < count; ++p) max_terms = std::max<uint64_t>(max_terms, prob[p].n);
+        uint32_t n_wg = (uint32_t)std::min<uint64_t>(256, std::max<uint64_t>(1, std::min<uint64_t>(4096 / (uint64_t)count, max_terms / 8192)));
         if (ctx->static_mode) n_wg = STATIC_TILES;     /* the tile histograms are n_wg rows of the key space */
         TileProblem one;
         std::vector<TileProblem> many;
@@ -1371,23 +1410,24 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
             h_prob[p].n = prob[p].n;
             /* a multiple of 16 terms, so that a tile of an aligned int8 / int16 array starts on a 16-byte boundary */
             h_prob[p].tile = (uint32_t)(((prob[p].n + n_wg - 1) / n_wg + 15) / 16 * 16);
+            h_prob[p].shift = prob[p].shift;
         }
         WS(d_prob, TileProblem, (uint32_t)count);
         WS(M, uint32_t, (uint64_t)count * n_wg * nbk_pp);
         TRY(upload_small(ctx, d_prob, h_prob, sizeof(TileProblem) * (size_t)count));
         uint32_t groups = (uint32_t)count * n_wg;
-        if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, CountTile<128>{d_prob, dtype, W, c, n_wg, M})));
-        else if (nbk_pp == 256) RT((launch_coop<1024>(groups, ctx->stream, CountTile<256>{d_prob, dtype, W, c, n_wg, M})));
-        else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, CountTile<512>{d_prob, dtype, W, c, n_wg, M})));
-        else if (nbk_pp == 32768) RT((launch_coop<1024>(groups, ctx->stream, CountTile<32768>{d_prob, dtype, W, c, n_wg, M})));
+        if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, CountTile<128>{d_prob, dtype, D, c, n_wg, M})));
+        else if (nbk_pp == 256) RT((launch_coop<1024>(groups, ctx->stream, CountTile<256>{d_prob, dtype, D, c, n_wg, M})));
+        else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, CountTile<512>{d_prob, dtype, D, c, n_wg, M})));
+        else if (nbk_pp == 32768) RT((launch_coop<1024>(groups, ctx->stream, CountTile<32768>{d_prob, dtype, D, c, n_wg, M})));
         else return fail(ctx, TC_ERR_STATE, "internal: unsupported key count");
         RT(rt::launch<256>(nbk, ctx->stream, TileColumnScan{nbk_pp, n_wg, M, cnt}));
         TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, nullptr, tot_a, tot_b, tot_max));
         if (!ctx->static_mode) RT(rt::memcpy_d2h(&max_count, tot_max + nchunks, 4, ctx->stream));
-        if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<128>{d_prob, dtype, W, c, n_wg, M, start, sorted})));
-        else if (nbk_pp == 256) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<256>{d_prob, dtype, W, c, n_wg, M, start, sorted})));
-        else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<512>{d_prob, dtype, W, c, n_wg, M, start, sorted})));
-        else RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<32768>{d_prob, dtype, W, c, n_wg, M, start, sorted})));
+        if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<128>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
+        else if (nbk_pp == 256) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<256>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
+        else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<512>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
+        else RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<32768>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
     } else {
         if (ctx->static_mode) return fail(ctx, TC_ERR_STATE, "internal: full-width scalars in a call that may not allocate");
         RT(rt::launch<256>(nbk, ctx->stream, Fill32{cnt, 0u}));
@@ -1503,14 +1543,15 @@ static int msm_engine_list(tc_ctx* ctx, int count, const MsmProblem* prob, const
     while (i < count) {
         int W, c;
         msm_config(ctx, dtype[i], prob[i].n, &W, &c);
-        uint64_t items = prob[i].n * (uint64_t)W, buckets = (uint64_t)W << (c - 1);
+        const int D = msm_digits(dtype[i], W);
+        uint64_t items = prob[i].n * (uint64_t)D, buckets = (uint64_t)W << (c - 1);
         int j = i + 1;
         while (j < count) {
             int W2, c2;
             msm_config(ctx, dtype[j], prob[j].n, &W2, &c2);
             if (dtype[j] != dtype[i] || W2 != W || c2 != c) break;
-            if (items + prob[j].n * (uint64_t)W > max_batch_items || buckets + ((uint64_t)W << (c - 1)) > max_batch_buckets) break;
-            items += prob[j].n * (uint64_t)W;
+            if (items + prob[j].n * (uint64_t)D > max_batch_items || buckets + ((uint64_t)W << (c - 1)) > max_batch_buckets) break;
+            items += prob[j].n * (uint64_t)D;
             buckets += (uint64_t)W << (c - 1);
             ++j;
         }
@@ -1684,6 +1725,8 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
             int two_digits = dt == TC_I8 ? DT_DIFF8 : DT_DIFF16;
             /* plain rows of the tensor (the table's route) are one 8-bit digit (int8) or two (int16) per entry */
             int plain_digits = dt == TC_I8 ? TC_I8 : DT_SPLIT16;
+            /* ... and with the shifted half of the table the two digits of a row share one window */
+            int row_digits = dt == TC_I16 && srs->shifted && J.inner < 0x40000000ull ? DT_SPLIT16M : plain_digits;
             if (J.use_table) {
                 for (size_t t = 0; t < tensors.size() && J.tensor < 0; ++t)
                     if (tensors[t].srs == srs && tensors[t].scalars == spec[o].scalars) J.tensor = (int)t;
@@ -1698,8 +1741,9 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
                             P.pts = srs->pts[0] + (uint64_t)k * J.inner;
                             P.scalars = base + (uint64_t)k * J.inner * esz;
                             P.n = J.inner;
+                            P.shift = (uint32_t)srs->n[0];
                             row_prob.push_back(P);
-                            row_dtype.push_back(plain_digits);
+                            row_dtype.push_back(row_digits);
                         }
                     }
                     J.tensor = (int)tensors.size();
