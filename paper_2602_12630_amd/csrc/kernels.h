@@ -762,8 +762,10 @@ struct AccAffine {
     g1_xyzz* out;
     uint32_t* redo_count;             /* zero before the launch */
     uint32_t* redo_list;              /* room for every lane */
-    TC_DEV void operator()(uint32_t t) const {
-        if (t >= lstart[nbk]) return;
+    const uint32_t* perm;             /* lane -> sub-run (lanes ordered by the length of their sub-runs), or null */
+    TC_DEV void operator()(uint32_t lane) const {
+        if (lane >= lstart[nbk]) return;
+        uint32_t t = perm ? perm[lane] : lane;
         uint32_t b = find_segment(lstart, nbk, t);
         uint32_t begin, end;
         subrun_bounds(start, lstart, b, t, begin, end);
@@ -806,6 +808,100 @@ struct AccAffine {
         out[t] = r;
     }
 };
+/* ---- lanes of the accumulation ordered by the length of their sub-runs ---------------------------------------
+ * The lanes of a wave run for as long as the longest of their sub-runs.  Where loads differ from bucket to bucket
+ * (the rows of an opening: 30 to 170 entries per bucket side by side) lanes in bucket order leave a fifth of a wave's
+ * lane-time idle; handed out in the order of their lengths, longest first, the sub-runs of a wave are equally long.
+ * perm[lane] = sub-run; its output slot stays the sub-run's own, so nothing after the accumulation changes.
+ * SubrunHist: one lane per bucket (k sub-runs of a bucket with c entries: c mod k of length c / k + 1, the others of
+ * length c / k).  SubrunBinStarts: one lane.  SubrunOrder: one lane per sub-run; positions inside a bin are handed out
+ * by atomics, so the order inside a bin varies from run to run -- the sums do not.  The passes over the partial sums
+ * are ordered the same way; lstart = null stands for their last one, a lane per bucket over all that it holds. */
+constexpr uint32_t SUBRUN_BINS = 65;          /* lengths 0 .. 63, and 64 or more */
+TC_HD uint32_t subrun_bin(uint32_t len) { return len < SUBRUN_BINS - 1u ? len : SUBRUN_BINS - 1u; }
+struct SubrunHist {
+    static constexpr int BLOCK = 256;
+    static constexpr int PHASES = 3;
+    static constexpr size_t LDS_BYTES = SUBRUN_BINS * sizeof(uint32_t);
+    const uint32_t* start;
+    const uint32_t* lstart;
+    uint32_t nbk;
+    uint32_t* hist;              /* SUBRUN_BINS counters, zero before the launch */
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        uint32_t* h = (uint32_t*)lds;
+        if (ph == 0) {
+            if (lane < SUBRUN_BINS) h[lane] = 0;
+        } else if (ph == 1) {
+            uint32_t b = wg * (uint32_t)BLOCK + lane;
+            if (b >= nbk) return;
+            uint32_t c = start[b + 1] - start[b];
+            if (!lstart) {                   /* one lane per bucket, whatever it holds */
+                atomic_add_u32(&h[subrun_bin(c)], 1u);
+                return;
+            }
+            uint32_t k = lstart[b + 1] - lstart[b];
+            if (!k) return;
+            uint32_t base = c / k, more = c % k;
+            if (more) atomic_add_u32(&h[subrun_bin(base + 1u)], more);
+            atomic_add_u32(&h[subrun_bin(base)], k - more);
+        } else if (lane < SUBRUN_BINS && h[lane]) {
+            atomic_add_u32(&hist[lane], h[lane]);
+        }
+    }
+};
+struct SubrunBinStarts {         /* longest first */
+    const uint32_t* hist;
+    uint32_t* binstart;
+    uint32_t* cursor;
+    TC_DEV void operator()(uint32_t) const {
+        uint32_t off = 0;
+        for (uint32_t i = SUBRUN_BINS; i-- > 0;) {
+            binstart[i] = off;
+            cursor[i] = 0;
+            off += hist[i];
+        }
+    }
+};
+struct SubrunOrder {
+    static constexpr int BLOCK = 256;
+    static constexpr int PHASES = 4;
+    static constexpr size_t LDS_BYTES = (2 * SUBRUN_BINS + BLOCK) * sizeof(uint32_t);
+    const uint32_t* start;
+    const uint32_t* lstart;
+    uint32_t nbk;
+    const uint32_t* binstart;
+    uint32_t* cursor;            /* zero before the launch */
+    uint32_t* perm;
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        uint32_t* cnt = (uint32_t*)lds;
+        uint32_t* base = cnt + SUBRUN_BINS;
+        uint32_t* bin_of = base + SUBRUN_BINS;
+        uint32_t t = wg * (uint32_t)BLOCK + lane;
+        if (ph == 0) {
+            if (lane < SUBRUN_BINS) cnt[lane] = 0;
+        } else if (ph == 1) {
+            uint32_t bin = 0xFFFFFFFFu;
+            if (!lstart) {
+                if (t < nbk) bin = subrun_bin(start[t + 1] - start[t]);
+            } else if (t < lstart[nbk]) {
+                uint32_t b = find_segment(lstart, nbk, t), begin, end;
+                subrun_bounds(start, lstart, b, t, begin, end);
+                bin = subrun_bin(end - begin);
+            }
+            if (bin != 0xFFFFFFFFu) atomic_add_u32(&cnt[bin], 1u);
+            bin_of[lane] = bin;
+        } else if (ph == 2) {
+            if (lane < SUBRUN_BINS) {
+                base[lane] = cnt[lane] ? binstart[lane] + atomic_add_u32(&cursor[lane], cnt[lane]) : 0u;
+                cnt[lane] = 0;
+            }
+        } else {
+            uint32_t bin = bin_of[lane];
+            if (bin != 0xFFFFFFFFu) perm[base[bin] + atomic_add_u32(&cnt[bin], 1u)] = t;
+        }
+    }
+};
+
 /* the sub-runs that AccAffine gave up, summed with every case of the group law */
 struct AccAffineRedo {
     const g1_affine* const* tables;
@@ -864,16 +960,17 @@ struct AccXyzzFast {
     uint32_t* redo_count;
     uint32_t* redo_list;
     bool final;
-    TC_DEV void operator()(uint32_t t) const {
+    const uint32_t* perm;          /* lane -> slot, ordered by the number of sums behind the slot, or null */
+    TC_DEV void operator()(uint32_t lane) const {
         uint32_t begin, end;
+        if (lane >= (final ? nbk : lstart[nbk])) return;
+        uint32_t t = perm ? perm[lane] : lane;
         if (final) {
             begin = start[t];
             end = start[t + 1];
         } else {
-            if (t >= lstart[nbk]) return;
             uint32_t b = find_segment(lstart, nbk, t);
-            begin = start[b] + (t - lstart[b]) * L;
-            end = begin + L < start[b + 1] ? begin + L : start[b + 1];
+            subrun_bounds(start, lstart, b, t, begin, end);
         }
         if (end - begin <= 1) {
             out[t] = begin < end ? in[begin] : xyzz_identity();
@@ -923,8 +1020,7 @@ struct AccXyzzRedo {
                 end = start[t + 1];
             } else {
                 uint32_t b = find_segment(lstart, nbk, t);
-                begin = start[b] + (t - lstart[b]) * L;
-                end = begin + L < start[b + 1] ? begin + L : start[b + 1];
+                subrun_bounds(start, lstart, b, t, begin, end);
             }
             xyzz_acc acc = acc_from(in[begin]);
             for (uint32_t i = begin + 1; i < end; ++i) acc_add(acc, acc_from(in[i]));

@@ -1310,6 +1310,12 @@ static const uint64_t FAST_PASS_LANES = 64;            /* the CPU build of the t
 static const uint64_t FAST_PASS_LANES = 131072;
 #endif
 static const uint32_t MAX_ACC_PASSES = 8;
+/* from this many sub-runs on, the accumulation takes them in the order of their lengths (three short launches) */
+#if defined(TC_HOST_EMU)
+static const uint64_t ORDERED_LANES_MIN = 64;
+#else
+static const uint64_t ORDERED_LANES_MIN = 1ull << 20;
+#endif
 /* lanes of the bucket accumulation that are resident at once: 256 compute units x 4 SIMDs x 3 waves x 64 */
 static const uint64_t ACC_RESIDENT_LANES = 256ull * 4 * 3 * 64;
 
@@ -1334,6 +1340,22 @@ static void msm_config(const tc_ctx* ctx, int dtype, uint64_t n, int* W, int* c)
         *W = 256 / *c;
     }
 }
+/* perm[lane] = sub-run (slot of the pass), longest first: the sub-runs of bucket b are the slots lstart[b] ..
+ * lstart[b + 1] over its entries start[b] .. start[b + 1]; lstart = null: one slot per bucket.  `lanes` bounds the
+ * number of slots from above. */
+static int order_lanes(tc_ctx* ctx, const uint32_t* start, const uint32_t* lstart, uint32_t nbk, uint64_t lanes, uint32_t** out_perm) {
+    uint32_t* perm = ws_array<uint32_t>(ctx, lanes);
+    uint32_t* bins = ws_array<uint32_t>(ctx, 3 * SUBRUN_BINS);          /* histogram, bin starts, cursors */
+    if (!perm || !bins) return fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed");
+    RT(rt::launch<64>(SUBRUN_BINS, ctx->stream, Fill32{bins, 0u}));
+    RT((launch_coop<SubrunHist::BLOCK>((nbk + SubrunHist::BLOCK - 1) / SubrunHist::BLOCK, ctx->stream, SubrunHist{start, lstart, nbk, bins})));
+    RT(rt::launch<64>(1, ctx->stream, SubrunBinStarts{bins, bins + SUBRUN_BINS, bins + 2 * SUBRUN_BINS}));
+    RT((launch_coop<SubrunOrder::BLOCK>((uint32_t)((lanes + SubrunOrder::BLOCK - 1) / SubrunOrder::BLOCK), ctx->stream,
+                                        SubrunOrder{start, lstart, nbk, bins + SUBRUN_BINS, bins + 2 * SUBRUN_BINS, perm})));
+    *out_perm = perm;
+    return TC_OK;
+}
+
 /* `count` problems of one scalar type and window plan, run through shared launches: the buckets of
  * problem p are the keys p * nbk .. (p + 1) * nbk of one big bucket space, so every pass (prefix
  * sums, balanced bucket sums, bucket reduction, window combination) is one launch for all problems. */
@@ -1382,7 +1404,10 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
      * per bucket: sub-runs of 50 entries and one middle pass 69.2 ms, of 64 entries and no middle pass 70.3 ms). */
     const uint64_t target_lanes = 2 * ACC_RESIDENT_LANES;
     uint32_t L1 = (uint32_t)std::min<uint64_t>(64, std::max<uint64_t>(4, (items + target_lanes - 1) / target_lanes));
-    L1 = (uint32_t)std::min<uint64_t>(L1, std::max<uint64_t>(4, (items + 2 * (uint64_t)nbk - 1) / (2 * (uint64_t)nbk)));
+    /* (launches large enough to hand their sub-runs out in the order of their lengths need no such bound: with it
+     * the LLaMA2-7B-shaped step takes 126.4 ms, with sub-runs of 64 entries 125.9 ms, and no less with 80 to 128) */
+    if (ctx->static_mode || items / L1 + nbk + 1 < ORDERED_LANES_MIN)
+        L1 = (uint32_t)std::min<uint64_t>(L1, std::max<uint64_t>(4, (items + 2 * (uint64_t)nbk - 1) / (2 * (uint64_t)nbk)));
     if (ctx->opt[TC_OPT_ACC_SUBRUN]) L1 = (uint32_t)ctx->opt[TC_OPT_ACC_SUBRUN];
     if (ctx->static_mode) L1 = STATIC_L1;      /* fewer, longer sub-runs: the partial sums must fit the static scratch */
     /* fan-in of the middle passes: with few buckets a pass costs the chain of additions of one lane, and shorter
@@ -1458,10 +1483,13 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     WS(redo_pass, uint32_t, MAX_ACC_PASSES);
     RT(rt::launch<64>(1, ctx->stream, Fill32{redo, 0u}));
     RT(rt::launch<64>(MAX_ACC_PASSES, ctx->stream, Fill32{redo_pass, 0u}));
+    /* launches with many more lanes than the chip holds hand their sub-runs out in the order of their lengths */
+    uint32_t* perm = nullptr;
+    if (max_part >= ORDERED_LANES_MIN && !ctx->static_mode) TRY(order_lanes(ctx, start, lstart, nbk, max_part, &perm));
     {
         rt::event_t e0, e1;
         prof_begin(ctx, TC_PROF_BUCKET_ACC, &e0, &e1);
-        RT((rt::launch_waves<64, 3>(max_part, ctx->stream, AccAffine{tables, nbk_pp, sorted, start, lstart, nbk, L1, bufA, redo, redo + 1})));
+        RT((rt::launch_waves<64, 3>(max_part, ctx->stream, AccAffine{tables, nbk_pp, sorted, start, lstart, nbk, L1, bufA, redo, redo + 1, perm})));
         prof_end(ctx, TC_PROF_BUCKET_ACC, e0, e1);
     }
     /* sub-runs with equal or opposite points in them: none in honest inputs; a degenerate input sends every sub-run
@@ -1502,7 +1530,9 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         lanes_bound = lanes_bound / L2 + nbk + 1;
         if (lanes_bound >= FAST_PASS_LANES && pass + 1 < MAX_ACC_PASSES) {
             uint32_t redo_lanes = (uint32_t)std::min<uint64_t>(lanes_bound, ACC_RESIDENT_LANES);
-            RT((rt::launch_waves<64, 2>(lanes_bound, ctx->stream, AccXyzzFast{cur, cur_start, nxt_start, nbk, L2, nxt, redo_pass + pass, redo + 1, false})));
+            uint32_t* pperm = nullptr;
+            if (lanes_bound >= ORDERED_LANES_MIN && !ctx->static_mode) TRY(order_lanes(ctx, cur_start, nxt_start, nbk, lanes_bound, &pperm));
+            RT((rt::launch_waves<64, 2>(lanes_bound, ctx->stream, AccXyzzFast{cur, cur_start, nxt_start, nbk, L2, nxt, redo_pass + pass, redo + 1, false, pperm})));
             RT(rt::launch<64>(redo_lanes, ctx->stream, AccXyzzRedo{cur, cur_start, nxt_start, nbk, L2, nxt, redo_pass + pass, redo + 1, false, redo_lanes}));
             ++pass;
         } else {
@@ -1515,7 +1545,10 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     if (nbk >= FAST_PASS_LANES && nbk <= max_part) {
         uint32_t redo_lanes = (uint32_t)std::min<uint64_t>(nbk, ACC_RESIDENT_LANES);
         uint32_t* count = redo_pass + (MAX_ACC_PASSES - 1);
-        RT((rt::launch_waves<64, 2>(nbk, ctx->stream, AccXyzzFast{cur, cur_start, nullptr, nbk, 0, bucket, count, redo + 1, true})));
+        uint32_t* pperm = nullptr;
+        /* (after a middle pass nearly every bucket is down to one sum and the order is not worth its three launches) */
+        if (nbk >= ORDERED_LANES_MIN && !ctx->static_mode && pass == 0) TRY(order_lanes(ctx, cur_start, nullptr, nbk, nbk, &pperm));
+        RT((rt::launch_waves<64, 2>(nbk, ctx->stream, AccXyzzFast{cur, cur_start, nullptr, nbk, 0, bucket, count, redo + 1, true, pperm})));
         RT(rt::launch<64>(redo_lanes, ctx->stream, AccXyzzRedo{cur, cur_start, nullptr, nbk, 0, bucket, count, redo + 1, true, redo_lanes}));
     } else {
         RT(rt::launch<64>(nbk, ctx->stream, AccFinal{cur, cur_start, bucket}));
