@@ -213,6 +213,13 @@ int tc_quant_scale(tc_ctx* ctx, const void* d_src, size_t n, float* d_inv_scale)
 /* tc_encode_tensor with the scale taken from device memory (what tc_quant_scale wrote, by launches that precede
  * this one on the stream): quantisation without a round trip to the host. */
 int tc_encode_tensor_scaled(tc_ctx* ctx, const void* d_src, int src_dtype, size_t n, const float* d_inv_scale, void* d_dst);
+/* tc_quant_scale followed by tc_encode_tensor_scaled (TC_F16) for `count` tensors in shared launches: the activations
+ * of one forward pass are a hundred tensors of a few MB, and launched one by one their passes are bound by the
+ * launches, not by HBM.  d_src[i]: n[i] fp16 values (device); d_inv_scale: `count` float32 in device memory, entry i
+ * receives the scale of tensor i; d_dst[i]: n[i] int16 values (device).  The pointer arrays and n are host arrays.
+ * Results are those of the two calls per tensor, bit for bit.  Asynchronous on the context's stream. */
+int tc_encode_batch_scaled(tc_ctx* ctx, int count, const void* const* d_src, const size_t* n, float* d_inv_scale,
+                           void* const* d_dst);
 
 /* ---- Com (Def. 4.1, Com) -------------------------------------------------------- */
 

@@ -97,6 +97,7 @@ def load_library(path=None):
         "tc_encode_tensor": (ctypes.c_int, [vp, vp, ctypes.c_int, ctypes.c_size_t, ctypes.c_float, vp]),
         "tc_quant_scale": (ctypes.c_int, [vp, vp, ctypes.c_size_t, vp]),
         "tc_encode_tensor_scaled": (ctypes.c_int, [vp, vp, ctypes.c_int, ctypes.c_size_t, vp, vp]),
+        "tc_encode_batch_scaled": (ctypes.c_int, [vp, ctypes.c_int, vp, vp, vp, vp]),
         "tc_commit": (ctypes.c_int, [vp, vp, vp, ctypes.c_int, vp]),
         "tc_commit_batch": (ctypes.c_int, [vp, ctypes.c_int, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                            ctypes.POINTER(ctypes.c_int), vp]),
@@ -445,6 +446,14 @@ class Context:
 
     def encode_tensor_scaled(self, src, src_dtype, n, inv_scale_dev, dst):
         self._check(self.lib.tc_encode_tensor_scaled(self.handle, _ptr(src), src_dtype, n, _ptr(inv_scale_dev), _ptr(dst)))
+
+    def encode_batch_scaled(self, srcs, ns, inv_scales_dev, dsts):
+        """Scale and quantisation of several fp16 tensors in shared launches; inv_scales_dev: len(srcs) float32 on the device."""
+        k = len(srcs)
+        a_src = (ctypes.c_void_p * k)(*[_ptr(x).value for x in srcs])
+        a_dst = (ctypes.c_void_p * k)(*[_ptr(x).value for x in dsts])
+        a_n = (ctypes.c_size_t * k)(*[int(v) for v in ns])
+        self._check(self.lib.tc_encode_batch_scaled(self.handle, k, a_src, a_n, _ptr(inv_scales_dev), a_dst))
 
     def commit(self, srs, scalars, dtype):
         out = ctypes.create_string_buffer(96)

@@ -226,9 +226,28 @@ struct AbsMaxF16 {
         if (best) atomic_max_u32(wmax, best);
     }
 };
-struct InvScaleFromAbsMax {        /* one lane: the 15-bit magnitude in *result becomes the float scale, in place */
+/* the same pass over several tensors in one launch: workgroup first[j] + g is workgroup g of tensor j */
+struct AbsMaxF16Batch {
+    static constexpr int BLOCK = AbsMaxF16::BLOCK;
+    static constexpr int PHASES = AbsMaxF16::PHASES;
+    static constexpr size_t LDS_BYTES = AbsMaxF16::LDS_BYTES;
+    const AbsMaxF16* jobs;
+    const uint32_t* first;         /* njobs + 1 */
+    uint32_t njobs;
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        uint32_t lo = 0, hi = njobs;
+        while (hi - lo > 1) {
+            uint32_t mid = (lo + hi) / 2;
+            if (first[mid] <= wg) lo = mid;
+            else hi = mid;
+        }
+        jobs[lo].phase(ph, lane, wg - first[lo], lds);
+    }
+};
+struct InvScaleFromAbsMax {        /* lane t: the 15-bit magnitude in result[t] becomes the float scale, in place */
     uint32_t* result;
-    TC_DEV void operator()(uint32_t) const {
+    TC_DEV void operator()(uint32_t t) const {
+        uint32_t* result = this->result + t;
         float amax = EncodeF16::half_to_float((uint16_t)*result);
         float inv = amax > 0.0f ? 32767.0f / amax : 0.0f;
         uint32_t bits;
@@ -1373,49 +1392,6 @@ struct GroupSumSrc {           /* out[g] = sum of in[g * group .. (g + 1) * grou
     TC_DEV void store(uint32_t g, const g1_xyzz& r) const { out[g] = r; }
 };
 
-/* Row and column sums for launches with many windows, where SIMD time matters more than depth: four rows (columns)
- * per wave, sixteen lanes each, 16 (8) buckets per lane one after the other and four halving steps; the weighted
- * sums of the 256 column sums and 128 row sums then go through WeightedBlockSum<256> and RowColFinish. */
-struct RowColSumsPacked {
-    static constexpr int BLOCK = 64;
-    static constexpr int PHASES = 6;           /* serial part, 4 halving steps, store */
-    static constexpr size_t LDS_BYTES = BLOCK * sizeof(g1_xyzz);
-    static constexpr uint32_t GROUPS = 32 + 64;
-    const g1_xyzz* bucket;      /* windows * 32768 */
-    g1_xyzz* rows;              /* windows * 256: entries 128..255 of a window are the identity */
-    g1_xyzz* cols;              /* windows * 256 */
-    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
-        g1_xyzz* buf = (g1_xyzz*)lds;
-        uint32_t w = wg / GROUPS, g = wg % GROUPS;
-        uint32_t sub = lane >> 4, j = lane & 15u;
-        const g1_xyzz* base = bucket + (uint64_t)w * 32768u;
-        if (ph == 0) {
-            xyzz_acc acc;
-            if (g < 32) {                      /* row 4 g + sub: lane takes 16 neighbouring buckets */
-                const g1_xyzz* p = base + (g * 4u + sub) * 256u + j * 16u;
-                acc = acc_from(p[0]);
-                for (int i = 1; i < 16; ++i) acc_add(acc, acc_from(p[i]));
-            } else {                           /* column 4 (g - 32) + sub: lane takes 8 of the 128 rows */
-                const g1_xyzz* p = base + ((g - 32u) * 4u + sub) + (uint64_t)(j * 8u) * 256u;
-                acc = acc_from(p[0]);
-                for (int i = 1; i < 8; ++i) acc_add(acc, acc_from(p[(uint64_t)i * 256u]));
-            }
-            buf[lane] = acc_result(acc);
-            return;
-        }
-        if (ph <= 4) {
-            uint32_t stride = 8u >> (ph - 1);
-            if (j < stride) buf[lane] = xyzz_add(buf[lane], buf[lane + stride]);
-            return;
-        }
-        if (j == 0) {
-            if (g < 32) rows[(uint64_t)w * 256 + g * 4u + sub] = buf[lane];
-            else cols[(uint64_t)w * 256 + (g - 32u) * 4u + sub] = buf[lane];
-        } else if (j == 1 && g < 32) {
-            rows[(uint64_t)w * 256 + 128 + g * 4u + sub] = xyzz_identity();
-        }
-    }
-};
 /* one lane per window: 256 (W_R - S_R) + W_C */
 struct RowColFinish {
     const g1_xyzz* w_rows;      /* sum_h (h + 1) R_h */
@@ -1431,75 +1407,155 @@ struct RowColFinish {
     }
 };
 
-/* sum_k k B_k for a window of 256 buckets seen as a 16 x 16 matrix (k = 16 h + l + 1): row and column
- * sums first (one addition per bucket and direction), then two weighted sums over 16 elements:
- *     16 sum_h h R_h + sum_l (l + 1) C_l.
- * About 3 additions per bucket instead of the 16 of a weighted scan over all 256.  A wave takes two windows:
- * 32 lanes each, 16 for the rows and 16 for the columns, so that no lane idles in the halving steps.
- * A window of 128 buckets is a 16 x 8 matrix (k = 8 h + l + 1): sixteen lanes sum a row of eight each, sixteen
- * half a column each (eight entries), one more step joins the halves, and the weights are 8 h and l + 1 -- seven
- * serial additions per lane in the first phase instead of fifteen with half the lanes idle (the row commitments of
- * the openings at the LLaMA2-7B shape: 13.5 -> 9.6 ms). */
-struct SmallWindowReduce256 {
-    static constexpr int BLOCK = 64;
-    static constexpr int PHASES = 12;
-    static constexpr size_t LDS_BYTES = 2 * BLOCK * sizeof(g1_xyzz);
-    const g1_xyzz* bucket;      /* windows * nb */
-    uint32_t nb;                /* buckets per window: 256 or 128 */
-    uint32_t n_windows;
-    g1_xyzz* out;               /* per window */
-    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
-        g1_xyzz* buf0 = (g1_xyzz*)lds;
-        g1_xyzz* buf1 = buf0 + BLOCK;
-        uint32_t win = lane >> 5, j = lane & 31u, i = lane & 15u;
-        uint32_t w = 2 * wg + win;
-        bool live = w < n_windows;
-        bool narrow = nb == 128u;
-        if (ph == 0) {
-            xyzz_acc acc = acc_identity();
-            if (live) {
-                const g1_xyzz* B = bucket + (uint64_t)w * nb;
-                uint32_t first, step, count;
-                if (narrow) {
-                    if (j < 16) { first = j * 8u; step = 1u; }                          /* row j */
-                    else { first = ((j - 16u) >> 1) + ((j - 16u) & 1u) * 64u; step = 8u; }   /* half of column (j - 16) / 2 */
-                    count = 8u;
-                } else {
-                    first = j < 16 ? j * 16u : j - 16u;                                  /* a row, or a column */
-                    step = j < 16 ? 1u : 16u;
-                    count = 16u;
-                }
-                for (uint32_t t = 0; t < count && first + t * step < nb; ++t) acc_add(acc, acc_from(B[first + t * step]));
-            }
-            (narrow ? buf0 : buf1)[lane] = acc_result(acc);
-        } else if (ph == 1) {                /* 128 buckets: the halves of a column, into the column's place in its family */
-            if (!narrow) return;
-            g1_xyzz v = buf0[lane];
-            if (j >= 16) {
-                uint32_t l = j - 16u;
-                v = l < 8u ? xyzz_add(buf0[lane - l + 2u * l], buf0[lane - l + 2u * l + 1u]) : xyzz_identity();
-            }
-            buf1[lane] = v;
-        } else if (ph <= 5) {                /* suffix sums within each family of 16 */
-            int s = ph - 2;
-            g1_xyzz* cur = (s & 1) ? buf0 : buf1;
-            g1_xyzz* nxt = (s & 1) ? buf1 : buf0;
-            uint32_t stride = 1u << s;
-            g1_xyzz v = cur[lane];
-            if (i + stride < 16u) v = xyzz_add(v, cur[lane + stride]);
-            nxt[lane] = v;
-        } else if (ph == 6) {                /* the suffix sums are in buf1 again; S_R = sum of the row sums */
-            if (j == 0) buf0[lane] = buf1[lane];
-        } else if (ph <= 10) {               /* sum of the suffix sums, in place */
-            uint32_t stride = 1u << (ph - 7);
-            if ((i & (2 * stride - 1)) == 0) buf1[lane] = xyzz_add(buf1[lane], buf1[lane + stride]);
-        } else if (j == 0 && live) {
-            xyzz_acc t = acc_from(buf1[lane]);
-            acc_add(t, acc_from(xyzz_neg(buf0[lane])));                /* sum_h h R_h */
-            for (int d = 0; d < (narrow ? 3 : 4); ++d) acc_dbl(t);
-            acc_add(t, acc_from(buf1[lane + 16]));
-            out[w] = acc_result(t);
+/* ---- many small windows: sum_k k B_k with one lane per row or column ---------------------------------------------
+ * The row problems of a batch of openings end in tens of thousands of windows of 128 (or 256) buckets.  A window
+ * is a 16 x 8 (16 x 16) matrix, k = cols h + l + 1:  sum_k k B_k = cols sum_h h R_h + sum_l (l + 1) C_l  over its row
+ * sums R_h and column sums C_l.  StridedSums: one lane per row and one per column, all rows of all windows first and
+ * the columns after them (the lanes of a wave then have equally many terms), the general addition expanded in place
+ * as in AccXyzzFast, no LDS, nothing shared between lanes; a lane that meets equal or opposite sums enters itself in
+ * a list that StridedRedo works off.  SmallWeighted: two lanes per window, the weighted sums by running sums
+ * (run += X_i, total += run, from the far end); SmallFinish: one lane per window.
+ * (Before: one wave per two windows summing through LDS with a call per product, at one wave per SIMD;
+ * the 23 552 windows of the LLaMA2-7B-shaped openings 4.6 ms.) */
+/* the sum of the terms that J.job hands lane t, to the slot it names: the loop of AccXyzzFast */
+template <class Job>
+TC_DEV void strided_sum_fast(const Job& J, uint32_t t) {
+    uint64_t first, slot;
+    uint32_t step, cnt;
+    J.job(t, first, step, cnt, slot);
+    g1_xyzz28 acc;
+    bool have = false;
+    for (uint32_t i = 0; i < cnt; ++i) {
+        g1_xyzz p = J.in[first + (uint64_t)i * step];
+        if (xyzz_is_identity(p)) continue;
+        g1_xyzz28 q = xyzz28_from(p);
+        if (!have) {
+            acc = q;
+            have = true;
+            continue;
         }
+        if (!acc_add_regular_expanded(acc, q)) {
+            J.redo_list[atomic_add_u32(J.redo_count, 1u)] = t;
+            return;
+        }
+    }
+    g1_xyzz r;
+    if (!have) {
+        r = xyzz_identity();
+    } else {
+        r.X = fp28_to_fp_outlined(acc.X); r.Y = fp28_to_fp_outlined(acc.Y);
+        r.ZZ = fp28_to_fp_outlined(acc.ZZ); r.ZZZ = fp28_to_fp_outlined(acc.ZZZ);
+    }
+    J.out[slot] = r;
+}
+/* the lanes that gave up, with the routine that settles every case */
+template <class Job>
+struct StridedRedo {
+    Job J;
+    uint32_t lanes;
+    TC_DEV void operator()(uint32_t lane) const {
+        for (uint32_t k = lane; k < *J.redo_count; k += lanes) {
+            uint64_t first, slot;
+            uint32_t step, cnt;
+            J.job(J.redo_list[k], first, step, cnt, slot);
+            xyzz_acc acc = acc_identity();
+            for (uint32_t i = 0; i < cnt; ++i) acc_add(acc, acc_from(J.in[first + (uint64_t)i * step]));
+            J.out[slot] = acc_result(acc);
+        }
+    }
+};
+struct StridedSums {
+    const g1_xyzz* in;            /* n_windows * nb buckets */
+    uint32_t nb;                  /* 128 or 256 */
+    uint32_t n_windows;
+    g1_xyzz* out;                 /* per window: 16 row sums, then nb / 16 column sums */
+    uint32_t* redo_count;         /* zero before the launch */
+    uint32_t* redo_list;          /* room for every lane */
+    TC_HD uint32_t cols() const { return nb / 16u; }
+    TC_HD uint64_t lanes() const { return (uint64_t)n_windows * (16u + cols()); }
+    /* the terms of lane t: in[first + i * step], i < cnt, and where their sum goes */
+    TC_HD void job(uint32_t t, uint64_t& first, uint32_t& step, uint32_t& cnt, uint64_t& slot) const {
+        uint32_t c = cols(), n_rows = 16u * n_windows;
+        if (t < n_rows) {
+            uint32_t w = t / 16u, h = t % 16u;
+            first = (uint64_t)w * nb + h * c; step = 1u; cnt = c;
+            slot = (uint64_t)w * (16u + c) + h;
+        } else {
+            uint32_t u = t - n_rows, w = u / c, l = u % c;
+            first = (uint64_t)w * nb + l; step = c; cnt = 16u;
+            slot = (uint64_t)w * (16u + c) + 16u + l;
+        }
+    }
+    TC_DEV void operator()(uint32_t t) const { strided_sum_fast(*this, t); }
+};
+/* The same for windows of 32768 buckets, a 128 x 256 matrix (k = 256 h + l + 1), in two levels so that the chip is
+ * full and no lane has more than sixteen terms.  Level 1, per window: 2048 lanes for the sixteen pieces of each row,
+ * 2048 for the eight pieces of each column (neighbouring lanes take neighbouring columns); level 2: 256 lanes for the
+ * rows (the upper 128 have nothing to add and write the identity that WeightedBlockSum<256> expects there), 256 for
+ * the columns.  (Before: four rows or columns per wave summed through LDS, a call per product: the 96 windows of the
+ * LLaMA2-7B-shaped build 2.27 ms.) */
+struct BigRowColSums {
+    const g1_xyzz* in;            /* level 1: windows * 32768 buckets; level 2: windows * 4096 sums of level 1 */
+    int level;
+    uint32_t n_windows;
+    g1_xyzz* out;                 /* level 1: windows * 4096; level 2: windows * 256 row sums, then windows * 256 column sums */
+    uint32_t* redo_count;
+    uint32_t* redo_list;
+    TC_HD uint64_t lanes() const { return (uint64_t)n_windows * (level == 1 ? 4096u : 512u); }
+    TC_HD void job(uint32_t t, uint64_t& first, uint32_t& step, uint32_t& cnt, uint64_t& slot) const {
+        if (level == 1) {
+            uint32_t half = 2048u * n_windows;
+            if (t < half) {                       /* row h, piece sg */
+                uint32_t w = t / 2048u, r = t % 2048u, h = r / 16u, sg = r % 16u;
+                first = (uint64_t)w * 32768u + h * 256u + sg * 16u; step = 1u; cnt = 16u;
+                slot = (uint64_t)w * 4096u + r;
+            } else {                              /* column l, piece sg */
+                uint32_t u = t - half, w = u / 2048u, r = u % 2048u, sg = r / 256u, l = r % 256u;
+                first = (uint64_t)w * 32768u + (uint64_t)sg * 16u * 256u + l; step = 256u; cnt = 16u;
+                slot = (uint64_t)w * 4096u + 2048u + l * 8u + sg;
+            }
+        } else {
+            uint32_t half = 256u * n_windows;
+            if (t < half) {
+                uint32_t w = t / 256u, h = t % 256u;
+                first = (uint64_t)w * 4096u + h * 16u; step = 1u; cnt = h < 128u ? 16u : 0u;
+                slot = t;
+            } else {
+                uint32_t u = t - half, w = u / 256u, l = u % 256u;
+                first = (uint64_t)w * 4096u + 2048u + l * 8u; step = 1u; cnt = 8u;
+                slot = (uint64_t)half + u;
+            }
+        }
+    }
+    TC_DEV void operator()(uint32_t t) const { strided_sum_fast(*this, t); }
+};
+/* lane t < n_windows: sum_h h R_h of window t; lane n_windows + w: sum_l (l + 1) C_l of window w */
+struct SmallWeighted {
+    const g1_xyzz* sums;          /* per window: 16 row sums, then `cols` column sums */
+    uint32_t cols, n_windows;
+    g1_xyzz* out;                 /* [0, n_windows): the row part, [n_windows, 2 n_windows): the column part */
+    TC_DEV void operator()(uint32_t t) const {
+        bool rows = t < n_windows;
+        uint32_t w = rows ? t : t - n_windows;
+        const g1_xyzz* X = sums + (uint64_t)w * (16u + cols) + (rows ? 0u : 16u);
+        uint32_t n = rows ? 16u : cols, last = rows ? 1u : 0u;      /* the row h = 0 has weight 0 */
+        xyzz_acc run = acc_identity(), total = acc_identity();
+        for (uint32_t i = n; i-- > last;) {
+            acc_add(run, acc_from(X[i]));
+            acc_add(total, run);
+        }
+        out[t] = acc_result(total);
+    }
+};
+struct SmallFinish {             /* cols * (row part) + (column part) */
+    const g1_xyzz* parts;
+    uint32_t cols, n_windows;
+    g1_xyzz* out;
+    TC_DEV void operator()(uint32_t w) const {
+        xyzz_acc t = acc_from(parts[w]);
+        for (uint32_t c = cols; c > 1u; c >>= 1) acc_dbl(t);
+        acc_add(t, acc_from(parts[n_windows + w]));
+        out[w] = acc_result(t);
     }
 };
 

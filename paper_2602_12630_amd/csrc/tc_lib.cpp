@@ -1230,6 +1230,8 @@ static int scan_counts(tc_ctx* ctx, const uint32_t* cnt, uint32_t n, uint32_t L,
     return TC_OK;
 }
 
+/* lanes of the bucket accumulation that are resident at once: 256 compute units x 4 SIMDs x 3 waves x 64 */
+static const uint64_t ACC_RESIDENT_LANES = 256ull * 4 * 3 * 64;
 /* from this many 128- or 256-bucket windows on (the row problems of openings), throughput matters and not depth */
 #if defined(TC_HOST_EMU)
 static const int SMALL_WINDOW_REDUCE_MIN = 8;          /* the CPU build of the tests reaches it with a handful of rows */
@@ -1243,7 +1245,19 @@ static const int ROWCOL_PACKED_WINDOWS = 8;
 static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb, g1_xyzz* wsum) {
     if ((nb == 256 || nb == 128) && W >= SMALL_WINDOW_REDUCE_MIN) {
         /* many small windows (row problems of openings): throughput matters, not depth */
-        RT((launch_coop<SmallWindowReduce256::BLOCK>(((uint32_t)W + 1) / 2, ctx->stream, SmallWindowReduce256{bucket, nb, (uint32_t)W, wsum})));
+        StridedSums S{bucket, nb, (uint32_t)W, nullptr, nullptr, nullptr};
+        uint64_t lanes = S.lanes();
+        if (lanes > 0xFFFFFFF0ull) return fail(ctx, TC_ERR_SHAPE, "too many windows in one launch");
+        WS(sums, g1_xyzz, lanes);
+        WS(parts, g1_xyzz, 2ull * (uint32_t)W);
+        WS(redo, uint32_t, lanes + 1);
+        S.out = sums; S.redo_count = redo; S.redo_list = redo + 1;
+        RT(rt::launch<64>(1, ctx->stream, Fill32{redo, 0u}));
+        RT((rt::launch_waves<64, 2>(lanes, ctx->stream, S)));
+        uint32_t redo_lanes = (uint32_t)std::min<uint64_t>(lanes, ACC_RESIDENT_LANES);
+        RT(rt::launch<64>(redo_lanes, ctx->stream, StridedRedo<StridedSums>{S, redo_lanes}));
+        RT(rt::launch<64>(2ull * (uint32_t)W, ctx->stream, SmallWeighted{sums, S.cols(), (uint32_t)W, parts}));
+        RT(rt::launch<64>((uint32_t)W, ctx->stream, SmallFinish{parts, S.cols(), (uint32_t)W, wsum}));
         return TC_OK;
     }
     if (nb == 128 || nb == 256) {
@@ -1256,8 +1270,8 @@ static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb
     }
     if (nb != 32768) return fail(ctx, TC_ERR_STATE, "unsupported bucket count");
     /* 128 x 256 bucket matrix: row / column sums, then two small weighted sums per window */
-    WS(rows, g1_xyzz, 256ull * W);
-    WS(cols, g1_xyzz, 256ull * W);
+    WS(rows, g1_xyzz, 512ull * W);          /* the row sums of all windows, then the column sums of all windows */
+    g1_xyzz* cols = rows + 256ull * W;
     if (W < ROWCOL_PACKED_WINDOWS) {
         /* few windows: depth is the cost; cooperative sums and bit-wise weights */
         typedef CoopReduce<RowColSrc> RowCol;
@@ -1273,7 +1287,21 @@ static int reduce_windows(tc_ctx* ctx, const g1_xyzz* bucket, int W, uint32_t nb
     }
     WS(w_rc, g1_xyzz, 2u * (uint32_t)W);     /* [0, W): columns, [W, 2W): rows */
     WS(s_rc, g1_xyzz, 2u * (uint32_t)W);
-    RT((launch_coop<RowColSumsPacked::BLOCK>((uint32_t)W * RowColSumsPacked::GROUPS, ctx->stream, RowColSumsPacked{bucket, rows, cols})));
+    {
+        if ((uint64_t)W * 4096u > 0xFFFFFFF0ull) return fail(ctx, TC_ERR_SHAPE, "too many windows in one launch");
+        WS(pieces, g1_xyzz, 4096ull * W);
+        WS(redo, uint32_t, 4096ull * W + 1);
+        RT(rt::launch<64>(1, ctx->stream, Fill32{redo, 0u}));
+        BigRowColSums L1{bucket, 1, (uint32_t)W, pieces, redo, redo + 1};
+        BigRowColSums L2{pieces, 2, (uint32_t)W, rows, redo, redo + 1};
+        uint32_t redo_lanes = (uint32_t)std::min<uint64_t>(L1.lanes(), ACC_RESIDENT_LANES);
+        RT((rt::launch_waves<64, 2>(L1.lanes(), ctx->stream, L1)));
+        RT(rt::launch<64>(redo_lanes, ctx->stream, StridedRedo<BigRowColSums>{L1, redo_lanes}));
+        RT(rt::launch<64>(1, ctx->stream, Fill32{redo, 0u}));
+        RT((rt::launch_waves<64, 2>(L2.lanes(), ctx->stream, L2)));
+        redo_lanes = (uint32_t)std::min<uint64_t>(L2.lanes(), ACC_RESIDENT_LANES);
+        RT(rt::launch<64>(redo_lanes, ctx->stream, StridedRedo<BigRowColSums>{L2, redo_lanes}));
+    }
     RT((launch_coop<256>(2u * (uint32_t)W, ctx->stream,
                          WeightedBlockSum<256>{cols, 256u * (uint32_t)W, w_rc, s_rc, rows, (uint32_t)W})));
     RT(rt::launch<64>((uint32_t)W, ctx->stream, RowColFinish{w_rc + W, s_rc + W, w_rc, wsum}));
@@ -1297,6 +1325,66 @@ static int launch_jobs(tc_ctx* ctx, const std::vector<F>& jobs, const std::vecto
     return TC_OK;
 }
 
+/* the scale and the quantised values of `count` fp16 tensors in five launches, whatever the count */
+extern "C" int tc_encode_batch_scaled(tc_ctx* ctx, int count, const void* const* d_src, const size_t* n, float* d_inv_scale,
+                                      void* const* d_dst) {
+    try {
+        if (!ctx) return TC_ERR_ARG;
+        if (count < 0 || (count && (!d_src || !n || !d_inv_scale || !d_dst))) return fail(ctx, TC_ERR_ARG, "null argument");
+        if ((uintptr_t)d_inv_scale & 3u) return fail(ctx, TC_ERR_ARG, "misaligned buffer");
+        for (int i = 0; i < count; ++i) {
+            if ((!d_src[i] || !d_dst[i]) && n[i]) return fail(ctx, TC_ERR_ARG, "null buffer");
+            if (((uintptr_t)d_src[i] & 1u) || ((uintptr_t)d_dst[i] & 1u)) return fail(ctx, TC_ERR_ARG, "misaligned buffer");
+            if (n[i] > 0xFFFFFFFFull) return fail(ctx, TC_ERR_SHAPE, "tensor too large");
+        }
+        if (!count) return TC_OK;
+        RT(rt::set_device(ctx->device));
+        TRY(ws_reset(ctx));
+        uint32_t* result = (uint32_t*)d_inv_scale;
+        /* workgroups per tensor: together they fill the chip, and no tensor has more than its share of atomics */
+        const uint32_t per_tensor = (uint32_t)std::max<uint64_t>(4, 2048 / (uint64_t)count);
+        std::vector<AbsMaxF16> amax;
+        std::vector<uint32_t> first(1, 0);
+        std::vector<EncodeF16x8> wide;
+        std::vector<EncodeF16> narrow;
+        std::vector<uint64_t> n_wide, n_narrow;
+        for (int i = 0; i < count; ++i) {
+            if (!n[i]) continue;
+            uint32_t groups = (uint32_t)std::min<uint64_t>(std::min<uint32_t>(per_tensor, ABSMAX_MAX_GROUPS),
+                                                           (n[i] / 8 + AbsMaxF16::BLOCK - 1) / AbsMaxF16::BLOCK);
+            if (groups == 0) groups = 1;
+            amax.push_back(AbsMaxF16{(const uint16_t*)d_src[i], (uint64_t)n[i], groups, result + i});
+            first.push_back(first.back() + groups);
+            bool aligned = (((uintptr_t)d_src[i] | (uintptr_t)d_dst[i]) & 15u) == 0;
+            size_t bulk = aligned ? n[i] / 8 : 0;
+            if (bulk) {
+                wide.push_back(EncodeF16x8{(const Words16*)d_src[i], (Words16*)d_dst[i], 0.0f, d_inv_scale + i});
+                n_wide.push_back(bulk);
+            }
+            if (n[i] > 8 * bulk) {
+                narrow.push_back(EncodeF16{(const uint16_t*)d_src[i] + 8 * bulk, (int16_t*)d_dst[i] + 8 * bulk, 0.0f, d_inv_scale + i});
+                n_narrow.push_back(n[i] - 8 * bulk);
+            }
+        }
+        RT(rt::launch<64>((uint32_t)count, ctx->stream, Fill32{result, 0u}));
+        if (!amax.empty()) {
+            WS(d_jobs, AbsMaxF16, amax.size());
+            WS(d_first, uint32_t, first.size());
+            TRY(h2d(ctx, d_jobs, amax.data(), sizeof(AbsMaxF16) * amax.size()));
+            TRY(h2d(ctx, d_first, first.data(), sizeof(uint32_t) * first.size()));
+            RT((launch_coop<AbsMaxF16Batch::BLOCK>(first.back(), ctx->stream, AbsMaxF16Batch{d_jobs, d_first, (uint32_t)amax.size()})));
+        }
+        RT(rt::launch<64>((uint32_t)count, ctx->stream, InvScaleFromAbsMax{result}));
+        TRY((launch_jobs<256>(ctx, wide, n_wide)));
+        TRY((launch_jobs<256>(ctx, narrow, n_narrow)));
+        return TC_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, TC_ERR_NOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(ctx, TC_ERR_STATE, "internal: unexpected exception");
+    }
+}
+
 /* plan of a call that may not allocate (tc_commit_static): entries per sub-run of the first pass and tiles of the
  * counting sort, chosen so that TC_STATIC_MAX_TERMS terms fit into TC_STATIC_SCRATCH_BYTES */
 static const uint32_t STATIC_L1 = 16;
@@ -1316,8 +1404,6 @@ static const uint64_t ORDERED_LANES_MIN = 64;
 #else
 static const uint64_t ORDERED_LANES_MIN = 1ull << 20;
 #endif
-/* lanes of the bucket accumulation that are resident at once: 256 compute units x 4 SIMDs x 3 waves x 64 */
-static const uint64_t ACC_RESIDENT_LANES = 256ull * 4 * 3 * 64;
 
 /* One MSM problem: result = sum_i [e(s_i)] pts[i] over n terms */
 struct MsmProblem {

@@ -365,6 +365,30 @@ def test_quant_scale_on_device(T, ctx):
             ok = np.isfinite(flat)
             assert np.array_equal(dst.cpu().numpy()[ok], ref[ok])
     assert scale[0].item() == -1.0 and scale[2].item() == -1.0        # only the one float was written
+    # all of them in shared launches (tc_encode_batch_scaled), aligned and not, an empty tensor among them
+    flats = [x.reshape(-1) for x in cases] + [np.zeros(0, np.float16)]
+    bufs = [torch.zeros(f.size + 8, dtype=torch.int16, device="cuda") for f in flats]
+    srcs = []
+    for i, (f, b) in enumerate(zip(flats, bufs)):
+        off = 3 if i % 2 else 0
+        b[off : off + f.size] = to_device(f.view(np.int16))
+        srcs.append(b[off : off + f.size])
+    dsts = [torch.full((f.size + 1,), 77, dtype=torch.int16, device="cuda") for f in flats]
+    scales = torch.full((len(flats) + 2,), -1.0, dtype=torch.float32, device="cuda")
+    ctx.encode_batch_scaled(srcs, [f.size for f in flats], scales[1:], [d[1:] if i % 3 == 1 else d for i, d in enumerate(dsts)])
+    ctx.sync()
+    got = scales.cpu().numpy()
+    assert got[0] == -1.0 and got[-1] == -1.0
+    for i, f in enumerate(flats):
+        finite = f[np.isfinite(f)]
+        want = quantize.inv_scale_for(finite) if finite.size else np.float32(0)
+        assert got[1 + i : 2 + i].view(np.uint32)[0] == np.float32(want).view(np.uint32), i
+        out = dsts[i].cpu().numpy()
+        out = out[1:] if i % 3 == 1 else out[:-1]
+        ok = np.isfinite(f)
+        ref = quantize.quantize_f16(np.where(ok, f, np.float16(0)), want)
+        assert np.array_equal(out[ok], ref[ok]), i
+        assert dsts[i][0 if i % 3 == 1 else -1].item() == 77           # nothing written outside the tensor
 
 
 def _check_tree_against_oracle(ctx, tree, otree):

@@ -659,6 +659,29 @@ def test_emulated_quant_scale(emu):
             ref = quantize.quantize_f16(np.where(np.isfinite(x), x, np.float16(0)), want)
             fin = np.isfinite(x)
             assert np.array_equal(q[fin], ref[fin])
+    # the same tensors through the launches that all of them share, at mixed alignments, an empty one among them
+    cases.append(np.zeros(0, np.float16))
+    stores = [np.zeros(x.size + 16, np.float16) for x in cases]
+    views = []
+    for i, (x, st) in enumerate(zip(cases, stores)):
+        v = st[i % 4 : i % 4 + x.size]
+        v[:] = x
+        views.append(v)
+    outs = [np.full(x.size + 9, 77, np.int16) for x in cases]
+    dsts = [o[(8 if i % 2 else 1) : (8 if i % 2 else 1) + x.size] for i, (x, o) in enumerate(zip(cases, outs))]
+    scales = np.full(len(cases) + 2, -1.0, np.float32)
+    emu.encode_batch_scaled(views, [x.size for x in cases], scales[1:], dsts)
+    assert scales[0] == -1.0 and scales[-1] == -1.0
+    for i, x in enumerate(cases):
+        fin = np.isfinite(x)
+        want = quantize.inv_scale_for(x[fin]) if fin.any() else np.float32(0)
+        assert scales[1 + i : 2 + i].view(np.uint32)[0] == np.float32(want).view(np.uint32), i
+        ref = quantize.quantize_f16(np.where(fin, x, np.float16(0)), want)
+        assert np.array_equal(dsts[i][fin], ref[fin]), i
+        lo = 8 if i % 2 else 1
+        assert (outs[i][:lo] == 77).all() and (outs[i][lo + x.size :] == 77).all()
+    with pytest.raises(T.TcError):
+        emu.encode_batch_scaled([views[0]], [1 << 33], scales[1:], [dsts[0]])
 
 
 def test_emulated_field_ops(emu):
