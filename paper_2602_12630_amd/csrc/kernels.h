@@ -833,8 +833,10 @@ struct AccAffine {
  * lane-time idle; handed out in the order of their lengths, longest first, the sub-runs of a wave are equally long.
  * perm[lane] = sub-run; its output slot stays the sub-run's own, so nothing after the accumulation changes.
  * SubrunHist: one lane per bucket (k sub-runs of a bucket with c entries: c mod k of length c / k + 1, the others of
- * length c / k).  SubrunBinStarts: one lane.  SubrunOrder: one lane per sub-run; positions inside a bin are handed out
- * by atomics, so the order inside a bin varies from run to run -- the sums do not.  The passes over the partial sums
+ * length c / k).  SubrunBinStarts: one lane.  SubrunOrder: one lane per bucket again (no search for the bucket of a
+ * sub-run; a bucket that holds most of a tensor makes its lane loop over thousands of sub-runs, which costs such an
+ * input milliseconds); positions inside a bin are handed out by atomics, so the order inside a bin varies from run to
+ * run -- the sums do not.  The passes over the partial sums
  * are ordered the same way; lstart = null stands for their last one, a lane per bucket over all that it holds. */
 constexpr uint32_t SUBRUN_BINS = 65;          /* lengths 0 .. 63, and 64 or more */
 TC_HD uint32_t subrun_bin(uint32_t len) { return len < SUBRUN_BINS - 1u ? len : SUBRUN_BINS - 1u; }
@@ -881,42 +883,55 @@ struct SubrunBinStarts {         /* longest first */
         }
     }
 };
-struct SubrunOrder {
+struct SubrunOrder {             /* one lane per bucket, which places its sub-runs one after the other */
     static constexpr int BLOCK = 256;
     static constexpr int PHASES = 4;
-    static constexpr size_t LDS_BYTES = (2 * SUBRUN_BINS + BLOCK) * sizeof(uint32_t);
+    static constexpr size_t LDS_BYTES = 2 * SUBRUN_BINS * sizeof(uint32_t);
     const uint32_t* start;
     const uint32_t* lstart;
     uint32_t nbk;
     const uint32_t* binstart;
     uint32_t* cursor;            /* zero before the launch */
     uint32_t* perm;
+    /* sub-runs of bucket b: its first slot, how many, and the entries that they share */
+    TC_DEV void bucket(uint32_t b, uint32_t& slot0, uint32_t& k, uint32_t& c) const {
+        c = start[b + 1] - start[b];
+        if (!lstart) { slot0 = b; k = 1u; return; }
+        slot0 = lstart[b];
+        k = lstart[b + 1] - slot0;
+    }
+    /* length of sub-run j of k over c entries: what subrun_bounds hands out */
+    TC_DEV static uint32_t length(uint32_t j, uint32_t k, uint32_t c) {
+        if ((c | k) < 65536u) return (j + 1u) * c / k - j * c / k;
+        return (uint32_t)((uint64_t)(j + 1) * c / k) - (uint32_t)((uint64_t)j * c / k);
+    }
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         uint32_t* cnt = (uint32_t*)lds;
         uint32_t* base = cnt + SUBRUN_BINS;
-        uint32_t* bin_of = base + SUBRUN_BINS;
-        uint32_t t = wg * (uint32_t)BLOCK + lane;
+        uint32_t b = wg * (uint32_t)BLOCK + lane;
         if (ph == 0) {
             if (lane < SUBRUN_BINS) cnt[lane] = 0;
         } else if (ph == 1) {
-            uint32_t bin = 0xFFFFFFFFu;
-            if (!lstart) {
-                if (t < nbk) bin = subrun_bin(start[t + 1] - start[t]);
-            } else if (t < lstart[nbk]) {
-                uint32_t b = find_segment(lstart, nbk, t), begin, end;
-                subrun_bounds(start, lstart, b, t, begin, end);
-                bin = subrun_bin(end - begin);
-            }
-            if (bin != 0xFFFFFFFFu) atomic_add_u32(&cnt[bin], 1u);
-            bin_of[lane] = bin;
+            if (b >= nbk) return;
+            uint32_t slot0, k, c;
+            bucket(b, slot0, k, c);
+            if (!k) return;
+            uint32_t low = c / k, more = c % k;
+            if (more) atomic_add_u32(&cnt[subrun_bin(low + 1u)], more);
+            atomic_add_u32(&cnt[subrun_bin(low)], k - more);
         } else if (ph == 2) {
             if (lane < SUBRUN_BINS) {
                 base[lane] = cnt[lane] ? binstart[lane] + atomic_add_u32(&cursor[lane], cnt[lane]) : 0u;
                 cnt[lane] = 0;
             }
         } else {
-            uint32_t bin = bin_of[lane];
-            if (bin != 0xFFFFFFFFu) perm[base[bin] + atomic_add_u32(&cnt[bin], 1u)] = t;
+            if (b >= nbk) return;
+            uint32_t slot0, k, c;
+            bucket(b, slot0, k, c);
+            for (uint32_t j = 0; j < k; ++j) {
+                uint32_t bin = subrun_bin(lstart ? length(j, k, c) : c);
+                perm[base[bin] + atomic_add_u32(&cnt[bin], 1u)] = slot0 + j;
+            }
         }
     }
 };

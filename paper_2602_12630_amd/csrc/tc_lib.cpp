@@ -1436,7 +1436,7 @@ static int order_lanes(tc_ctx* ctx, const uint32_t* start, const uint32_t* lstar
     RT(rt::launch<64>(SUBRUN_BINS, ctx->stream, Fill32{bins, 0u}));
     RT((launch_coop<SubrunHist::BLOCK>((nbk + SubrunHist::BLOCK - 1) / SubrunHist::BLOCK, ctx->stream, SubrunHist{start, lstart, nbk, bins})));
     RT(rt::launch<64>(1, ctx->stream, SubrunBinStarts{bins, bins + SUBRUN_BINS, bins + 2 * SUBRUN_BINS}));
-    RT((launch_coop<SubrunOrder::BLOCK>((uint32_t)((lanes + SubrunOrder::BLOCK - 1) / SubrunOrder::BLOCK), ctx->stream,
+    RT((launch_coop<SubrunOrder::BLOCK>((nbk + SubrunOrder::BLOCK - 1) / SubrunOrder::BLOCK, ctx->stream,
                                         SubrunOrder{start, lstart, nbk, bins + SUBRUN_BINS, bins + 2 * SUBRUN_BINS, perm})));
     *out_perm = perm;
     return TC_OK;
