@@ -834,8 +834,8 @@ struct AccAffine {
  * perm[lane] = sub-run; its output slot stays the sub-run's own, so nothing after the accumulation changes.
  * SubrunHist: one lane per bucket (k sub-runs of a bucket with c entries: c mod k of length c / k + 1, the others of
  * length c / k).  SubrunBinStarts: one lane.  SubrunOrder: one lane per bucket again (no search for the bucket of a
- * sub-run; a bucket that holds most of a tensor makes its lane loop over thousands of sub-runs, which costs such an
- * input milliseconds); positions inside a bin are handed out by atomics, so the order inside a bin varies from run to
+ * sub-run; the sub-runs of a bucket that has more than 64 of them -- one that holds most of a tensor has a million --
+ * are placed by its whole workgroup); positions inside a bin are handed out by atomics, so the order inside a bin varies from run to
  * run -- the sums do not.  The passes over the partial sums
  * are ordered the same way; lstart = null stands for their last one, a lane per bucket over all that it holds. */
 constexpr uint32_t SUBRUN_BINS = 65;          /* lengths 0 .. 63, and 64 or more */
@@ -886,7 +886,8 @@ struct SubrunBinStarts {         /* longest first */
 struct SubrunOrder {             /* one lane per bucket, which places its sub-runs one after the other */
     static constexpr int BLOCK = 256;
     static constexpr int PHASES = 4;
-    static constexpr size_t LDS_BYTES = 2 * SUBRUN_BINS * sizeof(uint32_t);
+    static constexpr size_t LDS_BYTES = (2 * SUBRUN_BINS + 1 + BLOCK) * sizeof(uint32_t);
+    static constexpr uint32_t OWN_MAX = 64;      /* a bucket with more sub-runs than this is placed by the whole workgroup */
     const uint32_t* start;
     const uint32_t* lstart;
     uint32_t nbk;
@@ -908,9 +909,12 @@ struct SubrunOrder {             /* one lane per bucket, which places its sub-ru
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         uint32_t* cnt = (uint32_t*)lds;
         uint32_t* base = cnt + SUBRUN_BINS;
+        uint32_t* n_big = base + SUBRUN_BINS;     /* buckets of this workgroup with more than OWN_MAX sub-runs ... */
+        uint32_t* big = n_big + 1;                /* ... and which (a bucket that holds most of a tensor has a million) */
         uint32_t b = wg * (uint32_t)BLOCK + lane;
         if (ph == 0) {
             if (lane < SUBRUN_BINS) cnt[lane] = 0;
+            if (lane == 0) *n_big = 0;
         } else if (ph == 1) {
             if (b >= nbk) return;
             uint32_t slot0, k, c;
@@ -919,18 +923,29 @@ struct SubrunOrder {             /* one lane per bucket, which places its sub-ru
             uint32_t low = c / k, more = c % k;
             if (more) atomic_add_u32(&cnt[subrun_bin(low + 1u)], more);
             atomic_add_u32(&cnt[subrun_bin(low)], k - more);
+            if (k > OWN_MAX) big[atomic_add_u32(n_big, 1u)] = b;
         } else if (ph == 2) {
             if (lane < SUBRUN_BINS) {
                 base[lane] = cnt[lane] ? binstart[lane] + atomic_add_u32(&cursor[lane], cnt[lane]) : 0u;
                 cnt[lane] = 0;
             }
         } else {
-            if (b >= nbk) return;
             uint32_t slot0, k, c;
-            bucket(b, slot0, k, c);
-            for (uint32_t j = 0; j < k; ++j) {
-                uint32_t bin = subrun_bin(lstart ? length(j, k, c) : c);
-                perm[base[bin] + atomic_add_u32(&cnt[bin], 1u)] = slot0 + j;
+            if (b < nbk) {
+                bucket(b, slot0, k, c);
+                if (k <= OWN_MAX) {
+                    for (uint32_t j = 0; j < k; ++j) {
+                        uint32_t bin = subrun_bin(lstart ? length(j, k, c) : c);
+                        perm[base[bin] + atomic_add_u32(&cnt[bin], 1u)] = slot0 + j;
+                    }
+                }
+            }
+            for (uint32_t q = 0; q < *n_big; ++q) {
+                bucket(big[q], slot0, k, c);
+                for (uint32_t j = lane; j < k; j += (uint32_t)BLOCK) {
+                    uint32_t bin = subrun_bin(length(j, k, c));
+                    perm[base[bin] + atomic_add_u32(&cnt[bin], 1u)] = slot0 + j;
+                }
             }
         }
     }

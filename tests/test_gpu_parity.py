@@ -239,6 +239,23 @@ def test_degenerate_bucket_loads_at_size(T, ctx):
         srs.close()
 
 
+def test_degenerate_bucket_loads_in_ordered_launches(T, ctx):
+    """The same at 2^26 entries, where the accumulation hands its sub-runs out in the order of their lengths: a
+    constant tensor (one bucket with a million sub-runs, all placed by one workgroup), and a tensor whose upper half is
+    constant and whose lower half is Gaussian (one such bucket among ordinary ones), against the oracle's closed form."""
+    shape = (8192, 8192)
+    pp = pps(shape)
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, 0)
+    try:
+        X = np.full(shape, -1234, np.int16)
+        assert ctx.commit(srs, to_device(X), T.TC_I16) == ec.g1_to_bytes(ec.mul(-1234 % R, ec.G1))
+        rng = np.random.default_rng(26)
+        X[4096:, :] = np.clip(np.rint(rng.standard_normal((4096, 8192)) * 3000.0), -32767, 32767).astype(np.int16)
+        assert ctx.commit(srs, to_device(X), T.TC_I16) == ec.g1_to_bytes(cbind.commit(pp, X, nthreads=16))
+    finally:
+        srs.close()
+
+
 @pytest.mark.parametrize("table", [False, True])
 @pytest.mark.parametrize("shape", [(64, 512), (5, 37, 100), (300, 64)])
 def test_open_by_rows_matches_oracle(T, ctx, shape, table):
