@@ -728,6 +728,89 @@ def tree_scaling(ctx, T, torch, tau):
     return out
 
 
+def other_configs(ctx, T, torch, node_srs, tau):
+    """Configurations 4 and 5 at their stated sizes, timed once each (their parity is the GPU tests' business):
+    the int8 weight matrices of all 32 LLaMA2-7B-shaped layers committed and put under one tree, and the eight
+    LLaMA2-13B-shaped requests -- quantise, build, 128 path openings each, then all 1024 paths verified in one batch."""
+    out = {}
+    # ---- config 4
+    shapes7 = tc_inputs.c4_shapes()
+    srs4 = {s: ctx.setup_from_trapdoor(tau, s, 0) for s in set(shapes7)}
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(tc_inputs.tensor_seed(3))
+    layers = tc_inputs.LLAMA7B["layers"]
+    leaves = [torch.randint(-127, 128, (s[0] * s[1],), generator=gen, device="cuda", dtype=torch.int8) for _ in range(layers) for s in shapes7]
+    leaf_srs = [srs4[s] for _ in range(layers) for s in shapes7]
+    scalars = sum(x.numel() for x in leaves)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    tree = ctx.terkle_build_tensors(node_srs, leaf_srs, leaves, [T.TC_I8] * len(leaves), (layers, 7), tc_inputs.NODE_SHAPE)
+    ms = (time.perf_counter() - t0) * 1e3
+    assert len(tree.root) == 96
+    tree.close()
+    out["c4_weights"] = {"workload": "C4: 32 layers x 7 LLaMA2-7B-shaped weight matrices, int8 uniform in [-127, 127], "
+                                     "224 commitments and the (4,4) tree over them in one tc_terkle_build",
+                         "scalars": scalars, "ms": ms, "scalars_per_s": scalars / (ms * 1e-3)}
+    del leaves, leaf_srs
+    for s in srs4.values():
+        s.close()
+    # ---- config 5
+    cfg = tc_inputs.LLAMA13B
+    shapes3 = tc_inputs.c3_shapes(cfg)
+    srs5 = {s: ctx.setup_from_trapdoor(tau, s, T.TC_SRS_SUFFIX | T.TC_SRS_OPEN_TABLE) for s in set(shapes3)}
+    vk = ctx.vk_from_trapdoor(tau)
+    grid = (cfg["layers"], 3)
+    gen.manual_seed(tc_inputs.tensor_seed(4))
+    rng = np.random.default_rng(tc_inputs.tensor_seed(4) + 999)
+    n_leaves = grid[0] * 3
+    qs = [torch.empty(shapes3[i % 3][0] * shapes3[i % 3][1], dtype=torch.int16, device="cuda") for i in range(n_leaves)]
+    scales = torch.zeros(n_leaves, dtype=torch.float32, device="cuda")
+    leaf_srs = [srs5[shapes3[i % 3]] for i in range(n_leaves)]
+    elements = sum(q.numel() for q in qs)
+    quant_ms, build_ms, open_ms = [], [], []
+    paths, roots, values, proofs = [], [], [], []
+    for _req in range(cfg["batch"]):
+        xs = [torch.randn(q.numel(), generator=gen, device="cuda", dtype=torch.float32).to(torch.float16) for q in qs]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ctx.encode_batch_scaled(xs, [x.numel() for x in xs], scales, qs)
+        ctx.sync()
+        t1 = time.perf_counter()
+        tree = ctx.terkle_build_tensors(node_srs, leaf_srs, qs, [T.TC_I16] * n_leaves, grid, tc_inputs.NODE_SHAPE)
+        t2 = time.perf_counter()
+        del xs
+        where = [(int(rng.integers(0, grid[0])), int(rng.integers(0, 3))) for _ in range(128)]
+        inner = [tuple(int(rng.integers(0, d)) for d in shapes3[l[1]]) for l in where]
+        t3 = time.perf_counter()
+        got = tree.open_batch(where, inner)
+        t4 = time.perf_counter()
+        flat = torch.stack([qs[l[0] * 3 + l[1]][i[0] * shapes3[l[1]][1] + i[1]] for l, i in zip(where, inner)])
+        values += [(int(v) % R_MODULUS).to_bytes(32, "little") for v in flat.cpu().tolist()]
+        paths += [tree.path(l, i) for l, i in zip(where, inner)]
+        roots += [tree.root] * 128
+        proofs += got
+        quant_ms.append((t1 - t0) * 1e3)
+        build_ms.append((t2 - t1) * 1e3)
+        open_ms.append((t4 - t3) * 1e3)
+        tree.close()
+    t0 = time.perf_counter()
+    ok = ctx.verify_paths_batch(vk, paths, roots, values, proofs)
+    verify_ms = (time.perf_counter() - t0) * 1e3
+    assert all(ok), "C5 openings failed verification"
+    assert len(set(roots)) == cfg["batch"]
+    med = lambda v: sorted(v)[len(v) // 2]
+    out["c5_batched_requests"] = {
+        "workload": "C5: 8 LLaMA2-13B-shaped requests, each 40 layers x {2048x5120, 2048x5120, 2048x13824} fp16 N(0,1) -> int16, "
+                    "one (4,4) tree per request, 128 random path openings per request, the 1024 paths verified in one batch",
+        "elements_per_request": elements, "requests": cfg["batch"],
+        "quantise_ms_per_request": med(quant_ms), "build_ms_per_request": med(build_ms),
+        "build_elements_per_s": elements / (med(build_ms) * 1e-3),
+        "open_128_paths_ms_per_request": med(open_ms), "verify_1024_paths_ms": verify_ms}
+    for s in srs5.values():
+        s.close()
+    return out
+
+
 def layer_selection(T, lib, with_oracle):
     """the verifier's layer selection (Problem 4.5) on synthetic benefits: library O(M L) against the oracle's O(M L^2)"""
     rng_sel = np.random.default_rng(9)
@@ -757,6 +840,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-c2", action="store_true", help="skip the single-layer step with steps in flight (sub-object c2_step)")
     ap.add_argument("--no-extras", action="store_true", help="skip the sub-objects beyond the hot path (coefficient route, layer selection, encode stream)")
+    ap.add_argument("--no-configs", action="store_true", help="skip the one-off timings of configurations 4 and 5 at their stated sizes "
+                    "(sub-objects c4_weights, c5_batched_requests; about 40 GB of device memory and 25 s)")
     ap.add_argument("--c2-steps", type=int, default=60, help="timed steps of the c2_step leg")
     ap.add_argument("--openings", type=int, default=8, help="path openings per step of the c2_step leg")
     ap.add_argument("--in-flight", type=int, default=12, help="steps in flight of the c2_step leg: each has its own host thread, "
@@ -844,6 +929,8 @@ def main():
         out["encode_stream"] = encode_stream(ctx, T, torch)
         out["layer_selection"] = layer_selection(T, lib, not args.no_cpu_baseline)
         out["coefficient_route"] = coefficient_route(ctx, T, torch, not args.no_cpu_baseline, peak)
+    if not args.no_configs:
+        out.update(other_configs(ctx, T, torch, node_srs, tau))
     if args.fig4:
         out["tree_scaling"] = tree_scaling(ctx, T, torch, tau)
     if not args.no_cpu_baseline:
