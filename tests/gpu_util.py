@@ -166,10 +166,13 @@ def check_one_point_throughout(ctx, upload, shape):
     back.close()
 
 
-def check_repeated_points(ctx, upload):
+def check_repeated_points(ctx, upload, many=512):
     """Commitments over public parameters in which most points repeat or are each other's negatives, with scalars of
     few distinct values: the bucket sums then run into doublings, sums that cancel to the identity and additions to
     the identity, the cases that the accumulation kernel's fast form of the chord rule hands to the slower routine.
+    Then the same in batches: eight int16 tensors in one call (the row and column sums of their 128 x 256 bucket
+    matrices go one lane per piece, with a list for the sums that meet equal or opposite points) and `many` int8
+    tensors in one call (that many windows of 128 buckets, a lane per row and column).
     Expected values: the C oracle's term-by-term sum over the same points.  `upload` puts a numpy array where the
     context reads it (device memory, or the array itself on the host build)."""
     import random
@@ -213,3 +216,17 @@ def check_repeated_points(ctx, upload):
         got = ctx.commit(back, upload(X), dtype)
         back.close()
         assert got == ec.g1_to_bytes(want), (dtype, X.reshape(-1)[:8])
+    for points in (mixed, same):
+        blob = b"".join(points)
+        back = ctx.srs_import(data[:56] + blob)
+        X16 = [nrng.choice(np.array([-700, -5, 5, 9, 700], np.int16), size=shape) for _ in range(8)]
+        X16[3] = np.full(shape, 9, np.int16)
+        X8 = [nrng.integers(-3, 4, size=shape).astype(np.int8) for _ in range(many)]
+        X8[1] = np.full(shape, -2, np.int8)
+        for batch, dtype in ((X16, T.TC_I16), (X8, T.TC_I8)):
+            held = [upload(X) for X in batch]
+            got = ctx.commit_batch([back] * len(batch), held, [dtype] * len(batch))
+            for j, X in enumerate(batch):
+                want, _ = cbind.msm_naive(X, blob, HOST_THREADS)
+                assert got[j] == ec.g1_to_bytes(want), (dtype, j)
+        back.close()

@@ -737,7 +737,7 @@ def test_emulated_options(emu, monkeypatch):
 
 def test_emulated_commit_over_repeated_points(emu):
     """Equal and opposite points inside the bucket sums (see check_repeated_points), on the host build."""
-    check_repeated_points(emu, lambda a: a)
+    check_repeated_points(emu, lambda a: a, many=8)
     check_one_point_throughout(emu, lambda a: a, (16, 128))
 
 
