@@ -798,8 +798,18 @@ struct AccAffine {
         }
         g1_xyzz28 acc;
         bool have = false;                                        /* acc holds a point (the sum so far is not the identity) */
+        /* the indices come four at a time (the list starts on a 16-byte boundary and its allocation ends on one): an
+         * addition lasts long enough for the other waves to push a line out of the caches, and a lane that fetches
+         * its indices one by one pulls every line of its run in again and again */
+        Words16 four = {{0u, 0u, 0u, 0u}};
+        uint32_t held = 0xFFFFFFFFu;                              /* which group of four `four` holds */
         for (uint32_t i = begin; i < end; ++i) {
-            uint32_t e = sorted[i];
+            if ((i >> 2) != held) {
+                held = i >> 2;
+                four = ((const Words16*)sorted)[held];
+            }
+            uint32_t j = i & 3u;
+            uint32_t e = j == 0u ? four.w[0] : j == 1u ? four.w[1] : j == 2u ? four.w[2] : four.w[3];
             g1_affine p = pts[e & 0x7FFFFFFFu];
             if (affine_is_identity(p)) continue;
             fp28 x2 = fp28_from_fp(p.x), y2 = fp28_from_fp(p.y);
