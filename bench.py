@@ -52,11 +52,11 @@ R_MODULUS = 0x73EDA753299D7D483339D80809A1D80553BDA402FFFE5BFEFFFFFFFF00000001  
 # HBM bytes moved by the bucket-accumulation launch of one LLaMA2-7B-shaped build (rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE of `bench.py --only-c3-build`, scaled by a 256 MiB copy kernel; runs and scale factors in
 # profiles/c3_build_hbm_traffic_pmc.txt).
-ACC_TRAFFIC_BYTES_C3 = 7.179e10
+ACC_TRAFFIC_BYTES_C3 = 5.179e10
 # Vector instructions that the same launch issues per SIMD and clock, and per mixed addition (rocprofv3 --pmc
 # SQ_INSTS_VALU / GRBM_GUI_ACTIVE of the same command: profiles/c3_build_sq_counters_pmc.txt).  A 64-lane wave takes
 # four clocks of a 16-lane SIMD, so 0.25 is the most a SIMD can issue.
-ACC_VALU_PER_SIMD_CLK_C3 = 0.248
+ACC_VALU_PER_SIMD_CLK_C3 = 0.250
 ACC_VALU_PER_ADDITION_C3 = 4834
 
 

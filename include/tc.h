@@ -174,7 +174,9 @@ int tc_ctx_field_op(tc_ctx* ctx, int op, const void* d_a, const void* d_b, size_
  * the image of the monomial SRS of Def. 4.1 under the (public, linear) change of
  * basis; committing against it gives the same group element as interpolating and
  * committing against the monomial SRS.  tau: m canonical Fr values (m * 32 bytes);
- * a trapdoor that is 0 or lies on the grid {1..d_j} is rejected with TC_ERR_RANGE. */
+ * a trapdoor that is 0 or lies on the grid {1..d_j} is rejected with TC_ERR_RANGE.
+ * Device memory: 96 bytes per point of every table, and 128 more per point of S^(0) for the copy at a stride of
+ * 128 bytes that the commitment kernels gather from (without memory for it they gather from the table itself). */
 int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, const uint32_t* shape, uint32_t flags,
                            tc_srs** out);
 void tc_srs_destroy(tc_srs* srs);

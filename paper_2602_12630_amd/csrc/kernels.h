@@ -755,6 +755,24 @@ TC_HD bool xyzz28_madd_regular(g1_xyzz28& a, const fp28& x2, const fp28& y2) {
     a.X = X3;
     return true;
 }
+/* Tables of the accumulation.  A table of 96-byte points at a stride of 96 bytes puts every second point across two
+ * of the 128-byte lines in which the second-level cache fetches: 192 bytes per point gathered at a random index.
+ * The SRS therefore keeps a copy of its first table at a stride of 128 bytes for the launches that gather from it;
+ * other tables (suffix tables, row commitments used as bases) stay at 96.  A table pointer carries its stride in
+ * bit 0 (tables start on 16-byte boundaries). */
+constexpr uint32_t PADDED_STRIDE = 128;
+TC_HD const g1_affine* tag_padded(const void* table) { return (const g1_affine*)((uintptr_t)table | 1u); }
+TC_HD const g1_affine& table_point(const g1_affine* tagged, uint32_t i) {
+    uintptr_t t = (uintptr_t)tagged;
+    uint32_t stride = (t & 1u) ? PADDED_STRIDE : (uint32_t)sizeof(g1_affine);
+    return *(const g1_affine*)((t & ~(uintptr_t)15u) + (uint64_t)i * stride);
+}
+struct PadPoints {            /* out: the points of `in` at a stride of 128 bytes */
+    const g1_affine* in;
+    uint8_t* out;
+    TC_DEV void operator()(uint32_t t) const { *(g1_affine*)(out + (uint64_t)t * PADDED_STRIDE) = in[t]; }
+};
+
 /* Lane t owns sub-run `t - lstart[b]` of bucket b: at most L entries, all of one bucket.
  * Output slot t, so the partial sums of bucket b are the slots lstart[b] .. lstart[b+1].
  * The k = ceil(c / L) sub-runs of a bucket with c entries are equally long (to within one entry), not L, L, .., rest:
@@ -788,10 +806,10 @@ struct AccAffine {
         uint32_t b = find_segment(lstart, nbk, t);
         uint32_t begin, end;
         subrun_bounds(start, lstart, b, t, begin, end);
-        const g1_affine* pts = tables[b / nbk_pp];
+        const g1_affine* pts = tables[b / nbk_pp];                /* tagged with its stride */
         if (end - begin == 1) {                                   /* a lone entry: no arithmetic */
             uint32_t e = sorted[begin];
-            g1_affine p = pts[e & 0x7FFFFFFFu];
+            g1_affine p = table_point(pts, e & 0x7FFFFFFFu);
             if (e >> 31) p.y = fp_neg(p.y);
             out[t] = xyzz_from_affine(p);
             return;
@@ -810,7 +828,7 @@ struct AccAffine {
             }
             uint32_t j = i & 3u;
             uint32_t e = j == 0u ? four.w[0] : j == 1u ? four.w[1] : j == 2u ? four.w[2] : four.w[3];
-            g1_affine p = pts[e & 0x7FFFFFFFu];
+            g1_affine p = table_point(pts, e & 0x7FFFFFFFu);
             if (affine_is_identity(p)) continue;
             fp28 x2 = fp28_from_fp(p.x), y2 = fp28_from_fp(p.y);
             if (e >> 31) y2 = fp28_sub(fp28{}, y2);
@@ -983,7 +1001,7 @@ struct AccAffineRedo {
             xyzz_acc acc = acc_identity();
             for (uint32_t i = begin; i < end; ++i) {
                 uint32_t e = sorted[i];
-                acc_madd(acc, pts[e & 0x7FFFFFFFu], (e >> 31) != 0);
+                acc_madd(acc, table_point(pts, e & 0x7FFFFFFFu), (e >> 31) != 0);
             }
             out[t] = acc_result(acc);
         }

@@ -107,6 +107,7 @@ struct tc_srs {
     g1_affine* fb[4] = {nullptr, nullptr, nullptr, nullptr};
     g1_affine* open_tab = nullptr;      /* U[kappa, t] of the leading axis (TC_SRS_OPEN_TABLE), n[0] points */
     bool shifted = false;               /* pts[0] has 2 n[0] points, the second half holding 2^8 times the first (TC_SRS_OPEN_TABLE) */
+    uint8_t* pad0 = nullptr;            /* pts[0] (both halves) once more at a stride of 128 bytes: what the accumulation gathers from */
     fr_t* axis_mem = nullptr;
     AxisTables ax[4];
 };
@@ -740,6 +741,7 @@ extern "C" void tc_srs_destroy(tc_srs* srs) {
     }
     if (srs->axis_mem) rt::dev_free(srs->axis_mem);
     if (srs->open_tab) rt::dev_free(srs->open_tab);
+    if (srs->pad0) rt::dev_free(srs->pad0);
     delete srs;
 }
 extern "C" uint64_t tc_srs_size(const tc_srs* srs, int first_axis) {
@@ -813,6 +815,23 @@ static int srs_build_shifted_half(tc_ctx* ctx, tc_srs* srs, g1_xyzz* tmp, uint64
     }
     srs->shifted = true;
     return TC_OK;
+}
+
+/* the copy of pts[0] (with its shifted half, if any) at a stride of 128 bytes; without memory for it the
+ * accumulation gathers from pts[0] itself */
+static int srs_build_padded_copy(tc_ctx* ctx, tc_srs* srs) {
+    uint64_t count = srs->n[0] * (srs->shifted ? 2 : 1);
+    if (count > 0xFFFFFFFFull) return TC_OK;
+    void* q = nullptr;
+    if (rt::dev_malloc(&q, (size_t)count * PADDED_STRIDE) != 0) return TC_OK;
+    srs->pad0 = (uint8_t*)q;
+    RT(rt::launch<256>(count, ctx->stream, PadPoints{srs->pts[0], srs->pad0}));
+    return TC_OK;
+}
+/* the table that a launch gathers the points i0 .. of S^(0) from, tagged with its stride */
+static const g1_affine* srs_gather_table(const tc_srs* srs, uint64_t i0) {
+    if (srs->pad0) return tag_padded(srs->pad0 + i0 * PADDED_STRIDE);
+    return srs->pts[0] + i0;
 }
 
 extern "C" int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, const uint32_t* shape, uint32_t flags,
@@ -913,6 +932,7 @@ extern "C" int tc_setup_from_trapdoor(tc_ctx* ctx, const uint8_t* tau, int m, co
                 }
                 if (rc == TC_OK && (flags & TC_SRS_FIXED_BASE)) rc = build_fixed_base_table(ctx, srs->pts[a], (uint32_t)na, &srs->fb[a]);
                 if (rc == TC_OK && twice) rc = srs_build_shifted_half(ctx, srs, (g1_xyzz*)tmp, std::min<uint64_t>(slab, total));
+                if (rc == TC_OK && a == 0 && !(flags & TC_SRS_MONOMIAL)) rc = srs_build_padded_copy(ctx, srs);
             }
             if (rc == TC_OK && (flags & TC_SRS_OPEN_TABLE)) {
                 /* U = the generator run once more with g(kappa) in the place of the leading axis' Lagrange values */
@@ -1109,6 +1129,7 @@ extern "C" int tc_srs_import(tc_ctx* ctx, const void* host_buf, size_t len, tc_s
                 if (e && rc == TC_OK) rc = fail_hip(ctx, e, "shifted SRS half");
                 rt::dev_free(tmp);
             }
+            if (rc == TC_OK && a == 0 && !(flags & TC_SRS_MONOMIAL)) rc = srs_build_padded_copy(ctx, srs);
         }
         if (rc == TC_OK && (flags & TC_SRS_OPEN_TABLE)) {
             void* q = nullptr;
@@ -1116,6 +1137,7 @@ extern "C" int tc_srs_import(tc_ctx* ctx, const void* host_buf, size_t len, tc_s
             srs->open_tab = (g1_affine*)q;
             if (rc == TC_OK) rc = import_points(ctx, src, total, srs->open_tab);
         }
+        if (rc == TC_OK && rt::stream_sync(ctx->stream) != 0) rc = fail(ctx, TC_ERR_HIP, "SRS import");      /* other contexts may use it next */
         if (rc != TC_OK) {
             rt::stream_sync(ctx->stream);
             tc_srs_destroy(srs);
@@ -1700,7 +1722,7 @@ extern "C" int tc_commit_batch(tc_ctx* ctx, int count, const tc_srs* const* srs,
         TRY(ws_reset(ctx));
         WS(results, g1_xyzz, (uint32_t)count);
         std::vector<MsmProblem> prob(count);
-        for (int i = 0; i < count; ++i) prob[i] = MsmProblem{srs[i]->pts[0], d_scalars[i], srs[i]->n[0]};
+        for (int i = 0; i < count; ++i) prob[i] = MsmProblem{srs_gather_table(srs[i], 0), d_scalars[i], srs[i]->n[0]};
         TRY(msm_engine_list(ctx, count, prob.data(), dtype, results));
         TRY(points_to_host(ctx, results, (uint32_t)count, out_g1));
         if (ctx->opt[TC_OPT_CHECK_LEVEL] >= 1) {
@@ -1765,7 +1787,7 @@ extern "C" int tc_commit_static(tc_ctx* ctx, const tc_srs* srs, const void* d_sc
         WS(aff, g1_affine, 1);
         int W, c;
         msm_config(ctx, dtype, srs->n[0], &W, &c);
-        MsmProblem one{srs->pts[0], d_scalars, srs->n[0]};
+        MsmProblem one{srs_gather_table(srs, 0), d_scalars, srs->n[0]};
         TRY(msm_engine_multi(ctx, 1, &one, dtype, W, c, result));
         TRY(normalize(ctx, result, 1, aff));
         RT(rt::launch<64>(1, ctx->stream, ToCanonical{aff, (uint32_t*)d_out_g1}));
@@ -1857,7 +1879,7 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
                         R.computed = true;
                         for (uint32_t k = 0; k < J.d; ++k) {
                             MsmProblem P;
-                            P.pts = srs->pts[0] + (uint64_t)k * J.inner;
+                            P.pts = srs_gather_table(srs, (uint64_t)k * J.inner);
                             P.scalars = base + (uint64_t)k * J.inner * esz;
                             P.n = J.inner;
                             P.shift = (uint32_t)srs->n[0];
@@ -2388,7 +2410,7 @@ extern "C" int tc_terkle_build(tc_ctx* ctx, const tc_tree_desc* desc, tc_tree** 
                 if (!acc) { rc = fail(ctx, TC_ERR_NOMEM, "device workspace allocation failed"); break; }
                 if (L == 0 && t->leaf_kind == TC_LEAF_TENSORS) {
                     std::vector<MsmProblem> prob(lv.n);
-                    for (uint64_t i = 0; i < lv.n; ++i) prob[i] = MsmProblem{t->leaf_srs[i]->pts[0], t->leaf_scalars[i], t->leaf_srs[i]->n[0]};
+                    for (uint64_t i = 0; i < lv.n; ++i) prob[i] = MsmProblem{srs_gather_table(t->leaf_srs[i], 0), t->leaf_scalars[i], t->leaf_srs[i]->n[0]};
                     rc = msm_engine_list(ctx, (int)lv.n, prob.data(), t->leaf_dtype.data(), acc);
                 } else {
                     const uint32_t* below = L == 0 ? t->grid : t->levels[L - 1].grid;
