@@ -352,7 +352,7 @@ struct MsmScatter {
     }
 };
 
-/* ---- MSM: count / scatter for one-digit scalars without global atomics ---------------- */
+/* ---- MSM: count / scatter without global atomics (small scalars; full-width ones in 8-bit windows) ---------------- */
 /* A workgroup owns a tile of consecutive terms of one problem.  CountTile builds the tile's
  * histogram in LDS and writes it as a row of the matrix M[problem][tile][key]; TileColumnScan turns
  * every column into exclusive offsets (and the per-key totals); ScatterTile reloads its row,
@@ -416,6 +416,17 @@ struct CountTile {
         } else if (ph == 1) {
             const TileProblem P = prob[p];
             uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
+            if (NBK == 4096 && dtype == DT_FR) {          /* full-width scalars in 8-bit windows: W digits per term */
+                for (uint64_t i = lo + lane; i < hi; i += BLOCK) {
+                    const uint32_t* v = ((const fr_plain*)P.scalars)[i].l;
+                    uint32_t carry = 0;
+                    for (int w = 0; w < W; ++w) {
+                        int32_t d = fr_window_digit(v, w, c, carry);
+                        if (d) atomic_add_u32(&hist[(uint32_t)w * nb + (uint32_t)(d < 0 ? -d : d) - 1u], 1u);
+                    }
+                }
+                return;
+            }
             tile_terms<BLOCK, NBK != 512>(P, dtype, lo, hi, lane, [&](uint64_t, int32_t v) {
                 uint32_t mag = (uint32_t)(v < 0 ? -v : v), carry = 0;
                 for (int w = 0; w < W; ++w) {
@@ -480,6 +491,20 @@ struct ScatterTile {
         } else {
             const TileProblem P = prob[p];
             uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
+            if (NBK == 4096 && dtype == DT_FR) {
+                for (uint64_t i = lo + lane; i < hi; i += BLOCK) {
+                    const uint32_t* v = ((const fr_plain*)P.scalars)[i].l;
+                    uint32_t carry = 0;
+                    for (int w = 0; w < W; ++w) {
+                        int32_t d = fr_window_digit(v, w, c, carry);
+                        if (d) {
+                            uint32_t pos = atomic_add_u32(&cur[(uint32_t)w * nb + (uint32_t)(d < 0 ? -d : d) - 1u], 1u);
+                            sorted[pos] = (uint32_t)i | (d < 0 ? 0x80000000u : 0u);
+                        }
+                    }
+                }
+                return;
+            }
             tile_terms<BLOCK, NBK != 512>(P, dtype, lo, hi, lane, [&](uint64_t i, int32_t v) {
                 uint32_t mag = (uint32_t)(v < 0 ? -v : v), carry = 0;
                 for (int w = 0; w < W; ++w) {

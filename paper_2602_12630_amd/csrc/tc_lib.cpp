@@ -1523,14 +1523,16 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     const uint32_t L2 = ctx->opt[TC_OPT_ACC_FANIN] && !ctx->static_mode ? (uint32_t)ctx->opt[TC_OPT_ACC_FANIN] : nbk <= ScanSmall::MAX_N ? 4 : 16;
 
     uint32_t max_count = 0;        /* largest bucket: fixes how many shrinking passes are needed */
-    if (dtype != TC_FR) {
-        /* small scalars (one or two digits per term): tile histograms in LDS, no global atomics */
+    if (dtype != TC_FR || (nbk_pp == 4096 && !ctx->static_mode)) {
+        /* small scalars (one or two digits per term), and full-width scalars in 8-bit windows (4096 keys per problem):
+         * tile histograms in LDS, no global atomics */
         /* tiles per problem: enough workgroups to fill the chip, but no tile so short that most of a workgroup's 1024
          * lanes (sixteen bytes of scalars per lane and step) find nothing to do -- the rows of a batch of openings,
          * tens of thousands of problems of a few thousand terms, are one tile each */
         uint64_t max_terms = 0;
         for (int p = 0; p < count; ++p) max_terms = std::max<uint64_t>(max_terms, prob[p].n);
-        uint32_t n_wg = (uint32_t)std::min<uint64_t>(256, std::max<uint64_t>(1, std::min<uint64_t>(4096 / (uint64_t)count, max_terms / 8192)));
+        const uint64_t tile_terms_min = dtype == TC_FR ? 1024 : 8192;      /* a full-width term is W digits' worth of work for its lane */
+        uint32_t n_wg = (uint32_t)std::min<uint64_t>(256, std::max<uint64_t>(1, std::min<uint64_t>(4096 / (uint64_t)count, max_terms / tile_terms_min)));
         if (ctx->static_mode) n_wg = STATIC_TILES;     /* the tile histograms are n_wg rows of the key space */
         TileProblem one;
         std::vector<TileProblem> many;
@@ -1552,6 +1554,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, CountTile<128>{d_prob, dtype, D, c, n_wg, M})));
         else if (nbk_pp == 256) RT((launch_coop<1024>(groups, ctx->stream, CountTile<256>{d_prob, dtype, D, c, n_wg, M})));
         else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, CountTile<512>{d_prob, dtype, D, c, n_wg, M})));
+        else if (nbk_pp == 4096) RT((launch_coop<1024>(groups, ctx->stream, CountTile<4096>{d_prob, dtype, D, c, n_wg, M})));
         else if (nbk_pp == 32768) RT((launch_coop<1024>(groups, ctx->stream, CountTile<32768>{d_prob, dtype, D, c, n_wg, M})));
         else return fail(ctx, TC_ERR_STATE, "internal: unsupported key count");
         RT(rt::launch<256>(nbk, ctx->stream, TileColumnScan{nbk_pp, n_wg, M, cnt}));
@@ -1560,6 +1563,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<128>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
         else if (nbk_pp == 256) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<256>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
         else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<512>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
+        else if (nbk_pp == 4096) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<4096>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
         else RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<32768>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
     } else {
         if (ctx->static_mode) return fail(ctx, TC_ERR_STATE, "internal: full-width scalars in a call that may not allocate");
