@@ -2176,18 +2176,6 @@ struct KappaWeights {          /* lane k: beta_k c_k in Montgomery form (0 for k
 struct Wide320 {
     uint32_t l[10];
 };
-TC_HD void wide_mac(Wide320& acc, const fr_t& w, uint32_t mag) {
-    uint64_t carry = 0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        uint64_t t = (uint64_t)w.l[i] * mag + acc.l[i] + carry;
-        acc.l[i] = (uint32_t)t;
-        carry = t >> 32;
-    }
-    uint64_t t = (uint64_t)acc.l[8] + carry;
-    acc.l[8] = (uint32_t)t;
-    acc.l[9] += (uint32_t)(t >> 32);
-}
 /* value mod r, keeping the Montgomery factor of the summands: lo R / R + hi R^2 / R = lo + hi 2^256 */
 TC_HD fr_t wide_reduce(const Wide320& a) {
     fr_t lo, hi, one, r2;
@@ -2206,14 +2194,47 @@ struct KappaRowDirect {        /* lane t: q[kap, t] = -(1/beta_kap) sum_{k != ka
     fr_plain* q;               /* inner values */
     TC_DEV void operator()(uint32_t t) const {
         int32_t gk = small_scalar(scalars, dtype, offset + (uint64_t)kap * inner + t);
+        /* limb by limb, without carries between the terms: a term adds less than 2^49 to a limb's sum (a 32-bit limb
+         * of the weight times a numerator of at most 17 bits), so 2^14 terms fit 64 bits; positive and negative
+         * numerators apart, every multiply-add independent of the others and no branch in the loop */
+        uint64_t sp[8], sn[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { sp[i] = 0; sn[i] = 0; }
         Wide320 pos, neg;
 #pragma unroll
         for (int i = 0; i < 10; ++i) { pos.l[i] = 0; neg.l[i] = 0; }
-        for (uint32_t k = 0; k < d; ++k) {
-            int32_t num = small_scalar(scalars, dtype, offset + (uint64_t)k * inner + t) - gk;
-            if (!num || k == kap) continue;
-            if (num > 0) wide_mac(pos, wk[k], (uint32_t)num);
-            else wide_mac(neg, wk[k], (uint32_t)(-num));
+        for (uint32_t k0 = 0; k0 < d; k0 += 8192u) {              /* sums are folded in before they could overflow */
+            uint32_t k1 = k0 + 8192u < d ? k0 + 8192u : d;
+#pragma unroll 4
+            for (uint32_t k = k0; k < k1; ++k) {
+                int32_t num = small_scalar(scalars, dtype, offset + (uint64_t)k * inner + t) - gk;
+                if (k == kap) num = 0;
+                uint32_t up = num > 0 ? (uint32_t)num : 0u, dn = num < 0 ? (uint32_t)(-num) : 0u;
+                const fr_t w = wk[k];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    sp[i] += (uint64_t)w.l[i] * up;
+                    sn[i] += (uint64_t)w.l[i] * dn;
+                }
+            }
+            uint64_t cp = 0, cn = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                cp += (sp[i] & 0xFFFFFFFFull) + pos.l[i];
+                cn += (sn[i] & 0xFFFFFFFFull) + neg.l[i];
+                pos.l[i] = (uint32_t)cp;
+                neg.l[i] = (uint32_t)cn;
+                cp = (cp >> 32) + (sp[i] >> 32);
+                cn = (cn >> 32) + (sn[i] >> 32);
+                sp[i] = 0;
+                sn[i] = 0;
+            }
+            cp += pos.l[8];
+            cn += neg.l[8];
+            pos.l[8] = (uint32_t)cp;
+            neg.l[8] = (uint32_t)cn;
+            pos.l[9] += (uint32_t)(cp >> 32);
+            neg.l[9] += (uint32_t)(cn >> 32);
         }
         fr_t acc = fr_sub(wide_reduce(pos), wide_reduce(neg));
         acc = fr_neg(fr_mul(acc, ax.beta_inv[kap]));

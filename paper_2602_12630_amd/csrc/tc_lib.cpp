@@ -1982,7 +1982,7 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
             fr_prob.push_back(B);
         } else {
             WS(q, fr_plain, J.na);
-            uint32_t chunks = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(64, 8192 / std::max<uint64_t>(J.inner, 1)));
+            uint32_t chunks = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(256, 8192 / std::max<uint64_t>(J.inner, 1)));
             chunks = std::min<uint32_t>(chunks, J.d);
             WS(part, fr_t, (uint64_t)chunks * J.inner);
             j_qr.push_back(QuotientRows{sc, dt, J.offset, J.d, J.kap, J.inner, srs->ax[J.axis], q});
