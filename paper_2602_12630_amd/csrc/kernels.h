@@ -1509,8 +1509,11 @@ TC_DEV void strided_sum_fast(const Job& J, uint32_t t) {
     g1_xyzz28 acc;
     bool have = false;
     for (uint32_t i = 0; i < cnt; ++i) {
-        g1_xyzz p = J.in[first + (uint64_t)i * step];
-        if (xyzz_is_identity(p)) continue;
+        const g1_xyzz* at = J.in + (first + (uint64_t)i * step);
+        /* four fifths of the 32768 buckets of a quantised activation are empty (its fp16 values are a coarse grid
+         * away from zero): ZZ alone says so, a quarter of the point's bytes */
+        if (fe_is_zero(at->ZZ)) continue;
+        g1_xyzz p = *at;
         g1_xyzz28 q = xyzz28_from(p);
         if (!have) {
             acc = q;
@@ -1586,23 +1589,31 @@ struct BigRowColSums {
     uint32_t* redo_list;
     TC_HD uint64_t lanes() const { return (uint64_t)n_windows * (level == 1 ? 4096u : 512u); }
     TC_HD void job(uint32_t t, uint64_t& first, uint32_t& step, uint32_t& cnt, uint64_t& slot) const {
+        /* Lanes are numbered with the small magnitudes first, over all windows: the buckets of a quantised activation
+         * are all full near zero and mostly empty further out (its fp16 values thin out), so a few lanes per window have
+         * sixteen sums to add and most have none -- in window order those few chains started all through the launch,
+         * one batch of resident waves after the other (1.2 ms); at its head they run side by side. */
         if (level == 1) {
-            uint32_t half = 2048u * n_windows;
-            if (t < half) {                       /* row h, piece sg */
-                uint32_t w = t / 2048u, r = t % 2048u, h = r / 16u, sg = r % 16u;
+            /* the rows 0 .. 15 of all windows, the columns' pieces over those rows, the other rows, the other pieces */
+            const uint32_t r0 = 16u * 16u * n_windows, c0 = 256u * n_windows, r1 = 112u * 16u * n_windows;
+            bool row = t < r0 || (t >= r0 + c0 && t < r0 + c0 + r1);
+            if (row) {                            /* row h, piece sg: (h * windows + w) * 16 + sg within its class */
+                uint32_t u = t < r0 ? t : t - r0 - c0, h0 = t < r0 ? 0u : 16u;
+                uint32_t sg = u % 16u, hw = u / 16u, w = hw % n_windows, h = h0 + hw / n_windows;
                 first = (uint64_t)w * 32768u + h * 256u + sg * 16u; step = 1u; cnt = 16u;
-                slot = (uint64_t)w * 4096u + r;
-            } else {                              /* column l, piece sg */
-                uint32_t u = t - half, w = u / 2048u, r = u % 2048u, sg = r / 256u, l = r % 256u;
+                slot = (uint64_t)w * 4096u + h * 16u + sg;
+            } else {                              /* column l, piece sg: (sg * windows + w) * 256 + l within its class */
+                uint32_t u = t < r0 + c0 ? t - r0 : t - r0 - c0 - r1, s0 = t < r0 + c0 ? 0u : 1u;
+                uint32_t l = u % 256u, sw = u / 256u, w = sw % n_windows, sg = s0 + sw / n_windows;
                 first = (uint64_t)w * 32768u + (uint64_t)sg * 16u * 256u + l; step = 256u; cnt = 16u;
                 slot = (uint64_t)w * 4096u + 2048u + l * 8u + sg;
             }
         } else {
             uint32_t half = 256u * n_windows;
-            if (t < half) {
-                uint32_t w = t / 256u, h = t % 256u;
+            if (t < half) {                       /* row h: t = h * windows + w */
+                uint32_t w = t % n_windows, h = t / n_windows;
                 first = (uint64_t)w * 4096u + h * 16u; step = 1u; cnt = h < 128u ? 16u : 0u;
-                slot = t;
+                slot = (uint64_t)w * 256u + h;
             } else {
                 uint32_t u = t - half, w = u / 256u, l = u % 256u;
                 first = (uint64_t)w * 4096u + 2048u + l * 8u; step = 1u; cnt = 8u;
