@@ -22,8 +22,9 @@ namespace tc {
 enum { DT_I8 = 1, DT_I16 = 2, DT_FR = 3, DT_F16 = 4,
        DT_DIFF8 = 5, DT_DIFF16 = 6, /* internal: difference of two int8 / int16 arrays, two 9-bit signed digits */
        DT_SPLIT16 = 7, /* internal: an int16 array as two 8-bit signed digits (problems too short for 32768 buckets) */
-       DT_SPLIT16M = 8 /* internal: the same two digits sharing ONE window of 128 buckets: the high digit of term i takes
-                          the point i + shift of the table, which holds 2^8 times the point i */ };
+       DT_SPLIT16M = 8, /* internal: the same two digits sharing ONE window of 128 buckets: the high digit of term i takes
+                          the point i + shift of the table, which holds 2^8 times the point i */
+       DT_FR128 = 9 /* internal: canonical Fr values below 2^128 (scalars split with the endomorphism): 17 windows of 8 bits */ };
 
 struct alignas(16) fr_plain {           /* canonical (non-Montgomery) Fr value, 8 limbs */
     uint32_t l[8];
@@ -416,7 +417,7 @@ struct CountTile {
         } else if (ph == 1) {
             const TileProblem P = prob[p];
             uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
-            if (NBK == 4096 && dtype == DT_FR) {          /* full-width scalars in 8-bit windows: W digits per term */
+            if ((NBK == 4096 && dtype == DT_FR) || (NBK == 2176 && dtype == DT_FR128)) {          /* full-width (or half-width) scalars in 8-bit windows: W digits per term */
                 for (uint64_t i = lo + lane; i < hi; i += BLOCK) {
                     const uint32_t* v = ((const fr_plain*)P.scalars)[i].l;
                     uint32_t carry = 0;
@@ -491,7 +492,7 @@ struct ScatterTile {
         } else {
             const TileProblem P = prob[p];
             uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
-            if (NBK == 4096 && dtype == DT_FR) {
+            if ((NBK == 4096 && dtype == DT_FR) || (NBK == 2176 && dtype == DT_FR128)) {
                 for (uint64_t i = lo + lane; i < hi; i += BLOCK) {
                     const uint32_t* v = ((const fr_plain*)P.scalars)[i].l;
                     uint32_t carry = 0;
@@ -2252,6 +2253,55 @@ struct KappaRowDirect {        /* lane t: q[kap, t] = -(1/beta_kap) sum_{k != ka
         fr_t plain = fe_to_plain(acc);
 #pragma unroll
         for (int i = 0; i < 8; ++i) q[t].l[i] = plain.l[i];
+    }
+};
+/* ---- halving the scalars of a short full-width problem with the curve endomorphism -------------------------------
+ * (x, y) -> (beta x, y) multiplies a point of the group by lambda, a root of X^2 + X + 1 mod r of 128 bits.  With
+ * k = k1 + k2 lambda, 0 <= k1 < lambda and k2 < 2^128 (k < r < lambda^2 + lambda + 1), the term [k] P becomes
+ * [k1] P + [k2] (beta x, y): twice the terms, half the windows, and -- what it is done for -- half the chain of
+ * doublings that combines the windows of a problem, which two waves walk alone at the end of a batch of openings. */
+TC_HD void glv_split128(const uint32_t k[8], uint32_t k1[4], uint32_t k2[4]) {
+    const uint64_t lam_lo = (uint64_t)GLV_LAMBDA[0] | ((uint64_t)GLV_LAMBDA[1] << 32);
+    const uint64_t lam_hi = (uint64_t)GLV_LAMBDA[2] | ((uint64_t)GLV_LAMBDA[3] << 32);
+    /* the upper half of k is below 2^127 <= lambda (k < r < 2^255): the long division starts with it as the remainder */
+    uint64_t r_lo = (uint64_t)k[4] | ((uint64_t)k[5] << 32), r_hi = (uint64_t)k[6] | ((uint64_t)k[7] << 32), q_lo = 0, q_hi = 0;
+    for (int i = 127; i >= 0; --i) {
+        bool top = (r_hi >> 63) != 0;
+        r_hi = (r_hi << 1) | (r_lo >> 63);
+        r_lo = (r_lo << 1) | (uint64_t)((k[i >> 5] >> (i & 31)) & 1u);
+        if (top || r_hi > lam_hi || (r_hi == lam_hi && r_lo >= lam_lo)) {
+            uint64_t borrow = r_lo < lam_lo ? 1u : 0u;      /* with `top` set the value is 2^128 + r, still >= lambda */
+            r_lo -= lam_lo;
+            r_hi -= lam_hi + borrow;
+            if (i < 64) q_lo |= 1ull << i;
+            else q_hi |= 1ull << (i - 64);
+        }
+    }
+    k1[0] = (uint32_t)r_lo; k1[1] = (uint32_t)(r_lo >> 32); k1[2] = (uint32_t)r_hi; k1[3] = (uint32_t)(r_hi >> 32);
+    k2[0] = (uint32_t)q_lo; k2[1] = (uint32_t)(q_lo >> 32); k2[2] = (uint32_t)q_hi; k2[3] = (uint32_t)(q_hi >> 32);
+}
+struct GlvExpand {           /* lane t: term t of the problem -> terms t and n + t of the expanded one */
+    const g1_affine* pts;
+    const fr_plain* k;
+    uint64_t n;
+    g1_affine* pts2;         /* 2 n points */
+    fr_plain* k2;            /* 2 n scalars below 2^128 */
+    TC_DEV void operator()(uint32_t t) const {
+        g1_affine p = pts[t];
+        pts2[t] = p;
+        if (!affine_is_identity(p)) {
+            fp_t beta;
+#pragma unroll
+            for (int i = 0; i < 12; ++i) beta.l[i] = GLV_BETA[i];
+            p.x = fp_mul(p.x, beta);
+        }
+        pts2[n + t] = p;
+        fr_plain lo, hi;
+        glv_split128(k[t].l, lo.l, hi.l);
+#pragma unroll
+        for (int i = 4; i < 8; ++i) { lo.l[i] = 0; hi.l[i] = 0; }
+        k2[t] = lo;
+        k2[n + t] = hi;
     }
 };
 /* Many small jobs of one kind in one launch: job j owns the lanes first[j] .. first[j + 1] and runs its own

@@ -1443,6 +1443,7 @@ static void msm_config(const tc_ctx* ctx, int dtype, uint64_t n, int* W, int* c)
     else if (dtype == DT_DIFF8 || dtype == DT_DIFF16) { *W = 2; *c = 9; }
     else if (dtype == DT_SPLIT16) { *W = 2; *c = 8; }
     else if (dtype == DT_SPLIT16M) { *W = 1; *c = 8; }
+    else if (dtype == DT_FR128) { *W = 17; *c = 8; }
     else {
         *c = ctx->opt[TC_OPT_FR_WINDOW] ? (int)ctx->opt[TC_OPT_FR_WINDOW] : n >= 32768 ? 16 : 8;
         *W = 256 / *c;
@@ -1523,7 +1524,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     const uint32_t L2 = ctx->opt[TC_OPT_ACC_FANIN] && !ctx->static_mode ? (uint32_t)ctx->opt[TC_OPT_ACC_FANIN] : nbk <= ScanSmall::MAX_N ? 4 : 16;
 
     uint32_t max_count = 0;        /* largest bucket: fixes how many shrinking passes are needed */
-    if (dtype != TC_FR || (nbk_pp == 4096 && !ctx->static_mode)) {
+    if ((dtype != TC_FR && dtype != DT_FR128) || ((nbk_pp == 4096 || nbk_pp == 2176) && !ctx->static_mode)) {
         /* small scalars (one or two digits per term), and full-width scalars in 8-bit windows (4096 keys per problem):
          * tile histograms in LDS, no global atomics */
         /* tiles per problem: enough workgroups to fill the chip, but no tile so short that most of a workgroup's 1024
@@ -1531,7 +1532,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
          * tens of thousands of problems of a few thousand terms, are one tile each */
         uint64_t max_terms = 0;
         for (int p = 0; p < count; ++p) max_terms = std::max<uint64_t>(max_terms, prob[p].n);
-        const uint64_t tile_terms_min = dtype == TC_FR ? 1024 : 8192;      /* a full-width term is W digits' worth of work for its lane */
+        const uint64_t tile_terms_min = (dtype == TC_FR || dtype == DT_FR128) ? 1024 : 8192;      /* a full-width term is W digits' worth of work for its lane */
         uint32_t n_wg = (uint32_t)std::min<uint64_t>(256, std::max<uint64_t>(1, std::min<uint64_t>(4096 / (uint64_t)count, max_terms / tile_terms_min)));
         if (ctx->static_mode) n_wg = STATIC_TILES;     /* the tile histograms are n_wg rows of the key space */
         TileProblem one;
@@ -1555,6 +1556,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         else if (nbk_pp == 256) RT((launch_coop<1024>(groups, ctx->stream, CountTile<256>{d_prob, dtype, D, c, n_wg, M})));
         else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, CountTile<512>{d_prob, dtype, D, c, n_wg, M})));
         else if (nbk_pp == 4096) RT((launch_coop<1024>(groups, ctx->stream, CountTile<4096>{d_prob, dtype, D, c, n_wg, M})));
+        else if (nbk_pp == 2176) RT((launch_coop<1024>(groups, ctx->stream, CountTile<2176>{d_prob, dtype, D, c, n_wg, M})));
         else if (nbk_pp == 32768) RT((launch_coop<1024>(groups, ctx->stream, CountTile<32768>{d_prob, dtype, D, c, n_wg, M})));
         else return fail(ctx, TC_ERR_STATE, "internal: unsupported key count");
         RT(rt::launch<256>(nbk, ctx->stream, TileColumnScan{nbk_pp, n_wg, M, cnt}));
@@ -1564,6 +1566,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         else if (nbk_pp == 256) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<256>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
         else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<512>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
         else if (nbk_pp == 4096) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<4096>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
+        else if (nbk_pp == 2176) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<2176>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
         else RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<32768>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
     } else {
         if (ctx->static_mode) return fail(ctx, TC_ERR_STATE, "internal: full-width scalars in a call that may not allocate");
@@ -1829,6 +1832,8 @@ struct OpenSpec {
  *     pi_1 = sum_(k != kap) c_k A_k - sum_t T[kap,t] U[kap,t] + sum_t q[kap,t] S[kap,t],    c_k = 1 / (zeta_k - zeta_kap),
  * where the row commitments A_k = sum_t T[k,t] S[k,t] do not depend on the position: they are computed once per
  * tensor of the batch and kept in the caller's slot for later calls. */
+/* full-width problems of fewer terms than this take 8-bit windows; those have their scalars halved (see below) */
+static const uint64_t GLV_MAX_TERMS = 32768;
 static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xyzz* pi, fr_plain* y) {
     struct AxisJob {
         int open, axis;
@@ -2002,15 +2007,37 @@ static int open_device_batch(tc_ctx* ctx, int count, const OpenSpec* spec, g1_xy
     TRY((launch_jobs<128>(ctx, j_qr, n_qr)));
     TRY((launch_jobs<128>(ctx, j_qkp, n_qkp)));
     TRY((launch_jobs<128>(ctx, j_qkr, n_qkr)));
+    /* The short ones (8-bit windows) get their scalars halved with the endomorphism: twice the terms, 17 windows instead
+     * of 32, and half the chain of doublings that combines the windows -- 248 doublings that two waves walk alone at
+     * the end of the batch (64 openings of the LLaMA2-7B-shaped forward: 2.9 -> 1.5 ms).  The long ones (16-bit
+     * windows, 32768 terms or more) stay as they are. */
+    std::vector<int> fr_dtype(fr_prob.size(), TC_FR);
+    {
+        std::vector<GlvExpand> j_glv;
+        std::vector<uint64_t> n_glv;
+        for (size_t i = 0; i < fr_prob.size(); ++i) {
+            MsmProblem& P = fr_prob[i];
+            if (P.n == 0 || P.n >= GLV_MAX_TERMS) continue;
+            WS(pts2, g1_affine, 2 * P.n);
+            WS(k2, fr_plain, 2 * P.n);
+            j_glv.push_back(GlvExpand{P.pts, (const fr_plain*)P.scalars, P.n, pts2, k2});
+            n_glv.push_back(P.n);
+            P.pts = pts2;
+            P.scalars = k2;
+            P.n *= 2;
+            fr_dtype[i] = DT_FR128;
+        }
+        TRY((launch_jobs<64>(ctx, j_glv, n_glv)));
+    }
     /* sort the full-width problems by window plan so that equal plans are neighbours and share launches */
     std::vector<int> order(fr_prob.size());
     for (size_t i = 0; i < order.size(); ++i) order[i] = (int)i;
-    std::stable_sort(order.begin(), order.end(), [&](int x, int z) { return (fr_prob[x].n >= 32768) < (fr_prob[z].n >= 32768); });
+    std::stable_sort(order.begin(), order.end(), [&](int x, int z) { return (fr_dtype[x] != DT_FR128) < (fr_dtype[z] != DT_FR128); });
     std::vector<MsmProblem> sorted_prob(fr_prob.size());
-    std::vector<int> fr_dtype(fr_prob.size(), TC_FR);
-    for (size_t i = 0; i < order.size(); ++i) sorted_prob[i] = fr_prob[order[i]];
+    std::vector<int> sorted_dtype(fr_prob.size(), TC_FR);
+    for (size_t i = 0; i < order.size(); ++i) { sorted_prob[i] = fr_prob[order[i]]; sorted_dtype[i] = fr_dtype[order[i]]; }
     WS(res_sorted, g1_xyzz, fr_prob.size());
-    TRY(msm_engine_list(ctx, (int)sorted_prob.size(), sorted_prob.data(), fr_dtype.data(), res_sorted));
+    TRY(msm_engine_list(ctx, (int)sorted_prob.size(), sorted_prob.data(), sorted_dtype.data(), res_sorted));
     std::vector<int32_t> where(fr_prob.size());           /* problem -> its place in the sorted results */
     for (size_t i = 0; i < order.size(); ++i) where[order[i]] = (int32_t)i;
     std::vector<CollectResult> j_out;
@@ -2067,23 +2094,7 @@ extern "C" int tc_open(tc_ctx* ctx, const tc_srs* srs, const void* d_scalars, in
 /* Ver                                                                                     */
 /* ======================================================================================= */
 /* k = k2 * lambda + k1 with 0 <= k1 < lambda < 2^128 (k < r < lambda^2 + lambda + 1, so k2 < 2^128) */
-static void glv_split(const uint32_t k[8], uint32_t k1[4], uint32_t k2[4]) {
-    typedef unsigned __int128 u128;
-    u128 lam = 0, rem = 0, q = 0;
-    for (int i = 3; i >= 0; --i) lam = (lam << 32) | GLV_LAMBDA[i];
-    for (int i = 255; i >= 0; --i) {
-        bool top = (rem >> 127) & 1;
-        rem = (rem << 1) | ((k[i >> 5] >> (i & 31)) & 1u);
-        if (top || rem >= lam) {
-            rem -= lam;                      /* when `top` is set the true value is 2^128 + rem, still >= lambda */
-            if (i < 128) q |= (u128)1 << i;
-        }
-    }
-    for (int i = 0; i < 4; ++i) {
-        k1[i] = (uint32_t)(rem >> (32 * i));
-        k2[i] = (uint32_t)(q >> (32 * i));
-    }
-}
+static void glv_split(const uint32_t k[8], uint32_t k1[4], uint32_t k2[4]) { glv_split128(k, k1, k2); }
 /* k = tau_i - (kappa + 1) mod r, split */
 static void step_scalar(const tc_vk* vk, int i, uint32_t kappa, uint32_t k1[4], uint32_t k2[4]) {
     uint32_t w[8];
