@@ -807,13 +807,9 @@ struct PadPoints {            /* out: the points of `in` at a stride of 128 byte
 TC_HD void subrun_bounds(const uint32_t* start, const uint32_t* lstart, uint32_t b, uint32_t t, uint32_t& begin, uint32_t& end) {
     uint32_t s0 = start[b], c = start[b + 1] - s0;
     uint32_t l0 = lstart[b], k = lstart[b + 1] - l0, j = t - l0;
-    if ((c | k) < 65536u) {                /* the usual case, without 64-bit divisions */
-        begin = s0 + j * c / k;
-        end = s0 + (j + 1u) * c / k;
-    } else {
-        begin = s0 + (uint32_t)((uint64_t)j * c / k);
-        end = s0 + (uint32_t)((uint64_t)(j + 1) * c / k);
-    }
+    uint32_t low = c / k, more = c - low * k;          /* the first `more` sub-runs hold one entry more than the others */
+    begin = s0 + j * low + (j < more ? j : more);
+    end = begin + low + (j < more ? 1u : 0u);
 }
 struct AccAffine {
     const g1_affine* const* tables;   /* SRS table of problem p; bucket b belongs to problem b / nbk_pp */
@@ -955,11 +951,6 @@ struct SubrunOrder {             /* one lane per bucket, which places its sub-ru
         slot0 = lstart[b];
         k = lstart[b + 1] - slot0;
     }
-    /* length of sub-run j of k over c entries: what subrun_bounds hands out */
-    TC_DEV static uint32_t length(uint32_t j, uint32_t k, uint32_t c) {
-        if ((c | k) < 65536u) return (j + 1u) * c / k - j * c / k;
-        return (uint32_t)((uint64_t)(j + 1) * c / k) - (uint32_t)((uint64_t)j * c / k);
-    }
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         uint32_t* cnt = (uint32_t*)lds;
         uint32_t* base = cnt + SUBRUN_BINS;
@@ -987,17 +978,19 @@ struct SubrunOrder {             /* one lane per bucket, which places its sub-ru
             uint32_t slot0, k, c;
             if (b < nbk) {
                 bucket(b, slot0, k, c);
-                if (k <= OWN_MAX) {
+                if (k && k <= OWN_MAX) {
+                    uint32_t low = lstart ? c / k : c, more = lstart ? c - low * k : 0u;
                     for (uint32_t j = 0; j < k; ++j) {
-                        uint32_t bin = subrun_bin(lstart ? length(j, k, c) : c);
+                        uint32_t bin = subrun_bin(low + (j < more ? 1u : 0u));
                         perm[base[bin] + atomic_add_u32(&cnt[bin], 1u)] = slot0 + j;
                     }
                 }
             }
             for (uint32_t q = 0; q < *n_big; ++q) {
                 bucket(big[q], slot0, k, c);
+                uint32_t low = c / k, more = c - low * k;
                 for (uint32_t j = lane; j < k; j += (uint32_t)BLOCK) {
-                    uint32_t bin = subrun_bin(length(j, k, c));
+                    uint32_t bin = subrun_bin(low + (j < more ? 1u : 0u));
                     perm[base[bin] + atomic_add_u32(&cnt[bin], 1u)] = slot0 + j;
                 }
             }
