@@ -398,9 +398,9 @@ TC_DEV void tile_terms(const TileProblem& P, int dtype, uint64_t lo, uint64_t hi
     }
     for (uint64_t i = rest + lane; i < hi; i += BLOCK) each(i, tile_value(P, dtype, i));
 }
-template <int NBK>            /* keys per problem = windows * buckets per window */
+template <int NBK, int LANES = 1024>            /* keys per problem = windows * buckets per window; lanes of a workgroup */
 struct CountTile {
-    static constexpr int BLOCK = 1024;
+    static constexpr int BLOCK = LANES;
     static constexpr int PHASES = 3;
     static constexpr size_t LDS_BYTES = NBK * sizeof(uint32_t);
     const TileProblem* prob;
@@ -469,9 +469,9 @@ struct TileColumnScan {       /* lane = (problem, key) */
         cnt[t] = off;
     }
 };
-template <int NBK>
+template <int NBK, int LANES = 1024>
 struct ScatterTile {
-    static constexpr int BLOCK = 1024;
+    static constexpr int BLOCK = LANES;
     static constexpr int PHASES = 2;
     static constexpr size_t LDS_BYTES = NBK * sizeof(uint32_t);
     const TileProblem* prob;
