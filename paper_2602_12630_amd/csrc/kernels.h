@@ -256,6 +256,14 @@ struct InvScaleFromAbsMax {        /* lane t: the 15-bit magnitude in result[t] 
         *result = bits;
     }
 };
+/* the same with several pieces per lane, for a launch that many tensors share (a lane first has to find its tensor) */
+struct EncodeF16x8Strided {
+    EncodeF16x8 one;
+    uint32_t pieces, lanes;
+    TC_DEV void operator()(uint32_t t) const {
+        for (uint32_t i = t; i < pieces; i += lanes) one(i);
+    }
+};
 struct Copy128 {
     const Words16* src;
     Words16* dst;

@@ -1367,7 +1367,7 @@ extern "C" int tc_encode_batch_scaled(tc_ctx* ctx, int count, const void* const*
         const uint32_t per_tensor = (uint32_t)std::max<uint64_t>(4, 2048 / (uint64_t)count);
         std::vector<AbsMaxF16> amax;
         std::vector<uint32_t> first(1, 0);
-        std::vector<EncodeF16x8> wide;
+        std::vector<EncodeF16x8Strided> wide;
         std::vector<EncodeF16> narrow;
         std::vector<uint64_t> n_wide, n_narrow;
         for (int i = 0; i < count; ++i) {
@@ -1380,8 +1380,9 @@ extern "C" int tc_encode_batch_scaled(tc_ctx* ctx, int count, const void* const*
             bool aligned = (((uintptr_t)d_src[i] | (uintptr_t)d_dst[i]) & 15u) == 0;
             size_t bulk = aligned ? n[i] / 8 : 0;
             if (bulk) {
-                wide.push_back(EncodeF16x8{(const Words16*)d_src[i], (Words16*)d_dst[i], 0.0f, d_inv_scale + i});
-                n_wide.push_back(bulk);
+                uint32_t lanes = (uint32_t)((bulk + 7) / 8);          /* eight 16-byte pieces per lane */
+                wide.push_back(EncodeF16x8Strided{EncodeF16x8{(const Words16*)d_src[i], (Words16*)d_dst[i], 0.0f, d_inv_scale + i}, (uint32_t)bulk, lanes});
+                n_wide.push_back(lanes);
             }
             if (n[i] > 8 * bulk) {
                 narrow.push_back(EncodeF16{(const uint16_t*)d_src[i] + 8 * bulk, (int16_t*)d_dst[i] + 8 * bulk, 0.0f, d_inv_scale + i});
