@@ -530,6 +530,213 @@ struct ScatterTile {
     }
 };
 
+/* ---- counting sort of 16-bit magnitudes in two levels, tiles sorted in LDS ------------
+ * ScatterTile<32768> sends every 4-byte entry to a memory line of its own: a tile's share of a bucket is a few
+ * entries, no cache holds the 32768 open lines of every workgroup, and memory writes a whole sector per entry
+ * (3.3 ms for the 3.1e8 entries of the LLaMA2-7B-shaped forward).  Sorting by the upper eight bits of the key
+ * (magnitude - 1) first and by the lower seven afterwards keeps the open lines few, but as long as every lane sends
+ * its own 4-byte write each pass is bound by the L2's one request per channel and clock (1.3 ms).  So both passes
+ * sort a tile of SORT_TILE entries in LDS first -- rank of every entry among those of its key from an LDS atomic,
+ * prefix sums of the tile's histogram, entries placed in key order -- and write it out as runs: neighbouring lanes
+ * write neighbouring words.  On the way from the first pass to the second an entry is one word: bits 0..23 index,
+ * 24..30 key mod 128, 31 sign; hence no more than 2^24 terms per problem. */
+constexpr uint32_t SORT_BINS = 256;          /* bins per problem (upper key bits) */
+constexpr uint32_t SORT_BIN_KEYS = 128;      /* keys per bin (lower key bits) */
+#if defined(TC_HOST_EMU)
+constexpr uint32_t SORT_TILE = 64;           /* the CPU build of the tests meets several tiles per bin at its sizes */
+#else
+constexpr uint32_t SORT_TILE = 8192;         /* entries a workgroup sorts in LDS */
+#endif
+constexpr uint64_t SORT_PACKED_MAX_TERMS = 1ull << 24;
+constexpr uint32_t SORT_NO_RANK = 0xFFFFu;
+
+/* largest b with off[b] <= j, off[0] = 0 non-decreasing, n a power of two */
+TC_HD uint32_t sort_owner(const uint32_t* off, uint32_t n, uint32_t j) {
+    uint32_t b = 0;
+    for (uint32_t step = n >> 1; step; step >>= 1)
+        if (off[b + step] <= j) b += step;
+    return b;
+}
+/* off[k] = hist[0] + .. + hist[k - 1] for k <= n, by the first n lanes: every lane adds up its own prefix */
+TC_DEV void sort_prefix(const uint32_t* hist, uint32_t n, uint32_t lane, uint32_t* off) {
+    if (lane >= n) return;
+    uint32_t at = 0;
+    for (uint32_t k = 0; k < lane; ++k) at += hist[k];
+    off[lane] = at;
+    if (lane == n - 1) off[n] = at + hist[lane];
+}
+struct CountBins {             /* workgroup = (problem, tile): terms per bin */
+    static constexpr int BLOCK = 512;
+    static constexpr int PHASES = 3;
+    static constexpr size_t LDS_BYTES = SORT_BINS * sizeof(uint32_t);
+    const TileProblem* prob;
+    uint32_t n_wg;
+    uint32_t* M;               /* problems * n_wg * SORT_BINS */
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        uint32_t* hist = (uint32_t*)lds;
+        uint32_t p = wg / n_wg, tl = wg % n_wg;
+        if (ph == 0) {
+            if (lane < SORT_BINS) hist[lane] = 0;
+        } else if (ph == 1) {
+            const TileProblem P = prob[p];
+            uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
+            tile_terms<BLOCK, true>(P, DT_I16, lo, hi, lane, [&](uint64_t, int32_t v) {
+                uint32_t mag = (uint32_t)(v < 0 ? -v : v);
+                if (mag) atomic_add_u32(&hist[(mag - 1u) / SORT_BIN_KEYS], 1u);
+            });
+        } else {
+            if (lane < SORT_BINS) M[(uint64_t)wg * SORT_BINS + lane] = hist[lane];
+        }
+    }
+};
+struct ScatterBins {           /* the same workgroups (tiles of at most SORT_TILE terms): their entries, bin by bin */
+    static constexpr int BLOCK = 512;
+    static constexpr int PHASES = 5;
+    /* histogram, its prefix sums (+ total), the tile's cursors; ranks; the tile in bin order */
+    static constexpr size_t LDS_BYTES = (3 * SORT_BINS + 1) * sizeof(uint32_t) + SORT_TILE * sizeof(uint16_t) + SORT_TILE * sizeof(uint32_t);
+    const TileProblem* prob;
+    uint32_t n_wg;
+    const uint32_t* M;         /* after TileColumnScan: offset of the tile within its bin */
+    const uint32_t* start;     /* bin starts, problems * SORT_BINS */
+    uint32_t* packed;
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        uint32_t* hist = (uint32_t*)lds;
+        uint32_t* off = hist + SORT_BINS;                  /* SORT_BINS + 1 */
+        uint32_t* cur = off + SORT_BINS + 1;
+        uint32_t* tile = cur + SORT_BINS;
+        uint16_t* rank = (uint16_t*)(tile + SORT_TILE);
+        uint32_t p = wg / n_wg, tl = wg % n_wg;
+        const TileProblem P = prob[p];
+        uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
+        if (ph == 0) {
+            if (lane < SORT_BINS) {
+                hist[lane] = 0;
+                cur[lane] = start[(uint64_t)p * SORT_BINS + lane] + M[(uint64_t)wg * SORT_BINS + lane];
+            }
+        } else if (ph == 1) {
+            tile_terms<BLOCK, true>(P, DT_I16, lo, hi, lane, [&](uint64_t i, int32_t v) {
+                uint32_t mag = (uint32_t)(v < 0 ? -v : v);
+                rank[i - lo] = mag ? (uint16_t)atomic_add_u32(&hist[(mag - 1u) / SORT_BIN_KEYS], 1u) : (uint16_t)SORT_NO_RANK;
+            });
+        } else if (ph == 2) {
+            sort_prefix(hist, SORT_BINS, lane, off);
+        } else if (ph == 3) {
+            tile_terms<BLOCK, true>(P, DT_I16, lo, hi, lane, [&](uint64_t i, int32_t v) {
+                uint32_t mag = (uint32_t)(v < 0 ? -v : v);
+                if (mag) {
+                    uint32_t key = mag - 1u;
+                    tile[off[key / SORT_BIN_KEYS] + rank[i - lo]] = (uint32_t)i | ((key % SORT_BIN_KEYS) << 24) | (v < 0 ? 0x80000000u : 0u);
+                }
+            });
+        } else {
+            uint32_t total = off[SORT_BINS];
+            for (uint32_t j = lane; j < total; j += BLOCK) {
+                uint32_t b = sort_owner(off, SORT_BINS, j);
+                packed[cur[b] + (j - off[b])] = tile[j];
+            }
+        }
+    }
+};
+/* Second level.  The stretch of a bin is cut into tiles of SORT_TILE entries; tile s of the launch is tile
+ * s - tstart[b] of the bin b that owns it (tstart: prefix sums of the tiles per bin; owner[s] = b). */
+struct SortTileOwners {        /* lane = bin */
+    const uint32_t* tstart;
+    uint32_t* owner;
+    TC_DEV void operator()(uint32_t b) const {
+        for (uint32_t s = tstart[b]; s < tstart[b + 1]; ++s) owner[s] = b;
+    }
+};
+/* bin, first and last + 1 entry of tile s -> r[0..2]; a workgroup past the last tile gets an empty stretch of bin 0 */
+TC_DEV void sort_tile_range(const uint32_t* start, const uint32_t* tstart, const uint32_t* owner, uint32_t bins, uint32_t s, uint32_t* r) {
+    if (s >= tstart[bins]) {
+        r[0] = r[1] = r[2] = 0;
+        return;
+    }
+    uint32_t b = owner[s];
+    uint32_t lo = start[b] + (s - tstart[b]) * SORT_TILE, end = start[b + 1];
+    r[0] = b;
+    r[1] = lo;
+    r[2] = end - lo < SORT_TILE ? end : lo + SORT_TILE;
+}
+struct CountKeys {             /* workgroup = tile of the packed array: entries per key */
+    static constexpr int BLOCK = 512;
+    static constexpr int PHASES = 3;
+    static constexpr size_t LDS_BYTES = (SORT_BIN_KEYS + 3) * sizeof(uint32_t);
+    const uint32_t* packed;
+    const uint32_t* start;     /* bin starts, bins + 1 */
+    const uint32_t* tstart;    /* first tile of every bin, bins + 1 */
+    const uint32_t* owner;
+    uint32_t bins;
+    uint32_t* T;               /* tiles * SORT_BIN_KEYS */
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        uint32_t* hist = (uint32_t*)lds;
+        uint32_t* r = hist + SORT_BIN_KEYS;
+        if (ph == 0) {
+            if (lane < SORT_BIN_KEYS) hist[lane] = 0;
+            if (lane == SORT_BIN_KEYS) sort_tile_range(start, tstart, owner, bins, wg, r);
+        } else if (ph == 1) {
+            for (uint32_t i = r[1] + lane; i < r[2]; i += BLOCK) atomic_add_u32(&hist[(packed[i] >> 24) & 127u], 1u);
+        } else {
+            if (lane < SORT_BIN_KEYS) T[(uint64_t)wg * SORT_BIN_KEYS + lane] = hist[lane];
+        }
+    }
+};
+struct KeyColumnScan {         /* lane = (bin, key): offsets of the bin's tiles within the bucket, bucket count */
+    const uint32_t* tstart;
+    uint32_t* T;
+    uint32_t* cnt;             /* bins * SORT_BIN_KEYS */
+    TC_DEV void operator()(uint32_t t) const {
+        uint32_t b = t / SORT_BIN_KEYS, key = t % SORT_BIN_KEYS;
+        uint32_t at = 0;
+        for (uint32_t s = tstart[b]; s < tstart[b + 1]; ++s) {
+            uint32_t v = T[(uint64_t)s * SORT_BIN_KEYS + key];
+            T[(uint64_t)s * SORT_BIN_KEYS + key] = at;
+            at += v;
+        }
+        cnt[t] = at;
+    }
+};
+struct SortKeys {              /* the tiles of CountKeys: entries in bucket order, as ScatterTile writes them */
+    static constexpr int BLOCK = 1024;
+    static constexpr int PHASES = 5;
+    static constexpr size_t LDS_BYTES = (3 * SORT_BIN_KEYS + 4) * sizeof(uint32_t) + SORT_TILE * sizeof(uint16_t) + SORT_TILE * sizeof(uint32_t);
+    const uint32_t* packed;
+    const uint32_t* start;     /* bin starts */
+    const uint32_t* tstart;
+    const uint32_t* owner;
+    uint32_t bins;
+    const uint32_t* T;         /* after KeyColumnScan */
+    const uint32_t* bucket_start;      /* bins * SORT_BIN_KEYS */
+    uint32_t* sorted;          /* index | sign << 31 */
+    TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
+        uint32_t* hist = (uint32_t*)lds;
+        uint32_t* off = hist + SORT_BIN_KEYS;              /* SORT_BIN_KEYS + 1 */
+        uint32_t* cur = off + SORT_BIN_KEYS + 1;
+        uint32_t* r = cur + SORT_BIN_KEYS;
+        uint32_t* tile = r + 3;
+        uint16_t* rank = (uint16_t*)(tile + SORT_TILE);
+        if (ph == 0) {
+            if (lane < SORT_BIN_KEYS) hist[lane] = 0;
+            if (lane == SORT_BIN_KEYS) sort_tile_range(start, tstart, owner, bins, wg, r);
+        } else if (ph == 1) {
+            if (lane < SORT_BIN_KEYS) cur[lane] = bucket_start[(uint64_t)r[0] * SORT_BIN_KEYS + lane] + T[(uint64_t)wg * SORT_BIN_KEYS + lane];
+            for (uint32_t j = lane; r[1] + j < r[2]; j += BLOCK) rank[j] = (uint16_t)atomic_add_u32(&hist[(packed[r[1] + j] >> 24) & 127u], 1u);
+        } else if (ph == 2) {
+            sort_prefix(hist, SORT_BIN_KEYS, lane, off);
+        } else if (ph == 3) {
+            for (uint32_t j = lane; r[1] + j < r[2]; j += BLOCK) {
+                uint32_t w = packed[r[1] + j];
+                tile[off[(w >> 24) & 127u] + rank[j]] = w;
+            }
+        } else {
+            for (uint32_t j = lane; r[1] + j < r[2]; j += BLOCK) {
+                uint32_t w = tile[j], key = (w >> 24) & 127u;
+                sorted[cur[key] + (j - off[key])] = w & 0x80FFFFFFu;
+            }
+        }
+    }
+};
+
 /* ---- prefix sums over bucket counts (three lane-independent steps) ---------------- */
 /* chunk = 256 consecutive buckets.  A: per-chunk totals of cnt and of ceil(cnt / L);
  * B: one lane turns the chunk totals into exclusive offsets; C: per-chunk serial prefix. */

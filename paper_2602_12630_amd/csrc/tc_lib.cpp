@@ -1428,6 +1428,13 @@ static const uint64_t ORDERED_LANES_MIN = 64;
 static const uint64_t ORDERED_LANES_MIN = 1ull << 20;
 #endif
 
+/* from this many 16-bit terms on, a launch sorts them in two levels */
+#if defined(TC_HOST_EMU)
+static const uint64_t TWO_LEVEL_SORT_MIN = 64;
+#else
+static const uint64_t TWO_LEVEL_SORT_MIN = 1ull << 23;
+#endif
+
 /* One MSM problem: result = sum_i [e(s_i)] pts[i] over n terms */
 struct MsmProblem {
     const g1_affine* pts;
@@ -1536,6 +1543,17 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         const uint64_t tile_terms_min = (dtype == TC_FR || dtype == DT_FR128) ? 1024 : 8192;      /* a full-width term is W digits' worth of work for its lane */
         uint32_t n_wg = (uint32_t)std::min<uint64_t>(256, std::max<uint64_t>(1, std::min<uint64_t>(4096 / (uint64_t)count, max_terms / tile_terms_min)));
         if (ctx->static_mode) n_wg = STATIC_TILES;     /* the tile histograms are n_wg rows of the key space */
+        /* many 16-bit magnitudes: sorted by the upper eight key bits first, then by the lower seven, in tiles that a
+         * workgroup sorts in LDS (the index of a term shares a word with its lower key bits on the way, so no problem
+         * may have more than 2^24 terms) */
+        bool two_level = nbk_pp == 32768 && dtype == TC_I16 && !ctx->static_mode && items >= TWO_LEVEL_SORT_MIN &&
+                         max_terms <= SORT_PACKED_MAX_TERMS;
+        for (int p = 0; p < count; ++p) two_level = two_level && !prob[p].sub;
+        if (two_level) {
+            uint64_t tiles = (max_terms + SORT_TILE - 1) / SORT_TILE;
+            if (tiles * (uint64_t)count <= (1ull << 20)) n_wg = (uint32_t)tiles;
+            else two_level = false;
+        }
         TileProblem one;
         std::vector<TileProblem> many;
         if (count > 1) many.resize(count);
@@ -1550,32 +1568,55 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
             h_prob[p].shift = prob[p].shift;
         }
         WS(d_prob, TileProblem, (uint32_t)count);
-        WS(M, uint32_t, (uint64_t)count * n_wg * nbk_pp);
         TRY(upload_small(ctx, d_prob, h_prob, sizeof(TileProblem) * (size_t)count));
         uint32_t groups = (uint32_t)count * n_wg;
-        /* counting tiles of a few thousand terms (the rows of a batch of openings) takes workgroups of 256 lanes: most of
-         * 1024 would idle (0.53 -> 0.23 ms for the 23 552 rows of config 3's openings) */
-        uint64_t max_tile = 0;
-        for (int p = 0; p < count; ++p) max_tile = std::max<uint64_t>(max_tile, h_prob[p].tile);
-        const bool narrow = nbk_pp == 128 && max_tile <= 16384 && !ctx->static_mode;
-        if (narrow) RT((launch_coop<256>(groups, ctx->stream, CountTile<128, 256>{d_prob, dtype, D, c, n_wg, M})));
-        else if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, CountTile<128>{d_prob, dtype, D, c, n_wg, M})));
-        else if (nbk_pp == 256) RT((launch_coop<1024>(groups, ctx->stream, CountTile<256>{d_prob, dtype, D, c, n_wg, M})));
-        else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, CountTile<512>{d_prob, dtype, D, c, n_wg, M})));
-        else if (nbk_pp == 4096) RT((launch_coop<1024>(groups, ctx->stream, CountTile<4096>{d_prob, dtype, D, c, n_wg, M})));
-        else if (nbk_pp == 2176) RT((launch_coop<1024>(groups, ctx->stream, CountTile<2176>{d_prob, dtype, D, c, n_wg, M})));
-        else if (nbk_pp == 32768) RT((launch_coop<1024>(groups, ctx->stream, CountTile<32768>{d_prob, dtype, D, c, n_wg, M})));
-        else return fail(ctx, TC_ERR_STATE, "internal: unsupported key count");
-        RT(rt::launch<256>(nbk, ctx->stream, TileColumnScan{nbk_pp, n_wg, M, cnt}));
-        TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, nullptr, tot_a, tot_b, tot_max));
-        if (!ctx->static_mode) RT(rt::memcpy_d2h(&max_count, tot_max + nchunks, 4, ctx->stream));
-        /* (the scatter is faster with 1024 lanes even on short tiles: 1.04 against 1.28 ms on those rows) */
-        if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<128>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
-        else if (nbk_pp == 256) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<256>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
-        else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<512>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
-        else if (nbk_pp == 4096) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<4096>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
-        else if (nbk_pp == 2176) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<2176>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
-        else RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<32768>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
+        if (two_level) {
+            const uint32_t bins = (uint32_t)count * SORT_BINS;
+            /* tiles of the second level: a bin of v entries has ceil(v / SORT_TILE) of them */
+            const uint32_t max_tiles = (uint32_t)(items / SORT_TILE) + bins;
+            WS(tile_bins, uint32_t, (uint64_t)groups * SORT_BINS);
+            WS(bin_cnt, uint32_t, bins);
+            WS(bin_start, uint32_t, bins + 1);
+            WS(bin_tiles, uint32_t, bins + 1);
+            WS(packed, uint32_t, items);
+            WS(tile_keys, uint32_t, (uint64_t)max_tiles * SORT_BIN_KEYS);
+            WS(tile_owner, uint32_t, max_tiles);
+            RT((launch_coop<CountBins::BLOCK>(groups, ctx->stream, CountBins{d_prob, n_wg, tile_bins})));
+            RT(rt::launch<256>(bins, ctx->stream, TileColumnScan{SORT_BINS, n_wg, tile_bins, bin_cnt}));
+            TRY(scan_counts(ctx, bin_cnt, bins, SORT_TILE, bin_start, bin_tiles, nullptr, tot_a, tot_b, tot_max));
+            RT((launch_coop<ScatterBins::BLOCK>(groups, ctx->stream, ScatterBins{d_prob, n_wg, tile_bins, bin_start, packed})));
+            RT(rt::launch<256>(bins, ctx->stream, SortTileOwners{bin_tiles, tile_owner}));
+            RT((launch_coop<CountKeys::BLOCK>(max_tiles, ctx->stream, CountKeys{packed, bin_start, bin_tiles, tile_owner, bins, tile_keys})));
+            RT(rt::launch<256>(nbk, ctx->stream, KeyColumnScan{bin_tiles, tile_keys, cnt}));
+            TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, nullptr, tot_a, tot_b, tot_max));
+            RT(rt::memcpy_d2h(&max_count, tot_max + nchunks, 4, ctx->stream));
+            RT((launch_coop<SortKeys::BLOCK>(max_tiles, ctx->stream, SortKeys{packed, bin_start, bin_tiles, tile_owner, bins, tile_keys, start, sorted})));
+        } else {
+            WS(M, uint32_t, (uint64_t)count * n_wg * nbk_pp);
+            /* counting tiles of a few thousand terms (the rows of a batch of openings) takes workgroups of 256 lanes: most of
+             * 1024 would idle (0.53 -> 0.23 ms for the 23 552 rows of config 3's openings) */
+            uint64_t max_tile = 0;
+            for (int p = 0; p < count; ++p) max_tile = std::max<uint64_t>(max_tile, h_prob[p].tile);
+            const bool narrow = nbk_pp == 128 && max_tile <= 16384 && !ctx->static_mode;
+            if (narrow) RT((launch_coop<256>(groups, ctx->stream, CountTile<128, 256>{d_prob, dtype, D, c, n_wg, M})));
+            else if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, CountTile<128>{d_prob, dtype, D, c, n_wg, M})));
+            else if (nbk_pp == 256) RT((launch_coop<1024>(groups, ctx->stream, CountTile<256>{d_prob, dtype, D, c, n_wg, M})));
+            else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, CountTile<512>{d_prob, dtype, D, c, n_wg, M})));
+            else if (nbk_pp == 4096) RT((launch_coop<1024>(groups, ctx->stream, CountTile<4096>{d_prob, dtype, D, c, n_wg, M})));
+            else if (nbk_pp == 2176) RT((launch_coop<1024>(groups, ctx->stream, CountTile<2176>{d_prob, dtype, D, c, n_wg, M})));
+            else if (nbk_pp == 32768) RT((launch_coop<1024>(groups, ctx->stream, CountTile<32768>{d_prob, dtype, D, c, n_wg, M})));
+            else return fail(ctx, TC_ERR_STATE, "internal: unsupported key count");
+            RT(rt::launch<256>(nbk, ctx->stream, TileColumnScan{nbk_pp, n_wg, M, cnt}));
+            TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, nullptr, tot_a, tot_b, tot_max));
+            if (!ctx->static_mode) RT(rt::memcpy_d2h(&max_count, tot_max + nchunks, 4, ctx->stream));
+            /* (the scatter is faster with 1024 lanes even on short tiles: 1.04 against 1.28 ms on those rows) */
+            if (nbk_pp == 128) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<128>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
+            else if (nbk_pp == 256) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<256>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
+            else if (nbk_pp == 512) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<512>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
+            else if (nbk_pp == 4096) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<4096>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
+            else if (nbk_pp == 2176) RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<2176>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
+            else RT((launch_coop<1024>(groups, ctx->stream, ScatterTile<32768>{d_prob, dtype, D, c, n_wg, M, start, sorted})));
+        }
     } else {
         if (ctx->static_mode) return fail(ctx, TC_ERR_STATE, "internal: full-width scalars in a call that may not allocate");
         RT(rt::launch<256>(nbk, ctx->stream, Fill32{cnt, 0u}));
