@@ -533,22 +533,28 @@ struct ScatterTile {
 /* ---- counting sort of 16-bit magnitudes in two levels, tiles sorted in LDS ------------
  * ScatterTile<32768> sends every 4-byte entry to a memory line of its own: a tile's share of a bucket is a few
  * entries, no cache holds the 32768 open lines of every workgroup, and memory writes a whole sector per entry
- * (3.3 ms for the 3.1e8 entries of the LLaMA2-7B-shaped forward).  Sorting by the upper eight bits of the key
- * (magnitude - 1) first and by the lower seven afterwards keeps the open lines few, but as long as every lane sends
- * its own 4-byte write each pass is bound by the L2's one request per channel and clock (1.3 ms).  So both passes
- * sort a tile of SORT_TILE entries in LDS first -- rank of every entry among those of its key from an LDS atomic,
- * prefix sums of the tile's histogram, entries placed in key order -- and write it out as runs: neighbouring lanes
- * write neighbouring words.  On the way from the first pass to the second an entry is one word: bits 0..23 index,
- * 24..30 key mod 128, 31 sign; hence no more than 2^24 terms per problem. */
-constexpr uint32_t SORT_BINS = 256;          /* bins per problem (upper key bits) */
-constexpr uint32_t SORT_BIN_KEYS = 128;      /* keys per bin (lower key bits) */
+ * (3.3 ms for the 3.1e8 entries of the LLaMA2-7B-shaped forward).  Sorting by the upper bits of the key
+ * (magnitude - 1) first and by the lower `low` bits afterwards keeps the open lines few, but as long as every lane
+ * sends its own 4-byte write each pass is bound by the L2's one request per channel and clock (1.3 ms).  So both
+ * passes sort a tile of SORT_TILE entries in LDS first -- rank of every entry among those of its key from an LDS
+ * atomic, prefix sums of the tile's histogram, entries placed in key order -- and write it out as runs: neighbouring
+ * lanes write neighbouring words.  On the way from the first pass to the second an entry is one word: the index in
+ * bits 0 .. 30 - low, above it the lower key bits, bit 31 the sign.  low = 7 (256 bins of 128 keys) for problems of
+ * up to 2^24 terms, low = 6 (512 bins of 64 keys) up to 2^25. */
+constexpr uint32_t SORT_KEY_BITS = 15;
+constexpr uint32_t SORT_BINS_MAX = 512;      /* bins per problem (upper key bits) at low = 6 */
+constexpr uint32_t SORT_KEYS_MAX = 128;      /* keys per bin (lower key bits) at low = 7 */
 #if defined(TC_HOST_EMU)
 constexpr uint32_t SORT_TILE = 64;           /* the CPU build of the tests meets several tiles per bin at its sizes */
 #else
 constexpr uint32_t SORT_TILE = 8192;         /* entries a workgroup sorts in LDS */
 #endif
-constexpr uint64_t SORT_PACKED_MAX_TERMS = 1ull << 24;
 constexpr uint32_t SORT_NO_RANK = 0xFFFFu;
+TC_HD uint32_t sort_pack(uint32_t i, uint32_t key, bool negative, uint32_t low) {
+    return i | ((key & ((1u << low) - 1u)) << (31u - low)) | (negative ? 0x80000000u : 0u);
+}
+TC_HD uint32_t sort_low_key(uint32_t w, uint32_t low) { return (w >> (31u - low)) & ((1u << low) - 1u); }
+TC_HD uint32_t sort_entry(uint32_t w, uint32_t low) { return w & (0x80000000u | ((1u << (31u - low)) - 1u)); }
 
 /* largest b with off[b] <= j, off[0] = 0 non-decreasing, n a power of two */
 TC_HD uint32_t sort_owner(const uint32_t* off, uint32_t n, uint32_t j) {
@@ -568,24 +574,26 @@ TC_DEV void sort_prefix(const uint32_t* hist, uint32_t n, uint32_t lane, uint32_
 struct CountBins {             /* workgroup = (problem, tile): terms per bin */
     static constexpr int BLOCK = 512;
     static constexpr int PHASES = 3;
-    static constexpr size_t LDS_BYTES = SORT_BINS * sizeof(uint32_t);
+    static constexpr size_t LDS_BYTES = SORT_BINS_MAX * sizeof(uint32_t);
+    static_assert(BLOCK >= (int)SORT_BINS_MAX, "a lane per bin");
     const TileProblem* prob;
-    uint32_t n_wg;
-    uint32_t* M;               /* problems * n_wg * SORT_BINS */
+    uint32_t n_wg, low;
+    uint32_t* M;               /* problems * n_wg * bins per problem */
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         uint32_t* hist = (uint32_t*)lds;
         uint32_t p = wg / n_wg, tl = wg % n_wg;
+        const uint32_t nbins = 1u << (SORT_KEY_BITS - low);
         if (ph == 0) {
-            if (lane < SORT_BINS) hist[lane] = 0;
+            if (lane < nbins) hist[lane] = 0;
         } else if (ph == 1) {
             const TileProblem P = prob[p];
             uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
             tile_terms<BLOCK, true>(P, DT_I16, lo, hi, lane, [&](uint64_t, int32_t v) {
                 uint32_t mag = (uint32_t)(v < 0 ? -v : v);
-                if (mag) atomic_add_u32(&hist[(mag - 1u) / SORT_BIN_KEYS], 1u);
+                if (mag) atomic_add_u32(&hist[(mag - 1u) >> low], 1u);
             });
         } else {
-            if (lane < SORT_BINS) M[(uint64_t)wg * SORT_BINS + lane] = hist[lane];
+            if (lane < nbins) M[(uint64_t)wg * nbins + lane] = hist[lane];
         }
     }
 };
@@ -593,45 +601,44 @@ struct ScatterBins {           /* the same workgroups (tiles of at most SORT_TIL
     static constexpr int BLOCK = 512;
     static constexpr int PHASES = 5;
     /* histogram, its prefix sums (+ total), the tile's cursors; ranks; the tile in bin order */
-    static constexpr size_t LDS_BYTES = (3 * SORT_BINS + 1) * sizeof(uint32_t) + SORT_TILE * sizeof(uint16_t) + SORT_TILE * sizeof(uint32_t);
+    static constexpr size_t LDS_BYTES = (3 * SORT_BINS_MAX + 1) * sizeof(uint32_t) + SORT_TILE * sizeof(uint16_t) + SORT_TILE * sizeof(uint32_t);
+    static_assert(BLOCK >= (int)SORT_BINS_MAX, "a lane per bin");
     const TileProblem* prob;
-    uint32_t n_wg;
+    uint32_t n_wg, low;
     const uint32_t* M;         /* after TileColumnScan: offset of the tile within its bin */
-    const uint32_t* start;     /* bin starts, problems * SORT_BINS */
+    const uint32_t* start;     /* bin starts, problems * bins per problem */
     uint32_t* packed;
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         uint32_t* hist = (uint32_t*)lds;
-        uint32_t* off = hist + SORT_BINS;                  /* SORT_BINS + 1 */
-        uint32_t* cur = off + SORT_BINS + 1;
-        uint32_t* tile = cur + SORT_BINS;
+        uint32_t* off = hist + SORT_BINS_MAX;              /* bins + 1 */
+        uint32_t* cur = off + SORT_BINS_MAX + 1;
+        uint32_t* tile = cur + SORT_BINS_MAX;
         uint16_t* rank = (uint16_t*)(tile + SORT_TILE);
         uint32_t p = wg / n_wg, tl = wg % n_wg;
+        const uint32_t nbins = 1u << (SORT_KEY_BITS - low);
         const TileProblem P = prob[p];
         uint64_t lo = (uint64_t)tl * P.tile, hi = lo + P.tile < P.n ? lo + P.tile : P.n;
         if (ph == 0) {
-            if (lane < SORT_BINS) {
+            if (lane < nbins) {
                 hist[lane] = 0;
-                cur[lane] = start[(uint64_t)p * SORT_BINS + lane] + M[(uint64_t)wg * SORT_BINS + lane];
+                cur[lane] = start[(uint64_t)p * nbins + lane] + M[(uint64_t)wg * nbins + lane];
             }
         } else if (ph == 1) {
             tile_terms<BLOCK, true>(P, DT_I16, lo, hi, lane, [&](uint64_t i, int32_t v) {
                 uint32_t mag = (uint32_t)(v < 0 ? -v : v);
-                rank[i - lo] = mag ? (uint16_t)atomic_add_u32(&hist[(mag - 1u) / SORT_BIN_KEYS], 1u) : (uint16_t)SORT_NO_RANK;
+                rank[i - lo] = mag ? (uint16_t)atomic_add_u32(&hist[(mag - 1u) >> low], 1u) : (uint16_t)SORT_NO_RANK;
             });
         } else if (ph == 2) {
-            sort_prefix(hist, SORT_BINS, lane, off);
+            sort_prefix(hist, nbins, lane, off);
         } else if (ph == 3) {
             tile_terms<BLOCK, true>(P, DT_I16, lo, hi, lane, [&](uint64_t i, int32_t v) {
                 uint32_t mag = (uint32_t)(v < 0 ? -v : v);
-                if (mag) {
-                    uint32_t key = mag - 1u;
-                    tile[off[key / SORT_BIN_KEYS] + rank[i - lo]] = (uint32_t)i | ((key % SORT_BIN_KEYS) << 24) | (v < 0 ? 0x80000000u : 0u);
-                }
+                if (mag) tile[off[(mag - 1u) >> low] + rank[i - lo]] = sort_pack((uint32_t)i, mag - 1u, v < 0, low);
             });
         } else {
-            uint32_t total = off[SORT_BINS];
+            uint32_t total = off[nbins];
             for (uint32_t j = lane; j < total; j += BLOCK) {
-                uint32_t b = sort_owner(off, SORT_BINS, j);
+                uint32_t b = sort_owner(off, nbins, j);
                 packed[cur[b] + (j - off[b])] = tile[j];
             }
         }
@@ -661,36 +668,39 @@ TC_DEV void sort_tile_range(const uint32_t* start, const uint32_t* tstart, const
 struct CountKeys {             /* workgroup = tile of the packed array: entries per key */
     static constexpr int BLOCK = 512;
     static constexpr int PHASES = 3;
-    static constexpr size_t LDS_BYTES = (SORT_BIN_KEYS + 3) * sizeof(uint32_t);
+    static constexpr size_t LDS_BYTES = (SORT_KEYS_MAX + 3) * sizeof(uint32_t);
     const uint32_t* packed;
     const uint32_t* start;     /* bin starts, bins + 1 */
     const uint32_t* tstart;    /* first tile of every bin, bins + 1 */
     const uint32_t* owner;
-    uint32_t bins;
-    uint32_t* T;               /* tiles * SORT_BIN_KEYS */
+    uint32_t bins, low;
+    uint32_t* T;               /* tiles * keys per bin */
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         uint32_t* hist = (uint32_t*)lds;
-        uint32_t* r = hist + SORT_BIN_KEYS;
+        uint32_t* r = hist + SORT_KEYS_MAX;
+        const uint32_t nkeys = 1u << low;
         if (ph == 0) {
-            if (lane < SORT_BIN_KEYS) hist[lane] = 0;
-            if (lane == SORT_BIN_KEYS) sort_tile_range(start, tstart, owner, bins, wg, r);
+            if (lane < nkeys) hist[lane] = 0;
+            if (lane == SORT_KEYS_MAX) sort_tile_range(start, tstart, owner, bins, wg, r);
         } else if (ph == 1) {
-            for (uint32_t i = r[1] + lane; i < r[2]; i += BLOCK) atomic_add_u32(&hist[(packed[i] >> 24) & 127u], 1u);
+            for (uint32_t i = r[1] + lane; i < r[2]; i += BLOCK) atomic_add_u32(&hist[sort_low_key(packed[i], low)], 1u);
         } else {
-            if (lane < SORT_BIN_KEYS) T[(uint64_t)wg * SORT_BIN_KEYS + lane] = hist[lane];
+            if (lane < nkeys) T[(uint64_t)wg * nkeys + lane] = hist[lane];
         }
     }
 };
 struct KeyColumnScan {         /* lane = (bin, key): offsets of the bin's tiles within the bucket, bucket count */
     const uint32_t* tstart;
+    uint32_t low;
     uint32_t* T;
-    uint32_t* cnt;             /* bins * SORT_BIN_KEYS */
+    uint32_t* cnt;             /* bins * keys per bin */
     TC_DEV void operator()(uint32_t t) const {
-        uint32_t b = t / SORT_BIN_KEYS, key = t % SORT_BIN_KEYS;
+        const uint32_t nkeys = 1u << low;
+        uint32_t b = t >> low, key = t & (nkeys - 1u);
         uint32_t at = 0;
         for (uint32_t s = tstart[b]; s < tstart[b + 1]; ++s) {
-            uint32_t v = T[(uint64_t)s * SORT_BIN_KEYS + key];
-            T[(uint64_t)s * SORT_BIN_KEYS + key] = at;
+            uint32_t v = T[(uint64_t)s * nkeys + key];
+            T[(uint64_t)s * nkeys + key] = at;
             at += v;
         }
         cnt[t] = at;
@@ -699,39 +709,40 @@ struct KeyColumnScan {         /* lane = (bin, key): offsets of the bin's tiles 
 struct SortKeys {              /* the tiles of CountKeys: entries in bucket order, as ScatterTile writes them */
     static constexpr int BLOCK = 1024;
     static constexpr int PHASES = 5;
-    static constexpr size_t LDS_BYTES = (3 * SORT_BIN_KEYS + 4) * sizeof(uint32_t) + SORT_TILE * sizeof(uint16_t) + SORT_TILE * sizeof(uint32_t);
+    static constexpr size_t LDS_BYTES = (3 * SORT_KEYS_MAX + 4) * sizeof(uint32_t) + SORT_TILE * sizeof(uint16_t) + SORT_TILE * sizeof(uint32_t);
     const uint32_t* packed;
     const uint32_t* start;     /* bin starts */
     const uint32_t* tstart;
     const uint32_t* owner;
-    uint32_t bins;
+    uint32_t bins, low;
     const uint32_t* T;         /* after KeyColumnScan */
-    const uint32_t* bucket_start;      /* bins * SORT_BIN_KEYS */
+    const uint32_t* bucket_start;      /* bins * keys per bin */
     uint32_t* sorted;          /* index | sign << 31 */
     TC_DEV void phase(int ph, uint32_t lane, uint32_t wg, uint8_t* lds) const {
         uint32_t* hist = (uint32_t*)lds;
-        uint32_t* off = hist + SORT_BIN_KEYS;              /* SORT_BIN_KEYS + 1 */
-        uint32_t* cur = off + SORT_BIN_KEYS + 1;
-        uint32_t* r = cur + SORT_BIN_KEYS;
+        uint32_t* off = hist + SORT_KEYS_MAX;              /* keys + 1 */
+        uint32_t* cur = off + SORT_KEYS_MAX + 1;
+        uint32_t* r = cur + SORT_KEYS_MAX;
         uint32_t* tile = r + 3;
         uint16_t* rank = (uint16_t*)(tile + SORT_TILE);
+        const uint32_t nkeys = 1u << low;
         if (ph == 0) {
-            if (lane < SORT_BIN_KEYS) hist[lane] = 0;
-            if (lane == SORT_BIN_KEYS) sort_tile_range(start, tstart, owner, bins, wg, r);
+            if (lane < nkeys) hist[lane] = 0;
+            if (lane == SORT_KEYS_MAX) sort_tile_range(start, tstart, owner, bins, wg, r);
         } else if (ph == 1) {
-            if (lane < SORT_BIN_KEYS) cur[lane] = bucket_start[(uint64_t)r[0] * SORT_BIN_KEYS + lane] + T[(uint64_t)wg * SORT_BIN_KEYS + lane];
-            for (uint32_t j = lane; r[1] + j < r[2]; j += BLOCK) rank[j] = (uint16_t)atomic_add_u32(&hist[(packed[r[1] + j] >> 24) & 127u], 1u);
+            if (lane < nkeys) cur[lane] = bucket_start[(uint64_t)r[0] * nkeys + lane] + T[(uint64_t)wg * nkeys + lane];
+            for (uint32_t j = lane; r[1] + j < r[2]; j += BLOCK) rank[j] = (uint16_t)atomic_add_u32(&hist[sort_low_key(packed[r[1] + j], low)], 1u);
         } else if (ph == 2) {
-            sort_prefix(hist, SORT_BIN_KEYS, lane, off);
+            sort_prefix(hist, nkeys, lane, off);
         } else if (ph == 3) {
             for (uint32_t j = lane; r[1] + j < r[2]; j += BLOCK) {
                 uint32_t w = packed[r[1] + j];
-                tile[off[(w >> 24) & 127u] + rank[j]] = w;
+                tile[off[sort_low_key(w, low)] + rank[j]] = w;
             }
         } else {
             for (uint32_t j = lane; r[1] + j < r[2]; j += BLOCK) {
-                uint32_t w = tile[j], key = (w >> 24) & 127u;
-                sorted[cur[key] + (j - off[key])] = w & 0x80FFFFFFu;
+                uint32_t w = tile[j], key = sort_low_key(w, low);
+                sorted[cur[key] + (j - off[key])] = sort_entry(w, low);
             }
         }
     }

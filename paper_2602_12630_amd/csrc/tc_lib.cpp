@@ -1431,8 +1431,10 @@ static const uint64_t ORDERED_LANES_MIN = 1ull << 20;
 /* from this many 16-bit terms on, a launch sorts them in two levels */
 #if defined(TC_HOST_EMU)
 static const uint64_t TWO_LEVEL_SORT_MIN = 64;
+static const uint64_t SORT_SEVEN_BITS_MAX_TERMS = 4096;        /* the CPU build of the tests meets both word layouts */
 #else
 static const uint64_t TWO_LEVEL_SORT_MIN = 1ull << 23;
+static const uint64_t SORT_SEVEN_BITS_MAX_TERMS = 1ull << 24;
 #endif
 
 /* One MSM problem: result = sum_i [e(s_i)] pts[i] over n terms */
@@ -1543,11 +1545,12 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         const uint64_t tile_terms_min = (dtype == TC_FR || dtype == DT_FR128) ? 1024 : 8192;      /* a full-width term is W digits' worth of work for its lane */
         uint32_t n_wg = (uint32_t)std::min<uint64_t>(256, std::max<uint64_t>(1, std::min<uint64_t>(4096 / (uint64_t)count, max_terms / tile_terms_min)));
         if (ctx->static_mode) n_wg = STATIC_TILES;     /* the tile histograms are n_wg rows of the key space */
-        /* many 16-bit magnitudes: sorted by the upper eight key bits first, then by the lower seven, in tiles that a
-         * workgroup sorts in LDS (the index of a term shares a word with its lower key bits on the way, so no problem
-         * may have more than 2^24 terms) */
+        /* many 16-bit magnitudes: sorted by the upper key bits first, then by the lower ones, in tiles that a workgroup
+         * sorts in LDS (the index of a term shares a word with its lower key bits on the way: seven of them for
+         * problems of up to 2^24 terms, six up to 2^25) */
         bool two_level = nbk_pp == 32768 && dtype == TC_I16 && !ctx->static_mode && items >= TWO_LEVEL_SORT_MIN &&
-                         max_terms <= SORT_PACKED_MAX_TERMS;
+                         max_terms <= 2 * SORT_SEVEN_BITS_MAX_TERMS;
+        const uint32_t sort_low = max_terms <= SORT_SEVEN_BITS_MAX_TERMS ? 7u : 6u;
         for (int p = 0; p < count; ++p) two_level = two_level && !prob[p].sub;
         if (two_level) {
             uint64_t tiles = (max_terms + SORT_TILE - 1) / SORT_TILE;
@@ -1571,26 +1574,27 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
         TRY(upload_small(ctx, d_prob, h_prob, sizeof(TileProblem) * (size_t)count));
         uint32_t groups = (uint32_t)count * n_wg;
         if (two_level) {
-            const uint32_t bins = (uint32_t)count * SORT_BINS;
+            const uint32_t bins_pp = 32768u >> sort_low, keys = 1u << sort_low;
+            const uint32_t bins = (uint32_t)count * bins_pp;
             /* tiles of the second level: a bin of v entries has ceil(v / SORT_TILE) of them */
             const uint32_t max_tiles = (uint32_t)(items / SORT_TILE) + bins;
-            WS(tile_bins, uint32_t, (uint64_t)groups * SORT_BINS);
+            WS(tile_bins, uint32_t, (uint64_t)groups * bins_pp);
             WS(bin_cnt, uint32_t, bins);
             WS(bin_start, uint32_t, bins + 1);
             WS(bin_tiles, uint32_t, bins + 1);
             WS(packed, uint32_t, items);
-            WS(tile_keys, uint32_t, (uint64_t)max_tiles * SORT_BIN_KEYS);
+            WS(tile_keys, uint32_t, (uint64_t)max_tiles * keys);
             WS(tile_owner, uint32_t, max_tiles);
-            RT((launch_coop<CountBins::BLOCK>(groups, ctx->stream, CountBins{d_prob, n_wg, tile_bins})));
-            RT(rt::launch<256>(bins, ctx->stream, TileColumnScan{SORT_BINS, n_wg, tile_bins, bin_cnt}));
+            RT((launch_coop<CountBins::BLOCK>(groups, ctx->stream, CountBins{d_prob, n_wg, sort_low, tile_bins})));
+            RT(rt::launch<256>(bins, ctx->stream, TileColumnScan{bins_pp, n_wg, tile_bins, bin_cnt}));
             TRY(scan_counts(ctx, bin_cnt, bins, SORT_TILE, bin_start, bin_tiles, nullptr, tot_a, tot_b, tot_max));
-            RT((launch_coop<ScatterBins::BLOCK>(groups, ctx->stream, ScatterBins{d_prob, n_wg, tile_bins, bin_start, packed})));
+            RT((launch_coop<ScatterBins::BLOCK>(groups, ctx->stream, ScatterBins{d_prob, n_wg, sort_low, tile_bins, bin_start, packed})));
             RT(rt::launch<256>(bins, ctx->stream, SortTileOwners{bin_tiles, tile_owner}));
-            RT((launch_coop<CountKeys::BLOCK>(max_tiles, ctx->stream, CountKeys{packed, bin_start, bin_tiles, tile_owner, bins, tile_keys})));
-            RT(rt::launch<256>(nbk, ctx->stream, KeyColumnScan{bin_tiles, tile_keys, cnt}));
+            RT((launch_coop<CountKeys::BLOCK>(max_tiles, ctx->stream, CountKeys{packed, bin_start, bin_tiles, tile_owner, bins, sort_low, tile_keys})));
+            RT(rt::launch<256>(nbk, ctx->stream, KeyColumnScan{bin_tiles, sort_low, tile_keys, cnt}));
             TRY(scan_counts(ctx, cnt, nbk, L1, start, lstart, nullptr, tot_a, tot_b, tot_max));
             RT(rt::memcpy_d2h(&max_count, tot_max + nchunks, 4, ctx->stream));
-            RT((launch_coop<SortKeys::BLOCK>(max_tiles, ctx->stream, SortKeys{packed, bin_start, bin_tiles, tile_owner, bins, tile_keys, start, sorted})));
+            RT((launch_coop<SortKeys::BLOCK>(max_tiles, ctx->stream, SortKeys{packed, bin_start, bin_tiles, tile_owner, bins, sort_low, tile_keys, start, sorted})));
         } else {
             WS(M, uint32_t, (uint64_t)count * n_wg * nbk_pp);
             /* counting tiles of a few thousand terms (the rows of a batch of openings) takes workgroups of 256 lanes: most of

@@ -111,11 +111,13 @@ def test_emulated_commit_open_verify(emu):
     srs.close()
 
 
-def test_emulated_int16_commits_over_several_tiles(emu):
+@pytest.mark.parametrize("shape", [(48, 131), (24, 85)])
+def test_emulated_int16_commits_over_several_tiles(emu, shape):
     """Tensors of a few thousand 16-bit terms span several ragged tiles of the count / scatter kernels, which read
     sixteen bytes per lane where a tile is aligned and single values elsewhere.  Commitments alone, as a batch, and
-    from a buffer at an odd offset, against the oracle's closed form; extreme and repeated values, a tensor of zeros."""
-    shape = (48, 131)
+    from a buffer at an odd offset, against the oracle's closed form; extreme and repeated values, a tensor of zeros.
+    In this build the two sizes take the two word layouts of the sort in two levels (six and seven lower key bits),
+    with tiles of 64 entries: many tiles per bin, the heavily loaded bucket several tiles of its own."""
     pp = pps(shape)
     srs = emu.setup_from_trapdoor(TAU_BYTES, shape, 0)
     rng = np.random.default_rng(9)
