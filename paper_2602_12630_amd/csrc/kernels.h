@@ -1010,19 +1010,59 @@ TC_HD bool xyzz28_madd_regular(g1_xyzz28& a, const fp28& x2, const fp28& y2) {
 /* Tables of the accumulation.  A table of 96-byte points at a stride of 96 bytes puts every second point across two
  * of the 128-byte lines in which the second-level cache fetches: 192 bytes per point gathered at a random index.
  * The SRS therefore keeps a copy of its first table at a stride of 128 bytes for the launches that gather from it;
- * other tables (suffix tables, row commitments used as bases) stay at 96.  A table pointer carries its stride in
- * bit 0 (tables start on 16-byte boundaries). */
+ * other tables (suffix tables, row commitments used as bases) stay at 96.  A table pointer carries its kind in
+ * bit 0 (tables start on 16-byte boundaries).
+ * The 128 bytes have room for the point as the accumulation wants it: words 0..13 the 28-bit limbs of x, 14..27 those
+ * of y (fp28_from_fp), so that a lane neither re-cuts the 32-bit limbs of every point it adds (56 instructions) nor
+ * tests 24 words for the identity, which has -1 as the top limb of y (that limb of a point is below 2^28). */
 constexpr uint32_t PADDED_STRIDE = 128;
+struct PaddedPoint {
+    fp28 x, y;
+    uint32_t unused[4];
+};
+static_assert(sizeof(PaddedPoint) == PADDED_STRIDE, "one point per 128-byte line");
 TC_HD const g1_affine* tag_padded(const void* table) { return (const g1_affine*)((uintptr_t)table | 1u); }
-TC_HD const g1_affine& table_point(const g1_affine* tagged, uint32_t i) {
-    uintptr_t t = (uintptr_t)tagged;
-    uint32_t stride = (t & 1u) ? PADDED_STRIDE : (uint32_t)sizeof(g1_affine);
-    return *(const g1_affine*)((t & ~(uintptr_t)15u) + (uint64_t)i * stride);
+TC_HD bool table_is_padded(const g1_affine* tagged) { return ((uintptr_t)tagged & 1u) != 0; }
+TC_HD const PaddedPoint* padded_point(const g1_affine* tagged, uint32_t i) {
+    return (const PaddedPoint*)(((uintptr_t)tagged & ~(uintptr_t)15u) + (uint64_t)i * PADDED_STRIDE);
 }
-struct PadPoints {            /* out: the points of `in` at a stride of 128 bytes */
+/* limbs of x and y from seven 16-byte loads */
+TC_HD void padded_load(const PaddedPoint* q, fp28& x, fp28& y) {
+    Words16 c[7];
+#pragma unroll
+    for (int k = 0; k < 7; ++k) c[k] = ((const Words16*)q)[k];
+#pragma unroll
+    for (int j = 0; j < 14; ++j) {
+        x.l[j] = (int32_t)c[j >> 2].w[j & 3];
+        y.l[j] = (int32_t)c[(14 + j) >> 2].w[(14 + j) & 3];
+    }
+}
+/* point i of either kind of table in the 32-bit form (the kernels off the fast path) */
+TC_HD g1_affine table_point(const g1_affine* tagged, uint32_t i) {
+    if (table_is_padded(tagged)) {
+        fp28 x, y;
+        padded_load(padded_point(tagged, i), x, y);
+        if (y.l[13] < 0) return affine_identity();
+        g1_affine p;
+        p.x = fp28_recut_to_fp(x);
+        p.y = fp28_recut_to_fp(y);
+        return p;
+    }
+    return tagged[i];
+}
+struct PadPoints {            /* out: the points of `in`, one per 128 bytes, in 28-bit limbs */
     const g1_affine* in;
     uint8_t* out;
-    TC_DEV void operator()(uint32_t t) const { *(g1_affine*)(out + (uint64_t)t * PADDED_STRIDE) = in[t]; }
+    TC_DEV void operator()(uint32_t t) const {
+        g1_affine p = in[t];
+        PaddedPoint v;
+        v.x = fp28_from_fp(p.x);
+        v.y = fp28_from_fp(p.y);
+        if (affine_is_identity(p)) v.y.l[13] = -1;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v.unused[k] = 0;
+        *(PaddedPoint*)(out + (uint64_t)t * PADDED_STRIDE) = v;
+    }
 };
 
 /* Lane t owns sub-run `t - lstart[b]` of bucket b: at most L entries, all of one bucket.
@@ -1037,6 +1077,11 @@ TC_HD void subrun_bounds(const uint32_t* start, const uint32_t* lstart, uint32_t
     begin = s0 + j * low + (j < more ? j : more);
     end = begin + low + (j < more ? 1u : 0u);
 }
+enum { TABLES_PLAIN = 0, TABLES_PADDED = 1, TABLES_MIXED = 2 };
+/* What the launch gathers from.  Only the kernel for padded tables alone stays within the 168 registers of three waves
+ * per SIMD (162); the other two spill some forty registers, which costs the full-width problems at the end of a batch
+ * of openings about 3 % (4.0 -> 4.1 ms of 58). */
+template <int TABLES>
 struct AccAffine {
     const g1_affine* const* tables;   /* SRS table of problem p; bucket b belongs to problem b / nbk_pp */
     uint32_t nbk_pp;
@@ -1057,7 +1102,7 @@ struct AccAffine {
         const g1_affine* pts = tables[b / nbk_pp];                /* tagged with its stride */
         if (end - begin == 1) {                                   /* a lone entry: no arithmetic */
             uint32_t e = sorted[begin];
-            g1_affine p = table_point(pts, e & 0x7FFFFFFFu);
+            g1_affine p = TABLES == TABLES_PLAIN ? pts[e & 0x7FFFFFFFu] : table_point(pts, e & 0x7FFFFFFFu);
             if (e >> 31) p.y = fp_neg(p.y);
             out[t] = xyzz_from_affine(p);
             return;
@@ -1076,9 +1121,16 @@ struct AccAffine {
             }
             uint32_t j = i & 3u;
             uint32_t e = j == 0u ? four.w[0] : j == 1u ? four.w[1] : j == 2u ? four.w[2] : four.w[3];
-            g1_affine p = table_point(pts, e & 0x7FFFFFFFu);
-            if (affine_is_identity(p)) continue;
-            fp28 x2 = fp28_from_fp(p.x), y2 = fp28_from_fp(p.y);
+            fp28 x2, y2;
+            if (TABLES == TABLES_PADDED || (TABLES == TABLES_MIXED && table_is_padded(pts))) {
+                padded_load(padded_point(pts, e & 0x7FFFFFFFu), x2, y2);
+                if (y2.l[13] < 0) continue;
+            } else {
+                g1_affine p = pts[e & 0x7FFFFFFFu];
+                if (affine_is_identity(p)) continue;
+                x2 = fp28_from_fp(p.x);
+                y2 = fp28_from_fp(p.y);
+            }
             if (e >> 31) y2 = fp28_sub(fp28{}, y2);
             if (!have) {
                 acc.X = x2;

@@ -1657,7 +1657,11 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
     {
         rt::event_t e0, e1;
         prof_begin(ctx, TC_PROF_BUCKET_ACC, &e0, &e1);
-        RT((rt::launch_waves<64, 3>(max_part, ctx->stream, AccAffine{tables, nbk_pp, sorted, start, lstart, nbk, L1, bufA, redo, redo + 1, perm})));
+        int padded = 0;
+        for (int p = 0; p < count; ++p) padded += table_is_padded(prob[p].pts) ? 1 : 0;
+        if (padded == count) RT((rt::launch_waves<64, 3>(max_part, ctx->stream, AccAffine<TABLES_PADDED>{tables, nbk_pp, sorted, start, lstart, nbk, L1, bufA, redo, redo + 1, perm})));
+        else if (padded == 0) RT((rt::launch_waves<64, 3>(max_part, ctx->stream, AccAffine<TABLES_PLAIN>{tables, nbk_pp, sorted, start, lstart, nbk, L1, bufA, redo, redo + 1, perm})));
+        else RT((rt::launch_waves<64, 3>(max_part, ctx->stream, AccAffine<TABLES_MIXED>{tables, nbk_pp, sorted, start, lstart, nbk, L1, bufA, redo, redo + 1, perm})));
         prof_end(ctx, TC_PROF_BUCKET_ACC, e0, e1);
     }
     /* sub-runs with equal or opposite points in them: none in honest inputs; a degenerate input sends every sub-run
