@@ -56,8 +56,8 @@ ACC_TRAFFIC_BYTES_C3 = 5.179e10
 # Vector instructions that the same launch issues per SIMD and clock, and per mixed addition (rocprofv3 --pmc
 # SQ_INSTS_VALU / GRBM_GUI_ACTIVE of the same command: profiles/c3_build_sq_counters_pmc.txt).  A 64-lane wave takes
 # four clocks of a 16-lane SIMD, so 0.25 is the most a SIMD can issue.
-ACC_VALU_PER_SIMD_CLK_C3 = 0.250
-ACC_VALU_PER_ADDITION_C3 = 4834
+ACC_VALU_PER_SIMD_CLK_C3 = 0.245
+ACC_VALU_PER_ADDITION_C3 = 4777
 
 
 # ----------------------------------------------------------------------------------------------------------
