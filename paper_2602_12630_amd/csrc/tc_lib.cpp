@@ -1432,9 +1432,13 @@ static const uint64_t ORDERED_LANES_MIN = 1ull << 20;
 #if defined(TC_HOST_EMU)
 static const uint64_t TWO_LEVEL_SORT_MIN = 64;
 static const uint64_t SORT_SEVEN_BITS_MAX_TERMS = 4096;        /* the CPU build of the tests meets both word layouts */
+static const uint64_t SORT_MIN_BIN_LOAD = 1;
 #else
 static const uint64_t TWO_LEVEL_SORT_MIN = 1ull << 23;
 static const uint64_t SORT_SEVEN_BITS_MAX_TERMS = 1ull << 24;
+/* ... and only where the bins hold a quarter of a tile on average: a batch of many small tensors would end up with a
+ * workgroup and five barriers per handful of entries */
+static const uint64_t SORT_MIN_BIN_LOAD = SORT_TILE / 4;
 #endif
 
 /* One MSM problem: result = sum_i [e(s_i)] pts[i] over n terms */
@@ -1552,6 +1556,7 @@ static int msm_engine_multi(tc_ctx* ctx, int count, const MsmProblem* prob, int 
                          max_terms <= 2 * SORT_SEVEN_BITS_MAX_TERMS;
         const uint32_t sort_low = max_terms <= SORT_SEVEN_BITS_MAX_TERMS ? 7u : 6u;
         for (int p = 0; p < count; ++p) two_level = two_level && !prob[p].sub;
+        two_level = two_level && items / ((uint64_t)count * (32768u >> sort_low)) >= SORT_MIN_BIN_LOAD;
         if (two_level) {
             uint64_t tiles = (max_terms + SORT_TILE - 1) / SORT_TILE;
             if (tiles * (uint64_t)count <= (1ull << 20)) n_wg = (uint32_t)tiles;
