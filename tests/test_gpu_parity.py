@@ -256,6 +256,34 @@ def test_degenerate_bucket_loads_in_ordered_launches(T, ctx):
         srs.close()
 
 
+@pytest.mark.parametrize("shape", [(4096, 4096), (4096, 8192)])
+def test_two_level_sort_at_its_limits(T, ctx, shape):
+    """Commitments of 2^24 and 2^25 int16 terms, the largest problems that the sort in two levels takes with seven and
+    with six lower key bits beside the index of a term: a constant tensor (every entry in one bucket: a bin of thousands
+    of tiles, ranks up to the tile's size), a tensor with two non-zero entries, the first and the last (the top bit of
+    the index field), and -- at 2^24 -- values on both sides of every kind of bin and key boundary next to a Gaussian
+    half, against the oracle's closed form."""
+    pp = pps(shape)
+    n = tc.prod(shape)
+    srs = ctx.setup_from_trapdoor(TAU_BYTES, shape, 0)
+    try:
+        X = np.full(shape, 257, np.int16)
+        assert ctx.commit(srs, to_device(X), T.TC_I16) == ec.g1_to_bytes(ec.mul(257, ec.G1))
+        X[:] = 0
+        X.reshape(-1)[0], X.reshape(-1)[-1] = -32768, 129
+        want = (-32768 * pp.lagrange_scalar(tc.multi_index(0, shape)) + 129 * pp.lagrange_scalar(tc.multi_index(n - 1, shape))) % R
+        assert ctx.commit(srs, to_device(X), T.TC_I16) == ec.g1_to_bytes(cbind.g1_mul(want, ec.G1))
+        if n == 1 << 24:
+            rng = np.random.default_rng(24)
+            X = np.clip(np.rint(rng.standard_normal(shape) * 6300.0), -32767, 32767).astype(np.int16)
+            edges = np.array([1, -1, 64, 65, -64, -65, 128, 129, -128, -129, 256, 257, 16384, 16385, -16384, -16385,
+                              32767, -32767, -32768, 0, 32640, 32641, -32640, -32641], np.int16)
+            X[: shape[0] // 2, :] = np.resize(edges, (shape[0] // 2, shape[1]))
+            assert ctx.commit(srs, to_device(X), T.TC_I16) == ec.g1_to_bytes(cbind.commit(pp, X, nthreads=16))
+    finally:
+        srs.close()
+
+
 @pytest.mark.parametrize("table", [False, True])
 @pytest.mark.parametrize("shape", [(64, 512), (5, 37, 100), (300, 64)])
 def test_open_by_rows_matches_oracle(T, ctx, shape, table):
